@@ -1,0 +1,148 @@
+/*
+ * snn.h -- C ABI of the MI355X (gfx950) library for backpropagation through time
+ * in multi-layer leaky-integrate-and-fire (LIF) spiking RNNs under the state
+ * storage strategies of "Optimal Gradient Checkpointing for Sparse and Recurrent
+ * Architectures using Off-Chip Memory" (Fig. 1 of that paper).
+ *
+ * Memory tiers.  The paper's "local" memory is a capped activation budget in HBM;
+ * its "remote / streaming" memory is pinned host DRAM reached with
+ * hipMemcpyAsync on a side stream.
+ *
+ * Strategy names follow the caption of Fig. 1:
+ *   SNN_STANDARD  plain BPTT, every state stored               (eq. M_Base)
+ *   SNN_CHUNK     paper Section "Standard Checkpointing"        (eq. M_Standard, T_Standard)
+ *   SNN_REMOTE    paper Section "Remote Checkpointing"          (eq. M_Remote, T_Remote)
+ *   SNN_DOUBLE    paper Section "Double Checkpointing"          (eq. M_Double, T_Double, N_c)
+ *
+ * Model (layers l = 1..L, s^0 = input spikes, zero initial state, t = 1..T):
+ *   I^l_t = sum_{j active in s^{l-1}_t} W_in^l[j,:] + sum_{j active in s^l_{t-1}} W_rec^l[j,:]
+ *   v^l_t = (alpha v^l_{t-1} - theta s^l_{t-1}) + I^l_t ;   s^l_t = [v^l_t > theta]
+ *   u_t   = beta u_{t-1} + sum_{j active in s^L_t} W_out[j,:] ;  ubar = mean_t u_t
+ *   loss  = mean_b softmax-cross-entropy(ubar_b, y_b)
+ * Backward pass: surrogate derivative 1/(1 + surr_beta |v - theta|)^2, full gradient
+ * (also through the reset term).
+ *
+ * Conventions.  Every function returns an snn_status (0 = success) unless noted;
+ * nothing throws or aborts.  Pointers marked "host or device" may be either (the
+ * library asks the HIP runtime which).  The caller owns every buffer it passes and
+ * keeps it alive for the duration of the call.  All calls on one context must come
+ * from one thread at a time.  All functions return after the work they queued on the
+ * context's stream (and on the library's private copy stream) has completed.
+ */
+#ifndef SNN_H
+#define SNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct snn_ctx snn_ctx; /* opaque; created by snn_init, freed by snn_destroy */
+
+typedef enum {
+  SNN_OK = 0,
+  SNN_E_INVAL = 1,   /* bad argument / unsupported shape                         */
+  SNN_E_BUDGET = 2,  /* strategy needs more HBM activation memory than the budget */
+  SNN_E_HIP = 3,     /* a HIP runtime call failed (text in snn_last_error)        */
+  SNN_E_HOSTMEM = 4, /* pinned host allocation failed                             */
+  SNN_E_STATE = 5    /* call order violated (e.g. snn_bptt before inputs are bound) */
+} snn_status;
+
+typedef enum { SNN_STANDARD = 0, SNN_CHUNK = 1, SNN_REMOTE = 2, SNN_DOUBLE = 3 } snn_strategy;
+typedef enum { SNN_W_IN = 0, SNN_W_REC = 1, SNN_W_OUT = 2 } snn_tensor_kind;
+
+#define SNN_MAX_LAYERS 4
+
+typedef struct {
+  int32_t n_in;                     /* input channels                                  */
+  int32_t n_layers;                 /* 1..SNN_MAX_LAYERS recurrent LIF layers          */
+  int32_t n_hidden[SNN_MAX_LAYERS]; /* neurons per layer (each <= 65535)               */
+  int32_t n_out;                    /* leaky non-spiking readouts (<= 1024)            */
+  int32_t T;                        /* maximum sequence length this context will see   */
+  int32_t batch;
+  float alpha;                      /* membrane leak                                   */
+  float beta_out;                   /* readout leak                                    */
+  float theta;                      /* threshold = reset amount                        */
+  float surr_beta;                  /* k in 1/(1+k|v-theta|)^2                          */
+  int32_t device;                   /* HIP device ordinal                              */
+  void *stream;                     /* hipStream_t to queue work on (NULL = default)   */
+} snn_config;
+
+/* Filled by snn_bptt (all times in milliseconds, measured with HIP events on the
+ * context's stream; bytes are what the call actually allocated/moved). */
+typedef struct {
+  float ms_total, ms_forward, ms_backward_total; /* whole step; forward incl. loss; everything after */
+  float ms_recompute, ms_adjoint, ms_dw;         /* sums over kernels of each kind (0 if not timed) */
+  int64_t bytes_states;      /* HBM: trajectory / chunk buffer / checkpoints / staging slots */
+  int64_t bytes_spikes;      /* HBM: spike bitmasks of all layers, all steps                  */
+  int64_t bytes_workspace;   /* HBM: readout-adjoint tile and other per-chunk scratch          */
+  int64_t bytes_host;        /* pinned host memory holding remote checkpoints                  */
+  int64_t d2h_bytes, h2d_bytes; /* checkpoint traffic over the host link                       */
+  int32_t n_d2h, n_h2d;         /* number of checkpoint transfers (N_c = n_d2h + n_h2d)        */
+  int64_t fwd_steps, refwd1_steps, refwd2_steps, bwd_steps; /* time steps per pass             */
+  int32_t local_state_slots; /* states resident in HBM at the peak (M_s units)                 */
+  int32_t remote_state_slots;
+  float firing_rate[SNN_MAX_LAYERS]; /* measured mean rate of each hidden layer                */
+} snn_stats;
+
+/* Create a context: validates the configuration, allocates weights, gradients and the
+ * spike store for cfg->T steps on cfg->device.  No state storage is allocated here. */
+snn_status snn_init(const snn_config *cfg, snn_ctx **out);
+
+/* Copy one weight matrix into the context.  w: [pre][post] row-major fp32 (row = presynaptic
+ * neuron), host or device.  kind SNN_W_IN/SNN_W_REC take layer 0..L-1, SNN_W_OUT ignores it.
+ * mask_or_null (SNN_W_REC only): [N][N] bytes, 1 = synapse exists; masked weights must already
+ * be zero in w; the gradient of a masked matrix is zero where the mask is zero. */
+snn_status snn_set_weights(snn_ctx *ctx, int kind, int layer, const float *w, const uint8_t *mask_or_null);
+
+/* Forward pass only (event-driven recurrence, readout, loss); binds the inputs that a following
+ * snn_bptt uses.  in_spikes: [T][B][n_in] bytes 0/1, host or device; T <= cfg.T.  labels: [B]
+ * int32, host or device.  loss_out: one float, host.  Stores spikes (bitmasks) but no states. */
+snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out);
+
+/* One full training step (forward with the strategy's storage plan, loss, backward with
+ * recomputation) on the inputs bound by the last snn_forward/snn_bind_inputs.  Gradients stay in
+ * the context (overwritten by each call) until snn_grads copies them out.
+ *   STANDARD ignores both intervals; CHUNK uses fine_interval; REMOTE uses coarse_interval;
+ *   DOUBLE needs 1 <= fine <= coarse <= T.  0 = default (coarse ceil(sqrt T), fine ceil(sqrt coarse),
+ *   fine ceil(sqrt T) for CHUNK: the square-root rules of the paper's Hyperparameter Study).
+ *   hbm_budget_bytes caps activation storage (states + spike bitmasks + workspace, i.e.
+ *   snn_bytes_required); 0 = unlimited.  Over budget -> SNN_E_BUDGET before anything is allocated. */
+snn_status snn_bptt(snn_ctx *ctx, snn_strategy strategy, int32_t coarse_interval, int32_t fine_interval,
+                    size_t hbm_budget_bytes, snn_stats *stats_or_null);
+
+/* Bind inputs without running anything (same arguments as snn_forward). */
+snn_status snn_bind_inputs(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T);
+
+/* Copy a gradient tensor out.  dst: [pre][post] fp32, host or device, n_elems must match. */
+snn_status snn_grads(snn_ctx *ctx, int kind, int layer, float *dst, size_t n_elems);
+
+/* Parity/debug accessors (valid after snn_forward or snn_bptt). */
+snn_status snn_get_spikes(snn_ctx *ctx, int layer /*0..L-1*/, uint8_t *dst /*[T][B][N_l] bytes, host*/);
+snn_status snn_get_readout(snn_ctx *ctx, float *ubar /*[B][n_out], host*/, float *loss /*1 float, host*/);
+/* Runs a forward pass that stores every state and copies them out: dst [T][B][sum N_l] fp32, host. */
+snn_status snn_debug_states(snn_ctx *ctx, float *dst);
+
+/* Activation bytes the strategy needs in HBM for sequence length T (no context, no GPU needed).
+ * Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes + bytes_workspace. */
+size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t T, int32_t coarse_interval,
+                          int32_t fine_interval);
+/* Number of M_s-sized state slots of that plan held in HBM (the paper's closed forms plus the
+ * staging slots of the host tier) and, in *remote_slots (may be NULL), on the host. */
+int32_t snn_state_slots(snn_strategy strategy, int32_t T, int32_t coarse_interval, int32_t fine_interval,
+                        int32_t *remote_slots);
+/* Writes the schedule of the plan as int32 triples (op, a, b), at most cap triples, and returns
+ * the number of triples the full schedule has.  Ops: 1 SAVE_LOCAL c, 2 SAVE_REMOTE c, 3 LOAD_REMOTE c,
+ * 4 REFWD1 (a,b], 5 KEEP_FINE c, 6 REFWD2 (a,b], 7 BACKWARD a..b (descending). */
+int64_t snn_schedule(snn_strategy strategy, int32_t T, int32_t coarse_interval, int32_t fine_interval,
+                     int32_t *out_triples, int64_t cap);
+
+const char *snn_last_error(const snn_ctx *ctx); /* never NULL; "" if none */
+void snn_destroy(snn_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNN_H */

@@ -46,6 +46,12 @@
  * Checkpointing" and the Discussion say spikes of the full sequence are kept
  * and only the states are recomputed).
  *
+ * "forced states" mode additionally takes the membrane potentials v_t as inputs
+ * (full storage only).  It exists for one purpose: evaluating the backward pass
+ * in double precision on the exact fp32 forward trajectory, which separates the
+ * rounding error of a backward implementation from the (shared, bit-identical)
+ * rounding of the fp32 forward states.
+ *
  * Storage strategies (names as in the caption of Fig. 1):
  *   STANDARD  every state x_1..x_T is kept (eq. M_Base).
  *   CHUNK     x_c kept for c in {0,F,2F,..} < T in local memory, one chunk buffer
@@ -107,6 +113,7 @@ typedef struct {
   int32_t strategy; /* STRAT_* */
   int32_t C, F;     /* coarse (remote) and fine (local) checkpoint intervals */
   int32_t nthreads; /* OpenMP threads over the batch (1 = plain loop) */
+  int32_t forced_states; /* 1: membrane potentials are inputs too (vtraj[] read, STANDARD only) */
 } oracle_cfg;
 
 typedef struct {
@@ -343,8 +350,12 @@ static double bptt_one(const net_t *n, const spikes_t *sp, const int32_t *labels
     }
     advance_state(n, sp, b, t, x, xn, scratch, !c->forced);
     st->fwd_steps++;
+    if (c->forced_states)
+      for (int l = 0; l < L; ++l)
+        memcpy(xn + n->off[l], vtraj[l] + ((size_t)(t - 1) * B + b) * c->n_hidden[l],
+               (size_t)c->n_hidden[l] * sizeof(REAL));
     if (strat == STRAT_STANDARD) memcpy(traj + (size_t)(t - 1) * SN, xn, (size_t)SN * sizeof(REAL));
-    if (vtraj)
+    if (vtraj && !c->forced_states)
       for (int l = 0; l < L; ++l)
         memcpy(vtraj[l] + ((size_t)(t - 1) * B + b) * c->n_hidden[l], xn + n->off[l],
                (size_t)c->n_hidden[l] * sizeof(REAL));
@@ -470,6 +481,7 @@ int FN(oracle_bptt)(const oracle_cfg *cfg, const REAL *const *W_in, const REAL *
   if (cfg->strategy == STRAT_REMOTE && (cfg->C < 1 || cfg->C > T)) return 1;
   if (cfg->strategy == STRAT_DOUBLE && (cfg->F < 1 || cfg->F > cfg->C || cfg->C > T)) return 1;
   if (cfg->strategy < 0 || cfg->strategy > 3) return 1;
+  if (cfg->forced_states && (cfg->strategy != STRAT_STANDARD || !cfg->forced || !vtraj)) return 1;
 
   net_t n;
   n.c = cfg; n.L = L; n.W_in = W_in; n.W_rec = W_rec; n.W_out = W_out;

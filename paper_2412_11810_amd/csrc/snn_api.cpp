@@ -1,0 +1,593 @@
+// C ABI of the LIF-SNN BPTT library: context, weights, input binding, the checkpoint manager that
+// maps the paper's local/remote memory hierarchy onto HBM + pinned host memory, and the executor
+// that walks a checkpoint schedule (Fig. 1 of the paper) launching the HIP kernels.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/snn.h"
+#include "snn_internal.h"
+
+struct snn_ctx {
+  snn_config cfg{};
+  NetDev net{};
+  hipStream_t stream = nullptr;      // caller's stream (may be the null stream)
+  hipStream_t copy_stream = nullptr; // private side stream for checkpoint traffic
+  float *W_in[SNN_MAXL]{}, *W_rec[SNN_MAXL]{}, *W_out = nullptr;
+  float *W_inT[SNN_MAXL]{}, *W_recT[SNN_MAXL]{}, *W_outT = nullptr;
+  float *dW_in[SNN_MAXL]{}, *dW_rec[SNN_MAXL]{}, *dW_out = nullptr;
+  double *acc_in[SNN_MAXL]{}, *acc_rec[SNN_MAXL]{}, *acc_out = nullptr; // fp64 gradient accumulators
+  uint8_t *rec_mask[SNN_MAXL]{};
+  size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
+  int32_t *labels = nullptr;
+  int T_bound = 0;
+  double *readout = nullptr;
+  float *ubar = nullptr, *g = nullptr, *loss_dev = nullptr, *carry = nullptr;
+  unsigned long long *counters = nullptr;
+  // activation arena (HBM "local memory"), readout-adjoint tile, pinned host checkpoints
+  float *arena = nullptr;
+  size_t arena_bytes = 0;
+  float *dubuf = nullptr;
+  size_t dubuf_bytes = 0;
+  float *host_ckpt = nullptr;
+  size_t host_bytes = 0;
+  std::vector<hipEvent_t> ev_pool;
+  std::string err;
+  size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
+};
+
+namespace {
+
+snn_status fail(snn_ctx *c, snn_status s, const std::string &msg) {
+  if (c) c->err = msg;
+  return s;
+}
+
+#define HIPCHK(ctx, call)                                                                          \
+  do {                                                                                             \
+    hipError_t e_ = (call);                                                                        \
+    if (e_ != hipSuccess)                                                                          \
+      return fail(ctx, SNN_E_HIP, std::string(#call) + ": " + hipGetErrorString(e_));              \
+  } while (0)
+
+bool is_device_ptr(const void *p) {
+  hipPointerAttribute_t a;
+  if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return a.type == hipMemoryTypeDevice;
+}
+
+bool valid_cfg(const snn_config *c, std::string *why) {
+  if (!c) { *why = "null config"; return false; }
+  if (c->n_in < 1 || c->n_out < 1 || c->n_out > 1024 || c->T < 1 || c->batch < 1) { *why = "sizes must be positive (n_out <= 1024)"; return false; }
+  if (c->n_layers < 1 || c->n_layers > SNN_MAX_LAYERS) { *why = "n_layers must be 1..4"; return false; }
+  for (int l = 0; l < c->n_layers; ++l)
+    if (c->n_hidden[l] < 1 || c->n_hidden[l] > 65535) { *why = "n_hidden must be 1..65535"; return false; }
+  if (c->n_in > 65535) { *why = "n_in must be <= 65535"; return false; }
+  return true;
+}
+
+void fill_shape(const snn_config &c, NetDev *n) {
+  n->L = c.n_layers; n->n_in = c.n_in; n->n_out = c.n_out; n->B = c.batch;
+  n->off[0] = 0;
+  n->Wd[0] = (c.n_in + 63) / 64;
+  for (int l = 0; l < c.n_layers; ++l) {
+    n->N[l] = c.n_hidden[l];
+    n->off[l + 1] = n->off[l] + c.n_hidden[l];
+    n->Wd[l + 1] = (c.n_hidden[l] + 63) / 64;
+  }
+  n->SN = n->off[c.n_layers];
+  n->alpha = c.alpha; n->beta = c.beta_out; n->theta = c.theta; n->k = c.surr_beta;
+}
+
+int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
+
+size_t spike_bytes(const NetDev &n, int T) {
+  size_t w = 0;
+  for (int l = 0; l <= n.L; ++l) w += (size_t)(T + 1) * n.B * n.Wd[l];
+  return w * 8;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *snn_last_error(const snn_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int32_t snn_state_slots(snn_strategy strategy, int32_t T, int32_t C, int32_t F, int32_t *remote_slots) {
+  Plan p;
+  if (!snn_make_plan((int)strategy, T, C, F, &p)) return 0;
+  if (remote_slots) *remote_slots = p.n_remote;
+  return p.local_slots();
+}
+
+int64_t snn_schedule(snn_strategy strategy, int32_t T, int32_t C, int32_t F, int32_t *out, int64_t cap) {
+  Plan p;
+  if (!snn_make_plan((int)strategy, T, C, F, &p)) return -1;
+  static_assert(sizeof(SchedOp) == 3 * sizeof(int32_t), "triples");
+  return snn_make_schedule(p, reinterpret_cast<SchedOp *>(out), out ? cap : 0);
+}
+
+size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t T, int32_t C, int32_t F) {
+  std::string why;
+  if (!valid_cfg(cfg, &why)) return 0;
+  Plan p;
+  if (!snn_make_plan((int)strategy, T, C, F, &p)) return 0;
+  NetDev n{};
+  fill_shape(*cfg, &n);
+  const size_t Ms = (size_t)n.B * n.SN * sizeof(float);
+  const size_t work = (size_t)p.chunk_len * n.B * n.n_out * sizeof(float);
+  return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work;
+}
+
+snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
+  if (!out) return SNN_E_INVAL;
+  *out = nullptr;
+  std::string why;
+  snn_ctx *c = new snn_ctx();
+  *out = c; // returned even on failure so that the caller can read the error text
+  if (!valid_cfg(cfg, &why)) return fail(c, SNN_E_INVAL, why);
+  c->cfg = *cfg;
+  fill_shape(*cfg, &c->net);
+  char buf[256];
+  if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
+  int ndev = 0;
+  HIPCHK(c, hipGetDeviceCount(&ndev));
+  if (cfg->device < 0 || cfg->device >= ndev) return fail(c, SNN_E_INVAL, "no such device");
+  HIPCHK(c, hipSetDevice(cfg->device));
+  c->stream = (hipStream_t)cfg->stream;
+  HIPCHK(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+  NetDev &n = c->net;
+  const int L = n.L, B = n.B, O = n.n_out;
+  for (int l = 0; l < L; ++l) {
+    const size_t ni = (size_t)pre_of(n, l) * n.N[l], nr = (size_t)n.N[l] * n.N[l];
+    HIPCHK(c, hipMalloc(&c->W_in[l], ni * 4));
+    HIPCHK(c, hipMalloc(&c->W_inT[l], ni * 4));
+    HIPCHK(c, hipMalloc(&c->dW_in[l], ni * 4));
+    HIPCHK(c, hipMalloc(&c->acc_in[l], ni * 8));
+    HIPCHK(c, hipMalloc(&c->acc_rec[l], nr * 8));
+    HIPCHK(c, hipMalloc(&c->W_rec[l], nr * 4));
+    HIPCHK(c, hipMalloc(&c->W_recT[l], nr * 4));
+    HIPCHK(c, hipMalloc(&c->dW_rec[l], nr * 4));
+    HIPCHK(c, hipMemsetAsync(c->W_in[l], 0, ni * 4, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->W_inT[l], 0, ni * 4, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->W_rec[l], 0, nr * 4, c->stream));
+    HIPCHK(c, hipMemsetAsync(c->W_recT[l], 0, nr * 4, c->stream));
+    n.W_in[l] = c->W_in[l]; n.W_rec[l] = c->W_rec[l]; n.W_inT[l] = c->W_inT[l]; n.W_recT[l] = c->W_recT[l];
+  }
+  const size_t no = (size_t)n.N[L - 1] * O;
+  HIPCHK(c, hipMalloc(&c->W_out, no * 4));
+  HIPCHK(c, hipMalloc(&c->W_outT, no * 4));
+  HIPCHK(c, hipMalloc(&c->dW_out, no * 4));
+  HIPCHK(c, hipMalloc(&c->acc_out, no * 8));
+  HIPCHK(c, hipMemsetAsync(c->W_out, 0, no * 4, c->stream));
+  HIPCHK(c, hipMemsetAsync(c->W_outT, 0, no * 4, c->stream));
+  n.W_out = c->W_out; n.W_outT = c->W_outT;
+  for (int l = 0; l <= L; ++l) {
+    c->mask_words[l] = (size_t)(cfg->T + 1) * B * n.Wd[l];
+    HIPCHK(c, hipMalloc(&n.mask[l], c->mask_words[l] * 8));
+    HIPCHK(c, hipMemsetAsync(n.mask[l], 0, c->mask_words[l] * 8, c->stream));
+  }
+  HIPCHK(c, hipMalloc(&c->labels, (size_t)B * 4));
+  HIPCHK(c, hipMalloc(&c->readout, (size_t)B * 2 * O * 8));
+  HIPCHK(c, hipMalloc(&c->ubar, (size_t)B * O * 4));
+  HIPCHK(c, hipMalloc(&c->g, (size_t)B * O * 4));
+  HIPCHK(c, hipMalloc(&c->loss_dev, 16));
+  HIPCHK(c, hipMalloc(&c->carry, (size_t)B * (n.SN + O) * 4));
+  HIPCHK(c, hipMalloc(&c->counters, 8 * (SNN_MAXL + 1)));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return SNN_OK;
+}
+
+void snn_destroy(snn_ctx *c) {
+  if (!c) return;
+  (void)hipSetDevice(c->cfg.device);
+  (void)hipDeviceSynchronize();
+  for (int l = 0; l < SNN_MAXL; ++l) {
+    (void)hipFree(c->W_in[l]); (void)hipFree(c->W_rec[l]); (void)hipFree(c->W_inT[l]); (void)hipFree(c->W_recT[l]);
+    (void)hipFree(c->dW_in[l]); (void)hipFree(c->dW_rec[l]); (void)hipFree(c->rec_mask[l]);
+    (void)hipFree(c->acc_in[l]); (void)hipFree(c->acc_rec[l]);
+  }
+  for (int l = 0; l <= SNN_MAXL; ++l) (void)hipFree(c->net.mask[l]);
+  (void)hipFree(c->W_out); (void)hipFree(c->W_outT); (void)hipFree(c->dW_out); (void)hipFree(c->acc_out);
+  (void)hipFree(c->labels); (void)hipFree(c->readout); (void)hipFree(c->ubar); (void)hipFree(c->g);
+  (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->counters);
+  (void)hipFree(c->arena); (void)hipFree(c->dubuf);
+  if (c->host_ckpt) (void)hipHostFree(c->host_ckpt);
+  for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+  if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  delete c;
+}
+
+snn_status snn_set_weights(snn_ctx *c, int kind, int layer, const float *w, const uint8_t *mask) {
+  if (!c || !w) return fail(c, SNN_E_INVAL, "null argument");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  NetDev &n = c->net;
+  float *dst, *dstT;
+  int rows, cols;
+  if (kind == SNN_W_OUT) {
+    dst = c->W_out; dstT = c->W_outT; rows = n.N[n.L - 1]; cols = n.n_out;
+  } else if ((kind == SNN_W_IN || kind == SNN_W_REC) && layer >= 0 && layer < n.L) {
+    dst = kind == SNN_W_IN ? c->W_in[layer] : c->W_rec[layer];
+    dstT = kind == SNN_W_IN ? c->W_inT[layer] : c->W_recT[layer];
+    rows = kind == SNN_W_IN ? pre_of(n, layer) : n.N[layer];
+    cols = n.N[layer];
+  } else {
+    return fail(c, SNN_E_INVAL, "bad tensor kind/layer");
+  }
+  if (mask && kind != SNN_W_REC) return fail(c, SNN_E_INVAL, "mask only for recurrent matrices");
+  const size_t ne = (size_t)rows * cols;
+  HIPCHK(c, hipMemcpyAsync(dst, w, ne * 4, hipMemcpyDefault, c->stream));
+  HIPCHK(c, launch_transpose(dst, dstT, rows, cols, c->stream));
+  if (kind == SNN_W_REC) {
+    if (mask) {
+      if (!c->rec_mask[layer]) HIPCHK(c, hipMalloc(&c->rec_mask[layer], ne));
+      HIPCHK(c, hipMemcpyAsync(c->rec_mask[layer], mask, ne, hipMemcpyDefault, c->stream));
+    } else if (c->rec_mask[layer]) {
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      HIPCHK(c, hipFree(c->rec_mask[layer]));
+      c->rec_mask[layer] = nullptr;
+    }
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return SNN_OK;
+}
+
+snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labels, int32_t T) {
+  if (!c || !in_spikes || !labels) return fail(c, SNN_E_INVAL, "null argument");
+  if (T < 1 || T > c->cfg.T) return fail(c, SNN_E_INVAL, "T out of range for this context");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  const NetDev &n = c->net;
+  const size_t bytes = (size_t)T * n.B * n.n_in;
+  const uint8_t *src = in_spikes;
+  uint8_t *tmp = nullptr;
+  if (!is_device_ptr(in_spikes)) {
+    HIPCHK(c, hipMalloc(&tmp, bytes));
+    hipError_t e = hipMemcpyAsync(tmp, in_spikes, bytes, hipMemcpyHostToDevice, c->stream);
+    if (e != hipSuccess) { (void)hipFree(tmp); return fail(c, SNN_E_HIP, hipGetErrorString(e)); }
+    src = tmp;
+  }
+  hipError_t e = launch_pack_inputs(src, n.mask[0], T, n.B, n.n_in, n.Wd[0], c->stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(c->labels, labels, (size_t)n.B * 4, hipMemcpyDefault, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (tmp) (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  // labels are validated on the host side of the binding; clamp nothing here
+  c->T_bound = T;
+  return SNN_OK;
+}
+
+static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
+  const NetDev &n = c->net;
+  StoreSpec st{};
+  if (traj_or_null) {
+    st.base = traj_or_null; st.slot_stride = (size_t)n.B * n.SN; st.t_base = 0; st.interval = 1; st.slot0 = 0;
+    st.t_max = c->T_bound;
+  }
+  HIPCHK(c, launch_forward(n, true, 0, c->T_bound, nullptr, nullptr, st, c->readout, 1, c->stream));
+  HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
+  return SNN_OK;
+}
+
+snn_status snn_forward(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out) {
+  snn_status s = snn_bind_inputs(c, in_spikes, labels, T);
+  if (s != SNN_OK) return s;
+  s = forward_only(c, nullptr);
+  if (s != SNN_OK) return s;
+  float loss = 0.f;
+  HIPCHK(c, hipMemcpyAsync(&loss, c->loss_dev, 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (loss_out) *loss_out = loss;
+  return SNN_OK;
+}
+
+snn_status snn_debug_states(snn_ctx *c, float *dst) {
+  if (!c || !dst) return fail(c, SNN_E_INVAL, "null argument");
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  float *traj = nullptr;
+  const size_t bytes = (size_t)c->T_bound * c->Ms();
+  HIPCHK(c, hipMalloc(&traj, bytes));
+  snn_status s = forward_only(c, traj);
+  hipError_t e = hipSuccess;
+  if (s == SNN_OK) e = hipMemcpyAsync(dst, traj, bytes, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  (void)hipFree(traj);
+  if (s != SNN_OK) return s;
+  if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  return SNN_OK;
+}
+
+snn_status snn_get_spikes(snn_ctx *c, int layer, uint8_t *dst) {
+  if (!c || !dst || layer < 0 || layer >= c->net.L) return fail(c, SNN_E_INVAL, "bad argument");
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  const NetDev &n = c->net;
+  const size_t bytes = (size_t)c->T_bound * n.B * n.N[layer];
+  uint8_t *tmp = nullptr;
+  HIPCHK(c, hipMalloc(&tmp, bytes));
+  hipError_t e = launch_unpack_spikes(n.mask[layer + 1], n.Wd[layer + 1], n.N[layer], c->T_bound, n.B, tmp, c->stream);
+  if (e == hipSuccess) e = hipMemcpyAsync(dst, tmp, bytes, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  return SNN_OK;
+}
+
+snn_status snn_get_readout(snn_ctx *c, float *ubar, float *loss) {
+  if (!c) return SNN_E_INVAL;
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  if (ubar) HIPCHK(c, hipMemcpyAsync(ubar, c->ubar, (size_t)c->net.B * c->net.n_out * 4, hipMemcpyDeviceToHost, c->stream));
+  if (loss) HIPCHK(c, hipMemcpyAsync(loss, c->loss_dev, 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return SNN_OK;
+}
+
+snn_status snn_grads(snn_ctx *c, int kind, int layer, float *dst, size_t n_elems) {
+  if (!c || !dst) return fail(c, SNN_E_INVAL, "null argument");
+  const NetDev &n = c->net;
+  const float *src;
+  size_t ne;
+  if (kind == SNN_W_OUT) { src = c->dW_out; ne = (size_t)n.N[n.L - 1] * n.n_out; }
+  else if ((kind == SNN_W_IN || kind == SNN_W_REC) && layer >= 0 && layer < n.L) {
+    src = kind == SNN_W_IN ? c->dW_in[layer] : c->dW_rec[layer];
+    ne = (size_t)(kind == SNN_W_IN ? pre_of(n, layer) : n.N[layer]) * n.N[layer];
+  } else return fail(c, SNN_E_INVAL, "bad tensor kind/layer");
+  if (ne != n_elems) return fail(c, SNN_E_INVAL, "n_elems does not match the tensor");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipMemcpyAsync(dst, src, ne * 4, hipMemcpyDefault, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return SNN_OK;
+}
+
+// ---- the training step ----------------------------------------------------------------------
+
+namespace {
+struct Timer {
+  snn_ctx *c;
+  bool on;
+  size_t used = 0;
+  struct Span { hipEvent_t a, b; int kind; };
+  std::vector<Span> spans;
+  hipEvent_t get() {
+    if (used == c->ev_pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      c->ev_pool.push_back(e);
+    }
+    return c->ev_pool[used++];
+  }
+  hipEvent_t mark() {
+    hipEvent_t e = get();
+    if (e) (void)hipEventRecord(e, c->stream);
+    return e;
+  }
+  void begin(int kind) { if (on) spans.push_back(Span{mark(), nullptr, kind}); }
+  void end() { if (on) spans.back().b = mark(); }
+};
+} // namespace
+
+snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_in, size_t budget, snn_stats *stats) {
+  if (!c) return SNN_E_INVAL;
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "snn_bptt needs inputs bound by snn_forward/snn_bind_inputs");
+  const int T = c->T_bound;
+  Plan p;
+  if (!snn_make_plan((int)strategy, T, C_in, F_in, &p)) return fail(c, SNN_E_INVAL, "invalid strategy/intervals");
+  NetDev &n = c->net;
+  const int B = n.B, O = n.n_out, L = n.L, SN = n.SN;
+  const size_t Ms = c->Ms(), slot = (size_t)B * SN;
+  const size_t need_states = (size_t)p.local_slots() * Ms;
+  const size_t need_work = (size_t)p.chunk_len * B * O * sizeof(float);
+  const size_t need_spikes = spike_bytes(n, T);
+  if (budget && need_states + need_work + need_spikes > budget) {
+    char buf[200];
+    snprintf(buf, sizeof buf, "needs %zu B of HBM activation memory (%d state slots), budget is %zu B",
+             need_states + need_work + need_spikes, p.local_slots(), budget);
+    return fail(c, SNN_E_BUDGET, buf);
+  }
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  hipStream_t s = c->stream, cs = c->copy_stream;
+  // ---- storage -----------------------------------------------------------------------------
+  if (c->arena_bytes < need_states) {
+    HIPCHK(c, hipStreamSynchronize(s));
+    if (c->arena) HIPCHK(c, hipFree(c->arena));
+    c->arena = nullptr; c->arena_bytes = 0;
+    HIPCHK(c, hipMalloc(&c->arena, need_states));
+    c->arena_bytes = need_states;
+  }
+  if (c->dubuf_bytes < need_work) {
+    HIPCHK(c, hipStreamSynchronize(s));
+    if (c->dubuf) HIPCHK(c, hipFree(c->dubuf));
+    c->dubuf = nullptr; c->dubuf_bytes = 0;
+    HIPCHK(c, hipMalloc(&c->dubuf, need_work));
+    c->dubuf_bytes = need_work;
+  }
+  const size_t need_host = (size_t)p.n_remote * Ms;
+  if (c->host_bytes < need_host) {
+    if (c->host_ckpt) HIPCHK(c, hipHostFree(c->host_ckpt));
+    c->host_ckpt = nullptr; c->host_bytes = 0;
+    if (hipHostMalloc(&c->host_ckpt, need_host, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(c, SNN_E_HOSTMEM, "pinned host allocation for remote checkpoints failed");
+    }
+    c->host_bytes = need_host;
+  }
+  float *chunk = c->arena;                                   // chunk buffer / trajectory
+  float *lckpt = chunk + (size_t)p.chunk_len * slot;         // local checkpoints
+  float *loadb = lckpt + (size_t)p.n_local_ckpt * slot;      // 2 slots receiving host checkpoints
+  float *stage = loadb + (size_t)p.n_load_slots * slot;      // 2 slots staging D2H copies
+
+  Timer tm{c, stats != nullptr};
+  hipEvent_t ev_start = tm.mark();
+  if (!ev_start) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+  snn_stats st{};
+  st.bytes_states = (int64_t)need_states; st.bytes_spikes = (int64_t)need_spikes; st.bytes_workspace = (int64_t)need_work;
+  st.bytes_host = (int64_t)need_host; st.local_state_slots = p.local_slots(); st.remote_state_slots = p.n_remote;
+
+  for (int l = 0; l < L; ++l) {
+    HIPCHK(c, hipMemsetAsync(c->acc_in[l], 0, (size_t)pre_of(n, l) * n.N[l] * 8, s));
+    HIPCHK(c, hipMemsetAsync(c->acc_rec[l], 0, (size_t)n.N[l] * n.N[l] * 8, s));
+  }
+  HIPCHK(c, hipMemsetAsync(c->acc_out, 0, (size_t)n.N[L - 1] * O * 8, s));
+
+  // events for the host tier
+  hipEvent_t ev_stage_ready[2] = {nullptr, nullptr}, ev_stage_free[2] = {nullptr, nullptr};
+  hipEvent_t ev_load_ready[2] = {nullptr, nullptr}, ev_load_free[2] = {nullptr, nullptr};
+  bool stage_busy[2] = {false, false}, load_used[2] = {false, false};
+  const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE;
+  if (remote)
+    for (int i = 0; i < 2; ++i) {
+      ev_stage_ready[i] = tm.get(); ev_stage_free[i] = tm.get(); ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
+      if (!ev_stage_ready[i] || !ev_stage_free[i] || !ev_load_ready[i] || !ev_load_free[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+    }
+
+  // ---- forward ------------------------------------------------------------------------------
+  if (strategy == SNN_STANDARD) {
+    StoreSpec sp{chunk, slot, 0, 1, 0, T};
+    HIPCHK(c, launch_forward(n, true, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+  } else if (strategy == SNN_CHUNK) {
+    HIPCHK(c, hipMemsetAsync(lckpt, 0, Ms, s)); // x_0
+    StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
+    HIPCHK(c, launch_forward(n, true, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+  } else {
+    std::memset(c->host_ckpt, 0, Ms); // x_0 lives in host slot 0
+    StoreSpec none{};
+    for (int K = 0; K < p.n_remote; ++K) {
+      const int a = K * p.C, e = std::min(a + p.C, T);
+      const bool keep = K + 1 < p.n_remote; // x_e is the next coarse checkpoint
+      const int so = K & 1;
+      if (keep && stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
+      HIPCHK(c, launch_forward(n, true, a, e, K == 0 ? nullptr : stage + (size_t)((K - 1) & 1) * slot,
+                               keep ? stage + (size_t)so * slot : nullptr, none, c->readout, K == 0, s));
+      if (keep) {
+        HIPCHK(c, hipEventRecord(ev_stage_ready[so], s));
+        HIPCHK(c, hipStreamWaitEvent(cs, ev_stage_ready[so], 0));
+        HIPCHK(c, hipMemcpyAsync(c->host_ckpt + (size_t)(K + 1) * slot, stage + (size_t)so * slot, Ms, hipMemcpyDeviceToHost, cs));
+        HIPCHK(c, hipEventRecord(ev_stage_free[so], cs));
+        stage_busy[so] = true;
+        st.n_d2h++; st.d2h_bytes += (int64_t)Ms;
+      }
+    }
+    // x_0 counts as a write of the paper's N_c (it is a host-side memset here, no transfer)
+  }
+  st.fwd_steps = T;
+  HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));
+  hipEvent_t ev_fwd = tm.mark();
+
+  // ---- backward: walk the schedule ------------------------------------------------------------
+  std::vector<SchedOp> ops((size_t)snn_make_schedule(p, nullptr, 0));
+  snn_make_schedule(p, ops.data(), (int64_t)ops.size());
+  if (remote) {
+    // every checkpoint must be on the host before the first load
+    HIPCHK(c, hipStreamSynchronize(cs));
+  }
+  int seg_start = 0, chunk_base = 0, cur_load = 0, n_loads = 0;
+  bool first_adjoint = true;
+  auto issue_load = [&](int K, int slot_i) -> hipError_t {
+    hipError_t e = hipSuccess;
+    if (load_used[slot_i]) e = hipStreamWaitEvent(cs, ev_load_free[slot_i], 0);
+    if (e == hipSuccess) e = hipMemcpyAsync(loadb + (size_t)slot_i * slot, c->host_ckpt + (size_t)K * slot, Ms, hipMemcpyHostToDevice, cs);
+    if (e == hipSuccess) e = hipEventRecord(ev_load_ready[slot_i], cs);
+    st.n_h2d++; st.h2d_bytes += (int64_t)Ms;
+    return e;
+  };
+  if (remote) HIPCHK(c, issue_load(p.n_remote - 1, (p.n_remote - 1) & 1));
+  for (size_t i = 0; i < ops.size(); ++i) {
+    const SchedOp &op = ops[i];
+    switch (op.op) {
+      case OP_LOAD_REMOTE: {
+        const int K = op.a / p.C;
+        if (n_loads > 0) {
+          // the segment that used the other... previous slot is fully queued: mark it reusable
+          HIPCHK(c, hipEventRecord(ev_load_free[cur_load], s));
+          load_used[cur_load] = true;
+        }
+        cur_load = K & 1;
+        seg_start = op.a;
+        HIPCHK(c, hipStreamWaitEvent(s, ev_load_ready[cur_load], 0));
+        ++n_loads;
+        // prefetch the next (earlier) coarse checkpoint into the other slot; that slot was last
+        // read by the segment before this one in execution order
+        if (K > 0) HIPCHK(c, issue_load(K - 1, (K - 1) & 1));
+        break;
+      }
+      case OP_REFWD1: {
+        StoreSpec sp{lckpt, slot, op.a, p.F, 0, op.b};
+        tm.begin(1);
+        HIPCHK(c, launch_forward(n, false, op.a, op.b, loadb + (size_t)cur_load * slot, nullptr, sp, c->readout, 0, s));
+        tm.end();
+        st.refwd1_steps += op.b - op.a;
+        break;
+      }
+      case OP_REFWD2: {
+        const float *src;
+        if (strategy == SNN_CHUNK) src = lckpt + (size_t)(op.a / p.F) * slot;
+        else if (strategy == SNN_REMOTE || op.a == seg_start) src = loadb + (size_t)cur_load * slot;
+        else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
+        StoreSpec sp{chunk, slot, op.a, 1, 0, op.b};
+        chunk_base = op.a;
+        tm.begin(1);
+        HIPCHK(c, launch_forward(n, false, op.a, op.b, src, nullptr, sp, c->readout, 0, s));
+        tm.end();
+        st.refwd2_steps += op.b - op.a;
+        break;
+      }
+      case OP_BACKWARD: {
+        const int t1 = op.a, t0 = op.b - 1;
+        const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
+        tm.begin(2);
+        HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0, s));
+        tm.end();
+        first_adjoint = false;
+        tm.begin(3);
+        HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, c->dubuf, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
+        for (int l = 0; l < L; ++l) {
+          HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
+          HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
+        }
+        tm.end();
+        st.bwd_steps += t1 - t0;
+        break;
+      }
+      default:
+        break; // SAVE_* happen in the forward pass; KEEP_FINE is part of REFWD1
+    }
+  }
+  for (int l = 0; l < L; ++l) {
+    HIPCHK(c, launch_finish_grad(c->acc_in[l], nullptr, c->dW_in[l], (size_t)pre_of(n, l) * n.N[l], s));
+    HIPCHK(c, launch_finish_grad(c->acc_rec[l], c->rec_mask[l], c->dW_rec[l], (size_t)n.N[l] * n.N[l], s));
+  }
+  HIPCHK(c, launch_finish_grad(c->acc_out, nullptr, c->dW_out, (size_t)n.N[L - 1] * O, s));
+  hipEvent_t ev_end = tm.mark();
+  if (stats) {
+    HIPCHK(c, hipMemsetAsync(c->counters, 0, 8 * (SNN_MAXL + 1), s));
+    for (int l = 1; l <= L; ++l)
+      HIPCHK(c, launch_count_spikes(n.mask[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
+  }
+  HIPCHK(c, hipStreamSynchronize(cs));
+  HIPCHK(c, hipStreamSynchronize(s));
+  if (stats) {
+    unsigned long long cnt[SNN_MAXL + 1];
+    HIPCHK(c, hipMemcpy(cnt, c->counters, sizeof cnt, hipMemcpyDeviceToHost));
+    for (int l = 0; l < L; ++l) st.firing_rate[l] = (float)((double)cnt[l + 1] / ((double)T * B * n.N[l]));
+    (void)hipEventElapsedTime(&st.ms_total, ev_start, ev_end);
+    (void)hipEventElapsedTime(&st.ms_forward, ev_start, ev_fwd);
+    (void)hipEventElapsedTime(&st.ms_backward_total, ev_fwd, ev_end);
+    for (const auto &sp : tm.spans) {
+      float ms = 0.f;
+      if (sp.a && sp.b) (void)hipEventElapsedTime(&ms, sp.a, sp.b);
+      if (sp.kind == 1) st.ms_recompute += ms;
+      else if (sp.kind == 2) st.ms_adjoint += ms;
+      else st.ms_dw += ms;
+    }
+    *stats = st;
+  }
+  return SNN_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,90 @@
+// Internal declarations shared by the host-side orchestration and the HIP kernels of the
+// LIF-SNN BPTT library (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#define SNN_MAXL 4
+
+// Device-visible description of the network and of where its data lives in HBM.
+//
+// Weights: fp32, [pre][post] row-major, so the synapses leaving one presynaptic neuron are one
+// contiguous row (one active spike = one coalesced row read).  *_T are [post][pre] copies used by
+// the adjoint pass (delta_s[j] = sum_n W[j][n] * delta_v[n] becomes a coalesced column walk).
+// Spikes: one bit per neuron, 64-bit words, mask[l] = [T+1][B][Wd[l]] with row 0 (t = 0) all zero;
+// layer index 0 is the input layer, l >= 1 hidden layer l.
+// States: slots of B*SN floats laid out [B][SN] (all layers of one batch element contiguous).
+struct NetDev {
+  int L, n_in, n_out, B, SN;
+  int N[SNN_MAXL];        // neurons of hidden layer l (0-based here)
+  int off[SNN_MAXL + 1];  // offset of layer l inside a state vector
+  int Wd[SNN_MAXL + 1];   // 64-bit words per (t, b) of layer index 0..L (0 = input)
+  const float *W_in[SNN_MAXL], *W_rec[SNN_MAXL], *W_out;
+  const float *W_inT[SNN_MAXL], *W_recT[SNN_MAXL], *W_outT;
+  uint64_t *mask[SNN_MAXL + 1];
+  float alpha, beta, theta, k;
+};
+
+// Where the forward / recompute kernel writes states it has to keep.
+struct StoreSpec {
+  float *base;        // slot 0 of the destination array (NULL = store nothing)
+  size_t slot_stride; // floats between slots (= B*SN)
+  int t_base;         // state x_t goes to slot (t - t_base)/interval - 1 + slot0 ...
+  int interval;       // ... when (t - t_base) % interval == 0
+  int slot0;
+  int t_max;          // ... and t <= t_max
+};
+
+struct LaunchCfg {
+  int nt_neuron; // threads that own neurons (multiple of 64)
+  int npt;       // neurons per owning thread (template instance)
+  size_t lds_bytes;
+};
+
+// ---- launchers (defined in snn_kernels.hip) ---------------------------------------------
+hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
+                              hipStream_t s);
+// Runs steps t0+1..t1 for all batch elements.  generate: threshold + compaction (forward pass);
+// otherwise spikes are read from the stored bitmasks (recompute pass, no spike generation).
+hipError_t launch_forward(const NetDev &net, bool generate, int t0, int t1, const float *state_in,
+                          float *state_out, const StoreSpec &st, double *readout /*[B][2][O]*/,
+                          int readout_init, hipStream_t s);
+hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
+                       float *g, float *loss, hipStream_t s);
+// Adjoint recurrence over steps t1, t1-1, ..., t0+1.  vbuf holds x_t at slot (t - t_base - 1) and is
+// overwritten in place by delta_v_t.  dubuf gets delta_u_t at the same slot index ([slot][B][O]).
+// carry: [B][SN + O] floats (delta_v_{t+1} of all layers, delta_u_{t+1}); carry_init zeroes it first.
+hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf,
+                          const float *g, float *carry, int carry_init, hipStream_t s);
+// dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
+// where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
+// element) and column offset post_off.
+hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,
+                     size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1,
+                     int t_base, double *dW, hipStream_t s);
+hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
+hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
+hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,
+                                hipStream_t s);
+hipError_t launch_count_spikes(const uint64_t *mask, size_t n_words, unsigned long long *count, hipStream_t s);
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len);
+
+// ---- schedule / budget logic (snn_schedule.cpp; plain host code) --------------------------
+enum { OP_SAVE_LOCAL = 1, OP_SAVE_REMOTE = 2, OP_LOAD_REMOTE = 3, OP_REFWD1 = 4, OP_KEEP_FINE = 5,
+       OP_REFWD2 = 6, OP_BACKWARD = 7 };
+struct SchedOp { int op, a, b; };
+struct Plan {
+  int strategy, T, C, F;
+  int chunk_len;      // slots of the chunk buffer (trajectory length for STANDARD)
+  int n_local_ckpt;   // HBM checkpoints (CHUNK: ceil(T/F); DOUBLE: fine checkpoints per segment)
+  int n_load_slots;   // HBM slots receiving host checkpoints (prefetch double buffer)
+  int n_stage_slots;  // HBM slots staging device->host copies
+  int n_remote;       // host slots
+  int local_slots() const { return chunk_len + n_local_ckpt + n_load_slots + n_stage_slots; }
+};
+// Resolves defaults (0 -> square-root rules) and validates.  Returns false on invalid arguments.
+bool snn_make_plan(int strategy, int T, int C, int F, Plan *out);
+// Backward-phase schedule (and forward-phase saves first), in execution order.
+int64_t snn_make_schedule(const Plan &p, SchedOp *out, int64_t cap);

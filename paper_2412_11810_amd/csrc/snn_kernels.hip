@@ -1,0 +1,622 @@
+// HIP kernels (gfx950, wave64) for event-driven LIF-SNN forward / recompute passes, the
+// surrogate-gradient adjoint recurrence and the weight-gradient accumulation over active spikes.
+//
+// Arithmetic contract (what makes spike trains reproducible bit for bit, and every storage
+// strategy give identical gradients):
+//   * the synaptic current of a neuron is two separate fp32 sums that start from 0.0f and add
+//     the weight rows of the active presynaptic neurons in ascending index order (input rows,
+//     then recurrent rows); they are added together, then to (alpha*v - theta*s_prev);
+//   * no fused multiply-add in the forward/recompute path (this file is compiled with
+//     -ffp-contract=off; the adjoint pass uses explicit fmaf);
+//   * a recompute pass runs the very same code as the forward pass, minus spike generation;
+//   * weight gradients are accumulated per element in a fixed order (time descending, batch
+//     ascending) that does not depend on where chunk boundaries fall;
+//   * no floating-point atomics anywhere.
+#include "snn_internal.h"
+
+#define WAVE 64
+
+static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+static __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+
+// ------------------------------------------------------------------------------------------
+// A1 (inputs): byte spikes [T][B][n_in] -> bit words mask0[t+1][b][w] (row 0 = step 0 = zeros)
+// One workgroup of one wave per (t, b); the wave ballots 64 channels at a time.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(WAVE) k_pack_inputs(const uint8_t *__restrict__ in, uint64_t *__restrict__ mask0,
+                                                      int B, int n_in, int Wd0) {
+  const size_t tb = blockIdx.x; // t*B + b, t zero-based
+  const uint8_t *row = in + tb * (size_t)n_in;
+  uint64_t *dst = mask0 + ((size_t)B + tb) * Wd0; // skip row 0
+  for (int w = 0; w < Wd0; ++w) {
+    const int j = w * WAVE + lane_id();
+    const bool s = j < n_in && row[j] != 0;
+    const uint64_t word = __ballot(s);
+    if (lane_id() == 0) dst[w] = word;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward / recompute: one workgroup per batch element, time loop on the device.
+// ------------------------------------------------------------------------------------------
+template <int NPT, int U>
+static __device__ __forceinline__ void gather_rows(const float *__restrict__ W, int N, int n0, int nt,
+                                                   const uint16_t *lst, int cnt, float (&acc)[NPT]) {
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) acc[k] = 0.0f;
+  int i = 0;
+  for (; i + U <= cnt; i += U) {
+    float w[U][NPT];
+#pragma unroll
+    for (int q = 0; q < U; ++q) {
+      const float *row = W + (size_t)lst[i + q] * N;
+#pragma unroll
+      for (int k = 0; k < NPT; ++k) {
+        const int n = n0 + k * nt;
+        w[q][k] = n < N ? row[n] : 0.0f;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < U; ++q)
+#pragma unroll
+      for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + w[q][k];
+  }
+  for (; i < cnt; ++i) {
+    const float *row = W + (size_t)lst[i] * N;
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      const int n = n0 + k * nt;
+      if (n < N) acc[k] = acc[k] + row[n];
+    }
+  }
+}
+
+// Owner threads turn the bit words of one layer into the ascending list of active indices
+// (popcount prefix over the words, then the rank of the own bit inside its word).
+static __device__ __forceinline__ void expand_owner(const uint64_t *words, int Wd, uint16_t *list, int *cnt,
+                                                    int tid, int nt, int npt) {
+  for (int k = 0; k < npt; ++k) {
+    const int widx = (tid >> 6) + k * (nt >> 6);
+    if (widx >= Wd) break;
+    const uint64_t word = words[widx];
+    int pre = 0;
+    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
+    if ((word >> lane_id()) & 1ull) list[pre + __popcll(word & lanemask_lt())] = (uint16_t)(widx * WAVE + lane_id());
+    if (widx == Wd - 1 && lane_id() == 0) *cnt = pre + __popcll(word);
+  }
+}
+
+template <int NPT, bool GEN>
+__global__ void __launch_bounds__(576)
+k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *__restrict__ state_out,
+          StoreSpec st, double *__restrict__ readout, int readout_init, int nt) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, b = blockIdx.x, lane = lane_id();
+  const int L = net.L, B = net.B, O = net.n_out;
+  const bool service = tid >= nt; // the last wave owns no neurons: input lists + readout
+
+  // ---- LDS carve-up -------------------------------------------------------------------
+  int wdmax = 1;
+  for (int l = 1; l <= L; ++l) wdmax = net.Wd[l] > wdmax ? net.Wd[l] : wdmax;
+  uint64_t *words = (uint64_t *)smem;                         // [L+1][wdmax] (row 0 unused)
+  // readout state in fp64: ubar feeds a softmax, which turns an absolute error of ubar into a
+  // relative error of the loss gradient, and fp32 sums over thousands of steps lose ~1e-4 there
+  double *u = (double *)(words + (size_t)(L + 1) * wdmax);   // [O]
+  double *usum = u + O;                                       // [O]
+  int *cnt = (int *)(usum + O);                               // [8]
+  uint16_t *lists = (uint16_t *)(cnt + 8);
+  int lo[SNN_MAXL + 2];
+  lo[0] = 0;
+  lo[1] = (net.n_in + 7) & ~7;
+  for (int l = 1; l <= L; ++l) lo[l + 1] = lo[l] + ((net.N[l - 1] + 7) & ~7);
+
+  // ---- initial condition at t0 ---------------------------------------------------------
+  float v[SNN_MAXL][NPT];
+  uint32_t sp[SNN_MAXL]; // bit k: own neuron k of that layer spiked at the previous step
+#pragma unroll
+  for (int l = 0; l < SNN_MAXL; ++l) {
+    sp[l] = 0;
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) v[l][k] = 0.0f;
+  }
+  if (!service) {
+#pragma unroll
+    for (int l = 0; l < SNN_MAXL; ++l) {
+      if (l >= L) break;
+      const int N = net.N[l];
+      const uint64_t *mrow = net.mask[l + 1] + ((size_t)t0 * B + b) * net.Wd[l + 1];
+#pragma unroll
+      for (int k = 0; k < NPT; ++k) {
+        const int n = tid + k * nt;
+        const int widx = n >> 6;
+        if (widx < net.Wd[l + 1]) {
+          const uint64_t word = mrow[widx];
+          if (lane == 0) words[(size_t)(l + 1) * wdmax + widx] = word;
+          if ((word >> lane) & 1ull) sp[l] |= 1u << k;
+        }
+        if (state_in && n < N) v[l][k] = state_in[(size_t)b * net.SN + net.off[l] + n];
+      }
+    }
+  } else {
+    for (int o = lane; o < O; o += WAVE) {
+      u[o] = readout_init ? 0.0 : readout[((size_t)b * 2 + 0) * O + o];
+      usum[o] = readout_init ? 0.0 : readout[((size_t)b * 2 + 1) * O + o];
+    }
+  }
+  __syncthreads();
+  uint64_t in_word = 0; // service wave: lane w holds word w of the next step's input spikes
+  if (!service) {
+    for (int l = 0; l < L; ++l)
+      expand_owner(words + (size_t)(l + 1) * wdmax, net.Wd[l + 1], lists + lo[l + 1], &cnt[l + 1], tid, nt, NPT);
+  } else {
+    if (t0 + 1 <= t1 && lane < net.Wd[0]) in_word = net.mask[0][((size_t)(t0 + 1) * B + b) * net.Wd[0] + lane];
+    int pre = 0;
+    for (int w = 0; w < net.Wd[0]; ++w) {
+      const uint32_t wl = __builtin_amdgcn_readlane((uint32_t)in_word, w);
+      const uint32_t wh = __builtin_amdgcn_readlane((uint32_t)(in_word >> 32), w);
+      const uint64_t word = ((uint64_t)wh << 32) | wl;
+      if ((word >> lane) & 1ull) lists[pre + __popcll(word & lanemask_lt())] = (uint16_t)(w * WAVE + lane);
+      pre += __popcll(word);
+    }
+    if (lane == 0) cnt[0] = pre;
+  }
+  __syncthreads();
+
+  // ---- time loop ------------------------------------------------------------------------
+  for (int t = t0 + 1; t <= t1; ++t) {
+    int store_slot = -1;
+    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
+      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
+
+    if (service) {
+      // readout of the previous step (its last-layer list is complete), then prefetch inputs
+      if (GEN && t > t0 + 1) {
+        const int c = cnt[L];
+        const uint16_t *lst = lists + lo[L];
+        for (int o = lane; o < O; o += WAVE) {
+          float acc = 0.0f;
+          for (int i = 0; i < c; ++i) acc = acc + net.W_out[(size_t)lst[i] * O + o];
+          const double un = (double)net.beta * u[o] + (double)acc;
+          u[o] = un;
+          usum[o] = usum[o] + un;
+        }
+      }
+      in_word = 0;
+      if (t + 1 <= t1 && lane < net.Wd[0]) in_word = net.mask[0][((size_t)(t + 1) * B + b) * net.Wd[0] + lane];
+    }
+
+#pragma unroll
+    for (int l = 0; l < SNN_MAXL; ++l) {
+      if (l >= L) break;
+      const int N = net.N[l];
+      uint64_t *wl_ = words + (size_t)(l + 1) * wdmax;
+      if (!service) {
+        // ---- phase 1: gather the rows of active presynaptic neurons, LIF update, threshold
+        float a_in[NPT], a_rec[NPT];
+        gather_rows<NPT, (NPT == 1 ? 16 : (NPT <= 4 ? 8 : 2))>(net.W_in[l], N, tid, nt, lists + lo[l], cnt[l], a_in);
+        gather_rows<NPT, (NPT == 1 ? 16 : (NPT <= 4 ? 8 : 2))>(net.W_rec[l], N, tid, nt, lists + lo[l + 1], cnt[l + 1], a_rec);
+        uint64_t *mrow = net.mask[l + 1] + ((size_t)t * B + b) * net.Wd[l + 1];
+        uint32_t spn = 0;
+#pragma unroll
+        for (int k = 0; k < NPT; ++k) {
+          const int n = tid + k * nt;
+          const int widx = n >> 6;
+          if (widx < net.Wd[l + 1]) { // uniform per wave
+            float a = net.alpha * v[l][k];
+            if ((sp[l] >> k) & 1u) a = a - net.theta;
+            const float vn = n < N ? a + (a_in[k] + a_rec[k]) : 0.0f;
+            v[l][k] = vn;
+            uint64_t word;
+            if (GEN) {
+              word = __ballot(n < N && vn > net.theta);
+              if (lane == 0) mrow[widx] = word;
+            } else {
+              word = mrow[widx];
+            }
+            if (lane == 0) wl_[widx] = word;
+            if ((word >> lane) & 1ull) spn |= 1u << k;
+            if (store_slot >= 0 && n < N)
+              st.base[(size_t)store_slot * st.slot_stride + (size_t)b * net.SN + net.off[l] + n] = vn;
+          }
+        }
+        sp[l] = spn;
+      }
+      __syncthreads();
+      // ---- phase 2: compaction of this layer's new spikes into the active-index list
+      if (!service) {
+        expand_owner(wl_, net.Wd[l + 1], lists + lo[l + 1], &cnt[l + 1], tid, nt, NPT);
+      } else if (l == L - 1) {
+        int pre = 0;
+        for (int w = 0; w < net.Wd[0]; ++w) {
+          const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)in_word, w);
+          const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(in_word >> 32), w);
+          const uint64_t word = ((uint64_t)whi << 32) | wlo;
+          if ((word >> lane) & 1ull) lists[pre + __popcll(word & lanemask_lt())] = (uint16_t)(w * WAVE + lane);
+          pre += __popcll(word);
+        }
+        if (lane == 0) cnt[0] = pre;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue: last readout, final state, readout state ---------------------------------
+  if (service) {
+    if (GEN && t1 > t0) {
+      const int c = cnt[L];
+      const uint16_t *lst = lists + lo[L];
+      for (int o = lane; o < O; o += WAVE) {
+        float acc = 0.0f;
+        for (int i = 0; i < c; ++i) acc = acc + net.W_out[(size_t)lst[i] * O + o];
+        const double un = (double)net.beta * u[o] + (double)acc;
+        u[o] = un;
+        usum[o] = usum[o] + un;
+      }
+    }
+    if (GEN)
+      for (int o = lane; o < O; o += WAVE) {
+        readout[((size_t)b * 2 + 0) * O + o] = u[o];
+        readout[((size_t)b * 2 + 1) * O + o] = usum[o];
+      }
+  } else if (state_out) {
+#pragma unroll
+    for (int l = 0; l < SNN_MAXL; ++l) {
+      if (l >= L) break;
+#pragma unroll
+      for (int k = 0; k < NPT; ++k) {
+        const int n = tid + k * nt;
+        if (n < net.N[l]) state_out[(size_t)b * net.SN + net.off[l] + n] = v[l][k];
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// A5: loss and its gradient with respect to every u_t (constant over t).
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_loss(const double *__restrict__ readout, const int32_t *__restrict__ labels,
+                                              int B, int O, int T, float *__restrict__ ubar, float *__restrict__ g,
+                                              float *__restrict__ loss) {
+  extern __shared__ float lossb[]; // [B]
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    const double *us = readout + ((size_t)b * 2 + 1) * O;
+    float *ub = ubar + (size_t)b * O;
+    float m = -INFINITY;
+    for (int o = 0; o < O; ++o) {
+      const float x = (float)(us[o] / (double)T);
+      ub[o] = x;
+      m = fmaxf(m, x);
+    }
+    float z = 0.0f;
+    for (int o = 0; o < O; ++o) z = z + expf(ub[o] - m);
+    const int y = labels[b];
+    lossb[b] = (m + logf(z)) - ub[y];
+    for (int o = 0; o < O; ++o) {
+      const float p = expf(ub[o] - m) / z;
+      g[(size_t)b * O + o] = (p - (o == y ? 1.0f : 0.0f)) / ((float)B * (float)T);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) s = s + lossb[b];
+    *loss = s / (float)B;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// B2-B4: adjoint recurrence, one workgroup per batch element, time loop (descending) on device.
+//   du_t   = beta du_{t+1} + g
+//   ds^l_t = (l==L ? W_out du_t : W_in^{l+1} dv^{l+1}_t) + W_rec^l dv^l_{t+1} - theta dv^l_{t+1}
+//   dv^l_t = alpha dv^l_{t+1} + ds^l_t / (1 + k |v^l_t - theta|)^2
+// The dense products walk the transposed weights so that consecutive threads (post index j) read
+// consecutive addresses; the K range is split over KG thread groups whose partial sums are
+// combined in a fixed order.
+// ------------------------------------------------------------------------------------------
+static __device__ __forceinline__ float dot_T(const float *__restrict__ WT, int ld, int j, const float *x, int n0,
+                                              int n1) {
+  float a0 = 0.0f, a1 = 0.0f;
+  int n = n0;
+  for (; n + 8 <= n1; n += 8) {
+    float w[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) w[q] = WT[(size_t)(n + q) * ld + j];
+#pragma unroll
+    for (int q = 0; q < 8; q += 2) {
+      a0 = fmaf(w[q], x[n + q], a0);
+      a1 = fmaf(w[q + 1], x[n + q + 1], a1);
+    }
+  }
+  for (; n < n1; ++n) a0 = fmaf(WT[(size_t)n * ld + j], x[n], a0);
+  return a0 + a1;
+}
+
+__global__ void __launch_bounds__(1024)
+k_adjoint(NetDev net, int t0, int t1, float *__restrict__ vbuf, int t_base, float *__restrict__ dubuf,
+          const float *__restrict__ g, float *__restrict__ carry, int carry_init) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, NT = blockDim.x, b = blockIdx.x;
+  const int L = net.L, O = net.n_out, SN = net.SN, B = net.B;
+  float *dvA = (float *)smem;   // [SN]
+  float *dvB = dvA + SN;        // [SN]
+  float *du = dvB + SN;         // [O]
+  float *gv = du + O;           // [O]
+  float *part = gv + O;         // [NT]
+  float *cb = carry + (size_t)b * (SN + O);
+
+  for (int i = tid; i < SN; i += NT) { dvA[i] = carry_init ? 0.0f : cb[i]; dvB[i] = 0.0f; }
+  for (int o = tid; o < O; o += NT) {
+    const float gg = g[(size_t)b * O + o];
+    gv[o] = gg;
+    const float d = carry_init ? 0.0f : cb[SN + o];
+    du[o] = net.beta * d + gg; // du of the first step processed (t1)
+  }
+  __syncthreads();
+  float *dv_next = dvA, *dv_cur = dvB;
+
+  for (int t = t1; t > t0; --t) {
+    const size_t slot = (size_t)(t - t_base - 1);
+    float *vrow = vbuf + slot * ((size_t)B * SN) + (size_t)b * SN;
+    for (int o = tid; o < O; o += NT) dubuf[(slot * B + b) * O + o] = du[o];
+
+    for (int l = L - 1; l >= 0; --l) {
+      const int N = net.N[l], off = net.off[l];
+      const int NJ = (N + WAVE - 1) & ~(WAVE - 1);
+      const int tile = NJ < NT ? NJ : NT;   // j values handled at once
+      const int KG = NT / tile;             // thread groups splitting the reduction
+      const int kg = tid / tile, jt = tid % tile;
+      const float *WupT;
+      const float *xup;
+      int Kup;
+      if (l == L - 1) { WupT = net.W_outT; xup = du; Kup = O; }
+      else { WupT = net.W_inT[l + 1]; xup = dv_cur + net.off[l + 1]; Kup = net.N[l + 1]; }
+      const float *xrec = dv_next + off;
+      for (int jb = 0; jb < NJ; jb += tile) {
+        const int j = jb + jt;
+        const bool act = kg < KG && j < N;
+        float vt = 0.0f;
+        if (act && kg == 0) vt = vrow[off + j];
+        float p = 0.0f;
+        if (act) {
+          const int u0 = (int)((long long)Kup * kg / KG), u1 = (int)((long long)Kup * (kg + 1) / KG);
+          const int r0 = (int)((long long)N * kg / KG), r1 = (int)((long long)N * (kg + 1) / KG);
+          p = dot_T(WupT, N, j, xup, u0, u1) + dot_T(net.W_recT[l], N, j, xrec, r0, r1);
+        }
+        if (kg < KG) part[kg * tile + jt] = p;
+        __syncthreads();
+        if (act && kg == 0) {
+          float s = part[jt];
+          for (int q = 1; q < KG; ++q) s = s + part[q * tile + jt];
+          const float dn = xrec[j];
+          const float ds = s - net.theta * dn;
+          const float d = 1.0f + net.k * fabsf(vt - net.theta);
+          const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+          dv_cur[off + j] = dvt;
+          vrow[off + j] = dvt;
+        }
+        __syncthreads();
+      }
+    }
+    // next step's readout adjoint (independent of the layers): safe to update now, every
+    // read of du for this step is behind the barrier above
+    for (int o = tid; o < O; o += NT) du[o] = net.beta * du[o] + gv[o];
+    float *tmp = dv_next; dv_next = dv_cur; dv_cur = tmp;
+    __syncthreads();
+  }
+  // carry out: dv_{t0+1} and du_{t0+1}.  du currently holds beta*du_{t0+1}+g; undo by recomputing
+  for (int i = tid; i < SN; i += NT) cb[i] = dv_next[i];
+  if (t1 > t0)
+    for (int o = tid; o < O; o += NT) cb[SN + o] = dubuf[((size_t)(t0 - t_base) * B + b) * O + o];
+}
+
+// ------------------------------------------------------------------------------------------
+// B5: weight gradient over active spikes.  One workgroup per presynaptic row j (x column tile);
+// dW[j][:] += sum_{t = t1..t0+1 desc} sum_{b asc} [spike(t - lag, b, j)] * post(t, b, :)
+// Sequential per-element accumulation continued from the value already in dW, so the result
+// does not depend on how the time axis is cut into launches.  The accumulators are fp64 (tens of
+// thousands of same-sign fp32 terms per element would otherwise lose ~1e-4 of the result); the
+// gradient is rounded to fp32 once, at the end of the training step.
+// ------------------------------------------------------------------------------------------
+#define DW_NPT 4
+__global__ void __launch_bounds__(256)
+k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float *__restrict__ postbuf,
+     size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1, int t_base,
+     double *__restrict__ dW) {
+  const int j = blockIdx.x;
+  const int c0 = blockIdx.y * (256 * DW_NPT) + threadIdx.x;
+  double acc[DW_NPT];
+#pragma unroll
+  for (int k = 0; k < DW_NPT; ++k) {
+    const int n = c0 + k * 256;
+    acc[k] = n < n_post ? dW[(size_t)j * n_post + n] : 0.0;
+  }
+  const int wj = j >> 6;
+  const uint64_t bit = 1ull << (j & 63);
+  for (int t = t1; t > t0; --t) {
+    const int tp = t - lag; // row 0 of the mask (t = 0) is all zero
+    const uint64_t *mrow = pre_mask + (size_t)tp * B * pre_words + wj;
+    const float *prow = postbuf + (size_t)(t - t_base - 1) * slot_stride + post_off;
+    for (int b = 0; b < B; ++b) {
+      if (mrow[(size_t)b * pre_words] & bit) {
+        const float *p = prow + (size_t)b * post_stride;
+#pragma unroll
+        for (int k = 0; k < DW_NPT; ++k) {
+          const int n = c0 + k * 256;
+          if (n < n_post) acc[k] = acc[k] + (double)p[n];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < DW_NPT; ++k) {
+    const int n = c0 + k * 256;
+    if (n < n_post) dW[(size_t)j * n_post + n] = acc[k];
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// small utilities
+// ------------------------------------------------------------------------------------------
+__global__ void k_transpose(const float *__restrict__ src, float *__restrict__ dst, int rows, int cols) {
+  __shared__ float tile[32][33];
+  int x = blockIdx.x * 32 + threadIdx.x, y = blockIdx.y * 32 + threadIdx.y;
+  for (int i = 0; i < 32; i += 8)
+    if (x < cols && y + i < rows) tile[threadIdx.y + i][threadIdx.x] = src[(size_t)(y + i) * cols + x];
+  __syncthreads();
+  x = blockIdx.y * 32 + threadIdx.x;
+  y = blockIdx.x * 32 + threadIdx.y;
+  for (int i = 0; i < 32; i += 8)
+    if (x < rows && y + i < cols) dst[(size_t)(y + i) * rows + x] = tile[threadIdx.x][threadIdx.y + i];
+}
+
+// fp64 accumulator -> fp32 gradient; a masked matrix has a gradient only where a synapse exists
+__global__ void k_finish_grad(const double *__restrict__ acc, const uint8_t *__restrict__ mask, float *__restrict__ dW,
+                              size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dW[i] = (mask && !mask[i]) ? 0.0f : (float)acc[i];
+}
+
+__global__ void k_unpack(const uint64_t *__restrict__ mask, int words, int N, size_t TB, uint8_t *__restrict__ dst) {
+  // mask rows 1..T -> dst[T][B][N]
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= TB * (size_t)N) return;
+  const size_t tb = i / N;
+  const int n = (int)(i % N);
+  const uint64_t w = mask[tb * words + (n >> 6)];
+  dst[i] = (uint8_t)((w >> (n & 63)) & 1ull);
+}
+
+__global__ void k_count(const uint64_t *__restrict__ mask, size_t n_words, unsigned long long *count) {
+  unsigned long long c = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x)
+    c += __popcll(mask[i]);
+  for (int s = 32; s > 0; s >>= 1) c += __shfl_down(c, s);
+  if (lane_id() == 0 && c) atomicAdd(count, c); // integer atomic: order-independent
+}
+
+__global__ void k_zero(uint32_t *p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// ------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------
+static LaunchCfg forward_cfg(const NetDev &net) {
+  int nmax = 64;
+  for (int l = 0; l < net.L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
+  LaunchCfg c;
+  c.npt = 1;
+  while (((nmax + c.npt - 1) / c.npt + 63) / 64 * 64 > 512 && c.npt < 16) c.npt *= 2;
+  c.nt_neuron = ((nmax + c.npt - 1) / c.npt + 63) / 64 * 64;
+  int wdmax = 1;
+  size_t lists = (size_t)((net.n_in + 7) & ~7);
+  for (int l = 0; l < net.L; ++l) {
+    wdmax = net.Wd[l + 1] > wdmax ? net.Wd[l + 1] : wdmax;
+    lists += (size_t)((net.N[l] + 7) & ~7);
+  }
+  c.lds_bytes = (size_t)(net.L + 1) * wdmax * 8 + (size_t)net.n_out * 16 + 32 + lists * 2;
+  return c;
+}
+
+static size_t adjoint_lds(const NetDev &net, int nt) {
+  return ((size_t)2 * net.SN + 2 * net.n_out + nt) * sizeof(float);
+}
+
+bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
+  const LaunchCfg c = forward_cfg(net);
+  const size_t lds_max = 64 * 1024; // per-workgroup limit without opting in to more
+  if (c.nt_neuron > 512 || c.nt_neuron * c.npt < 1) { snprintf(why, why_len, "layer too wide for the forward kernel"); return false; }
+  for (int l = 0; l < net.L; ++l)
+    if ((net.N[l] + c.npt - 1) / c.npt > c.nt_neuron) { snprintf(why, why_len, "layer too wide for the forward kernel (max %d neurons)", 512 * 16); return false; }
+  if (net.Wd[0] > WAVE) { snprintf(why, why_len, "n_in > 4096 not supported"); return false; }
+  if (c.lds_bytes > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", c.lds_bytes, lds_max); return false; }
+  if (adjoint_lds(net, 1024) > lds_max) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
+  return true;
+}
+
+hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
+                              hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_pack_inputs, dim3((unsigned)((size_t)T * B)), dim3(WAVE), 0, s, in_spikes, mask0, B, n_in, Wd0);
+  return hipGetLastError();
+}
+
+template <bool GEN>
+static hipError_t launch_forward_t(const NetDev &net, const LaunchCfg &c, int t0, int t1, const float *state_in,
+                                   float *state_out, const StoreSpec &st, double *readout, int readout_init,
+                                   hipStream_t s) {
+  const dim3 grid(net.B), block(c.nt_neuron + WAVE);
+#define FWD_CASE(NPT_)                                                                                          \
+  case NPT_:                                                                                                     \
+    hipLaunchKernelGGL((k_forward<NPT_, GEN>), grid, block, c.lds_bytes, s, net, t0, t1, state_in, state_out, st, \
+                       readout, readout_init, c.nt_neuron);                                                      \
+    break;
+  switch (c.npt) {
+    FWD_CASE(1) FWD_CASE(2) FWD_CASE(4) FWD_CASE(8) FWD_CASE(16)
+    default: return hipErrorInvalidValue;
+  }
+#undef FWD_CASE
+  return hipGetLastError();
+}
+
+hipError_t launch_forward(const NetDev &net, bool generate, int t0, int t1, const float *state_in, float *state_out,
+                          const StoreSpec &st, double *readout, int readout_init, hipStream_t s) {
+  if (t1 < t0) return hipErrorInvalidValue;
+  const LaunchCfg c = forward_cfg(net);
+  return generate ? launch_forward_t<true>(net, c, t0, t1, state_in, state_out, st, readout, readout_init, s)
+                  : launch_forward_t<false>(net, c, t0, t1, state_in, state_out, st, readout, readout_init, s);
+}
+
+hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar, float *g,
+                       float *loss, hipStream_t s) {
+  hipLaunchKernelGGL(k_loss, dim3(1), dim3(256), (size_t)B * sizeof(float), s, readout, labels, B, O, T, ubar, g, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf, const float *g,
+                          float *carry, int carry_init, hipStream_t s) {
+  if (t1 < t0) return hipErrorInvalidValue;
+  const int nt = 1024;
+  hipLaunchKernelGGL(k_adjoint, dim3(net.B), dim3(nt), adjoint_lds(net, nt), s, net, t0, t1, vbuf, t_base, dubuf, g,
+                     carry, carry_init);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,
+                     size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1,
+                     int t_base, double *dW, hipStream_t s) {
+  if (t1 <= t0) return hipSuccess;
+  const dim3 grid(n_pre, (n_post + 256 * DW_NPT - 1) / (256 * DW_NPT));
+  hipLaunchKernelGGL(k_dw, grid, dim3(256), 0, s, pre_mask, pre_words, lag, postbuf, slot_stride, post_stride,
+                     post_off, n_post, B, t0, t1, t_base, dW);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s) {
+  hipLaunchKernelGGL(k_transpose, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, s, src, dst, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_finish_grad(const double *acc, const uint8_t *mask, float *dW, size_t n, hipStream_t s) {
+  hipLaunchKernelGGL(k_finish_grad, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, acc, mask, dW, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst, hipStream_t s) {
+  const size_t TB = (size_t)T * B, n = TB * N;
+  // skip row 0 (t = 0)
+  hipLaunchKernelGGL(k_unpack, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, mask + (size_t)B * words, words, N,
+                     TB, dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_count_spikes(const uint64_t *mask, size_t n_words, unsigned long long *count, hipStream_t s) {
+  hipLaunchKernelGGL(k_count, dim3(512), dim3(256), 0, s, mask, n_words, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_zero, dim3(1024), dim3(256), 0, s, (uint32_t *)p, bytes / 4);
+  return hipGetLastError();
+}

@@ -1,0 +1,113 @@
+// Checkpoint plan and schedule: pure integer host logic, no GPU calls.
+//
+// Checkpoints sit at multiples of the interval starting at x_0 (the zero initial state); the last
+// segment may be shorter; the coarse interval need not be a multiple of the fine one.  A segment
+// (a, b] recomputed from x_a yields x_{a+1..b} from the stored spikes.  State-slot counts are the
+// paper's closed forms (eq. M_Base, M_Standard, M_Remote, M_Double) plus, for the host tier, two
+// slots that receive prefetched checkpoints and two that stage device-to-host copies.
+#include <cmath>
+
+#include "snn_internal.h"
+
+static int cdiv(int a, int b) { return (a + b - 1) / b; }
+static int isqrt_ceil(int x) {
+  int r = (int)std::ceil(std::sqrt((double)x));
+  while ((long long)r * r < x) ++r;
+  while (r > 1 && (long long)(r - 1) * (r - 1) >= x) --r;
+  return r < 1 ? 1 : r;
+}
+
+bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
+  if (T < 1 || C < 0 || F < 0) return false;
+  Plan q{};
+  q.strategy = strategy;
+  q.T = T;
+  switch (strategy) {
+    case 0: // STANDARD: every state
+      q.C = q.F = 0;
+      q.chunk_len = T;
+      break;
+    case 1: // CHUNK: local checkpoints every F steps (default sqrt T) + one chunk buffer
+      q.F = F ? F : isqrt_ceil(T);
+      if (q.F > T) return false;
+      q.C = 0;
+      q.chunk_len = q.F;
+      q.n_local_ckpt = cdiv(T, q.F);
+      break;
+    case 2: // REMOTE: host checkpoints every C steps, chunk buffer of C states
+      q.C = C ? C : isqrt_ceil(T);
+      if (q.C > T) return false;
+      q.F = 0;
+      q.chunk_len = q.C;
+      q.n_load_slots = 2;
+      q.n_stage_slots = 2;
+      q.n_remote = cdiv(T, q.C);
+      break;
+    case 3: // DOUBLE: host checkpoints every C, recomputed local checkpoints every F
+      q.C = C ? C : isqrt_ceil(T);
+      if (q.C > T) return false;
+      q.F = F ? F : isqrt_ceil(q.C);
+      if (q.F > q.C) return false;
+      q.chunk_len = q.F;
+      q.n_local_ckpt = cdiv(q.C, q.F) - 1; // the first fine checkpoint of a segment is the loaded coarse one
+      q.n_load_slots = 2;
+      q.n_stage_slots = 2;
+      q.n_remote = cdiv(T, q.C);
+      break;
+    default:
+      return false;
+  }
+  *p = q;
+  return true;
+}
+
+int64_t snn_make_schedule(const Plan &p, SchedOp *out, int64_t cap) {
+  int64_t n = 0;
+  auto emit = [&](int op, int a, int b) {
+    if (out && n < cap) out[n] = SchedOp{op, a, b};
+    ++n;
+  };
+  const int T = p.T;
+  auto imin = [](int a, int b) { return a < b ? a : b; };
+  switch (p.strategy) {
+    case 0:
+      emit(OP_BACKWARD, T, 1);
+      break;
+    case 1:
+      for (int c = 0; c < T; c += p.F) emit(OP_SAVE_LOCAL, c, 0);
+      for (int k = cdiv(T, p.F) - 1; k >= 0; --k) {
+        const int a = k * p.F, e = imin(a + p.F, T);
+        emit(OP_REFWD2, a, e);
+        emit(OP_BACKWARD, e, a + 1);
+      }
+      break;
+    case 2:
+      for (int c = 0; c < T; c += p.C) emit(OP_SAVE_REMOTE, c, 0);
+      for (int k = cdiv(T, p.C) - 1; k >= 0; --k) {
+        const int a = k * p.C, e = imin(a + p.C, T);
+        emit(OP_LOAD_REMOTE, a, 0);
+        emit(OP_REFWD2, a, e);
+        emit(OP_BACKWARD, e, a + 1);
+      }
+      break;
+    case 3:
+      for (int c = 0; c < T; c += p.C) emit(OP_SAVE_REMOTE, c, 0);
+      for (int K = cdiv(T, p.C) - 1; K >= 0; --K) {
+        const int s0 = K * p.C, e = imin(s0 + p.C, T);
+        emit(OP_LOAD_REMOTE, s0, 0);
+        const int nf = cdiv(e - s0, p.F);
+        const int last = s0 + (nf - 1) * p.F;
+        if (last > s0) {
+          emit(OP_REFWD1, s0, last);
+          for (int c = s0 + p.F; c <= last; c += p.F) emit(OP_KEEP_FINE, c, 0);
+        }
+        for (int m = nf - 1; m >= 0; --m) {
+          const int a = s0 + m * p.F, fe = imin(a + p.F, e);
+          emit(OP_REFWD2, a, fe);
+          emit(OP_BACKWARD, fe, a + 1);
+        }
+      }
+      break;
+  }
+  return n;
+}

@@ -1,0 +1,88 @@
+"""Host-side logic of the GPU library (no GPU needed): the shared library loads and exports every
+symbol the header declares, its schedule generator reproduces the order of Fig. 1 and the
+oracle's own execution order, and its state-slot / byte accounting follows the paper's closed forms."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2412_11810_amd as snn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = os.path.join(ROOT, "tests", "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "snn.h")).read()
+    declared = set(re.findall(r"^(?:snn_status|size_t|int32_t|int64_t|const char \*|void)\s*(snn_[a-z_]+)\(", header, re.M))
+    assert declared == set(snn.EXPORTS)
+    L = snn.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_schedule_matches_fig1_double_panel():
+    gold = []
+    for line in open(os.path.join(GOLD, "fig1_double_schedule.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            p = line.split()
+            gold.append((p[0], int(p[1]), int(p[2]) if len(p) > 2 else 0))
+    ops = [o for o in snn.snn_schedule(snn.SNN_DOUBLE, 11, 6, 3) if o[0] != "SAVE_REMOTE"]
+    assert ops == gold
+
+
+@pytest.mark.parametrize("strategy,T,C,F", [
+    (snn.SNN_STANDARD, 23, 0, 0), (snn.SNN_CHUNK, 23, 0, 5), (snn.SNN_CHUNK, 24, 0, 6), (snn.SNN_CHUNK, 7, 0, 7),
+    (snn.SNN_REMOTE, 23, 4, 0), (snn.SNN_REMOTE, 9, 9, 0), (snn.SNN_DOUBLE, 23, 7, 3), (snn.SNN_DOUBLE, 50, 20, 6),
+    (snn.SNN_DOUBLE, 31, 10, 10), (snn.SNN_DOUBLE, 17, 17, 1), (snn.SNN_DOUBLE, 40, 9, 2)])
+def test_schedule_equals_oracle_execution_order(strategy, T, C, F):
+    """The library's schedule generator and the oracle were written separately; both must walk the
+    same checkpoints in the same order."""
+    rng = np.random.default_rng(0)
+    r = oracle.bptt(3, [4], 2, [rng.standard_normal((3, 4))], [rng.standard_normal((4, 4))],
+                    rng.standard_normal((4, 2)), (rng.random((T, 1, 3)) < 0.3).astype(np.uint8), [0],
+                    strategy=strategy, coarse=C, fine=F, want_events=True)
+    assert snn.snn_schedule(strategy, T, C, F) == r.events
+
+
+@pytest.mark.parametrize("T,C,F", [(64, 16, 4), (4096, 64, 8), (100, 25, 5), (1000, 32, 6), (100000, 316, 18)])
+def test_state_slots_follow_closed_forms(T, C, F):
+    cd = lambda a, b: -(-a // b)
+    assert snn.snn_state_slots(snn.SNN_STANDARD, T) == (T, 0)                        # M_Base
+    assert snn.snn_state_slots(snn.SNN_CHUNK, T, 0, F) == (F + cd(T, F), 0)          # M_Standard
+    # host tier: the paper's count plus 3 staging slots (second prefetch slot, two D2H staging slots)
+    assert snn.snn_state_slots(snn.SNN_REMOTE, T, C, 0) == (C + 1 + 3, cd(T, C))     # M_Remote
+    assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 3, cd(T, C))  # M_Double
+
+
+def test_default_intervals_are_square_roots():
+    assert snn.snn_state_slots(snn.SNN_CHUNK, 4096) == (64 + 64, 0)                  # chunk = sqrt(T) = 64
+    n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 4096)
+    assert (n, r) == (8 + 8 + 3, 64)                                                 # C = 64, F = 8
+    n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 100000)
+    assert r == math.ceil(100000 / 317)                                              # ceil(sqrt(1e5)) = 317
+
+
+def test_bytes_required_accounting():
+    cfg = snn.make_config(700, [256, 256], 20, 1000, 32)
+    Ms = 4 * 32 * 512
+    spikes = 8 * 1001 * 32 * (11 + 4 + 4)
+    for strat, C, F in [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 100, 10)]:
+        slots, _ = snn.snn_state_slots(strat, 1000, C, F)
+        chunk = {snn.SNN_STANDARD: 1000, snn.SNN_CHUNK: 32, snn.SNN_REMOTE: 32, snn.SNN_DOUBLE: 10}[strat]
+        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + chunk * 32 * 20 * 4
+    # invalid intervals
+    assert snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, 1000, 10, 20) == 0
+    assert snn.snn_state_slots(snn.SNN_CHUNK, 10, 0, 11) == (0, 0)
+
+
+def test_double_local_memory_grows_like_fourth_root():
+    """With C = sqrt(T) and F = sqrt(C), Double keeps 2 T^(1/4) states resident (Discussion; Fig. 1 label)."""
+    for T in (256, 4096, 65536):
+        Cc = int(round(T ** 0.5))
+        Ff = int(round(Cc ** 0.5))
+        assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 3 == 2 * round(T ** 0.25)

@@ -360,3 +360,20 @@ def test_invalid_intervals_rejected():
         _run(net, strategy=oracle.DOUBLE, coarse=3, fine=5)
     with pytest.raises(ValueError):
         _run(net, strategy=oracle.CHUNK, fine=0)
+
+
+def test_forced_states_mode_is_consistent():
+    """Feeding the double-precision oracle its own states changes nothing; feeding it the fp32
+    trajectory moves the gradients only by the fp32 rounding of the states."""
+    net = _tiny(23, n_in=10, hidden=(12, 8), T=20, B=2, p=0.25, scale=0.6)
+    a = _run(net, dtype=np.float64, want_v=True)
+    b = _run(net, dtype=np.float64, forced_spikes=a.spikes, forced_v=a.v)
+    for p, q in zip(a.dW_in + a.dW_rec + [a.dW_out], b.dW_in + b.dW_rec + [b.dW_out]):
+        assert np.array_equal(p, q)
+    f = _run(net, dtype=np.float32, want_v=True)
+    assert all(np.array_equal(x, y) for x, y in zip(f.spikes, a.spikes))
+    c = _run(net, dtype=np.float64, forced_spikes=f.spikes, forced_v=f.v)
+    for p, q in zip(a.dW_in + a.dW_rec, c.dW_in + c.dW_rec):
+        assert np.allclose(p, q, rtol=0, atol=1e-4 * np.abs(p).max()) and not np.array_equal(p, q)
+    with pytest.raises(ValueError):
+        _run(net, dtype=np.float64, forced_spikes=a.spikes, forced_v=a.v, strategy=oracle.CHUNK, fine=4)
