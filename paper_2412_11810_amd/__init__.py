@@ -65,6 +65,13 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2412_11810_amd.build`")
+        # One HIP runtime per process: PyTorch ships its own libamdhip64 (same SONAME as the system
+        # one).  Loading it first makes this library bind to that copy, so torch tensors, streams
+        # and this library share one runtime; a second runtime could not open the GPU.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         L.snn_init.argtypes = [C.POINTER(snn_config), C.POINTER(vp)]
