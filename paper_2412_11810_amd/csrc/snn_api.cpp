@@ -145,12 +145,12 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   const int L = n.L, B = n.B, O = n.n_out;
   for (int l = 0; l < L; ++l) {
     const size_t ni = (size_t)pre_of(n, l) * n.N[l], nr = (size_t)n.N[l] * n.N[l];
-    HIPCHK(c, hipMalloc(&c->W_in[l], ni * 4));
+    HIPCHK(c, hipMalloc(&c->W_in[l], (ni + nr) * 4)); // [W_in ; W_rec] stacked row-wise
+    c->W_rec[l] = c->W_in[l] + ni;
     HIPCHK(c, hipMalloc(&c->W_inT[l], ni * 4));
     HIPCHK(c, hipMalloc(&c->dW_in[l], ni * 4));
     HIPCHK(c, hipMalloc(&c->acc_in[l], ni * 8));
     HIPCHK(c, hipMalloc(&c->acc_rec[l], nr * 8));
-    HIPCHK(c, hipMalloc(&c->W_rec[l], nr * 4));
     HIPCHK(c, hipMalloc(&c->W_recT[l], nr * 4));
     HIPCHK(c, hipMalloc(&c->dW_rec[l], nr * 4));
     HIPCHK(c, hipMemsetAsync(c->W_in[l], 0, ni * 4, c->stream));
@@ -188,7 +188,7 @@ void snn_destroy(snn_ctx *c) {
   (void)hipSetDevice(c->cfg.device);
   (void)hipDeviceSynchronize();
   for (int l = 0; l < SNN_MAXL; ++l) {
-    (void)hipFree(c->W_in[l]); (void)hipFree(c->W_rec[l]); (void)hipFree(c->W_inT[l]); (void)hipFree(c->W_recT[l]);
+    (void)hipFree(c->W_in[l]); (void)hipFree(c->W_inT[l]); (void)hipFree(c->W_recT[l]);
     (void)hipFree(c->dW_in[l]); (void)hipFree(c->dW_rec[l]); (void)hipFree(c->rec_mask[l]);
     (void)hipFree(c->acc_in[l]); (void)hipFree(c->acc_rec[l]);
   }
@@ -268,7 +268,7 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
     st.base = traj_or_null; st.slot_stride = (size_t)n.B * n.SN; st.t_base = 0; st.interval = 1; st.slot0 = 0;
     st.t_max = c->T_bound;
   }
-  HIPCHK(c, launch_forward(n, true, 0, c->T_bound, nullptr, nullptr, st, c->readout, 1, c->stream));
+  HIPCHK(c, launch_forward(n, 0, c->T_bound, nullptr, nullptr, st, c->readout, 1, c->stream));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
   return SNN_OK;
 }
@@ -449,11 +449,11 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // ---- forward ------------------------------------------------------------------------------
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk, slot, 0, 1, 0, T};
-    HIPCHK(c, launch_forward(n, true, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+    HIPCHK(c, launch_forward(n, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, hipMemsetAsync(lckpt, 0, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
-    HIPCHK(c, launch_forward(n, true, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+    HIPCHK(c, launch_forward(n, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
   } else {
     std::memset(c->host_ckpt, 0, Ms); // x_0 lives in host slot 0
     StoreSpec none{};
@@ -462,7 +462,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       const bool keep = K + 1 < p.n_remote; // x_e is the next coarse checkpoint
       const int so = K & 1;
       if (keep && stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
-      HIPCHK(c, launch_forward(n, true, a, e, K == 0 ? nullptr : stage + (size_t)((K - 1) & 1) * slot,
+      HIPCHK(c, launch_forward(n, a, e, K == 0 ? nullptr : stage + (size_t)((K - 1) & 1) * slot,
                                keep ? stage + (size_t)so * slot : nullptr, none, c->readout, K == 0, s));
       if (keep) {
         HIPCHK(c, hipEventRecord(ev_stage_ready[so], s));
@@ -517,9 +517,13 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         break;
       }
       case OP_REFWD1: {
-        StoreSpec sp{lckpt, slot, op.a, p.F, 0, op.b};
+        // rebuild the fine checkpoints x_{a+F}, x_{a+2F}, ..., x_b, one fine interval at a time: the
+        // chunk buffer takes the currents of the interval, the scan keeps only its last state
         tm.begin(1);
-        HIPCHK(c, launch_forward(n, false, op.a, op.b, loadb + (size_t)cur_load * slot, nullptr, sp, c->readout, 0, s));
+        for (int a = op.a, m = 0; a < op.b; a += p.F, ++m) {
+          const float *src = m == 0 ? loadb + (size_t)cur_load * slot : lckpt + (size_t)(m - 1) * slot;
+          HIPCHK(c, launch_recompute(n, a, a + p.F, src, chunk, a, slot, 0, lckpt + (size_t)m * slot, s));
+        }
         tm.end();
         st.refwd1_steps += op.b - op.a;
         break;
@@ -529,10 +533,9 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         if (strategy == SNN_CHUNK) src = lckpt + (size_t)(op.a / p.F) * slot;
         else if (strategy == SNN_REMOTE || op.a == seg_start) src = loadb + (size_t)cur_load * slot;
         else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
-        StoreSpec sp{chunk, slot, op.a, 1, 0, op.b};
         chunk_base = op.a;
         tm.begin(1);
-        HIPCHK(c, launch_forward(n, false, op.a, op.b, src, nullptr, sp, c->readout, 0, s));
+        HIPCHK(c, launch_recompute(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
         tm.end();
         st.refwd2_steps += op.b - op.a;
         break;

@@ -10,7 +10,8 @@
 // Device-visible description of the network and of where its data lives in HBM.
 //
 // Weights: fp32, [pre][post] row-major, so the synapses leaving one presynaptic neuron are one
-// contiguous row (one active spike = one coalesced row read).  *_T are [post][pre] copies used by
+// contiguous row (one active spike = one coalesced row read).  W_in[l] and W_rec[l] are stacked in
+// one allocation (W_rec[l] = W_in[l] + pre_l * N_l) so that a gather walks one row stream.  *_T are [post][pre] copies used by
 // the adjoint pass (delta_s[j] = sum_n W[j][n] * delta_v[n] becomes a coalesced column walk).
 // Spikes: one bit per neuron, 64-bit words, mask[l] = [T+1][B][Wd[l]] with row 0 (t = 0) all zero;
 // layer index 0 is the input layer, l >= 1 hidden layer l.
@@ -45,11 +46,16 @@ struct LaunchCfg {
 // ---- launchers (defined in snn_kernels.hip) ---------------------------------------------
 hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
                               hipStream_t s);
-// Runs steps t0+1..t1 for all batch elements.  generate: threshold + compaction (forward pass);
-// otherwise spikes are read from the stored bitmasks (recompute pass, no spike generation).
-hipError_t launch_forward(const NetDev &net, bool generate, int t0, int t1, const float *state_in,
+// Forward pass over steps t0+1..t1 for all batch elements (gather, LIF update, threshold, compaction,
+// readout), time loop on the device.
+hipError_t launch_forward(const NetDev &net, int t0, int t1, const float *state_in,
                           float *state_out, const StoreSpec &st, double *readout /*[B][2][O]*/,
                           int readout_init, hipStream_t s);
+// Recompute pass over steps t0+1..t1 from state_in = x_{t0}, spikes read from the stored bitmasks:
+// currents of the whole range in parallel into buf (slot of x_t = t - t_base - 1), then a scan that
+// turns them into states in place (store_all) and/or writes x_{t1} to state_out.
+hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
+                            size_t slot_stride, int store_all, float *state_out, hipStream_t s);
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
                        float *g, float *loss, hipStream_t s);
 // Adjoint recurrence over steps t1, t1-1, ..., t0+1.  vbuf holds x_t at slot (t - t_base - 1) and is

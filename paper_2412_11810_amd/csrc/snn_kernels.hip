@@ -39,35 +39,61 @@ __global__ void __launch_bounds__(WAVE) k_pack_inputs(const uint8_t *__restrict_
 // ------------------------------------------------------------------------------------------
 // Forward / recompute: one workgroup per batch element, time loop on the device.
 // ------------------------------------------------------------------------------------------
-template <int NPT, int U>
-static __device__ __forceinline__ void gather_rows(const float *__restrict__ W, int N, int n0, int nt,
-                                                   const uint16_t *lst, int cnt, float (&acc)[NPT]) {
+// Synaptic currents of the NPT neurons n0 + k*nt this thread owns: a_in = sum of the rows of Wcat
+// selected by lst_in, a_rec = sum of the rows rec_row0 + lst_rec (each in ascending list order,
+// starting from 0.0f).  Wcat is [W_in ; W_rec] stacked row-wise, so both sums are one stream of row
+// reads.  The wave fetches 64 stream entries with one LDS read (lane i holds entry i) and broadcasts
+// them through a scalar register: each row costs a scalar address computation, one coalesced load
+// per owned neuron and two selects+adds; 32 loads per thread are in flight before the adds (in
+// stream order) consume them.  Slots past the end of the stream read row 0 and add +0.0f, which
+// leaves a sum unchanged bit for bit.
+template <int NPT>
+static __device__ __forceinline__ void gather2(const float *__restrict__ Wcat, int N, uint32_t rec_row0, int n0, int nt,
+                                               const uint16_t *lst_in, int cnt_in, const uint16_t *lst_rec,
+                                               int cnt_rec, float (&a_in)[NPT], float (&a_rec)[NPT]) {
+  constexpr int U = NPT >= 32 ? 1 : 32 / NPT;
+  const int ci = __builtin_amdgcn_readfirstlane(cnt_in), cr = __builtin_amdgcn_readfirstlane(cnt_rec);
+  const int tot = ci + cr;
+  uint32_t off[NPT];
+  bool ok[NPT];
 #pragma unroll
-  for (int k = 0; k < NPT; ++k) acc[k] = 0.0f;
-  int i = 0;
-  for (; i + U <= cnt; i += U) {
-    float w[U][NPT];
+  for (int k = 0; k < NPT; ++k) {
+    a_in[k] = 0.0f;
+    a_rec[k] = 0.0f;
+    const int n = n0 + k * nt;
+    ok[k] = n < N;
+    off[k] = ok[k] ? (uint32_t)n : 0u; // out-of-range lanes read column 0 and discard it
+  }
+  for (int e0 = 0; e0 < tot; e0 += WAVE) {
+    const int m = tot - e0 < WAVE ? tot - e0 : WAVE;
+    const int e = e0 + lane_id();
+    uint32_t mine = 0u;
+    if (e < tot) mine = e < ci ? (uint32_t)lst_in[e] : rec_row0 + (uint32_t)lst_rec[e - ci];
+    for (int q = 0; q < m; q += U) {
+      float w[U][NPT];
 #pragma unroll
-    for (int q = 0; q < U; ++q) {
-      const float *row = W + (size_t)lst[i + q] * N;
+      for (int r = 0; r < U; ++r) {
+        const uint32_t j = __builtin_amdgcn_readlane(mine, (q + r) & (WAVE - 1));
+        const float *row = Wcat + (size_t)j * (uint32_t)N;
 #pragma unroll
-      for (int k = 0; k < NPT; ++k) {
-        const int n = n0 + k * nt;
-        w[q][k] = n < N ? row[n] : 0.0f;
+        for (int k = 0; k < NPT; ++k) w[r][k] = row[off[k]];
+      }
+#pragma unroll
+      for (int r = 0; r < U; ++r) {
+        const int pos = e0 + q + r;
+        const bool is_in = pos < ci, is_rec = pos >= ci && pos < tot;
+#pragma unroll
+        for (int k = 0; k < NPT; ++k) {
+          a_in[k] = a_in[k] + (is_in ? w[r][k] : 0.0f);
+          a_rec[k] = a_rec[k] + (is_rec ? w[r][k] : 0.0f);
+        }
       }
     }
-#pragma unroll
-    for (int q = 0; q < U; ++q)
-#pragma unroll
-      for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + w[q][k];
   }
-  for (; i < cnt; ++i) {
-    const float *row = W + (size_t)lst[i] * N;
 #pragma unroll
-    for (int k = 0; k < NPT; ++k) {
-      const int n = n0 + k * nt;
-      if (n < N) acc[k] = acc[k] + row[n];
-    }
+  for (int k = 0; k < NPT; ++k) {
+    a_in[k] = ok[k] ? a_in[k] : 0.0f;
+    a_rec[k] = ok[k] ? a_rec[k] : 0.0f;
   }
 }
 
@@ -86,7 +112,7 @@ static __device__ __forceinline__ void expand_owner(const uint64_t *words, int W
   }
 }
 
-template <int NPT, bool GEN>
+template <int NPT>
 __global__ void __launch_bounds__(576)
 k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *__restrict__ state_out,
           StoreSpec st, double *__restrict__ readout, int readout_init, int nt) {
@@ -170,15 +196,16 @@ k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float 
 
     if (service) {
       // readout of the previous step (its last-layer list is complete), then prefetch inputs
-      if (GEN && t > t0 + 1) {
-        const int c = cnt[L];
-        const uint16_t *lst = lists + lo[L];
-        for (int o = lane; o < O; o += WAVE) {
-          float acc = 0.0f;
-          for (int i = 0; i < c; ++i) acc = acc + net.W_out[(size_t)lst[i] * O + o];
-          const double un = (double)net.beta * u[o] + (double)acc;
-          u[o] = un;
-          usum[o] = usum[o] + un;
+      if (t > t0 + 1) {
+        for (int o0 = 0; o0 < O; o0 += WAVE) {
+          float acc[1], unused[1];
+          gather2<1>(net.W_out, O, 0u, o0 + lane, WAVE, lists + lo[L], cnt[L], lists, 0, acc, unused);
+          const int o = o0 + lane;
+          if (o < O) {
+            const double un = (double)net.beta * u[o] + (double)acc[0];
+            u[o] = un;
+            usum[o] = usum[o] + un;
+          }
         }
       }
       in_word = 0;
@@ -193,8 +220,8 @@ k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float 
       if (!service) {
         // ---- phase 1: gather the rows of active presynaptic neurons, LIF update, threshold
         float a_in[NPT], a_rec[NPT];
-        gather_rows<NPT, (NPT == 1 ? 16 : (NPT <= 4 ? 8 : 2))>(net.W_in[l], N, tid, nt, lists + lo[l], cnt[l], a_in);
-        gather_rows<NPT, (NPT == 1 ? 16 : (NPT <= 4 ? 8 : 2))>(net.W_rec[l], N, tid, nt, lists + lo[l + 1], cnt[l + 1], a_rec);
+        gather2<NPT>(net.W_in[l], N, (uint32_t)(l == 0 ? net.n_in : net.N[l - 1]), tid, nt, lists + lo[l], cnt[l],
+                     lists + lo[l + 1], cnt[l + 1], a_in, a_rec);
         uint64_t *mrow = net.mask[l + 1] + ((size_t)t * B + b) * net.Wd[l + 1];
         uint32_t spn = 0;
 #pragma unroll
@@ -206,14 +233,11 @@ k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float 
             if ((sp[l] >> k) & 1u) a = a - net.theta;
             const float vn = n < N ? a + (a_in[k] + a_rec[k]) : 0.0f;
             v[l][k] = vn;
-            uint64_t word;
-            if (GEN) {
-              word = __ballot(n < N && vn > net.theta);
-              if (lane == 0) mrow[widx] = word;
-            } else {
-              word = mrow[widx];
+            const uint64_t word = __ballot(n < N && vn > net.theta);
+            if (lane == 0) {
+              mrow[widx] = word;
+              wl_[widx] = word;
             }
-            if (lane == 0) wl_[widx] = word;
             if ((word >> lane) & 1ull) spn |= 1u << k;
             if (store_slot >= 0 && n < N)
               st.base[(size_t)store_slot * st.slot_stride + (size_t)b * net.SN + net.off[l] + n] = vn;
@@ -242,22 +266,22 @@ k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float 
 
   // ---- epilogue: last readout, final state, readout state ---------------------------------
   if (service) {
-    if (GEN && t1 > t0) {
-      const int c = cnt[L];
-      const uint16_t *lst = lists + lo[L];
-      for (int o = lane; o < O; o += WAVE) {
-        float acc = 0.0f;
-        for (int i = 0; i < c; ++i) acc = acc + net.W_out[(size_t)lst[i] * O + o];
-        const double un = (double)net.beta * u[o] + (double)acc;
-        u[o] = un;
-        usum[o] = usum[o] + un;
+    if (t1 > t0) {
+      for (int o0 = 0; o0 < O; o0 += WAVE) {
+        float acc[1], unused[1];
+        gather2<1>(net.W_out, O, 0u, o0 + lane, WAVE, lists + lo[L], cnt[L], lists, 0, acc, unused);
+        const int o = o0 + lane;
+        if (o < O) {
+          const double un = (double)net.beta * u[o] + (double)acc[0];
+          u[o] = un;
+          usum[o] = usum[o] + un;
+        }
       }
     }
-    if (GEN)
-      for (int o = lane; o < O; o += WAVE) {
-        readout[((size_t)b * 2 + 0) * O + o] = u[o];
-        readout[((size_t)b * 2 + 1) * O + o] = usum[o];
-      }
+    for (int o = lane; o < O; o += WAVE) {
+      readout[((size_t)b * 2 + 0) * O + o] = u[o];
+      readout[((size_t)b * 2 + 1) * O + o] = usum[o];
+    }
   } else if (state_out) {
 #pragma unroll
     for (int l = 0; l < SNN_MAXL; ++l) {
@@ -269,6 +293,105 @@ k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float 
       }
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// B1 (recompute), part 1: synaptic currents of a whole chunk, parallel over time.
+// A recompute pass reads the stored spikes instead of generating them, so nothing in it depends on
+// the threshold: the currents I_t = I_in,t + I_rec,t of every (t, b, layer) of a chunk are
+// independent gathers.  One workgroup per (t, b, layer) expands the two stored bit rows into index
+// lists and runs the same gather as the forward pass; the result lands in the chunk buffer at the
+// slot of x_t.  Part 2 (k_scan) then turns currents into states in place.
+// ------------------------------------------------------------------------------------------
+static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd, uint16_t *list, int *cnt, int tid,
+                                                  int nt) {
+  for (int widx = tid >> 6; widx < Wd; widx += nt >> 6) {
+    const uint64_t word = words[widx];
+    int pre = 0;
+    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
+    if ((word >> lane_id()) & 1ull) list[pre + __popcll(word & lanemask_lt())] = (uint16_t)(widx * WAVE + lane_id());
+    if (widx == Wd - 1 && lane_id() == 0) *cnt = pre + __popcll(word);
+  }
+}
+
+template <int NPT>
+__global__ void __launch_bounds__(512)
+k_currents(NetDev net, int t0, float *__restrict__ buf, int t_base, size_t slot_stride) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int l = blockIdx.y, B = net.B;
+  const int t = t0 + 1 + (int)(blockIdx.x / B), b = (int)(blockIdx.x % B);
+  const int N = net.N[l], P = l == 0 ? net.n_in : net.N[l - 1];
+  const int Wi = net.Wd[l], Wr = net.Wd[l + 1];
+  uint64_t *w_in = (uint64_t *)smem;       // [Wi]
+  uint64_t *w_rec = w_in + Wi;             // [Wr]
+  int *cnt = (int *)(w_rec + Wr);          // [2] (+2 pad)
+  uint16_t *l_in = (uint16_t *)(cnt + 4);  // [P rounded up to 8]
+  uint16_t *l_rec = l_in + ((P + 7) & ~7); // [N]
+  const uint64_t *g_in = net.mask[l] + ((size_t)t * B + b) * Wi;
+  const uint64_t *g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * Wr;
+  for (int i = tid; i < Wi; i += nt) w_in[i] = g_in[i];
+  for (int i = tid; i < Wr; i += nt) w_rec[i] = g_rec[i];
+  __syncthreads();
+  expand_all(w_in, Wi, l_in, &cnt[0], tid, nt);
+  expand_all(w_rec, Wr, l_rec, &cnt[1], tid, nt);
+  __syncthreads();
+  float a_in[NPT], a_rec[NPT];
+  gather2<NPT>(net.W_in[l], N, (uint32_t)P, tid, nt, l_in, cnt[0], l_rec, cnt[1], a_in, a_rec);
+  float *dst = buf + (size_t)(t - t_base - 1) * slot_stride + (size_t)b * net.SN + net.off[l];
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    const int n = tid + k * nt;
+    if (n < N) dst[n] = a_in[k] + a_rec[k];
+  }
+}
+
+// B1, part 2: v_t = (alpha v_{t-1} - theta s_{t-1}) + I_t along a chunk, one thread per (b, neuron).
+// buf holds I_t at the slot of x_t on entry; with store_all the states replace the currents in
+// place, otherwise only the final state is written (state_out).  Same operations, in the same
+// order, as the forward pass, so the recomputed states are bit-identical to the original ones.
+__global__ void __launch_bounds__(256)
+k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *buf, int t_base, size_t slot_stride,
+       int store_all, float *__restrict__ state_out) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int B = net.B, SN = net.SN;
+  if (i >= (size_t)B * SN) return;
+  const int b = (int)(i / SN), idx = (int)(i % SN);
+  int l = 0;
+  while (l + 1 < net.L && idx >= net.off[l + 1]) ++l;
+  const int n = idx - net.off[l], Wd = net.Wd[l + 1];
+  const uint64_t *mcol = net.mask[l + 1] + (size_t)b * Wd + (n >> 6);
+  const size_t mstride = (size_t)B * Wd;
+  const int sh = n & 63;
+  float v = state_in[i];
+  float *col = buf + i;
+  constexpr int U = 8;
+  int t = t0 + 1;
+  for (; t + U - 1 <= t1; t += U) {
+    float cur[U];
+    uint64_t wd[U];
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      cur[r] = col[(size_t)(t + r - t_base - 1) * slot_stride];
+      wd[r] = mcol[(size_t)(t + r - 1) * mstride];
+    }
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      float a = net.alpha * v;
+      if ((wd[r] >> sh) & 1ull) a = a - net.theta;
+      v = a + cur[r];
+      if (store_all) col[(size_t)(t + r - t_base - 1) * slot_stride] = v;
+    }
+  }
+  for (; t <= t1; ++t) {
+    const float cur = col[(size_t)(t - t_base - 1) * slot_stride];
+    const uint64_t wd = mcol[(size_t)(t - 1) * mstride];
+    float a = net.alpha * v;
+    if ((wd >> sh) & 1ull) a = a - net.theta;
+    v = a + cur;
+    if (store_all) col[(size_t)(t - t_base - 1) * slot_stride] = v;
+  }
+  if (state_out) state_out[i] = v;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -522,6 +645,7 @@ static size_t adjoint_lds(const NetDev &net, int nt) {
   return ((size_t)2 * net.SN + 2 * net.n_out + nt) * sizeof(float);
 }
 
+static size_t currents_lds(const NetDev &net);
 bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
   const LaunchCfg c = forward_cfg(net);
   const size_t lds_max = 64 * 1024; // per-workgroup limit without opting in to more
@@ -530,6 +654,7 @@ bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
     if ((net.N[l] + c.npt - 1) / c.npt > c.nt_neuron) { snprintf(why, why_len, "layer too wide for the forward kernel (max %d neurons)", 512 * 16); return false; }
   if (net.Wd[0] > WAVE) { snprintf(why, why_len, "n_in > 4096 not supported"); return false; }
   if (c.lds_bytes > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", c.lds_bytes, lds_max); return false; }
+  if (currents_lds(net) > lds_max) { snprintf(why, why_len, "recompute kernel needs %zu B of LDS (> %zu)", currents_lds(net), lds_max); return false; }
   if (adjoint_lds(net, 1024) > lds_max) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
   return true;
 }
@@ -541,15 +666,15 @@ hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, 
   return hipGetLastError();
 }
 
-template <bool GEN>
-static hipError_t launch_forward_t(const NetDev &net, const LaunchCfg &c, int t0, int t1, const float *state_in,
-                                   float *state_out, const StoreSpec &st, double *readout, int readout_init,
-                                   hipStream_t s) {
+hipError_t launch_forward(const NetDev &net, int t0, int t1, const float *state_in, float *state_out,
+                          const StoreSpec &st, double *readout, int readout_init, hipStream_t s) {
+  if (t1 < t0) return hipErrorInvalidValue;
+  const LaunchCfg c = forward_cfg(net);
   const dim3 grid(net.B), block(c.nt_neuron + WAVE);
-#define FWD_CASE(NPT_)                                                                                          \
-  case NPT_:                                                                                                     \
-    hipLaunchKernelGGL((k_forward<NPT_, GEN>), grid, block, c.lds_bytes, s, net, t0, t1, state_in, state_out, st, \
-                       readout, readout_init, c.nt_neuron);                                                      \
+#define FWD_CASE(NPT_)                                                                                       \
+  case NPT_:                                                                                                  \
+    hipLaunchKernelGGL((k_forward<NPT_>), grid, block, c.lds_bytes, s, net, t0, t1, state_in, state_out, st, \
+                       readout, readout_init, c.nt_neuron);                                                   \
     break;
   switch (c.npt) {
     FWD_CASE(1) FWD_CASE(2) FWD_CASE(4) FWD_CASE(8) FWD_CASE(16)
@@ -559,12 +684,37 @@ static hipError_t launch_forward_t(const NetDev &net, const LaunchCfg &c, int t0
   return hipGetLastError();
 }
 
-hipError_t launch_forward(const NetDev &net, bool generate, int t0, int t1, const float *state_in, float *state_out,
-                          const StoreSpec &st, double *readout, int readout_init, hipStream_t s) {
-  if (t1 < t0) return hipErrorInvalidValue;
+static size_t currents_lds(const NetDev &net) {
+  size_t mx = 0;
+  for (int l = 0; l < net.L; ++l) {
+    const int P = l == 0 ? net.n_in : net.N[l - 1];
+    const size_t b = (size_t)(net.Wd[l] + net.Wd[l + 1]) * 8 + 16 + (size_t)(((P + 7) & ~7) + ((net.N[l] + 7) & ~7)) * 2;
+    mx = b > mx ? b : mx;
+  }
+  return mx;
+}
+
+hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
+                            size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
+  if (t1 <= t0) return hipErrorInvalidValue;
   const LaunchCfg c = forward_cfg(net);
-  return generate ? launch_forward_t<true>(net, c, t0, t1, state_in, state_out, st, readout, readout_init, s)
-                  : launch_forward_t<false>(net, c, t0, t1, state_in, state_out, st, readout, readout_init, s);
+  const dim3 grid((unsigned)((size_t)(t1 - t0) * net.B), net.L), block(c.nt_neuron);
+  const size_t lds = currents_lds(net);
+#define CUR_CASE(NPT_)                                                                                         \
+  case NPT_:                                                                                                    \
+    hipLaunchKernelGGL((k_currents<NPT_>), grid, block, lds, s, net, t0, buf, t_base, slot_stride);            \
+    break;
+  switch (c.npt) {
+    CUR_CASE(1) CUR_CASE(2) CUR_CASE(4) CUR_CASE(8) CUR_CASE(16)
+    default: return hipErrorInvalidValue;
+  }
+#undef CUR_CASE
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t n = (size_t)net.B * net.SN;
+  hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
+                     slot_stride, store_all, state_out);
+  return hipGetLastError();
 }
 
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar, float *g,
