@@ -3,6 +3,7 @@
 // that walks a checkpoint schedule (Fig. 1 of the paper) launching the HIP kernels.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -34,6 +35,7 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
+  bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -133,6 +135,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (!valid_cfg(cfg, &why)) return fail(c, SNN_E_INVAL, why);
   c->cfg = *cfg;
   fill_shape(*cfg, &c->net);
+  if (const char *e = std::getenv("SNN_DW")) c->dw_event_driven = std::strcmp(e, "event") == 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -548,10 +551,20 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         tm.end();
         first_adjoint = false;
         tm.begin(3);
-        HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, c->dubuf, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
-        for (int l = 0; l < L; ++l) {
-          HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
-          HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
+        if (c->dw_event_driven || B > 128) {
+          HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, c->dubuf, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
+          for (int l = 0; l < L; ++l) {
+            HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
+            HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
+          }
+        } else {
+          DwBatch db{};
+          db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, c->dubuf, (size_t)B * O, O, 0, c->acc_out, 0, 0};
+          for (int l = 0; l < L; ++l) {
+            db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], chunk, slot, SN, n.off[l], c->acc_in[l], 0, 0};
+            db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], chunk, slot, SN, n.off[l], c->acc_rec[l], 0, 0};
+          }
+          HIPCHK(c, launch_dw_mfma(db, B, t0, t1, base, s));
         }
         tm.end();
         st.bwd_steps += t1 - t0;

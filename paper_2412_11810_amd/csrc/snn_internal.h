@@ -69,6 +69,22 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
 hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,
                      size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1,
                      int t_base, double *dW, hipStream_t s);
+// One weight matrix of the dense dW contraction (see k_dw_mfma).
+struct DwDesc {
+  const uint64_t *pre_mask; // spike words of the presynaptic layer, [T+1][B][pre_words]
+  int pre_words, lag;       // lag 0: spikes of step t; lag 1: spikes of step t-1 (recurrent matrices)
+  int n_pre, n_post;
+  const float *post;        // adjoint buffer: slot (t - t_base - 1), row b at b*post_stride + post_off
+  size_t slot_stride;
+  int post_stride, post_off;
+  double *acc;              // [n_pre][n_post] fp64 accumulators
+  int tile0, tiles_n;       // filled by the launcher
+};
+struct DwBatch {
+  DwDesc d[2 * SNN_MAXL + 1];
+  int count;
+};
+hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipStream_t s);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
 hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,

@@ -578,6 +578,109 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
 }
 
 // ------------------------------------------------------------------------------------------
+// B5, dense path: dW += S^T . P on the fp64 matrix cores, where S[(t,b)][j] are the presynaptic
+// spikes (0/1) and P[(t,b)][n] the postsynaptic adjoints dv_t (or du_t).  At the activity levels the
+// benchmark networks run at, adding rows event by event moves more bytes than this contraction
+// costs in flops.  v_mfma_f64_16x16x4: one K-step covers 4 consecutive batch elements of one time
+// step, K-steps run over (t descending, b ascending) and the fp64 accumulators persist in HBM
+// between launches, so the sequence of operations applied to an element does not depend on how the
+// time axis is cut into chunks: every storage strategy gets bit-identical gradients.  A K-step
+// whose 16x4 spike block is empty is skipped (it would add exact zeros).
+// Lane layouts (checked on gfx950): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
+// D[(lane/16) + 4r][lane%16] in register r of the lane.
+// One launch covers every weight matrix of the network: blockIdx.x -> (matrix, 64 x 16*NT tile).
+// ------------------------------------------------------------------------------------------
+typedef double dvec4 __attribute__((ext_vector_type(4)));
+
+template <int NT>
+__global__ void __launch_bounds__(256)
+k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  int di = 0;
+  while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
+  const DwDesc &d = batch.d[di];
+  const int tile = blockIdx.x - d.tile0;
+  const int j0 = (tile / d.tiles_n) * 64, n0 = (tile % d.tiles_n) * (16 * NT);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int Bp = (B + 3) & ~3;
+  constexpr int COLS = 16 * NT, STRIDE = COLS + 16; // rows 16 banks apart: conflict-free operand reads
+  float *Pt = (float *)smem;                                   // [2][Bp][STRIDE]
+  uint64_t *Sw = (uint64_t *)(Pt + (size_t)2 * Bp * STRIDE);  // [2][Bp]
+  const int li = lane & 15, lk = lane >> 4;
+
+  dvec4 acc[NT];
+#pragma unroll
+  for (int q = 0; q < NT; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * q + li;
+      acc[q][r] = (j < d.n_pre && n < d.n_post) ? d.acc[(size_t)j * d.n_post + n] : 0.0;
+    }
+
+  // staging: thread -> (row, 4 columns) of the P tile; 256 threads cover 256/(COLS/4) rows per pass
+  constexpr int TPR = COLS / 4;          // threads per row
+  constexpr int RPP = 256 / TPR;         // rows per pass
+  const int srow = tid / TPR, scol = (tid % TPR) * 4;
+  const int passes = (Bp + RPP - 1) / RPP;
+  auto stage_load = [&](int t, float (&reg)[4][4], uint64_t &wreg) {
+    const float *prow = d.post + (size_t)(t - t_base - 1) * d.slot_stride + d.post_off + n0 + scol;
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int b = srow + ps * RPP;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        reg[ps][c] = (ps < passes && b < B && n0 + scol + c < d.n_post) ? prow[(size_t)b * d.post_stride + c] : 0.0f;
+    }
+    wreg = 0;
+    if (tid < B) wreg = d.pre_mask[((size_t)(t - d.lag) * B + tid) * d.pre_words + (j0 >> 6)];
+  };
+  auto stage_store = [&](int buf, const float (&reg)[4][4], uint64_t wreg) {
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int b = srow + ps * RPP;
+      if (ps < passes && b < Bp) {
+        float *dst = Pt + ((size_t)buf * Bp + b) * STRIDE + scol;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dst[c] = reg[ps][c];
+      }
+    }
+    if (tid < Bp) Sw[(size_t)buf * Bp + tid] = wreg;
+  };
+
+  float reg[4][4];
+  uint64_t wreg;
+  stage_load(t1, reg, wreg);
+  stage_store(0, reg, wreg);
+  __syncthreads();
+  int buf = 0;
+  for (int t = t1; t > t0; --t) {
+    if (t - 1 > t0) stage_load(t - 1, reg, wreg); // global loads in flight during the MFMAs
+    const float *P = Pt + (size_t)buf * Bp * STRIDE;
+    const uint64_t *S = Sw + (size_t)buf * Bp;
+    for (int b0 = 0; b0 < Bp; b0 += 4) {
+      const uint64_t word = S[b0 + lk];
+      const bool bit = (word >> (16 * w + li)) & 1ull;
+      if (__ballot(bit) == 0ull) continue;
+      const double a = bit ? 1.0 : 0.0;
+      const float *prow = P + (size_t)(b0 + lk) * STRIDE + li;
+#pragma unroll
+      for (int q = 0; q < NT; ++q)
+        acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)prow[16 * q], acc[q], 0, 0, 0);
+    }
+    if (t - 1 > t0) stage_store(buf ^ 1, reg, wreg);
+    __syncthreads();
+    buf ^= 1;
+  }
+#pragma unroll
+  for (int q = 0; q < NT; ++q)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * q + li;
+      if (j < d.n_pre && n < d.n_post) d.acc[(size_t)j * d.n_post + n] = acc[q][r];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // small utilities
 // ------------------------------------------------------------------------------------------
 __global__ void k_transpose(const float *__restrict__ src, float *__restrict__ dst, int rows, int cols) {
@@ -739,6 +842,26 @@ hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag
   const dim3 grid(n_pre, (n_post + 256 * DW_NPT - 1) / (256 * DW_NPT));
   hipLaunchKernelGGL(k_dw, grid, dim3(256), 0, s, pre_mask, pre_words, lag, postbuf, slot_stride, post_stride,
                      post_off, n_post, B, t0, t1, t_base, dW);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipStream_t s) {
+  if (t1 <= t0 || batch.count <= 0) return hipSuccess;
+  const int Bp = (B + 3) & ~3;
+  if (Bp > 128) return hipErrorInvalidValue; // the staging registers cover at most 128 batch rows
+  // wide tiles when they already fill the chip, narrow ones otherwise
+  int tiles4 = 0;
+  for (int i = 0; i < batch.count; ++i) tiles4 += ((batch.d[i].n_pre + 63) / 64) * ((batch.d[i].n_post + 63) / 64);
+  const int NT = (tiles4 >= 256 && Bp <= 64) ? 4 : 2;
+  int total = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    batch.d[i].tiles_n = (batch.d[i].n_post + 16 * NT - 1) / (16 * NT);
+    batch.d[i].tile0 = total;
+    total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
+  }
+  const size_t lds = (size_t)2 * Bp * (16 * NT + 16) * sizeof(float) + (size_t)2 * Bp * 8;
+  if (NT == 4) hipLaunchKernelGGL((k_dw_mfma<4>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
+  else hipLaunchKernelGGL((k_dw_mfma<2>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
   return hipGetLastError();
 }
 
