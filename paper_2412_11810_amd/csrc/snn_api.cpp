@@ -30,7 +30,7 @@ struct snn_ctx {
   // activation arena (HBM "local memory"), readout-adjoint tile, pinned host checkpoints
   float *arena = nullptr;
   size_t arena_bytes = 0;
-  float *dubuf = nullptr;
+  float *dubuf = nullptr; // readout adjoints of a chunk, followed by the inter-layer product scratch
   size_t dubuf_bytes = 0;
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
@@ -88,6 +88,13 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
+// per-chunk scratch: readout adjoints [chunk][B][O] + inter-layer products of one layer [chunk][B][max N_l]
+size_t work_bytes(const NetDev &n, int chunk_len) {
+  int nmax = 0;
+  for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
+  return (size_t)chunk_len * n.B * (n.n_out + nmax) * sizeof(float);
+}
+
 size_t spike_bytes(const NetDev &n, int T) {
   size_t w = 0;
   for (int l = 0; l <= n.L; ++l) w += (size_t)(T + 1) * n.B * n.Wd[l];
@@ -122,8 +129,7 @@ size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t 
   NetDev n{};
   fill_shape(*cfg, &n);
   const size_t Ms = (size_t)n.B * n.SN * sizeof(float);
-  const size_t work = (size_t)p.chunk_len * n.B * n.n_out * sizeof(float);
-  return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work;
+  return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work_bytes(n, p.chunk_len);
 }
 
 snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
@@ -385,7 +391,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   const int B = n.B, O = n.n_out, L = n.L, SN = n.SN;
   const size_t Ms = c->Ms(), slot = (size_t)B * SN;
   const size_t need_states = (size_t)p.local_slots() * Ms;
-  const size_t need_work = (size_t)p.chunk_len * B * O * sizeof(float);
+  const size_t need_work = work_bytes(n, p.chunk_len);
   const size_t need_spikes = spike_bytes(n, T);
   if (budget && need_states + need_work + need_spikes > budget) {
     char buf[200];
@@ -547,7 +553,8 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         const int t1 = op.a, t0 = op.b - 1;
         const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
         tm.begin(2);
-        HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0, s));
+        HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0,
+                                 c->dubuf + (size_t)p.chunk_len * B * O, s));
         tm.end();
         first_adjoint = false;
         tm.begin(3);

@@ -58,11 +58,12 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s);
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
                        float *g, float *loss, hipStream_t s);
-// Adjoint recurrence over steps t1, t1-1, ..., t0+1.  vbuf holds x_t at slot (t - t_base - 1) and is
+// Adjoint pass over steps t1, t1-1, ..., t0+1.  vbuf holds x_t at slot (t - t_base - 1) and is
 // overwritten in place by delta_v_t.  dubuf gets delta_u_t at the same slot index ([slot][B][O]).
 // carry: [B][SN + O] floats (delta_v_{t+1} of all layers, delta_u_{t+1}); carry_init zeroes it first.
+// upbuf: scratch for the inter-layer products of one layer, (t1 - t0) * B * max_l N_l floats.
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf,
-                          const float *g, float *carry, int carry_init, hipStream_t s);
+                          const float *g, float *carry, int carry_init, float *upbuf, hipStream_t s);
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
 // element) and column offset post_off.

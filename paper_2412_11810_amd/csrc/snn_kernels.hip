@@ -428,14 +428,145 @@ __global__ void __launch_bounds__(256) k_loss(const double *__restrict__ readout
 }
 
 // ------------------------------------------------------------------------------------------
-// B2-B4: adjoint recurrence, one workgroup per batch element, time loop (descending) on device.
-//   du_t   = beta du_{t+1} + g
-//   ds^l_t = (l==L ? W_out du_t : W_in^{l+1} dv^{l+1}_t) + W_rec^l dv^l_{t+1} - theta dv^l_{t+1}
+// B2-B4: adjoint pass over one chunk of time steps, layer by layer (top layer first):
+//   du_t   = beta du_{t+1} + g                                             (k_du_scan)
+//   up^l_t = (l==L ? W_out du_t : W_in^{l+1} dv^{l+1}_t)                   (k_up_gemm, all t of the chunk at once)
+//   ds^l_t = up^l_t + W_rec^l dv^l_{t+1} - theta dv^l_{t+1}                (k_adj_rec_*: the only sequential part)
 //   dv^l_t = alpha dv^l_{t+1} + ds^l_t / (1 + k |v^l_t - theta|)^2
-// The dense products walk the transposed weights so that consecutive threads (post index j) read
-// consecutive addresses; the K range is split over KG thread groups whose partial sums are
-// combined in a fixed order.
+// dv^l_t needs dv^{l+1}_t of the same step and dv^l_{t+1}; running a whole chunk of layer l+1 before
+// layer l keeps both available and turns the inter-layer product into one dense GEMM per chunk that
+// fills the chip, leaving only the recurrent product in the per-batch-element time loop.
 // ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restrict__ dubuf, int B, int O, int SN,
+          int t0, int t1, int t_base, float beta, int carry_init) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * O) return;
+  const int b = i / O, o = i % O;
+  float *cb = carry + (size_t)b * (SN + O) + SN + o;
+  float d = carry_init ? 0.0f : *cb;
+  const float gg = g[i];
+  for (int t = t1; t > t0; --t) {
+    d = beta * d + gg;
+    dubuf[((size_t)(t - t_base - 1) * B + b) * O + o] = d;
+  }
+  *cb = d;
+}
+
+// C[m][j] = sum_k A[m*lda + k] * W[j*K + k]   (m < M rows = (slot, b) pairs, j < N, k ascending)
+__global__ void __launch_bounds__(256)
+k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
+          int ldc, int M) {
+  __shared__ float As[16][68], Ws[16][68];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
+  const int r = tid >> 2, kq = (tid & 3) * 4;
+  for (int k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int kk = kq + e;
+      As[kk][r] = (m0 + r < M && k0 + kk < K) ? A[(size_t)(m0 + r) * lda + k0 + kk] : 0.0f;
+      Ws[kk][r] = (j0 + r < N && k0 + kk < K) ? W[(size_t)(j0 + r) * K + k0 + kk] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; w[i] = Ws[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, jj = j0 + tx * 4 + j;
+      if (m < M && jj < N) C[(size_t)m * ldc + jj] = acc[i][j];
+    }
+}
+
+// Recurrent part, layers of up to 2*KH neurons: the recurrent matrix stays in registers for the
+// whole chunk.  Thread (j, h) keeps W_rec[j][h*KH .. h*KH+KH) (two threads per postsynaptic row, each
+// half of the reduction); dv_{t+1} is broadcast from LDS; per step 2*KH/2 fused multiply-adds per
+// thread and two barriers, no weight traffic at all.  One workgroup per batch element.
+template <int KH>
+__global__ void __launch_bounds__(512)
+k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
+             int ldu, float *__restrict__ carry, int carry_init) {
+  __shared__ __align__(16) float x[2][2 * KH];
+  __shared__ float part[256];
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x;
+  const int NJ = blockDim.x >> 1, tid = threadIdx.x;
+  const int j = tid % NJ, h = tid / NJ;
+  const bool own = h == 0 && j < N;
+  float *cb = carry + (size_t)b * (SN + net.n_out) + off;
+
+  float w[KH];
+#pragma unroll
+  for (int q = 0; q < KH; ++q) {
+    const int n = h * KH + q;
+    w[q] = (j < N && n < N) ? net.W_recT[l][(size_t)n * N + j] : 0.0f; // = W_rec[j][n], coalesced over j
+  }
+  for (int i = tid; i < 2 * KH; i += blockDim.x) {
+    x[0][i] = (i < N && !carry_init) ? cb[i] : 0.0f;
+    x[1][i] = 0.0f;
+  }
+  __syncthreads();
+  int cur = 0;
+  const size_t slot_stride = (size_t)B * SN;
+  float vt = 0.0f, upv = 0.0f;
+  if (own && t1 > t0) {
+    vt = vbuf[(size_t)(t1 - t_base - 1) * slot_stride + (size_t)b * SN + off + j];
+    upv = up[((size_t)(t1 - t_base - 1) * B + b) * ldu + j];
+  }
+  for (int t = t1; t > t0; --t) {
+    float vt_n = 0.0f, up_n = 0.0f; // operands of the next (earlier) step, in flight during the product
+    if (own && t - 1 > t0) {
+      vt_n = vbuf[(size_t)(t - 2 - t_base) * slot_stride + (size_t)b * SN + off + j];
+      up_n = up[((size_t)(t - 2 - t_base) * B + b) * ldu + j];
+    }
+    const float4 *xs = reinterpret_cast<const float4 *>(&x[cur][h * KH]);
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+#pragma unroll
+    for (int q = 0; q < KH / 4; ++q) {
+      const float4 xv = xs[q];
+      a0 = fmaf(w[4 * q + 0], xv.x, a0);
+      a1 = fmaf(w[4 * q + 1], xv.y, a1);
+      a2 = fmaf(w[4 * q + 2], xv.z, a2);
+      a3 = fmaf(w[4 * q + 3], xv.w, a3);
+    }
+    const float p = (a0 + a1) + (a2 + a3);
+    if (h == 1 && j < 256) part[j] = p;
+    __syncthreads();
+    if (own) {
+      const float dn = x[cur][j];
+      const float ds = ((p + part[j]) + upv) - net.theta * dn;
+      const float d = 1.0f + net.k * fabsf(vt - net.theta);
+      const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+      x[cur ^ 1][j] = dvt;
+      vbuf[(size_t)(t - t_base - 1) * slot_stride + (size_t)b * SN + off + j] = dvt;
+    }
+    __syncthreads();
+    cur ^= 1;
+    vt = vt_n;
+    upv = up_n;
+  }
+  if (own) cb[j] = x[cur][j];
+}
+
+// Recurrent part, any layer width: the transposed recurrent matrix is streamed from L2 every step
+// (coalesced over the output index), the reduction split over KG thread groups with a fixed
+// combination order.
 static __device__ __forceinline__ float dot_T(const float *__restrict__ WT, int ld, int j, const float *x, int n0,
                                               int n1) {
   float a0 = 0.0f, a1 = 0.0f;
@@ -455,81 +586,51 @@ static __device__ __forceinline__ float dot_T(const float *__restrict__ WT, int 
 }
 
 __global__ void __launch_bounds__(1024)
-k_adjoint(NetDev net, int t0, int t1, float *__restrict__ vbuf, int t_base, float *__restrict__ dubuf,
-          const float *__restrict__ g, float *__restrict__ carry, int carry_init) {
+k_adj_rec_stream(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base,
+                 const float *__restrict__ up, int ldu, float *__restrict__ carry, int carry_init) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, NT = blockDim.x, b = blockIdx.x;
-  const int L = net.L, O = net.n_out, SN = net.SN, B = net.B;
-  float *dvA = (float *)smem;   // [SN]
-  float *dvB = dvA + SN;        // [SN]
-  float *du = dvB + SN;         // [O]
-  float *gv = du + O;           // [O]
-  float *part = gv + O;         // [NT]
-  float *cb = carry + (size_t)b * (SN + O);
-
-  for (int i = tid; i < SN; i += NT) { dvA[i] = carry_init ? 0.0f : cb[i]; dvB[i] = 0.0f; }
-  for (int o = tid; o < O; o += NT) {
-    const float gg = g[(size_t)b * O + o];
-    gv[o] = gg;
-    const float d = carry_init ? 0.0f : cb[SN + o];
-    du[o] = net.beta * d + gg; // du of the first step processed (t1)
-  }
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN;
+  float *xa = (float *)smem; // [N]
+  float *xb = xa + N;        // [N]
+  float *part = xb + N;      // [NT]
+  float *cb = carry + (size_t)b * (SN + net.n_out) + off;
+  for (int i = tid; i < N; i += NT) { xa[i] = carry_init ? 0.0f : cb[i]; xb[i] = 0.0f; }
   __syncthreads();
-  float *dv_next = dvA, *dv_cur = dvB;
-
+  float *x_next = xa, *x_cur = xb;
+  const int NJ = (N + WAVE - 1) & ~(WAVE - 1);
+  const int tile = NJ < NT ? NJ : NT;
+  const int KG = NT / tile;
+  const int kg = tid / tile, jt = tid % tile;
+  const int r0 = (int)((long long)N * kg / KG), r1 = (int)((long long)N * (kg + 1) / KG);
   for (int t = t1; t > t0; --t) {
     const size_t slot = (size_t)(t - t_base - 1);
-    float *vrow = vbuf + slot * ((size_t)B * SN) + (size_t)b * SN;
-    for (int o = tid; o < O; o += NT) dubuf[(slot * B + b) * O + o] = du[o];
-
-    for (int l = L - 1; l >= 0; --l) {
-      const int N = net.N[l], off = net.off[l];
-      const int NJ = (N + WAVE - 1) & ~(WAVE - 1);
-      const int tile = NJ < NT ? NJ : NT;   // j values handled at once
-      const int KG = NT / tile;             // thread groups splitting the reduction
-      const int kg = tid / tile, jt = tid % tile;
-      const float *WupT;
-      const float *xup;
-      int Kup;
-      if (l == L - 1) { WupT = net.W_outT; xup = du; Kup = O; }
-      else { WupT = net.W_inT[l + 1]; xup = dv_cur + net.off[l + 1]; Kup = net.N[l + 1]; }
-      const float *xrec = dv_next + off;
-      for (int jb = 0; jb < NJ; jb += tile) {
-        const int j = jb + jt;
-        const bool act = kg < KG && j < N;
-        float vt = 0.0f;
-        if (act && kg == 0) vt = vrow[off + j];
-        float p = 0.0f;
-        if (act) {
-          const int u0 = (int)((long long)Kup * kg / KG), u1 = (int)((long long)Kup * (kg + 1) / KG);
-          const int r0 = (int)((long long)N * kg / KG), r1 = (int)((long long)N * (kg + 1) / KG);
-          p = dot_T(WupT, N, j, xup, u0, u1) + dot_T(net.W_recT[l], N, j, xrec, r0, r1);
-        }
-        if (kg < KG) part[kg * tile + jt] = p;
-        __syncthreads();
-        if (act && kg == 0) {
-          float s = part[jt];
-          for (int q = 1; q < KG; ++q) s = s + part[q * tile + jt];
-          const float dn = xrec[j];
-          const float ds = s - net.theta * dn;
-          const float d = 1.0f + net.k * fabsf(vt - net.theta);
-          const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
-          dv_cur[off + j] = dvt;
-          vrow[off + j] = dvt;
-        }
-        __syncthreads();
+    float *vrow = vbuf + slot * ((size_t)B * SN) + (size_t)b * SN + off;
+    const float *urow = up + (slot * B + b) * ldu;
+    for (int jb = 0; jb < NJ; jb += tile) {
+      const int j = jb + jt;
+      const bool act = kg < KG && j < N;
+      float vt = 0.0f, upv = 0.0f;
+      if (act && kg == 0) { vt = vrow[j]; upv = urow[j]; }
+      float p = 0.0f;
+      if (act) p = dot_T(net.W_recT[l], N, j, x_next, r0, r1);
+      if (kg < KG) part[kg * tile + jt] = p;
+      __syncthreads();
+      if (act && kg == 0) {
+        float s = part[jt];
+        for (int q = 1; q < KG; ++q) s = s + part[q * tile + jt];
+        const float dn = x_next[j];
+        const float ds = (s + upv) - net.theta * dn;
+        const float d = 1.0f + net.k * fabsf(vt - net.theta);
+        const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+        x_cur[j] = dvt;
+        vrow[j] = dvt;
       }
+      __syncthreads();
     }
-    // next step's readout adjoint (independent of the layers): safe to update now, every
-    // read of du for this step is behind the barrier above
-    for (int o = tid; o < O; o += NT) du[o] = net.beta * du[o] + gv[o];
-    float *tmp = dv_next; dv_next = dv_cur; dv_cur = tmp;
-    __syncthreads();
+    float *tmp = x_next; x_next = x_cur; x_cur = tmp;
   }
-  // carry out: dv_{t0+1} and du_{t0+1}.  du currently holds beta*du_{t0+1}+g; undo by recomputing
-  for (int i = tid; i < SN; i += NT) cb[i] = dv_next[i];
-  if (t1 > t0)
-    for (int o = tid; o < O; o += NT) cb[SN + o] = dubuf[((size_t)(t0 - t_base) * B + b) * O + o];
+  for (int i = tid; i < N; i += NT) cb[i] = x_next[i];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -745,7 +846,9 @@ static LaunchCfg forward_cfg(const NetDev &net) {
 }
 
 static size_t adjoint_lds(const NetDev &net, int nt) {
-  return ((size_t)2 * net.SN + 2 * net.n_out + nt) * sizeof(float);
+  int nmax = 0;
+  for (int l = 0; l < net.L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
+  return nmax <= 256 ? 0 : ((size_t)2 * nmax + nt) * sizeof(float);
 }
 
 static size_t currents_lds(const NetDev &net);
@@ -827,11 +930,35 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
 }
 
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf, const float *g,
-                          float *carry, int carry_init, hipStream_t s) {
-  if (t1 < t0) return hipErrorInvalidValue;
-  const int nt = 1024;
-  hipLaunchKernelGGL(k_adjoint, dim3(net.B), dim3(nt), adjoint_lds(net, nt), s, net, t0, t1, vbuf, t_base, dubuf, g,
-                     carry, carry_init);
+                          float *carry, int carry_init, float *upbuf, hipStream_t s) {
+  if (t1 <= t0) return hipErrorInvalidValue;
+  const int B = net.B, O = net.n_out, SN = net.SN, L = net.L;
+  const int M = (t1 - t0) * B;
+  // slots are addressed relative to t_base; the chunk processed here starts at slot (t0 - t_base)
+  const size_t s0 = (size_t)(t0 - t_base);
+  hipLaunchKernelGGL(k_du_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, g, carry, dubuf, B, O, SN, t0, t1, t_base,
+                     net.beta, carry_init);
+  for (int l = L - 1; l >= 0; --l) {
+    const int N = net.N[l];
+    const float *A;
+    const float *W;
+    int lda, K;
+    if (l == L - 1) { A = dubuf + s0 * B * O; lda = O; K = O; W = net.W_out; }
+    else { A = vbuf + s0 * ((size_t)B * SN) + net.off[l + 1]; lda = SN; K = net.N[l + 1]; W = net.W_in[l + 1]; }
+    float *C = upbuf; // row m = (slot - s0)*B + b, ldc = N
+    hipLaunchKernelGGL(k_up_gemm, dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
+    const float *up = upbuf - s0 * B * N;
+    if (N <= 256) {
+      const int NJ = (N + 63) & ~63;
+      hipLaunchKernelGGL((k_adj_rec_rs<128>), dim3(B), dim3(2 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N, carry,
+                         carry_init);
+    } else {
+      const int nt = 1024;
+      hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), ((size_t)2 * N + nt) * sizeof(float), s, net, l, t0, t1,
+                         vbuf, t_base, up, N, carry, carry_init);
+    }
+  }
   return hipGetLastError();
 }
 
