@@ -25,6 +25,7 @@ struct snn_ctx {
   int32_t *labels = nullptr;
   int T_bound = 0;
   double *readout = nullptr;
+  float *cur_state = nullptr; // [B][SN] state carried through the forward pass
   float *ubar = nullptr, *g = nullptr, *loss_dev = nullptr, *carry = nullptr;
   unsigned long long *counters = nullptr;
   // activation arena (HBM "local memory"), readout-adjoint tile, pinned host checkpoints
@@ -89,10 +90,12 @@ void fill_shape(const snn_config &c, NetDev *n) {
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
 // per-chunk scratch: readout adjoints [chunk][B][O] + inter-layer products of one layer [chunk][B][max N_l]
+// (the forward pass uses the same scratch for the currents of one time tile)
 size_t work_bytes(const NetDev &n, int chunk_len) {
   int nmax = 0;
   for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
-  return (size_t)chunk_len * n.B * (n.n_out + nmax) * sizeof(float);
+  const int steps = chunk_len > SNN_FWD_TILE ? chunk_len : SNN_FWD_TILE;
+  return (size_t)steps * n.B * (n.n_out + nmax) * sizeof(float);
 }
 
 size_t spike_bytes(const NetDev &n, int T) {
@@ -187,6 +190,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   HIPCHK(c, hipMalloc(&c->g, (size_t)B * O * 4));
   HIPCHK(c, hipMalloc(&c->loss_dev, 16));
   HIPCHK(c, hipMalloc(&c->carry, (size_t)B * (n.SN + O) * 4));
+  HIPCHK(c, hipMalloc(&c->cur_state, (size_t)B * n.SN * 4));
   HIPCHK(c, hipMalloc(&c->counters, 8 * (SNN_MAXL + 1)));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return SNN_OK;
@@ -204,7 +208,7 @@ void snn_destroy(snn_ctx *c) {
   for (int l = 0; l <= SNN_MAXL; ++l) (void)hipFree(c->net.mask[l]);
   (void)hipFree(c->W_out); (void)hipFree(c->W_outT); (void)hipFree(c->dW_out); (void)hipFree(c->acc_out);
   (void)hipFree(c->labels); (void)hipFree(c->readout); (void)hipFree(c->ubar); (void)hipFree(c->g);
-  (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->counters);
+  (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->cur_state); (void)hipFree(c->counters);
   (void)hipFree(c->arena); (void)hipFree(c->dubuf);
   if (c->host_ckpt) (void)hipHostFree(c->host_ckpt);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
@@ -270,6 +274,16 @@ snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *
   return SNN_OK;
 }
 
+static snn_status ensure_work(snn_ctx *c, size_t bytes) {
+  if (c->dubuf_bytes >= bytes) return SNN_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (c->dubuf) HIPCHK(c, hipFree(c->dubuf));
+  c->dubuf = nullptr; c->dubuf_bytes = 0;
+  HIPCHK(c, hipMalloc(&c->dubuf, bytes));
+  c->dubuf_bytes = bytes;
+  return SNN_OK;
+}
+
 static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
   const NetDev &n = c->net;
   StoreSpec st{};
@@ -277,7 +291,10 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
     st.base = traj_or_null; st.slot_stride = (size_t)n.B * n.SN; st.t_base = 0; st.interval = 1; st.slot0 = 0;
     st.t_max = c->T_bound;
   }
-  HIPCHK(c, launch_forward(n, 0, c->T_bound, nullptr, nullptr, st, c->readout, 1, c->stream));
+  snn_status rs = ensure_work(c, work_bytes(n, 1));
+  if (rs != SNN_OK) return rs;
+  HIPCHK(c, hipMemsetAsync(c->cur_state, 0, c->Ms(), c->stream));
+  HIPCHK(c, launch_forward(n, 0, c->T_bound, c->cur_state, st, c->readout, 1, c->dubuf, c->stream));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
   return SNN_OK;
 }
@@ -409,12 +426,9 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     HIPCHK(c, hipMalloc(&c->arena, need_states));
     c->arena_bytes = need_states;
   }
-  if (c->dubuf_bytes < need_work) {
-    HIPCHK(c, hipStreamSynchronize(s));
-    if (c->dubuf) HIPCHK(c, hipFree(c->dubuf));
-    c->dubuf = nullptr; c->dubuf_bytes = 0;
-    HIPCHK(c, hipMalloc(&c->dubuf, need_work));
-    c->dubuf_bytes = need_work;
+  {
+    snn_status rs = ensure_work(c, need_work);
+    if (rs != SNN_OK) return rs;
   }
   const size_t need_host = (size_t)p.n_remote * Ms;
   if (c->host_bytes < need_host) {
@@ -456,13 +470,14 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     }
 
   // ---- forward ------------------------------------------------------------------------------
+  HIPCHK(c, hipMemsetAsync(c->cur_state, 0, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk, slot, 0, 1, 0, T};
-    HIPCHK(c, launch_forward(n, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, hipMemsetAsync(lckpt, 0, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
-    HIPCHK(c, launch_forward(n, 0, T, nullptr, nullptr, sp, c->readout, 1, s));
+    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
   } else {
     std::memset(c->host_ckpt, 0, Ms); // x_0 lives in host slot 0
     StoreSpec none{};
@@ -470,10 +485,11 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       const int a = K * p.C, e = std::min(a + p.C, T);
       const bool keep = K + 1 < p.n_remote; // x_e is the next coarse checkpoint
       const int so = K & 1;
-      if (keep && stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
-      HIPCHK(c, launch_forward(n, a, e, K == 0 ? nullptr : stage + (size_t)((K - 1) & 1) * slot,
-                               keep ? stage + (size_t)so * slot : nullptr, none, c->readout, K == 0, s));
+      HIPCHK(c, launch_forward(n, a, e, c->cur_state, none, c->readout, K == 0, c->dubuf, s));
       if (keep) {
+        // snapshot x_e into a staging slot (D2D on the compute stream), then D2H on the side stream
+        if (stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
+        HIPCHK(c, hipMemcpyAsync(stage + (size_t)so * slot, c->cur_state, Ms, hipMemcpyDeviceToDevice, s));
         HIPCHK(c, hipEventRecord(ev_stage_ready[so], s));
         HIPCHK(c, hipStreamWaitEvent(cs, ev_stage_ready[so], 0));
         HIPCHK(c, hipMemcpyAsync(c->host_ckpt + (size_t)(K + 1) * slot, stage + (size_t)so * slot, Ms, hipMemcpyDeviceToHost, cs));
@@ -482,7 +498,6 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         st.n_d2h++; st.d2h_bytes += (int64_t)Ms;
       }
     }
-    // x_0 counts as a write of the paper's N_c (it is a host-side memset here, no transfer)
   }
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));

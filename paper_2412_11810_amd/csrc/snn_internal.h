@@ -47,10 +47,18 @@ struct LaunchCfg {
 hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
                               hipStream_t s);
 // Forward pass over steps t0+1..t1 for all batch elements (gather, LIF update, threshold, compaction,
-// readout), time loop on the device.
-hipError_t launch_forward(const NetDev &net, int t0, int t1, const float *state_in,
-                          float *state_out, const StoreSpec &st, double *readout /*[B][2][O]*/,
-                          int readout_init, hipStream_t s);
+// readout).  state: [B][SN], x_{t0} on entry, x_{t1} on return.  work: scratch of
+// SNN_FWD_TILE * B * (max_l N_l + n_out) floats.
+#define SNN_FWD_TILE 64
+hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st,
+                          double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s);
+// Arguments of the parallel current kernel (see k_currents).
+struct CurArgs {
+  int mode, lsel;
+  float *out;
+  size_t slot_stride; // mode 0 only
+  int reserved;
+};
 // Recompute pass over steps t0+1..t1 from state_in = x_{t0}, spikes read from the stored bitmasks:
 // currents of the whole range in parallel into buf (slot of x_t = t - t_base - 1), then a scan that
 // turns them into states in place (store_all) and/or writes x_{t1} to state_out.

@@ -97,212 +97,8 @@ static __device__ __forceinline__ void gather2(const float *__restrict__ Wcat, i
   }
 }
 
-// Owner threads turn the bit words of one layer into the ascending list of active indices
-// (popcount prefix over the words, then the rank of the own bit inside its word).
-static __device__ __forceinline__ void expand_owner(const uint64_t *words, int Wd, uint16_t *list, int *cnt,
-                                                    int tid, int nt, int npt) {
-  for (int k = 0; k < npt; ++k) {
-    const int widx = (tid >> 6) + k * (nt >> 6);
-    if (widx >= Wd) break;
-    const uint64_t word = words[widx];
-    int pre = 0;
-    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
-    if ((word >> lane_id()) & 1ull) list[pre + __popcll(word & lanemask_lt())] = (uint16_t)(widx * WAVE + lane_id());
-    if (widx == Wd - 1 && lane_id() == 0) *cnt = pre + __popcll(word);
-  }
-}
-
-template <int NPT>
-__global__ void __launch_bounds__(576)
-k_forward(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *__restrict__ state_out,
-          StoreSpec st, double *__restrict__ readout, int readout_init, int nt) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, b = blockIdx.x, lane = lane_id();
-  const int L = net.L, B = net.B, O = net.n_out;
-  const bool service = tid >= nt; // the last wave owns no neurons: input lists + readout
-
-  // ---- LDS carve-up -------------------------------------------------------------------
-  int wdmax = 1;
-  for (int l = 1; l <= L; ++l) wdmax = net.Wd[l] > wdmax ? net.Wd[l] : wdmax;
-  uint64_t *words = (uint64_t *)smem;                         // [L+1][wdmax] (row 0 unused)
-  // readout state in fp64: ubar feeds a softmax, which turns an absolute error of ubar into a
-  // relative error of the loss gradient, and fp32 sums over thousands of steps lose ~1e-4 there
-  double *u = (double *)(words + (size_t)(L + 1) * wdmax);   // [O]
-  double *usum = u + O;                                       // [O]
-  int *cnt = (int *)(usum + O);                               // [8]
-  uint16_t *lists = (uint16_t *)(cnt + 8);
-  int lo[SNN_MAXL + 2];
-  lo[0] = 0;
-  lo[1] = (net.n_in + 7) & ~7;
-  for (int l = 1; l <= L; ++l) lo[l + 1] = lo[l] + ((net.N[l - 1] + 7) & ~7);
-
-  // ---- initial condition at t0 ---------------------------------------------------------
-  float v[SNN_MAXL][NPT];
-  uint32_t sp[SNN_MAXL]; // bit k: own neuron k of that layer spiked at the previous step
-#pragma unroll
-  for (int l = 0; l < SNN_MAXL; ++l) {
-    sp[l] = 0;
-#pragma unroll
-    for (int k = 0; k < NPT; ++k) v[l][k] = 0.0f;
-  }
-  if (!service) {
-#pragma unroll
-    for (int l = 0; l < SNN_MAXL; ++l) {
-      if (l >= L) break;
-      const int N = net.N[l];
-      const uint64_t *mrow = net.mask[l + 1] + ((size_t)t0 * B + b) * net.Wd[l + 1];
-#pragma unroll
-      for (int k = 0; k < NPT; ++k) {
-        const int n = tid + k * nt;
-        const int widx = n >> 6;
-        if (widx < net.Wd[l + 1]) {
-          const uint64_t word = mrow[widx];
-          if (lane == 0) words[(size_t)(l + 1) * wdmax + widx] = word;
-          if ((word >> lane) & 1ull) sp[l] |= 1u << k;
-        }
-        if (state_in && n < N) v[l][k] = state_in[(size_t)b * net.SN + net.off[l] + n];
-      }
-    }
-  } else {
-    for (int o = lane; o < O; o += WAVE) {
-      u[o] = readout_init ? 0.0 : readout[((size_t)b * 2 + 0) * O + o];
-      usum[o] = readout_init ? 0.0 : readout[((size_t)b * 2 + 1) * O + o];
-    }
-  }
-  __syncthreads();
-  uint64_t in_word = 0; // service wave: lane w holds word w of the next step's input spikes
-  if (!service) {
-    for (int l = 0; l < L; ++l)
-      expand_owner(words + (size_t)(l + 1) * wdmax, net.Wd[l + 1], lists + lo[l + 1], &cnt[l + 1], tid, nt, NPT);
-  } else {
-    if (t0 + 1 <= t1 && lane < net.Wd[0]) in_word = net.mask[0][((size_t)(t0 + 1) * B + b) * net.Wd[0] + lane];
-    int pre = 0;
-    for (int w = 0; w < net.Wd[0]; ++w) {
-      const uint32_t wl = __builtin_amdgcn_readlane((uint32_t)in_word, w);
-      const uint32_t wh = __builtin_amdgcn_readlane((uint32_t)(in_word >> 32), w);
-      const uint64_t word = ((uint64_t)wh << 32) | wl;
-      if ((word >> lane) & 1ull) lists[pre + __popcll(word & lanemask_lt())] = (uint16_t)(w * WAVE + lane);
-      pre += __popcll(word);
-    }
-    if (lane == 0) cnt[0] = pre;
-  }
-  __syncthreads();
-
-  // ---- time loop ------------------------------------------------------------------------
-  for (int t = t0 + 1; t <= t1; ++t) {
-    int store_slot = -1;
-    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
-      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
-
-    if (service) {
-      // readout of the previous step (its last-layer list is complete), then prefetch inputs
-      if (t > t0 + 1) {
-        for (int o0 = 0; o0 < O; o0 += WAVE) {
-          float acc[1], unused[1];
-          gather2<1>(net.W_out, O, 0u, o0 + lane, WAVE, lists + lo[L], cnt[L], lists, 0, acc, unused);
-          const int o = o0 + lane;
-          if (o < O) {
-            const double un = (double)net.beta * u[o] + (double)acc[0];
-            u[o] = un;
-            usum[o] = usum[o] + un;
-          }
-        }
-      }
-      in_word = 0;
-      if (t + 1 <= t1 && lane < net.Wd[0]) in_word = net.mask[0][((size_t)(t + 1) * B + b) * net.Wd[0] + lane];
-    }
-
-#pragma unroll
-    for (int l = 0; l < SNN_MAXL; ++l) {
-      if (l >= L) break;
-      const int N = net.N[l];
-      uint64_t *wl_ = words + (size_t)(l + 1) * wdmax;
-      if (!service) {
-        // ---- phase 1: gather the rows of active presynaptic neurons, LIF update, threshold
-        float a_in[NPT], a_rec[NPT];
-        gather2<NPT>(net.W_in[l], N, (uint32_t)(l == 0 ? net.n_in : net.N[l - 1]), tid, nt, lists + lo[l], cnt[l],
-                     lists + lo[l + 1], cnt[l + 1], a_in, a_rec);
-        uint64_t *mrow = net.mask[l + 1] + ((size_t)t * B + b) * net.Wd[l + 1];
-        uint32_t spn = 0;
-#pragma unroll
-        for (int k = 0; k < NPT; ++k) {
-          const int n = tid + k * nt;
-          const int widx = n >> 6;
-          if (widx < net.Wd[l + 1]) { // uniform per wave
-            float a = net.alpha * v[l][k];
-            if ((sp[l] >> k) & 1u) a = a - net.theta;
-            const float vn = n < N ? a + (a_in[k] + a_rec[k]) : 0.0f;
-            v[l][k] = vn;
-            const uint64_t word = __ballot(n < N && vn > net.theta);
-            if (lane == 0) {
-              mrow[widx] = word;
-              wl_[widx] = word;
-            }
-            if ((word >> lane) & 1ull) spn |= 1u << k;
-            if (store_slot >= 0 && n < N)
-              st.base[(size_t)store_slot * st.slot_stride + (size_t)b * net.SN + net.off[l] + n] = vn;
-          }
-        }
-        sp[l] = spn;
-      }
-      __syncthreads();
-      // ---- phase 2: compaction of this layer's new spikes into the active-index list
-      if (!service) {
-        expand_owner(wl_, net.Wd[l + 1], lists + lo[l + 1], &cnt[l + 1], tid, nt, NPT);
-      } else if (l == L - 1) {
-        int pre = 0;
-        for (int w = 0; w < net.Wd[0]; ++w) {
-          const uint32_t wlo = __builtin_amdgcn_readlane((uint32_t)in_word, w);
-          const uint32_t whi = __builtin_amdgcn_readlane((uint32_t)(in_word >> 32), w);
-          const uint64_t word = ((uint64_t)whi << 32) | wlo;
-          if ((word >> lane) & 1ull) lists[pre + __popcll(word & lanemask_lt())] = (uint16_t)(w * WAVE + lane);
-          pre += __popcll(word);
-        }
-        if (lane == 0) cnt[0] = pre;
-      }
-      __syncthreads();
-    }
-  }
-
-  // ---- epilogue: last readout, final state, readout state ---------------------------------
-  if (service) {
-    if (t1 > t0) {
-      for (int o0 = 0; o0 < O; o0 += WAVE) {
-        float acc[1], unused[1];
-        gather2<1>(net.W_out, O, 0u, o0 + lane, WAVE, lists + lo[L], cnt[L], lists, 0, acc, unused);
-        const int o = o0 + lane;
-        if (o < O) {
-          const double un = (double)net.beta * u[o] + (double)acc[0];
-          u[o] = un;
-          usum[o] = usum[o] + un;
-        }
-      }
-    }
-    for (int o = lane; o < O; o += WAVE) {
-      readout[((size_t)b * 2 + 0) * O + o] = u[o];
-      readout[((size_t)b * 2 + 1) * O + o] = usum[o];
-    }
-  } else if (state_out) {
-#pragma unroll
-    for (int l = 0; l < SNN_MAXL; ++l) {
-      if (l >= L) break;
-#pragma unroll
-      for (int k = 0; k < NPT; ++k) {
-        const int n = tid + k * nt;
-        if (n < net.N[l]) state_out[(size_t)b * net.SN + net.off[l] + n] = v[l][k];
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// B1 (recompute), part 1: synaptic currents of a whole chunk, parallel over time.
-// A recompute pass reads the stored spikes instead of generating them, so nothing in it depends on
-// the threshold: the currents I_t = I_in,t + I_rec,t of every (t, b, layer) of a chunk are
-// independent gathers.  One workgroup per (t, b, layer) expands the two stored bit rows into index
-// lists and runs the same gather as the forward pass; the result lands in the chunk buffer at the
-// slot of x_t.  Part 2 (k_scan) then turns currents into states in place.
-// ------------------------------------------------------------------------------------------
+// Turns the bit words of one spike row into the ascending list of active indices: popcount prefix
+// over the words, then the rank of the own bit inside its word (A1, second half).
 static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd, uint16_t *list, int *cnt, int tid,
                                                   int nt) {
   for (int widx = tid >> 6; widx < Wd; widx += nt >> 6) {
@@ -314,35 +110,217 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Forward pass.  The time axis is cut into tiles; inside a tile the layers run one after the other:
+//   1. k_currents (mode 1): feed-forward currents I_in^l of every step of the tile, in parallel -- they
+//      depend only on the spikes of the layer below, which are complete for the tile;
+//   2. k_layer_seq_*: the only sequential part, one workgroup per batch element looping over the
+//      steps of the tile: recurrent current, LIF update, threshold, ballot -> stored spike words;
+//   3. after the last layer, k_currents (mode 2) + k_readout_scan for the leaky readout.
+// v^l_t = (alpha v^l_{t-1} - theta s^l_{t-1}) + (I_in + I_rec): same operations, same order, as the
+// definition, so spike trains match a plain sequential implementation bit for bit.
+// ------------------------------------------------------------------------------------------
+
+// Sequential part, layers of up to NW neurons: the recurrent matrix stays in registers (thread i keeps
+// column i, W_rec[0..NW)[i]); the previous step's spikes are broadcast from LDS as 0.0f/1.0f and
+// I_rec = fma(s_j, w_j, I_rec) runs over ascending j: fma(1, w, a) = a + w rounded once and
+// fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  One barrier per step.
+template <int NW>
+__global__ void __launch_bounds__(256)
+k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, StoreSpec st,
+               const float *__restrict__ iin, int t_tile) {
+  __shared__ __align__(16) float sf[2][NW];
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
+  const int b = blockIdx.x, i = threadIdx.x, lane = lane_id(), wave = i >> 6;
+  const bool own = i < N;
+  float w[NW];
+#pragma unroll
+  for (int q = 0; q < NW; ++q) w[q] = (own && q < N) ? net.W_rec[l][(size_t)q * N + i] : 0.0f;
+  float v = own ? state[(size_t)b * SN + off + i] : 0.0f;
+  uint64_t *mrow = net.mask[l + 1] + (size_t)b * Wd + wave;
+  const size_t mstride = (size_t)B * Wd;
+  bool sprev = false;
+  if (wave < Wd) sprev = (mrow[(size_t)t0 * mstride] >> lane) & 1ull;
+  for (int q = i; q < NW; q += blockDim.x) { sf[0][q] = 0.0f; sf[1][q] = 0.0f; }
+  __syncthreads();
+  sf[0][i] = sprev ? 1.0f : 0.0f;
+  __syncthreads();
+  int cur = 0;
+  const float *icol = iin + (size_t)b * N + i;
+  const size_t istride = (size_t)B * N;
+  float in_next = (own && t1 > t0) ? icol[(size_t)(t0 - t_tile) * istride] : 0.0f;
+  for (int t = t0 + 1; t <= t1; ++t) {
+    const float in_t = in_next;
+    if (own && t < t1) in_next = icol[(size_t)(t - t_tile) * istride]; // next step's current, in flight
+    const float4 *sv = reinterpret_cast<const float4 *>(sf[cur]);
+    float acc = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NW / 4; ++q) {
+      const float4 x = sv[q];
+      acc = fmaf(x.x, w[4 * q + 0], acc);
+      acc = fmaf(x.y, w[4 * q + 1], acc);
+      acc = fmaf(x.z, w[4 * q + 2], acc);
+      acc = fmaf(x.w, w[4 * q + 3], acc);
+    }
+    float a = net.alpha * v;
+    if (sprev) a = a - net.theta;
+    v = a + (in_t + acc);
+    sprev = own && v > net.theta;
+    const uint64_t word = __ballot(sprev);
+    if (lane == 0 && wave < Wd) mrow[(size_t)t * mstride] = word;
+    sf[cur ^ 1][i] = sprev ? 1.0f : 0.0f;
+    if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
+      st.base[(size_t)((t - st.t_base) / st.interval - 1 + st.slot0) * st.slot_stride + (size_t)b * SN + off + i] = v;
+    __syncthreads();
+    cur ^= 1;
+  }
+  if (own) state[(size_t)b * SN + off + i] = v;
+}
+
+// Sequential part, any layer width: event-driven.  The layer's spikes of the previous step are kept
+// as an ascending index list in LDS (ballot words -> popcount prefix -> list) and only the weight
+// rows of those neurons are gathered.  NPT neurons per thread; two barriers per step.
 template <int NPT>
 __global__ void __launch_bounds__(512)
-k_currents(NetDev net, int t0, float *__restrict__ buf, int t_base, size_t slot_stride) {
+k_layer_seq_gather(NetDev net, int l, int t0, int t1, float *__restrict__ state, StoreSpec st,
+                   const float *__restrict__ iin, int t_tile) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int l = blockIdx.y, B = net.B;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
+  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
+  uint64_t *words = (uint64_t *)smem;       // [Wd]
+  int *cnt = (int *)(words + Wd);           // [1] (+3 pad)
+  uint16_t *list = (uint16_t *)(cnt + 4);   // [N]
+  uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
+  const size_t mstride = (size_t)B * Wd;
+  float v[NPT];
+  uint32_t sp = 0;
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    const int n = tid + k * nt, widx = n >> 6;
+    v[k] = n < N ? state[(size_t)b * SN + off + n] : 0.0f;
+    if (widx < Wd) {
+      const uint64_t word = mbase[(size_t)t0 * mstride + widx];
+      if (lane == 0) words[widx] = word;
+      if ((word >> lane) & 1ull) sp |= 1u << k;
+    }
+  }
+  if (tid == 0) *cnt = 0;
+  __syncthreads();
+  expand_all(words, Wd, list, cnt, tid, nt);
+  __syncthreads();
+  const size_t istride = (size_t)B * N;
+  for (int t = t0 + 1; t <= t1; ++t) {
+    int store_slot = -1;
+    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
+      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
+    const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N;
+    float in_t[NPT];
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      const int n = tid + k * nt;
+      in_t[k] = n < N ? irow[n] : 0.0f;
+    }
+    float unused[NPT], a_rec[NPT];
+    gather2<NPT>(net.W_rec[l], N, 0u, tid, nt, list, 0, list, *cnt, unused, a_rec);
+    uint32_t spn = 0;
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      const int n = tid + k * nt, widx = n >> 6;
+      if (widx < Wd) { // uniform per wave
+        float a = net.alpha * v[k];
+        if ((sp >> k) & 1u) a = a - net.theta;
+        const float vn = n < N ? a + (in_t[k] + a_rec[k]) : 0.0f;
+        v[k] = vn;
+        const uint64_t word = __ballot(n < N && vn > net.theta);
+        if ((word >> lane) & 1ull) spn |= 1u << k;
+        if (store_slot >= 0 && n < N)
+          st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + n] = vn;
+        if (lane == 0) { // the words are only read by the list expansion, after the barrier
+          words[widx] = word;
+          mbase[(size_t)t * mstride + widx] = word;
+        }
+      }
+    }
+    sp = spn;
+    __syncthreads(); // every wave is done with the old list
+    expand_all(words, Wd, list, cnt, tid, nt);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    const int n = tid + k * nt;
+    if (n < N) state[(size_t)b * SN + off + n] = v[k];
+  }
+}
+
+// A4: u_t = beta u_{t-1} + I_out,t ; usum += u_t over the steps of a tile (fp64 state: ubar feeds a
+// softmax, which turns an absolute error of ubar into a relative error of the loss gradient).
+__global__ void __launch_bounds__(256)
+k_readout_scan(const float *__restrict__ iout, double *__restrict__ readout, int B, int O, int nsteps, float beta,
+               int init) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * O) return;
+  const int b = i / O, o = i % O;
+  double u = init ? 0.0 : readout[((size_t)b * 2 + 0) * O + o];
+  double us = init ? 0.0 : readout[((size_t)b * 2 + 1) * O + o];
+  for (int k = 0; k < nsteps; ++k) {
+    u = (double)beta * u + (double)iout[(size_t)k * B * O + i];
+    us = us + u;
+  }
+  readout[((size_t)b * 2 + 0) * O + o] = u;
+  readout[((size_t)b * 2 + 1) * O + o] = us;
+}
+
+// ------------------------------------------------------------------------------------------
+// B1 (recompute), part 1: synaptic currents of a whole chunk, parallel over time.
+// A recompute pass reads the stored spikes instead of generating them, so nothing in it depends on
+// the threshold: the currents I_t = I_in,t + I_rec,t of every (t, b, layer) of a chunk are
+// independent gathers.  One workgroup per (t, b, layer) expands the two stored bit rows into index
+// lists and runs the same gather as the forward pass; the result lands in the chunk buffer at the
+// slot of x_t.  Part 2 (k_scan) then turns currents into states in place.
+// ------------------------------------------------------------------------------------------
+template <int NPT>
+__global__ void __launch_bounds__(512)
+k_currents(NetDev net, int t0, int t_base, CurArgs ca) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int tid = threadIdx.x, nt = blockDim.x, B = net.B;
   const int t = t0 + 1 + (int)(blockIdx.x / B), b = (int)(blockIdx.x % B);
-  const int N = net.N[l], P = l == 0 ? net.n_in : net.N[l - 1];
-  const int Wi = net.Wd[l], Wr = net.Wd[l + 1];
+  // mode 0: recompute, all layers (blockIdx.y), I_in + I_rec into the state slot of x_t
+  // mode 1: forward, feed-forward current I_in of layer ca.lsel into a [step][B][N] tile
+  // mode 2: forward, readout current sum of W_out rows of the last layer's spikes, [step][B][O] tile
+  const int l = ca.mode == 0 ? (int)blockIdx.y : ca.lsel;
+  int N, P, Wi, Wr;
+  const float *W;
+  const uint64_t *g_in, *g_rec = nullptr;
+  if (ca.mode == 2) {
+    N = net.n_out; P = net.N[net.L - 1]; Wi = net.Wd[net.L]; Wr = 0; W = net.W_out;
+    g_in = net.mask[net.L] + ((size_t)t * B + b) * Wi;
+  } else {
+    N = net.N[l]; P = l == 0 ? net.n_in : net.N[l - 1]; Wi = net.Wd[l]; Wr = ca.mode == 0 ? net.Wd[l + 1] : 0;
+    W = net.W_in[l];
+    g_in = net.mask[l] + ((size_t)t * B + b) * Wi;
+    g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * net.Wd[l + 1];
+  }
   uint64_t *w_in = (uint64_t *)smem;       // [Wi]
   uint64_t *w_rec = w_in + Wi;             // [Wr]
   int *cnt = (int *)(w_rec + Wr);          // [2] (+2 pad)
   uint16_t *l_in = (uint16_t *)(cnt + 4);  // [P rounded up to 8]
   uint16_t *l_rec = l_in + ((P + 7) & ~7); // [N]
-  const uint64_t *g_in = net.mask[l] + ((size_t)t * B + b) * Wi;
-  const uint64_t *g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * Wr;
   for (int i = tid; i < Wi; i += nt) w_in[i] = g_in[i];
   for (int i = tid; i < Wr; i += nt) w_rec[i] = g_rec[i];
+  if (tid < 2) cnt[tid] = 0;
   __syncthreads();
   expand_all(w_in, Wi, l_in, &cnt[0], tid, nt);
   expand_all(w_rec, Wr, l_rec, &cnt[1], tid, nt);
   __syncthreads();
   float a_in[NPT], a_rec[NPT];
-  gather2<NPT>(net.W_in[l], N, (uint32_t)P, tid, nt, l_in, cnt[0], l_rec, cnt[1], a_in, a_rec);
-  float *dst = buf + (size_t)(t - t_base - 1) * slot_stride + (size_t)b * net.SN + net.off[l];
+  gather2<NPT>(W, N, (uint32_t)P, tid, nt, l_in, cnt[0], l_rec, cnt[1], a_in, a_rec);
+  float *dst = ca.mode == 0 ? ca.out + (size_t)(t - t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
+                            : ca.out + ((size_t)(t - t_base - 1) * B + b) * N;
 #pragma unroll
   for (int k = 0; k < NPT; ++k) {
     const int n = tid + k * nt;
-    if (n < N) dst[n] = a_in[k] + a_rec[k];
+    if (n < N) dst[n] = ca.mode == 0 ? a_in[k] + a_rec[k] : a_in[k];
   }
 }
 
@@ -841,7 +819,7 @@ static LaunchCfg forward_cfg(const NetDev &net) {
     wdmax = net.Wd[l + 1] > wdmax ? net.Wd[l + 1] : wdmax;
     lists += (size_t)((net.N[l] + 7) & ~7);
   }
-  c.lds_bytes = (size_t)(net.L + 1) * wdmax * 8 + (size_t)net.n_out * 16 + 32 + lists * 2;
+  c.lds_bytes = (size_t)wdmax * 8 + 16 + lists * 2;
   return c;
 }
 
@@ -851,43 +829,13 @@ static size_t adjoint_lds(const NetDev &net, int nt) {
   return nmax <= 256 ? 0 : ((size_t)2 * nmax + nt) * sizeof(float);
 }
 
-static size_t currents_lds(const NetDev &net);
-bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
-  const LaunchCfg c = forward_cfg(net);
-  const size_t lds_max = 64 * 1024; // per-workgroup limit without opting in to more
-  if (c.nt_neuron > 512 || c.nt_neuron * c.npt < 1) { snprintf(why, why_len, "layer too wide for the forward kernel"); return false; }
-  for (int l = 0; l < net.L; ++l)
-    if ((net.N[l] + c.npt - 1) / c.npt > c.nt_neuron) { snprintf(why, why_len, "layer too wide for the forward kernel (max %d neurons)", 512 * 16); return false; }
-  if (net.Wd[0] > WAVE) { snprintf(why, why_len, "n_in > 4096 not supported"); return false; }
-  if (c.lds_bytes > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", c.lds_bytes, lds_max); return false; }
-  if (currents_lds(net) > lds_max) { snprintf(why, why_len, "recompute kernel needs %zu B of LDS (> %zu)", currents_lds(net), lds_max); return false; }
-  if (adjoint_lds(net, 1024) > lds_max) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
-  return true;
-}
-
-hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
-                              hipStream_t s) {
-  if (T <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_pack_inputs, dim3((unsigned)((size_t)T * B)), dim3(WAVE), 0, s, in_spikes, mask0, B, n_in, Wd0);
-  return hipGetLastError();
-}
-
-hipError_t launch_forward(const NetDev &net, int t0, int t1, const float *state_in, float *state_out,
-                          const StoreSpec &st, double *readout, int readout_init, hipStream_t s) {
-  if (t1 < t0) return hipErrorInvalidValue;
-  const LaunchCfg c = forward_cfg(net);
-  const dim3 grid(net.B), block(c.nt_neuron + WAVE);
-#define FWD_CASE(NPT_)                                                                                       \
-  case NPT_:                                                                                                  \
-    hipLaunchKernelGGL((k_forward<NPT_>), grid, block, c.lds_bytes, s, net, t0, t1, state_in, state_out, st, \
-                       readout, readout_init, c.nt_neuron);                                                   \
-    break;
-  switch (c.npt) {
-    FWD_CASE(1) FWD_CASE(2) FWD_CASE(4) FWD_CASE(8) FWD_CASE(16)
-    default: return hipErrorInvalidValue;
+static size_t seq_gather_lds(const NetDev &net) {
+  size_t mx = 0;
+  for (int l = 0; l < net.L; ++l) {
+    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)((net.N[l] + 7) & ~7) * 2;
+    mx = b > mx ? b : mx;
   }
-#undef FWD_CASE
-  return hipGetLastError();
+  return mx;
 }
 
 static size_t currents_lds(const NetDev &net) {
@@ -900,22 +848,98 @@ static size_t currents_lds(const NetDev &net) {
   return mx;
 }
 
+bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
+  const LaunchCfg c = forward_cfg(net);
+  const size_t lds_max = 64 * 1024; // per-workgroup limit without opting in to more
+  if (c.nt_neuron > 512 || c.nt_neuron * c.npt < 1) { snprintf(why, why_len, "layer too wide for the forward kernel"); return false; }
+  for (int l = 0; l < net.L; ++l)
+    if ((net.N[l] + c.npt - 1) / c.npt > c.nt_neuron) { snprintf(why, why_len, "layer too wide for the forward kernel (max %d neurons)", 512 * 16); return false; }
+  if (net.Wd[0] > WAVE) { snprintf(why, why_len, "n_in > 4096 not supported"); return false; }
+  if (c.lds_bytes > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", c.lds_bytes, lds_max); return false; }
+  if (seq_gather_lds(net) > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", seq_gather_lds(net), lds_max); return false; }
+  if (currents_lds(net) > lds_max) { snprintf(why, why_len, "recompute kernel needs %zu B of LDS (> %zu)", currents_lds(net), lds_max); return false; }
+  if (adjoint_lds(net, 1024) > lds_max) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
+  return true;
+}
+
+hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
+                              hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_pack_inputs, dim3((unsigned)((size_t)T * B)), dim3(WAVE), 0, s, in_spikes, mask0, B, n_in, Wd0);
+  return hipGetLastError();
+}
+
+template <int NPT>
+static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, int t0, int t_base, const CurArgs &ca,
+                              hipStream_t s) {
+  hipLaunchKernelGGL((k_currents<NPT>), grid, dim3(nt), lds, s, net, t0, t_base, ca);
+}
+static hipError_t launch_currents(const NetDev &net, int t0, int t1, int t_base, const CurArgs &ca, hipStream_t s) {
+  const LaunchCfg c = forward_cfg(net);
+  const dim3 grid((unsigned)((size_t)(t1 - t0) * net.B), ca.mode == 0 ? net.L : 1);
+  const size_t lds = currents_lds(net);
+  switch (c.npt) {
+    case 1: launch_currents_t<1>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    case 2: launch_currents_t<2>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    case 4: launch_currents_t<4>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    case 8: launch_currents_t<8>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    case 16: launch_currents_t<16>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st, double *readout,
+                          int readout_init, float *work, hipStream_t s) {
+  if (t1 < t0) return hipErrorInvalidValue;
+  const int B = net.B, O = net.n_out, L = net.L;
+  int nmax = 0;
+  for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
+  float *iin = work;                                          // [tile][B][N_l] of the layer being run
+  float *iout = work + (size_t)SNN_FWD_TILE * B * nmax;       // [tile][B][O]
+  const LaunchCfg c = forward_cfg(net);
+  bool first = true;
+  for (int ta = t0; ta < t1; ta += SNN_FWD_TILE) {
+    const int tb = ta + SNN_FWD_TILE < t1 ? ta + SNN_FWD_TILE : t1;
+    for (int l = 0; l < L; ++l) {
+      const int N = net.N[l];
+      CurArgs ca{1, l, iin, 0, 0};
+      hipError_t e = launch_currents(net, ta, tb, ta, ca, s);
+      if (e != hipSuccess) return e;
+      if (N <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B), dim3(64), 0, s, net, l, ta, tb, state, st, iin, ta);
+      else if (N <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B), dim3(128), 0, s, net, l, ta, tb, state, st, iin, ta);
+      else if (N <= 256) hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B), dim3(256), 0, s, net, l, ta, tb, state, st, iin, ta);
+      else {
+        const size_t lds = seq_gather_lds(net);
+        const dim3 grid(B), block(c.nt_neuron);
+#define SEQ_CASE(NPT_)                                                                                              \
+  case NPT_:                                                                                                         \
+    hipLaunchKernelGGL((k_layer_seq_gather<NPT_>), grid, block, lds, s, net, l, ta, tb, state, st, iin, ta);        \
+    break;
+        switch (c.npt) {
+          SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
+          default: return hipErrorInvalidValue;
+        }
+#undef SEQ_CASE
+      }
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    CurArgs co{2, L, iout, 0, 0};
+    hipError_t e = launch_currents(net, ta, tb, ta, co, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O, tb - ta, net.beta,
+                       (first && readout_init) ? 1 : 0);
+    first = false;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
   if (t1 <= t0) return hipErrorInvalidValue;
-  const LaunchCfg c = forward_cfg(net);
-  const dim3 grid((unsigned)((size_t)(t1 - t0) * net.B), net.L), block(c.nt_neuron);
-  const size_t lds = currents_lds(net);
-#define CUR_CASE(NPT_)                                                                                         \
-  case NPT_:                                                                                                    \
-    hipLaunchKernelGGL((k_currents<NPT_>), grid, block, lds, s, net, t0, buf, t_base, slot_stride);            \
-    break;
-  switch (c.npt) {
-    CUR_CASE(1) CUR_CASE(2) CUR_CASE(4) CUR_CASE(8) CUR_CASE(16)
-    default: return hipErrorInvalidValue;
-  }
-#undef CUR_CASE
-  hipError_t e = hipGetLastError();
+  CurArgs ca{0, 0, buf, slot_stride, 0};
+  hipError_t e = launch_currents(net, t0, t1, t_base, ca, s);
   if (e != hipSuccess) return e;
   const size_t n = (size_t)net.B * net.SN;
   hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
