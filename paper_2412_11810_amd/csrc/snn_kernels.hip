@@ -122,14 +122,17 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
 // ------------------------------------------------------------------------------------------
 
 // Sequential part, layers of up to NW neurons: the recurrent matrix stays in registers (thread i keeps
-// column i, W_rec[0..NW)[i]); the previous step's spikes are broadcast from LDS as 0.0f/1.0f and
-// I_rec = fma(s_j, w_j, I_rec) runs over ascending j: fma(1, w, a) = a + w rounded once and
-// fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  One barrier per step.
+// column i, W_rec[0..NW)[i]).  The previous step's spike words are shared through LDS; each lane turns
+// its own bit of every word into 0.0f/1.0f, v_readlane broadcasts spike j through a scalar register
+// and I_rec = fma(s_j, w_j, I_rec) runs over ascending j: fma(1, w, a) = a + w rounded once and
+// fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  Two instructions per
+// presynaptic neuron, no memory traffic in the loop, one barrier per step.
 template <int NW>
 __global__ void __launch_bounds__(256)
 k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, StoreSpec st,
                const float *__restrict__ iin, int t_tile) {
-  __shared__ __align__(16) float sf[2][NW];
+  constexpr int NWD = NW / 64;
+  __shared__ uint64_t sw[2][NWD];
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
   const int b = blockIdx.x, i = threadIdx.x, lane = lane_id(), wave = i >> 6;
   const bool own = i < N;
@@ -139,12 +142,9 @@ k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, Sto
   float v = own ? state[(size_t)b * SN + off + i] : 0.0f;
   uint64_t *mrow = net.mask[l + 1] + (size_t)b * Wd + wave;
   const size_t mstride = (size_t)B * Wd;
-  bool sprev = false;
-  if (wave < Wd) sprev = (mrow[(size_t)t0 * mstride] >> lane) & 1ull;
-  for (int q = i; q < NW; q += blockDim.x) { sf[0][q] = 0.0f; sf[1][q] = 0.0f; }
+  if (i < NWD) sw[0][i] = i < Wd ? net.mask[l + 1][(size_t)t0 * mstride + (size_t)b * Wd + i] : 0ull;
   __syncthreads();
-  sf[0][i] = sprev ? 1.0f : 0.0f;
-  __syncthreads();
+  bool sprev = (sw[0][wave] >> lane) & 1ull;
   int cur = 0;
   const float *icol = iin + (size_t)b * N + i;
   const size_t istride = (size_t)B * N;
@@ -152,23 +152,28 @@ k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, Sto
   for (int t = t0 + 1; t <= t1; ++t) {
     const float in_t = in_next;
     if (own && t < t1) in_next = icol[(size_t)(t - t_tile) * istride]; // next step's current, in flight
-    const float4 *sv = reinterpret_cast<const float4 *>(sf[cur]);
+    int sbits[NWD]; // lane j%64 of sbits[j/64] holds spike j of the previous step as a float
+#pragma unroll
+    for (int q = 0; q < NWD; ++q) sbits[q] = ((sw[cur][q] >> lane) & 1ull) ? 0x3f800000 : 0;
     float acc = 0.0f;
 #pragma unroll
-    for (int q = 0; q < NW / 4; ++q) {
-      const float4 x = sv[q];
-      acc = fmaf(x.x, w[4 * q + 0], acc);
-      acc = fmaf(x.y, w[4 * q + 1], acc);
-      acc = fmaf(x.z, w[4 * q + 2], acc);
-      acc = fmaf(x.w, w[4 * q + 3], acc);
+    for (int j0 = 0; j0 < NW; j0 += 16) { // 16 broadcasts, then 16 dependent fmas: no scalar-write stalls
+      float sj[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        sj[r] = __int_as_float(__builtin_amdgcn_readlane(sbits[(j0 + r) >> 6], (j0 + r) & 63));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc = fmaf(sj[r], w[j0 + r], acc);
     }
     float a = net.alpha * v;
     if (sprev) a = a - net.theta;
     v = a + (in_t + acc);
     sprev = own && v > net.theta;
     const uint64_t word = __ballot(sprev);
-    if (lane == 0 && wave < Wd) mrow[(size_t)t * mstride] = word;
-    sf[cur ^ 1][i] = sprev ? 1.0f : 0.0f;
+    if (lane == 0) {
+      sw[cur ^ 1][wave] = word;
+      if (wave < Wd) mrow[(size_t)t * mstride] = word;
+    }
     if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
       st.base[(size_t)((t - st.t_base) / st.interval - 1 + st.slot0) * st.slot_stride + (size_t)b * SN + off + i] = v;
     __syncthreads();
