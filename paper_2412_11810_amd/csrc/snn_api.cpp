@@ -36,6 +36,11 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
+  struct GraphKeyT { int strategy, T, C, F; void *arena, *work, *host; bool dw_event; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event; } };
+  GraphKeyT graph_key{};
+  hipGraphExec_t graph_exec = nullptr;
+  bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
+  bool own_stream = false;
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
@@ -145,6 +150,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   c->cfg = *cfg;
   fill_shape(*cfg, &c->net);
   if (const char *e = std::getenv("SNN_DW")) c->dw_event_driven = std::strcmp(e, "event") == 0;
+  if (const char *e = std::getenv("SNN_GRAPH")) c->graphs_enabled = std::strcmp(e, "0") != 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -152,6 +158,12 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (cfg->device < 0 || cfg->device >= ndev) return fail(c, SNN_E_INVAL, "no such device");
   HIPCHK(c, hipSetDevice(cfg->device));
   c->stream = (hipStream_t)cfg->stream;
+  if (!c->stream) {
+    // the legacy default stream cannot be recorded into a graph: work runs on a stream of the library's
+    // own; every entry point returns only after that stream has drained, so callers see no difference
+    HIPCHK(c, hipStreamCreateWithFlags(&c->stream, hipStreamNonBlocking));
+    c->own_stream = true;
+  }
   HIPCHK(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
   NetDev &n = c->net;
   const int L = n.L, B = n.B, O = n.n_out;
@@ -212,7 +224,9 @@ void snn_destroy(snn_ctx *c) {
   (void)hipFree(c->arena); (void)hipFree(c->dubuf);
   if (c->host_ckpt) (void)hipHostFree(c->host_ckpt);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+  if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  if (c->own_stream && c->stream) (void)hipStreamDestroy(c->stream);
   delete c;
 }
 
@@ -254,6 +268,9 @@ snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *
   if (!c || !in_spikes || !labels) return fail(c, SNN_E_INVAL, "null argument");
   if (T < 1 || T > c->cfg.T) return fail(c, SNN_E_INVAL, "T out of range for this context");
   HIPCHK(c, hipSetDevice(c->cfg.device));
+  // inputs may have been produced on the caller's default stream, which the library's own stream
+  // does not synchronise with implicitly
+  if (c->own_stream) HIPCHK(c, hipStreamSynchronize(nullptr));
   const NetDev &n = c->net;
   const size_t bytes = (size_t)T * n.B * n.n_in;
   const uint8_t *src = in_spikes;
@@ -398,88 +415,55 @@ struct Timer {
 };
 } // namespace
 
-snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_in, size_t budget, snn_stats *stats) {
-  if (!c) return SNN_E_INVAL;
-  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "snn_bptt needs inputs bound by snn_forward/snn_bind_inputs");
-  const int T = c->T_bound;
-  Plan p;
-  if (!snn_make_plan((int)strategy, T, C_in, F_in, &p)) return fail(c, SNN_E_INVAL, "invalid strategy/intervals");
+// Queues one whole training step on the context's streams; no host synchronisation inside, no
+// allocation, no hipMemsetAsync (fill kernels instead), so that the same code can be recorded into
+// a HIP graph.  The copy stream is forked from and joined back into the compute stream with events.
+static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &tm, hipEvent_t *ev_fwd_out) {
   NetDev &n = c->net;
-  const int B = n.B, O = n.n_out, L = n.L, SN = n.SN;
+  const int T = p.T, B = n.B, O = n.n_out, L = n.L, SN = n.SN;
+  const int strategy = p.strategy;
   const size_t Ms = c->Ms(), slot = (size_t)B * SN;
-  const size_t need_states = (size_t)p.local_slots() * Ms;
-  const size_t need_work = work_bytes(n, p.chunk_len);
-  const size_t need_spikes = spike_bytes(n, T);
-  if (budget && need_states + need_work + need_spikes > budget) {
-    char buf[200];
-    snprintf(buf, sizeof buf, "needs %zu B of HBM activation memory (%d state slots), budget is %zu B",
-             need_states + need_work + need_spikes, p.local_slots(), budget);
-    return fail(c, SNN_E_BUDGET, buf);
-  }
-  HIPCHK(c, hipSetDevice(c->cfg.device));
   hipStream_t s = c->stream, cs = c->copy_stream;
-  // ---- storage -----------------------------------------------------------------------------
-  if (c->arena_bytes < need_states) {
-    HIPCHK(c, hipStreamSynchronize(s));
-    if (c->arena) HIPCHK(c, hipFree(c->arena));
-    c->arena = nullptr; c->arena_bytes = 0;
-    HIPCHK(c, hipMalloc(&c->arena, need_states));
-    c->arena_bytes = need_states;
-  }
-  {
-    snn_status rs = ensure_work(c, need_work);
-    if (rs != SNN_OK) return rs;
-  }
-  const size_t need_host = (size_t)p.n_remote * Ms;
-  if (c->host_bytes < need_host) {
-    if (c->host_ckpt) HIPCHK(c, hipHostFree(c->host_ckpt));
-    c->host_ckpt = nullptr; c->host_bytes = 0;
-    if (hipHostMalloc(&c->host_ckpt, need_host, hipHostMallocDefault) != hipSuccess) {
-      (void)hipGetLastError();
-      return fail(c, SNN_E_HOSTMEM, "pinned host allocation for remote checkpoints failed");
-    }
-    c->host_bytes = need_host;
-  }
   float *chunk = c->arena;                                   // chunk buffer / trajectory
   float *lckpt = chunk + (size_t)p.chunk_len * slot;         // local checkpoints
   float *loadb = lckpt + (size_t)p.n_local_ckpt * slot;      // 2 slots receiving host checkpoints
   float *stage = loadb + (size_t)p.n_load_slots * slot;      // 2 slots staging D2H copies
 
-  Timer tm{c, stats != nullptr};
-  hipEvent_t ev_start = tm.mark();
-  if (!ev_start) return fail(c, SNN_E_HIP, "hipEventCreate failed");
-  snn_stats st{};
-  st.bytes_states = (int64_t)need_states; st.bytes_spikes = (int64_t)need_spikes; st.bytes_workspace = (int64_t)need_work;
-  st.bytes_host = (int64_t)need_host; st.local_state_slots = p.local_slots(); st.remote_state_slots = p.n_remote;
-
   for (int l = 0; l < L; ++l) {
-    HIPCHK(c, hipMemsetAsync(c->acc_in[l], 0, (size_t)pre_of(n, l) * n.N[l] * 8, s));
-    HIPCHK(c, hipMemsetAsync(c->acc_rec[l], 0, (size_t)n.N[l] * n.N[l] * 8, s));
+    HIPCHK(c, launch_fill_zero(c->acc_in[l], (size_t)pre_of(n, l) * n.N[l] * 8, s));
+    HIPCHK(c, launch_fill_zero(c->acc_rec[l], (size_t)n.N[l] * n.N[l] * 8, s));
   }
-  HIPCHK(c, hipMemsetAsync(c->acc_out, 0, (size_t)n.N[L - 1] * O * 8, s));
+  HIPCHK(c, launch_fill_zero(c->acc_out, (size_t)n.N[L - 1] * O * 8, s));
 
   // events for the host tier
   hipEvent_t ev_stage_ready[2] = {nullptr, nullptr}, ev_stage_free[2] = {nullptr, nullptr};
   hipEvent_t ev_load_ready[2] = {nullptr, nullptr}, ev_load_free[2] = {nullptr, nullptr};
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool stage_busy[2] = {false, false}, load_used[2] = {false, false};
   const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE;
-  if (remote)
+  if (remote) {
     for (int i = 0; i < 2; ++i) {
       ev_stage_ready[i] = tm.get(); ev_stage_free[i] = tm.get(); ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
       if (!ev_stage_ready[i] || !ev_stage_free[i] || !ev_load_ready[i] || !ev_load_free[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
     }
+    ev_fork = tm.get(); ev_join = tm.get();
+    if (!ev_fork || !ev_join) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+    // fork: everything the copy stream does in this step is ordered after this point
+    HIPCHK(c, hipEventRecord(ev_fork, s));
+    HIPCHK(c, hipStreamWaitEvent(cs, ev_fork, 0));
+  }
 
   // ---- forward ------------------------------------------------------------------------------
-  HIPCHK(c, hipMemsetAsync(c->cur_state, 0, Ms, s)); // x_0
+  HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk, slot, 0, 1, 0, T};
     HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
   } else if (strategy == SNN_CHUNK) {
-    HIPCHK(c, hipMemsetAsync(lckpt, 0, Ms, s)); // x_0
+    HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
     HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
   } else {
-    std::memset(c->host_ckpt, 0, Ms); // x_0 lives in host slot 0
+    // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again
     StoreSpec none{};
     for (int K = 0; K < p.n_remote; ++K) {
       const int a = K * p.C, e = std::min(a + p.C, T);
@@ -501,17 +485,14 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   }
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));
-  hipEvent_t ev_fwd = tm.mark();
+  if (ev_fwd_out) *ev_fwd_out = tm.mark();
 
   // ---- backward: walk the schedule ------------------------------------------------------------
   std::vector<SchedOp> ops((size_t)snn_make_schedule(p, nullptr, 0));
   snn_make_schedule(p, ops.data(), (int64_t)ops.size());
-  if (remote) {
-    // every checkpoint must be on the host before the first load
-    HIPCHK(c, hipStreamSynchronize(cs));
-  }
   int seg_start = 0, chunk_base = 0, cur_load = 0, n_loads = 0;
   bool first_adjoint = true;
+  // host->device loads run on the copy stream, behind every device->host copy of the forward pass
   auto issue_load = [&](int K, int slot_i) -> hipError_t {
     hipError_t e = hipSuccess;
     if (load_used[slot_i]) e = hipStreamWaitEvent(cs, ev_load_free[slot_i], 0);
@@ -527,7 +508,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       case OP_LOAD_REMOTE: {
         const int K = op.a / p.C;
         if (n_loads > 0) {
-          // the segment that used the other... previous slot is fully queued: mark it reusable
+          // the segment that used the previous slot is fully queued: mark that slot reusable
           HIPCHK(c, hipEventRecord(ev_load_free[cur_load], s));
           load_used[cur_load] = true;
         }
@@ -535,8 +516,8 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         seg_start = op.a;
         HIPCHK(c, hipStreamWaitEvent(s, ev_load_ready[cur_load], 0));
         ++n_loads;
-        // prefetch the next (earlier) coarse checkpoint into the other slot; that slot was last
-        // read by the segment before this one in execution order
+        // prefetch the next (earlier) coarse checkpoint into the other slot, overlapped with this
+        // segment's recomputation and backward pass
         if (K > 0) HIPCHK(c, issue_load(K - 1, (K - 1) & 1));
         break;
       }
@@ -601,13 +582,99 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     HIPCHK(c, launch_finish_grad(c->acc_rec[l], c->rec_mask[l], c->dW_rec[l], (size_t)n.N[l] * n.N[l], s));
   }
   HIPCHK(c, launch_finish_grad(c->acc_out, nullptr, c->dW_out, (size_t)n.N[L - 1] * O, s));
+  if (remote) { // join the copy stream back
+    HIPCHK(c, hipEventRecord(ev_join, cs));
+    HIPCHK(c, hipStreamWaitEvent(s, ev_join, 0));
+  }
+  return SNN_OK;
+}
+
+snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_in, size_t budget, snn_stats *stats) {
+  if (!c) return SNN_E_INVAL;
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "snn_bptt needs inputs bound by snn_forward/snn_bind_inputs");
+  const int T = c->T_bound;
+  Plan p;
+  if (!snn_make_plan((int)strategy, T, C_in, F_in, &p)) return fail(c, SNN_E_INVAL, "invalid strategy/intervals");
+  NetDev &n = c->net;
+  const int B = n.B, L = n.L;
+  const size_t Ms = c->Ms();
+  const size_t need_states = (size_t)p.local_slots() * Ms;
+  const size_t need_work = work_bytes(n, p.chunk_len);
+  const size_t need_spikes = spike_bytes(n, T);
+  if (budget && need_states + need_work + need_spikes > budget) {
+    char buf[200];
+    snprintf(buf, sizeof buf, "needs %zu B of HBM activation memory (%d state slots), budget is %zu B",
+             need_states + need_work + need_spikes, p.local_slots(), budget);
+    return fail(c, SNN_E_BUDGET, buf);
+  }
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  hipStream_t s = c->stream;
+  // ---- storage (before anything is queued or recorded) -----------------------------------------
+  if (c->arena_bytes < need_states) {
+    HIPCHK(c, hipStreamSynchronize(s));
+    if (c->arena) HIPCHK(c, hipFree(c->arena));
+    c->arena = nullptr; c->arena_bytes = 0;
+    HIPCHK(c, hipMalloc(&c->arena, need_states));
+    c->arena_bytes = need_states;
+  }
+  {
+    snn_status rs = ensure_work(c, need_work);
+    if (rs != SNN_OK) return rs;
+  }
+  const size_t need_host = (size_t)p.n_remote * Ms;
+  if (c->host_bytes < need_host) {
+    HIPCHK(c, hipStreamSynchronize(s));
+    if (c->host_ckpt) HIPCHK(c, hipHostFree(c->host_ckpt));
+    c->host_ckpt = nullptr; c->host_bytes = 0;
+    if (hipHostMalloc(&c->host_ckpt, need_host, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(c, SNN_E_HOSTMEM, "pinned host allocation for remote checkpoints failed");
+    }
+    c->host_bytes = need_host;
+  }
+  if (need_host) std::memset(c->host_ckpt, 0, Ms); // host slot 0 = x_0 (nothing is in flight here)
+
+  snn_stats st{};
+  st.bytes_states = (int64_t)need_states; st.bytes_spikes = (int64_t)need_spikes; st.bytes_workspace = (int64_t)need_work;
+  st.bytes_host = (int64_t)need_host; st.local_state_slots = p.local_slots(); st.remote_state_slots = p.n_remote;
+
+  // A step whose launches are recorded once and replayed as a HIP graph: the per-launch host cost
+  // (hundreds of small dependent kernels per step) disappears.  Used when no per-kernel timing is
+  // requested; the recording is redone whenever the plan or a buffer it refers to changes.
+  const bool use_graph = c->graphs_enabled && !stats;
+  if (use_graph) {
+    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven};
+    if (!c->graph_exec || !(key == c->graph_key)) {
+      if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
+      Timer tm{c, false};
+      snn_stats scratch{};
+      HIPCHK(c, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+      snn_status rs = enqueue_step(c, p, scratch, tm, nullptr);
+      hipGraph_t graph = nullptr;
+      hipError_t e = hipStreamEndCapture(s, &graph);
+      if (rs != SNN_OK) { if (graph) (void)hipGraphDestroy(graph); return rs; }
+      if (e != hipSuccess) return fail(c, SNN_E_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+      e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(graph);
+      if (e != hipSuccess) { c->graph_exec = nullptr; return fail(c, SNN_E_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e)); }
+      c->graph_key = key;
+    }
+    HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    return SNN_OK;
+  }
+
+  Timer tm{c, stats != nullptr};
+  hipEvent_t ev_start = tm.mark(), ev_fwd = nullptr;
+  if (!ev_start) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+  snn_status rs = enqueue_step(c, p, st, tm, &ev_fwd);
+  if (rs != SNN_OK) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamSynchronize(s); return rs; }
   hipEvent_t ev_end = tm.mark();
   if (stats) {
-    HIPCHK(c, hipMemsetAsync(c->counters, 0, 8 * (SNN_MAXL + 1), s));
+    HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
     for (int l = 1; l <= L; ++l)
       HIPCHK(c, launch_count_spikes(n.mask[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
   }
-  HIPCHK(c, hipStreamSynchronize(cs));
   HIPCHK(c, hipStreamSynchronize(s));
   if (stats) {
     unsigned long long cnt[SNN_MAXL + 1];

@@ -210,3 +210,31 @@ def test_shorter_sequence_in_same_context_and_device_inputs():
     assert _check_spikes(net, short, ref, "short") == 0
     _check_grads(_gpu_grads(net, 1), _oracle_f64_on_f32_trajectory(short, ds, ref, 1), "short")
     net.snn_destroy()
+
+
+def test_graph_replay_matches_eager():
+    """snn_bptt without statistics replays a recorded HIP graph.  Every replay must give exactly what
+    the eager (instrumented) call gives, also after other work ran in between and after the plan changed."""
+    w = synth.config(1, T=200, B=8)
+    d = synth.generate(w)
+    net = snn.from_workload(w, d)
+    net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+    L = len(w.n_hidden)
+    for strat, C, F in [(snn.SNN_DOUBLE, 50, 7), (snn.SNN_REMOTE, 32, 0), (snn.SNN_STANDARD, 0, 0)]:
+        net.snn_bptt(strat, C, F, want_stats=True)              # eager
+        ref = _gpu_grads(net, L)
+        ref_spk = net.snn_get_spikes(1, w.T)
+        for rep in range(3):
+            net.snn_bptt(strat, C, F, want_stats=False)         # records on the first call, replays after
+            assert _identical(_gpu_grads(net, L), ref), (strat, rep)
+            assert np.array_equal(net.snn_get_spikes(1, w.T), ref_spk)
+            net.snn_forward(d["in_spikes"], d["labels"], w.T)   # eager work between replays
+            net.snn_bptt(snn.SNN_CHUNK, 0, 9, want_stats=True)  # a different plan, eager
+    # new inputs through the same graph: the recording must not have baked any input in
+    d2 = synth.generate(synth.config(1, T=200, B=8, seed=77))
+    net.snn_bind_inputs(d2["in_spikes"], d2["labels"], w.T)
+    net.snn_bptt(snn.SNN_STANDARD, 0, 0, want_stats=False)
+    g_graph = _gpu_grads(net, L)
+    net.snn_bptt(snn.SNN_STANDARD, 0, 0, want_stats=True)
+    assert _identical(_gpu_grads(net, L), g_graph)
+    net.snn_destroy()
