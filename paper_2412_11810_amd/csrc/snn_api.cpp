@@ -25,6 +25,7 @@ struct snn_ctx {
   int32_t *labels = nullptr;
   int T_bound = 0;
   double *readout = nullptr;
+  WsArgs ws{};                // chip-wide recurrent kernel: exchange buffer, barrier counters, error flag
   float *cur_state = nullptr; // [B][SN] state carried through the forward pass
   float *ubar = nullptr, *g = nullptr, *loss_dev = nullptr, *carry = nullptr;
   unsigned long long *counters = nullptr;
@@ -67,6 +68,23 @@ bool is_device_ptr(const void *p) {
     return false;
   }
   return a.type == hipMemoryTypeDevice;
+}
+
+// Pool of uncached device blocks (never returned to the driver before the process ends).
+struct UncachedBlock { int device; size_t bytes; void *ptr; bool busy; };
+std::vector<UncachedBlock> &uncached_pool() { static std::vector<UncachedBlock> pool; return pool; }
+void *uncached_block(int device, size_t bytes) {
+  bytes = (bytes + 320 + 4095) & ~(size_t)4095;
+  for (auto &b : uncached_pool())
+    if (!b.busy && b.device == device && b.bytes >= bytes) { b.busy = true; return b.ptr; }
+  void *p = nullptr;
+  if (hipExtMallocWithFlags(&p, bytes, hipDeviceMallocUncached) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  uncached_pool().push_back(UncachedBlock{device, bytes, p, true});
+  return p;
+}
+void uncached_release(int device, void *ptr) {
+  for (auto &b : uncached_pool())
+    if (b.device == device && b.ptr == ptr) b.busy = false;
 }
 
 bool valid_cfg(const snn_config *c, std::string *why) {
@@ -203,6 +221,24 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   HIPCHK(c, hipMalloc(&c->loss_dev, 16));
   HIPCHK(c, hipMalloc(&c->carry, (size_t)B * (n.SN + O) * 4));
   HIPCHK(c, hipMalloc(&c->cur_state, (size_t)B * n.SN * 4));
+  {
+    int nmax = 0;
+    for (int l = 0; l < L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
+    if (nmax > 256 && nmax <= 1024 && !std::getenv("SNN_NO_WS")) {
+      // exchange buffer + barrier counters in uncached device memory (coherent across the chip
+      // without cache maintenance).  Such memory is never freed while the process lives: blocks are
+      // kept in a per-process pool and handed out again.
+      const size_t bytes = (size_t)2 * B * nmax * 4 + 65 * sizeof(unsigned);
+      void *blk = uncached_block(cfg->device, bytes);
+      if (!blk) return fail(c, SNN_E_HIP, "uncached device allocation failed");
+      c->ws.bar = (unsigned *)blk;
+      c->ws.xg = (float *)((char *)blk + 65 * sizeof(unsigned) + 60); // keep 64-byte alignment: 65*4+60 = 320
+      HIPCHK(c, hipMemsetAsync(c->ws.bar, 0, 65 * sizeof(unsigned), c->stream));
+      c->ws.err = c->ws.bar + 64;
+      c->ws.max_groups = ws_max_resident_groups(cfg->device);
+      c->ws.spin_limit = 4000000u; // ~1 s of polling: far beyond any real wait
+    }
+  }
   HIPCHK(c, hipMalloc(&c->counters, 8 * (SNN_MAXL + 1)));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return SNN_OK;
@@ -220,7 +256,8 @@ void snn_destroy(snn_ctx *c) {
   for (int l = 0; l <= SNN_MAXL; ++l) (void)hipFree(c->net.mask[l]);
   (void)hipFree(c->W_out); (void)hipFree(c->W_outT); (void)hipFree(c->dW_out); (void)hipFree(c->acc_out);
   (void)hipFree(c->labels); (void)hipFree(c->readout); (void)hipFree(c->ubar); (void)hipFree(c->g);
-  (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->cur_state); (void)hipFree(c->counters);
+  (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->cur_state);
+  if (c->ws.bar) uncached_release(c->cfg.device, c->ws.bar); (void)hipFree(c->counters);
   (void)hipFree(c->arena); (void)hipFree(c->dubuf);
   if (c->host_ckpt) (void)hipHostFree(c->host_ckpt);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
@@ -415,6 +452,17 @@ struct Timer {
 };
 } // namespace
 
+static snn_status check_ws_error(snn_ctx *c) {
+  if (!c->ws.err) return SNN_OK;
+  unsigned e = 0;
+  HIPCHK(c, hipMemcpy(&e, c->ws.err, sizeof e, hipMemcpyDeviceToHost));
+  if (e) {
+    HIPCHK(c, hipMemset(c->ws.err, 0, sizeof e));
+    return fail(c, SNN_E_HIP, "a workgroup barrier of the recurrent adjoint kernel timed out; gradients are invalid");
+  }
+  return SNN_OK;
+}
+
 // Queues one whole training step on the context's streams; no host synchronisation inside, no
 // allocation, no hipMemsetAsync (fill kernels instead), so that the same code can be recorded into
 // a HIP graph.  The copy stream is forked from and joined back into the compute stream with events.
@@ -550,7 +598,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
         tm.begin(2);
         HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0,
-                                 c->dubuf + (size_t)p.chunk_len * B * O, s));
+                                 c->dubuf + (size_t)p.chunk_len * B * O, c->ws, s));
         tm.end();
         first_adjoint = false;
         tm.begin(3);
@@ -661,7 +709,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     }
     HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
     HIPCHK(c, hipStreamSynchronize(s));
-    return SNN_OK;
+    return check_ws_error(c);
   }
 
   Timer tm{c, stats != nullptr};
@@ -692,7 +740,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     }
     *stats = st;
   }
-  return SNN_OK;
+  return check_ws_error(c);
 }
 
 } // extern "C"

@@ -70,8 +70,19 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
 // overwritten in place by delta_v_t.  dubuf gets delta_u_t at the same slot index ([slot][B][O]).
 // carry: [B][SN + O] floats (delta_v_{t+1} of all layers, delta_u_{t+1}); carry_init zeroes it first.
 // upbuf: scratch for the inter-layer products of one layer, (t1 - t0) * B * max_l N_l floats.
+// Exchange buffer, barrier counters and error flag of the chip-wide weight-stationary recurrent
+// kernel (see k_adj_rec_ws); xg == NULL disables that kernel.
+struct WsArgs {
+  float *xg;           // [2][B][max N_l]
+  unsigned *bar;       // [64] counters, zeroed before every launch (bar[63] doubles as nothing else)
+  unsigned *err;       // raised if a barrier gave up waiting
+  int max_groups;      // workgroups of that kernel that can be resident at once
+  unsigned spin_limit; // barrier polls before giving up
+};
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf,
-                          const float *g, float *carry, int carry_init, float *upbuf, hipStream_t s);
+                          const float *g, float *carry, int carry_init, float *upbuf, const WsArgs &ws,
+                          hipStream_t s);
+int ws_max_resident_groups(int device);
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
 // element) and column offset post_off.

@@ -547,6 +547,120 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
   if (own) cb[j] = x[cur][j];
 }
 
+// Recurrent part, wide layers (N/8 weights per thread fit in registers, N <= 1024): the recurrent
+// matrix is spread over the chip and stays in registers for the whole chunk.  Workgroup (js, bg)
+// owns 32 postsynaptic rows x 8 batch elements: thread (jl, kp) keeps W_rec[j][kp*NR .. +NR) and
+// forms partial products for the 8 batch elements against dv_{t+1} broadcast from LDS; the 8
+// partial sums are combined in a fixed order.  The N/32 workgroups that share a batch group
+// exchange their slices of dv_t through a double-buffered array in device memory and a counting
+// barrier (one atomic per workgroup and step).  The barrier spins a bounded number of times: if a
+// workgroup never arrives the kernel raises *err and every workgroup runs to completion.
+template <int NR>
+__global__ void __launch_bounds__(256)
+k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
+             int ldu, float *__restrict__ carry, int carry_init, float *xg, unsigned *bar, unsigned *err, int G_b,
+             unsigned spin_limit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out;
+  const int tid = threadIdx.x;
+  const int bg = blockIdx.x % G_b, js = blockIdx.x / G_b, n_slices = gridDim.x / G_b;
+  const int b0 = bg * 8, j0 = js * 32;
+  const int NP = NR * 8;                       // padded reduction length (>= N)
+  float *xs = (float *)smem;                   // [NP][8]  dv_{t+1}, batch-minor
+  float *part = xs + (size_t)NP * 8;           // [8][32][8]
+  const int jl = tid & 31, kp = tid >> 5;
+
+  float w[NR];
+#pragma unroll
+  for (int q = 0; q < NR; ++q) {
+    const int n = kp * NR + q;
+    w[q] = (j0 + jl < N && n < N) ? net.W_recT[l][(size_t)n * N + j0 + jl] : 0.0f; // = W_rec[j][n]
+  }
+  // dv_{t1+1} of this batch group
+  for (int i = tid; i < NP * 8; i += 256) {
+    const int n = i >> 3, bb = i & 7;
+    xs[i] = (!carry_init && n < N && b0 + bb < B) ? carry[(size_t)(b0 + bb) * (SN + O) + off + n] : 0.0f;
+  }
+  __syncthreads();
+  // finalising role of this thread: row fj, batch element fb
+  const int fj = j0 + (tid & 31), fbb = tid >> 5, fb = b0 + fbb;
+  const bool fin = fj < N && fb < B;
+  const size_t slot_stride = (size_t)B * SN;
+  unsigned step = 0;
+  bool dead = false;
+  for (int t = t1; t > t0; --t, ++step) {
+    const size_t slot = (size_t)(t - t_base - 1);
+    float vt = 0.0f, upv = 0.0f;
+    if (fin) {
+      vt = vbuf[slot * slot_stride + (size_t)fb * SN + off + fj];
+      upv = up[(slot * B + fb) * ldu + fj];
+    }
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
+    const float4 *x4 = reinterpret_cast<const float4 *>(xs + (size_t)kp * NR * 8);
+#pragma unroll 8
+    for (int q = 0; q < NR; ++q) {
+      const float4 xa = x4[2 * q], xb = x4[2 * q + 1];
+      acc[0] = fmaf(w[q], xa.x, acc[0]); acc[1] = fmaf(w[q], xa.y, acc[1]);
+      acc[2] = fmaf(w[q], xa.z, acc[2]); acc[3] = fmaf(w[q], xa.w, acc[3]);
+      acc[4] = fmaf(w[q], xb.x, acc[4]); acc[5] = fmaf(w[q], xb.y, acc[5]);
+      acc[6] = fmaf(w[q], xb.z, acc[6]); acc[7] = fmaf(w[q], xb.w, acc[7]);
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) part[((size_t)kp * 32 + jl) * 8 + c] = acc[c];
+    __syncthreads();
+    const int par = step & 1;
+    if (fin) {
+      float sacc = part[((size_t)0 * 32 + (tid & 31)) * 8 + fbb];
+#pragma unroll
+      for (int k = 1; k < 8; ++k) sacc = sacc + part[((size_t)k * 32 + (tid & 31)) * 8 + fbb];
+      const float dn = xs[(size_t)fj * 8 + fbb];
+      const float ds = (sacc + upv) - net.theta * dn;
+      const float d = 1.0f + net.k * fabsf(vt - net.theta);
+      const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+      vbuf[slot * slot_stride + (size_t)fb * SN + off + fj] = dvt;
+      xg[((size_t)par * B + fb) * N + fj] = dvt;
+    }
+    // ---- counting barrier over the workgroups of this batch group -------------------------
+    // xg and bar live in uncached device memory: stores to them are visible to every other
+    // workgroup as soon as they are acknowledged, so waiting for this wave's own memory operations
+    // is all the release that is needed (no L2 write-back or invalidate per step).
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0 && !dead) {
+      __hip_atomic_fetch_add(&bar[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned target = (step + 1u) * (unsigned)n_slices;
+      unsigned spins = 0;
+      while (__hip_atomic_load(&bar[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        if (++spins > spin_limit || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __syncthreads();
+    if (!dead && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) dead = true; // keep going, never wait again
+    // ---- dv_t of the whole layer for this batch group -> LDS --------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    {
+      // thread -> batch element tid/32, columns (tid%32) + 32*i: all loads issued before the first use
+      const int bb = tid >> 5, nb = tid & 31;
+      const float *src = xg + ((size_t)par * B + b0 + bb) * N + nb;
+      float r[NR / 4];
+#pragma unroll
+      for (int i = 0; i < NR / 4; ++i) r[i] = (b0 + bb < B && nb + 32 * i < N) ? src[32 * i] : 0.0f;
+#pragma unroll
+      for (int i = 0; i < NR / 4; ++i)
+        if (nb + 32 * i < N) xs[(size_t)(nb + 32 * i) * 8 + bb] = r[i];
+    }
+    __syncthreads();
+  }
+  // carry out dv_{t0+1}: every workgroup writes its own rows
+  if (fin) carry[(size_t)fb * (SN + O) + off + fj] = xs[(size_t)fj * 8 + fbb];
+}
+
 // Recurrent part, any layer width: the transposed recurrent matrix is streamed from L2 every step
 // (coalesced over the output index), the reduction split over KG thread groups with a fixed
 // combination order.
@@ -959,7 +1073,7 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
 }
 
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf, const float *g,
-                          float *carry, int carry_init, float *upbuf, hipStream_t s) {
+                          float *carry, int carry_init, float *upbuf, const WsArgs &ws, hipStream_t s) {
   if (t1 <= t0) return hipErrorInvalidValue;
   const int B = net.B, O = net.n_out, SN = net.SN, L = net.L;
   const int M = (t1 - t0) * B;
@@ -982,6 +1096,18 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
       const int NJ = (N + 63) & ~63;
       hipLaunchKernelGGL((k_adj_rec_rs<128>), dim3(B), dim3(2 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N, carry,
                          carry_init);
+    } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
+      const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
+      const int NR = N <= 512 ? 64 : 128;
+      const size_t lds = ((size_t)NR * 8 * 8 + 8 * 32 * 8) * sizeof(float);
+      hipError_t e = launch_fill_zero(ws.bar, 64 * sizeof(unsigned), s);
+      if (e != hipSuccess) return e;
+      if (NR == 64)
+        hipLaunchKernelGGL((k_adj_rec_ws<64>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, t0, t1, vbuf, t_base, up,
+                           N, carry, carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
+      else
+        hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, t0, t1, vbuf, t_base, up,
+                           N, carry, carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
     } else {
       const int nt = 1024;
       hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), ((size_t)2 * N + nt) * sizeof(float), s, net, l, t0, t1,
@@ -989,6 +1115,15 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     }
   }
   return hipGetLastError();
+}
+
+int ws_max_resident_groups(int device) {
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+  int per_cu = 0;
+  const size_t lds = ((size_t)128 * 8 * 8 + 8 * 32 * 8) * sizeof(float);
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_ws<128>, 256, lds) != hipSuccess) return 0;
+  return per_cu * prop.multiProcessorCount;
 }
 
 hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,

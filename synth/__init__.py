@@ -53,7 +53,7 @@ CONFIGS = {
     0: Workload("cfg0_tiny_32-64-10", 32, (64,), 10, T=50, B=2, p_in=0.05, seed=0),
     1: Workload("cfg1_classifier_700-256-256-20", 700, (256, 256), 20, T=1000, B=32, p_in=0.02, seed=1),
     2: Workload("cfg2_wide_700-3x1024-20", 700, (1024, 1024, 1024), 20, T=10000, B=64, p_in=0.01,
-                gain=0.35, seed=2),
+                gain=0.156, seed=2),
     3: Workload("cfg3_long_128-2x512-10", 128, (512, 512), 10, T=100000, B=16, p_in=0.01, seed=3),
     4: Workload("cfg4_large_1024-4x8192-100", 1024, (8192,) * 4, 100, T=5000, B=32, p_in=0.02,
                 gain=0.3, rec_density=0.1, seed=4),
