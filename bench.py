@@ -3,10 +3,14 @@
 
 One "step" = one whole training step over one synthetic batch that is already resident in HBM:
 input-spike packing, event-driven forward with the strategy's state storage, loss, recomputation
-from checkpoints, adjoint recurrence and weight-gradient accumulation (everything behind
+from checkpoints, adjoint pass and weight-gradient accumulation (everything behind
 snn_bind_inputs + snn_bptt).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--strategy remote]
+
+Other modes (used to produce the summaries under profiles/):
+  --pmc-copy      run only the plain copy kernel (reference for scaling hardware byte counters)
+  --single        one un-instrumented step of the chosen strategy and nothing else
 """
 from __future__ import annotations
 
@@ -21,9 +25,13 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+MFMA_F64_PEAK_TF = 78.6   # MI355X published fp64 matrix peak
+# fp32 vector peak without packed-fp32 instructions (this build disables them):
+# 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s (the published 157.3 needs v_pk_fma_f32)
+ALU_F32_PEAK_TF = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 
-# strategy parameters per benchmark configuration: (coarse, fine) and the HBM activation budget
+# strategy parameters per benchmark configuration: (coarse, fine); budgets from the configurations
 STRATEGY_PARAMS = {
     0: {"standard": (0, 0), "chunk": (0, 10), "remote": (10, 0), "double": (20, 5)},
     1: {"standard": (0, 0), "chunk": (0, 32), "remote": (32, 0), "double": (100, 10)},
@@ -31,42 +39,53 @@ STRATEGY_PARAMS = {
     3: {"standard": (0, 0), "chunk": (0, 316), "remote": (316, 0), "double": (316, 18)},
 }
 BUDGET = {2: 8 * 10**9, 3: 4 * 10**9}
+SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3}
 
 
-def gather_bytes(w, rates, T, in_rate):
-    """Algorithmic bytes of one forward (or recompute) pass: the weight rows of every active
-    presynaptic spike (4*N_l bytes per event and target layer) plus the spike bits written/read."""
-    total = 0.0
-    pre_n, pre_r = w.n_in, in_rate
-    for l, n in enumerate(w.n_hidden):
-        ev_in = pre_r * pre_n * w.B * T
-        ev_rec = rates[l] * n * w.B * T
-        total += 4.0 * n * (ev_in + ev_rec) + (n / 8.0) * w.B * T
-        pre_n, pre_r = n, rates[l]
-    return total
+def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
+    """Algorithmic work of one training step per kernel kind (bytes for the bandwidth-bound kinds,
+    flops for the arithmetic ones), from the measured event counts."""
+    B, L = w.B, len(w.n_hidden)
+    pre_n = [w.n_in] + list(w.n_hidden[:-1])
+    pre_r = [in_rate] + list(rates[:-1])
+    ev_in = [pre_r[l] * pre_n[l] * B for l in range(L)]       # feed-forward events per step
+    ev_rec = [rates[l] * w.n_hidden[l] * B for l in range(L)]  # recurrent events per step
+    ev_out = rates[-1] * w.n_hidden[-1] * B
+    N = w.n_hidden
+    out = {}
+    # forward, parallel part: rows of W_in (4*N_l bytes per event), the current tile written and read
+    # once, readout rows (4*n_out per last-layer spike)
+    out["fwd_currents"] = ("hbm", T * (sum(4.0 * N[l] * ev_in[l] + 8.0 * N[l] * B for l in range(L)) + 4.0 * w.n_out * ev_out))
+    # forward, sequential part: register-stationary layers do dense fma chains (2*N^2 flop per (b, t));
+    # wider layers gather the rows of active neurons
+    seq_flops = sum(2.0 * N[l] * N[l] * B * T for l in range(L) if N[l] <= 256)
+    seq_bytes = T * sum(4.0 * N[l] * ev_rec[l] + (N[l] / 8.0 + 4.0 * N[l]) * B for l in range(L) if N[l] > 256)
+    out["fwd_seq"] = ("alu", seq_flops) if seq_flops >= seq_bytes else ("hbm", seq_bytes)
+    # recompute: rows of W_in and W_rec per event + current written, read, state written (12*N_l per (b, t))
+    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * (ev_in[l] + ev_rec[l]) + 12.0 * N[l] * B for l in range(L)))
+    # adjoint: dense recurrent product, 2*N^2 flop per (b, t, layer)
+    out["adjoint"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)))
+    up = [w.n_out if l == L - 1 else N[l + 1] for l in range(L)]
+    out["up_gemm"] = ("alu", sum(2.0 * N[l] * up[l] * B * T for l in range(L)))
+    # dW: dense fp64 contraction over (t, b): 2 * n_pre * n_post * B * T per matrix
+    out["dw"] = ("mfma", 2.0 * B * T * (sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out))
+    return out
 
 
-def adjoint_bytes(w, T):
-    """Dense transposed products: each matrix read once per step for the whole batch, plus the
-    state read and the delta_v write (4+4 bytes per neuron, batch element and step)."""
-    total = 0.0
-    L = len(w.n_hidden)
-    for l, n in enumerate(w.n_hidden):
-        up = w.n_out if l == L - 1 else w.n_hidden[l + 1]
-        total += 4.0 * n * (up + n) * T + 8.0 * n * w.B * T
-    return total
-
-
-def dw_bytes(w, rates, T, in_rate, launches):
-    """delta_v row reads for every active presynaptic spike + one fp64 read-modify-write of every
-    gradient matrix per launch."""
-    total = 0.0
-    pre_n, pre_r = w.n_in, in_rate
-    for l, n in enumerate(w.n_hidden):
-        total += 4.0 * n * (pre_r * pre_n + rates[l] * n) * w.B * T + 16.0 * (pre_n * n + n * n) * launches
-        pre_n, pre_r = n, rates[l]
-    total += 4.0 * w.n_out * rates[-1] * w.n_hidden[-1] * w.B * T + 16.0 * w.n_hidden[-1] * w.n_out * launches
-    return total
+def read_traffic(workload, strategy, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{workload}_{strategy}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        p = line.split()
+        if len(p) >= 4 and p[0] == "kernel" and p[1] == kernel:
+            kv = dict(zip(p[2::2], p[3::2]))
+            try:
+                return float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"])
+            except (KeyError, ValueError):
+                return None
+    return None
 
 
 def main():
@@ -75,9 +94,14 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1)
-    ap.add_argument("--strategy", default="remote", choices=["standard", "chunk", "remote", "double"])
+    ap.add_argument("--strategy", default="remote", choices=list(SID))
     ap.add_argument("--T", type=int, default=0, help="override the sequence length")
+    ap.add_argument("--coarse", type=int, default=-1)
+    ap.add_argument("--fine", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="do not time the other strategies")
+    ap.add_argument("--single", action="store_true")
+    ap.add_argument("--pmc-copy", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -90,21 +114,41 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    dev = torch.device("cuda:0")
+
+    if args.pmc_copy:
+        net = snn.Snn(snn.make_config(8, [64], 2, 4, 1))
+        nbytes = 256 << 20
+        a = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            net.snn_debug_copy(a, b, nbytes)
+        print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "launches": 3}))
+        return
+
     w = synth.config(args.config, **({"T": args.T} if args.T else {}))
     d = synth.generate(w)
-    dev = torch.device("cuda:0")
     x = torch.from_numpy(d["in_spikes"]).to(dev)
     y = torch.from_numpy(d["labels"]).to(dev)
-    stream = torch.cuda.current_stream().cuda_stream
-    net = snn.from_workload(w, d, stream=stream)
-    sid = {"standard": snn.SNN_STANDARD, "chunk": snn.SNN_CHUNK, "remote": snn.SNN_REMOTE, "double": snn.SNN_DOUBLE}
-    params = STRATEGY_PARAMS[args.config]
+    net = snn.from_workload(w, d)  # stream = None: the library runs on a stream of its own
+    params = dict(STRATEGY_PARAMS[args.config])
+    if args.coarse >= 0 or args.fine >= 0:
+        c0, f0 = params[args.strategy]
+        params[args.strategy] = (args.coarse if args.coarse >= 0 else c0, args.fine if args.fine >= 0 else f0)
     budget = BUDGET.get(args.config, 0)
 
     def step(name, stats=False):
         C, F = params[name]
         net.snn_bind_inputs(x, y, w.T)
-        return net.snn_bptt(sid[name], C, F, budget, want_stats=stats)
+        return net.snn_bptt(SID[name], C, F, budget, want_stats=stats)
+
+    if args.single:
+        step(args.strategy)
+        torch.cuda.synchronize()
+        print(json.dumps({"single_step": args.strategy, "workload": w.name}))
+        net.snn_destroy()
+        return
 
     def time_strategy(name, steps, warmup):
         for _ in range(warmup):
@@ -119,63 +163,85 @@ def main():
     nts = w.neuron_timesteps()
     sec = time_strategy(args.strategy, args.steps, args.warmup)
     others = {}
-    for name in params:
-        if name != args.strategy:
-            try:
-                others[name] = nts / time_strategy(name, max(2, args.steps // 4), 1)
-            except snn.SnnError as e:
-                others[name] = str(e)
+    if not args.no_others:
+        for name in params:
+            if name != args.strategy:
+                try:
+                    others[name] = round(nts / time_strategy(name, max(2, args.steps // 4), 2), 1)
+                except snn.SnnError as e:
+                    others[name] = str(e)
 
-    # instrumented call of the timed strategy: per-kernel-kind durations from HIP events on the stream
+    # instrumented (eager) steps of the timed strategy: per-kernel-kind durations from HIP events
+    # recorded on the stream the kernels run on; the second one is used (the first pays one-time costs)
+    step(args.strategy, stats=True)
     st = step(args.strategy, stats=True)
     rates = list(st.firing_rate)[: len(w.n_hidden)]
     in_rate = float(d["in_spikes"].mean())
     C, F = params[args.strategy]
-    slots, rslots = snn.snn_state_slots(sid[args.strategy], w.T, C, F)
-    n_bwd_launch = max(1, sum(1 for o in snn.snn_schedule(sid[args.strategy], w.T, C, F) if o[0] == "BACKWARD"))
-    n_rec_launch = max(1, sum(1 for o in snn.snn_schedule(sid[args.strategy], w.T, C, F) if o[0] in ("REFWD1", "REFWD2")))
-    n_fwd_launch = max(1, rslots)
-    kinds = {
-        "forward_gather": (st.ms_forward, gather_bytes(w, rates, w.T, in_rate), n_fwd_launch),
-        "recompute_gather": (st.ms_recompute, gather_bytes(w, rates, st.refwd1_steps + st.refwd2_steps, in_rate), n_rec_launch),
-        "adjoint": (st.ms_adjoint, adjoint_bytes(w, w.T), n_bwd_launch),
-        "dw_scatter": (st.ms_dw, dw_bytes(w, rates, w.T, in_rate, n_bwd_launch), n_bwd_launch),
-    }
-    dom = max(kinds, key=lambda k: kinds[k][0])
-    ms, byts, launches = kinds[dom]
-    achieved = byts / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
-                "launches_per_step": launches, "avg_launch_ms": round(ms / launches, 4),
-                "algorithmic_bytes_per_launch": int(byts / launches),
-                "per_kind": {k: {"ms_per_step": round(v[0], 3), "GB/s": round(v[1] / (v[0] * 1e-3) / 1e9, 2) if v[0] > 0 else None}
-                             for k, v in kinds.items()}}
+    slots, rslots = snn.snn_state_slots(SID[args.strategy], w.T, C, F)
+    sched = snn.snn_schedule(SID[args.strategy], w.T, C, F)
+    n_bwd = max(1, sum(1 for o in sched if o[0] == "BACKWARD"))
+    n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
+    n_tiles = sum(-(-(min((k + 1) * C, w.T) - k * C) // 64) for k in range(rslots)) if rslots else -(-w.T // 64)
+    L = len(w.n_hidden)
+    model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, n_bwd)
+    ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute,
+          "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw}
+    launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
+                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd}
+    kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
+                 "fwd_currents": "k_currents", "recompute": "k_currents", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma",
+                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_ws" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
+    peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12)}
+    kinds = {}
+    for k, (bound, work) in model.items():
+        if ms[k] <= 0:
+            continue
+        peak, unit, scale = peaks[bound]
+        ach = work / (ms[k] * 1e-3) / scale
+        kinds[k] = {"kernel": kernel_of[k], "bound": bound, "ms_per_step": round(ms[k], 3), "launches_per_step": launches[k],
+                    "avg_launch_ms": round(ms[k] / launches[k], 4), "achieved": round(ach, 3), "peak": round(peak, 1),
+                    "unit": unit, "frac": round(ach / peak, 5)}
+    dom = max(kinds, key=lambda k: kinds[k]["ms_per_step"])
+    dk = kinds[dom]
+    work_per_launch = model[dom][1] / launches[dom]
+    roofline = {"bound": dk["bound"], "kernel": dk["kernel"], "kind": dom, "achieved": dk["achieved"], "peak": dk["peak"],
+                "unit": dk["unit"], "frac": dk["frac"],
+                "traffic": read_traffic(w.name, args.strategy, dk["kernel"]),
+                "launches_per_step": dk["launches_per_step"], "avg_launch_ms": dk["avg_launch_ms"],
+                "algorithmic_work_per_launch": int(work_per_launch),
+                "note": "work = flops for alu/mfma kinds, bytes for hbm kinds; durations from HIP events on the compute stream",
+                "kinds": kinds}
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), w.B)
+        cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), w.B))
         Tcpu = min(w.T, 1000 if w.neurons <= 1024 else 100)
-        t0 = time.perf_counter()
-        oracle.bptt(w.n_in, list(w.n_hidden), w.n_out, d["W_in"], d["W_rec"], d["W_out"],
-                    np.ascontiguousarray(d["in_spikes"][:Tcpu]), d["labels"], alpha=w.alpha, beta=w.beta,
-                    theta=w.theta, surr_beta=w.surr_beta, dtype=np.float32, nthreads=cores)
-        dt = time.perf_counter() - t0
-        cpu = {"value": round(w.B * Tcpu * w.neurons / dt, 1), "unit": "neuron-timesteps/s", "cores": cores,
-               "kind": "oracle", "sample": f"oracle fp32 Standard BPTT, first {Tcpu} of {w.T} steps, full batch, {dt:.2f} s wall"}
+        xs = np.ascontiguousarray(d["in_spikes"][:Tcpu])
+        wall, reps = 0.0, 0
+        while reps < 6 and (reps < 1 or wall < 1.5):
+            t0 = time.perf_counter()
+            oracle.bptt(w.n_in, list(w.n_hidden), w.n_out, d["W_in"], d["W_rec"], d["W_out"], xs, d["labels"],
+                        alpha=w.alpha, beta=w.beta, theta=w.theta, surr_beta=w.surr_beta, dtype=np.float32, nthreads=cores)
+            wall += time.perf_counter() - t0
+            reps += 1
+        cpu = {"value": round(reps * w.B * Tcpu * w.neurons / wall, 1), "unit": "neuron-timesteps/s", "cores": cores,
+               "kind": "oracle",
+               "sample": f"oracle fp32 Standard BPTT (fwd+bwd), first {Tcpu} of {w.T} steps, full batch, {reps} repetitions, {wall:.2f} s wall"}
 
     out = {
-        "metric": "BPTT neuron-timesteps/sec (fwd+bwd) at fixed HBM budget",
-        "value": round(nts / sec, 1), "unit": "neuron-timesteps/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "metric": "BPTT neuron-timesteps/sec (fwd+bwd) at fixed HBM budget", "value": round(nts / sec, 1),
+        "unit": "neuron-timesteps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "batch": w.B, "strategy": args.strategy, "coarse_interval": C,
                    "fine_interval": F, "hbm_budget_bytes": budget,
                    "hbm_activation_bytes": int(st.bytes_states + st.bytes_spikes + st.bytes_workspace),
-                   "state_slots_hbm": slots, "state_slots_host": rslots,
+                   "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots, "state_slots_host": rslots,
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
                    "host_link_bytes_per_step": int(st.d2h_bytes + st.h2d_bytes),
-                   "other_strategies_neuron_timesteps_per_s": {k: (round(v, 1) if not isinstance(v, str) else v) for k, v in others.items()}},
+                   "other_strategies_neuron_timesteps_per_s": others},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))

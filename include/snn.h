@@ -67,14 +67,19 @@ typedef struct {
   float theta;                      /* threshold = reset amount                        */
   float surr_beta;                  /* k in 1/(1+k|v-theta|)^2                          */
   int32_t device;                   /* HIP device ordinal                              */
-  void *stream;                     /* hipStream_t to queue work on (NULL = default)   */
+  void *stream;                     /* hipStream_t to queue work on; NULL = a stream the
+                                       library creates (the legacy default stream cannot be
+                                       recorded into a HIP graph)                        */
 } snn_config;
 
 /* Filled by snn_bptt (all times in milliseconds, measured with HIP events on the
  * context's stream; bytes are what the call actually allocated/moved). */
 typedef struct {
   float ms_total, ms_forward, ms_backward_total; /* whole step; forward incl. loss; everything after */
-  float ms_recompute, ms_adjoint, ms_dw;         /* sums over kernels of each kind (0 if not timed) */
+  float ms_recompute, ms_adjoint, ms_dw;         /* sums over kernels of each kind: recompute (currents+scan),
+                                                    recurrent adjoint kernels, weight-gradient kernels */
+  float ms_fwd_seq, ms_fwd_currents, ms_up_gemm; /* forward: sequential per-layer kernels / parallel current and
+                                                    readout kernels; adjoint: inter-layer GEMMs */
   int64_t bytes_states;      /* HBM: trajectory / chunk buffer / checkpoints / staging slots */
   int64_t bytes_spikes;      /* HBM: spike bitmasks of all layers, all steps                  */
   int64_t bytes_workspace;   /* HBM: readout-adjoint tile and other per-chunk scratch          */
@@ -124,6 +129,11 @@ snn_status snn_get_spikes(snn_ctx *ctx, int layer /*0..L-1*/, uint8_t *dst /*[T]
 snn_status snn_get_readout(snn_ctx *ctx, float *ubar /*[B][n_out], host*/, float *loss /*1 float, host*/);
 /* Runs a forward pass that stores every state and copies them out: dst [T][B][sum N_l] fp32, host. */
 snn_status snn_debug_states(snn_ctx *ctx, float *dst);
+
+/* Measurement aid: one plain streaming copy kernel of `bytes` bytes (a multiple of 16), device to
+ * device.  Hardware byte counters read under a profiler are scaled by what they read for this
+ * kernel, whose traffic is known (bytes read + bytes written). */
+snn_status snn_debug_copy(snn_ctx *ctx, const void *src, void *dst, size_t bytes);
 
 /* Activation bytes the strategy needs in HBM for sequence length T (no context, no GPU needed).
  * Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes + bytes_workspace. */

@@ -24,7 +24,7 @@ OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5:
 
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",
-           "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy"]
+           "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy"]
 
 
 class snn_config(C.Structure):
@@ -37,6 +37,7 @@ class snn_config(C.Structure):
 class snn_stats(C.Structure):
     _fields_ = [("ms_total", C.c_float), ("ms_forward", C.c_float), ("ms_backward_total", C.c_float),
                 ("ms_recompute", C.c_float), ("ms_adjoint", C.c_float), ("ms_dw", C.c_float),
+                ("ms_fwd_seq", C.c_float), ("ms_fwd_currents", C.c_float), ("ms_up_gemm", C.c_float),
                 ("bytes_states", C.c_int64), ("bytes_spikes", C.c_int64), ("bytes_workspace", C.c_int64),
                 ("bytes_host", C.c_int64), ("d2h_bytes", C.c_int64), ("h2d_bytes", C.c_int64),
                 ("n_d2h", C.c_int32), ("n_h2d", C.c_int32), ("fwd_steps", C.c_int64),
@@ -83,6 +84,7 @@ def lib() -> C.CDLL:
         L.snn_get_spikes.argtypes = [vp, C.c_int, vp]
         L.snn_get_readout.argtypes = [vp, vp, vp]
         L.snn_debug_states.argtypes = [vp, vp]
+        L.snn_debug_copy.argtypes = [vp, vp, vp, sz]
         L.snn_bytes_required.argtypes = [C.POINTER(snn_config), C.c_int, i32, i32, i32]
         L.snn_bytes_required.restype = sz
         L.snn_state_slots.argtypes = [C.c_int, i32, i32, i32, C.POINTER(i32)]
@@ -94,7 +96,7 @@ def lib() -> C.CDLL:
         L.snn_destroy.argtypes = [vp]
         L.snn_destroy.restype = None
         for name in ("snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
-                     "snn_get_spikes", "snn_get_readout", "snn_debug_states"):
+                     "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -212,6 +214,9 @@ class Snn:
         out = np.empty((T, self.cfg.batch, sn), dtype=np.float32)
         self._check(lib().snn_debug_states(self._h, out.ctypes.data))
         return out
+
+    def snn_debug_copy(self, src, dst, nbytes: int):
+        self._check(lib().snn_debug_copy(self._h, _ptr(src), _ptr(dst), nbytes))
 
     def snn_destroy(self):
         if self._h:

@@ -408,6 +408,14 @@ snn_status snn_get_readout(snn_ctx *c, float *ubar, float *loss) {
   return SNN_OK;
 }
 
+snn_status snn_debug_copy(snn_ctx *c, const void *src, void *dst, size_t bytes) {
+  if (!c || !src || !dst) return fail(c, SNN_E_INVAL, "null argument");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, launch_copy(src, dst, bytes, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return SNN_OK;
+}
+
 snn_status snn_grads(snn_ctx *c, int kind, int layer, float *dst, size_t n_elems) {
   if (!c || !dst) return fail(c, SNN_E_INVAL, "null argument");
   const NetDev &n = c->net;
@@ -449,6 +457,9 @@ struct Timer {
   }
   void begin(int kind) { if (on) spans.push_back(Span{mark(), nullptr, kind}); }
   void end() { if (on) spans.back().b = mark(); }
+  static void hook_begin(void *self, int kind) { static_cast<Timer *>(self)->begin(kind); }
+  static void hook_end(void *self) { static_cast<Timer *>(self)->end(); }
+  SpanHook hook() { return SpanHook{this, &Timer::hook_begin, &Timer::hook_end}; }
 };
 } // namespace
 
@@ -472,6 +483,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   const int strategy = p.strategy;
   const size_t Ms = c->Ms(), slot = (size_t)B * SN;
   hipStream_t s = c->stream, cs = c->copy_stream;
+  const SpanHook hk = tm.hook();
   float *chunk = c->arena;                                   // chunk buffer / trajectory
   float *lckpt = chunk + (size_t)p.chunk_len * slot;         // local checkpoints
   float *loadb = lckpt + (size_t)p.n_local_ckpt * slot;      // 2 slots receiving host checkpoints
@@ -505,11 +517,11 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk, slot, 0, 1, 0, T};
-    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
+    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
-    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s));
+    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else {
     // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again
     StoreSpec none{};
@@ -517,7 +529,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       const int a = K * p.C, e = std::min(a + p.C, T);
       const bool keep = K + 1 < p.n_remote; // x_e is the next coarse checkpoint
       const int so = K & 1;
-      HIPCHK(c, launch_forward(n, a, e, c->cur_state, none, c->readout, K == 0, c->dubuf, s));
+      HIPCHK(c, launch_forward(n, a, e, c->cur_state, none, c->readout, K == 0, c->dubuf, s, &hk));
       if (keep) {
         // snapshot x_e into a staging slot (D2D on the compute stream), then D2H on the side stream
         if (stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
@@ -596,10 +608,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       case OP_BACKWARD: {
         const int t1 = op.a, t0 = op.b - 1;
         const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
-        tm.begin(2);
         HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0,
-                                 c->dubuf + (size_t)p.chunk_len * B * O, c->ws, s));
-        tm.end();
+                                 c->dubuf + (size_t)p.chunk_len * B * O, c->ws, s, &hk));
         first_adjoint = false;
         tm.begin(3);
         if (c->dw_event_driven || B > 128) {
@@ -734,9 +744,14 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     for (const auto &sp : tm.spans) {
       float ms = 0.f;
       if (sp.a && sp.b) (void)hipEventElapsedTime(&ms, sp.a, sp.b);
-      if (sp.kind == 1) st.ms_recompute += ms;
-      else if (sp.kind == 2) st.ms_adjoint += ms;
-      else st.ms_dw += ms;
+      switch (sp.kind) {
+        case 1: st.ms_recompute += ms; break;
+        case 2: st.ms_adjoint += ms; break;
+        case 3: st.ms_dw += ms; break;
+        case 4: st.ms_fwd_seq += ms; break;
+        case 5: st.ms_fwd_currents += ms; break;
+        default: st.ms_up_gemm += ms; break;
+      }
     }
     *stats = st;
   }

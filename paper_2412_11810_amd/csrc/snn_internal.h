@@ -37,6 +37,15 @@ struct StoreSpec {
   int t_max;          // ... and t <= t_max
 };
 
+// Optional timing hook: the launchers bracket groups of kernels of one kind (HIP events on the
+// stream the kernels run on).  Kinds: 1 recompute, 2 adjoint recurrence, 3 dW, 4 forward sequential
+// part, 5 forward parallel currents + readout, 6 inter-layer GEMM of the adjoint pass.
+struct SpanHook {
+  void *ctx;
+  void (*begin)(void *ctx, int kind);
+  void (*end)(void *ctx);
+};
+
 struct LaunchCfg {
   int nt_neuron; // threads that own neurons (multiple of 64)
   int npt;       // neurons per owning thread (template instance)
@@ -51,7 +60,8 @@ hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, 
 // SNN_FWD_TILE * B * (max_l N_l + n_out) floats.
 #define SNN_FWD_TILE 64
 hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st,
-                          double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s);
+                          double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s,
+                          const SpanHook *hook = nullptr);
 // Arguments of the parallel current kernel (see k_currents).
 struct CurArgs {
   int mode, lsel;
@@ -81,7 +91,7 @@ struct WsArgs {
 };
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf,
                           const float *g, float *carry, int carry_init, float *upbuf, const WsArgs &ws,
-                          hipStream_t s);
+                          hipStream_t s, const SpanHook *hook = nullptr);
 int ws_max_resident_groups(int device);
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
@@ -111,6 +121,7 @@ hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, i
                                 hipStream_t s);
 hipError_t launch_count_spikes(const uint64_t *mask, size_t n_words, unsigned long long *count, hipStream_t s);
 hipError_t launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len);
 
 // ---- schedule / budget logic (snn_schedule.cpp; plain host code) --------------------------

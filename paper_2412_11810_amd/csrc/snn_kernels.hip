@@ -918,6 +918,11 @@ __global__ void k_count(const uint64_t *__restrict__ mask, size_t n_words, unsig
   if (lane_id() == 0 && c) atomicAdd(count, c); // integer atomic: order-independent
 }
 
+// plain streaming copy of known size (reference for scaling hardware byte counters)
+__global__ void __launch_bounds__(256) k_copy(const float4 *__restrict__ src, float4 *__restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 __global__ void k_zero(uint32_t *p, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
@@ -1009,8 +1014,10 @@ static hipError_t launch_currents(const NetDev &net, int t0, int t1, int t_base,
 }
 
 hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st, double *readout,
-                          int readout_init, float *work, hipStream_t s) {
+                          int readout_init, float *work, hipStream_t s, const SpanHook *hook) {
   if (t1 < t0) return hipErrorInvalidValue;
+  auto hb = [&](int kind) { if (hook) hook->begin(hook->ctx, kind); };
+  auto he = [&]() { if (hook) hook->end(hook->ctx); };
   const int B = net.B, O = net.n_out, L = net.L;
   int nmax = 0;
   for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
@@ -1023,8 +1030,11 @@ hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const
     for (int l = 0; l < L; ++l) {
       const int N = net.N[l];
       CurArgs ca{1, l, iin, 0, 0};
+      hb(5);
       hipError_t e = launch_currents(net, ta, tb, ta, ca, s);
+      he();
       if (e != hipSuccess) return e;
+      hb(4);
       if (N <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B), dim3(64), 0, s, net, l, ta, tb, state, st, iin, ta);
       else if (N <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B), dim3(128), 0, s, net, l, ta, tb, state, st, iin, ta);
       else if (N <= 256) hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B), dim3(256), 0, s, net, l, ta, tb, state, st, iin, ta);
@@ -1041,14 +1051,17 @@ hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const
         }
 #undef SEQ_CASE
       }
+      he();
       e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
     CurArgs co{2, L, iout, 0, 0};
+    hb(5);
     hipError_t e = launch_currents(net, ta, tb, ta, co, s);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O, tb - ta, net.beta,
                        (first && readout_init) ? 1 : 0);
+    he();
     first = false;
   }
   return hipGetLastError();
@@ -1073,8 +1086,11 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
 }
 
 hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf, const float *g,
-                          float *carry, int carry_init, float *upbuf, const WsArgs &ws, hipStream_t s) {
+                          float *carry, int carry_init, float *upbuf, const WsArgs &ws, hipStream_t s,
+                          const SpanHook *hook) {
   if (t1 <= t0) return hipErrorInvalidValue;
+  auto hb = [&](int kind) { if (hook) hook->begin(hook->ctx, kind); };
+  auto he = [&]() { if (hook) hook->end(hook->ctx); };
   const int B = net.B, O = net.n_out, SN = net.SN, L = net.L;
   const int M = (t1 - t0) * B;
   // slots are addressed relative to t_base; the chunk processed here starts at slot (t0 - t_base)
@@ -1089,7 +1105,10 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     if (l == L - 1) { A = dubuf + s0 * B * O; lda = O; K = O; W = net.W_out; }
     else { A = vbuf + s0 * ((size_t)B * SN) + net.off[l + 1]; lda = SN; K = net.N[l + 1]; W = net.W_in[l + 1]; }
     float *C = upbuf; // row m = (slot - s0)*B + b, ldc = N
+    hb(6);
     hipLaunchKernelGGL(k_up_gemm, dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    he();
+    hb(2);
     // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
     const float *up = upbuf - s0 * B * N;
     if (N <= 256) {
@@ -1113,6 +1132,7 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
       hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), ((size_t)2 * N + nt) * sizeof(float), s, net, l, t0, t1,
                          vbuf, t_base, up, N, carry, carry_init);
     }
+    he();
   }
   return hipGetLastError();
 }
@@ -1176,6 +1196,12 @@ hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, i
 
 hipError_t launch_count_spikes(const uint64_t *mask, size_t n_words, unsigned long long *count, hipStream_t s) {
   hipLaunchKernelGGL(k_count, dim3(512), dim3(256), 0, s, mask, n_words, count);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {
+  if (bytes % 16) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_copy, dim3(4096), dim3(256), 0, s, (const float4 *)src, (float4 *)dst, bytes / 16);
   return hipGetLastError();
 }
 

@@ -56,7 +56,7 @@ CONFIGS = {
                 gain=0.156, seed=2),
     3: Workload("cfg3_long_128-2x512-10", 128, (512, 512), 10, T=100000, B=16, p_in=0.01, seed=3),
     4: Workload("cfg4_large_1024-4x8192-100", 1024, (8192,) * 4, 100, T=5000, B=32, p_in=0.02,
-                gain=0.3, rec_density=0.1, seed=4),
+                gain=0.2175, rec_density=0.1, seed=4),
 }
 
 
