@@ -100,6 +100,9 @@ def main():
     ap.add_argument("--fine", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="do not time the other strategies")
+    ap.add_argument("--no-long", action="store_true", help="skip the 10x-sequence-length comparison")
+    ap.add_argument("--long-coarse", type=int, default=1000)
+    ap.add_argument("--long-fine", type=int, default=100)
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true")
     args = ap.parse_args()
@@ -213,6 +216,68 @@ def main():
                 "note": "work = flops for alu/mfma kinds, bytes for hbm kinds; durations from HIP events on the compute stream",
                 "kinds": kinds}
 
+    # ---- "max trainable T" and the long-sequence comparison -----------------------------------------
+    # Budget = what Standard BPTT needs for this workload's T.  Under that same budget: the largest T
+    # each strategy can train (closed form from snn_bytes_required, intervals by the square-root rules
+    # unless the configuration fixes them), and Double Checkpointing actually run at 10x the sequence
+    # length, with its time per time step next to Standard's.
+    long_seq = None
+    if not args.no_long:
+        ref_budget = snn.snn_bytes_required(net.cfg, snn.SNN_STANDARD, w.T)
+
+        def fits(sid, T, Cc, Ff):
+            cfgT = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T, w.B)
+            need = snn.snn_bytes_required(cfgT, sid, T, Cc, Ff)
+            return 0 < need <= ref_budget
+
+        def t_max(sid, Cc, Ff):
+            lo, hi = 1, 1
+            while fits(sid, hi, min(Cc, hi), min(Ff, min(Cc, hi) if Cc else hi)) and hi < (1 << 26):
+                lo, hi = hi, hi * 2
+            while hi - lo > 1:
+                mid = (lo + hi) // 2
+                if fits(sid, mid, min(Cc, mid), min(Ff, min(Cc, mid) if Cc else mid)):
+                    lo = mid
+                else:
+                    hi = mid
+            return lo
+        tmax = {"standard": t_max(snn.SNN_STANDARD, 0, 0), "chunk": t_max(snn.SNN_CHUNK, 0, 0),
+                "remote": t_max(snn.SNN_REMOTE, 0, 0), "double": t_max(snn.SNN_DOUBLE, 0, 0)}
+        T_long = 10 * w.T
+        CL, FL = args.long_coarse, args.long_fine
+        wl = synth.config(args.config, T=T_long)
+        cfg_long = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T_long, w.B)
+        need_long = snn.snn_bytes_required(cfg_long, snn.SNN_DOUBLE, T_long, CL, FL)
+        long_seq = {"budget_bytes": ref_budget, "budget_is": f"Standard BPTT at T={w.T}", "t_max_under_budget": tmax,
+                    "double_T": T_long, "double_coarse": CL, "double_fine": FL, "double_bytes_required": need_long}
+        if 0 < need_long <= ref_budget:
+            dl = synth.generate(wl)
+            xl = torch.from_numpy(dl["in_spikes"]).to(dev)
+            yl = torch.from_numpy(dl["labels"]).to(dev)
+            netl = snn.from_workload(wl, dl)
+
+            def step_long():
+                netl.snn_bind_inputs(xl, yl, T_long)
+                netl.snn_bptt(snn.SNN_DOUBLE, CL, FL, ref_budget, want_stats=False)
+            for _ in range(2):
+                step_long()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nrep = 3
+            for _ in range(nrep):
+                step_long()
+            torch.cuda.synchronize()
+            sec_long = (time.perf_counter() - t0) / nrep
+            sec_std = time_strategy("standard", max(3, args.steps // 4), 2) if args.strategy != "standard" else sec
+            long_seq.update({"double_ms_per_step": round(sec_long * 1e3, 3),
+                             "double_us_per_timestep": round(sec_long / T_long * 1e6, 4),
+                             "standard_T": w.T, "standard_ms_per_step": round(sec_std * 1e3, 3),
+                             "standard_us_per_timestep": round(sec_std / w.T * 1e6, 4),
+                             "time_per_timestep_ratio_double_over_standard": round((sec_long / T_long) / (sec_std / w.T), 4),
+                             "sequence_length_ratio": 10})
+            netl.snn_destroy()
+            del xl, yl
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -242,7 +307,7 @@ def main():
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
                    "host_link_bytes_per_step": int(st.d2h_bytes + st.h2d_bytes),
                    "other_strategies_neuron_timesteps_per_s": others},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "long_sequence": long_seq,
     }
     print(json.dumps(out))
     net.snn_destroy()
