@@ -117,8 +117,9 @@ int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 size_t work_bytes(const NetDev &n, int chunk_len) {
   int nmax = 0;
   for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
-  const int steps = chunk_len > SNN_FWD_TILE ? chunk_len : SNN_FWD_TILE;
-  return (size_t)steps * n.B * (n.n_out + nmax) * sizeof(float);
+  const size_t bwd = (size_t)chunk_len * n.B * (n.n_out + nmax) * sizeof(float);
+  const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (n.n_out + n.SN) * sizeof(float); // currents of one tile, every layer
+  return bwd > fwd ? bwd : fwd;
 }
 
 size_t spike_bytes(const NetDev &n, int T) {
@@ -328,6 +329,20 @@ snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *
   return SNN_OK;
 }
 
+// Tile boundaries of a forward pass over (t0, t1]: at most SNN_FWD_TILE steps per tile, and a
+// boundary at every multiple of `seg` (the coarse checkpoints of the host tier).
+static std::vector<int> tile_bounds(int t0, int t1, int seg) {
+  std::vector<int> b{t0};
+  for (int a = t0; a < t1;) {
+    int e = std::min(a + SNN_FWD_TILE, t1);
+    const int next_seg = (a / seg + 1) * seg;
+    if (next_seg < e) e = next_seg;
+    b.push_back(e);
+    a = e;
+  }
+  return b;
+}
+
 static snn_status ensure_work(snn_ctx *c, size_t bytes) {
   if (c->dubuf_bytes >= bytes) return SNN_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -348,7 +363,8 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
   snn_status rs = ensure_work(c, work_bytes(n, 1));
   if (rs != SNN_OK) return rs;
   HIPCHK(c, hipMemsetAsync(c->cur_state, 0, c->Ms(), c->stream));
-  HIPCHK(c, launch_forward(n, 0, c->T_bound, c->cur_state, st, c->readout, 1, c->dubuf, c->stream));
+  std::vector<int> bounds = tile_bounds(0, c->T_bound, c->T_bound);
+  HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, c->dubuf, c->stream));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
   return SNN_OK;
 }
@@ -496,15 +512,14 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   HIPCHK(c, launch_fill_zero(c->acc_out, (size_t)n.N[L - 1] * O * 8, s));
 
   // events for the host tier
-  hipEvent_t ev_stage_ready[2] = {nullptr, nullptr}, ev_stage_free[2] = {nullptr, nullptr};
   hipEvent_t ev_load_ready[2] = {nullptr, nullptr}, ev_load_free[2] = {nullptr, nullptr};
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  bool stage_busy[2] = {false, false}, load_used[2] = {false, false};
+  bool load_used[2] = {false, false};
   const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE;
   if (remote) {
     for (int i = 0; i < 2; ++i) {
-      ev_stage_ready[i] = tm.get(); ev_stage_free[i] = tm.get(); ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
-      if (!ev_stage_ready[i] || !ev_stage_free[i] || !ev_load_ready[i] || !ev_load_free[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+      ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
+      if (!ev_load_ready[i] || !ev_load_free[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
     }
     ev_fork = tm.get(); ev_join = tm.get();
     if (!ev_fork || !ev_join) return fail(c, SNN_E_HIP, "hipEventCreate failed");
@@ -517,31 +532,49 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk, slot, 0, 1, 0, T};
-    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    const std::vector<int> bounds = tile_bounds(0, T, T);
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
-    HIPCHK(c, launch_forward(n, 0, T, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    const std::vector<int> bounds = tile_bounds(0, T, T);
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else {
-    // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again
-    StoreSpec none{};
-    for (int K = 0; K < p.n_remote; ++K) {
-      const int a = K * p.C, e = std::min(a + p.C, T);
-      const bool keep = K + 1 < p.n_remote; // x_e is the next coarse checkpoint
-      const int so = K & 1;
-      HIPCHK(c, launch_forward(n, a, e, c->cur_state, none, c->readout, K == 0, c->dubuf, s, &hk));
-      if (keep) {
-        // snapshot x_e into a staging slot (D2D on the compute stream), then D2H on the side stream
-        if (stage_busy[so]) HIPCHK(c, hipStreamWaitEvent(s, ev_stage_free[so], 0));
-        HIPCHK(c, hipMemcpyAsync(stage + (size_t)so * slot, c->cur_state, Ms, hipMemcpyDeviceToDevice, s));
-        HIPCHK(c, hipEventRecord(ev_stage_ready[so], s));
-        HIPCHK(c, hipStreamWaitEvent(cs, ev_stage_ready[so], 0));
-        HIPCHK(c, hipMemcpyAsync(c->host_ckpt + (size_t)(K + 1) * slot, stage + (size_t)so * slot, Ms, hipMemcpyDeviceToHost, cs));
-        HIPCHK(c, hipEventRecord(ev_stage_free[so], cs));
-        stage_busy[so] = true;
-        st.n_d2h++; st.d2h_bytes += (int64_t)Ms;
+    // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again.
+    // Each layer's part of a coarse checkpoint x_{KC} is snapshotted into a staging slot right after
+    // that layer finished step KC (the layers run one tile apart); when the last layer's part is in,
+    // the slot goes to the host on the copy stream.
+    struct Snap {
+      snn_ctx *c; const Plan *p; float *stage; size_t slot, Ms; int n_stage; hipStream_t s, cs;
+      std::vector<hipEvent_t> ready, freed; std::vector<char> busy; snn_stats *st;
+      static hipError_t done(void *self, int layer, int t_end) {
+        Snap &q = *static_cast<Snap *>(self);
+        const NetDev &n = q.c->net;
+        if (t_end % q.p->C != 0 || t_end >= q.p->T) return hipSuccess;
+        const int K = t_end / q.p->C, so = K % q.n_stage; // checkpoint x_{K*C} -> host slot K
+        hipError_t e = hipSuccess;
+        if (layer == 0 && q.busy[so]) e = hipStreamWaitEvent(q.s, q.freed[so], 0);
+        if (e == hipSuccess)
+          e = hipMemcpy2DAsync(q.stage + (size_t)so * q.slot + n.off[layer], (size_t)n.SN * 4, q.c->cur_state + n.off[layer],
+                               (size_t)n.SN * 4, (size_t)n.N[layer] * 4, (size_t)n.B, hipMemcpyDeviceToDevice, q.s);
+        if (e != hipSuccess || layer != n.L - 1) return e;
+        e = hipEventRecord(q.ready[so], q.s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(q.cs, q.ready[so], 0);
+        if (e == hipSuccess)
+          e = hipMemcpyAsync(q.c->host_ckpt + (size_t)K * q.slot, q.stage + (size_t)so * q.slot, q.Ms, hipMemcpyDeviceToHost, q.cs);
+        if (e == hipSuccess) e = hipEventRecord(q.freed[so], q.cs);
+        q.busy[so] = 1;
+        q.st->n_d2h++; q.st->d2h_bytes += (int64_t)q.Ms;
+        return e;
       }
+    } snap{c, &p, stage, slot, Ms, p.n_stage_slots, s, cs, {}, {}, {}, &st};
+    for (int i = 0; i < p.n_stage_slots; ++i) {
+      snap.ready.push_back(tm.get()); snap.freed.push_back(tm.get()); snap.busy.push_back(0);
+      if (!snap.ready.back() || !snap.freed.back()) return fail(c, SNN_E_HIP, "hipEventCreate failed");
     }
+    const FwdCallbacks cb{&snap, &Snap::done};
+    const std::vector<int> bounds = tile_bounds(0, T, p.C);
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, StoreSpec{}, c->readout, 1, c->dubuf, s, &hk, &cb));
   }
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));

@@ -55,20 +55,23 @@ struct LaunchCfg {
 // ---- launchers (defined in snn_kernels.hip) ---------------------------------------------
 hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, int B, int n_in, int Wd0,
                               hipStream_t s);
-// Forward pass over steps t0+1..t1 for all batch elements (gather, LIF update, threshold, compaction,
-// readout).  state: [B][SN], x_{t0} on entry, x_{t1} on return.  work: scratch of
-// SNN_FWD_TILE * B * (max_l N_l + n_out) floats.
+// Forward pass (gather, LIF update, threshold, compaction, readout) over consecutive time tiles
+// bounds[0..n_tiles], each at most SNN_FWD_TILE steps.  state: [B][SN], x_{bounds[0]} on entry,
+// x_{bounds[n_tiles]} on return.  work: scratch of SNN_FWD_TILE * B * (SN + n_out) floats.
+// layer_tile_done(layer, t_end) is called (on the host, in stream order) after the launch that
+// completes layer `layer` up to step t_end has been queued.
 #define SNN_FWD_TILE 64
-hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st,
-                          double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s,
-                          const SpanHook *hook = nullptr);
-// Arguments of the parallel current kernel (see k_currents).
-struct CurArgs {
-  int mode, lsel;
-  float *out;
-  size_t slot_stride; // mode 0 only
-  int reserved;
+struct FwdCallbacks {
+  void *ctx;
+  hipError_t (*layer_tile_done)(void *ctx, int layer, int t_end);
 };
+struct SeqJob { int l, t0, t1, t_tile; const float *iin; };
+struct SeqJobs { SeqJob j[SNN_MAXL]; int count; };
+struct CurJob { int mode, lsel, t0, nsteps, t_base; float *out; size_t slot_stride; };
+struct CurJobs { CurJob j[SNN_MAXL + 1]; int count; };
+hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
+                          double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s,
+                          const SpanHook *hook = nullptr, const FwdCallbacks *cb = nullptr);
 // Recompute pass over steps t0+1..t1 from state_in = x_{t0}, spikes read from the stored bitmasks:
 // currents of the whole range in parallel into buf (slot of x_t = t - t_base - 1), then a scan that
 // turns them into states in place (store_all) and/or writes x_{t1} to state_out.
@@ -133,7 +136,7 @@ struct Plan {
   int chunk_len;      // slots of the chunk buffer (trajectory length for STANDARD)
   int n_local_ckpt;   // HBM checkpoints (CHUNK: ceil(T/F); DOUBLE: fine checkpoints per segment)
   int n_load_slots;   // HBM slots receiving host checkpoints (prefetch double buffer)
-  int n_stage_slots;  // HBM slots staging device->host copies
+  int n_stage_slots;  // HBM slots staging device->host copies (layers are pipelined, see launch_forward)
   int n_remote;       // host slots
   int local_slots() const { return chunk_len + n_local_ckpt + n_load_slots + n_stage_slots; }
 };

@@ -129,10 +129,13 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
 // presynaptic neuron, no memory traffic in the loop, one barrier per step.
 template <int NW>
 __global__ void __launch_bounds__(256)
-k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, StoreSpec st,
-               const float *__restrict__ iin, int t_tile) {
+k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st) {
   constexpr int NWD = NW / 64;
   __shared__ uint64_t sw[2][NWD];
+  // blockIdx.y selects the (layer, tile) this workgroup runs: layers are pipelined one tile apart
+  const int l = jobs.j[blockIdx.y].l, t0 = jobs.j[blockIdx.y].t0, t1 = jobs.j[blockIdx.y].t1;
+  const int t_tile = jobs.j[blockIdx.y].t_tile;
+  const float *__restrict__ iin = jobs.j[blockIdx.y].iin;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
   const int b = blockIdx.x, i = threadIdx.x, lane = lane_id(), wave = i >> 6;
   const bool own = i < N;
@@ -187,9 +190,11 @@ k_layer_seq_rs(NetDev net, int l, int t0, int t1, float *__restrict__ state, Sto
 // rows of those neurons are gathered.  NPT neurons per thread; two barriers per step.
 template <int NPT>
 __global__ void __launch_bounds__(512)
-k_layer_seq_gather(NetDev net, int l, int t0, int t1, float *__restrict__ state, StoreSpec st,
-                   const float *__restrict__ iin, int t_tile) {
+k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st) {
   extern __shared__ __align__(16) unsigned char smem[];
+  const int l = jobs.j[blockIdx.y].l, t0 = jobs.j[blockIdx.y].t0, t1 = jobs.j[blockIdx.y].t1;
+  const int t_tile = jobs.j[blockIdx.y].t_tile;
+  const float *__restrict__ iin = jobs.j[blockIdx.y].iin;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
   uint64_t *words = (uint64_t *)smem;       // [Wd]
@@ -286,14 +291,17 @@ k_readout_scan(const float *__restrict__ iout, double *__restrict__ readout, int
 // ------------------------------------------------------------------------------------------
 template <int NPT>
 __global__ void __launch_bounds__(512)
-k_currents(NetDev net, int t0, int t_base, CurArgs ca) {
+k_currents(NetDev net, CurJobs jobs) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int tid = threadIdx.x, nt = blockDim.x, B = net.B;
+  const CurJob &ca = jobs.j[blockIdx.y];
+  if ((int)blockIdx.x >= ca.nsteps * B) return; // jobs of one launch may cover different numbers of steps
+  const int t0 = ca.t0, t_base = ca.t_base;
   const int t = t0 + 1 + (int)(blockIdx.x / B), b = (int)(blockIdx.x % B);
-  // mode 0: recompute, all layers (blockIdx.y), I_in + I_rec into the state slot of x_t
+  // mode 0: recompute, I_in + I_rec of layer ca.lsel into the state slot of x_t
   // mode 1: forward, feed-forward current I_in of layer ca.lsel into a [step][B][N] tile
   // mode 2: forward, readout current sum of W_out rows of the last layer's spikes, [step][B][O] tile
-  const int l = ca.mode == 0 ? (int)blockIdx.y : ca.lsel;
+  const int l = ca.lsel;
   int N, P, Wi, Wr;
   const float *W;
   const uint64_t *g_in, *g_rec = nullptr;
@@ -994,75 +1002,102 @@ hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, 
 }
 
 template <int NPT>
-static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, int t0, int t_base, const CurArgs &ca,
-                              hipStream_t s) {
-  hipLaunchKernelGGL((k_currents<NPT>), grid, dim3(nt), lds, s, net, t0, t_base, ca);
+static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, const CurJobs &jobs, hipStream_t s) {
+  hipLaunchKernelGGL((k_currents<NPT>), grid, dim3(nt), lds, s, net, jobs);
 }
-static hipError_t launch_currents(const NetDev &net, int t0, int t1, int t_base, const CurArgs &ca, hipStream_t s) {
+static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
+  if (jobs.count <= 0) return hipSuccess;
   const LaunchCfg c = forward_cfg(net);
-  const dim3 grid((unsigned)((size_t)(t1 - t0) * net.B), ca.mode == 0 ? net.L : 1);
+  int max_steps = 0;
+  for (int i = 0; i < jobs.count; ++i) max_steps = jobs.j[i].nsteps > max_steps ? jobs.j[i].nsteps : max_steps;
+  if (max_steps <= 0) return hipSuccess;
+  const dim3 grid((unsigned)((size_t)max_steps * net.B), jobs.count);
   const size_t lds = currents_lds(net);
   switch (c.npt) {
-    case 1: launch_currents_t<1>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
-    case 2: launch_currents_t<2>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
-    case 4: launch_currents_t<4>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
-    case 8: launch_currents_t<8>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
-    case 16: launch_currents_t<16>(net, grid, c.nt_neuron, lds, t0, t_base, ca, s); break;
+    case 1: launch_currents_t<1>(net, grid, c.nt_neuron, lds, jobs, s); break;
+    case 2: launch_currents_t<2>(net, grid, c.nt_neuron, lds, jobs, s); break;
+    case 4: launch_currents_t<4>(net, grid, c.nt_neuron, lds, jobs, s); break;
+    case 8: launch_currents_t<8>(net, grid, c.nt_neuron, lds, jobs, s); break;
+    case 16: launch_currents_t<16>(net, grid, c.nt_neuron, lds, jobs, s); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
-hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const StoreSpec &st, double *readout,
-                          int readout_init, float *work, hipStream_t s, const SpanHook *hook) {
-  if (t1 < t0) return hipErrorInvalidValue;
+// Forward pass over the tiles bounds[0] < bounds[1] < ... < bounds[n_tiles] (each at most
+// SNN_FWD_TILE steps).  The layers are pipelined one tile apart: in stage s, layer l runs tile s - l,
+// so the sequential kernels of all layers share one launch (blockIdx.y = layer) and so do the
+// parallel current kernels; a layer's feed-forward currents for a tile are computed in the stage
+// after the layer below finished that tile.
+hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
+                          double *readout, int readout_init, float *work, hipStream_t s, const SpanHook *hook,
+                          const FwdCallbacks *cb) {
+  if (n_tiles < 0) return hipErrorInvalidValue;
+  for (int k = 0; k < n_tiles; ++k)
+    if (bounds[k + 1] <= bounds[k] || bounds[k + 1] - bounds[k] > SNN_FWD_TILE) return hipErrorInvalidValue;
   auto hb = [&](int kind) { if (hook) hook->begin(hook->ctx, kind); };
   auto he = [&]() { if (hook) hook->end(hook->ctx); };
   const int B = net.B, O = net.n_out, L = net.L;
-  int nmax = 0;
-  for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
-  float *iin = work;                                          // [tile][B][N_l] of the layer being run
-  float *iout = work + (size_t)SNN_FWD_TILE * B * nmax;       // [tile][B][O]
+  float *iin[SNN_MAXL];
+  for (int l = 0; l < L; ++l) iin[l] = work + (size_t)SNN_FWD_TILE * B * net.off[l]; // [tile][B][N_l]
+  float *iout = work + (size_t)SNN_FWD_TILE * B * net.SN;                              // [tile][B][O]
   const LaunchCfg c = forward_cfg(net);
-  bool first = true;
-  for (int ta = t0; ta < t1; ta += SNN_FWD_TILE) {
-    const int tb = ta + SNN_FWD_TILE < t1 ? ta + SNN_FWD_TILE : t1;
+  for (int stage = 0; stage < n_tiles + L; ++stage) {
+    // ---- parallel part: feed-forward currents of every layer's next tile, readout currents ----
+    CurJobs cj{};
     for (int l = 0; l < L; ++l) {
-      const int N = net.N[l];
-      CurArgs ca{1, l, iin, 0, 0};
-      hb(5);
-      hipError_t e = launch_currents(net, ta, tb, ta, ca, s);
-      he();
-      if (e != hipSuccess) return e;
-      hb(4);
-      if (N <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B), dim3(64), 0, s, net, l, ta, tb, state, st, iin, ta);
-      else if (N <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B), dim3(128), 0, s, net, l, ta, tb, state, st, iin, ta);
-      else if (N <= 256) hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B), dim3(256), 0, s, net, l, ta, tb, state, st, iin, ta);
-      else {
-        const size_t lds = seq_gather_lds(net);
-        const dim3 grid(B), block(c.nt_neuron);
-#define SEQ_CASE(NPT_)                                                                                              \
-  case NPT_:                                                                                                         \
-    hipLaunchKernelGGL((k_layer_seq_gather<NPT_>), grid, block, lds, s, net, l, ta, tb, state, st, iin, ta);        \
-    break;
-        switch (c.npt) {
-          SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
-          default: return hipErrorInvalidValue;
-        }
-#undef SEQ_CASE
-      }
-      he();
-      e = hipGetLastError();
-      if (e != hipSuccess) return e;
+      const int k = stage - l;
+      if (k < 0 || k >= n_tiles) continue;
+      cj.j[cj.count++] = CurJob{1, l, bounds[k], bounds[k + 1] - bounds[k], bounds[k], iin[l], 0};
     }
-    CurArgs co{2, L, iout, 0, 0};
+    const int ko = stage - L; // tile whose last-layer spikes are complete
+    if (ko >= 0 && ko < n_tiles) cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], iout, 0};
     hb(5);
-    hipError_t e = launch_currents(net, ta, tb, ta, co, s);
+    hipError_t e = launch_currents(net, cj, s);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O, tb - ta, net.beta,
-                       (first && readout_init) ? 1 : 0);
+    if (ko >= 0 && ko < n_tiles)
+      hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O,
+                         bounds[ko + 1] - bounds[ko], net.beta, (ko == 0 && readout_init) ? 1 : 0);
     he();
-    first = false;
+    // ---- sequential part: all layers in one launch per kernel flavour --------------------------
+    SeqJobs rs{}, ga{};
+    int nw = 64;
+    for (int l = 0; l < L; ++l) {
+      const int k = stage - l;
+      if (k < 0 || k >= n_tiles) continue;
+      const SeqJob job{l, bounds[k], bounds[k + 1], bounds[k], iin[l]};
+      if (net.N[l] <= 256) { rs.j[rs.count++] = job; nw = net.N[l] > nw ? net.N[l] : nw; }
+      else ga.j[ga.count++] = job;
+    }
+    hb(4);
+    if (rs.count) {
+      if (nw <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B, rs.count), dim3(64), 0, s, net, rs, state, st);
+      else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
+      else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
+    }
+    if (ga.count) {
+      const size_t lds = seq_gather_lds(net);
+      const dim3 grid(B, ga.count), block(c.nt_neuron);
+#define SEQ_CASE(NPT_)                                                                               \
+  case NPT_:                                                                                          \
+    hipLaunchKernelGGL((k_layer_seq_gather<NPT_>), grid, block, lds, s, net, ga, state, st);          \
+    break;
+      switch (c.npt) {
+        SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
+        default: return hipErrorInvalidValue;
+      }
+#undef SEQ_CASE
+    }
+    he();
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (cb)
+      for (int l = 0; l < L; ++l) {
+        const int k = stage - l;
+        if (k < 0 || k >= n_tiles) continue;
+        e = cb->layer_tile_done(cb->ctx, l, bounds[k + 1]);
+        if (e != hipSuccess) return e;
+      }
   }
   return hipGetLastError();
 }
@@ -1070,8 +1105,9 @@ hipError_t launch_forward(const NetDev &net, int t0, int t1, float *state, const
 hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
   if (t1 <= t0) return hipErrorInvalidValue;
-  CurArgs ca{0, 0, buf, slot_stride, 0};
-  hipError_t e = launch_currents(net, t0, t1, t_base, ca, s);
+  CurJobs cj{};
+  for (int l = 0; l < net.L; ++l) cj.j[cj.count++] = CurJob{0, l, t0, t1 - t0, t_base, buf, slot_stride};
+  hipError_t e = launch_currents(net, cj, s);
   if (e != hipSuccess) return e;
   const size_t n = (size_t)net.B * net.SN;
   hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,

@@ -3,8 +3,10 @@
 // Checkpoints sit at multiples of the interval starting at x_0 (the zero initial state); the last
 // segment may be shorter; the coarse interval need not be a multiple of the fine one.  A segment
 // (a, b] recomputed from x_a yields x_{a+1..b} from the stored spikes.  State-slot counts are the
-// paper's closed forms (eq. M_Base, M_Standard, M_Remote, M_Double) plus, for the host tier, two
-// slots that receive prefetched checkpoints and two that stage device-to-host copies.
+// paper's closed forms (eq. M_Base, M_Standard, M_Remote, M_Double) plus, for the host tier, a second
+// slot for prefetched checkpoints and SNN_MAXL + 1 slots that stage device-to-host copies (the layers
+// of the forward pass are pipelined one tile apart, so up to SNN_MAXL segment ends are being
+// assembled while one is on its way to the host).
 #include <cmath>
 
 #include "snn_internal.h"
@@ -40,7 +42,7 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       q.F = 0;
       q.chunk_len = q.C;
       q.n_load_slots = 2;
-      q.n_stage_slots = 2;
+      q.n_stage_slots = SNN_MAXL + 1;
       q.n_remote = cdiv(T, q.C);
       break;
     case 3: // DOUBLE: host checkpoints every C, recomputed local checkpoints every F
@@ -51,7 +53,7 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       q.chunk_len = q.F;
       q.n_local_ckpt = cdiv(q.C, q.F) - 1; // the first fine checkpoint of a segment is the loaded coarse one
       q.n_load_slots = 2;
-      q.n_stage_slots = 2;
+      q.n_stage_slots = SNN_MAXL + 1;
       q.n_remote = cdiv(T, q.C);
       break;
     default:

@@ -54,15 +54,15 @@ def test_state_slots_follow_closed_forms(T, C, F):
     cd = lambda a, b: -(-a // b)
     assert snn.snn_state_slots(snn.SNN_STANDARD, T) == (T, 0)                        # M_Base
     assert snn.snn_state_slots(snn.SNN_CHUNK, T, 0, F) == (F + cd(T, F), 0)          # M_Standard
-    # host tier: the paper's count plus 3 staging slots (second prefetch slot, two D2H staging slots)
-    assert snn.snn_state_slots(snn.SNN_REMOTE, T, C, 0) == (C + 1 + 3, cd(T, C))     # M_Remote
-    assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 3, cd(T, C))  # M_Double
+    # host tier: the paper's count plus 6 staging slots (second prefetch slot, five D2H staging slots)
+    assert snn.snn_state_slots(snn.SNN_REMOTE, T, C, 0) == (C + 1 + 6, cd(T, C))     # M_Remote
+    assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 6, cd(T, C))  # M_Double
 
 
 def test_default_intervals_are_square_roots():
     assert snn.snn_state_slots(snn.SNN_CHUNK, 4096) == (64 + 64, 0)                  # chunk = sqrt(T) = 64
     n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 4096)
-    assert (n, r) == (8 + 8 + 3, 64)                                                 # C = 64, F = 8
+    assert (n, r) == (8 + 8 + 6, 64)                                                 # C = 64, F = 8
     n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 100000)
     assert r == math.ceil(100000 / 317)                                              # ceil(sqrt(1e5)) = 317
 
@@ -74,7 +74,7 @@ def test_bytes_required_accounting():
     for strat, C, F in [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 100, 10)]:
         slots, _ = snn.snn_state_slots(strat, 1000, C, F)
         chunk = {snn.SNN_STANDARD: 1000, snn.SNN_CHUNK: 32, snn.SNN_REMOTE: 32, snn.SNN_DOUBLE: 10}[strat]
-        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(chunk, 64) * 32 * (20 + 256) * 4
+        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(chunk * 32 * (20 + 256) * 4, 64 * 32 * (20 + 512) * 4)
     # invalid intervals
     assert snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, 1000, 10, 20) == 0
     assert snn.snn_state_slots(snn.SNN_CHUNK, 10, 0, 11) == (0, 0)
@@ -85,4 +85,4 @@ def test_double_local_memory_grows_like_fourth_root():
     for T in (256, 4096, 65536):
         Cc = int(round(T ** 0.5))
         Ff = int(round(Cc ** 0.5))
-        assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 3 == 2 * round(T ** 0.25)
+        assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 6 == 2 * round(T ** 0.25)
