@@ -486,18 +486,19 @@ k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int
     }
 }
 
-// Recurrent part, layers of up to 2*KH neurons: the recurrent matrix stays in registers for the
-// whole chunk.  Thread (j, h) keeps W_rec[j][h*KH .. h*KH+KH) (two threads per postsynaptic row, each
-// half of the reduction); dv_{t+1} is broadcast from LDS; per step 2*KH/2 fused multiply-adds per
-// thread and two barriers, no weight traffic at all.  One workgroup per batch element.
-template <int KH>
-__global__ void __launch_bounds__(512)
+// Recurrent part, layers of up to H*KH neurons: the recurrent matrix stays in registers for the
+// whole chunk.  Thread (j, h) keeps W_rec[j][h*KH .. h*KH+KH) (H threads per postsynaptic row, each a
+// slice of the reduction, partial sums combined in a fixed order); dv_{t+1} is broadcast from LDS;
+// no weight traffic at all in the time loop, two barriers per step.  One workgroup per batch
+// element.
+template <int KH, int H>
+__global__ void __launch_bounds__(1024)
 k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
              int ldu, float *__restrict__ carry, int carry_init) {
-  __shared__ __align__(16) float x[2][2 * KH];
-  __shared__ float part[256];
+  __shared__ __align__(16) float x[2][H * KH];
+  __shared__ float part[H][256];
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x;
-  const int NJ = blockDim.x >> 1, tid = threadIdx.x;
+  const int NJ = blockDim.x / H, tid = threadIdx.x;
   const int j = tid % NJ, h = tid / NJ;
   const bool own = h == 0 && j < N;
   float *cb = carry + (size_t)b * (SN + net.n_out) + off;
@@ -508,23 +509,24 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
     const int n = h * KH + q;
     w[q] = (j < N && n < N) ? net.W_recT[l][(size_t)n * N + j] : 0.0f; // = W_rec[j][n], coalesced over j
   }
-  for (int i = tid; i < 2 * KH; i += blockDim.x) {
+  for (int i = tid; i < H * KH; i += blockDim.x) {
     x[0][i] = (i < N && !carry_init) ? cb[i] : 0.0f;
     x[1][i] = 0.0f;
   }
   __syncthreads();
   int cur = 0;
   const size_t slot_stride = (size_t)B * SN;
+  auto up_term = [&](int t) -> float { return up[((size_t)(t - t_base - 1) * B + b) * ldu + j]; };
   float vt = 0.0f, upv = 0.0f;
   if (own && t1 > t0) {
     vt = vbuf[(size_t)(t1 - t_base - 1) * slot_stride + (size_t)b * SN + off + j];
-    upv = up[((size_t)(t1 - t_base - 1) * B + b) * ldu + j];
+    upv = up_term(t1);
   }
   for (int t = t1; t > t0; --t) {
     float vt_n = 0.0f, up_n = 0.0f; // operands of the next (earlier) step, in flight during the product
     if (own && t - 1 > t0) {
       vt_n = vbuf[(size_t)(t - 2 - t_base) * slot_stride + (size_t)b * SN + off + j];
-      up_n = up[((size_t)(t - 2 - t_base) * B + b) * ldu + j];
+      up_n = up_term(t - 1);
     }
     const float4 *xs = reinterpret_cast<const float4 *>(&x[cur][h * KH]);
     float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
@@ -537,11 +539,14 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
       a3 = fmaf(w[4 * q + 3], xv.w, a3);
     }
     const float p = (a0 + a1) + (a2 + a3);
-    if (h == 1 && j < 256) part[j] = p;
+    if (h > 0 && j < 256) part[h][j] = p;
     __syncthreads();
     if (own) {
+      float sacc = p;
+#pragma unroll
+      for (int q = 1; q < H; ++q) sacc = sacc + part[q][j];
       const float dn = x[cur][j];
-      const float ds = ((p + part[j]) + upv) - net.theta * dn;
+      const float ds = (sacc + upv) - net.theta * dn;
       const float d = 1.0f + net.k * fabsf(vt - net.theta);
       const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
       x[cur ^ 1][j] = dvt;
@@ -1149,8 +1154,12 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     const float *up = upbuf - s0 * B * N;
     if (N <= 256) {
       const int NJ = (N + 63) & ~63;
-      hipLaunchKernelGGL((k_adj_rec_rs<128>), dim3(B), dim3(2 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N, carry,
-                         carry_init);
+      if (N <= 128)
+        hipLaunchKernelGGL((k_adj_rec_rs<32, 4>), dim3(B), dim3(4 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+                           carry, carry_init);
+      else
+        hipLaunchKernelGGL((k_adj_rec_rs<64, 4>), dim3(B), dim3(4 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+                           carry, carry_init);
     } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
       const int NR = N <= 512 ? 64 : 128;
