@@ -33,13 +33,13 @@ ALU_F32_PEAK_TF = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
 
 # strategy parameters per benchmark configuration: (coarse, fine); budgets from the configurations
 STRATEGY_PARAMS = {
-    0: {"standard": (0, 0), "chunk": (0, 10), "remote": (10, 0), "double": (20, 5)},
-    1: {"standard": (0, 0), "chunk": (0, 32), "remote": (32, 0), "double": (100, 10)},
-    2: {"standard": (0, 0), "chunk": (0, 100), "remote": (100, 0), "double": (100, 10)},
-    3: {"standard": (0, 0), "chunk": (0, 316), "remote": (316, 0), "double": (316, 18)},
+    0: {"standard": (0, 0), "chunk": (0, 10), "remote": (10, 0), "double": (20, 5), "hier": (2, 10)},
+    1: {"standard": (0, 0), "chunk": (0, 32), "remote": (32, 0), "double": (100, 10), "hier": (4, 32)},
+    2: {"standard": (0, 0), "chunk": (0, 100), "remote": (100, 0), "double": (100, 10), "hier": (4, 100)},
+    3: {"standard": (0, 0), "chunk": (0, 316), "remote": (316, 0), "double": (316, 18), "hier": (4, 316)},
 }
 BUDGET = {2: 8 * 10**9, 3: 4 * 10**9}
-SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3}
+SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3, "hier": 4}  # hier: (nb_local, chunk)
 
 
 def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--no-long", action="store_true", help="skip the 10x-sequence-length comparison")
     ap.add_argument("--long-coarse", type=int, default=1000)
     ap.add_argument("--long-fine", type=int, default=100)
+    ap.add_argument("--long-reps", type=int, default=3)
+    ap.add_argument("--long-warmup", type=int, default=2)
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true")
     args = ap.parse_args()
@@ -184,6 +186,8 @@ def main():
     slots, rslots = snn.snn_state_slots(SID[args.strategy], w.T, C, F)
     sched = snn.snn_schedule(SID[args.strategy], w.T, C, F)
     n_bwd = max(1, sum(1 for o in sched if o[0] == "BACKWARD"))
+    if args.strategy == "hier":
+        rslots = 0  # forward tiles follow the checkpoint interval, not host segments
     n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
     n_tiles = sum(-(-(min((k + 1) * C, w.T) - k * C) // 64) for k in range(rslots)) if rslots else -(-w.T // 64)
     L = len(w.n_hidden)
@@ -259,16 +263,27 @@ def main():
             def step_long():
                 netl.snn_bind_inputs(xl, yl, T_long)
                 netl.snn_bptt(snn.SNN_DOUBLE, CL, FL, ref_budget, want_stats=False)
-            for _ in range(2):
+            for _ in range(args.long_warmup):
                 step_long()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            nrep = 3
+            nrep = args.long_reps
             for _ in range(nrep):
                 step_long()
             torch.cuda.synchronize()
             sec_long = (time.perf_counter() - t0) / nrep
-            sec_std = time_strategy("standard", max(3, args.steps // 4), 2) if args.strategy != "standard" else sec
+
+            def step_std():
+                net.snn_bind_inputs(x, y, w.T)
+                net.snn_bptt(snn.SNN_STANDARD, 0, 0, ref_budget, want_stats=False)
+            for _ in range(2):
+                step_std()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(max(3, args.steps // 4)):
+                step_std()
+            torch.cuda.synchronize()
+            sec_std = (time.perf_counter() - t0) / max(3, args.steps // 4)
             long_seq.update({"double_ms_per_step": round(sec_long * 1e3, 3),
                              "double_us_per_timestep": round(sec_long / T_long * 1e6, 4),
                              "standard_T": w.T, "standard_ms_per_step": round(sec_std * 1e3, 3),

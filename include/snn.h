@@ -13,6 +13,7 @@
  *   SNN_CHUNK     paper Section "Standard Checkpointing"        (eq. M_Standard, T_Standard)
  *   SNN_REMOTE    paper Section "Remote Checkpointing"          (eq. M_Remote, T_Remote)
  *   SNN_DOUBLE    paper Section "Double Checkpointing"          (eq. M_Double, T_Double, N_c)
+ *   SNN_HIER      paper Section "Hierarchical Checkpointing"    (eq. M_Hier, T_Hier)
  *
  * Model (layers l = 1..L, s^0 = input spikes, zero initial state, t = 1..T):
  *   I^l_t = sum_{j active in s^{l-1}_t} W_in^l[j,:] + sum_{j active in s^l_{t-1}} W_rec^l[j,:]
@@ -50,7 +51,7 @@ typedef enum {
   SNN_E_STATE = 5    /* call order violated (e.g. snn_bptt before inputs are bound) */
 } snn_status;
 
-typedef enum { SNN_STANDARD = 0, SNN_CHUNK = 1, SNN_REMOTE = 2, SNN_DOUBLE = 3 } snn_strategy;
+typedef enum { SNN_STANDARD = 0, SNN_CHUNK = 1, SNN_REMOTE = 2, SNN_DOUBLE = 3, SNN_HIER = 4 } snn_strategy;
 typedef enum { SNN_W_IN = 0, SNN_W_REC = 1, SNN_W_OUT = 2 } snn_tensor_kind;
 
 #define SNN_MAX_LAYERS 4
@@ -111,7 +112,8 @@ snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *la
  * recomputation) on the inputs bound by the last snn_forward/snn_bind_inputs.  Gradients stay in
  * the context (overwritten by each call) until snn_grads copies them out.
  *   STANDARD ignores both intervals; CHUNK uses fine_interval; REMOTE uses coarse_interval;
- *   DOUBLE needs 1 <= fine <= coarse <= T.  0 = default (coarse ceil(sqrt T), fine ceil(sqrt coarse),
+ *   DOUBLE needs 1 <= fine <= coarse <= T; HIER takes fine_interval = steps between checkpoints and
+ *   coarse_interval = nb_local, the number of checkpoints per host transfer.  0 = default (coarse ceil(sqrt T), fine ceil(sqrt coarse),
  *   fine ceil(sqrt T) for CHUNK: the square-root rules of the paper's Hyperparameter Study).
  *   hbm_budget_bytes caps activation storage (states + spike bitmasks + workspace, i.e.
  *   snn_bytes_required); 0 = unlimited.  Over budget -> SNN_E_BUDGET before anything is allocated. */
@@ -145,7 +147,8 @@ int32_t snn_state_slots(snn_strategy strategy, int32_t T, int32_t coarse_interva
                         int32_t *remote_slots);
 /* Writes the schedule of the plan as int32 triples (op, a, b), at most cap triples, and returns
  * the number of triples the full schedule has.  Ops: 1 SAVE_LOCAL c, 2 SAVE_REMOTE c, 3 LOAD_REMOTE c,
- * 4 REFWD1 (a,b], 5 KEEP_FINE c, 6 REFWD2 (a,b], 7 BACKWARD a..b (descending). */
+ * 4 REFWD1 (a,b], 5 KEEP_FINE c, 6 REFWD2 (a,b], 7 BACKWARD a..b (descending), 8 SAVE_BATCH (first
+ * checkpoint c, count), 9 LOAD_BATCH (first checkpoint c, count). */
 int64_t snn_schedule(snn_strategy strategy, int32_t T, int32_t coarse_interval, int32_t fine_interval,
                      int32_t *out_triples, int64_t cap);
 

@@ -21,11 +21,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "snn_oracle.c")
 
-STANDARD, CHUNK, REMOTE, DOUBLE = 0, 1, 2, 3
+STANDARD, CHUNK, REMOTE, DOUBLE, HIER = 0, 1, 2, 3, 4
 HEAVISIDE, SMOOTH = 0, 1
 
 EVENT_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1",
-               5: "KEEP_FINE", 6: "REFWD2", 7: "BACKWARD"}
+               5: "KEEP_FINE", 6: "REFWD2", 7: "BACKWARD", 8: "SAVE_BATCH", 9: "LOAD_BATCH"}
 
 
 def _lib_path(suffix: str) -> str:

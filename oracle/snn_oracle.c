@@ -63,6 +63,11 @@
  *             segment one is loaded, Re-Forward_1 rebuilds fine checkpoints every
  *             F steps, then Re-Forward_2 rebuilds each fine chunk which is then
  *             back-propagated (eq. M_Double, T_Double, N_c).
+ *   HIER      Section "Hierarchical Checkpointing": checkpoints every F steps are
+ *             moved to and from remote memory in batches of C = nb_local checkpoints
+ *             (one transfer per batch); the last batch never leaves local memory
+ *             (eq. M_Hier).  The paper's count of transfers is read from its prose:
+ *             one write and one read per batch except the last, N_c = 2 (batches - 1).
  *
  * All work is organised per batch element (forward, recompute and the adjoint
  * recurrence are independent across the batch; only weight gradients and the
@@ -90,7 +95,7 @@
 #define CAT(a, b) CAT_(a, b)
 #define FN(name) CAT(name, SUFFIX)
 
-enum { STRAT_STANDARD = 0, STRAT_CHUNK = 1, STRAT_REMOTE = 2, STRAT_DOUBLE = 3 };
+enum { STRAT_STANDARD = 0, STRAT_CHUNK = 1, STRAT_REMOTE = 2, STRAT_DOUBLE = 3, STRAT_HIER = 4 };
 enum { MODE_HEAVISIDE = 0, MODE_SMOOTH = 1 };
 
 /* schedule event codes written to the optional event log (batch element 0 only) */
@@ -101,7 +106,9 @@ enum {
   EV_REFWD1 = 4,      /* recompute (a, b], keeping only fine checkpoints           */
   EV_KEEP_FINE = 5,   /* a = c (fine checkpoint x_c kept during Re-Forward_1)      */
   EV_REFWD2 = 6,      /* recompute (a, b] into the chunk buffer                    */
-  EV_BACKWARD = 7     /* back-propagate steps a, a-1, ..., b  (a >= b)             */
+  EV_BACKWARD = 7,    /* back-propagate steps a, a-1, ..., b  (a >= b)             */
+  EV_SAVE_BATCH = 8,  /* a = first checkpoint index c of a batch written to remote, b = count */
+  EV_LOAD_BATCH = 9   /* a = first checkpoint index c of a batch read back, b = count        */
 };
 
 typedef struct {
@@ -323,6 +330,13 @@ static double bptt_one(const net_t *n, const spikes_t *sp, const int32_t *labels
     chunk = (REAL *)malloc((size_t)chunk_len * SN * sizeof(REAL));
     loaded = (REAL *)malloc((size_t)SN * sizeof(REAL));
     local_slots = (int64_t)chunk_len + 1; remote_slots = n_ckpt;
+  } else if (strat == STRAT_HIER) {
+    n_ckpt = cdiv(T, F); chunk_len = F; /* C = nb_local checkpoints per batch */
+    const int n_batches = cdiv(n_ckpt, C);
+    ckpt = (REAL *)malloc((size_t)C * SN * sizeof(REAL));                       /* the local batch */
+    chunk = (REAL *)malloc((size_t)chunk_len * SN * sizeof(REAL));
+    remote = (REAL *)malloc((size_t)(n_batches > 1 ? (n_batches - 1) * C : 1) * SN * sizeof(REAL));
+    local_slots = (int64_t)chunk_len + C; remote_slots = (int64_t)(n_batches - 1) * C;
   } else {
     n_ckpt = cdiv(T, C); chunk_len = F; n_fine = cdiv(C, F); /* fine[0] mirrors the loaded coarse one and is not counted twice */
     remote = (REAL *)malloc((size_t)n_ckpt * SN * sizeof(REAL));
@@ -343,6 +357,15 @@ static double bptt_one(const net_t *n, const spikes_t *sp, const int32_t *labels
     if (strat == STRAT_CHUNK && (t - 1) % F == 0) {
       memcpy(ckpt + (size_t)((t - 1) / F) * SN, x, (size_t)SN * sizeof(REAL));
       ev(elog, EV_SAVE_LOCAL, t - 1, 0);
+    }
+    if (strat == STRAT_HIER && (t - 1) % F == 0) {
+      const int k = (t - 1) / F, n_batches = cdiv(n_ckpt, C);
+      memcpy(ckpt + (size_t)(k % C) * SN, x, (size_t)SN * sizeof(REAL));
+      ev(elog, EV_SAVE_LOCAL, t - 1, 0);
+      if (k % C == C - 1 && k / C < n_batches - 1) { /* batch complete and not the last one: one transfer */
+        memcpy(remote + (size_t)(k / C) * C * SN, ckpt, (size_t)C * SN * sizeof(REAL));
+        st->remote_writes++; ev(elog, EV_SAVE_BATCH, (k / C) * C * F, C);
+      }
     }
     if ((strat == STRAT_REMOTE || strat == STRAT_DOUBLE) && (t - 1) % C == 0) {
       memcpy(remote + (size_t)((t - 1) / C) * SN, x, (size_t)SN * sizeof(REAL));
@@ -418,6 +441,26 @@ static double bptt_one(const net_t *n, const spikes_t *sp, const int32_t *labels
         ev(elog, EV_BACKWARD, e, s0 + 1);
         for (int t = e; t > s0; --t) { backward_step(n, sp, b, t, chunk + (size_t)(t - s0 - 1) * SN, g, &a, G); st->bwd_steps++; }
       }
+    } else if (strat == STRAT_HIER) {
+      const int n_batches = cdiv(n_ckpt, C);
+      for (int gb = n_batches - 1; gb >= 0; --gb) {
+        const int k_hi = imin((gb + 1) * C, n_ckpt) - 1;
+        if (gb < n_batches - 1) { /* the last batch is still in local memory */
+          memcpy(ckpt, remote + (size_t)gb * C * SN, (size_t)C * SN * sizeof(REAL));
+          st->remote_reads++; ev(elog, EV_LOAD_BATCH, gb * C * F, C);
+        }
+        for (int k = k_hi; k >= gb * C; --k) {
+          const int s0 = k * F, e = imin(s0 + F, T);
+          ev(elog, EV_REFWD2, s0, e);
+          for (int t = s0 + 1; t <= e; ++t) {
+            advance_state(n, sp, b, t, t == s0 + 1 ? ckpt + (size_t)(k % C) * SN : chunk + (size_t)(t - s0 - 2) * SN,
+                          chunk + (size_t)(t - s0 - 1) * SN, scratch, 0);
+            st->refwd2_steps++;
+          }
+          ev(elog, EV_BACKWARD, e, s0 + 1);
+          for (int t = e; t > s0; --t) { backward_step(n, sp, b, t, chunk + (size_t)(t - s0 - 1) * SN, g, &a, G); st->bwd_steps++; }
+        }
+      }
     } else { /* DOUBLE */
       for (int K = cdiv(T, C) - 1; K >= 0; --K) {
         const int s0 = K * C, e = imin((K + 1) * C, T);
@@ -480,7 +523,8 @@ int FN(oracle_bptt)(const oracle_cfg *cfg, const REAL *const *W_in, const REAL *
   if (cfg->strategy == STRAT_CHUNK && (cfg->F < 1 || cfg->F > T)) return 1;
   if (cfg->strategy == STRAT_REMOTE && (cfg->C < 1 || cfg->C > T)) return 1;
   if (cfg->strategy == STRAT_DOUBLE && (cfg->F < 1 || cfg->F > cfg->C || cfg->C > T)) return 1;
-  if (cfg->strategy < 0 || cfg->strategy > 3) return 1;
+  if (cfg->strategy == STRAT_HIER && (cfg->F < 1 || cfg->F > T || cfg->C < 1)) return 1;
+  if (cfg->strategy < 0 || cfg->strategy > 4) return 1;
   if (cfg->forced_states && (cfg->strategy != STRAT_STANDARD || !cfg->forced || !vtraj)) return 1;
 
   net_t n;

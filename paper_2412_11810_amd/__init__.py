@@ -14,13 +14,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsnn_mi355x.so")
 
-SNN_STANDARD, SNN_CHUNK, SNN_REMOTE, SNN_DOUBLE = 0, 1, 2, 3
+SNN_STANDARD, SNN_CHUNK, SNN_REMOTE, SNN_DOUBLE, SNN_HIER = 0, 1, 2, 3, 4
 SNN_W_IN, SNN_W_REC, SNN_W_OUT = 0, 1, 2
 SNN_OK, SNN_E_INVAL, SNN_E_BUDGET, SNN_E_HIP, SNN_E_HOSTMEM, SNN_E_STATE = range(6)
 SNN_MAX_LAYERS = 4
 STATUS_NAMES = ["SNN_OK", "SNN_E_INVAL", "SNN_E_BUDGET", "SNN_E_HIP", "SNN_E_HOSTMEM", "SNN_E_STATE"]
 OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5: "KEEP_FINE",
-            6: "REFWD2", 7: "BACKWARD"}
+            6: "REFWD2", 7: "BACKWARD", 8: "SAVE_BATCH", 9: "LOAD_BATCH"}
 
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",

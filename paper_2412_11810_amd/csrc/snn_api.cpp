@@ -11,6 +11,8 @@
 #include "../../include/snn.h"
 #include "snn_internal.h"
 
+#define SNN_BWD_TILE 256 // steps of the adjoint pass per launch group (bounds the per-chunk scratch)
+
 struct snn_ctx {
   snn_config cfg{};
   NetDev net{};
@@ -117,7 +119,7 @@ int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 size_t work_bytes(const NetDev &n, int chunk_len) {
   int nmax = 0;
   for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
-  const size_t bwd = (size_t)chunk_len * n.B * (n.n_out + nmax) * sizeof(float);
+  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (n.n_out + nmax) * sizeof(float);
   const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (n.n_out + n.SN) * sizeof(float); // currents of one tile, every layer
   return bwd > fwd ? bwd : fwd;
 }
@@ -512,12 +514,13 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   HIPCHK(c, launch_fill_zero(c->acc_out, (size_t)n.N[L - 1] * O * 8, s));
 
   // events for the host tier
-  hipEvent_t ev_load_ready[2] = {nullptr, nullptr}, ev_load_free[2] = {nullptr, nullptr};
+  const int n_load_ev = strategy == SNN_HIER ? p.n_local_ckpt / p.C : 2; // load slots (HIER: ring positions)
+  std::vector<hipEvent_t> ev_load_ready(n_load_ev, nullptr), ev_load_free(n_load_ev, nullptr);
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  bool load_used[2] = {false, false};
-  const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE;
+  std::vector<char> load_used(n_load_ev, 0);
+  const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE || strategy == SNN_HIER;
   if (remote) {
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < n_load_ev; ++i) {
       ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
       if (!ev_load_ready[i] || !ev_load_free[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
     }
@@ -531,14 +534,62 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   // ---- forward ------------------------------------------------------------------------------
   HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
-    StoreSpec sp{chunk, slot, 0, 1, 0, T};
+    StoreSpec sp{chunk, slot, 0, 1, 0, T, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T);
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0
-    StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1};
+    StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T);
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+  } else if (strategy == SNN_HIER) {
+    // Checkpoint k = x_{kF} goes to slot k mod 2*nb_local of a ring of two batches.  When every layer
+    // has passed the last checkpoint of a batch (and it is not the final batch), the batch travels to
+    // the host as one transfer; the ring half is reused two batches later.
+    const int NL = p.C, n_ckpt = (T + p.F - 1) / p.F, n_batches = (n_ckpt + NL - 1) / NL;
+    const int RB = p.n_local_ckpt / NL; // ring positions (batches)
+    struct Hier {
+      snn_ctx *c; const Plan *p; float *ring; size_t slot, Ms; int NL, RB, n_batches; hipStream_t s, cs;
+      std::vector<hipEvent_t> ready, freed; std::vector<char> busy; int waited_for; snn_stats *st;
+      static hipError_t done(void *self, int layer, int t_end) {
+        Hier &q = *static_cast<Hier *>(self);
+        const NetDev &n = q.c->net;
+        const int F = q.p->F, T = q.p->T;
+        hipError_t e = hipSuccess;
+        if (layer == 0) {
+          // the first checkpoint of batch g lands at step g*NL*F: before the tile that ends there is
+          // queued, the ring position it reuses (batch g - RB) must have left for the host
+          const int g = (t_end + F) / (q.NL * F);
+          if (g >= q.RB && g < q.n_batches && t_end < g * q.NL * F && q.waited_for < g && q.busy[g % q.RB]) {
+            e = hipStreamWaitEvent(q.s, q.freed[g % q.RB], 0);
+            q.waited_for = g;
+          }
+          if (e != hipSuccess) return e;
+        }
+        if (layer != n.L - 1 || t_end % F != 0 || t_end >= T) return e;
+        const int k = t_end / F; // checkpoint index just completed by every layer
+        if (k % q.NL != q.NL - 1 || k / q.NL >= q.n_batches - 1) return e;
+        const int g = k / q.NL, pos = g % q.RB;
+        e = hipEventRecord(q.ready[pos], q.s);
+        if (e == hipSuccess) e = hipStreamWaitEvent(q.cs, q.ready[pos], 0);
+        if (e == hipSuccess)
+          e = hipMemcpyAsync(q.c->host_ckpt + (size_t)g * q.NL * q.slot, q.ring + (size_t)pos * q.NL * q.slot,
+                             (size_t)q.NL * q.Ms, hipMemcpyDeviceToHost, q.cs);
+        if (e == hipSuccess) e = hipEventRecord(q.freed[pos], q.cs);
+        q.busy[pos] = 1;
+        q.st->n_d2h++; q.st->d2h_bytes += (int64_t)q.NL * (int64_t)q.Ms;
+        return e;
+      }
+    } hier{c, &p, lckpt, slot, Ms, NL, RB, n_batches, s, cs, {}, {}, {}, 0, &st};
+    for (int i = 0; i < RB; ++i) {
+      hier.ready.push_back(tm.get()); hier.freed.push_back(tm.get()); hier.busy.push_back(0);
+      if (!hier.ready.back() || !hier.freed.back()) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+    }
+    HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0 = checkpoint 0
+    StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1, RB * NL};
+    const FwdCallbacks cb{&hier, &Hier::done};
+    const std::vector<int> bounds = tile_bounds(0, T, p.F);
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
   } else {
     // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again.
     // Each layer's part of a coarse checkpoint x_{KC} is snapshotted into a staging slot right after
@@ -594,7 +645,25 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     st.n_h2d++; st.h2d_bytes += (int64_t)Ms;
     return e;
   };
-  if (remote) HIPCHK(c, issue_load(p.n_remote - 1, (p.n_remote - 1) & 1));
+  // HIER: one transfer brings a whole batch of nb_local checkpoints into a half of the ring
+  auto issue_batch_load = [&](int g) -> hipError_t {
+    const int half = g % n_load_ev;
+    hipError_t e = hipSuccess;
+    if (load_used[half]) e = hipStreamWaitEvent(cs, ev_load_free[half], 0);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(lckpt + (size_t)half * p.C * slot, c->host_ckpt + (size_t)g * p.C * slot, (size_t)p.C * Ms, hipMemcpyHostToDevice, cs);
+    if (e == hipSuccess) e = hipEventRecord(ev_load_ready[half], cs);
+    st.n_h2d++; st.h2d_bytes += (int64_t)p.C * (int64_t)Ms;
+    return e;
+  };
+  const int hier_batches = strategy == SNN_HIER ? (((T + p.F - 1) / p.F) + p.C - 1) / p.C : 0;
+  int hier_cur = hier_batches - 1; // batch whose ring half the chunks are reading
+  if (strategy == SNN_HIER) {
+    // the final batch is still in its ring half; the one before it can start travelling back now,
+    // as soon as the forward pass no longer needs the other half (its last device->host copy is
+    // ordered before this on the copy stream)
+    if (hier_batches >= 2) HIPCHK(c, issue_batch_load(hier_batches - 2));
+  } else if (remote) HIPCHK(c, issue_load(p.n_remote - 1, (p.n_remote - 1) & 1));
   for (size_t i = 0; i < ops.size(); ++i) {
     const SchedOp &op = ops[i];
     switch (op.op) {
@@ -603,7 +672,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         if (n_loads > 0) {
           // the segment that used the previous slot is fully queued: mark that slot reusable
           HIPCHK(c, hipEventRecord(ev_load_free[cur_load], s));
-          load_used[cur_load] = true;
+          load_used[cur_load] = 1;
         }
         cur_load = K & 1;
         seg_start = op.a;
@@ -612,6 +681,16 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         // prefetch the next (earlier) coarse checkpoint into the other slot, overlapped with this
         // segment's recomputation and backward pass
         if (K > 0) HIPCHK(c, issue_load(K - 1, (K - 1) & 1));
+        break;
+      }
+      case OP_LOAD_BATCH: {
+        const int g = op.a / (p.C * p.F);
+        // every chunk of the batch processed before this one is queued: its ring half may be reused
+        HIPCHK(c, hipEventRecord(ev_load_free[hier_cur % n_load_ev], s));
+        load_used[hier_cur % n_load_ev] = 1;
+        hier_cur = g;
+        HIPCHK(c, hipStreamWaitEvent(s, ev_load_ready[g % n_load_ev], 0));
+        if (g > 0) HIPCHK(c, issue_batch_load(g - 1));
         break;
       }
       case OP_REFWD1: {
@@ -629,6 +708,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       case OP_REFWD2: {
         const float *src;
         if (strategy == SNN_CHUNK) src = lckpt + (size_t)(op.a / p.F) * slot;
+        else if (strategy == SNN_HIER) src = lckpt + (size_t)((op.a / p.F) % p.n_local_ckpt) * slot;
         else if (strategy == SNN_REMOTE || op.a == seg_start) src = loadb + (size_t)cur_load * slot;
         else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
         chunk_base = op.a;
@@ -639,29 +719,35 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         break;
       }
       case OP_BACKWARD: {
-        const int t1 = op.a, t0 = op.b - 1;
+        // long spans (Standard: the whole sequence) are walked in tiles of SNN_BWD_TILE steps so that
+        // the per-chunk scratch stays small; neither the adjoint recurrence (carried state) nor the
+        // weight-gradient accumulation (continued per element) depends on where the cuts fall
         const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
-        HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, c->dubuf, c->g, c->carry, first_adjoint ? 1 : 0,
-                                 c->dubuf + (size_t)p.chunk_len * B * O, c->ws, s, &hk));
-        first_adjoint = false;
-        tm.begin(3);
-        if (c->dw_event_driven || B > 128) {
-          HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, c->dubuf, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
-          for (int l = 0; l < L; ++l) {
-            HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
-            HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
+        for (int t1 = op.a; t1 >= op.b; t1 -= SNN_BWD_TILE) {
+          const int t0 = std::max(op.b - 1, t1 - SNN_BWD_TILE);
+          float *du = c->dubuf - (size_t)(t0 - base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
+          float *upb = c->dubuf + (size_t)std::min(p.chunk_len, SNN_BWD_TILE) * B * O;
+          HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, du, c->g, c->carry, first_adjoint ? 1 : 0, upb, c->ws, s, &hk));
+          first_adjoint = false;
+          tm.begin(3);
+          if (c->dw_event_driven || B > 128) {
+            HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, du, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
+            for (int l = 0; l < L; ++l) {
+              HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
+              HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
+            }
+          } else {
+            DwBatch db{};
+            db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, du, (size_t)B * O, O, 0, c->acc_out, 0, 0};
+            for (int l = 0; l < L; ++l) {
+              db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], chunk, slot, SN, n.off[l], c->acc_in[l], 0, 0};
+              db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], chunk, slot, SN, n.off[l], c->acc_rec[l], 0, 0};
+            }
+            HIPCHK(c, launch_dw_mfma(db, B, t0, t1, base, s));
           }
-        } else {
-          DwBatch db{};
-          db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, c->dubuf, (size_t)B * O, O, 0, c->acc_out, 0, 0};
-          for (int l = 0; l < L; ++l) {
-            db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], chunk, slot, SN, n.off[l], c->acc_in[l], 0, 0};
-            db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], chunk, slot, SN, n.off[l], c->acc_rec[l], 0, 0};
-          }
-          HIPCHK(c, launch_dw_mfma(db, B, t0, t1, base, s));
+          tm.end();
+          st.bwd_steps += t1 - t0;
         }
-        tm.end();
-        st.bwd_steps += t1 - t0;
         break;
       }
       default:

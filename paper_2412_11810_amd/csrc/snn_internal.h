@@ -35,6 +35,7 @@ struct StoreSpec {
   int interval;       // ... when (t - t_base) % interval == 0
   int slot0;
   int t_max;          // ... and t <= t_max
+  int slot_mod;       // if > 0 the slot index is taken modulo this (ring of checkpoint slots)
 };
 
 // Optional timing hook: the launchers bracket groups of kernels of one kind (HIP events on the
@@ -129,7 +130,7 @@ bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len);
 
 // ---- schedule / budget logic (snn_schedule.cpp; plain host code) --------------------------
 enum { OP_SAVE_LOCAL = 1, OP_SAVE_REMOTE = 2, OP_LOAD_REMOTE = 3, OP_REFWD1 = 4, OP_KEEP_FINE = 5,
-       OP_REFWD2 = 6, OP_BACKWARD = 7 };
+       OP_REFWD2 = 6, OP_BACKWARD = 7, OP_SAVE_BATCH = 8, OP_LOAD_BATCH = 9 };
 struct SchedOp { int op, a, b; };
 struct Plan {
   int strategy, T, C, F;

@@ -177,8 +177,11 @@ k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st
       sw[cur ^ 1][wave] = word;
       if (wave < Wd) mrow[(size_t)t * mstride] = word;
     }
-    if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
-      st.base[(size_t)((t - st.t_base) / st.interval - 1 + st.slot0) * st.slot_stride + (size_t)b * SN + off + i] = v;
+    if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
+      int sl = (t - st.t_base) / st.interval - 1 + st.slot0;
+      if (st.slot_mod > 0) sl %= st.slot_mod;
+      st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
+    }
     __syncthreads();
     cur ^= 1;
   }
@@ -221,8 +224,10 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   const size_t istride = (size_t)B * N;
   for (int t = t0 + 1; t <= t1; ++t) {
     int store_slot = -1;
-    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0)
+    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
       store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
+      if (st.slot_mod > 0) store_slot %= st.slot_mod;
+    }
     const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N;
     float in_t[NPT];
 #pragma unroll

@@ -56,6 +56,20 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       q.n_stage_slots = SNN_MAXL + 1;
       q.n_remote = cdiv(T, q.C);
       break;
+    case 4: { // HIER: checkpoints every F steps, moved to/from the host in batches of C = nb_local
+      q.F = F ? F : isqrt_ceil(T);
+      if (q.F > T) return false;
+      const int n_ckpt = cdiv(T, q.F);
+      q.C = C ? C : isqrt_ceil(n_ckpt);
+      if (q.C < 1) return false;
+      q.chunk_len = q.F;
+      // ring of batches: the one in use, the one in flight to/from the host, and enough more that the
+      // lowest layer of the pipelined forward pass never laps the top layer (up to SNN_MAXL - 1
+      // checkpoints behind)
+      q.n_local_ckpt = (2 + cdiv(SNN_MAXL - 1, q.C)) * q.C;
+      q.n_remote = (cdiv(n_ckpt, q.C) - 1) * q.C;
+      break;
+    }
     default:
       return false;
   }
@@ -110,6 +124,22 @@ int64_t snn_make_schedule(const Plan &p, SchedOp *out, int64_t cap) {
         }
       }
       break;
+    case 4: {
+      const int n_ckpt = cdiv(T, p.F), n_batches = cdiv(n_ckpt, p.C);
+      for (int k = 0; k < n_ckpt; ++k) {
+        emit(OP_SAVE_LOCAL, k * p.F, 0);
+        if (k % p.C == p.C - 1 && k / p.C < n_batches - 1) emit(OP_SAVE_BATCH, (k / p.C) * p.C * p.F, p.C);
+      }
+      for (int g = n_batches - 1; g >= 0; --g) {
+        if (g < n_batches - 1) emit(OP_LOAD_BATCH, g * p.C * p.F, p.C);
+        for (int k = imin((g + 1) * p.C, n_ckpt) - 1; k >= g * p.C; --k) {
+          const int a = k * p.F, e = imin(a + p.F, T);
+          emit(OP_REFWD2, a, e);
+          emit(OP_BACKWARD, e, a + 1);
+        }
+      }
+      break;
+    }
   }
   return n;
 }

@@ -85,7 +85,12 @@ def generate(w: Workload, dtype=np.float32) -> dict:
             m = (rng.random((n, n)) < w.rec_density).astype(np.uint8)
             rec_mask.append(m)
             W_rec[l] = W_rec[l] * m.astype(dtype)
-    in_spikes = (rng.random((w.T, w.B, w.n_in)) < w.p_in).astype(np.uint8)
+    # drawn in blocks of time steps (same stream as one big draw, bounded temporary memory)
+    in_spikes = np.empty((w.T, w.B, w.n_in), dtype=np.uint8)
+    blk = max(1, (1 << 24) // max(1, w.B * w.n_in))
+    for t0 in range(0, w.T, blk):
+        t1 = min(w.T, t0 + blk)
+        in_spikes[t0:t1] = rng.random((t1 - t0, w.B, w.n_in)) < w.p_in
     labels = rng.integers(0, w.n_out, size=w.B).astype(np.int32)
     return dict(W_in=W_in, W_rec=W_rec, W_out=W_out, rec_mask=rec_mask,
                 in_spikes=in_spikes, labels=labels)

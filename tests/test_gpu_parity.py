@@ -136,14 +136,15 @@ def test_config0_all_strategies():
     _full_parity(synth.config(0), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 10), (snn.SNN_CHUNK, 0, 7),
                                    (snn.SNN_REMOTE, 10, 0), (snn.SNN_REMOTE, 13, 0), (snn.SNN_DOUBLE, 20, 5),
                                    (snn.SNN_DOUBLE, 17, 4), (snn.SNN_DOUBLE, 50, 1), (snn.SNN_CHUNK, 0, 50),
-                                   (snn.SNN_DOUBLE, 0, 0), (snn.SNN_CHUNK, 0, 0)], nthreads=1)
+                                   (snn.SNN_DOUBLE, 0, 0), (snn.SNN_CHUNK, 0, 0), (snn.SNN_HIER, 2, 5),
+                                   (snn.SNN_HIER, 1, 7), (snn.SNN_HIER, 3, 10), (snn.SNN_HIER, 0, 0)], nthreads=1)
 
 
 def test_ragged_three_layer_net():
     """Layer widths that are not multiples of the wavefront, several words per layer, a ragged tail."""
     w = synth.Workload("ragged_70-100-72-130-7", 70, (100, 72, 130), 7, T=61, B=3, p_in=0.1, gain=0.5, seed=11)
-    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 9), (snn.SNN_REMOTE, 8, 0), (snn.SNN_DOUBLE, 16, 5)],
-                 nthreads=3)
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 9), (snn.SNN_REMOTE, 8, 0), (snn.SNN_DOUBLE, 16, 5),
+                     (snn.SNN_HIER, 2, 4), (snn.SNN_HIER, 1, 3)], nthreads=3)
 
 
 def test_masked_recurrent_weights():
@@ -161,7 +162,7 @@ def test_config1_full_size():
     """Configuration 1 at its full size (T = 1000, batch 32), the launch configuration the benchmark times:
     Standard, Chunk(32), Remote(32) as the configuration lists, plus Double."""
     _full_parity(synth.config(1), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0),
-                                   (snn.SNN_DOUBLE, 100, 10)], nthreads=8, check_states=True)
+                                   (snn.SNN_DOUBLE, 100, 10), (snn.SNN_HIER, 4, 32)], nthreads=8, check_states=True)
 
 
 def test_config3_width_reduced_length():
@@ -243,7 +244,8 @@ def test_graph_replay_matches_eager():
 
 
 @pytest.mark.parametrize("T,B,strat,C,F", [(1, 1, 0, 0, 0), (1, 2, 3, 1, 1), (2, 1, 2, 1, 0), (65, 2, 1, 0, 64),
-                                           (129, 1, 3, 64, 64), (130, 3, 2, 65, 0), (7, 5, 3, 7, 1)])
+                                           (129, 1, 3, 64, 64), (130, 3, 2, 65, 0), (7, 5, 3, 7, 1),
+                                           (130, 2, 4, 1, 3), (70, 1, 4, 2, 70), (33, 2, 4, 5, 2)])
 def test_degenerate_sizes(T, B, strat, C, F):
     """One step, one batch element, intervals equal to T or to 1, tile and segment boundaries that
     do not line up (the forward tile is 64 steps)."""

@@ -38,7 +38,8 @@ def test_schedule_matches_fig1_double_panel():
 @pytest.mark.parametrize("strategy,T,C,F", [
     (snn.SNN_STANDARD, 23, 0, 0), (snn.SNN_CHUNK, 23, 0, 5), (snn.SNN_CHUNK, 24, 0, 6), (snn.SNN_CHUNK, 7, 0, 7),
     (snn.SNN_REMOTE, 23, 4, 0), (snn.SNN_REMOTE, 9, 9, 0), (snn.SNN_DOUBLE, 23, 7, 3), (snn.SNN_DOUBLE, 50, 20, 6),
-    (snn.SNN_DOUBLE, 31, 10, 10), (snn.SNN_DOUBLE, 17, 17, 1), (snn.SNN_DOUBLE, 40, 9, 2)])
+    (snn.SNN_DOUBLE, 31, 10, 10), (snn.SNN_DOUBLE, 17, 17, 1), (snn.SNN_DOUBLE, 40, 9, 2),
+    (snn.SNN_HIER, 50, 2, 5), (snn.SNN_HIER, 23, 3, 4), (snn.SNN_HIER, 40, 1, 10), (snn.SNN_HIER, 30, 8, 5)])
 def test_schedule_equals_oracle_execution_order(strategy, T, C, F):
     """The library's schedule generator and the oracle were written separately; both must walk the
     same checkpoints in the same order."""
@@ -59,6 +60,16 @@ def test_state_slots_follow_closed_forms(T, C, F):
     assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 6, cd(T, C))  # M_Double
 
 
+def test_hierarchical_slots():
+    """M_Hier = chunk + nb_local (paper) plus the ring positions that keep the pipelined forward pass
+    and the host transfers from colliding: (1 + ceil(3/nb_local)) more batches."""
+    cd = lambda a, b: -(-a // b)
+    for T, NL, F in [(1000, 4, 25), (4096, 8, 64), (100, 1, 10), (100, 2, 10)]:
+        n_ckpt = cd(T, F)
+        extra = (1 + cd(3, NL)) * NL
+        assert snn.snn_state_slots(snn.SNN_HIER, T, NL, F) == (F + NL + extra, (cd(n_ckpt, NL) - 1) * NL)
+
+
 def test_default_intervals_are_square_roots():
     assert snn.snn_state_slots(snn.SNN_CHUNK, 4096) == (64 + 64, 0)                  # chunk = sqrt(T) = 64
     n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 4096)
@@ -74,7 +85,7 @@ def test_bytes_required_accounting():
     for strat, C, F in [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 100, 10)]:
         slots, _ = snn.snn_state_slots(strat, 1000, C, F)
         chunk = {snn.SNN_STANDARD: 1000, snn.SNN_CHUNK: 32, snn.SNN_REMOTE: 32, snn.SNN_DOUBLE: 10}[strat]
-        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(chunk * 32 * (20 + 256) * 4, 64 * 32 * (20 + 512) * 4)
+        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(min(chunk, 256) * 32 * (20 + 256) * 4, 64 * 32 * (20 + 512) * 4)
     # invalid intervals
     assert snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, 1000, 10, 20) == 0
     assert snn.snn_state_slots(snn.SNN_CHUNK, 10, 0, 11) == (0, 0)

@@ -229,7 +229,8 @@ def test_masked_recurrent_gradient():
 STRATS = [(oracle.STANDARD, 0, 0), (oracle.CHUNK, 0, 10), (oracle.CHUNK, 0, 7), (oracle.CHUNK, 0, 1),
           (oracle.CHUNK, 0, 50), (oracle.REMOTE, 10, 0), (oracle.REMOTE, 13, 0), (oracle.REMOTE, 50, 0),
           (oracle.DOUBLE, 20, 5), (oracle.DOUBLE, 17, 4), (oracle.DOUBLE, 50, 7), (oracle.DOUBLE, 6, 6),
-          (oracle.DOUBLE, 9, 1)]
+          (oracle.DOUBLE, 9, 1), (oracle.HIER, 2, 5), (oracle.HIER, 3, 7), (oracle.HIER, 1, 10), (oracle.HIER, 20, 4),
+          (oracle.HIER, 4, 50)]
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
@@ -325,6 +326,22 @@ def test_memory_and_time_closed_forms(T, C, F):
     assert (st["fwd_steps"], st["refwd2_steps"], st["bwd_steps"]) == (T, T, T)
     # the extra pass stops at the last fine checkpoint of each coarse segment
     assert st["refwd1_steps"] == (T // C) * (C - F)
+
+
+@pytest.mark.parametrize("T,F,NL", [(64, 4, 4), (100, 5, 2), (96, 8, 3), (60, 6, 10)])
+def test_hierarchical_closed_forms(T, F, NL):
+    """Section "Hierarchical Checkpointing": M_Hier = chunk + nb_local states in local memory; checkpoints
+    travel in batches of nb_local, the last batch never leaves local memory, so there are
+    nb_checkpoints/nb_local - 1 batch writes and as many batch reads (the reading of N_c that the
+    paper's prose gives); one recompute pass as in Standard Checkpointing."""
+    net = _tiny(9, T=T, B=1, hidden=(4,))
+    st = _run(net, strategy=oracle.HIER, coarse=NL, fine=F).stats
+    n_ckpt = -(-T // F)
+    batches = -(-n_ckpt // NL)
+    assert st["local_slots"] == F + NL
+    assert st["remote_writes"] == batches - 1 and st["remote_reads"] == batches - 1
+    assert st["remote_slots"] == (batches - 1) * NL
+    assert (st["fwd_steps"], st["refwd1_steps"], st["refwd2_steps"], st["bwd_steps"]) == (T, 0, T, T)
 
 
 def test_sqrt_rules_minimise_local_memory():
