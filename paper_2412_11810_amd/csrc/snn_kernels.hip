@@ -997,10 +997,10 @@ bool snn_kernel_shape_ok(const NetDev &net, char *why, size_t why_len) {
   for (int l = 0; l < net.L; ++l)
     if ((net.N[l] + c.npt - 1) / c.npt > c.nt_neuron) { snprintf(why, why_len, "layer too wide for the forward kernel (max %d neurons)", 512 * 16); return false; }
   if (net.Wd[0] > WAVE) { snprintf(why, why_len, "n_in > 4096 not supported"); return false; }
-  if (c.lds_bytes > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", c.lds_bytes, lds_max); return false; }
   if (seq_gather_lds(net) > lds_max) { snprintf(why, why_len, "forward kernel needs %zu B of LDS (> %zu)", seq_gather_lds(net), lds_max); return false; }
   if (currents_lds(net) > lds_max) { snprintf(why, why_len, "recompute kernel needs %zu B of LDS (> %zu)", currents_lds(net), lds_max); return false; }
-  if (adjoint_lds(net, 1024) > lds_max) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
+  // the streamed adjoint kernel may opt in to the full 160 KB of LDS of a gfx950 compute unit
+  if (adjoint_lds(net, 1024) > 160 * 1024) { snprintf(why, why_len, "adjoint kernel needs %zu B of LDS (> %zu)", adjoint_lds(net, 1024), lds_max); return false; }
   return true;
 }
 
@@ -1179,8 +1179,14 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
                            N, carry, carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
     } else {
       const int nt = 1024;
-      hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), ((size_t)2 * N + nt) * sizeof(float), s, net, l, t0, t1,
-                         vbuf, t_base, up, N, carry, carry_init);
+      const size_t lds = ((size_t)2 * N + nt) * sizeof(float);
+      if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_stream),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), lds, s, net, l, t0, t1, vbuf, t_base, up, N, carry,
+                         carry_init);
     }
     he();
   }

@@ -296,3 +296,11 @@ def test_config2_full_size_properties():
 def test_config3_full_size_properties():
     """Configuration 3 (128 -> 2x512 -> 10, T = 100 000, batch 16) under its 4 GB budget: Double(316, 18)."""
     _full_size_properties(3, [(snn.SNN_DOUBLE, 316, 18), (snn.SNN_CHUNK, 0, 316)], 4 * 10**9, 1500)
+
+
+def test_config4_widths_short():
+    """Configuration 4's layer widths (1024 -> 4 x 8192 -> 100, recurrent matrices 90 % zero with a
+    per-seed mask) at a short T and small batch: 16 neurons per thread in the gather kernels, the
+    streamed adjoint kernel, masked gradients."""
+    w = synth.config(4, T=6, B=2)
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 4, 2)], nthreads=2, check_states=True)
