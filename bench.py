@@ -106,6 +106,7 @@ def main():
     ap.add_argument("--long-reps", type=int, default=3)
     ap.add_argument("--long-warmup", type=int, default=2)
     ap.add_argument("--single", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="chunk-size / remote-chunk-size study (use with --T 4096)")
     ap.add_argument("--pmc-copy", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -147,6 +148,41 @@ def main():
         C, F = params[name]
         net.snn_bind_inputs(x, y, w.T)
         return net.snn_bptt(SID[name], C, F, budget, want_stats=stats)
+
+    if args.sweep:
+        # Hyper-parameter study (shape of the paper's Figs. 4-5): time per step and HBM state memory
+        # against the chunk size (Chunk, Remote), the number of checkpoints per transfer (Hier) and the
+        # remote chunk size with chunk = sqrt(remote chunk) (Double).
+        Ms = 4 * w.B * w.neurons
+        rows = []
+
+        def run(name, sid, C, F, reps=3):
+            net.snn_bind_inputs(x, y, w.T)
+            net.snn_bptt(sid, C, F, 0, want_stats=False)
+            net.snn_bptt(sid, C, F, 0, want_stats=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                net.snn_bind_inputs(x, y, w.T)
+                net.snn_bptt(sid, C, F, 0, want_stats=False)
+            torch.cuda.synchronize()
+            slots, rs = snn.snn_state_slots(sid, w.T, C, F)
+            rows.append({"strategy": name, "coarse": C, "fine": F, "ms_per_step": round((time.perf_counter() - t0) / reps * 1e3, 3),
+                         "state_slots_hbm": slots, "state_bytes_hbm": slots * Ms, "state_slots_host": rs})
+        run("standard", snn.SNN_STANDARD, 0, 0)
+        for F in (8, 16, 32, 64, 128, 256, 512):
+            run("chunk", snn.SNN_CHUNK, 0, F)
+        for Cc in (8, 16, 32, 64, 128, 256, 512):
+            run("remote", snn.SNN_REMOTE, Cc, 0)
+        for NL in (1, 2, 4, 8, 16):
+            run("hier", snn.SNN_HIER, NL, 64)
+        for Cc in (16, 64, 256, 1024, 4096):
+            run("double", snn.SNN_DOUBLE, Cc, max(1, int(round(Cc ** 0.5))))
+        for Ff in (2, 4, 8, 16, 32, 64):
+            run("double", snn.SNN_DOUBLE, 256, Ff)
+        print(json.dumps({"sweep": w.name, "T": w.T, "batch": w.B, "M_s_bytes": Ms, "rows": rows}))
+        net.snn_destroy()
+        return
 
     if args.single:
         step(args.strategy)
