@@ -13,8 +13,11 @@
 //     ascending) that does not depend on where chunk boundaries fall;
 //   * no floating-point atomics anywhere.
 #include "snn_internal.h"
+#include <stdlib.h>
+#include <string.h>
 
 #define WAVE 64
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
 static __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
@@ -342,6 +345,157 @@ k_currents(NetDev net, CurJobs jobs) {
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// A2 on the matrix cores: currents of 16 (t, b) rows x 64 postsynaptic neurons per wavefront.
+// acc[row][col] = fma(s[row][k], W[k][col], acc[row][col]) for k ascending, one K = 1 MFMA
+// (v_mfma_f32_16x16x1, four 16x16 blocks sharing the A column) per presynaptic neuron k.  With
+// s in {0, 1} every step is either acc + W[k][col] rounded once or acc unchanged, i.e. the ascending
+// sum over the active presynaptic neurons -- bit-identical to the gather (checked on the device for
+// normal and denormal operands).  A presynaptic neuron that is silent in all 16 rows is skipped
+// altogether (no row load, no MFMA): the 64-bit spike words of the 16 rows are OR-ed and the set bits
+// of the union expanded into an index list in LDS, so the kernel degrades gracefully from a dense
+// contraction (rates of tens of percent: the union is all ones) to a gather shared by 16 rows
+// (rates of a few percent).  One coalesced 256-byte row segment is loaded per MFMA.
+//   lane layout (verified on the device): A[i] in lane i (< 16, block 0 broadcast: cbsz = 2);
+//   B[col] in lane col; D[4*(lane/16) + (r%4)][16*(r/4) + lane%16] in register r.
+// mode 0 (recompute): workgroup = 2 row blocks x {feed-forward, recurrent} part, the two partial
+// currents are combined through LDS as I_in + I_rec; mode 1 (forward): 4 row blocks, I_in only.
+// ------------------------------------------------------------------------------------------
+
+// Contraction over the presynaptic neurons list[0..n_pad) (ascending; n_pad a multiple of U*D, the
+// entries past the real ones point at an all-zero spike word, so they multiply a valid row by 0 and
+// add +0: no change).  Row segments are fetched with buffer loads (scalar row offset, per-lane column
+// offset: no vector address arithmetic), U at a time, D - 1 groups ahead of the MFMAs that consume
+// them.
+template <int U, int D>
+static __device__ __forceinline__ void mfma_stream(const uint16_t *list, int n_pad, const uint32_t *myw32,
+                                                   __amdgpu_buffer_rsrc_t wres, uint32_t col4, int N, int P, int lane,
+                                                   v16f &acc) {
+  if (n_pad <= 0) return;
+  const int ng = n_pad / U;
+  float w[D][U];
+  uint32_t a[D][U]; // the 32-bit half word holding the row's bit for slot u; the bit is extracted at use
+  int sh[D][U];
+  auto issue = [&](int g, float (&wv)[U], uint32_t (&av)[U], int (&sv)[U]) {
+    int idx = g * U + (lane & (U - 1));
+    idx = idx < n_pad ? idx : n_pad - 1;
+    const int kv = list[idx];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = __builtin_amdgcn_readlane(kv, u);
+      const int kr = k < P ? k : P - 1;
+      wv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, col4, kr * N * 4, 0));
+      av[u] = myw32[k >> 5];
+      sv[u] = k & 31;
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < D - 1; ++s) issue(s, w[s], a[s], sh[s]);
+  for (int g = 0; g < ng; g += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
+      issue(g + j + D - 1, w[(j + D - 1) % D], a[(j + D - 1) % D], sh[(j + D - 1) % D]);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        acc = __builtin_amdgcn_mfma_f32_16x16x1f32((float)((a[j][u] >> sh[j][u]) & 1u), w[j][u], acc, 2, 0, 0);
+    }
+  }
+}
+
+// ws: 64-bit words per row of the LDS copy of the spike words (odd, > the widest presynaptic layer
+// of the launch in words: one extra all-zero word); lcap: entries of a wave's list.
+__global__ void __launch_bounds__(256)
+k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ float comb[2][16][64];
+  constexpr int U = 8, D = 4;
+  const CurJob &ca = jobs.j[blockIdx.y];
+  const int B = net.B, l = ca.lsel, N = net.N[l];
+  const int rows = ca.nsteps * B, ncb = (N + 63) >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
+  const int rb_per_wg = ca.mode == 0 ? 2 : 4;
+  const int n_rbg = (rows + 16 * rb_per_wg - 1) / (16 * rb_per_wg);
+  if ((int)blockIdx.x >= n_rbg * ncb) return;
+  const int cb = (int)blockIdx.x % ncb, rbg = (int)blockIdx.x / ncb;
+  const int part = ca.mode == 0 ? (wave & 1) : 0; // 0 feed-forward, 1 recurrent
+  const int rbi = ca.mode == 0 ? (wave >> 1) : wave;
+  const int m0 = (rbg * rb_per_wg + rbi) * 16;
+  const int m = m0 + (lane & 15);
+  const int pl = part == 0 ? l : l + 1;
+  const int Wp = net.Wd[pl];
+  const int P = part == 0 ? (l == 0 ? net.n_in : net.N[l - 1]) : N;
+  const float *W = part == 0 ? net.W_in[l] : net.W_rec[l];
+  const uint64_t *g = nullptr;
+  if (m < rows) {
+    const int t = ca.t0 + 1 + m / B, b = m % B;
+    g = net.mask[pl] + ((size_t)(part == 0 ? t : t - 1) * B + b) * Wp;
+  }
+  uint64_t *words = (uint64_t *)smem + (size_t)wave * 16 * ws;              // [16][ws]
+  uint16_t *list = (uint16_t *)((uint64_t *)smem + (size_t)4 * 16 * ws) + (size_t)wave * lcap;
+  // spike words of the 16 rows -> LDS (rows past the end are silent), plus one all-zero word per row
+  for (int wi = lane >> 4; wi < Wp; wi += 4) words[(lane & 15) * ws + wi] = g ? g[wi] : 0ull;
+  if (lane < 16) words[lane * ws + Wp] = 0ull;
+  __syncthreads();
+  // union of the 16 rows, one word per lane, expanded into the ascending list of its set bits
+  int n = 0;
+  for (int c0 = 0; c0 < Wp; c0 += 64) {
+    const int wi = c0 + lane;
+    uint64_t un = 0ull;
+    if (wi < Wp) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) un |= words[r * ws + wi];
+      const int rem = P - wi * 64;
+      if (rem < 64) un &= rem <= 0 ? 0ull : (1ull << rem) - 1ull;
+    }
+    const int nq = Wp - c0 < 64 ? Wp - c0 : 64;
+    for (int q = 0; q < nq; ++q) {
+      const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)un, q);
+      const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(un >> 32), q);
+      const uint64_t any = ((uint64_t)hi << 32) | lo;
+      if (any == 0ull) continue;
+      if ((any >> lane) & 1ull) list[n + __popcll(any & lanemask_lt())] = (uint16_t)((c0 + q) * 64 + lane);
+      n += __popcll(any);
+    }
+  }
+  // pad to whole rounds with entries that select the all-zero word
+  const int n_pad = n > 0 ? (n + U * D - 1) / (U * D) * (U * D) : 0;
+  if (n + lane < n_pad) list[n + lane] = (uint16_t)(Wp * 64 + (lane & 31));
+  __syncthreads();
+  const int col = cb * 64 + lane;
+  v16f acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  const __amdgpu_buffer_rsrc_t wres =
+      __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((size_t)P * N * sizeof(float)), 0x00027000);
+  mfma_stream<U, D>(list, n_pad, (const uint32_t *)(words + (lane & 15) * ws), wres,
+                    (uint32_t)(col < N ? col : 0) * 4u, N, P, lane, acc);
+  if (ca.mode == 0) {
+    if (part == 1) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) comb[rbi][r][lane] = acc[r];
+    }
+    __syncthreads();
+    if (part == 1) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = acc[r] + comb[rbi][r][lane];
+  }
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int mm = m0 + 4 * (lane >> 4) + rr;
+    if (mm >= rows) continue;
+    const int t = ca.t0 + 1 + mm / B, b = mm % B;
+    float *dst = ca.mode == 0
+                     ? ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
+                     : ca.out + ((size_t)(t - ca.t_base - 1) * B + b) * N;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c = cb * 64 + 16 * q + (lane & 15);
+      if (c < N) dst[c] = acc[4 * q + rr];
+    }
+  }
+}
+
 // B1, part 2: v_t = (alpha v_{t-1} - theta s_{t-1}) + I_t along a chunk, one thread per (b, neuron).
 // buf holds I_t at the slot of x_t on entry; with store_all the states replace the currents in
 // place, otherwise only the final state is written (state_out).  Same operations, in the same
@@ -449,46 +603,67 @@ k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restr
   *cb = d;
 }
 
-// C[m][j] = sum_k A[m*lda + k] * W[j*K + k]   (m < M rows = (slot, b) pairs, j < N, k ascending)
-__global__ void __launch_bounds__(256)
+// C[m][j] = sum_k A[m*lda + k] * W[j*K + k]   (m < M rows = (slot, b) pairs, j < N)
+// fp32 matrix cores (v_mfma_f32_32x32x2): a workgroup of WM x WN wavefronts owns a (32 WM) x (32 WN)
+// tile of C, each wavefront a 32 x 32 block.  K runs in tiles of 32 through LDS; the next tile's
+// global loads are in flight while the current one is multiplied.  The order of the additions per
+// element (k ascending in pairs) is fixed and independent of M, i.e. of how time is cut into chunks.
+//   lane layout (verified on the device): A[i][k] in lane i + 32k, B[k][j] in lane j + 32k,
+//   D[8*(r/4) + 4*(lane/32) + r%4][lane%32] in register r.
+template <int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN)
 k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
           int ldc, int M) {
-  __shared__ float As[16][68], Ws[16][68];
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  const int m0 = blockIdx.x * 64, j0 = blockIdx.y * 64;
-  float acc[4][4];
+  constexpr int NT = 64 * WM * WN, TM = 32 * WM, TN = 32 * WN, KT = 32;
+  constexpr int LA = TM * KT / NT, LW = TN * KT / NT;
+  __shared__ float As[TM][KT + 1], Ws[TN][KT + 1];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WM, wn = wave / WM;
+  const int m0 = blockIdx.x * TM, j0 = blockIdx.y * TN;
+  v16f acc;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  float ra[LA], rw[LW];
+  auto gload = [&](int k0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0f;
-  const int r = tid >> 2, kq = (tid & 3) * 4;
-  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = 0; i < LA; ++i) {
+      const int e = tid + i * NT, r = e / KT, kk = e % KT;
+      ra[i] = (m0 + r < M && k0 + kk < K) ? A[(size_t)(m0 + r) * lda + k0 + kk] : 0.0f;
+    }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int kk = kq + e;
-      As[kk][r] = (m0 + r < M && k0 + kk < K) ? A[(size_t)(m0 + r) * lda + k0 + kk] : 0.0f;
-      Ws[kk][r] = (j0 + r < N && k0 + kk < K) ? W[(size_t)(j0 + r) * K + k0 + kk] : 0.0f;
+    for (int i = 0; i < LW; ++i) {
+      const int e = tid + i * NT, r = e / KT, kk = e % KT;
+      rw[i] = (j0 + r < N && k0 + kk < K) ? W[(size_t)(j0 + r) * K + k0 + kk] : 0.0f;
+    }
+  };
+  gload(0);
+  for (int k0 = 0; k0 < K; k0 += KT) {
+#pragma unroll
+    for (int i = 0; i < LA; ++i) {
+      const int e = tid + i * NT;
+      As[e / KT][e % KT] = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < LW; ++i) {
+      const int e = tid + i * NT;
+      Ws[e / KT][e % KT] = rw[i];
     }
     __syncthreads();
+    if (k0 + KT < K) gload(k0 + KT);
 #pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-      float a[4], w[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; w[i] = Ws[kk][tx * 4 + i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    for (int kk = 0; kk < KT; kk += 2) {
+      const float a = As[wm * 32 + (lane & 31)][kk + (lane >> 5)];
+      const float b = Ws[wn * 32 + (lane & 31)][kk + (lane >> 5)];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
     }
     __syncthreads();
   }
+  const int j = j0 + wn * 32 + (lane & 31);
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int m = m0 + ty * 4 + i, jj = j0 + tx * 4 + j;
-      if (m < M && jj < N) C[(size_t)m * ldc + jj] = acc[i][j];
-    }
+  for (int r = 0; r < 16; ++r) {
+    const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    if (m < M && j < N) C[(size_t)m * ldc + j] = acc[r];
+  }
 }
 
 // Recurrent part, layers of up to H*KH neurons: the recurrent matrix stays in registers for the
@@ -642,9 +817,13 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
     }
     // ---- counting barrier over the workgroups of this batch group -------------------------
     // xg and bar live in uncached device memory: stores to them are visible to every other
-    // workgroup as soon as they are acknowledged, so waiting for this wave's own memory operations
-    // is all the release that is needed (no L2 write-back or invalidate per step).
+    // workgroup as soon as they are acknowledged, so each wave waiting for its own stores
+    // (s_waitcnt vmcnt(0), written out: a workgroup-scope fence does not emit it) before the
+    // workgroup barrier is all the release that is needed -- the arrival below is only counted
+    // once every wave of this workgroup has its slice of dv_t in memory.  No L2 write-back or
+    // invalidate per step.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
     __syncthreads();
     if (tid == 0 && !dead) {
       __hip_atomic_fetch_add(&bar[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -668,7 +847,10 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
       const float *src = xg + ((size_t)par * B + b0 + bb) * N + nb;
       float r[NR / 4];
 #pragma unroll
-      for (int i = 0; i < NR / 4; ++i) r[i] = (b0 + bb < B && nb + 32 * i < N) ? src[32 * i] : 0.0f;
+      for (int i = 0; i < NR / 4; ++i) // agent-scope loads: never served from this compute unit's L1
+        r[i] = (b0 + bb < B && nb + 32 * i < N)
+                   ? __hip_atomic_load(&src[32 * i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                   : 0.0f;
 #pragma unroll
       for (int i = 0; i < NR / 4; ++i)
         if (nb + 32 * i < N) xs[(size_t)(nb + 32 * i) * 8 + bb] = r[i];
@@ -1015,7 +1197,50 @@ template <int NPT>
 static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, const CurJobs &jobs, hipStream_t s) {
   hipLaunchKernelGGL((k_currents<NPT>), grid, dim3(nt), lds, s, net, jobs);
 }
+// SNN_CURRENTS=gather selects the event-by-event gather kernel for every current (the default runs
+// the feed-forward and recurrent currents on the matrix cores and only the narrow readout as a gather).
+static bool currents_use_mfma() {
+  static const bool v = [] {
+    const char *e = getenv("SNN_CURRENTS");
+    return !(e && strcmp(e, "gather") == 0);
+  }();
+  return v;
+}
+static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
+  if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
+  CurJobs mf{}, ga{};
+  unsigned gx = 0;
+  for (int i = 0; i < jobs.count; ++i) {
+    const CurJob &j = jobs.j[i];
+    if (j.nsteps <= 0) continue;
+    if (j.mode == 2) { ga.j[ga.count++] = j; continue; }
+    mf.j[mf.count++] = j;
+    const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? 2 : 4);
+    const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((net.N[j.lsel] + 63) / 64);
+    gx = n > gx ? n : gx;
+  }
+  if (mf.count) {
+    int pmax = 1;
+    for (int i = 0; i < mf.count; ++i) {
+      const int l = mf.j[i].lsel, p_in = l == 0 ? net.n_in : net.N[l - 1];
+      pmax = p_in > pmax ? p_in : pmax;
+      if (mf.j[i].mode == 0) pmax = net.N[l] > pmax ? net.N[l] : pmax;
+    }
+    const int ws = ((pmax + 63) / 64 + 1) | 1, lcap = ((pmax + 31) & ~31) + 32;
+    const size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
+    if (lds > 48 * 1024) {
+      const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_mfma),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (ea != hipSuccess) return ea;
+    }
+    hipLaunchKernelGGL(k_currents_mfma, dim3(gx, mf.count), dim3(256), lds, s, net, mf, ws, lcap);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return launch_currents_gather(net, ga, s);
+}
+static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (jobs.count <= 0) return hipSuccess;
   const LaunchCfg c = forward_cfg(net);
   int max_steps = 0;
@@ -1152,7 +1377,10 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     else { A = vbuf + s0 * ((size_t)B * SN) + net.off[l + 1]; lda = SN; K = net.N[l + 1]; W = net.W_in[l + 1]; }
     float *C = upbuf; // row m = (slot - s0)*B + b, ldc = N
     hb(6);
-    hipLaunchKernelGGL(k_up_gemm, dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
+      hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    else // small products: one wavefront per 32 x 32 block, so that more compute units take part
+      hipLaunchKernelGGL((k_up_gemm<1, 1>), dim3((M + 31) / 32, (N + 31) / 32), dim3(64), 0, s, A, lda, W, K, N, C, N, M);
     he();
     hb(2);
     // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
