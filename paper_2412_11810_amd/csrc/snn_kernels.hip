@@ -1002,8 +1002,16 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int Bp = (B + 3) & ~3;
   constexpr int COLS = 16 * NT, STRIDE = COLS + 16; // rows 16 banks apart: conflict-free operand reads
-  float *Pt = (float *)smem;                                   // [2][Bp][STRIDE]
-  uint64_t *Sw = (uint64_t *)(Pt + (size_t)2 * Bp * STRIDE);  // [2][Bp]
+  // staging: thread -> (row, 4 columns) of the P tile; 256 threads cover RPP rows per pass, 4 passes.
+  // A stage holds TS consecutive time steps (row = ts*Bp + b, step t_hi - ts): several steps of
+  // MFMAs per barrier, so that the global loads of the next stage (issued before the MFMAs of the
+  // current one) have time to arrive.
+  constexpr int TPR = COLS / 4;          // threads per row
+  constexpr int RPP = 256 / TPR;         // rows per pass
+  constexpr int ROWS = 4 * RPP;          // rows per stage
+  const int TS = ROWS / Bp;              // time steps per stage (>= 1: the launcher checks Bp <= ROWS)
+  float *Pt = (float *)smem;                                   // [2][ROWS][STRIDE]
+  uint64_t *Sw = (uint64_t *)(Pt + (size_t)2 * ROWS * STRIDE); // [2][ROWS]
   const int li = lane & 15, lk = lane >> 4;
 
   dvec4 acc[NT];
@@ -1015,59 +1023,103 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
       acc[q][r] = (j < d.n_pre && n < d.n_post) ? d.acc[(size_t)j * d.n_post + n] : 0.0;
     }
 
-  // staging: thread -> (row, 4 columns) of the P tile; 256 threads cover 256/(COLS/4) rows per pass
-  constexpr int TPR = COLS / 4;          // threads per row
-  constexpr int RPP = 256 / TPR;         // rows per pass
   const int srow = tid / TPR, scol = (tid % TPR) * 4;
-  const int passes = (Bp + RPP - 1) / RPP;
-  auto stage_load = [&](int t, float (&reg)[4][4], uint64_t &wreg) {
-    const float *prow = d.post + (size_t)(t - t_base - 1) * d.slot_stride + d.post_off + n0 + scol;
+  // rows of the stage that starts at step t_hi and covers nts steps.  stage_load only issues the
+  // loads -- unconditionally, from clamped (valid) addresses, so that all of them are in flight
+  // together while the MFMAs of the current stage run; stage_store zeroes what lies outside the
+  // stage (integer masks: a select would let the compiler move a load back under its condition)
+  // and writes the tile to LDS.
+  auto stage_load = [&](int t_hi, int nts, float (&reg)[4][4], uint64_t &wreg) {
 #pragma unroll
     for (int ps = 0; ps < 4; ++ps) {
-      const int b = srow + ps * RPP;
+      const int r = srow + ps * RPP, ts = r / Bp, b = r - ts * Bp;
+      const bool ok = ts < nts && b < B;
+      const float *prow = d.post + (size_t)(t_hi - (ok ? ts : 0) - t_base - 1) * d.slot_stride + d.post_off +
+                          (size_t)(ok ? b : 0) * d.post_stride;
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        reg[ps][c] = (ps < passes && b < B && n0 + scol + c < d.n_post) ? prow[(size_t)b * d.post_stride + c] : 0.0f;
-    }
-    wreg = 0;
-    if (tid < B) wreg = d.pre_mask[((size_t)(t - d.lag) * B + tid) * d.pre_words + (j0 >> 6)];
-  };
-  auto stage_store = [&](int buf, const float (&reg)[4][4], uint64_t wreg) {
-#pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
-      const int b = srow + ps * RPP;
-      if (ps < passes && b < Bp) {
-        float *dst = Pt + ((size_t)buf * Bp + b) * STRIDE + scol;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) dst[c] = reg[ps][c];
+      for (int c = 0; c < 4; ++c) {
+        const int n = n0 + scol + c;
+        reg[ps][c] = prow[n < d.n_post ? n : d.n_post - 1];
       }
     }
-    if (tid < Bp) Sw[(size_t)buf * Bp + tid] = wreg;
+    {
+      const int ts = tid / Bp, b = tid - ts * Bp;
+      const bool ok = tid < ROWS && ts < nts && b < B;
+      wreg = d.pre_mask[((size_t)(t_hi - (ok ? ts : 0) - d.lag) * B + (ok ? b : 0)) * d.pre_words + (j0 >> 6)];
+    }
+  };
+  auto stage_store = [&](int buf, int nts, const float (&reg)[4][4], uint64_t wreg) {
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps) {
+      const int r = srow + ps * RPP, ts = r / Bp, b = r - ts * Bp;
+      const bool ok = ts < nts && b < B;
+      float *dst = Pt + ((size_t)buf * ROWS + r) * STRIDE + scol;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        dst[c] = __uint_as_float(__float_as_uint(reg[ps][c]) & (0u - (uint32_t)(ok && n0 + scol + c < d.n_post)));
+    }
+    if (tid < ROWS) {
+      const int ts = tid / Bp, b = tid - ts * Bp;
+      Sw[(size_t)buf * ROWS + tid] = wreg & (0ull - (uint64_t)(ts < nts && b < B));
+    }
   };
 
   float reg[4][4];
   uint64_t wreg;
-  stage_load(t1, reg, wreg);
-  stage_store(0, reg, wreg);
+  int t_hi = t1;
+  int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
+  stage_load(t_hi, nts, reg, wreg);
+  stage_store(0, nts, reg, wreg);
   __syncthreads();
   int buf = 0;
-  for (int t = t1; t > t0; --t) {
-    if (t - 1 > t0) stage_load(t - 1, reg, wreg); // global loads in flight during the MFMAs
-    const float *P = Pt + (size_t)buf * Bp * STRIDE;
-    const uint64_t *S = Sw + (size_t)buf * Bp;
-    for (int b0 = 0; b0 < Bp; b0 += 4) {
-      const uint64_t word = S[b0 + lk];
-      const bool bit = (word >> (16 * w + li)) & 1ull;
-      if (__ballot(bit) == 0ull) continue;
-      const double a = bit ? 1.0 : 0.0;
-      const float *prow = P + (size_t)(b0 + lk) * STRIDE + li;
+  while (t_hi > t0) {
+    const int t_nx = t_hi - nts;
+    const int nts_nx = t_nx - t0 < TS ? t_nx - t0 : TS;
+    if (t_nx > t0) stage_load(t_nx, nts_nx, reg, wreg); // global loads in flight during the MFMAs
+    const float *P = Pt + (size_t)buf * ROWS * STRIDE;
+    const uint64_t *S = Sw + (size_t)buf * ROWS;
+    // (t descending, b ascending), 4 batch elements per K-step.  The operands of KU K-steps are read
+    // from LDS one group ahead of the MFMAs that use them (rows past the stage's last one hold zeros,
+    // and the buffer has a whole group of them to spare only when the stage is not full: the read
+    // of the group after the last is clamped to the last one and discarded).
+    constexpr int KU = 4;
+    const int nrows = nts * Bp;
+    uint64_t word[2][KU];
+    float pv[2][KU][NT];
+    auto fetch = [&](int r0, uint64_t (&wd)[KU], float (&p)[KU][NT]) {
+      const int rr = r0 < nrows ? r0 : nrows - 4 * KU < 0 ? 0 : ((nrows - 1) / (4 * KU)) * (4 * KU);
 #pragma unroll
-      for (int q = 0; q < NT; ++q)
-        acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)prow[16 * q], acc[q], 0, 0, 0);
+      for (int u = 0; u < KU; ++u) {
+        wd[u] = S[rr + 4 * u + lk];
+        const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + li;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) p[u][q] = prow[16 * q];
+      }
+    };
+    auto mma = [&](const uint64_t (&wd)[KU], const float (&p)[KU][NT]) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        const bool bit = (wd[u] >> (16 * w + li)) & 1ull;
+        if (__ballot(bit) == 0ull) continue;
+        const double a = bit ? 1.0 : 0.0;
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+          acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)p[u][q], acc[q], 0, 0, 0);
+      }
+    };
+    fetch(0, word[0], pv[0]);
+    for (int r0 = 0; r0 < nrows; r0 += 8 * KU) {
+      fetch(r0 + 4 * KU, word[1], pv[1]);
+      mma(word[0], pv[0]);
+      if (r0 + 4 * KU >= nrows) break;
+      fetch(r0 + 8 * KU, word[0], pv[0]);
+      mma(word[1], pv[1]);
     }
-    if (t - 1 > t0) stage_store(buf ^ 1, reg, wreg);
+    if (t_nx > t0) stage_store(buf ^ 1, nts_nx, reg, wreg);
     __syncthreads();
     buf ^= 1;
+    t_hi = t_nx;
+    nts = nts_nx;
   }
 #pragma unroll
   for (int q = 0; q < NT; ++q)
@@ -1447,14 +1499,15 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipS
   // wide tiles when they already fill the chip, narrow ones otherwise
   int tiles4 = 0;
   for (int i = 0; i < batch.count; ++i) tiles4 += ((batch.d[i].n_pre + 63) / 64) * ((batch.d[i].n_post + 63) / 64);
-  const int NT = (tiles4 >= 256 && Bp <= 64) ? 4 : 2;
+  const int NT = (tiles4 >= 256 && Bp <= 64) ? 4 : 2; // a stage holds 256 / NT rows of 16 * NT columns
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
     batch.d[i].tiles_n = (batch.d[i].n_post + 16 * NT - 1) / (16 * NT);
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
   }
-  const size_t lds = (size_t)2 * Bp * (16 * NT + 16) * sizeof(float) + (size_t)2 * Bp * 8;
+  const int rows = 256 / NT;
+  const size_t lds = (size_t)2 * rows * (16 * NT + 16) * sizeof(float) + (size_t)2 * rows * 8;
   if (NT == 4) hipLaunchKernelGGL((k_dw_mfma<4>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
   else hipLaunchKernelGGL((k_dw_mfma<2>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
   return hipGetLastError();
