@@ -120,7 +120,8 @@ size_t work_bytes(const NetDev &n, int chunk_len) {
   int nmax = 0;
   for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
   const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (n.n_out + nmax) * sizeof(float);
-  const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (n.n_out + n.SN) * sizeof(float); // currents of one tile, every layer
+  // currents of one tile of every layer + readout currents of SNN_RO_TILES tiles
+  const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + n.SN) * sizeof(float);
   return bwd > fwd ? bwd : fwd;
 }
 

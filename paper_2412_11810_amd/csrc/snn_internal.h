@@ -58,10 +58,11 @@ hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, 
                               hipStream_t s);
 // Forward pass (gather, LIF update, threshold, compaction, readout) over consecutive time tiles
 // bounds[0..n_tiles], each at most SNN_FWD_TILE steps.  state: [B][SN], x_{bounds[0]} on entry,
-// x_{bounds[n_tiles]} on return.  work: scratch of SNN_FWD_TILE * B * (SN + n_out) floats.
+// x_{bounds[n_tiles]} on return.  work: scratch of SNN_FWD_TILE * B * (SN + SNN_RO_TILES * n_out) floats.
 // layer_tile_done(layer, t_end) is called (on the host, in stream order) after the launch that
 // completes layer `layer` up to step t_end has been queued.
 #define SNN_FWD_TILE 64
+#define SNN_RO_TILES 8 // tiles of readout currents per launch of the readout scan
 struct FwdCallbacks {
   void *ctx;
   hipError_t (*layer_tile_done)(void *ctx, int layer, int t_end);

@@ -359,7 +359,8 @@ k_currents(NetDev net, CurJobs jobs) {
 //   lane layout (verified on the device): A[i] in lane i (< 16, block 0 broadcast: cbsz = 2);
 //   B[col] in lane col; D[4*(lane/16) + (r%4)][16*(r/4) + lane%16] in register r.
 // mode 0 (recompute): workgroup = 2 row blocks x {feed-forward, recurrent} part, the two partial
-// currents are combined through LDS as I_in + I_rec; mode 1 (forward): 4 row blocks, I_in only.
+// currents are combined through LDS as I_in + I_rec; mode 1 (forward): 4 row blocks, I_in only;
+// mode 2 (readout): like mode 1 with W_out and the last layer's spikes.
 // ------------------------------------------------------------------------------------------
 
 // Contraction over the presynaptic neurons list[0..n_pad) (ascending; n_pad a multiple of U*D, the
@@ -411,7 +412,8 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
   __shared__ float comb[2][16][64];
   constexpr int U = 8, D = 4;
   const CurJob &ca = jobs.j[blockIdx.y];
-  const int B = net.B, l = ca.lsel, N = net.N[l];
+  const bool ro = ca.mode == 2; // readout: W_out rows of the last layer's spikes, n_out columns
+  const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
   const int rows = ca.nsteps * B, ncb = (N + 63) >> 6;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
   const int rb_per_wg = ca.mode == 0 ? 2 : 4;
@@ -422,10 +424,10 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
   const int rbi = ca.mode == 0 ? (wave >> 1) : wave;
   const int m0 = (rbg * rb_per_wg + rbi) * 16;
   const int m = m0 + (lane & 15);
-  const int pl = part == 0 ? l : l + 1;
+  const int pl = (part == 0 && !ro) ? l : l + 1;
   const int Wp = net.Wd[pl];
-  const int P = part == 0 ? (l == 0 ? net.n_in : net.N[l - 1]) : N;
-  const float *W = part == 0 ? net.W_in[l] : net.W_rec[l];
+  const int P = ro ? net.N[l] : part == 0 ? (l == 0 ? net.n_in : net.N[l - 1]) : N;
+  const float *W = ro ? net.W_out : part == 0 ? net.W_in[l] : net.W_rec[l];
   const uint64_t *g = nullptr;
   if (m < rows) {
     const int t = ca.t0 + 1 + m / B, b = m % B;
@@ -1266,15 +1268,16 @@ static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStr
   for (int i = 0; i < jobs.count; ++i) {
     const CurJob &j = jobs.j[i];
     if (j.nsteps <= 0) continue;
-    if (j.mode == 2) { ga.j[ga.count++] = j; continue; }
     mf.j[mf.count++] = j;
     const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? 2 : 4);
-    const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((net.N[j.lsel] + 63) / 64);
+    const int ncols = j.mode == 2 ? net.n_out : net.N[j.lsel];
+    const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((ncols + 63) / 64);
     gx = n > gx ? n : gx;
   }
   if (mf.count) {
     int pmax = 1;
     for (int i = 0; i < mf.count; ++i) {
+      if (mf.j[i].mode == 2) { pmax = net.N[net.L - 1] > pmax ? net.N[net.L - 1] : pmax; continue; }
       const int l = mf.j[i].lsel, p_in = l == 0 ? net.n_in : net.N[l - 1];
       pmax = p_in > pmax ? p_in : pmax;
       if (mf.j[i].mode == 0) pmax = net.N[l] > pmax ? net.N[l] : pmax;
@@ -1329,6 +1332,8 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   for (int l = 0; l < L; ++l) iin[l] = work + (size_t)SNN_FWD_TILE * B * net.off[l]; // [tile][B][N_l]
   float *iout = work + (size_t)SNN_FWD_TILE * B * net.SN;                              // [tile][B][O]
   const LaunchCfg c = forward_cfg(net);
+  int ro_steps = 0, ro_tiles = 0;
+  bool ro_first = true;
   for (int stage = 0; stage < n_tiles + L; ++stage) {
     // ---- parallel part: feed-forward currents of every layer's next tile, readout currents ----
     CurJobs cj{};
@@ -1337,14 +1342,24 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
       if (k < 0 || k >= n_tiles) continue;
       cj.j[cj.count++] = CurJob{1, l, bounds[k], bounds[k + 1] - bounds[k], bounds[k], iin[l], 0};
     }
-    const int ko = stage - L; // tile whose last-layer spikes are complete
-    if (ko >= 0 && ko < n_tiles) cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], iout, 0};
+    // readout currents of the tile whose last-layer spikes are complete; they queue up in iout and
+    // the (cheap, sequential) leaky scan runs once per SNN_RO_TILES tiles
+    const int ko = stage - L;
+    if (ko >= 0 && ko < n_tiles)
+      cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], iout + (size_t)ro_steps * B * O, 0};
     hb(5);
     hipError_t e = launch_currents(net, cj, s);
     if (e != hipSuccess) return e;
-    if (ko >= 0 && ko < n_tiles)
-      hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O,
-                         bounds[ko + 1] - bounds[ko], net.beta, (ko == 0 && readout_init) ? 1 : 0);
+    if (ko >= 0 && ko < n_tiles) {
+      ro_steps += bounds[ko + 1] - bounds[ko];
+      if (++ro_tiles == SNN_RO_TILES || ko == n_tiles - 1) {
+        hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O, ro_steps,
+                           net.beta, (ro_first && readout_init) ? 1 : 0);
+        ro_first = false;
+        ro_steps = 0;
+        ro_tiles = 0;
+      }
+    }
     he();
     // ---- sequential part: all layers in one launch per kernel flavour --------------------------
     SeqJobs rs{}, ga{};
