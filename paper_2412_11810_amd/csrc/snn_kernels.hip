@@ -17,10 +17,32 @@
 #include <string.h>
 
 #define WAVE 64
+#define SNN_SEQ_GROUP 8 // steps whose per-step operands the sequential kernels load ahead in one go
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
 static __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+
+// acc = fma(x[lane n of the own 16-lane row], w[n], acc) for n = 0..15, one VOP2 instruction each:
+// the DPP row broadcast (row_newbcast:n) feeds lane n of every row to all 16 lanes of that row, so a
+// register whose lanes hold 16 consecutive operands replaces 16 scalar broadcasts.  The leading
+// s_nop covers the wait states a DPP read needs after a VALU write of its source or of EXEC (the
+// compiler does not see into the asm).  One accumulator: a strictly sequential chain.
+#define DPP_BC(n) " row_newbcast:" #n " row_mask:0xf bank_mask:0xf\n\t"
+#define FMAC16_1(acc, x, w, b)                                                                              \
+  asm volatile("s_nop 4\n\t"                                                                                \
+               "v_fmac_f32_dpp %0, %1, %2" DPP_BC(0) "v_fmac_f32_dpp %0, %1, %3" DPP_BC(1)                  \
+               "v_fmac_f32_dpp %0, %1, %4" DPP_BC(2) "v_fmac_f32_dpp %0, %1, %5" DPP_BC(3)                  \
+               "v_fmac_f32_dpp %0, %1, %6" DPP_BC(4) "v_fmac_f32_dpp %0, %1, %7" DPP_BC(5)                  \
+               "v_fmac_f32_dpp %0, %1, %8" DPP_BC(6) "v_fmac_f32_dpp %0, %1, %9" DPP_BC(7)                  \
+               "v_fmac_f32_dpp %0, %1, %10" DPP_BC(8) "v_fmac_f32_dpp %0, %1, %11" DPP_BC(9)                \
+               "v_fmac_f32_dpp %0, %1, %12" DPP_BC(10) "v_fmac_f32_dpp %0, %1, %13" DPP_BC(11)              \
+               "v_fmac_f32_dpp %0, %1, %14" DPP_BC(12) "v_fmac_f32_dpp %0, %1, %15" DPP_BC(13)              \
+               "v_fmac_f32_dpp %0, %1, %16" DPP_BC(14) "v_fmac_f32_dpp %0, %1, %17" DPP_BC(15)              \
+               : "+v"(acc)                                                                                  \
+               : "v"(x), "v"(w[b + 0]), "v"(w[b + 1]), "v"(w[b + 2]), "v"(w[b + 3]), "v"(w[b + 4]),         \
+                 "v"(w[b + 5]), "v"(w[b + 6]), "v"(w[b + 7]), "v"(w[b + 8]), "v"(w[b + 9]), "v"(w[b + 10]), \
+                 "v"(w[b + 11]), "v"(w[b + 12]), "v"(w[b + 13]), "v"(w[b + 14]), "v"(w[b + 15]))
 
 // ------------------------------------------------------------------------------------------
 // A1 (inputs): byte spikes [T][B][n_in] -> bit words mask0[t+1][b][w] (row 0 = step 0 = zeros)
@@ -126,15 +148,16 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
 
 // Sequential part, layers of up to NW neurons: the recurrent matrix stays in registers (thread i keeps
 // column i, W_rec[0..NW)[i]).  The previous step's spike words are shared through LDS; each lane turns
-// its own bit of every word into 0.0f/1.0f, v_readlane broadcasts spike j through a scalar register
-// and I_rec = fma(s_j, w_j, I_rec) runs over ascending j: fma(1, w, a) = a + w rounded once and
-// fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  Two instructions per
+// bits into 0.0f/1.0f (lane L of register g: spike 16g + L%16), a DPP row broadcast feeds spike j to
+// every lane and I_rec = fma(s_j, w_j, I_rec) runs over ascending j: fma(1, w, a) = a + w rounded once
+// and fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  One instruction per
 // presynaptic neuron, no memory traffic in the loop, one barrier per step.
 template <int NW>
 __global__ void __launch_bounds__(256)
 k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st) {
   constexpr int NWD = NW / 64;
   __shared__ uint64_t sw[2][NWD];
+  __shared__ float ring[SNN_SEQ_GROUP][NW];
   // blockIdx.y selects the (layer, tile) this workgroup runs: layers are pipelined one tile apart
   const int l = jobs.j[blockIdx.y].l, t0 = jobs.j[blockIdx.y].t0, t1 = jobs.j[blockIdx.y].t1;
   const int t_tile = jobs.j[blockIdx.y].t_tile;
@@ -154,39 +177,56 @@ k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st
   int cur = 0;
   const float *icol = iin + (size_t)b * N + i;
   const size_t istride = (size_t)B * N;
-  float in_next = (own && t1 > t0) ? icol[(size_t)(t0 - t_tile) * istride] : 0.0f;
-  for (int t = t0 + 1; t <= t1; ++t) {
-    const float in_t = in_next;
-    if (own && t < t1) in_next = icol[(size_t)(t - t_tile) * istride]; // next step's current, in flight
-    int sbits[NWD]; // lane j%64 of sbits[j/64] holds spike j of the previous step as a float
+  // The feed-forward currents of G steps are loaded one group ahead, parked in a thread-private
+  // column of an LDS ring when their group starts (the only point that waits for them) and read
+  // from there: no step waits on global memory.
+  constexpr int G = SNN_SEQ_GROUP;
+  float ri[G];
+  auto stage_issue = [&](int t_lo) { // steps t_lo + 1 .. t_lo + G (steps past the end re-read the last one)
 #pragma unroll
-    for (int q = 0; q < NWD; ++q) sbits[q] = ((sw[cur][q] >> lane) & 1ull) ? 0x3f800000 : 0;
-    float acc = 0.0f;
-#pragma unroll
-    for (int j0 = 0; j0 < NW; j0 += 16) { // 16 broadcasts, then 16 dependent fmas: no scalar-write stalls
-      float sj[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        sj[r] = __int_as_float(__builtin_amdgcn_readlane(sbits[(j0 + r) >> 6], (j0 + r) & 63));
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc = fmaf(sj[r], w[j0 + r], acc);
+    for (int k = 0; k < G; ++k) {
+      const int t = t_lo + 1 + k <= t1 ? t_lo + 1 + k : t1;
+      ri[k] = icol[(size_t)(t - 1 - t_tile) * istride];
     }
-    float a = net.alpha * v;
-    if (sprev) a = a - net.theta;
-    v = a + (in_t + acc);
-    sprev = own && v > net.theta;
-    const uint64_t word = __ballot(sprev);
-    if (lane == 0) {
-      sw[cur ^ 1][wave] = word;
-      if (wave < Wd) mrow[(size_t)t * mstride] = word;
+  };
+  // the weights are in registers from here on (otherwise the compiler, which cannot tell their loads
+  // from the staged ones, would wait for every outstanding load before each block of FMAs)
+  __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+  if (own && t1 > t0) stage_issue(t0);
+  for (int tg = t0; tg < t1; tg += G) {
+    if (own) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) ring[k][i] = ri[k];
+      if (tg + G < t1) stage_issue(tg + G);
     }
-    if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
-      int sl = (t - st.t_base) / st.interval - 1 + st.slot0;
-      if (st.slot_mod > 0) sl %= st.slot_mod;
-      st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
+    const int thi = tg + G < t1 ? tg + G : t1;
+    for (int t = tg + 1; t <= thi; ++t) {
+      const float in_t = own ? ring[t - tg - 1][i] : 0.0f;
+      // lane L of sb[g] holds spike 16g + L%16 of the previous step as 0.0f / 1.0f
+      float sb[NW / 16];
+#pragma unroll
+      for (int g = 0; g < NW / 16; ++g)
+        sb[g] = ((sw[cur][g >> 2] >> (16 * (g & 3) + (lane & 15))) & 1ull) ? 1.0f : 0.0f;
+      float acc = 0.0f;
+#pragma unroll
+      for (int g = 0; g < NW / 16; ++g) FMAC16_1(acc, sb[g], w, 16 * g);
+      float a = net.alpha * v;
+      if (sprev) a = a - net.theta;
+      v = a + (in_t + acc);
+      sprev = own && v > net.theta;
+      const uint64_t word = __ballot(sprev);
+      if (lane == 0) {
+        sw[cur ^ 1][wave] = word;
+        if (wave < Wd) mrow[(size_t)t * mstride] = word;
+      }
+      if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
+        int sl = (t - st.t_base) / st.interval - 1 + st.slot0;
+        if (st.slot_mod > 0) sl %= st.slot_mod;
+        st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
+      }
+      __syncthreads();
+      cur ^= 1;
     }
-    __syncthreads();
-    cur ^= 1;
   }
   if (own) state[(size_t)b * SN + off + i] = v;
 }
@@ -668,76 +708,102 @@ k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int
   }
 }
 
-// Recurrent part, layers of up to H*KH neurons: the recurrent matrix stays in registers for the
-// whole chunk.  Thread (j, h) keeps W_rec[j][h*KH .. h*KH+KH) (H threads per postsynaptic row, each a
-// slice of the reduction, partial sums combined in a fixed order); dv_{t+1} is broadcast from LDS;
-// no weight traffic at all in the time loop, two barriers per step.  One workgroup per batch
-// element.
-template <int KH, int H>
-__global__ void __launch_bounds__(1024)
+// Recurrent part, layers of up to 4*KH neurons: the recurrent matrix stays in registers for the
+// whole chunk.  Thread (jj, h) keeps W_rec[j][h*KH .. h*KH+KH) for the two postsynaptic rows
+// j = jj and j = jj + NJ2 (four threads per row, each a slice of the reduction; partial sums
+// combined in a fixed order).  dv_{t+1} is broadcast from LDS; every value read feeds two FMAs,
+// which halves the LDS traffic that bounds this kernel (all threads of a wavefront read the same
+// address).  No weight traffic and no waiting on global memory in the time loop (operands staged
+// G steps ahead), two barriers per step.  One workgroup per batch element, 4*NJ2 threads.
+template <int KH>
+__global__ void __launch_bounds__(512)
 k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
              int ldu, float *__restrict__ carry, int carry_init) {
-  __shared__ __align__(16) float x[2][H * KH];
-  __shared__ float part[H][256];
+  __shared__ __align__(16) float x[2][4 * KH];
+  __shared__ float part[4][256];
+  __shared__ float ring[2 * SNN_SEQ_GROUP][256];
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x;
-  const int NJ = blockDim.x / H, tid = threadIdx.x;
-  const int j = tid % NJ, h = tid / NJ;
-  const bool own = h == 0 && j < N;
+  const int NJ2 = blockDim.x >> 2, tid = threadIdx.x;
+  const int jj = tid % NJ2, h = tid / NJ2;
+  const int jA = jj, jB = jj + NJ2;
+  const int j = tid;                 // finalising role: the first 2*NJ2 threads own one row each
+  const bool own = tid < 2 * NJ2 && j < N;
   float *cb = carry + (size_t)b * (SN + net.n_out) + off;
 
-  float w[KH];
+  float wA[KH], wB[KH];
 #pragma unroll
   for (int q = 0; q < KH; ++q) {
     const int n = h * KH + q;
-    w[q] = (j < N && n < N) ? net.W_recT[l][(size_t)n * N + j] : 0.0f; // = W_rec[j][n], coalesced over j
+    wA[q] = (jA < N && n < N) ? net.W_recT[l][(size_t)n * N + jA] : 0.0f; // = W_rec[jA][n], coalesced over jj
+    wB[q] = (jB < N && n < N) ? net.W_recT[l][(size_t)n * N + jB] : 0.0f;
   }
-  for (int i = tid; i < H * KH; i += blockDim.x) {
+  for (int i = tid; i < 4 * KH; i += blockDim.x) {
     x[0][i] = (i < N && !carry_init) ? cb[i] : 0.0f;
     x[1][i] = 0.0f;
   }
   __syncthreads();
   int cur = 0;
   const size_t slot_stride = (size_t)B * SN;
-  auto up_term = [&](int t) -> float { return up[((size_t)(t - t_base - 1) * B + b) * ldu + j]; };
-  float vt = 0.0f, upv = 0.0f;
-  if (own && t1 > t0) {
-    vt = vbuf[(size_t)(t1 - t_base - 1) * slot_stride + (size_t)b * SN + off + j];
-    upv = up_term(t1);
-  }
-  for (int t = t1; t > t0; --t) {
-    float vt_n = 0.0f, up_n = 0.0f; // operands of the next (earlier) step, in flight during the product
-    if (own && t - 1 > t0) {
-      vt_n = vbuf[(size_t)(t - 2 - t_base) * slot_stride + (size_t)b * SN + off + j];
-      up_n = up_term(t - 1);
-    }
-    const float4 *xs = reinterpret_cast<const float4 *>(&x[cur][h * KH]);
-    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+  // Operand staging.  A global load issued in one step and used in the next would put most of a
+  // memory round trip into every step.  Instead the v_t and up_t of G steps are loaded into
+  // registers one group ahead (stage_issue), parked in a thread-private column of an LDS ring when
+  // their group starts (stage_park: the only point that waits for them, G steps after the issue),
+  // and read from there step by step.
+  constexpr int G = SNN_SEQ_GROUP;
+  float rv[G], ru[G];
+  auto stage_issue = [&](int t_hi) { // steps t_hi, t_hi - 1, ... (steps past the end re-read the last one)
 #pragma unroll
-    for (int q = 0; q < KH / 4; ++q) {
-      const float4 xv = xs[q];
-      a0 = fmaf(w[4 * q + 0], xv.x, a0);
-      a1 = fmaf(w[4 * q + 1], xv.y, a1);
-      a2 = fmaf(w[4 * q + 2], xv.z, a2);
-      a3 = fmaf(w[4 * q + 3], xv.w, a3);
+    for (int k = 0; k < G; ++k) {
+      const int t = t_hi - k > t0 ? t_hi - k : t0 + 1;
+      rv[k] = vbuf[(size_t)(t - t_base - 1) * slot_stride + (size_t)b * SN + off + j];
+      ru[k] = up[((size_t)(t - t_base - 1) * B + b) * ldu + j];
     }
-    const float p = (a0 + a1) + (a2 + a3);
-    if (h > 0 && j < 256) part[h][j] = p;
-    __syncthreads();
+  };
+  auto stage_park = [&]() {
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      ring[2 * k][j] = rv[k];
+      ring[2 * k + 1][j] = ru[k];
+    }
+  };
+  if (own) stage_issue(t1);
+  for (int tg = t1; tg > t0; tg -= G) {
     if (own) {
-      float sacc = p;
-#pragma unroll
-      for (int q = 1; q < H; ++q) sacc = sacc + part[q][j];
-      const float dn = x[cur][j];
-      const float ds = (sacc + upv) - net.theta * dn;
-      const float d = 1.0f + net.k * fabsf(vt - net.theta);
-      const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
-      x[cur ^ 1][j] = dvt;
-      vbuf[(size_t)(t - t_base - 1) * slot_stride + (size_t)b * SN + off + j] = dvt;
+      stage_park();
+      if (tg - G > t0) stage_issue(tg - G);
     }
-    __syncthreads();
-    cur ^= 1;
-    vt = vt_n;
-    upv = up_n;
+    const int tlo = tg - G > t0 ? tg - G : t0;
+    for (int t = tg; t > tlo; --t) {
+      const float4 *xs = reinterpret_cast<const float4 *>(&x[cur][h * KH]);
+      float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f, b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f;
+#pragma unroll
+      for (int q = 0; q < KH / 4; ++q) {
+        const float4 xv = xs[q];
+        a0 = fmaf(wA[4 * q + 0], xv.x, a0);
+        a1 = fmaf(wA[4 * q + 1], xv.y, a1);
+        a2 = fmaf(wA[4 * q + 2], xv.z, a2);
+        a3 = fmaf(wA[4 * q + 3], xv.w, a3);
+        b0 = fmaf(wB[4 * q + 0], xv.x, b0);
+        b1 = fmaf(wB[4 * q + 1], xv.y, b1);
+        b2 = fmaf(wB[4 * q + 2], xv.z, b2);
+        b3 = fmaf(wB[4 * q + 3], xv.w, b3);
+      }
+      part[h][jA] = (a0 + a1) + (a2 + a3);
+      part[h][jB] = (b0 + b1) + (b2 + b3);
+      __syncthreads();
+      if (own) {
+        const float vt = ring[2 * (tg - t)][j], upv = ring[2 * (tg - t) + 1][j];
+        const float sacc = ((part[0][j] + part[1][j]) + part[2][j]) + part[3][j];
+        const float dn = x[cur][j];
+        const float ds = (sacc + upv) - net.theta * dn;
+        const float d = 1.0f + net.k * fabsf(vt - net.theta);
+        const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+        x[cur ^ 1][j] = dvt;
+        vbuf[(size_t)(t - t_base - 1) * slot_stride + (size_t)b * SN + off + j] = dvt;
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
   }
   if (own) cb[j] = x[cur][j];
 }
@@ -1453,12 +1519,12 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
     const float *up = upbuf - s0 * B * N;
     if (N <= 256) {
-      const int NJ = (N + 63) & ~63;
+      const int nthr = 2 * ((N + 63) & ~63); // four threads per two postsynaptic rows
       if (N <= 128)
-        hipLaunchKernelGGL((k_adj_rec_rs<32, 4>), dim3(B), dim3(4 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+        hipLaunchKernelGGL((k_adj_rec_rs<32>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
                            carry, carry_init);
       else
-        hipLaunchKernelGGL((k_adj_rec_rs<64, 4>), dim3(B), dim3(4 * NJ), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+        hipLaunchKernelGGL((k_adj_rec_rs<64>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
                            carry, carry_init);
     } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
