@@ -1054,29 +1054,34 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
 // whose 16x4 spike block is empty is skipped (it would add exact zeros).
 // Lane layouts (checked on gfx950): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
 // D[(lane/16) + 4r][lane%16] in register r of the lane.
-// One launch covers every weight matrix of the network: blockIdx.x -> (matrix, 64 x 16*NT tile).
+// One launch covers every weight matrix of the network: blockIdx.x -> (matrix, 64 x 16*NT*CW tile).
 // ------------------------------------------------------------------------------------------
 typedef double dvec4 __attribute__((ext_vector_type(4)));
 
-template <int NT>
-__global__ void __launch_bounds__(256)
+template <int NT, int CW>
+__global__ void __launch_bounds__(256 * CW)
 k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
   extern __shared__ __align__(16) unsigned char smem[];
   int di = 0;
   while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
   const DwDesc &d = batch.d[di];
   const int tile = blockIdx.x - d.tile0;
-  const int j0 = (tile / d.tiles_n) * 64, n0 = (tile % d.tiles_n) * (16 * NT);
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  constexpr int COLS = 16 * NT * CW;
+  const int j0 = (tile / d.tiles_n) * 64, n0 = (tile % d.tiles_n) * COLS;
+  // wavefront (w, cg): presynaptic rows 16w .. 16w+15 of the tile, column blocks NT*cg .. NT*cg+NT-1.
+  // With CW > 1 two (or four) wavefronts share a SIMD, so that the operand preparation of one overlaps
+  // the MFMAs of the other.
+  const int tid = threadIdx.x, lane = tid & 63, w = (tid >> 6) & 3, cb0 = NT * (tid >> 8);
   const int Bp = (B + 3) & ~3;
-  constexpr int COLS = 16 * NT, STRIDE = COLS + 16; // rows 16 banks apart: conflict-free operand reads
-  // staging: thread -> (row, 4 columns) of the P tile; 256 threads cover RPP rows per pass, 4 passes.
+  constexpr int STRIDE = COLS + 16; // rows 16 banks apart: conflict-free operand reads
+  // staging: thread -> (row, 4 columns) of the P tile; the threads cover RPP rows per pass, NPASS passes.
   // A stage holds TS consecutive time steps (row = ts*Bp + b, step t_hi - ts): several steps of
   // MFMAs per barrier, so that the global loads of the next stage (issued before the MFMAs of the
   // current one) have time to arrive.
   constexpr int TPR = COLS / 4;          // threads per row
-  constexpr int RPP = 256 / TPR;         // rows per pass
-  constexpr int ROWS = 4 * RPP;          // rows per stage
+  constexpr int RPP = 256 * CW / TPR;    // rows per pass
+  constexpr int NPASS = 4 / CW;
+  constexpr int ROWS = NPASS * RPP;      // rows per stage (= 4096 / COLS)
   const int TS = ROWS / Bp;              // time steps per stage (>= 1: the launcher checks Bp <= ROWS)
   float *Pt = (float *)smem;                                   // [2][ROWS][STRIDE]
   uint64_t *Sw = (uint64_t *)(Pt + (size_t)2 * ROWS * STRIDE); // [2][ROWS]
@@ -1087,7 +1092,7 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
   for (int q = 0; q < NT; ++q)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * q + li;
+      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * (cb0 + q) + li;
       acc[q][r] = (j < d.n_pre && n < d.n_post) ? d.acc[(size_t)j * d.n_post + n] : 0.0;
     }
 
@@ -1097,9 +1102,9 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
   // together while the MFMAs of the current stage run; stage_store zeroes what lies outside the
   // stage (integer masks: a select would let the compiler move a load back under its condition)
   // and writes the tile to LDS.
-  auto stage_load = [&](int t_hi, int nts, float (&reg)[4][4], uint64_t &wreg) {
+  auto stage_load = [&](int t_hi, int nts, float (&reg)[NPASS][4], uint64_t &wreg) {
 #pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
+    for (int ps = 0; ps < NPASS; ++ps) {
       const int r = srow + ps * RPP, ts = r / Bp, b = r - ts * Bp;
       const bool ok = ts < nts && b < B;
       const float *prow = d.post + (size_t)(t_hi - (ok ? ts : 0) - t_base - 1) * d.slot_stride + d.post_off +
@@ -1116,9 +1121,9 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
       wreg = d.pre_mask[((size_t)(t_hi - (ok ? ts : 0) - d.lag) * B + (ok ? b : 0)) * d.pre_words + (j0 >> 6)];
     }
   };
-  auto stage_store = [&](int buf, int nts, const float (&reg)[4][4], uint64_t wreg) {
+  auto stage_store = [&](int buf, int nts, const float (&reg)[NPASS][4], uint64_t wreg) {
 #pragma unroll
-    for (int ps = 0; ps < 4; ++ps) {
+    for (int ps = 0; ps < NPASS; ++ps) {
       const int r = srow + ps * RPP, ts = r / Bp, b = r - ts * Bp;
       const bool ok = ts < nts && b < B;
       float *dst = Pt + ((size_t)buf * ROWS + r) * STRIDE + scol;
@@ -1132,7 +1137,7 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
     }
   };
 
-  float reg[4][4];
+  float reg[NPASS][4];
   uint64_t wreg;
   int t_hi = t1;
   int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
@@ -1159,7 +1164,7 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
 #pragma unroll
       for (int u = 0; u < KU; ++u) {
         wd[u] = S[rr + 4 * u + lk];
-        const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + li;
+        const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + 16 * cb0 + li;
 #pragma unroll
         for (int q = 0; q < NT; ++q) p[u][q] = prow[16 * q];
       }
@@ -1193,7 +1198,7 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
   for (int q = 0; q < NT; ++q)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * q + li;
+      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * (cb0 + q) + li;
       if (j < d.n_pre && n < d.n_post) d.acc[(size_t)j * d.n_post + n] = acc[q][r];
     }
 }
@@ -1577,20 +1582,21 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipS
   if (t1 <= t0 || batch.count <= 0) return hipSuccess;
   const int Bp = (B + 3) & ~3;
   if (Bp > 128) return hipErrorInvalidValue; // the staging registers cover at most 128 batch rows
-  // wide tiles when they already fill the chip, narrow ones otherwise
   int tiles4 = 0;
   for (int i = 0; i < batch.count; ++i) tiles4 += ((batch.d[i].n_pre + 63) / 64) * ((batch.d[i].n_post + 63) / 64);
-  const int NT = (tiles4 >= 256 && Bp <= 64) ? 4 : 2; // a stage holds 256 / NT rows of 16 * NT columns
+  // wide tiles when they already fill the chip; otherwise narrow ones and two wavefronts per SIMD
+  const bool wide = tiles4 >= 256 && Bp <= 64;
+  const int cols = wide ? 64 : 32; // a stage holds 4096 / cols rows
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
-    batch.d[i].tiles_n = (batch.d[i].n_post + 16 * NT - 1) / (16 * NT);
+    batch.d[i].tiles_n = (batch.d[i].n_post + cols - 1) / cols;
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
   }
-  const int rows = 256 / NT;
-  const size_t lds = (size_t)2 * rows * (16 * NT + 16) * sizeof(float) + (size_t)2 * rows * 8;
-  if (NT == 4) hipLaunchKernelGGL((k_dw_mfma<4>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
-  else hipLaunchKernelGGL((k_dw_mfma<2>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
+  const int rows = 4096 / cols;
+  const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
+  if (wide) hipLaunchKernelGGL((k_dw_mfma<4, 1>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
+  else hipLaunchKernelGGL((k_dw_mfma<1, 2>), dim3(total), dim3(512), lds, s, batch, B, t0, t1, t_base);
   return hipGetLastError();
 }
 
