@@ -28,9 +28,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 MFMA_F64_PEAK_TF = 78.6   # MI355X published fp64 matrix peak
 MFMA_F32_PEAK_TF = 157.3  # MI355X published fp32 matrix peak
-# fp32 vector peak without packed-fp32 instructions (this build disables them):
-# 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz = 78.6 TFLOP/s (the published 157.3 needs v_pk_fma_f32)
-ALU_F32_PEAK_TF = 256 * 4 * 16 * 2 * 2.4e9 / 1e12
+ALU_F32_PEAK_TF = 157.3   # MI355X published fp32 vector peak (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 
 # strategy parameters per benchmark configuration: (coarse, fine); budgets from the configurations
 STRATEGY_PARAMS = {
