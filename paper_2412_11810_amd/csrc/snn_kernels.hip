@@ -708,6 +708,56 @@ k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int
   }
 }
 
+// The same product for small weight matrices (N * K <= 65536, K a multiple of 16, 16-byte aligned rows):
+// one wavefront per 16 x 16 block of C, operands straight from memory as float4 (no LDS, no barrier),
+// v_mfma_f32_16x16x4.  Lane (i, kk) loads columns k0 + 4kk .. 4kk+3 of row i of its 16 rows; MFMA e of
+// a 16-column chunk takes element e of every lane, i.e. columns k0 + 4kk + e -- the same assignment
+// for both operands, a fixed order of additions that does not depend on M.  A chunk of time steps is
+// only a few thousand rows: blocks this small put a wavefront on every SIMD of the chip, where the
+// LDS-tiled kernel would occupy a quarter of them.  Which of the two kernels runs depends on the
+// layer shapes only, never on M, so every storage strategy sees the same arithmetic.
+//   lane layout (verified on the device): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
+//   D[4*(lane/16) + r][lane%16] in register r.
+typedef float v4f __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256)
+k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
+            int ldc, int M) {
+  const int lane = threadIdx.x & 63, i = lane & 15, kk = lane >> 4;
+  const int tiles_n = (N + 15) >> 4;
+  const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int m0 = (tile / tiles_n) * 16, j0 = (tile % tiles_n) * 16;
+  if (m0 >= M) return;
+  const int ra = m0 + i < M ? m0 + i : M - 1, rw = j0 + i < N ? j0 + i : N - 1; // rows past the end: loaded, not stored
+  const float4 *pa = reinterpret_cast<const float4 *>(A + (size_t)ra * lda) + kk;
+  const float4 *pw = reinterpret_cast<const float4 *>(W + (size_t)rw * K) + kk;
+  v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  const int nch = K >> 4; // chunks of 16 columns
+  for (int c0 = 0; c0 < nch; c0 += 8) {
+    float4 a[8], b[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int cc = c0 + c < nch ? c0 + c : nch - 1;
+      a[c] = pa[cc * 4];
+      b[c] = pw[cc * 4];
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      if (c0 + c < nch) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[c].x, b[c].x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[c].y, b[c].y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[c].z, b[c].z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[c].w, b[c].w, acc, 0, 0, 0);
+      }
+    }
+  }
+  const int j = j0 + i;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int m = m0 + 4 * kk + r;
+    if (m < M && j < N) C[(size_t)m * ldc + j] = acc[r];
+  }
+}
+
 // Recurrent part, layers of up to 4*KH neurons: the recurrent matrix stays in registers for the
 // whole chunk.  Thread (jj, h) keeps W_rec[j][h*KH .. h*KH+KH) for the two postsynaptic rows
 // j = jj and j = jj + NJ2 (four threads per row, each a slice of the reduction; partial sums
@@ -1515,7 +1565,11 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     else { A = vbuf + s0 * ((size_t)B * SN) + net.off[l + 1]; lda = SN; K = net.N[l + 1]; W = net.W_in[l + 1]; }
     float *C = upbuf; // row m = (slot - s0)*B + b, ldc = N
     hb(6);
-    if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
+    const bool aligned16 = K % 16 == 0 && lda % 4 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
+    if (aligned16 && (size_t)N * K <= 65536) {
+      const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
+      hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    } else if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
       hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
     else // small products: one wavefront per 32 x 32 block, so that more compute units take part
       hipLaunchKernelGGL((k_up_gemm<1, 1>), dim3((M + 31) / 32, (N + 31) / 32), dim3(64), 0, s, A, lda, W, K, N, C, N, M);
