@@ -593,23 +593,28 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
   } else {
     // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again.
-    // Each layer's part of a coarse checkpoint x_{KC} is snapshotted into a staging slot right after
-    // that layer finished step KC (the layers run one tile apart); when the last layer's part is in,
-    // the slot goes to the host on the copy stream.
+    // The sequential kernels write each layer's part of a coarse checkpoint x_{KC} straight into a
+    // staging slot (ring of n_stage slots: the layers run one tile apart, so several checkpoints are
+    // being assembled at once); when the last layer's part is in, the slot goes to the host on the
+    // copy stream.  Before the lowest layer starts the tile that ends at a boundary, the compute
+    // stream waits for the copy that last used that boundary's slot.
     struct Snap {
       snn_ctx *c; const Plan *p; float *stage; size_t slot, Ms; int n_stage; hipStream_t s, cs;
       std::vector<hipEvent_t> ready, freed; std::vector<char> busy; snn_stats *st;
+      int waited_for = 0; // highest checkpoint index whose slot has been waited for
+      hipError_t reserve(int t_done) { // layer 0 has finished step t_done: make the next boundary's slot writable
+        const int K = t_done / p->C + 1, so = K % n_stage;
+        if (K <= waited_for || (long long)K * p->C >= p->T) return hipSuccess;
+        waited_for = K;
+        return busy[so] ? hipStreamWaitEvent(s, freed[so], 0) : hipSuccess;
+      }
       static hipError_t done(void *self, int layer, int t_end) {
         Snap &q = *static_cast<Snap *>(self);
         const NetDev &n = q.c->net;
-        if (t_end % q.p->C != 0 || t_end >= q.p->T) return hipSuccess;
-        const int K = t_end / q.p->C, so = K % q.n_stage; // checkpoint x_{K*C} -> host slot K
         hipError_t e = hipSuccess;
-        if (layer == 0 && q.busy[so]) e = hipStreamWaitEvent(q.s, q.freed[so], 0);
-        if (e == hipSuccess)
-          e = hipMemcpy2DAsync(q.stage + (size_t)so * q.slot + n.off[layer], (size_t)n.SN * 4, q.c->cur_state + n.off[layer],
-                               (size_t)n.SN * 4, (size_t)n.N[layer] * 4, (size_t)n.B, hipMemcpyDeviceToDevice, q.s);
-        if (e != hipSuccess || layer != n.L - 1) return e;
+        if (layer == 0) e = q.reserve(t_end);
+        if (e != hipSuccess || layer != n.L - 1 || t_end % q.p->C != 0 || t_end >= q.p->T) return e;
+        const int K = t_end / q.p->C, so = K % q.n_stage; // checkpoint x_{K*C} -> host slot K
         e = hipEventRecord(q.ready[so], q.s);
         if (e == hipSuccess) e = hipStreamWaitEvent(q.cs, q.ready[so], 0);
         if (e == hipSuccess)
@@ -626,7 +631,9 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     }
     const FwdCallbacks cb{&snap, &Snap::done};
     const std::vector<int> bounds = tile_bounds(0, T, p.C);
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, StoreSpec{}, c->readout, 1, c->dubuf, s, &hk, &cb));
+    HIPCHK(c, snap.reserve(0)); // nothing to wait for yet; marks checkpoint 1 as reserved
+    const StoreSpec sp{stage, slot, 0, p.C, 1, T - 1, p.n_stage_slots}; // x_{KC} -> staging slot K % n_stage
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
   }
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));
