@@ -223,6 +223,11 @@ def main():
     n_bwd = max(1, sum(1 for o in sched if o[0] == "BACKWARD"))
     if args.strategy == "hier":
         rslots = 0  # forward tiles follow the checkpoint interval, not host segments
+    # Remote/Double with states of up to 1 MiB: the kernels access the pinned host block themselves, so the
+    # forward pass is not cut at the checkpoints (same rule as the library; SNN_HOST_TIER overrides it)
+    tier = os.environ.get("SNN_HOST_TIER", "")
+    if args.strategy in ("remote", "double") and tier != "dma" and (tier == "direct" or 4 * w.B * w.neurons <= (1 << 20)):
+        rslots = 0
     n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
     n_tiles = sum(-(-(min((k + 1) * C, w.T) - k * C) // 64) for k in range(rslots)) if rslots else -(-w.T // 64)
     L = len(w.n_hidden)

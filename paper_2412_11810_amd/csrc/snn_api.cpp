@@ -18,6 +18,11 @@ struct snn_ctx {
   NetDev net{};
   hipStream_t stream = nullptr;      // caller's stream (may be the null stream)
   hipStream_t copy_stream = nullptr; // private side stream for checkpoint traffic
+  // Host tier of Remote/Double.  Checkpoints of up to host_direct_max bytes are written to and read from the
+  // pinned host block by the kernels themselves (it is mapped into the device's address space): for small
+  // states the cross-stream synchronisation of a DMA copy costs several times the transfer.  Larger states go
+  // through hipMemcpyAsync on the copy stream, overlapped with compute.  SNN_HOST_TIER=dma|direct forces one.
+  size_t host_direct_max = (size_t)1 << 20;
   float *W_in[SNN_MAXL]{}, *W_rec[SNN_MAXL]{}, *W_out = nullptr;
   float *W_inT[SNN_MAXL]{}, *W_recT[SNN_MAXL]{}, *W_outT = nullptr;
   float *dW_in[SNN_MAXL]{}, *dW_rec[SNN_MAXL]{}, *dW_out = nullptr;
@@ -172,6 +177,10 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   c->cfg = *cfg;
   fill_shape(*cfg, &c->net);
   if (const char *e = std::getenv("SNN_DW")) c->dw_event_driven = std::strcmp(e, "event") == 0;
+  if (const char *e = std::getenv("SNN_HOST_TIER")) {
+    if (std::strcmp(e, "dma") == 0) c->host_direct_max = 0;
+    else if (std::strcmp(e, "direct") == 0) c->host_direct_max = ~(size_t)0;
+  }
   if (const char *e = std::getenv("SNN_GRAPH")) c->graphs_enabled = std::strcmp(e, "0") != 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
@@ -519,7 +528,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   std::vector<hipEvent_t> ev_load_ready(n_load_ev, nullptr), ev_load_free(n_load_ev, nullptr);
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::vector<char> load_used(n_load_ev, 0);
-  const bool remote = strategy == SNN_REMOTE || strategy == SNN_DOUBLE || strategy == SNN_HIER;
+  const bool direct = (strategy == SNN_REMOTE || strategy == SNN_DOUBLE) && Ms <= c->host_direct_max;
+  const bool remote = (strategy == SNN_REMOTE || strategy == SNN_DOUBLE || strategy == SNN_HIER) && !direct;
   if (remote) {
     for (int i = 0; i < n_load_ev; ++i) {
       ev_load_ready[i] = tm.get(); ev_load_free[i] = tm.get();
@@ -591,6 +601,13 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     const FwdCallbacks cb{&hier, &Hier::done};
     const std::vector<int> bounds = tile_bounds(0, T, p.F);
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
+  } else if (direct) {
+    // x_0 lives in host slot 0 (zeroed on the host); the sequential kernels store x_{KC} into host slot K
+    const StoreSpec sp{c->host_ckpt, slot, 0, p.C, 1, T - 1, 0};
+    const std::vector<int> bounds = tile_bounds(0, T, T); // no host-side work at the checkpoints: full tiles
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    st.n_d2h += p.n_remote - 1;
+    st.d2h_bytes += (int64_t)(p.n_remote - 1) * (int64_t)Ms;
   } else {
     // x_0 lives in host slot 0, zeroed when the pinned block was allocated and never written again.
     // The sequential kernels write each layer's part of a coarse checkpoint x_{KC} straight into a
@@ -643,6 +660,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   std::vector<SchedOp> ops((size_t)snn_make_schedule(p, nullptr, 0));
   snn_make_schedule(p, ops.data(), (int64_t)ops.size());
   int seg_start = 0, chunk_base = 0, cur_load = 0, n_loads = 0;
+  const float *seg_src = nullptr; // state the current remote segment starts from (HBM load slot or host slot)
   bool first_adjoint = true;
   // host->device loads run on the copy stream, behind every device->host copy of the forward pass
   auto issue_load = [&](int K, int slot_i) -> hipError_t {
@@ -677,6 +695,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     switch (op.op) {
       case OP_LOAD_REMOTE: {
         const int K = op.a / p.C;
+        if (direct) { // the recompute kernels read x_{KC} from the host slot themselves
+          seg_start = op.a;
+          seg_src = c->host_ckpt + (size_t)K * slot;
+          st.n_h2d++; st.h2d_bytes += (int64_t)Ms;
+          break;
+        }
         if (n_loads > 0) {
           // the segment that used the previous slot is fully queued: mark that slot reusable
           HIPCHK(c, hipEventRecord(ev_load_free[cur_load], s));
@@ -685,6 +709,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         cur_load = K & 1;
         seg_start = op.a;
         HIPCHK(c, hipStreamWaitEvent(s, ev_load_ready[cur_load], 0));
+        seg_src = loadb + (size_t)cur_load * slot;
         ++n_loads;
         // prefetch the next (earlier) coarse checkpoint into the other slot, overlapped with this
         // segment's recomputation and backward pass
@@ -706,7 +731,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         // chunk buffer takes the currents of the interval, the scan keeps only its last state
         tm.begin(1);
         for (int a = op.a, m = 0; a < op.b; a += p.F, ++m) {
-          const float *src = m == 0 ? loadb + (size_t)cur_load * slot : lckpt + (size_t)(m - 1) * slot;
+          const float *src = m == 0 ? seg_src : lckpt + (size_t)(m - 1) * slot;
           HIPCHK(c, launch_recompute(n, a, a + p.F, src, chunk, a, slot, 0, lckpt + (size_t)m * slot, s));
         }
         tm.end();
@@ -717,7 +742,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         const float *src;
         if (strategy == SNN_CHUNK) src = lckpt + (size_t)(op.a / p.F) * slot;
         else if (strategy == SNN_HIER) src = lckpt + (size_t)((op.a / p.F) % p.n_local_ckpt) * slot;
-        else if (strategy == SNN_REMOTE || op.a == seg_start) src = loadb + (size_t)cur_load * slot;
+        else if (strategy == SNN_REMOTE || op.a == seg_start) src = seg_src;
         else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
         chunk_base = op.a;
         tm.begin(1);

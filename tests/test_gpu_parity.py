@@ -243,6 +243,34 @@ def test_graph_replay_matches_eager():
     net.snn_destroy()
 
 
+def test_host_tier_dma_and_direct_agree(monkeypatch):
+    """Remote and Double keep their coarse checkpoints in pinned host memory.  Small states are written
+    and read by the kernels themselves, larger ones travel by hipMemcpyAsync on the copy stream
+    (SNN_HOST_TIER forces either way, read when the context is created).  Both ways must give the
+    gradients of full storage bit for bit, eagerly and as a replayed graph."""
+    w = synth.config(1, T=300, B=8)
+    d = synth.generate(w)
+    L = len(w.n_hidden)
+    ref = None
+    for tier in ("dma", "direct"):
+        monkeypatch.setenv("SNN_HOST_TIER", tier)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            if ref is None:
+                net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+                ref = _gpu_grads(net, L)
+            for strat, C, F in [(snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 70, 9), (snn.SNN_REMOTE, 300, 0)]:
+                st = net.snn_bptt(strat, C, F)
+                assert _identical(_gpu_grads(net, L), ref), (tier, strat, "eager")
+                assert st.n_d2h == -(-w.T // C) - 1 and st.n_h2d == -(-w.T // C)
+                for rep in range(2):
+                    net.snn_bptt(strat, C, F, want_stats=False)
+                    assert _identical(_gpu_grads(net, L), ref), (tier, strat, "graph", rep)
+        finally:
+            net.snn_destroy()
+
+
 @pytest.mark.parametrize("T,B,strat,C,F", [(1, 1, 0, 0, 0), (1, 2, 3, 1, 1), (2, 1, 2, 1, 0), (65, 2, 1, 0, 64),
                                            (129, 1, 3, 64, 64), (130, 3, 2, 65, 0), (7, 5, 3, 7, 1),
                                            (130, 2, 4, 1, 3), (70, 1, 4, 2, 70), (33, 2, 4, 5, 2)])
