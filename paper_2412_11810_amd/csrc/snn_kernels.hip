@@ -867,13 +867,15 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
 // barrier (one atomic per workgroup and step).  The barrier spins a bounded number of times: if a
 // workgroup never arrives the kernel raises *err and every workgroup runs to completion.
 template <int NR>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) // one wave per SIMD: the weights must stay in registers
 k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
              int ldu, float *__restrict__ carry, int carry_init, float *xg, unsigned *bar, unsigned *err, int G_b,
              unsigned spin_limit) {
   extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_dead; // set by thread 0 when a barrier gave up
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out;
   const int tid = threadIdx.x;
+  if (tid == 0) s_dead = 0;
   const int bg = blockIdx.x % G_b, js = blockIdx.x / G_b, n_slices = gridDim.x / G_b;
   const int b0 = bg * 8, j0 = js * 32;
   const int NP = NR * 8;                       // padded reduction length (>= N)
@@ -881,16 +883,33 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
   float *part = xs + (size_t)NP * 8;           // [8][32][8]
   const int jl = tid & 31, kp = tid >> 5;
 
+  // every load unconditional, from a clamped address, zeroed with an integer mask afterwards: a select
+  // lets the compiler put each load under its condition, one memory round trip after the other
   float w[NR];
+  {
+    const int jc = j0 + jl < N ? j0 + jl : N - 1;
 #pragma unroll
-  for (int q = 0; q < NR; ++q) {
-    const int n = kp * NR + q;
-    w[q] = (j0 + jl < N && n < N) ? net.W_recT[l][(size_t)n * N + j0 + jl] : 0.0f; // = W_rec[j][n]
+    for (int q = 0; q < NR; ++q) {
+      const int n = kp * NR + q, nc = n < N ? n : N - 1;
+      w[q] = net.W_recT[l][(size_t)nc * N + jc]; // = W_rec[j][n]
+    }
+#pragma unroll
+    for (int q = 0; q < NR; ++q)
+      w[q] = __uint_as_float(__float_as_uint(w[q]) & (0u - (uint32_t)(j0 + jl < N && kp * NR + q < N)));
   }
-  // dv_{t1+1} of this batch group
-  for (int i = tid; i < NP * 8; i += 256) {
-    const int n = i >> 3, bb = i & 7;
-    xs[i] = (!carry_init && n < N && b0 + bb < B) ? carry[(size_t)(b0 + bb) * (SN + O) + off + n] : 0.0f;
+  // dv_{t1+1} of this batch group (loads unconditional and clamped, zeroed afterwards: see above)
+  {
+    float cv[NR / 4];
+#pragma unroll
+    for (int r = 0; r < NR / 4; ++r) {
+      const int i = tid + 256 * r, n = i >> 3, bb = i & 7;
+      cv[r] = carry[(size_t)(b0 + bb < B ? b0 + bb : B - 1) * (SN + O) + off + (n < N ? n : N - 1)];
+    }
+#pragma unroll
+    for (int r = 0; r < NR / 4; ++r) {
+      const int i = tid + 256 * r, n = i >> 3, bb = i & 7;
+      xs[i] = __uint_as_float(__float_as_uint(cv[r]) & (0u - (uint32_t)(!carry_init && n < N && b0 + bb < B)));
+    }
   }
   __syncthreads();
   // finalising role of this thread: row fj, batch element fb
@@ -910,7 +929,7 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
     const float4 *x4 = reinterpret_cast<const float4 *>(xs + (size_t)kp * NR * 8);
-#pragma unroll 8
+#pragma unroll
     for (int q = 0; q < NR; ++q) {
       const float4 xa = x4[2 * q], xb = x4[2 * q + 1];
       acc[0] = fmaf(w[q], xa.x, acc[0]); acc[1] = fmaf(w[q], xa.y, acc[1]);
@@ -947,16 +966,21 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
       __hip_atomic_fetch_add(&bar[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       const unsigned target = (step + 1u) * (unsigned)n_slices;
       unsigned spins = 0;
-      while (__hip_atomic_load(&bar[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-        if (++spins > spin_limit || __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+      // spin_limit == 0 (only ever set by a test of this path): give up at once, arrived or not
+      while (spin_limit == 0u || __hip_atomic_load(&bar[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        // give up after spin_limit polls, or (looked at now and then: every poll is a memory round
+        // trip) when another workgroup already has
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
           __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_dead = 1;
           break;
         }
         __builtin_amdgcn_s_sleep(1);
       }
     }
     __syncthreads();
-    if (!dead && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) dead = true; // keep going, never wait again
+    if (s_dead) dead = true; // keep going to the end of the chunk, never wait again
     // ---- dv_t of the whole layer for this batch group -> LDS --------------------------------
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     {

@@ -243,6 +243,25 @@ def test_graph_replay_matches_eager():
     net.snn_destroy()
 
 
+def test_barrier_timeout_is_reported_not_hung(monkeypatch):
+    """The chip-wide adjoint kernel of wide layers synchronises its workgroups with a counting barrier
+    that polls a bounded number of times.  With the limit forced to zero from the host every workgroup
+    gives up at its first barrier: all kernels still run to completion, and snn_bptt reports the
+    failure instead of returning gradients.  A context created afterwards works normally."""
+    w = synth.Workload("wide_24-512-6", 24, (512,), 6, T=12, B=4, p_in=0.1, seed=11)
+    d = synth.generate(w)
+    monkeypatch.setenv("SNN_WS_SPIN_LIMIT", "0")
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        with pytest.raises(RuntimeError, match="timed out"):
+            net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+    finally:
+        net.snn_destroy()
+    monkeypatch.delenv("SNN_WS_SPIN_LIMIT")
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 5)], nthreads=1)
+
+
 def test_host_tier_dma_and_direct_agree(monkeypatch):
     """Remote and Double keep their coarse checkpoints in pinned host memory.  Small states are written
     and read by the kernels themselves, larger ones travel by hipMemcpyAsync on the copy stream
