@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="chunk-size / remote-chunk-size study (use with --T 4096)")
     ap.add_argument("--pmc-copy", action="store_true")
+    ap.add_argument("--model-sweep", action="store_true",
+                    help="largest hidden width per strategy at fixed T and HBM budget (use with --T and --budget-mb)")
+    ap.add_argument("--budget-mb", type=float, default=200.0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -130,6 +133,51 @@ def main():
         for _ in range(3):
             net.snn_debug_copy(a, b, nbytes)
         print(json.dumps({"copy_bytes_read": nbytes, "copy_bytes_written": nbytes, "launches": 3}))
+        return
+
+    if args.model_sweep:
+        # Model-size scaling (the shape of the paper's Fig. 2 right / Fig. 3): at a fixed sequence length and HBM
+        # activation budget, the widest two-layer network (700 -> N -> N -> 20, batch 32, widths in steps of 64)
+        # each strategy can train -- closed form from snn_bytes_required, intervals by the square-root rules --
+        # and one training step actually run at that width (Standard's and Double's).
+        T = args.T or 4096
+        budget_b = int(args.budget_mb * 1e6)
+        rows = []
+        for name in ("standard", "chunk", "remote", "double", "hier"):
+            sid = SID[name]
+            lo, hi = 0, 8192 // 64
+            while lo < hi:  # largest N = 64*k with bytes_required <= budget
+                mid = (lo + hi + 1) // 2
+                need = snn.snn_bytes_required(snn.make_config(700, [64 * mid] * 2, 20, T, 32), sid, T, 0, 0)
+                if 0 < need <= budget_b:
+                    lo = mid
+                else:
+                    hi = mid - 1
+            N = 64 * lo
+            row = {"strategy": name, "max_width": N, "neurons": 2 * N}
+            if N >= 64:
+                cfgN = snn.make_config(700, [N] * 2, 20, T, 32)
+                row["bytes_required"] = snn.snn_bytes_required(cfgN, sid, T, 0, 0)
+                row["state_slots_hbm"], row["state_slots_host"] = snn.snn_state_slots(sid, T, 0, 0)
+                if name in ("standard", "double"):
+                    wl = synth.Workload(f"model_sweep_700-2x{N}-20", 700, (N, N), 20, T=T, B=32, p_in=0.02,
+                                        gain=1.0 if N <= 256 else 0.2, seed=1)
+                    dd = synth.generate(wl)
+                    nn_ = snn.from_workload(wl, dd)
+                    xx = torch.from_numpy(dd["in_spikes"]).to(dev)
+                    yy = torch.from_numpy(dd["labels"]).to(dev)
+                    nn_.snn_bind_inputs(xx, yy, T)
+                    nn_.snn_bptt(sid, 0, 0, budget_b, want_stats=False)
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    nn_.snn_bind_inputs(xx, yy, T)
+                    nn_.snn_bptt(sid, 0, 0, budget_b, want_stats=False)
+                    torch.cuda.synchronize()
+                    row["ms_per_step"] = round((time.perf_counter() - t0) * 1e3, 2)
+                    row["neuron_timesteps_per_s"] = round(32 * T * 2 * N / (time.perf_counter() - t0), 1)
+                    nn_.snn_destroy()
+            rows.append(row)
+        print(json.dumps({"model_sweep": "700->N->N->20, batch 32", "T": T, "budget_bytes": budget_b, "rows": rows}))
         return
 
     w = synth.config(args.config, **({"T": args.T} if args.T else {}))

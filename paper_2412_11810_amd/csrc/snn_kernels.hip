@@ -1398,12 +1398,9 @@ static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, 
 }
 // SNN_CURRENTS=gather selects the event-by-event gather kernel for every current (the default runs
 // the feed-forward and recurrent currents on the matrix cores and only the narrow readout as a gather).
-static bool currents_use_mfma() {
-  static const bool v = [] {
-    const char *e = getenv("SNN_CURRENTS");
-    return !(e && strcmp(e, "gather") == 0);
-  }();
-  return v;
+static bool currents_use_mfma() { // read at every launch: a test switches it between two contexts
+  const char *e = getenv("SNN_CURRENTS");
+  return !(e && strcmp(e, "gather") == 0);
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {

@@ -243,6 +243,31 @@ def test_graph_replay_matches_eager():
     net.snn_destroy()
 
 
+def test_gather_and_matrix_core_currents_agree(monkeypatch):
+    """The synaptic currents are computed either event by event (gather of the active rows) or by the K = 1
+    MFMA kernel, which visits the same rows in the same order.  Both must give the very same bits: spike
+    trains, membrane potentials and gradients, for a dense-activity and a sparse-activity network."""
+    for w in (synth.config(1, T=150, B=6), synth.Workload("sparse_90-200-130-7", 90, (200, 130), 7, T=150, B=5, p_in=0.03, gain=0.3, seed=21)):
+        d = synth.generate(w)
+        L = len(w.n_hidden)
+        got = {}
+        for mode in ("gather", "mfma"):
+            monkeypatch.setenv("SNN_CURRENTS", mode)
+            net = snn.from_workload(w, d)
+            try:
+                net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+                states = net.snn_debug_states(w.T)
+                net.snn_bptt(snn.SNN_CHUNK, 0, 16)
+                got[mode] = (_gpu_grads(net, L), [net.snn_get_spikes(l, w.T) for l in range(L)], states)
+            finally:
+                net.snn_destroy()
+        assert _identical(got["gather"][0], got["mfma"][0]), w.name
+        for a, b in zip(got["gather"][1], got["mfma"][1]):
+            assert np.array_equal(a, b), w.name
+        assert np.array_equal(got["gather"][2].view(np.uint32), got["mfma"][2].view(np.uint32)), w.name
+    monkeypatch.delenv("SNN_CURRENTS")
+
+
 def test_barrier_timeout_is_reported_not_hung(monkeypatch):
     """The chip-wide adjoint kernel of wide layers synchronises its workgroups with a counting barrier
     that polls a bounded number of times.  With the limit forced to zero from the host every workgroup
