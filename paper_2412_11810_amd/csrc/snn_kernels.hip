@@ -758,36 +758,37 @@ k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, i
   }
 }
 
-// Recurrent part, layers of up to 4*KH neurons: the recurrent matrix stays in registers for the
-// whole chunk.  Thread (jj, h) keeps W_rec[j][h*KH .. h*KH+KH) for the two postsynaptic rows
-// j = jj and j = jj + NJ2 (four threads per row, each a slice of the reduction; partial sums
-// combined in a fixed order).  dv_{t+1} is broadcast from LDS; every value read feeds two FMAs,
-// which halves the LDS traffic that bounds this kernel (all threads of a wavefront read the same
-// address).  No weight traffic and no waiting on global memory in the time loop (operands staged
-// G steps ahead), two barriers per step.  One workgroup per batch element, 4*NJ2 threads.
-template <int KH>
+// Recurrent part, layers of up to H*KH neurons: the recurrent matrix stays in registers for the
+// whole chunk.  Thread (jj, h) keeps W_rec[j][h*KH .. h*KH+KH) for the R postsynaptic rows
+// j = jj, jj + NJR, ..., jj + (R-1)*NJR (H threads per row, each a slice of the reduction; partial sums
+// combined in a fixed order).  dv_{t+1} is broadcast from LDS; every value read feeds R FMAs: the LDS
+// traffic that bounds this kernel (every thread re-reading its slice of dv) shrinks by R, while the
+// weights per thread stay R*KH.  No weight traffic and no waiting on global memory in the time loop
+// (operands staged G steps ahead), two barriers per step.  One workgroup per batch element,
+// H*NJR threads.
+template <int KH, int H, int R>
 __global__ void __launch_bounds__(512)
 k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
              int ldu, float *__restrict__ carry, int carry_init) {
-  __shared__ __align__(16) float x[2][4 * KH];
-  __shared__ float part[4][256];
+  __shared__ __align__(16) float x[2][H * KH];
+  __shared__ float part[H][256];
   __shared__ float ring[2 * SNN_SEQ_GROUP][256];
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x;
-  const int NJ2 = blockDim.x >> 2, tid = threadIdx.x;
-  const int jj = tid % NJ2, h = tid / NJ2;
-  const int jA = jj, jB = jj + NJ2;
-  const int j = tid;                 // finalising role: the first 2*NJ2 threads own one row each
-  const bool own = tid < 2 * NJ2 && j < N;
+  const int NJR = blockDim.x / H, tid = threadIdx.x;
+  const int jj = tid % NJR, h = tid / NJR;
+  const int j = tid;                 // finalising role: the first R*NJR threads own one row each
+  const bool own = tid < R * NJR && j < N;
   float *cb = carry + (size_t)b * (SN + net.n_out) + off;
 
-  float wA[KH], wB[KH];
+  float w[R][KH];
 #pragma unroll
-  for (int q = 0; q < KH; ++q) {
-    const int n = h * KH + q;
-    wA[q] = (jA < N && n < N) ? net.W_recT[l][(size_t)n * N + jA] : 0.0f; // = W_rec[jA][n], coalesced over jj
-    wB[q] = (jB < N && n < N) ? net.W_recT[l][(size_t)n * N + jB] : 0.0f;
-  }
-  for (int i = tid; i < 4 * KH; i += blockDim.x) {
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int q = 0; q < KH; ++q) {
+      const int n = h * KH + q, jr = jj + r * NJR;
+      w[r][q] = (jr < N && n < N) ? net.W_recT[l][(size_t)n * N + jr] : 0.0f; // = W_rec[jr][n], coalesced over jj
+    }
+  for (int i = tid; i < H * KH; i += blockDim.x) {
     x[0][i] = (i < N && !carry_init) ? cb[i] : 0.0f;
     x[1][i] = 0.0f;
   }
@@ -825,25 +826,28 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
     const int tlo = tg - G > t0 ? tg - G : t0;
     for (int t = tg; t > tlo; --t) {
       const float4 *xs = reinterpret_cast<const float4 *>(&x[cur][h * KH]);
-      float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f, b0 = 0.0f, b1 = 0.0f, b2 = 0.0f, b3 = 0.0f;
+      float a[R][4];
+#pragma unroll
+      for (int r = 0; r < R; ++r) a[r][0] = a[r][1] = a[r][2] = a[r][3] = 0.0f;
 #pragma unroll
       for (int q = 0; q < KH / 4; ++q) {
         const float4 xv = xs[q];
-        a0 = fmaf(wA[4 * q + 0], xv.x, a0);
-        a1 = fmaf(wA[4 * q + 1], xv.y, a1);
-        a2 = fmaf(wA[4 * q + 2], xv.z, a2);
-        a3 = fmaf(wA[4 * q + 3], xv.w, a3);
-        b0 = fmaf(wB[4 * q + 0], xv.x, b0);
-        b1 = fmaf(wB[4 * q + 1], xv.y, b1);
-        b2 = fmaf(wB[4 * q + 2], xv.z, b2);
-        b3 = fmaf(wB[4 * q + 3], xv.w, b3);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          a[r][0] = fmaf(w[r][4 * q + 0], xv.x, a[r][0]);
+          a[r][1] = fmaf(w[r][4 * q + 1], xv.y, a[r][1]);
+          a[r][2] = fmaf(w[r][4 * q + 2], xv.z, a[r][2]);
+          a[r][3] = fmaf(w[r][4 * q + 3], xv.w, a[r][3]);
+        }
       }
-      part[h][jA] = (a0 + a1) + (a2 + a3);
-      part[h][jB] = (b0 + b1) + (b2 + b3);
+#pragma unroll
+      for (int r = 0; r < R; ++r) part[h][jj + r * NJR] = (a[r][0] + a[r][1]) + (a[r][2] + a[r][3]);
       __syncthreads();
       if (own) {
         const float vt = ring[2 * (tg - t)][j], upv = ring[2 * (tg - t) + 1][j];
-        const float sacc = ((part[0][j] + part[1][j]) + part[2][j]) + part[3][j];
+        float sacc = part[0][j];
+#pragma unroll
+        for (int q = 1; q < H; ++q) sacc = sacc + part[q][j];
         const float dn = x[cur][j];
         const float ds = (sacc + upv) - net.theta * dn;
         const float d = 1.0f + net.k * fabsf(vt - net.theta);
@@ -1599,12 +1603,12 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
     // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
     const float *up = upbuf - s0 * B * N;
     if (N <= 256) {
-      const int nthr = 2 * ((N + 63) & ~63); // four threads per two postsynaptic rows
+      const int nthr = 2 * ((N + 63) & ~63); // H threads per R postsynaptic rows, H = 2R
       if (N <= 128)
-        hipLaunchKernelGGL((k_adj_rec_rs<32>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+        hipLaunchKernelGGL((k_adj_rec_rs<16, 8, 4>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
                            carry, carry_init);
       else
-        hipLaunchKernelGGL((k_adj_rec_rs<64>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
+        hipLaunchKernelGGL((k_adj_rec_rs<32, 8, 4>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
                            carry, carry_init);
     } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
