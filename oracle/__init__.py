@@ -49,7 +49,7 @@ class _Cfg(C.Structure):
                 ("alpha", C.c_double), ("beta", C.c_double), ("theta", C.c_double),
                 ("surr_beta", C.c_double), ("mode", C.c_int32), ("forced", C.c_int32),
                 ("strategy", C.c_int32), ("C", C.c_int32), ("F", C.c_int32),
-                ("nthreads", C.c_int32), ("forced_states", C.c_int32)]
+                ("nthreads", C.c_int32), ("forced_states", C.c_int32), ("surr_window", C.c_double)]
 
 
 class _Stats(C.Structure):
@@ -98,7 +98,7 @@ def bptt(n_in, n_hidden, n_out, W_in, W_rec, W_out, in_spikes, labels, *,
          alpha=0.9, beta=0.9, theta=1.0, surr_beta=10.0, dtype=np.float32,
          strategy=STANDARD, coarse=0, fine=0, mode=HEAVISIDE, forced_spikes=None,
          forced_v=None, rec_mask=None, backward=True, want_v=False, nthreads=1,
-         want_events=False) -> Result:
+         want_events=False, surr_window=0.0) -> Result:
     """Run the oracle: forward, loss and (optionally) the backward pass.
 
     W_in[l]: [N_{l-1}, N_l], W_rec[l]: [N_l, N_l], W_out: [N_L, n_out] (row = presynaptic neuron);
@@ -106,6 +106,7 @@ def bptt(n_in, n_hidden, n_out, W_in, W_rec, W_out, in_spikes, labels, *,
     the forward pass read the hidden spike trains instead of thresholding; ``forced_v`` (same
     shapes, needs ``forced_spikes``, full storage only) also fixes the membrane potentials, so that
     the backward pass can be evaluated in double precision on an fp32 forward trajectory.
+    ``surr_window`` w > 0 cuts the surrogate derivative to zero wherever |v - theta| >= w.
     """
     dt = np.dtype(dtype)
     ct = C.c_float if dt == np.float32 else C.c_double
@@ -125,7 +126,7 @@ def bptt(n_in, n_hidden, n_out, W_in, W_rec, W_out, in_spikes, labels, *,
     nh = np.asarray(n_hidden, dtype=np.int32)
     cfg = _Cfg(n_in, L, n_out, T, B, nh.ctypes.data_as(C.POINTER(C.c_int32)), alpha, beta, theta,
                surr_beta, mode, 1 if forced_spikes is not None else 0, strategy, coarse, fine, nthreads,
-               1 if forced_v is not None else 0)
+               1 if forced_v is not None else 0, surr_window)
     if forced_spikes is not None:
         spikes = [np.ascontiguousarray(s, dtype=dt).copy() for s in forced_spikes]
     else:

@@ -30,6 +30,8 @@
  *     dv^l_t   = alpha * dv^l_{t+1} + sigma'(v^l_t - theta) * ds^l_t
  *     dW_in^l[j,:]  += s^{l-1}_t[j] * dv^l_t
  *     dW_rec^l[j,:] += s^l_{t-1}[j] * dv^l_t
+ *   optional window w > 0 (not in the paper; the compact-support variant that makes the spike
+ *   derivative sparse): sigma'(x) is replaced by 0 wherever |x| >= w.
  *
  * Every sum over presynaptic neurons runs over ascending j starting from 0 and
  * skips entries with s[j] == 0; the input sum and the recurrent sum are formed
@@ -121,6 +123,7 @@ typedef struct {
   int32_t C, F;     /* coarse (remote) and fine (local) checkpoint intervals */
   int32_t nthreads; /* OpenMP threads over the batch (1 = plain loop) */
   int32_t forced_states; /* 1: membrane potentials are inputs too (vtraj[] read, STANDARD only) */
+  double surr_window;    /* w > 0: sigma'(x) = 0 wherever |x| >= w (Heaviside mode only); <= 0: no window */
 } oracle_cfg;
 
 typedef struct {
@@ -145,6 +148,7 @@ typedef struct {
   const REAL *const *W_in, *const *W_rec;
   const REAL *W_out;
   REAL alpha, beta, theta, k;
+  float win; /* surrogate window, <= 0 for none */
 } net_t;
 
 static int npre(const net_t *n, int l) { return l == 0 ? n->c->n_in : n->c->n_hidden[l - 1]; }
@@ -155,6 +159,9 @@ static REAL spike_fn(const net_t *n, REAL x) {
   return x > (REAL)0 ? (REAL)1 : (REAL)0;
 }
 static REAL surrogate(const net_t *n, REAL x) {
+  /* The window test is a decision, so it is taken in single precision whatever REAL is: on an
+   * fp32 trajectory x = v - theta rounds to the float the single-precision build compares. */
+  if (n->win > 0.0f && !(fabsf((float)x) < n->win)) return (REAL)0;
   REAL d = (REAL)1 + n->k * (REAL)fabs((double)x);
   return (REAL)1 / (d * d);
 }
@@ -526,10 +533,12 @@ int FN(oracle_bptt)(const oracle_cfg *cfg, const REAL *const *W_in, const REAL *
   if (cfg->strategy == STRAT_HIER && (cfg->F < 1 || cfg->F > T || cfg->C < 1)) return 1;
   if (cfg->strategy < 0 || cfg->strategy > 4) return 1;
   if (cfg->forced_states && (cfg->strategy != STRAT_STANDARD || !cfg->forced || !vtraj)) return 1;
+  if (cfg->surr_window > 0 && cfg->mode != MODE_HEAVISIDE) return 1; /* S has no windowed antiderivative here */
 
   net_t n;
   n.c = cfg; n.L = L; n.W_in = W_in; n.W_rec = W_rec; n.W_out = W_out;
   n.alpha = (REAL)cfg->alpha; n.beta = (REAL)cfg->beta; n.theta = (REAL)cfg->theta; n.k = (REAL)cfg->surr_beta;
+  n.win = (float)cfg->surr_window;
   int off[17]; off[0] = 0;
   for (int l = 0; l < L; ++l) off[l + 1] = off[l] + cfg->n_hidden[l];
   n.off = off; n.SN = off[L];

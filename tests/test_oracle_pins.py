@@ -153,13 +153,10 @@ def test_backward_matches_finite_differences(seed, hidden):
         assert abs(fd - ana[i]) <= 1e-7 * max(1.0, np.abs(ana).max()) + 1e-9, (i, fd, ana[i])
 
 
-def test_backward_matches_autograd_with_surrogate():
-    """Heaviside forward with the surrogate derivative in the backward pass, against torch's
-    reverse-mode differentiation of an independently written forward (double precision).  The
-    backward equations of the oracle are hand-derived; here a library derives them."""
-    torch = pytest.importorskip("torch")
-    net = _tiny(7, n_in=6, hidden=(7, 5), n_out=4, T=9, B=3, scale=0.8)
-    alpha, beta, theta, k = 0.9, 0.85, 1.0, 10.0
+def _autograd_reference(net, alpha, beta, theta, k, window):
+    """Heaviside forward written with torch ops, the surrogate (cut to zero outside ``window``
+    when that is positive) as the backward of the threshold; torch derives everything else."""
+    import torch
 
     class Spike(torch.autograd.Function):
         @staticmethod
@@ -170,7 +167,11 @@ def test_backward_matches_autograd_with_surrogate():
         @staticmethod
         def backward(ctx, go):
             (x,) = ctx.saved_tensors
-            return go / (1 + k * x.abs()) ** 2
+            g = go / (1 + k * x.abs()) ** 2
+            if window > 0:
+                g = torch.where(x.abs().to(torch.float32) < torch.tensor(window, dtype=torch.float32),
+                                g, torch.zeros_like(g))
+            return g
 
     Wi = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in net["W_in"]]
     Wr = [torch.tensor(w, dtype=torch.float64, requires_grad=True) for w in net["W_rec"]]
@@ -181,26 +182,70 @@ def test_backward_matches_autograd_with_surrogate():
     s = [torch.zeros(B, n, dtype=torch.float64) for n in net["n_hidden"]]
     u = torch.zeros(B, net["n_out"], dtype=torch.float64)
     usum = torch.zeros_like(u)
-    spikes = []
+    spikes, inside = [], 0
     for t in range(T):
         below = x[t]
         for l in range(len(v)):
             v[l] = alpha * v[l] - theta * s[l] + below @ Wi[l] + s[l] @ Wr[l]
             s[l] = Spike.apply(v[l] - theta)
+            inside += int(((v[l] - theta).abs() < window).sum()) if window > 0 else 0
             below = s[l]
         spikes.append([q.detach().numpy().copy() for q in s])
         u = beta * u + s[-1] @ Wo
         usum = usum + u
     loss = torch.nn.functional.cross_entropy(usum / T, torch.tensor(net["labels"], dtype=torch.long))
     loss.backward()
+    return spikes, loss.item(), [w.grad.numpy() for w in Wi + Wr + [Wo]], inside
 
-    r = _run(net, dtype=np.float64, alpha=alpha, beta=beta, theta=theta, surr_beta=k)
-    for l in range(len(v)):
+
+@pytest.mark.parametrize("window", [0.0, 0.4])
+def test_backward_matches_autograd_with_surrogate(window):
+    """Heaviside forward with the surrogate derivative in the backward pass, against torch's
+    reverse-mode differentiation of an independently written forward (double precision).  The
+    backward equations of the oracle are hand-derived; here a library derives them.  With a
+    window the surrogate is zero wherever |v - theta| >= window."""
+    pytest.importorskip("torch")
+    net = _tiny(7, n_in=6, hidden=(7, 5), n_out=4, T=9, B=3, scale=0.8)
+    alpha, beta, theta, k = 0.9, 0.85, 1.0, 10.0
+    spikes, loss, grads, inside = _autograd_reference(net, alpha, beta, theta, k, window)
+
+    r = _run(net, dtype=np.float64, alpha=alpha, beta=beta, theta=theta, surr_beta=k, surr_window=window)
+    for l in range(len(net["n_hidden"])):
         assert np.array_equal(r.spikes[l], np.stack([sp[l] for sp in spikes]))
-    assert abs(r.loss - loss.item()) < 1e-12
-    for mine, ref in zip(r.dW_in + r.dW_rec + [r.dW_out], Wi + Wr + [Wo]):
-        assert np.allclose(mine, ref.grad.numpy(), rtol=1e-9, atol=1e-12)
+    assert abs(r.loss - loss) < 1e-12
+    for mine, ref in zip(r.dW_in + r.dW_rec + [r.dW_out], grads):
+        assert np.allclose(mine, ref, rtol=1e-9, atol=1e-12)
     assert any(np.abs(d).max() > 1e-6 for d in r.dW_rec)
+    if window > 0:  # the window must cut some neurons and keep others, else this case pins nothing
+        total = 9 * 3 * (7 + 5)
+        assert 0 < inside < total
+        full = _run(net, dtype=np.float64, alpha=alpha, beta=beta, theta=theta, surr_beta=k)
+        assert not np.allclose(full.dW_rec[0], r.dW_rec[0], rtol=1e-3, atol=0)
+
+
+def test_surrogate_window_limits():
+    """A window wider than any |v - theta| changes nothing, bit for bit; a window that admits no
+    neuron leaves only the readout gradient (dW_out does not pass through any threshold), and
+    the strategies still agree bit for bit with a window in force."""
+    net = _tiny(11, n_in=8, hidden=(9, 6), n_out=3, T=14, B=2, scale=0.9)
+    for dt in (np.float32, np.float64):
+        base = _run(net, dtype=dt, want_v=True)
+        vmax = max(np.abs(v - 1.0).max() for v in base.v)
+        wide = _run(net, dtype=dt, surr_window=float(vmax) * 2 + 1)
+        none = _run(net, dtype=dt, surr_window=1e-30)
+        for a, b in zip(base.dW_in + base.dW_rec + [base.dW_out], wide.dW_in + wide.dW_rec + [wide.dW_out]):
+            assert np.array_equal(a, b)
+        assert np.array_equal(none.dW_out, base.dW_out) and np.abs(base.dW_out).max() > 0
+        for d in none.dW_in + none.dW_rec:
+            assert not d.any()
+        mid = _run(net, dtype=dt, surr_window=0.5)
+        assert any(not np.array_equal(a, b) for a, b in zip(mid.dW_rec, base.dW_rec))
+        for strat, c, f in ((oracle.CHUNK, 0, 4), (oracle.REMOTE, 5, 0), (oracle.DOUBLE, 6, 2)):
+            o = _run(net, dtype=dt, surr_window=0.5, strategy=strat, coarse=c, fine=f)
+            for a, b in zip(mid.dW_in + mid.dW_rec + [mid.dW_out], o.dW_in + o.dW_rec + [o.dW_out]):
+                assert np.array_equal(a, b)
+    with pytest.raises(Exception):
+        _run(net, dtype=np.float64, mode=oracle.SMOOTH, surr_window=0.5)
 
 
 def test_masked_recurrent_gradient():
