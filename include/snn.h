@@ -21,7 +21,8 @@
  *   u_t   = beta u_{t-1} + sum_{j active in s^L_t} W_out[j,:] ;  ubar = mean_t u_t
  *   loss  = mean_b softmax-cross-entropy(ubar_b, y_b)
  * Backward pass: surrogate derivative 1/(1 + surr_beta |v - theta|)^2, full gradient
- * (also through the reset term).
+ * (also through the reset term).  With surr_window = w > 0 the derivative is cut to 0
+ * wherever |v - theta| >= w, the test taken in fp32 on the stored fp32 potential.
  *
  * Conventions.  Every function returns an snn_status (0 = success) unless noted;
  * nothing throws or aborts.  Pointers marked "host or device" may be either (the
@@ -67,6 +68,8 @@ typedef struct {
   float beta_out;                   /* readout leak                                    */
   float theta;                      /* threshold = reset amount                        */
   float surr_beta;                  /* k in 1/(1+k|v-theta|)^2                          */
+  float surr_window;                /* w > 0: the surrogate derivative is 0 wherever
+                                       |v-theta| >= w (compact support); <= 0: no window  */
   int32_t device;                   /* HIP device ordinal                              */
   void *stream;                     /* hipStream_t to queue work on; NULL = a stream the
                                        library creates (the legacy default stream cannot be

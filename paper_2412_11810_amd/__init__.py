@@ -31,7 +31,7 @@ class snn_config(C.Structure):
     _fields_ = [("n_in", C.c_int32), ("n_layers", C.c_int32), ("n_hidden", C.c_int32 * SNN_MAX_LAYERS),
                 ("n_out", C.c_int32), ("T", C.c_int32), ("batch", C.c_int32), ("alpha", C.c_float),
                 ("beta_out", C.c_float), ("theta", C.c_float), ("surr_beta", C.c_float),
-                ("device", C.c_int32), ("stream", C.c_void_p)]
+                ("surr_window", C.c_float), ("device", C.c_int32), ("stream", C.c_void_p)]
 
 
 class snn_stats(C.Structure):
@@ -103,12 +103,13 @@ def lib() -> C.CDLL:
 
 
 def make_config(n_in, n_hidden, n_out, T, batch, alpha=0.9, beta_out=0.9, theta=1.0, surr_beta=10.0,
-                device=0, stream=None) -> snn_config:
+                device=0, stream=None, surr_window=0.0) -> snn_config:
     cfg = snn_config()
     cfg.n_in, cfg.n_layers, cfg.n_out, cfg.T, cfg.batch = n_in, len(n_hidden), n_out, T, batch
     for i, n in enumerate(n_hidden):
         cfg.n_hidden[i] = n
     cfg.alpha, cfg.beta_out, cfg.theta, cfg.surr_beta = alpha, beta_out, theta, surr_beta
+    cfg.surr_window = surr_window
     cfg.device = device
     cfg.stream = stream
     return cfg
@@ -230,10 +231,11 @@ class Snn:
             pass
 
 
-def from_workload(w, data: dict, T: int | None = None, device: int = 0, stream=None) -> Snn:
+def from_workload(w, data: dict, T: int | None = None, device: int = 0, stream=None,
+                  surr_window: float = 0.0) -> Snn:
     """Context for a synth.Workload with its weights loaded."""
     cfg = make_config(w.n_in, list(w.n_hidden), w.n_out, T or w.T, w.B, w.alpha, w.beta, w.theta,
-                      w.surr_beta, device, stream)
+                      w.surr_beta, device, stream, surr_window)
     net = Snn(cfg)
     for l in range(len(w.n_hidden)):
         net.snn_set_weights(SNN_W_IN, l, data["W_in"][l])

@@ -101,6 +101,7 @@ bool valid_cfg(const snn_config *c, std::string *why) {
   for (int l = 0; l < c->n_layers; ++l)
     if (c->n_hidden[l] < 1 || c->n_hidden[l] > 65535) { *why = "n_hidden must be 1..65535"; return false; }
   if (c->n_in > 65535) { *why = "n_in must be <= 65535"; return false; }
+  if (!(c->surr_window == c->surr_window)) { *why = "surr_window must not be NaN"; return false; }
   return true;
 }
 
@@ -115,6 +116,7 @@ void fill_shape(const snn_config &c, NetDev *n) {
   }
   n->SN = n->off[c.n_layers];
   n->alpha = c.alpha; n->beta = c.beta_out; n->theta = c.theta; n->k = c.surr_beta;
+  n->win = c.surr_window;
 }
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }

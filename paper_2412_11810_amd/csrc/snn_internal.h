@@ -25,6 +25,7 @@ struct NetDev {
   const float *W_inT[SNN_MAXL], *W_recT[SNN_MAXL], *W_outT;
   uint64_t *mask[SNN_MAXL + 1];
   float alpha, beta, theta, k;
+  float win;  // surrogate window (<= 0: none)
 };
 
 // Where the forward / recompute kernel writes states it has to keep.

@@ -758,6 +758,15 @@ k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, i
   }
 }
 
+// Surrogate derivative of the threshold at membrane potential v: 1/(1 + k|v - theta|)^2, and 0
+// outside the window |v - theta| < win when a window is set (win > 0).
+__device__ __forceinline__ float surrogate(const NetDev &net, float v) {
+  const float x = fabsf(v - net.theta);
+  const float d = 1.0f + net.k * x;
+  const float g = 1.0f / (d * d);
+  return (net.win > 0.0f && !(x < net.win)) ? 0.0f : g;
+}
+
 // Recurrent part, layers of up to H*KH neurons: the recurrent matrix stays in registers for the
 // whole chunk.  Thread (jj, h) keeps W_rec[j][h*KH .. h*KH+KH) for the R postsynaptic rows
 // j = jj, jj + NJR, ..., jj + (R-1)*NJR (H threads per row, each a slice of the reduction; partial sums
@@ -850,8 +859,7 @@ k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
         for (int q = 1; q < H; ++q) sacc = sacc + part[q][j];
         const float dn = x[cur][j];
         const float ds = (sacc + upv) - net.theta * dn;
-        const float d = 1.0f + net.k * fabsf(vt - net.theta);
-        const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+        const float dvt = fmaf(ds, surrogate(net, vt), net.alpha * dn);
         x[cur ^ 1][j] = dvt;
         vbuf[(size_t)(t - t_base - 1) * slot_stride + (size_t)b * SN + off + j] = dvt;
       }
@@ -951,8 +959,7 @@ k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_
       for (int k = 1; k < 8; ++k) sacc = sacc + part[((size_t)k * 32 + (tid & 31)) * 8 + fbb];
       const float dn = xs[(size_t)fj * 8 + fbb];
       const float ds = (sacc + upv) - net.theta * dn;
-      const float d = 1.0f + net.k * fabsf(vt - net.theta);
-      const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+      const float dvt = fmaf(ds, surrogate(net, vt), net.alpha * dn);
       vbuf[slot * slot_stride + (size_t)fb * SN + off + fj] = dvt;
       xg[((size_t)par * B + fb) * N + fj] = dvt;
     }
@@ -1064,8 +1071,7 @@ k_adj_rec_stream(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, in
         for (int q = 1; q < KG; ++q) s = s + part[q * tile + jt];
         const float dn = x_next[j];
         const float ds = (s + upv) - net.theta * dn;
-        const float d = 1.0f + net.k * fabsf(vt - net.theta);
-        const float dvt = fmaf(ds, 1.0f / (d * d), net.alpha * dn);
+        const float dvt = fmaf(ds, surrogate(net, vt), net.alpha * dn);
         x_cur[j] = dvt;
         vrow[j] = dvt;
       }

@@ -22,7 +22,7 @@ def _oracle(w, d, **kw):
                        rec_mask=d.get("rec_mask"), dtype=np.float32, **kw)
 
 
-def _oracle_f64_on_f32_trajectory(w, d, ref32, nthreads):
+def _oracle_f64_on_f32_trajectory(w, d, ref32, nthreads, window=0.0):
     """Gradient reference: the oracle's backward pass in double precision, evaluated on the fp32 forward
     trajectory (spike trains and membrane potentials of the fp32 oracle, which the GPU reproduces bit for
     bit).  The fp32 oracle itself cannot serve at 1e-4: its sequential fp32 gradient sums over tens of
@@ -31,7 +31,7 @@ def _oracle_f64_on_f32_trajectory(w, d, ref32, nthreads):
                        d["labels"], alpha=w.alpha, beta=w.beta, theta=w.theta, surr_beta=w.surr_beta,
                        rec_mask=d.get("rec_mask"), dtype=np.float64,
                        forced_spikes=[s.astype(np.float64) for s in ref32.spikes],
-                       forced_v=[v.astype(np.float64) for v in ref32.v], nthreads=nthreads)
+                       forced_v=[v.astype(np.float64) for v in ref32.v], nthreads=nthreads, surr_window=window)
 
 
 def _gpu_grads(net, L):
@@ -75,11 +75,11 @@ def _identical(a, b):
     return all(np.array_equal(x, y) for x, y in zip(a[0] + a[1] + [a[2]], b[0] + b[1] + [b[2]]))
 
 
-def _full_parity(w, strategies, nthreads=8, check_states=True):
+def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0):
     d = synth.generate(w)
-    ref = _oracle(w, d, want_v=True, nthreads=nthreads)
-    ref64 = _oracle_f64_on_f32_trajectory(w, d, ref, nthreads)
-    net = snn.from_workload(w, d)
+    ref = _oracle(w, d, want_v=True, nthreads=nthreads, surr_window=window)
+    ref64 = _oracle_f64_on_f32_trajectory(w, d, ref, nthreads, window)
+    net = snn.from_workload(w, d, surr_window=window)
     try:
         loss = net.snn_forward(d["in_spikes"], d["labels"], w.T)
         assert _check_spikes(net, w, ref, w.name + " forward") == 0
@@ -106,6 +106,7 @@ def _full_parity(w, strategies, nthreads=8, check_states=True):
             assert st.fwd_steps == w.T and st.bwd_steps == w.T
             rates = [float(ref.spikes[l].mean()) for l in range(len(w.n_hidden))]
             assert np.allclose(list(st.firing_rate)[:len(rates)], rates, atol=1e-6)
+        return first, ref
     finally:
         net.snn_destroy()
 
@@ -156,6 +157,26 @@ def test_wide_layer_two_neurons_per_thread():
     """1024-wide layers (the width of configuration 2) at a short T: more than one neuron per thread."""
     w = synth.config(2, T=24, B=3)
     _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 10, 4)], nthreads=3)
+
+
+def test_surrogate_window():
+    """Surrogate derivative with compact support (zero where |v - theta| >= w): every adjoint kernel
+    (register-stationary, cross-workgroup for 512 and 1024 neurons, streaming for wider layers) against
+    the oracle with the same window, and the window must actually cut: the gradients differ from the
+    unwindowed ones while dW_out (which passes through no threshold) stays the same bit for bit."""
+    w0 = synth.config(0)
+    strategies = [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 7), (snn.SNN_REMOTE, 13, 0), (snn.SNN_DOUBLE, 17, 4),
+                  (snn.SNN_HIER, 2, 5)]
+    g_win, ref = _full_parity(w0, strategies, nthreads=1, window=0.5)
+    g_all, _ = _full_parity(w0, strategies[:1], nthreads=1)
+    inside = np.mean([float((np.abs(v - w0.theta) < 0.5).mean()) for v in ref.v])
+    print(f"[window 0.5] fraction of (t, b, neuron) inside the window: {inside:.3f}")
+    assert 0.0 < inside < 1.0
+    assert np.array_equal(g_win[2], g_all[2])
+    assert not np.array_equal(g_win[1][0], g_all[1][0])
+    wide = synth.Workload("window_40-300-1100-5", 40, (300, 1100), 5, T=20, B=3, p_in=0.1, gain=0.6, seed=21)
+    _full_parity(wide, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3)], nthreads=3, window=0.4)
+    _full_parity(synth.config(2, T=24, B=3), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 5)], nthreads=3, window=0.4)
 
 
 def test_config1_full_size():
