@@ -44,12 +44,13 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
-  struct GraphKeyT { int strategy, T, C, F; void *arena, *work, *host; bool dw_event; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event; } };
+  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event; } };
   GraphKeyT graph_key{};
   hipGraphExec_t graph_exec = nullptr;
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
   bool own_stream = false;
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
+  bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -121,12 +122,11 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
-// per-chunk scratch: readout adjoints [chunk][B][O] + inter-layer products of one layer [chunk][B][max N_l]
-// (the forward pass uses the same scratch for the currents of one time tile)
+// per-tile scratch of the adjoint pass: readout adjoints [tile][B][O] + one inter-layer product per layer
+// [tile][B][N_l] (the layers run one tile apart, so every layer's product is alive at once); the forward pass
+// uses the same scratch for the currents of one time tile
 size_t work_bytes(const NetDev &n, int chunk_len) {
-  int nmax = 0;
-  for (int l = 0; l < n.L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
-  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (n.n_out + nmax) * sizeof(float);
+  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (n.n_out + n.SN) * sizeof(float);
   // currents of one tile of every layer + readout currents of SNN_RO_TILES tiles
   const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + n.SN) * sizeof(float);
   return bwd > fwd ? bwd : fwd;
@@ -184,6 +184,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
     else if (std::strcmp(e, "direct") == 0) c->host_direct_max = ~(size_t)0;
   }
   if (const char *e = std::getenv("SNN_GRAPH")) c->graphs_enabled = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_BWD_PIPE")) c->bwd_pipeline = std::strcmp(e, "0") != 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -508,6 +509,108 @@ static snn_status check_ws_error(snn_ctx *c) {
 // Queues one whole training step on the context's streams; no host synchronisation inside, no
 // allocation, no hipMemsetAsync (fill kernels instead), so that the same code can be recorded into
 // a HIP graph.  The copy stream is forked from and joined back into the compute stream with events.
+// Adjoint pass, layers one tile apart.  Layer l of a tile needs layer l+1 of the same tile (through the
+// inter-layer product) and layer l of the tile after it in time (through the carried dv): while the top layer
+// works on the newest tile, layer L-2 works on the one before, and so on.  The L recurrences of a stage are
+// independent and go out together, so the sequential part of the backward pass is as long as one layer's, not
+// the sum over layers.  Nothing in the arithmetic depends on the grouping: each recurrence, product and
+// weight-gradient update sees the same operands in the same order as when a tile is finished layer by layer.
+struct BwdTile { int t0, t1, base, layer; float *vbuf, *du; };
+struct BwdPipe {
+  snn_ctx *c; const SpanHook *hk; Timer *tm; snn_stats *st; hipStream_t s;
+  float *du_base = nullptr, *up[SNN_MAXL]{};
+  bool first[SNN_MAXL + 1];
+  bool dw_wide = false;
+  std::vector<BwdTile> inflight; // oldest (lowest layer) first
+  std::vector<BwdTile> done;     // (tile, layer) pairs whose weight gradients are still to be added
+  bool dw_every_stage = true;
+
+  void init(int tile_rows) {
+    const NetDev &n = c->net;
+    du_base = c->dubuf;
+    float *q = c->dubuf + (size_t)tile_rows * n.B * n.n_out;
+    for (int l = 0; l < n.L; ++l) { up[l] = q; q += (size_t)tile_rows * n.B * n.N[l]; }
+    for (int l = 0; l <= n.L; ++l) first[l] = true;
+    int tiles4 = ((n.N[n.L - 1] + 63) / 64) * ((n.n_out + 63) / 64);
+    for (int l = 0; l < n.L; ++l)
+      tiles4 += ((pre_of(n, l) + 63) / 64) * ((n.N[l] + 63) / 64) + ((n.N[l] + 63) / 64) * ((n.N[l] + 63) / 64);
+    dw_wide = tiles4 >= 256;
+  }
+
+  // one stage: optionally admit a new tile at the top layer, run one layer of every tile in flight
+  snn_status stage(const BwdTile *fresh) {
+    const NetDev &n = c->net;
+    const int B = n.B, O = n.n_out, L = n.L;
+    if (fresh) {
+      BwdTile t = *fresh;
+      t.layer = L - 1;
+      t.du = du_base - (size_t)(t.t0 - t.base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
+      HIPCHK(c, launch_adjoint_head(n, t.t0, t.t1, t.base, t.du, c->g, c->carry, first[L] ? 1 : 0, up[L - 1], s, hk));
+      first[L] = false;
+      inflight.push_back(t);
+    }
+    if (inflight.empty()) return SNN_OK;
+    AdjJobs jobs{};
+    for (const BwdTile &t : inflight) {
+      const int l = t.layer;
+      jobs.j[jobs.count++] = AdjJob{l, t.t0, t.t1, t.base, first[l] ? 1 : 0, t.vbuf,
+                                    up[l] - (size_t)(t.t0 - t.base) * B * n.N[l]};
+      first[l] = false;
+    }
+    HIPCHK(c, launch_adjoint_jobs(n, jobs, c->carry, c->ws, s, hk));
+    // what each finished layer feeds: the product for the layer below, and its weight gradients
+    for (const BwdTile &t : inflight)
+      if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
+    for (const BwdTile &t : inflight) done.push_back(t);
+    for (BwdTile &t : inflight) --t.layer;
+    if (inflight.front().layer < 0) {
+      st->bwd_steps += inflight.front().t1 - inflight.front().t0;
+      inflight.erase(inflight.begin());
+    }
+    // weight gradients of everything finished so far: every stage when the layers are pipelined (a full set
+    // of matrices per stage), otherwise once per tile, when its last layer is done
+    if (dw_every_stage || inflight.empty()) return emit_dw();
+    return SNN_OK;
+  }
+  snn_status emit_dw() {
+    const NetDev &n = c->net;
+    const int B = n.B, O = n.n_out, L = n.L, SN = n.SN;
+    const size_t slot = (size_t)B * SN;
+    if (done.empty()) return SNN_OK;
+    tm->begin(3);
+    if (c->dw_event_driven || B > 128) {
+      for (const BwdTile &t : done) {
+        const int l = t.layer;
+        if (l == L - 1)
+          HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, t.du, (size_t)B * O, O, 0, O, B, t.t0, t.t1, t.base, c->acc_out, s));
+        HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_in[l], s));
+        HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_rec[l], s));
+      }
+    } else {
+      DwBatch db{};
+      db.wide = dw_wide ? 1 : 0;
+      for (const BwdTile &t : done) {
+        const int l = t.layer;
+        if (l == L - 1)
+          db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0};
+        db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, 0, 0};
+        db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0};
+      }
+      HIPCHK(c, launch_dw_mfma(db, B, s));
+    }
+    tm->end();
+    done.clear();
+    return SNN_OK;
+  }
+  snn_status flush() {
+    while (!inflight.empty()) {
+      const snn_status r = stage(nullptr);
+      if (r != SNN_OK) return r;
+    }
+    return SNN_OK;
+  }
+};
+
 static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &tm, hipEvent_t *ev_fwd_out) {
   NetDev &n = c->net;
   const int T = p.T, B = n.B, O = n.n_out, L = n.L, SN = n.SN;
@@ -515,8 +618,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   const size_t Ms = c->Ms(), slot = (size_t)B * SN;
   hipStream_t s = c->stream, cs = c->copy_stream;
   const SpanHook hk = tm.hook();
-  float *chunk = c->arena;                                   // chunk buffer / trajectory
-  float *lckpt = chunk + (size_t)p.chunk_len * slot;         // local checkpoints
+  float *const chunk0 = c->arena;                            // chunk buffer(s) / trajectory
+  float *lckpt = chunk0 + (size_t)p.chunk_len * p.n_chunk_bufs * slot; // local checkpoints
   float *loadb = lckpt + (size_t)p.n_local_ckpt * slot;      // 2 slots receiving host checkpoints
   float *stage = loadb + (size_t)p.n_load_slots * slot;      // 2 slots staging D2H copies
 
@@ -548,7 +651,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   // ---- forward ------------------------------------------------------------------------------
   HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
   if (strategy == SNN_STANDARD) {
-    StoreSpec sp{chunk, slot, 0, 1, 0, T, 0};
+    StoreSpec sp{chunk0, slot, 0, 1, 0, T, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T);
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
   } else if (strategy == SNN_CHUNK) {
@@ -663,8 +766,15 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   std::vector<SchedOp> ops((size_t)snn_make_schedule(p, nullptr, 0));
   snn_make_schedule(p, ops.data(), (int64_t)ops.size());
   int seg_start = 0, chunk_base = 0, cur_load = 0, n_loads = 0;
+  // Chunk buffers form a ring of n_chunk_bufs: with the layers of the adjoint pass one chunk apart, the
+  // lower layers of the previous chunk(s) are still being worked on while the next one is recomputed.
+  int n_chunks_done = 0;
+  float *chunk = chunk0; // buffer the next recomputation fills
+  const bool pipelined = L > 1 && c->bwd_pipeline && (strategy == SNN_STANDARD || p.n_chunk_bufs >= L);
+  BwdPipe pipe{c, &hk, &tm, &st, s};
+  pipe.init(std::min(p.chunk_len, SNN_BWD_TILE));
+  pipe.dw_every_stage = pipelined;
   const float *seg_src = nullptr; // state the current remote segment starts from (HBM load slot or host slot)
-  bool first_adjoint = true;
   // host->device loads run on the copy stream, behind every device->host copy of the forward pass
   auto issue_load = [&](int K, int slot_i) -> hipError_t {
     hipError_t e = hipSuccess;
@@ -756,39 +866,29 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       }
       case OP_BACKWARD: {
         // long spans (Standard: the whole sequence) are walked in tiles of SNN_BWD_TILE steps so that
-        // the per-chunk scratch stays small; neither the adjoint recurrence (carried state) nor the
+        // the per-tile scratch stays small; neither the adjoint recurrence (carried state) nor the
         // weight-gradient accumulation (continued per element) depends on where the cuts fall
         const int base = strategy == SNN_STANDARD ? 0 : chunk_base;
         for (int t1 = op.a; t1 >= op.b; t1 -= SNN_BWD_TILE) {
           const int t0 = std::max(op.b - 1, t1 - SNN_BWD_TILE);
-          float *du = c->dubuf - (size_t)(t0 - base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
-          float *upb = c->dubuf + (size_t)std::min(p.chunk_len, SNN_BWD_TILE) * B * O;
-          HIPCHK(c, launch_adjoint(n, t0, t1, chunk, base, du, c->g, c->carry, first_adjoint ? 1 : 0, upb, c->ws, s, &hk));
-          first_adjoint = false;
-          tm.begin(3);
-          if (c->dw_event_driven || B > 128) {
-            HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, du, (size_t)B * O, O, 0, O, B, t0, t1, base, c->acc_out, s));
-            for (int l = 0; l < L; ++l) {
-              HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_in[l], s));
-              HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, chunk, slot, SN, n.off[l], n.N[l], B, t0, t1, base, c->acc_rec[l], s));
-            }
-          } else {
-            DwBatch db{};
-            db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, du, (size_t)B * O, O, 0, c->acc_out, 0, 0};
-            for (int l = 0; l < L; ++l) {
-              db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], chunk, slot, SN, n.off[l], c->acc_in[l], 0, 0};
-              db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], chunk, slot, SN, n.off[l], c->acc_rec[l], 0, 0};
-            }
-            HIPCHK(c, launch_dw_mfma(db, B, t0, t1, base, s));
-          }
-          tm.end();
-          st.bwd_steps += t1 - t0;
+          const BwdTile tile{t0, t1, base, 0, chunk, nullptr};
+          snn_status rs = pipe.stage(&tile);
+          if (rs == SNN_OK && !pipelined) rs = pipe.flush();
+          if (rs != SNN_OK) return rs;
+        }
+        if (strategy != SNN_STANDARD) { // the next recomputation goes to the next buffer of the ring
+          ++n_chunks_done;
+          chunk = chunk0 + (size_t)(n_chunks_done % p.n_chunk_bufs) * p.chunk_len * slot;
         }
         break;
       }
       default:
         break; // SAVE_* happen in the forward pass; KEEP_FINE is part of REFWD1
     }
+  }
+  {
+    const snn_status rs = pipe.flush();
+    if (rs != SNN_OK) return rs;
   }
   for (int l = 0; l < L; ++l) {
     HIPCHK(c, launch_finish_grad(c->acc_in[l], nullptr, c->dW_in[l], (size_t)pre_of(n, l) * n.N[l], s));
@@ -811,6 +911,14 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   NetDev &n = c->net;
   const int B = n.B, L = n.L;
   const size_t Ms = c->Ms();
+  // One chunk buffer per layer lets the adjoint pass run its layers one chunk apart (see BwdPipe).  The extra
+  // (L - 1) * chunk_len state slots are taken only if the budget has room for them; the results are the same
+  // bit for bit either way.
+  if (L > 1 && c->bwd_pipeline && strategy != SNN_STANDARD) {
+    Plan q = p;
+    q.n_chunk_bufs = L;
+    if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T) <= budget) p = q;
+  }
   const size_t need_states = (size_t)p.local_slots() * Ms;
   const size_t need_work = work_bytes(n, p.chunk_len);
   const size_t need_spikes = spike_bytes(n, T);
@@ -856,7 +964,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // requested; the recording is redone whenever the plan or a buffer it refers to changes.
   const bool use_graph = c->graphs_enabled && !stats;
   if (use_graph) {
-    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven};
+    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
       Timer tm{c, false};

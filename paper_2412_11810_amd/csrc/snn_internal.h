@@ -82,10 +82,10 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s);
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
                        float *g, float *loss, hipStream_t s);
-// Adjoint pass over steps t1, t1-1, ..., t0+1.  vbuf holds x_t at slot (t - t_base - 1) and is
-// overwritten in place by delta_v_t.  dubuf gets delta_u_t at the same slot index ([slot][B][O]).
-// carry: [B][SN + O] floats (delta_v_{t+1} of all layers, delta_u_{t+1}); carry_init zeroes it first.
-// upbuf: scratch for the inter-layer products of one layer, (t1 - t0) * B * max_l N_l floats.
+// Adjoint pass over steps t1, t1-1, ..., t0+1 of a tile.  vbuf holds x_t at slot (t - t_base - 1) and is
+// overwritten in place by delta_v_t, layer by layer from the top.  Layer l of a tile needs layer l+1 of the
+// same tile and layer l of the later tile, so the layers of consecutive tiles can run one tile apart.
+// carry: [B][SN + O] floats (delta_v_{t+1} of all layers, delta_u_{t+1}); carry_init zeroes a layer's part first.
 // Exchange buffer, barrier counters and error flag of the chip-wide weight-stationary recurrent
 // kernel (see k_adj_rec_ws); xg == NULL disables that kernel.
 struct WsArgs {
@@ -95,9 +95,23 @@ struct WsArgs {
   int max_groups;      // workgroups of that kernel that can be resident at once
   unsigned spin_limit; // barrier polls before giving up
 };
-hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf,
-                          const float *g, float *carry, int carry_init, float *upbuf, const WsArgs &ws,
-                          hipStream_t s, const SpanHook *hook = nullptr);
+// One recurrence of the adjoint pass: layer l over steps t1, ..., t0+1 of a tile whose states sit in vbuf.
+// up: the inter-layer product of that layer and tile, addressed by absolute slot (row (t - t_base - 1)*B + b,
+// N_l columns), i.e. the buffer's base shifted back by (t0 - t_base)*B rows.
+struct AdjJob { int l, t0, t1, t_base, carry_init; float *vbuf; const float *up; };
+struct AdjJobs { AdjJob j[SNN_MAXL]; int count; };
+// du_t of a tile into dubuf (slot index as above, [slot][B][O]) and the top layer's product
+// up_top[(t - t0 - 1)*B + b][:] = W_out du_t.
+hipError_t launch_adjoint_head(const NetDev &net, int t0, int t1, int t_base, float *dubuf, const float *g,
+                               float *carry, int carry_init, float *up_top, hipStream_t s,
+                               const SpanHook *hook = nullptr);
+// up_l[(t - t0 - 1)*B + b][:] = W_in^{l+1} dv^{l+1}_t for a tile whose layer l+1 is done (dv in vbuf).
+hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_base, const float *vbuf, float *up_l,
+                             hipStream_t s, const SpanHook *hook = nullptr);
+// The recurrences of all jobs; jobs must be independent of each other (different layers of different
+// tiles).  Register-stationary layers of equal block size share one launch.
+hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *carry, const WsArgs &ws, hipStream_t s,
+                               const SpanHook *hook = nullptr);
 int ws_max_resident_groups(int device);
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
@@ -114,13 +128,15 @@ struct DwDesc {
   size_t slot_stride;
   int post_stride, post_off;
   double *acc;              // [n_pre][n_post] fp64 accumulators
+  int t0, t1, t_base;       // steps t1, ..., t0+1
   int tile0, tiles_n;       // filled by the launcher
 };
 struct DwBatch {
   DwDesc d[2 * SNN_MAXL + 1];
   int count;
+  int wide;                 // tile shape, fixed per network (see snn_dw_wide_tiles)
 };
-hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipStream_t s);
+hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
 hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,
@@ -137,11 +153,12 @@ struct SchedOp { int op, a, b; };
 struct Plan {
   int strategy, T, C, F;
   int chunk_len;      // slots of the chunk buffer (trajectory length for STANDARD)
+  int n_chunk_bufs;   // chunk buffers (1; n_layers when the adjoint pass runs its layers one chunk apart)
   int n_local_ckpt;   // HBM checkpoints (CHUNK: ceil(T/F); DOUBLE: fine checkpoints per segment)
   int n_load_slots;   // HBM slots receiving host checkpoints (prefetch double buffer)
   int n_stage_slots;  // HBM slots staging device->host copies (layers are pipelined, see launch_forward)
   int n_remote;       // host slots
-  int local_slots() const { return chunk_len + n_local_ckpt + n_load_slots + n_stage_slots; }
+  int local_slots() const { return chunk_len * n_chunk_bufs + n_local_ckpt + n_load_slots + n_stage_slots; }
 };
 // Resolves defaults (0 -> square-root rules) and validates.  Returns false on invalid arguments.
 bool snn_make_plan(int strategy, int T, int C, int F, Plan *out);

@@ -777,12 +777,16 @@ __device__ __forceinline__ float surrogate(const NetDev &net, float v) {
 // H*NJR threads.
 template <int KH, int H, int R>
 __global__ void __launch_bounds__(512)
-k_adj_rec_rs(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
-             int ldu, float *__restrict__ carry, int carry_init) {
+k_adj_rec_rs(NetDev net, AdjJobs jobs, float *__restrict__ carry) {
   __shared__ __align__(16) float x[2][H * KH];
   __shared__ float part[H][256];
   __shared__ float ring[2 * SNN_SEQ_GROUP][256];
-  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x;
+  // blockIdx.y selects the job: layers that are one tile apart in the layer pipeline share a launch
+  const AdjJob &jb = jobs.j[blockIdx.y];
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x, ldu = N;
   const int NJR = blockDim.x / H, tid = threadIdx.x;
   const int jj = tid % NJR, h = tid / NJR;
   const int j = tid;                 // finalising role: the first R*NJR threads own one row each
@@ -1144,11 +1148,12 @@ typedef double dvec4 __attribute__((ext_vector_type(4)));
 
 template <int NT, int CW>
 __global__ void __launch_bounds__(256 * CW)
-k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
+k_dw_mfma(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
   int di = 0;
   while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
   const DwDesc &d = batch.d[di];
+  const int t0 = d.t0, t1 = d.t1, t_base = d.t_base;
   const int tile = blockIdx.x - d.tile0;
   constexpr int COLS = 16 * NT * CW;
   const int j0 = (tile / d.tiles_n) * 64, n0 = (tile % d.tiles_n) * COLS;
@@ -1221,62 +1226,73 @@ k_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base) {
     }
   };
 
-  float reg[NPASS][4];
-  uint64_t wreg;
-  int t_hi = t1;
-  int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
-  stage_load(t_hi, nts, reg, wreg);
-  stage_store(0, nts, reg, wreg);
+  // Stage s covers steps t1 - s*TS, ... (TS of them, fewer in the last).  The loads of PF stages are in
+  // flight while a stage is multiplied.  Register sets are indexed statically (the stage loop is unrolled
+  // PF times); loads for stages past the end are still issued (clamped to the last stage) so that the
+  // number of loads in flight is the same on every path and the compiler can wait for exactly the oldest
+  // set.  Measured: a depth beyond 1 buys nothing (37.5 us per 32-step launch at PF = 4, 34.8 at PF = 1):
+  // the stage loop is bound by the matrix cores and the operand preparation, not by memory latency.
+  constexpr int PF = 1;
+  const int nstages = (t1 - t0 + TS - 1) / TS;
+  float reg[PF][NPASS][4];
+  uint64_t wreg[PF];
+  auto t_of = [&](int sidx) { return t1 - (sidx < nstages ? sidx : nstages - 1) * TS; };
+  auto n_of = [&](int sidx) { const int th = t_of(sidx); return th - t0 < TS ? th - t0 : TS; };
+#pragma unroll
+  for (int pf = 0; pf < PF; ++pf) stage_load(t_of(pf), n_of(pf), reg[pf], wreg[pf]);
+  stage_store(0, n_of(0), reg[0], wreg[0]);
   __syncthreads();
   int buf = 0;
-  while (t_hi > t0) {
-    const int t_nx = t_hi - nts;
-    const int nts_nx = t_nx - t0 < TS ? t_nx - t0 : TS;
-    if (t_nx > t0) stage_load(t_nx, nts_nx, reg, wreg); // global loads in flight during the MFMAs
-    const float *P = Pt + (size_t)buf * ROWS * STRIDE;
-    const uint64_t *S = Sw + (size_t)buf * ROWS;
-    // (t descending, b ascending), 4 batch elements per K-step.  The operands of KU K-steps are read
-    // from LDS one group ahead of the MFMAs that use them (rows past the stage's last one hold zeros,
-    // and the buffer has a whole group of them to spare only when the stage is not full: the read
-    // of the group after the last is clamped to the last one and discarded).
-    constexpr int KU = 4;
-    const int nrows = nts * Bp;
-    uint64_t word[2][KU];
-    float pv[2][KU][NT];
-    auto fetch = [&](int r0, uint64_t (&wd)[KU], float (&p)[KU][NT]) {
-      const int rr = r0 < nrows ? r0 : nrows - 4 * KU < 0 ? 0 : ((nrows - 1) / (4 * KU)) * (4 * KU);
+  for (int s0 = 0; s0 < nstages; s0 += PF) {
 #pragma unroll
-      for (int u = 0; u < KU; ++u) {
-        wd[u] = S[rr + 4 * u + lk];
-        const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + 16 * cb0 + li;
+    for (int pf = 0; pf < PF; ++pf) {
+      const int sidx = s0 + pf;
+      if (sidx >= nstages) break;
+      const int nts = n_of(sidx);
+      stage_load(t_of(sidx + PF), n_of(sidx + PF), reg[pf], wreg[pf]); // set pf went to LDS one stage ago
+      const float *P = Pt + (size_t)buf * ROWS * STRIDE;
+      const uint64_t *S = Sw + (size_t)buf * ROWS;
+      // (t descending, b ascending), 4 batch elements per K-step.  The operands of KU K-steps are read
+      // from LDS one group ahead of the MFMAs that use them (rows past the stage's last one hold zeros,
+      // and the buffer has a whole group of them to spare only when the stage is not full: the read
+      // of the group after the last is clamped to the last one and discarded).
+      constexpr int KU = 4;
+      const int nrows = nts * Bp;
+      uint64_t word[2][KU];
+      float pv[2][KU][NT];
+      auto fetch = [&](int r0, uint64_t (&wd)[KU], float (&p)[KU][NT]) {
+        const int rr = r0 < nrows ? r0 : nrows - 4 * KU < 0 ? 0 : ((nrows - 1) / (4 * KU)) * (4 * KU);
 #pragma unroll
-        for (int q = 0; q < NT; ++q) p[u][q] = prow[16 * q];
+        for (int u = 0; u < KU; ++u) {
+          wd[u] = S[rr + 4 * u + lk];
+          const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + 16 * cb0 + li;
+#pragma unroll
+          for (int q = 0; q < NT; ++q) p[u][q] = prow[16 * q];
+        }
+      };
+      auto mma = [&](const uint64_t (&wd)[KU], const float (&p)[KU][NT]) {
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          const bool bit = (wd[u] >> (16 * w + li)) & 1ull;
+          if (__ballot(bit) == 0ull) continue;
+          const double a = bit ? 1.0 : 0.0;
+#pragma unroll
+          for (int q = 0; q < NT; ++q)
+            acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)p[u][q], acc[q], 0, 0, 0);
+        }
+      };
+      fetch(0, word[0], pv[0]);
+      for (int r0 = 0; r0 < nrows; r0 += 8 * KU) {
+        fetch(r0 + 4 * KU, word[1], pv[1]);
+        mma(word[0], pv[0]);
+        if (r0 + 4 * KU >= nrows) break;
+        fetch(r0 + 8 * KU, word[0], pv[0]);
+        mma(word[1], pv[1]);
       }
-    };
-    auto mma = [&](const uint64_t (&wd)[KU], const float (&p)[KU][NT]) {
-#pragma unroll
-      for (int u = 0; u < KU; ++u) {
-        const bool bit = (wd[u] >> (16 * w + li)) & 1ull;
-        if (__ballot(bit) == 0ull) continue;
-        const double a = bit ? 1.0 : 0.0;
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-          acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)p[u][q], acc[q], 0, 0, 0);
-      }
-    };
-    fetch(0, word[0], pv[0]);
-    for (int r0 = 0; r0 < nrows; r0 += 8 * KU) {
-      fetch(r0 + 4 * KU, word[1], pv[1]);
-      mma(word[0], pv[0]);
-      if (r0 + 4 * KU >= nrows) break;
-      fetch(r0 + 8 * KU, word[0], pv[0]);
-      mma(word[1], pv[1]);
+      if (sidx + 1 < nstages) stage_store(buf ^ 1, n_of(sidx + 1), reg[(pf + 1) % PF], wreg[(pf + 1) % PF]);
+      __syncthreads();
+      buf ^= 1;
     }
-    if (t_nx > t0) stage_store(buf ^ 1, nts_nx, reg, wreg);
-    __syncthreads();
-    buf ^= 1;
-    t_hi = t_nx;
-    nts = nts_nx;
   }
 #pragma unroll
   for (int q = 0; q < NT; ++q)
@@ -1575,59 +1591,88 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
   return hipGetLastError();
 }
 
-hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_base, float *dubuf, const float *g,
-                          float *carry, int carry_init, float *upbuf, const WsArgs &ws, hipStream_t s,
-                          const SpanHook *hook) {
+static hipError_t launch_up_gemm(const float *A, int lda, const float *W, int K, int N, float *C, int M,
+                                 hipStream_t s) {
+  // The choice of kernel may depend on the layer's shape and on alignments that are the same for every
+  // tile (lda % 4 == 0 makes the alignment of A independent of the slot it starts at), never on M.
+  const bool aligned16 = K % 16 == 0 && lda % 4 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
+  if (aligned16 && (size_t)N * K <= 65536) {
+    const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
+    hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+  } else if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
+    hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+  else // small products: one wavefront per 32 x 32 block, so that more compute units take part
+    hipLaunchKernelGGL((k_up_gemm<1, 1>), dim3((M + 31) / 32, (N + 31) / 32), dim3(64), 0, s, A, lda, W, K, N, C, N, M);
+  return hipGetLastError();
+}
+
+hipError_t launch_adjoint_head(const NetDev &net, int t0, int t1, int t_base, float *dubuf, const float *g,
+                               float *carry, int carry_init, float *up_top, hipStream_t s, const SpanHook *hook) {
   if (t1 <= t0) return hipErrorInvalidValue;
-  auto hb = [&](int kind) { if (hook) hook->begin(hook->ctx, kind); };
-  auto he = [&]() { if (hook) hook->end(hook->ctx); };
-  const int B = net.B, O = net.n_out, SN = net.SN, L = net.L;
-  const int M = (t1 - t0) * B;
-  // slots are addressed relative to t_base; the chunk processed here starts at slot (t0 - t_base)
+  const int B = net.B, O = net.n_out, L = net.L;
   const size_t s0 = (size_t)(t0 - t_base);
-  hipLaunchKernelGGL(k_du_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, g, carry, dubuf, B, O, SN, t0, t1, t_base,
-                     net.beta, carry_init);
-  for (int l = L - 1; l >= 0; --l) {
-    const int N = net.N[l];
-    const float *A;
-    const float *W;
-    int lda, K;
-    if (l == L - 1) { A = dubuf + s0 * B * O; lda = O; K = O; W = net.W_out; }
-    else { A = vbuf + s0 * ((size_t)B * SN) + net.off[l + 1]; lda = SN; K = net.N[l + 1]; W = net.W_in[l + 1]; }
-    float *C = upbuf; // row m = (slot - s0)*B + b, ldc = N
-    hb(6);
-    const bool aligned16 = K % 16 == 0 && lda % 4 == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)W & 15) == 0;
-    if (aligned16 && (size_t)N * K <= 65536) {
-      const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
-      hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
-    } else if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
-      hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
-    else // small products: one wavefront per 32 x 32 block, so that more compute units take part
-      hipLaunchKernelGGL((k_up_gemm<1, 1>), dim3((M + 31) / 32, (N + 31) / 32), dim3(64), 0, s, A, lda, W, K, N, C, N, M);
-    he();
-    hb(2);
-    // the recurrent kernels index `up` by absolute slot: shift the base back by s0 rows of B
-    const float *up = upbuf - s0 * B * N;
-    if (N <= 256) {
-      const int nthr = 2 * ((N + 63) & ~63); // H threads per R postsynaptic rows, H = 2R
-      if (N <= 128)
-        hipLaunchKernelGGL((k_adj_rec_rs<16, 8, 4>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
-                           carry, carry_init);
-      else
-        hipLaunchKernelGGL((k_adj_rec_rs<32, 8, 4>), dim3(B), dim3(nthr), 0, s, net, l, t0, t1, vbuf, t_base, up, N,
-                           carry, carry_init);
-    } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
+  hipLaunchKernelGGL(k_du_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, g, carry, dubuf, B, O, net.SN, t0, t1,
+                     t_base, net.beta, carry_init);
+  if (hook) hook->begin(hook->ctx, 6);
+  const hipError_t e = launch_up_gemm(dubuf + s0 * B * O, O, net.W_out, O, net.N[L - 1], up_top, (t1 - t0) * B, s);
+  if (hook) hook->end(hook->ctx);
+  return e;
+}
+
+hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_base, const float *vbuf, float *up_l,
+                             hipStream_t s, const SpanHook *hook) {
+  if (t1 <= t0 || l < 0 || l + 1 >= net.L) return hipErrorInvalidValue;
+  const size_t s0 = (size_t)(t0 - t_base);
+  if (hook) hook->begin(hook->ctx, 6);
+  const hipError_t e = launch_up_gemm(vbuf + s0 * ((size_t)net.B * net.SN) + net.off[l + 1], net.SN, net.W_in[l + 1],
+                                      net.N[l + 1], net.N[l], up_l, (t1 - t0) * net.B, s);
+  if (hook) hook->end(hook->ctx);
+  return e;
+}
+
+hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *carry, const WsArgs &ws, hipStream_t s,
+                               const SpanHook *hook) {
+  const int B = net.B;
+  for (int i = 0; i < jobs.count; ++i)
+    if (jobs.j[i].t1 <= jobs.j[i].t0 || jobs.j[i].l < 0 || jobs.j[i].l >= net.L) return hipErrorInvalidValue;
+  if (hook) hook->begin(hook->ctx, 2);
+  // register-stationary layers of one size class go out together (blockIdx.y = job)
+  for (int cls = 0; cls < 2; ++cls) {
+    AdjJobs rs{};
+    int nthr = 0;
+    for (int i = 0; i < jobs.count; ++i) {
+      const int N = net.N[jobs.j[i].l];
+      if (N > 256 || (N <= 128) != (cls == 0)) continue;
+      const int nt = 2 * ((N + 63) & ~63); // H threads per R postsynaptic rows, H = 2R
+      if (nthr && nt != nthr) { // same class, different block size: a launch of its own
+        if (cls == 0) hipLaunchKernelGGL((k_adj_rec_rs<16, 8, 4>), dim3(B, rs.count), dim3(nthr), 0, s, net, rs, carry);
+        else hipLaunchKernelGGL((k_adj_rec_rs<32, 8, 4>), dim3(B, rs.count), dim3(nthr), 0, s, net, rs, carry);
+        rs.count = 0;
+      }
+      nthr = nt;
+      rs.j[rs.count++] = jobs.j[i];
+    }
+    if (rs.count) {
+      if (cls == 0) hipLaunchKernelGGL((k_adj_rec_rs<16, 8, 4>), dim3(B, rs.count), dim3(nthr), 0, s, net, rs, carry);
+      else hipLaunchKernelGGL((k_adj_rec_rs<32, 8, 4>), dim3(B, rs.count), dim3(nthr), 0, s, net, rs, carry);
+    }
+  }
+  for (int i = 0; i < jobs.count; ++i) {
+    const AdjJob &jb = jobs.j[i];
+    const int l = jb.l, N = net.N[l];
+    if (N <= 256) continue;
+    if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
       const int NR = N <= 512 ? 64 : 128;
       const size_t lds = ((size_t)NR * 8 * 8 + 8 * 32 * 8) * sizeof(float);
       hipError_t e = launch_fill_zero(ws.bar, 64 * sizeof(unsigned), s);
       if (e != hipSuccess) return e;
       if (NR == 64)
-        hipLaunchKernelGGL((k_adj_rec_ws<64>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, t0, t1, vbuf, t_base, up,
-                           N, carry, carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
+        hipLaunchKernelGGL((k_adj_rec_ws<64>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, jb.t0, jb.t1, jb.vbuf,
+                           jb.t_base, jb.up, N, carry, jb.carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
       else
-        hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, t0, t1, vbuf, t_base, up,
-                           N, carry, carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
+        hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, jb.t0, jb.t1, jb.vbuf,
+                           jb.t_base, jb.up, N, carry, jb.carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
     } else {
       const int nt = 1024;
       const size_t lds = ((size_t)2 * N + nt) * sizeof(float);
@@ -1636,11 +1681,11 @@ hipError_t launch_adjoint(const NetDev &net, int t0, int t1, float *vbuf, int t_
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
       }
-      hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), lds, s, net, l, t0, t1, vbuf, t_base, up, N, carry,
-                         carry_init);
+      hipLaunchKernelGGL(k_adj_rec_stream, dim3(B), dim3(nt), lds, s, net, l, jb.t0, jb.t1, jb.vbuf, jb.t_base, jb.up, N,
+                         carry, jb.carry_init);
     }
-    he();
   }
+  if (hook) hook->end(hook->ctx);
   return hipGetLastError();
 }
 
@@ -1663,14 +1708,15 @@ hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag
   return hipGetLastError();
 }
 
-hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipStream_t s) {
-  if (t1 <= t0 || batch.count <= 0) return hipSuccess;
+hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s) {
+  if (batch.count <= 0) return hipSuccess;
+  for (int i = 0; i < batch.count; ++i)
+    if (batch.d[i].t1 <= batch.d[i].t0) return hipErrorInvalidValue;
   const int Bp = (B + 3) & ~3;
   if (Bp > 128) return hipErrorInvalidValue; // the staging registers cover at most 128 batch rows
-  int tiles4 = 0;
-  for (int i = 0; i < batch.count; ++i) tiles4 += ((batch.d[i].n_pre + 63) / 64) * ((batch.d[i].n_post + 63) / 64);
-  // wide tiles when they already fill the chip; otherwise narrow ones and two wavefronts per SIMD
-  const bool wide = tiles4 >= 256 && Bp <= 64;
+  // wide tiles when the network's matrices already fill the chip with them; otherwise narrow ones and
+  // two wavefronts per SIMD
+  const bool wide = batch.wide && Bp <= 64;
   const int cols = wide ? 64 : 32; // a stage holds 4096 / cols rows
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
@@ -1680,8 +1726,8 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, int t0, int t1, int t_base, hipS
   }
   const int rows = 4096 / cols;
   const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
-  if (wide) hipLaunchKernelGGL((k_dw_mfma<4, 1>), dim3(total), dim3(256), lds, s, batch, B, t0, t1, t_base);
-  else hipLaunchKernelGGL((k_dw_mfma<1, 2>), dim3(total), dim3(512), lds, s, batch, B, t0, t1, t_base);
+  if (wide) hipLaunchKernelGGL((k_dw_mfma<4, 1>), dim3(total), dim3(256), lds, s, batch, B);
+  else hipLaunchKernelGGL((k_dw_mfma<1, 2>), dim3(total), dim3(512), lds, s, batch, B);
   return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
   Plan q{};
   q.strategy = strategy;
   q.T = T;
+  q.n_chunk_bufs = 1;
   switch (strategy) {
     case 0: // STANDARD: every state
       q.C = q.F = 0;

@@ -264,6 +264,45 @@ def test_graph_replay_matches_eager():
     net.snn_destroy()
 
 
+def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
+    """The adjoint pass runs its layers one chunk apart (layer l of chunk c together with layer l+1 of the
+    chunk before it in time) when the budget has room for one chunk buffer per layer; otherwise, or with
+    SNN_BWD_PIPE=0, it finishes a chunk layer by layer.  Gradients must not differ by a bit, for every strategy,
+    with chunks longer and shorter than the adjoint tile, three layers, and mixed kernel flavours."""
+    cases = [(synth.config(1, T=300, B=6), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 7), (snn.SNN_REMOTE, 32, 0),
+                                             (snn.SNN_DOUBLE, 100, 10), (snn.SNN_HIER, 2, 16), (snn.SNN_CHUNK, 0, 290)]),
+             (synth.Workload("pipe_50-100-72-300-7", 50, (100, 72, 300), 7, T=45, B=3, p_in=0.1, gain=0.5, seed=31),
+              [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 12, 5), (snn.SNN_REMOTE, 1, 0)])]
+    for w, strategies in cases:
+        d = synth.generate(w)
+        L = len(w.n_hidden)
+        got = {}
+        for mode in ("1", "0"):
+            monkeypatch.setenv("SNN_BWD_PIPE", mode)
+            net = snn.from_workload(w, d)
+            try:
+                net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+                for strat, C, F in strategies:
+                    st = net.snn_bptt(strat, C, F)
+                    got[(mode, strat, C, F)] = (_gpu_grads(net, L), st.local_state_slots)
+                    if mode == "1":  # a budget with no room for the extra chunk buffers: same result, fewer slots
+                        need = snn.snn_bytes_required(net.cfg, strat, w.T, C, F)
+                        st2 = net.snn_bptt(strat, C, F, need)
+                        assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
+                        assert st2.local_state_slots == snn.snn_state_slots(strat, w.T, C, F)[0]
+                        net.snn_bptt(strat, C, F, want_stats=False)  # and through graph replay
+                        assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
+            finally:
+                net.snn_destroy()
+        for strat, C, F in strategies:
+            a, b = got[("1", strat, C, F)], got[("0", strat, C, F)]
+            assert _identical(a[0], b[0]), (w.name, strat, C, F)
+            assert _identical(a[0], got[("1",) + strategies[0]][0]), (w.name, strat, C, F)
+            if strat != snn.SNN_STANDARD:
+                assert a[1] > b[1] == snn.snn_state_slots(strat, w.T, C, F)[0]
+    monkeypatch.delenv("SNN_BWD_PIPE")
+
+
 def test_gather_and_matrix_core_currents_agree(monkeypatch):
     """The synaptic currents are computed either event by event (gather of the active rows) or by the K = 1
     MFMA kernel, which visits the same rows in the same order.  Both must give the very same bits: spike
