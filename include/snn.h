@@ -84,6 +84,8 @@ typedef struct {
                                                     recurrent adjoint kernels, weight-gradient kernels */
   float ms_fwd_seq, ms_fwd_currents, ms_up_gemm; /* forward: sequential per-layer kernels / parallel current and
                                                     readout kernels; adjoint: inter-layer GEMMs */
+  float ms_bwd_stage;        /* launches that carry the recurrences of one pipeline stage together with the
+                                weight-gradient contraction of the stage before (not in ms_adjoint / ms_dw) */
   int64_t bytes_states;      /* HBM: trajectory / chunk buffer / checkpoints / staging slots */
   int64_t bytes_spikes;      /* HBM: spike bitmasks of all layers, all steps                  */
   int64_t bytes_workspace;   /* HBM: readout-adjoint tile and other per-chunk scratch          */

@@ -51,6 +51,7 @@ struct snn_ctx {
   bool own_stream = false;
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
   bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
+  bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -122,14 +123,22 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
-// per-tile scratch of the adjoint pass: readout adjoints [tile][B][O] + one inter-layer product per layer
+// per-tile scratch of the adjoint pass: readout adjoints 2 x [tile][B][O] (two tiles alive) + one inter-layer product per layer
 // [tile][B][N_l] (the layers run one tile apart, so every layer's product is alive at once); the forward pass
 // uses the same scratch for the currents of one time tile
 size_t work_bytes(const NetDev &n, int chunk_len) {
-  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (n.n_out + n.SN) * sizeof(float);
+  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (2 * n.n_out + n.SN) * sizeof(float);
   // currents of one tile of every layer + readout currents of SNN_RO_TILES tiles
   const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + n.SN) * sizeof(float);
   return bwd > fwd ? bwd : fwd;
+}
+
+// tile shape of the dense weight-gradient contraction: wide tiles when the network's matrices fill the chip with them
+bool dw_wide_tiles(const NetDev &n) {
+  int tiles4 = ((n.N[n.L - 1] + 63) / 64) * ((n.n_out + 63) / 64);
+  for (int l = 0; l < n.L; ++l)
+    tiles4 += ((pre_of(n, l) + 63) / 64) * ((n.N[l] + 63) / 64) + ((n.N[l] + 63) / 64) * ((n.N[l] + 63) / 64);
+  return tiles4 >= 256;
 }
 
 size_t spike_bytes(const NetDev &n, int T) {
@@ -185,6 +194,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   }
   if (const char *e = std::getenv("SNN_GRAPH")) c->graphs_enabled = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_BWD_PIPE")) c->bwd_pipeline = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -518,23 +528,23 @@ static snn_status check_ws_error(snn_ctx *c) {
 struct BwdTile { int t0, t1, base, layer; float *vbuf, *du; };
 struct BwdPipe {
   snn_ctx *c; const SpanHook *hk; Timer *tm; snn_stats *st; hipStream_t s;
-  float *du_base = nullptr, *up[SNN_MAXL]{};
+  float *du_base[2]{}, *up[SNN_MAXL]{};
+  int du_sel = 0;
   bool first[SNN_MAXL + 1];
   bool dw_wide = false;
+  bool fused = false; // the weight gradients of a stage ride along with the recurrences of the next one
   std::vector<BwdTile> inflight; // oldest (lowest layer) first
   std::vector<BwdTile> done;     // (tile, layer) pairs whose weight gradients are still to be added
   bool dw_every_stage = true;
 
   void init(int tile_rows) {
     const NetDev &n = c->net;
-    du_base = c->dubuf;
-    float *q = c->dubuf + (size_t)tile_rows * n.B * n.n_out;
+    du_base[0] = c->dubuf;
+    du_base[1] = c->dubuf + (size_t)tile_rows * n.B * n.n_out;
+    float *q = c->dubuf + (size_t)2 * tile_rows * n.B * n.n_out;
     for (int l = 0; l < n.L; ++l) { up[l] = q; q += (size_t)tile_rows * n.B * n.N[l]; }
     for (int l = 0; l <= n.L; ++l) first[l] = true;
-    int tiles4 = ((n.N[n.L - 1] + 63) / 64) * ((n.n_out + 63) / 64);
-    for (int l = 0; l < n.L; ++l)
-      tiles4 += ((pre_of(n, l) + 63) / 64) * ((n.N[l] + 63) / 64) + ((n.N[l] + 63) / 64) * ((n.N[l] + 63) / 64);
-    dw_wide = tiles4 >= 256;
+    dw_wide = dw_wide_tiles(n);
   }
 
   // one stage: optionally admit a new tile at the top layer, run one layer of every tile in flight
@@ -544,7 +554,8 @@ struct BwdPipe {
     if (fresh) {
       BwdTile t = *fresh;
       t.layer = L - 1;
-      t.du = du_base - (size_t)(t.t0 - t.base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
+      t.du = du_base[du_sel] - (size_t)(t.t0 - t.base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
+      du_sel ^= 1; // the previous tile's du is still to be read by its weight-gradient update
       HIPCHK(c, launch_adjoint_head(n, t.t0, t.t1, t.base, t.du, c->g, c->carry, first[L] ? 1 : 0, up[L - 1], s, hk));
       first[L] = false;
       inflight.push_back(t);
@@ -557,7 +568,14 @@ struct BwdPipe {
                                     up[l] - (size_t)(t.t0 - t.base) * B * n.N[l]};
       first[l] = false;
     }
-    HIPCHK(c, launch_adjoint_jobs(n, jobs, c->carry, c->ws, s, hk));
+    if (fused && !done.empty()) {
+      DwBatch db{};
+      fill_dw_batch(&db);
+      HIPCHK(c, launch_bwd_stage(n, jobs, c->carry, db, s, hk));
+      done.clear();
+    } else {
+      HIPCHK(c, launch_adjoint_jobs(n, jobs, c->carry, c->ws, s, hk));
+    }
     // what each finished layer feeds: the product for the layer below, and its weight gradients
     for (const BwdTile &t : inflight)
       if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
@@ -569,8 +587,21 @@ struct BwdPipe {
     }
     // weight gradients of everything finished so far: every stage when the layers are pipelined (a full set
     // of matrices per stage), otherwise once per tile, when its last layer is done
-    if (dw_every_stage || inflight.empty()) return emit_dw();
+    if (fused ? inflight.empty() : (dw_every_stage || inflight.empty())) return emit_dw();
     return SNN_OK;
+  }
+  void fill_dw_batch(DwBatch *db) const {
+    const NetDev &n = c->net;
+    const int B = n.B, O = n.n_out, L = n.L, SN = n.SN;
+    const size_t slot = (size_t)B * SN;
+    db->wide = dw_wide ? 1 : 0;
+    for (const BwdTile &t : done) {
+      const int l = t.layer;
+      if (l == L - 1)
+        db->d[db->count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0};
+      db->d[db->count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, 0, 0};
+      db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0};
+    }
   }
   snn_status emit_dw() {
     const NetDev &n = c->net;
@@ -588,14 +619,7 @@ struct BwdPipe {
       }
     } else {
       DwBatch db{};
-      db.wide = dw_wide ? 1 : 0;
-      for (const BwdTile &t : done) {
-        const int l = t.layer;
-        if (l == L - 1)
-          db.d[db.count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0};
-        db.d[db.count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, 0, 0};
-        db.d[db.count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0};
-      }
+      fill_dw_batch(&db);
       HIPCHK(c, launch_dw_mfma(db, B, s));
     }
     tm->end();
@@ -774,6 +798,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   BwdPipe pipe{c, &hk, &tm, &st, s};
   pipe.init(std::min(p.chunk_len, SNN_BWD_TILE));
   pipe.dw_every_stage = pipelined;
+  pipe.fused = pipelined && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, pipe.dw_wide) &&
+               (strategy == SNN_STANDARD || p.n_chunk_bufs >= L + 1);
   const float *seg_src = nullptr; // state the current remote segment starts from (HBM load slot or host slot)
   // host->device loads run on the copy stream, behind every device->host copy of the forward pass
   auto issue_load = [&](int K, int slot_i) -> hipError_t {
@@ -915,9 +941,13 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // (L - 1) * chunk_len state slots are taken only if the budget has room for them; the results are the same
   // bit for bit either way.
   if (L > 1 && c->bwd_pipeline && strategy != SNN_STANDARD) {
-    Plan q = p;
-    q.n_chunk_bufs = L;
-    if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T) <= budget) p = q;
+    // one more buffer when the weight gradients of a stage are fused into the next stage's launch
+    const bool fuse = c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0);
+    for (int nb = fuse ? L + 1 : L; nb >= L; --nb) {
+      Plan q = p;
+      q.n_chunk_bufs = nb;
+      if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T) <= budget) { p = q; break; }
+    }
   }
   const size_t need_states = (size_t)p.local_slots() * Ms;
   const size_t need_work = work_bytes(n, p.chunk_len);
@@ -1013,6 +1043,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         case 3: st.ms_dw += ms; break;
         case 4: st.ms_fwd_seq += ms; break;
         case 5: st.ms_fwd_currents += ms; break;
+        case 7: st.ms_bwd_stage += ms; break;
         default: st.ms_up_gemm += ms; break;
       }
     }

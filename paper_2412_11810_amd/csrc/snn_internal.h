@@ -41,7 +41,8 @@ struct StoreSpec {
 
 // Optional timing hook: the launchers bracket groups of kernels of one kind (HIP events on the
 // stream the kernels run on).  Kinds: 1 recompute, 2 adjoint recurrence, 3 dW, 4 forward sequential
-// part, 5 forward parallel currents + readout, 6 inter-layer GEMM of the adjoint pass.
+// part, 5 forward parallel currents + readout, 6 inter-layer GEMM of the adjoint pass, 7 fused stage
+// (recurrences + weight gradients of the previous stage).
 struct SpanHook {
   void *ctx;
   void (*begin)(void *ctx, int kind);
@@ -137,6 +138,12 @@ struct DwBatch {
   int wide;                 // tile shape, fixed per network (see snn_dw_wide_tiles)
 };
 hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
+// The recurrences of a stage and the weight-gradient contraction of the previous stage in one launch
+// (see k_bwd_stage).  Only for networks bwd_stage_fusable() accepts; the caller guarantees that the two
+// parts touch different tiles.
+bool bwd_stage_fusable(const NetDev &net, int dw_wide);
+hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, hipStream_t s,
+                            const SpanHook *hook = nullptr);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
 hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,

@@ -776,17 +776,14 @@ __device__ __forceinline__ float surrogate(const NetDev &net, float v) {
 // (operands staged G steps ahead), two barriers per step.  One workgroup per batch element,
 // H*NJR threads.
 template <int KH, int H, int R>
-__global__ void __launch_bounds__(512)
-k_adj_rec_rs(NetDev net, AdjJobs jobs, float *__restrict__ carry) {
+__device__ __forceinline__ void adj_rec_rs_body(const NetDev &net, const AdjJob &jb, float *__restrict__ carry, int b) {
   __shared__ __align__(16) float x[2][H * KH];
   __shared__ float part[H][256];
   __shared__ float ring[2 * SNN_SEQ_GROUP][256];
-  // blockIdx.y selects the job: layers that are one tile apart in the layer pipeline share a launch
-  const AdjJob &jb = jobs.j[blockIdx.y];
   const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
   float *__restrict__ vbuf = jb.vbuf;
   const float *__restrict__ up = jb.up;
-  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, b = blockIdx.x, ldu = N;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, ldu = N;
   const int NJR = blockDim.x / H, tid = threadIdx.x;
   const int jj = tid % NJR, h = tid / NJR;
   const int j = tid;                 // finalising role: the first R*NJR threads own one row each
@@ -872,6 +869,13 @@ k_adj_rec_rs(NetDev net, AdjJobs jobs, float *__restrict__ carry) {
     }
   }
   if (own) cb[j] = x[cur][j];
+}
+
+// blockIdx.y selects the job: layers that are one tile apart in the layer pipeline share a launch
+template <int KH, int H, int R>
+__global__ void __launch_bounds__(512)
+k_adj_rec_rs(NetDev net, AdjJobs jobs, float *__restrict__ carry) {
+  adj_rec_rs_body<KH, H, R>(net, jobs.j[blockIdx.y], carry, blockIdx.x);
 }
 
 // Recurrent part, wide layers (N/8 weights per thread fit in registers, N <= 1024): the recurrent
@@ -1147,14 +1151,12 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
 typedef double dvec4 __attribute__((ext_vector_type(4)));
 
 template <int NT, int CW>
-__global__ void __launch_bounds__(256 * CW)
-k_dw_mfma(DwBatch batch, int B) {
-  extern __shared__ __align__(16) unsigned char smem[];
+__device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vblock, unsigned char *smem) {
   int di = 0;
-  while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
+  while (di + 1 < batch.count && vblock >= batch.d[di + 1].tile0) ++di;
   const DwDesc &d = batch.d[di];
   const int t0 = d.t0, t1 = d.t1, t_base = d.t_base;
-  const int tile = blockIdx.x - d.tile0;
+  const int tile = vblock - d.tile0;
   constexpr int COLS = 16 * NT * CW;
   const int j0 = (tile / d.tiles_n) * 64, n0 = (tile % d.tiles_n) * COLS;
   // wavefront (w, cg): presynaptic rows 16w .. 16w+15 of the tile, column blocks NT*cg .. NT*cg+NT-1.
@@ -1301,6 +1303,29 @@ k_dw_mfma(DwBatch batch, int B) {
       const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * (cb0 + q) + li;
       if (j < d.n_pre && n < d.n_post) d.acc[(size_t)j * d.n_post + n] = acc[q][r];
     }
+}
+
+template <int NT, int CW>
+__global__ void __launch_bounds__(256 * CW)
+k_dw_mfma(DwBatch batch, int B) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  dw_mfma_body<NT, CW>(batch, B, (int)blockIdx.x, smem);
+}
+
+// One stage of the layer-pipelined backward pass in a single launch: the first n_adj_blocks workgroups run
+// the adjoint recurrences of the stage (job = block / B, batch element = block % B), the others the
+// weight-gradient contraction of what the previous stage finished.  The two are independent, and the
+// recurrences (a chain of dependent steps on a few dozen compute units) leave most of the chip idle: the
+// contraction fills it.  The launcher asks for enough LDS that no two workgroups share a compute unit, so
+// that a contraction workgroup never competes with a recurrence for issue slots.
+template <int KH, int H, int R>
+__global__ void __launch_bounds__(512)
+k_bwd_stage(NetDev net, AdjJobs jobs, float *__restrict__ carry, DwBatch batch, int n_adj_blocks) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  if ((int)blockIdx.x < n_adj_blocks) // uniform per workgroup
+    adj_rec_rs_body<KH, H, R>(net, jobs.j[blockIdx.x / net.B], carry, (int)blockIdx.x % net.B);
+  else
+    dw_mfma_body<1, 2>(batch, net.B, (int)blockIdx.x - n_adj_blocks, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1728,6 +1753,46 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s) {
   const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
   if (wide) hipLaunchKernelGGL((k_dw_mfma<4, 1>), dim3(total), dim3(256), lds, s, batch, B);
   else hipLaunchKernelGGL((k_dw_mfma<1, 2>), dim3(total), dim3(512), lds, s, batch, B);
+  return hipGetLastError();
+}
+
+bool bwd_stage_fusable(const NetDev &net, int dw_wide) {
+  // the fused stage kernel is built for 512-thread recurrences (layers of 193..256 neurons) and the narrow
+  // contraction tiles
+  const int Bp = (net.B + 3) & ~3;
+  if ((dw_wide && Bp <= 64) || Bp > 128 || net.L < 2) return false;
+  for (int l = 0; l < net.L; ++l)
+    if (net.N[l] <= 192 || net.N[l] > 256) return false;
+  return true;
+}
+
+hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, hipStream_t s,
+                            const SpanHook *hook) {
+  if (!bwd_stage_fusable(net, batch.wide) || jobs.count < 1 || batch.count < 1) return hipErrorInvalidValue;
+  for (int i = 0; i < jobs.count; ++i)
+    if (jobs.j[i].t1 <= jobs.j[i].t0 || jobs.j[i].l < 0 || jobs.j[i].l >= net.L) return hipErrorInvalidValue;
+  for (int i = 0; i < batch.count; ++i)
+    if (batch.d[i].t1 <= batch.d[i].t0) return hipErrorInvalidValue;
+  const int cols = 32, rows = 4096 / cols;
+  int total = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    batch.d[i].tiles_n = (batch.d[i].n_post + cols - 1) / cols;
+    batch.d[i].tile0 = total;
+    total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
+  }
+  // the recurrence part holds 26 KB of static LDS; asking for 56 KB more puts the total above half of a
+  // compute unit's 160 KB, so every workgroup gets a compute unit of its own
+  size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
+  if (lds < 56 * 1024) lds = 56 * 1024;
+  {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_stage<32, 8, 4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  const int n_adj = net.B * jobs.count;
+  if (hook) hook->begin(hook->ctx, 7);
+  hipLaunchKernelGGL((k_bwd_stage<32, 8, 4>), dim3(n_adj + total), dim3(512), lds, s, net, jobs, carry, batch, n_adj);
+  if (hook) hook->end(hook->ctx);
   return hipGetLastError();
 }
 

@@ -266,41 +266,58 @@ def test_graph_replay_matches_eager():
 
 def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
     """The adjoint pass runs its layers one chunk apart (layer l of chunk c together with layer l+1 of the
-    chunk before it in time) when the budget has room for one chunk buffer per layer; otherwise, or with
-    SNN_BWD_PIPE=0, it finishes a chunk layer by layer.  Gradients must not differ by a bit, for every strategy,
-    with chunks longer and shorter than the adjoint tile, three layers, and mixed kernel flavours."""
+    chunk before it in time) when the budget has room for one chunk buffer per layer, and for layers of
+    193..256 neurons the weight gradients of a stage ride in the next stage's launch (one more buffer);
+    otherwise, or with SNN_BWD_PIPE=0 / SNN_BWD_FUSE=0, it falls back step by step to finishing a chunk layer
+    by layer.  Gradients must not differ by a bit, for every strategy, with chunks longer and shorter than the
+    adjoint tile, three layers, and mixed kernel flavours."""
     cases = [(synth.config(1, T=300, B=6), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 7), (snn.SNN_REMOTE, 32, 0),
                                              (snn.SNN_DOUBLE, 100, 10), (snn.SNN_HIER, 2, 16), (snn.SNN_CHUNK, 0, 290)]),
+             (synth.Workload("pipe_50-200-256-230-7", 50, (200, 256, 230), 7, T=70, B=5, p_in=0.1, gain=0.5, seed=32),
+              [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 9), (snn.SNN_DOUBLE, 30, 4), (snn.SNN_REMOTE, 1, 0)]),
              (synth.Workload("pipe_50-100-72-300-7", 50, (100, 72, 300), 7, T=45, B=3, p_in=0.1, gain=0.5, seed=31),
               [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 12, 5), (snn.SNN_REMOTE, 1, 0)])]
+    modes = {"fused": {}, "pipelined": {"SNN_BWD_FUSE": "0"}, "plain": {"SNN_BWD_PIPE": "0"}}
     for w, strategies in cases:
         d = synth.generate(w)
         L = len(w.n_hidden)
+        fusable = all(192 < n <= 256 for n in w.n_hidden)
         got = {}
-        for mode in ("1", "0"):
-            monkeypatch.setenv("SNN_BWD_PIPE", mode)
+        for mode, env in modes.items():
+            for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE"):
+                monkeypatch.delenv(k, raising=False)
+            for k, v in env.items():
+                monkeypatch.setenv(k, v)
             net = snn.from_workload(w, d)
             try:
                 net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
                 for strat, C, F in strategies:
                     st = net.snn_bptt(strat, C, F)
-                    got[(mode, strat, C, F)] = (_gpu_grads(net, L), st.local_state_slots)
-                    if mode == "1":  # a budget with no room for the extra chunk buffers: same result, fewer slots
+                    got[(mode, strat, C, F)] = (_gpu_grads(net, L), st.local_state_slots, st.ms_bwd_stage)
+                    if mode == "fused":
+                        # budgets with room for fewer chunk buffers: same result, fewer slots
                         need = snn.snn_bytes_required(net.cfg, strat, w.T, C, F)
                         st2 = net.snn_bptt(strat, C, F, need)
                         assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
                         assert st2.local_state_slots == snn.snn_state_slots(strat, w.T, C, F)[0]
+                        chunk_len = {snn.SNN_CHUNK: F, snn.SNN_REMOTE: C, snn.SNN_DOUBLE: F, snn.SNN_HIER: F}.get(strat, 0)
+                        st3 = net.snn_bptt(strat, C, F, need + (L - 1) * chunk_len * 4 * w.B * sum(w.n_hidden))
+                        assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
+                        assert st3.ms_bwd_stage == 0 or strat == snn.SNN_STANDARD
                         net.snn_bptt(strat, C, F, want_stats=False)  # and through graph replay
                         assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
             finally:
                 net.snn_destroy()
         for strat, C, F in strategies:
-            a, b = got[("1", strat, C, F)], got[("0", strat, C, F)]
-            assert _identical(a[0], b[0]), (w.name, strat, C, F)
-            assert _identical(a[0], got[("1",) + strategies[0]][0]), (w.name, strat, C, F)
+            a, b, c = (got[(m, strat, C, F)] for m in ("fused", "pipelined", "plain"))
+            assert _identical(a[0], b[0]) and _identical(a[0], c[0]), (w.name, strat, C, F)
+            assert _identical(a[0], got[("fused",) + strategies[0]][0]), (w.name, strat, C, F)
+            assert (a[2] > 0) == fusable and b[2] == 0 and c[2] == 0
             if strat != snn.SNN_STANDARD:
-                assert a[1] > b[1] == snn.snn_state_slots(strat, w.T, C, F)[0]
-    monkeypatch.delenv("SNN_BWD_PIPE")
+                assert b[1] > c[1] == snn.snn_state_slots(strat, w.T, C, F)[0]
+                assert (a[1] > b[1]) == fusable
+    for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE"):
+        monkeypatch.delenv(k, raising=False)
 
 
 def test_gather_and_matrix_core_currents_agree(monkeypatch):
