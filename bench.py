@@ -71,6 +71,9 @@ def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
     # fused stage launches (recurrences of one pipeline stage + weight gradients of the stage before): the
     # flops of both parts; the launch is as long as the longer of the two, the recurrence chain as a rule
     out["bwd_stage"] = ("alu", out["adjoint"][1] + out["dw"][1])
+    # fused forward stage launches (sequential parts + the currents the next stage consumes): the sequential
+    # chain decides their length
+    out["fwd_stage"] = out["fwd_seq"]
     return out
 
 
@@ -284,15 +287,21 @@ def main():
     L = len(w.n_hidden)
     model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, n_bwd)
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute,
-          "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage}
+          "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
+          "fwd_stage": st.ms_fwd_stage}
     launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
-                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 2)}
+                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 2),
+                "fwd_stage": max(1, n_tiles + 2 * L - 2)}
     if st.ms_bwd_stage > 0:
         # all but the first stage's recurrences and the last stage's weight gradients ran inside fused launches:
         # what is left of the two separate kinds is one launch each, not worth a line
         ms["adjoint"] = ms["dw"] = 0.0
+    if st.ms_fwd_stage > 0:
+        # likewise: what is left outside the fused launches is the first stage's currents, the last stage's
+        # sequential parts and the readout scans
+        ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
-                 "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage",
+                 "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_ws" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12),
              "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}

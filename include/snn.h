@@ -86,6 +86,8 @@ typedef struct {
                                                     readout kernels; adjoint: inter-layer GEMMs */
   float ms_bwd_stage;        /* launches that carry the recurrences of one pipeline stage together with the
                                 weight-gradient contraction of the stage before (not in ms_adjoint / ms_dw) */
+  float ms_fwd_stage;        /* launches that carry the sequential parts of one forward stage together with the
+                                currents of the next (not in ms_fwd_seq / ms_fwd_currents)                    */
   int64_t bytes_states;      /* HBM: trajectory / chunk buffer / checkpoints / staging slots */
   int64_t bytes_spikes;      /* HBM: spike bitmasks of all layers, all steps                  */
   int64_t bytes_workspace;   /* HBM: readout-adjoint tile and other per-chunk scratch          */

@@ -128,8 +128,8 @@ int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 // uses the same scratch for the currents of one time tile
 size_t work_bytes(const NetDev &n, int chunk_len) {
   const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (2 * n.n_out + n.SN) * sizeof(float);
-  // currents of one tile of every layer + readout currents of SNN_RO_TILES tiles
-  const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + n.SN) * sizeof(float);
+  // currents of two tiles of every layer (double-buffered) + readout currents of SNN_RO_TILES tiles
+  const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + 2 * n.SN) * sizeof(float);
   return bwd > fwd ? bwd : fwd;
 }
 
@@ -1044,6 +1044,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         case 4: st.ms_fwd_seq += ms; break;
         case 5: st.ms_fwd_currents += ms; break;
         case 7: st.ms_bwd_stage += ms; break;
+        case 8: st.ms_fwd_stage += ms; break;
         default: st.ms_up_gemm += ms; break;
       }
     }

@@ -42,7 +42,8 @@ struct StoreSpec {
 // Optional timing hook: the launchers bracket groups of kernels of one kind (HIP events on the
 // stream the kernels run on).  Kinds: 1 recompute, 2 adjoint recurrence, 3 dW, 4 forward sequential
 // part, 5 forward parallel currents + readout, 6 inter-layer GEMM of the adjoint pass, 7 fused stage
-// (recurrences + weight gradients of the previous stage).
+// (recurrences + weight gradients of the previous stage), 8 fused forward stage (sequential parts + the
+// currents of the next stage).
 struct SpanHook {
   void *ctx;
   void (*begin)(void *ctx, int kind);
@@ -60,10 +61,11 @@ hipError_t launch_pack_inputs(const uint8_t *in_spikes, uint64_t *mask0, int T, 
                               hipStream_t s);
 // Forward pass (gather, LIF update, threshold, compaction, readout) over consecutive time tiles
 // bounds[0..n_tiles], each at most SNN_FWD_TILE steps.  state: [B][SN], x_{bounds[0]} on entry,
-// x_{bounds[n_tiles]} on return.  work: scratch of SNN_FWD_TILE * B * (SN + SNN_RO_TILES * n_out) floats.
+// x_{bounds[n_tiles]} on return.  work: scratch of SNN_FWD_TILE * B * (2 * SN + SNN_RO_TILES * n_out) floats.
 // layer_tile_done(layer, t_end) is called (on the host, in stream order) after the launch that
 // completes layer `layer` up to step t_end has been queued.
 #define SNN_FWD_TILE 64
+#define SNN_FWD_LAG (2 * (SNN_MAXL - 1)) // tiles the lowest layer can be ahead of the top layer
 #define SNN_RO_TILES 8 // tiles of readout currents per launch of the readout scan
 struct FwdCallbacks {
   void *ctx;
@@ -164,6 +166,7 @@ struct Plan {
   int n_local_ckpt;   // HBM checkpoints (CHUNK: ceil(T/F); DOUBLE: fine checkpoints per segment)
   int n_load_slots;   // HBM slots receiving host checkpoints (prefetch double buffer)
   int n_stage_slots;  // HBM slots staging device->host copies (layers are pipelined, see launch_forward)
+                      // = SNN_FWD_LAG + 2, SNN_FWD_LAG = tiles the lowest layer can be ahead of the top one
   int n_remote;       // host slots
   int local_slots() const { return chunk_len * n_chunk_bufs + n_local_ckpt + n_load_slots + n_stage_slots; }
 };

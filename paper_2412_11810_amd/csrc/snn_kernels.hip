@@ -153,17 +153,16 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
 // and fma(0, w, a) = a, i.e. exactly the ascending sum over the active neurons.  One instruction per
 // presynaptic neuron, no memory traffic in the loop, one barrier per step.
 template <int NW>
-__global__ void __launch_bounds__(256)
-k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st) {
+__device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJob &jb, float *__restrict__ state,
+                                                  const StoreSpec &st, int b) {
   constexpr int NWD = NW / 64;
   __shared__ uint64_t sw[2][NWD];
   __shared__ float ring[SNN_SEQ_GROUP][NW];
-  // blockIdx.y selects the (layer, tile) this workgroup runs: layers are pipelined one tile apart
-  const int l = jobs.j[blockIdx.y].l, t0 = jobs.j[blockIdx.y].t0, t1 = jobs.j[blockIdx.y].t1;
-  const int t_tile = jobs.j[blockIdx.y].t_tile;
-  const float *__restrict__ iin = jobs.j[blockIdx.y].iin;
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1;
+  const int t_tile = jb.t_tile;
+  const float *__restrict__ iin = jb.iin;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
-  const int b = blockIdx.x, i = threadIdx.x, lane = lane_id(), wave = i >> 6;
+  const int i = threadIdx.x, lane = lane_id(), wave = i >> 6;
   const bool own = i < N;
   float w[NW];
 #pragma unroll
@@ -229,6 +228,13 @@ k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st
     }
   }
   if (own) state[(size_t)b * SN + off + i] = v;
+}
+
+// blockIdx.y selects the (layer, tile) this workgroup runs: the layers are pipelined, a few tiles apart
+template <int NW>
+__global__ void __launch_bounds__(256)
+k_layer_seq_rs(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st) {
+  layer_seq_rs_body<NW>(net, jobs.j[blockIdx.y], state, st, (int)blockIdx.x);
 }
 
 // Sequential part, any layer width: event-driven.  The layer's spikes of the previous step are kept
@@ -446,20 +452,18 @@ static __device__ __forceinline__ void mfma_stream(const uint16_t *list, int n_p
 
 // ws: 64-bit words per row of the LDS copy of the spike words (odd, > the widest presynaptic layer
 // of the launch in words: one extra all-zero word); lcap: entries of a wave's list.
-__global__ void __launch_bounds__(256)
-k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
-  extern __shared__ __align__(16) unsigned char smem[];
+__device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJob &ca, int ws, int lcap, int vblock,
+                                                   unsigned char *smem) {
   __shared__ float comb[2][16][64];
   constexpr int U = 8, D = 4;
-  const CurJob &ca = jobs.j[blockIdx.y];
   const bool ro = ca.mode == 2; // readout: W_out rows of the last layer's spikes, n_out columns
   const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
   const int rows = ca.nsteps * B, ncb = (N + 63) >> 6;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
   const int rb_per_wg = ca.mode == 0 ? 2 : 4;
   const int n_rbg = (rows + 16 * rb_per_wg - 1) / (16 * rb_per_wg);
-  if ((int)blockIdx.x >= n_rbg * ncb) return;
-  const int cb = (int)blockIdx.x % ncb, rbg = (int)blockIdx.x / ncb;
+  if (vblock >= n_rbg * ncb) return;
+  const int cb = vblock % ncb, rbg = vblock / ncb;
   const int part = ca.mode == 0 ? (wave & 1) : 0; // 0 feed-forward, 1 recurrent
   const int rbi = ca.mode == 0 ? (wave >> 1) : wave;
   const int m0 = (rbg * rb_per_wg + rbi) * 16;
@@ -535,6 +539,30 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
       const int c = cb * 64 + 16 * q + (lane & 15);
       if (c < N) dst[c] = acc[4 * q + rr];
     }
+  }
+}
+
+__global__ void __launch_bounds__(256)
+k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  currents_mfma_body(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
+}
+
+// One stage of the pipelined forward pass in a single launch: the first n_seq_blocks workgroups run the
+// sequential part of every layer's current tile (job = block / B, batch element = block % B), the others
+// compute the synaptic currents that the NEXT stage's sequential parts will consume (virtual grid cur_gx x
+// jobs).  The two are independent; the launcher asks for enough LDS that every workgroup gets a compute unit
+// of its own, so the current kernels fill the compute units the sequential part leaves idle without
+// competing with it for issue slots.
+__global__ void __launch_bounds__(256)
+k_fwd_stage(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, CurJobs cj, int ws, int lcap,
+            int n_seq_blocks, int cur_gx) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  if ((int)blockIdx.x < n_seq_blocks) { // uniform per workgroup
+    layer_seq_rs_body<256>(net, sj.j[blockIdx.x / net.B], state, st, (int)blockIdx.x % net.B);
+  } else {
+    const int v = (int)blockIdx.x - n_seq_blocks;
+    currents_mfma_body(net, cj.j[v / cur_gx], ws, lcap, v % cur_gx, smem);
   }
 }
 
@@ -1454,39 +1482,24 @@ static bool currents_use_mfma() { // read at every launch: a test switches it be
   return !(e && strcmp(e, "gather") == 0);
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
+static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap);
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
-  CurJobs mf{}, ga{};
-  unsigned gx = 0;
-  for (int i = 0; i < jobs.count; ++i) {
-    const CurJob &j = jobs.j[i];
-    if (j.nsteps <= 0) continue;
-    mf.j[mf.count++] = j;
-    const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? 2 : 4);
-    const int ncols = j.mode == 2 ? net.n_out : net.N[j.lsel];
-    const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((ncols + 63) / 64);
-    gx = n > gx ? n : gx;
+  CurJobs mf{};
+  for (int i = 0; i < jobs.count; ++i)
+    if (jobs.j[i].nsteps > 0) mf.j[mf.count++] = jobs.j[i];
+  if (!mf.count) return hipSuccess;
+  unsigned gx;
+  int ws, lcap;
+  currents_geometry(net, mf, &gx, &ws, &lcap);
+  const size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
+  if (lds > 48 * 1024) {
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_mfma),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (ea != hipSuccess) return ea;
   }
-  if (mf.count) {
-    int pmax = 1;
-    for (int i = 0; i < mf.count; ++i) {
-      if (mf.j[i].mode == 2) { pmax = net.N[net.L - 1] > pmax ? net.N[net.L - 1] : pmax; continue; }
-      const int l = mf.j[i].lsel, p_in = l == 0 ? net.n_in : net.N[l - 1];
-      pmax = p_in > pmax ? p_in : pmax;
-      if (mf.j[i].mode == 0) pmax = net.N[l] > pmax ? net.N[l] : pmax;
-    }
-    const int ws = ((pmax + 63) / 64 + 1) | 1, lcap = ((pmax + 31) & ~31) + 32;
-    const size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
-    if (lds > 48 * 1024) {
-      const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_mfma),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (ea != hipSuccess) return ea;
-    }
-    hipLaunchKernelGGL(k_currents_mfma, dim3(gx, mf.count), dim3(256), lds, s, net, mf, ws, lcap);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return launch_currents_gather(net, ga, s);
+  hipLaunchKernelGGL(k_currents_mfma, dim3(gx, mf.count), dim3(256), lds, s, net, mf, ws, lcap);
+  return hipGetLastError();
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (jobs.count <= 0) return hipSuccess;
@@ -1507,11 +1520,53 @@ static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs,
   return hipGetLastError();
 }
 
+// Currents jobs of a launch: virtual grid width and LDS geometry of the matrix-core current kernel.
+static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap) {
+  unsigned g = 0;
+  int pmax = 1;
+  for (int i = 0; i < jobs.count; ++i) {
+    const CurJob &j = jobs.j[i];
+    const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? 2 : 4);
+    const int ncols = j.mode == 2 ? net.n_out : net.N[j.lsel];
+    const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((ncols + 63) / 64);
+    g = n > g ? n : g;
+    if (j.mode == 2) { pmax = net.N[net.L - 1] > pmax ? net.N[net.L - 1] : pmax; continue; }
+    const int l = j.lsel, p_in = l == 0 ? net.n_in : net.N[l - 1];
+    pmax = p_in > pmax ? p_in : pmax;
+    if (j.mode == 0) pmax = net.N[l] > pmax ? net.N[l] : pmax;
+  }
+  *gx = g;
+  *ws = ((pmax + 63) / 64 + 1) | 1;
+  *lcap = ((pmax + 31) & ~31) + 32;
+}
+
+static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *state, const StoreSpec &st,
+                                   const CurJobs &cj, hipStream_t s) {
+  for (int i = 0; i < cj.count; ++i)
+    if (cj.j[i].nsteps <= 0) return hipErrorInvalidValue;
+  unsigned gx;
+  int ws, lcap;
+  currents_geometry(net, cj, &gx, &ws, &lcap);
+  // the sequential part holds ~8 KB of static LDS, the current part 8 KB; asking for 72 KB more puts the
+  // total above half of a compute unit's 160 KB, so every workgroup gets a compute unit of its own
+  size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
+  if (lds < 72 * 1024) lds = 72 * 1024;
+  const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fwd_stage),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (ea != hipSuccess) return ea;
+  const int n_seq = net.B * sj.count;
+  hipLaunchKernelGGL(k_fwd_stage, dim3(n_seq + gx * cj.count), dim3(256), lds, s, net, sj, state, st, cj, ws, lcap, n_seq,
+                     (int)gx);
+  return hipGetLastError();
+}
+
 // Forward pass over the tiles bounds[0] < bounds[1] < ... < bounds[n_tiles] (each at most
-// SNN_FWD_TILE steps).  The layers are pipelined one tile apart: in stage s, layer l runs tile s - l,
-// so the sequential kernels of all layers share one launch (blockIdx.y = layer) and so do the
-// parallel current kernels; a layer's feed-forward currents for a tile are computed in the stage
-// after the layer below finished that tile.
+// SNN_FWD_TILE steps).  The layers are pipelined two stages apart: the feed-forward currents of layer l for
+// tile k are computed in stage k + 2l (the layer below finished that tile in stage k + 2l - 1), its
+// sequential part runs in stage k + 2l + 1, the readout currents of tile k in stage k + 2L.  Everything a
+// stage does is independent of everything else in it, so a stage is one launch (k_fwd_stage) when all
+// layers are register-stationary, and otherwise one launch per kernel flavour.  The current tiles are
+// double-buffered by tile parity.
 hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
                           double *readout, int readout_init, float *work, hipStream_t s, const SpanHook *hook,
                           const FwdCallbacks *cb) {
@@ -1521,74 +1576,89 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   auto hb = [&](int kind) { if (hook) hook->begin(hook->ctx, kind); };
   auto he = [&]() { if (hook) hook->end(hook->ctx); };
   const int B = net.B, O = net.n_out, L = net.L;
-  float *iin[SNN_MAXL];
-  for (int l = 0; l < L; ++l) iin[l] = work + (size_t)SNN_FWD_TILE * B * net.off[l]; // [tile][B][N_l]
-  float *iout = work + (size_t)SNN_FWD_TILE * B * net.SN;                              // [tile][B][O]
+  float *iin[SNN_MAXL][2];
+  for (int l = 0; l < L; ++l)
+    for (int par = 0; par < 2; ++par)
+      iin[l][par] = work + (size_t)SNN_FWD_TILE * B * ((size_t)par * net.SN + net.off[l]); // [tile][B][N_l]
+  float *iout = work + (size_t)2 * SNN_FWD_TILE * B * net.SN;                              // [tile][B][O]
   const LaunchCfg c = forward_cfg(net);
+  int nmax = 0;
+  for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
+  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma();
   int ro_steps = 0, ro_tiles = 0;
   bool ro_first = true;
-  for (int stage = 0; stage < n_tiles + L; ++stage) {
-    // ---- parallel part: feed-forward currents of every layer's next tile, readout currents ----
+  for (int stage = 0; stage < n_tiles + 2 * L; ++stage) {
+    // ---- parallel part: feed-forward currents for the next stage's sequential parts, readout currents ----
     CurJobs cj{};
     for (int l = 0; l < L; ++l) {
-      const int k = stage - l;
+      const int k = stage - 2 * l;
       if (k < 0 || k >= n_tiles) continue;
-      cj.j[cj.count++] = CurJob{1, l, bounds[k], bounds[k + 1] - bounds[k], bounds[k], iin[l], 0};
+      cj.j[cj.count++] = CurJob{1, l, bounds[k], bounds[k + 1] - bounds[k], bounds[k], iin[l][k & 1], 0};
     }
     // readout currents of the tile whose last-layer spikes are complete; they queue up in iout and
     // the (cheap, sequential) leaky scan runs once per SNN_RO_TILES tiles
-    const int ko = stage - L;
+    const int ko = stage - 2 * L;
     if (ko >= 0 && ko < n_tiles)
       cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], iout + (size_t)ro_steps * B * O, 0};
-    hb(5);
-    hipError_t e = launch_currents(net, cj, s);
-    if (e != hipSuccess) return e;
+    // ---- sequential part: every layer's current tile ----------------------------------------------
+    SeqJobs rs{}, ga{};
+    int nw = 64;
+    for (int l = 0; l < L; ++l) {
+      const int k = stage - 2 * l - 1;
+      if (k < 0 || k >= n_tiles) continue;
+      const SeqJob job{l, bounds[k], bounds[k + 1], bounds[k], iin[l][k & 1]};
+      if (net.N[l] <= 256) { rs.j[rs.count++] = job; nw = net.N[l] > nw ? net.N[l] : nw; }
+      else ga.j[ga.count++] = job;
+    }
+    hipError_t e = hipSuccess;
+    if (fuse && rs.count && cj.count && !ga.count) {
+      hb(8);
+      e = launch_fwd_stage(net, rs, state, st, cj, s);
+      he();
+      if (e != hipSuccess) return e;
+    } else {
+      hb(5);
+      e = launch_currents(net, cj, s);
+      he();
+      if (e != hipSuccess) return e;
+      hb(4);
+      if (rs.count) {
+        if (nw <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B, rs.count), dim3(64), 0, s, net, rs, state, st);
+        else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
+        else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
+      }
+      if (ga.count) {
+        const size_t lds = seq_gather_lds(net);
+        const dim3 grid(B, ga.count), block(c.nt_neuron);
+#define SEQ_CASE(NPT_)                                                                               \
+  case NPT_:                                                                                          \
+    hipLaunchKernelGGL((k_layer_seq_gather<NPT_>), grid, block, lds, s, net, ga, state, st);          \
+    break;
+        switch (c.npt) {
+          SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
+          default: return hipErrorInvalidValue;
+        }
+#undef SEQ_CASE
+      }
+      he();
+    }
     if (ko >= 0 && ko < n_tiles) {
       ro_steps += bounds[ko + 1] - bounds[ko];
       if (++ro_tiles == SNN_RO_TILES || ko == n_tiles - 1) {
+        hb(5);
         hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, iout, readout, B, O, ro_steps,
                            net.beta, (ro_first && readout_init) ? 1 : 0);
+        he();
         ro_first = false;
         ro_steps = 0;
         ro_tiles = 0;
       }
     }
-    he();
-    // ---- sequential part: all layers in one launch per kernel flavour --------------------------
-    SeqJobs rs{}, ga{};
-    int nw = 64;
-    for (int l = 0; l < L; ++l) {
-      const int k = stage - l;
-      if (k < 0 || k >= n_tiles) continue;
-      const SeqJob job{l, bounds[k], bounds[k + 1], bounds[k], iin[l]};
-      if (net.N[l] <= 256) { rs.j[rs.count++] = job; nw = net.N[l] > nw ? net.N[l] : nw; }
-      else ga.j[ga.count++] = job;
-    }
-    hb(4);
-    if (rs.count) {
-      if (nw <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B, rs.count), dim3(64), 0, s, net, rs, state, st);
-      else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
-      else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
-    }
-    if (ga.count) {
-      const size_t lds = seq_gather_lds(net);
-      const dim3 grid(B, ga.count), block(c.nt_neuron);
-#define SEQ_CASE(NPT_)                                                                               \
-  case NPT_:                                                                                          \
-    hipLaunchKernelGGL((k_layer_seq_gather<NPT_>), grid, block, lds, s, net, ga, state, st);          \
-    break;
-      switch (c.npt) {
-        SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
-        default: return hipErrorInvalidValue;
-      }
-#undef SEQ_CASE
-    }
-    he();
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (cb)
       for (int l = 0; l < L; ++l) {
-        const int k = stage - l;
+        const int k = stage - 2 * l - 1;
         if (k < 0 || k >= n_tiles) continue;
         e = cb->layer_tile_done(cb->ctx, l, bounds[k + 1]);
         if (e != hipSuccess) return e;

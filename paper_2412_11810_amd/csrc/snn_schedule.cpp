@@ -4,8 +4,8 @@
 // segment may be shorter; the coarse interval need not be a multiple of the fine one.  A segment
 // (a, b] recomputed from x_a yields x_{a+1..b} from the stored spikes.  State-slot counts are the
 // paper's closed forms (eq. M_Base, M_Standard, M_Remote, M_Double) plus, for the host tier, a second
-// slot for prefetched checkpoints and SNN_MAXL + 1 slots that stage device-to-host copies (the layers
-// of the forward pass are pipelined one tile apart, so up to SNN_MAXL segment ends are being
+// slot for prefetched checkpoints and SNN_FWD_LAG + 2 slots that stage device-to-host copies (the layers
+// of the forward pass are pipelined two tiles apart, so up to SNN_FWD_LAG + 1 segment ends are being
 // assembled while one is on its way to the host).
 #include <cmath>
 
@@ -43,7 +43,7 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       q.F = 0;
       q.chunk_len = q.C;
       q.n_load_slots = 2;
-      q.n_stage_slots = SNN_MAXL + 1;
+      q.n_stage_slots = SNN_FWD_LAG + 2;
       q.n_remote = cdiv(T, q.C);
       break;
     case 3: // DOUBLE: host checkpoints every C, recomputed local checkpoints every F
@@ -54,7 +54,7 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       q.chunk_len = q.F;
       q.n_local_ckpt = cdiv(q.C, q.F) - 1; // the first fine checkpoint of a segment is the loaded coarse one
       q.n_load_slots = 2;
-      q.n_stage_slots = SNN_MAXL + 1;
+      q.n_stage_slots = SNN_FWD_LAG + 2;
       q.n_remote = cdiv(T, q.C);
       break;
     case 4: { // HIER: checkpoints every F steps, moved to/from the host in batches of C = nb_local
@@ -65,9 +65,9 @@ bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
       if (q.C < 1) return false;
       q.chunk_len = q.F;
       // ring of batches: the one in use, the one in flight to/from the host, and enough more that the
-      // lowest layer of the pipelined forward pass never laps the top layer (up to SNN_MAXL - 1
+      // lowest layer of the pipelined forward pass never laps the top layer (up to SNN_FWD_LAG
       // checkpoints behind)
-      q.n_local_ckpt = (2 + cdiv(SNN_MAXL - 1, q.C)) * q.C;
+      q.n_local_ckpt = (2 + cdiv(SNN_FWD_LAG, q.C)) * q.C;
       q.n_remote = (cdiv(n_ckpt, q.C) - 1) * q.C;
       break;
     }

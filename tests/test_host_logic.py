@@ -55,25 +55,26 @@ def test_state_slots_follow_closed_forms(T, C, F):
     cd = lambda a, b: -(-a // b)
     assert snn.snn_state_slots(snn.SNN_STANDARD, T) == (T, 0)                        # M_Base
     assert snn.snn_state_slots(snn.SNN_CHUNK, T, 0, F) == (F + cd(T, F), 0)          # M_Standard
-    # host tier: the paper's count plus 6 staging slots (second prefetch slot, five D2H staging slots)
-    assert snn.snn_state_slots(snn.SNN_REMOTE, T, C, 0) == (C + 1 + 6, cd(T, C))     # M_Remote
-    assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 6, cd(T, C))  # M_Double
+    # host tier: the paper's count plus 9 staging slots (second prefetch slot, eight D2H staging slots: the
+    # layers of the forward pass run two tiles apart, up to seven segment ends are being assembled at once)
+    assert snn.snn_state_slots(snn.SNN_REMOTE, T, C, 0) == (C + 1 + 9, cd(T, C))     # M_Remote
+    assert snn.snn_state_slots(snn.SNN_DOUBLE, T, C, F) == (F + cd(C, F) + 9, cd(T, C))  # M_Double
 
 
 def test_hierarchical_slots():
     """M_Hier = chunk + nb_local (paper) plus the ring positions that keep the pipelined forward pass
-    and the host transfers from colliding: (1 + ceil(3/nb_local)) more batches."""
+    and the host transfers from colliding: (1 + ceil(6/nb_local)) more batches."""
     cd = lambda a, b: -(-a // b)
     for T, NL, F in [(1000, 4, 25), (4096, 8, 64), (100, 1, 10), (100, 2, 10)]:
         n_ckpt = cd(T, F)
-        extra = (1 + cd(3, NL)) * NL
+        extra = (1 + cd(6, NL)) * NL
         assert snn.snn_state_slots(snn.SNN_HIER, T, NL, F) == (F + NL + extra, (cd(n_ckpt, NL) - 1) * NL)
 
 
 def test_default_intervals_are_square_roots():
     assert snn.snn_state_slots(snn.SNN_CHUNK, 4096) == (64 + 64, 0)                  # chunk = sqrt(T) = 64
     n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 4096)
-    assert (n, r) == (8 + 8 + 6, 64)                                                 # C = 64, F = 8
+    assert (n, r) == (8 + 8 + 9, 64)                                                 # C = 64, F = 8
     n, r = snn.snn_state_slots(snn.SNN_DOUBLE, 100000)
     assert r == math.ceil(100000 / 317)                                              # ceil(sqrt(1e5)) = 317
 
@@ -85,7 +86,7 @@ def test_bytes_required_accounting():
     for strat, C, F in [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 100, 10)]:
         slots, _ = snn.snn_state_slots(strat, 1000, C, F)
         chunk = {snn.SNN_STANDARD: 1000, snn.SNN_CHUNK: 32, snn.SNN_REMOTE: 32, snn.SNN_DOUBLE: 10}[strat]
-        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(min(chunk, 256) * 32 * (2 * 20 + 512) * 4, 64 * 32 * (8 * 20 + 512) * 4)
+        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(min(chunk, 256) * 32 * (2 * 20 + 512) * 4, 64 * 32 * (8 * 20 + 2 * 512) * 4)
     # invalid intervals
     assert snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, 1000, 10, 20) == 0
     assert snn.snn_state_slots(snn.SNN_CHUNK, 10, 0, 11) == (0, 0)
@@ -96,4 +97,4 @@ def test_double_local_memory_grows_like_fourth_root():
     for T in (256, 4096, 65536):
         Cc = int(round(T ** 0.5))
         Ff = int(round(Cc ** 0.5))
-        assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 6 == 2 * round(T ** 0.25)
+        assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 9 == 2 * round(T ** 0.25)
