@@ -123,11 +123,11 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
-// per-tile scratch of the adjoint pass: readout adjoints 2 x [tile][B][O] (two tiles alive) + one inter-layer product per layer
+// per-tile scratch of the adjoint pass: readout adjoints 3 x [tile][B][O] (three tiles alive) + one inter-layer product per layer
 // [tile][B][N_l] (the layers run one tile apart, so every layer's product is alive at once); the forward pass
 // uses the same scratch for the currents of one time tile
 size_t work_bytes(const NetDev &n, int chunk_len) {
-  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (2 * n.n_out + n.SN) * sizeof(float);
+  const size_t bwd = (size_t)std::min(chunk_len, SNN_BWD_TILE) * n.B * (3 * n.n_out + n.SN) * sizeof(float);
   // currents of two tiles of every layer (double-buffered) + readout currents of SNN_RO_TILES tiles
   const size_t fwd = (size_t)SNN_FWD_TILE * n.B * (SNN_RO_TILES * n.n_out + 2 * n.SN) * sizeof(float);
   return bwd > fwd ? bwd : fwd;
@@ -528,8 +528,12 @@ static snn_status check_ws_error(snn_ctx *c) {
 struct BwdTile { int t0, t1, base, layer; float *vbuf, *du; };
 struct BwdPipe {
   snn_ctx *c; const SpanHook *hk; Timer *tm; snn_stats *st; hipStream_t s;
-  float *du_base[2]{}, *up[SNN_MAXL]{};
+  float *du_base[3]{}, *up[SNN_MAXL]{};
   int du_sel = 0;
+  // head of the next tile (du_t and the top layer's product) already computed by the previous stage's launches
+  bool head_ready = false;
+  float *head_du = nullptr;
+  int head_t0 = 0, head_t1 = 0;
   bool first[SNN_MAXL + 1];
   bool dw_wide = false;
   bool fused = false; // the weight gradients of a stage ride along with the recurrences of the next one
@@ -539,25 +543,33 @@ struct BwdPipe {
 
   void init(int tile_rows) {
     const NetDev &n = c->net;
-    du_base[0] = c->dubuf;
-    du_base[1] = c->dubuf + (size_t)tile_rows * n.B * n.n_out;
-    float *q = c->dubuf + (size_t)2 * tile_rows * n.B * n.n_out;
+    for (int k = 0; k < 3; ++k) du_base[k] = c->dubuf + (size_t)k * tile_rows * n.B * n.n_out;
+    float *q = c->dubuf + (size_t)3 * tile_rows * n.B * n.n_out;
     for (int l = 0; l < n.L; ++l) { up[l] = q; q += (size_t)tile_rows * n.B * n.N[l]; }
     for (int l = 0; l <= n.L; ++l) first[l] = true;
     dw_wide = dw_wide_tiles(n);
   }
 
   // one stage: optionally admit a new tile at the top layer, run one layer of every tile in flight
-  snn_status stage(const BwdTile *fresh) {
+  struct NextTile { int t0, t1; };
+  snn_status stage(const BwdTile *fresh, const NextTile *next = nullptr, const PreJobs *pre = nullptr) {
     const NetDev &n = c->net;
     const int B = n.B, O = n.n_out, L = n.L;
     if (fresh) {
       BwdTile t = *fresh;
       t.layer = L - 1;
-      t.du = du_base[du_sel] - (size_t)(t.t0 - t.base) * B * O; // slot (t - base - 1) of the tile lands at row t - t0 - 1
-      du_sel ^= 1; // the previous tile's du is still to be read by its weight-gradient update
-      HIPCHK(c, launch_adjoint_head(n, t.t0, t.t1, t.base, t.du, c->g, c->carry, first[L] ? 1 : 0, up[L - 1], s, hk));
-      first[L] = false;
+      if (head_ready) {
+        if (t.t0 != head_t0 || t.t1 != head_t1) return fail(c, SNN_E_STATE, "internal: tile order differs from the one planned");
+        t.du = head_du - (size_t)(t.t0 - t.base) * B * O;
+        head_ready = false;
+      } else {
+        // slot (t - base - 1) of the tile lands at row t - t0 - 1; the du of the two tiles before this one is
+        // still to be read by their weight-gradient updates
+        t.du = du_base[du_sel] - (size_t)(t.t0 - t.base) * B * O;
+        du_sel = (du_sel + 1) % 3;
+        HIPCHK(c, launch_adjoint_head(n, t.t0, t.t1, t.base, t.du, c->g, c->carry, first[L] ? 1 : 0, up[L - 1], s, hk));
+        first[L] = false;
+      }
       inflight.push_back(t);
     }
     if (inflight.empty()) return SNN_OK;
@@ -568,17 +580,42 @@ struct BwdPipe {
                                     up[l] - (size_t)(t.t0 - t.base) * B * n.N[l]};
       first[l] = false;
     }
-    if (fused && !done.empty()) {
+    const bool have_pre = pre && (pre->cur.count > 0 || pre->n_scan != 0);
+    if (fused) {
+      // launch 1: the recurrences, the weight gradients of the previous stage, du_t of the next tile
       DwBatch db{};
       fill_dw_batch(&db);
-      HIPCHK(c, launch_bwd_stage(n, jobs, c->carry, db, s, hk));
+      DuJob du{};
+      if (next) {
+        du = DuJob{1, next->t0, next->t1, next->t0, first[L] ? 1 : 0, du_base[du_sel]};
+        first[L] = false;
+        head_du = du_base[du_sel];
+        head_t0 = next->t0; head_t1 = next->t1;
+        du_sel = (du_sel + 1) % 3;
+      }
+      HIPCHK(c, launch_bwd_stage(n, jobs, c->carry, db, du, c->g, s, hk));
       done.clear();
+      // launch 2: the products the next stage's recurrences need, and recompute work for later chunks
+      InterJobs ij{};
+      for (const BwdTile &t : inflight)
+        if (t.layer > 0) {
+          const int l = t.layer;
+          ij.g[ij.n_gemm++] = GemmJob{t.vbuf + (size_t)(t.t0 - t.base) * B * n.SN + n.off[l], n.SN, n.W_in[l], n.N[l],
+                                      n.N[l - 1], up[l - 1], (t.t1 - t.t0) * B, 0, 0, 0};
+        }
+      if (next) {
+        ij.g[ij.n_gemm++] = GemmJob{head_du, O, n.W_out, O, n.N[L - 1], up[L - 1], (next->t1 - next->t0) * B, 0, 0, 0};
+        head_ready = true;
+      }
+      if (have_pre) ij.pre = *pre;
+      HIPCHK(c, launch_bwd_inter(n, ij, s, hk));
     } else {
+      if (have_pre) return fail(c, SNN_E_STATE, "internal: recompute work attached to an unfused stage");
       HIPCHK(c, launch_adjoint_jobs(n, jobs, c->carry, c->ws, s, hk));
+      // what each finished layer feeds: the product for the layer below
+      for (const BwdTile &t : inflight)
+        if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
     }
-    // what each finished layer feeds: the product for the layer below, and its weight gradients
-    for (const BwdTile &t : inflight)
-      if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
     for (const BwdTile &t : inflight) done.push_back(t);
     for (BwdTile &t : inflight) --t.layer;
     if (inflight.front().layer < 0) {
@@ -790,6 +827,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   std::vector<SchedOp> ops((size_t)snn_make_schedule(p, nullptr, 0));
   snn_make_schedule(p, ops.data(), (int64_t)ops.size());
   int seg_start = 0, chunk_base = 0, cur_load = 0, n_loads = 0;
+  const float *seg_src = nullptr; // state the current remote segment starts from (HBM load slot or host slot)
   // Chunk buffers form a ring of n_chunk_bufs: with the layers of the adjoint pass one chunk apart, the
   // lower layers of the previous chunk(s) are still being worked on while the next one is recomputed.
   int n_chunks_done = 0;
@@ -800,7 +838,52 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   pipe.dw_every_stage = pipelined;
   pipe.fused = pipelined && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, pipe.dw_wide) &&
                (strategy == SNN_STANDARD || p.n_chunk_bufs >= L + 1);
-  const float *seg_src = nullptr; // state the current remote segment starts from (HBM load slot or host slot)
+  // Recompute ahead: with two more chunk buffers the currents of the chunk two stages ahead and the scan of
+  // the chunk one stage ahead ride in the stage launch (see k_bwd_stage).  pre_state[i] tells how far the
+  // recompute of the REFWD2 op at index i has got (0 nothing, 1 currents in its buffer, 2 states in its buffer).
+  const bool prefetch = pipe.fused && strategy != SNN_STANDARD && p.n_chunk_bufs >= L + 3;
+  std::vector<char> pre_state(ops.size(), 0);
+  std::vector<int> refwd2_ordinal(ops.size(), -1);
+  {
+    int k = 0;
+    for (size_t i = 0; i < ops.size(); ++i)
+      if (ops[i].op == OP_REFWD2) refwd2_ordinal[i] = k++;
+  }
+  // every tile of the adjoint pass in order (their time ranges are fixed by the schedule): the head of a
+  // tile (du_t, the top layer's product) is computed one stage early
+  std::vector<BwdPipe::NextTile> all_tiles;
+  for (const SchedOp &o : ops)
+    if (o.op == OP_BACKWARD)
+      for (int t1 = o.a; t1 >= o.b; t1 -= SNN_BWD_TILE) all_tiles.push_back({std::max(o.b - 1, t1 - SNN_BWD_TILE), t1});
+  size_t tile_no = 0;
+  auto buf_of = [&](size_t i) { return chunk0 + (size_t)(refwd2_ordinal[i] % p.n_chunk_bufs) * p.chunk_len * slot; };
+  // Looks past op index `from` for the next `want` REFWD2 ops that can be started early: nothing between here
+  // and them may change what they read (a fine-checkpoint pass, a batch or DMA load).  Returns how many were
+  // found; idx[k] is the op index, src[k] the state the k-th one starts from.
+  auto peek = [&](size_t from, int want, size_t *idx, const float **src) {
+    int found = 0, ss = seg_start;
+    const float *sp = seg_src;
+    for (size_t j = from + 1; j < ops.size() && found < want; ++j) {
+      const SchedOp &o = ops[j];
+      if (o.op == OP_REFWD1 || o.op == OP_LOAD_BATCH) break;
+      if (o.op == OP_LOAD_REMOTE) {
+        if (!direct) break;
+        ss = o.a;
+        sp = c->host_ckpt + (size_t)(o.a / p.C) * slot;
+        continue;
+      }
+      if (o.op != OP_REFWD2) continue;
+      const float *q;
+      if (strategy == SNN_CHUNK) q = lckpt + (size_t)(o.a / p.F) * slot;
+      else if (strategy == SNN_HIER) q = lckpt + (size_t)((o.a / p.F) % p.n_local_ckpt) * slot;
+      else if (strategy == SNN_REMOTE || o.a == ss) q = sp;
+      else q = lckpt + (size_t)((o.a - ss) / p.F - 1) * slot;
+      idx[found] = j;
+      src[found] = q;
+      ++found;
+    }
+    return found;
+  };
   // host->device loads run on the copy stream, behind every device->host copy of the forward pass
   auto issue_load = [&](int K, int slot_i) -> hipError_t {
     hipError_t e = hipSuccess;
@@ -884,9 +967,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         else if (strategy == SNN_REMOTE || op.a == seg_start) src = seg_src;
         else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
         chunk_base = op.a;
-        tm.begin(1);
-        HIPCHK(c, launch_recompute(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
-        tm.end();
+        if (pre_state[i] < 2) {
+          tm.begin(1);
+          if (pre_state[i] == 1) HIPCHK(c, launch_recompute_scan(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
+          else HIPCHK(c, launch_recompute(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
+          tm.end();
+        }
         st.refwd2_steps += op.b - op.a;
         break;
       }
@@ -898,7 +984,29 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         for (int t1 = op.a; t1 >= op.b; t1 -= SNN_BWD_TILE) {
           const int t0 = std::max(op.b - 1, t1 - SNN_BWD_TILE);
           const BwdTile tile{t0, t1, base, 0, chunk, nullptr};
-          snn_status rs = pipe.stage(&tile);
+          PreJobs pre{};
+          if (prefetch && t1 == op.a) { // once per chunk, with its first tile
+            size_t idx[2];
+            const float *src[2];
+            const int found = peek(i, 2, idx, src);
+            if (found >= 1 && pre_state[idx[0]] == 1) { // scan of the next chunk
+              const SchedOp &o = ops[idx[0]];
+              pre.n_scan = 1;
+              pre.t0 = o.a; pre.t1 = o.b; pre.t_base = o.a; pre.store_all = 1;
+              pre.state_in = src[0]; pre.buf = buf_of(idx[0]); pre.state_out = nullptr; pre.slot_stride = slot;
+              pre_state[idx[0]] = 2;
+            }
+            for (int k = 0; k < found; ++k) // currents of the chunks that have none yet (two only when the pipeline starts)
+              if (pre_state[idx[k]] == 0) {
+                const SchedOp &o = ops[idx[k]];
+                for (int l = 0; l < L; ++l)
+                  pre.cur.j[pre.cur.count++] = CurJob{0, l, o.a, o.b - o.a, o.a, buf_of(idx[k]), slot};
+                pre_state[idx[k]] = 1;
+              }
+          }
+          const BwdPipe::NextTile *next = tile_no + 1 < all_tiles.size() ? &all_tiles[tile_no + 1] : nullptr;
+          ++tile_no;
+          snn_status rs = pipe.stage(&tile, pipe.fused ? next : nullptr, &pre);
           if (rs == SNN_OK && !pipelined) rs = pipe.flush();
           if (rs != SNN_OK) return rs;
         }
@@ -941,9 +1049,11 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // (L - 1) * chunk_len state slots are taken only if the budget has room for them; the results are the same
   // bit for bit either way.
   if (L > 1 && c->bwd_pipeline && strategy != SNN_STANDARD) {
-    // one more buffer when the weight gradients of a stage are fused into the next stage's launch
+    // one more buffer when the weight gradients of a stage are fused into the next stage's launch, and two
+    // more again when the recompute of the next two chunks rides in it as well
     const bool fuse = c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0);
-    for (int nb = fuse ? L + 1 : L; nb >= L; --nb) {
+    const int cand[3] = {fuse ? L + 3 : L, fuse ? L + 1 : L, L};
+    for (int nb : cand) {
       Plan q = p;
       q.n_chunk_bufs = nb;
       if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T) <= budget) { p = q; break; }

@@ -74,7 +74,7 @@ struct FwdCallbacks {
 struct SeqJob { int l, t0, t1, t_tile; const float *iin; };
 struct SeqJobs { SeqJob j[SNN_MAXL]; int count; };
 struct CurJob { int mode, lsel, t0, nsteps, t_base; float *out; size_t slot_stride; };
-struct CurJobs { CurJob j[SNN_MAXL + 1]; int count; };
+struct CurJobs { CurJob j[2 * SNN_MAXL + 1]; int count; };
 hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
                           double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s,
                           const SpanHook *hook = nullptr, const FwdCallbacks *cb = nullptr);
@@ -83,6 +83,9 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
 // turns them into states in place (store_all) and/or writes x_{t1} to state_out.
 hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s);
+// Part 2 of a recompute pass alone: buf already holds the currents of steps t0+1..t1.
+hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
+                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s);
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
                        float *g, float *loss, hipStream_t s);
 // Adjoint pass over steps t1, t1-1, ..., t0+1 of a tile.  vbuf holds x_t at slot (t - t_base - 1) and is
@@ -144,8 +147,26 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
 // (see k_bwd_stage).  Only for networks bwd_stage_fusable() accepts; the caller guarantees that the two
 // parts touch different tiles.
 bool bwd_stage_fusable(const NetDev &net, int dw_wide);
-hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, hipStream_t s,
-                            const SpanHook *hook = nullptr);
+// du_t of a tile, computed inside a stage launch (n != 0: present; the launcher turns it into a workgroup count)
+struct DuJob { int n, t0, t1, t_base, carry_init; float *dubuf; };
+hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, DuJob du,
+                            const float *g, hipStream_t s, const SpanHook *hook = nullptr);
+// Recompute work of later chunks that rides in the launch between two stages: part 1 (currents, mode-0 jobs of
+// all layers of one or two chunks) and/or part 2 (the scan of another chunk whose currents are already in its
+// buffer).
+struct PreJobs {
+  CurJobs cur;          // mode-0 jobs, count 0 = none
+  int ws, lcap, cur_gx; // filled by the launcher
+  int n_scan;           // != 0: scan present (the launcher turns it into a workgroup count)
+  int t0, t1, t_base, store_all;
+  const float *state_in;
+  float *buf, *state_out;
+  size_t slot_stride;
+};
+// C[m][:] = A[m][:] W^T, an inter-layer product of the adjoint pass (kind, n_blocks, tiles_m: filled by the launcher)
+struct GemmJob { const float *A; int lda; const float *W; int K, N; float *C; int M, kind, n_blocks, tiles_m; };
+struct InterJobs { GemmJob g[SNN_MAXL + 1]; int n_gemm; PreJobs pre; };
+hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, const SpanHook *hook = nullptr);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
 hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,

@@ -452,15 +452,16 @@ static __device__ __forceinline__ void mfma_stream(const uint16_t *list, int n_p
 
 // ws: 64-bit words per row of the LDS copy of the spike words (odd, > the widest presynaptic layer
 // of the launch in words: one extra all-zero word); lcap: entries of a wave's list.
+template <int NWV> // wavefronts per workgroup (4 or 8)
 __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJob &ca, int ws, int lcap, int vblock,
                                                    unsigned char *smem) {
-  __shared__ float comb[2][16][64];
+  __shared__ float comb[NWV / 2][16][64];
   constexpr int U = 8, D = 4;
   const bool ro = ca.mode == 2; // readout: W_out rows of the last layer's spikes, n_out columns
   const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
   const int rows = ca.nsteps * B, ncb = (N + 63) >> 6;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
-  const int rb_per_wg = ca.mode == 0 ? 2 : 4;
+  const int rb_per_wg = ca.mode == 0 ? NWV / 2 : NWV;
   const int n_rbg = (rows + 16 * rb_per_wg - 1) / (16 * rb_per_wg);
   if (vblock >= n_rbg * ncb) return;
   const int cb = vblock % ncb, rbg = vblock / ncb;
@@ -478,7 +479,7 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
     g = net.mask[pl] + ((size_t)(part == 0 ? t : t - 1) * B + b) * Wp;
   }
   uint64_t *words = (uint64_t *)smem + (size_t)wave * 16 * ws;              // [16][ws]
-  uint16_t *list = (uint16_t *)((uint64_t *)smem + (size_t)4 * 16 * ws) + (size_t)wave * lcap;
+  uint16_t *list = (uint16_t *)((uint64_t *)smem + (size_t)NWV * 16 * ws) + (size_t)wave * lcap;
   // spike words of the 16 rows -> LDS (rows past the end are silent), plus one all-zero word per row
   for (int wi = lane >> 4; wi < Wp; wi += 4) words[(lane & 15) * ws + wi] = g ? g[wi] : 0ull;
   if (lane < 16) words[lane * ws + Wp] = 0ull;
@@ -545,7 +546,7 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
 __global__ void __launch_bounds__(256)
 k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
   extern __shared__ __align__(16) unsigned char smem[];
-  currents_mfma_body(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
+  currents_mfma_body<4>(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
 }
 
 // One stage of the pipelined forward pass in a single launch: the first n_seq_blocks workgroups run the
@@ -562,7 +563,7 @@ k_fwd_stage(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, Cur
     layer_seq_rs_body<256>(net, sj.j[blockIdx.x / net.B], state, st, (int)blockIdx.x % net.B);
   } else {
     const int v = (int)blockIdx.x - n_seq_blocks;
-    currents_mfma_body(net, cj.j[v / cur_gx], ws, lcap, v % cur_gx, smem);
+    currents_mfma_body<4>(net, cj.j[v / cur_gx], ws, lcap, v % cur_gx, smem);
   }
 }
 
@@ -570,10 +571,10 @@ k_fwd_stage(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, Cur
 // buf holds I_t at the slot of x_t on entry; with store_all the states replace the currents in
 // place, otherwise only the final state is written (state_out).  Same operations, in the same
 // order, as the forward pass, so the recomputed states are bit-identical to the original ones.
-__global__ void __launch_bounds__(256)
-k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *buf, int t_base, size_t slot_stride,
-       int store_all, float *__restrict__ state_out) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, const float *__restrict__ state_in,
+                                          float *buf, int t_base, size_t slot_stride, int store_all,
+                                          float *__restrict__ state_out, int vblock) {
+  const size_t i = (size_t)vblock * blockDim.x + threadIdx.x;
   const int B = net.B, SN = net.SN;
   if (i >= (size_t)B * SN) return;
   const int b = (int)(i / SN), idx = (int)(i % SN);
@@ -612,6 +613,12 @@ k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *bu
     if (store_all) col[(size_t)(t - t_base - 1) * slot_stride] = v;
   }
   if (state_out) state_out[i] = v;
+}
+
+__global__ void __launch_bounds__(256)
+k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *buf, int t_base, size_t slot_stride,
+       int store_all, float *__restrict__ state_out) {
+  scan_body(net, t0, t1, state_in, buf, t_base, slot_stride, store_all, state_out, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -657,10 +664,10 @@ __global__ void __launch_bounds__(256) k_loss(const double *__restrict__ readout
 // layer l keeps both available and turns the inter-layer product into one dense GEMM per chunk that
 // fills the chip, leaving only the recurrent product in the per-batch-element time loop.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restrict__ dubuf, int B, int O, int SN,
-          int t0, int t1, int t_base, float beta, int carry_init) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void du_scan_body(const float *__restrict__ g, float *__restrict__ carry,
+                                             float *__restrict__ dubuf, int B, int O, int SN, int t0, int t1,
+                                             int t_base, float beta, int carry_init, int vblock) {
+  const int i = vblock * blockDim.x + threadIdx.x;
   if (i >= B * O) return;
   const int b = i / O, o = i % O;
   float *cb = carry + (size_t)b * (SN + O) + SN + o;
@@ -673,6 +680,12 @@ k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restr
   *cb = d;
 }
 
+__global__ void __launch_bounds__(256)
+k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restrict__ dubuf, int B, int O, int SN,
+          int t0, int t1, int t_base, float beta, int carry_init) {
+  du_scan_body(g, carry, dubuf, B, O, SN, t0, t1, t_base, beta, carry_init, (int)blockIdx.x);
+}
+
 // C[m][j] = sum_k A[m*lda + k] * W[j*K + k]   (m < M rows = (slot, b) pairs, j < N)
 // fp32 matrix cores (v_mfma_f32_32x32x2): a workgroup of WM x WN wavefronts owns a (32 WM) x (32 WN)
 // tile of C, each wavefront a 32 x 32 block.  K runs in tiles of 32 through LDS; the next tile's
@@ -681,15 +694,14 @@ k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restr
 //   lane layout (verified on the device): A[i][k] in lane i + 32k, B[k][j] in lane j + 32k,
 //   D[8*(r/4) + 4*(lane/32) + r%4][lane%32] in register r.
 template <int WM, int WN>
-__global__ void __launch_bounds__(64 * WM * WN)
-k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
-          int ldc, int M) {
+__device__ __forceinline__ void up_gemm_body(const float *__restrict__ A, int lda, const float *__restrict__ W, int K,
+                                             int N, float *__restrict__ C, int ldc, int M, int bx, int by) {
   constexpr int NT = 64 * WM * WN, TM = 32 * WM, TN = 32 * WN, KT = 32;
   constexpr int LA = TM * KT / NT, LW = TN * KT / NT;
   __shared__ float As[TM][KT + 1], Ws[TN][KT + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
-  const int m0 = blockIdx.x * TM, j0 = blockIdx.y * TN;
+  const int m0 = bx * TM, j0 = by * TN;
   v16f acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
@@ -747,12 +759,18 @@ k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int
 //   lane layout (verified on the device): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
 //   D[4*(lane/16) + r][lane%16] in register r.
 typedef float v4f __attribute__((ext_vector_type(4)));
-__global__ void __launch_bounds__(256)
-k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
-            int ldc, int M) {
+template <int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN)
+k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
+          int ldc, int M) {
+  up_gemm_body<WM, WN>(A, lda, W, K, N, C, ldc, M, (int)blockIdx.x, (int)blockIdx.y);
+}
+
+__device__ __forceinline__ void up_gemm16_body(const float *__restrict__ A, int lda, const float *__restrict__ W, int K,
+                                               int N, float *__restrict__ C, int ldc, int M, int vblock) {
   const int lane = threadIdx.x & 63, i = lane & 15, kk = lane >> 4;
   const int tiles_n = (N + 15) >> 4;
-  const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int tile = vblock * 4 + (threadIdx.x >> 6);
   const int m0 = (tile / tiles_n) * 16, j0 = (tile % tiles_n) * 16;
   if (m0 >= M) return;
   const int ra = m0 + i < M ? m0 + i : M - 1, rw = j0 + i < N ? j0 + i : N - 1; // rows past the end: loaded, not stored
@@ -784,6 +802,12 @@ k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, i
     const int m = m0 + 4 * kk + r;
     if (m < M && j < N) C[(size_t)m * ldc + j] = acc[r];
   }
+}
+
+__global__ void __launch_bounds__(256)
+k_up_gemm16(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
+            int ldc, int M) {
+  up_gemm16_body(A, lda, W, K, N, C, ldc, M, (int)blockIdx.x);
 }
 
 // Surrogate derivative of the threshold at membrane potential v: 1/(1 + k|v - theta|)^2, and 0
@@ -1340,20 +1364,59 @@ k_dw_mfma(DwBatch batch, int B) {
   dw_mfma_body<NT, CW>(batch, B, (int)blockIdx.x, smem);
 }
 
-// One stage of the layer-pipelined backward pass in a single launch: the first n_adj_blocks workgroups run
-// the adjoint recurrences of the stage (job = block / B, batch element = block % B), the others the
-// weight-gradient contraction of what the previous stage finished.  The two are independent, and the
-// recurrences (a chain of dependent steps on a few dozen compute units) leave most of the chip idle: the
-// contraction fills it.  The launcher asks for enough LDS that no two workgroups share a compute unit, so
-// that a contraction workgroup never competes with a recurrence for issue slots.
+// One stage of the layer-pipelined backward pass takes two launches.
+// k_bwd_stage (512 threads), workgroup ranges in this order:
+//   [0, n_adj)        adjoint recurrences of the stage (job = block / B, batch element = block % B)
+//   [.., + du.n)      du_t of the NEXT tile (a scan over its steps; needs only the carried du)
+//   the rest          weight-gradient contraction of what the previous stage finished
+// All of them are independent of each other, and the recurrences (a chain of dependent steps on a few dozen
+// compute units) leave most of the chip idle: the contraction fills it.  The register footprint of the
+// recurrence part keeps two workgroups from sharing a compute unit, so nothing competes with a recurrence
+// for issue slots.
 template <int KH, int H, int R>
 __global__ void __launch_bounds__(512)
-k_bwd_stage(NetDev net, AdjJobs jobs, float *__restrict__ carry, DwBatch batch, int n_adj_blocks) {
+k_bwd_stage(NetDev net, AdjJobs jobs, float *__restrict__ carry, DwBatch batch, DuJob du, const float *__restrict__ g,
+            int n_adj_blocks) {
   extern __shared__ __align__(16) unsigned char smem[];
-  if ((int)blockIdx.x < n_adj_blocks) // uniform per workgroup
-    adj_rec_rs_body<KH, H, R>(net, jobs.j[blockIdx.x / net.B], carry, (int)blockIdx.x % net.B);
-  else
-    dw_mfma_body<1, 2>(batch, net.B, (int)blockIdx.x - n_adj_blocks, smem);
+  int v = (int)blockIdx.x; // every branch below is uniform per workgroup
+  if (v < n_adj_blocks) {
+    adj_rec_rs_body<KH, H, R>(net, jobs.j[v / net.B], carry, v % net.B);
+    return;
+  }
+  v -= n_adj_blocks;
+  if (v < du.n) {
+    du_scan_body(g, carry, du.dubuf, net.B, net.n_out, net.SN, du.t0, du.t1, du.t_base, net.beta, du.carry_init, v);
+    return;
+  }
+  dw_mfma_body<1, 2>(batch, net.B, v - du.n, smem);
+}
+
+// k_bwd_inter (256 threads) runs between two stage launches, workgroup ranges in this order:
+//   the inter-layer products that the next stage's recurrences need (of the layers just finished, and the top
+//   layer's product of the next tile), then the recompute work that rides along: part 1 (currents) of the chunk
+//   two stages ahead, part 2 (scan) of the chunk one stage ahead.  All short and independent of each other.
+__global__ void __launch_bounds__(256)
+k_bwd_inter(NetDev net, InterJobs ij) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  int v = (int)blockIdx.x; // every branch below is uniform per workgroup
+  for (int q = 0; q < ij.n_gemm; ++q) {
+    const GemmJob &gj = ij.g[q];
+    if (v < gj.n_blocks) {
+      if (gj.kind == 0) up_gemm16_body(gj.A, gj.lda, gj.W, gj.K, gj.N, gj.C, gj.N, gj.M, v);
+      else up_gemm_body<2, 2>(gj.A, gj.lda, gj.W, gj.K, gj.N, gj.C, gj.N, gj.M, v % gj.tiles_m, v / gj.tiles_m);
+      return;
+    }
+    v -= gj.n_blocks;
+  }
+  const PreJobs &pre = ij.pre;
+  const int n_cur = pre.cur_gx * pre.cur.count;
+  if (v < n_cur) {
+    currents_mfma_body<4>(net, pre.cur.j[v / pre.cur_gx], pre.ws, pre.lcap, v % pre.cur_gx, smem);
+    return;
+  }
+  v -= n_cur;
+  if (v < pre.n_scan)
+    scan_body(net, pre.t0, pre.t1, pre.state_in, pre.buf, pre.t_base, pre.slot_stride, pre.store_all, pre.state_out, v);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1482,7 +1545,7 @@ static bool currents_use_mfma() { // read at every launch: a test switches it be
   return !(e && strcmp(e, "gather") == 0);
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
-static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap);
+static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap, int nwv);
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
   CurJobs mf{};
@@ -1491,7 +1554,7 @@ static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStr
   if (!mf.count) return hipSuccess;
   unsigned gx;
   int ws, lcap;
-  currents_geometry(net, mf, &gx, &ws, &lcap);
+  currents_geometry(net, mf, &gx, &ws, &lcap, 4);
   const size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
   if (lds > 48 * 1024) {
     const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_mfma),
@@ -1521,12 +1584,12 @@ static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs,
 }
 
 // Currents jobs of a launch: virtual grid width and LDS geometry of the matrix-core current kernel.
-static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap) {
+static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap, int nwv = 4) {
   unsigned g = 0;
   int pmax = 1;
   for (int i = 0; i < jobs.count; ++i) {
     const CurJob &j = jobs.j[i];
-    const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? 2 : 4);
+    const int rows = j.nsteps * net.B, per = 16 * (j.mode == 0 ? nwv / 2 : nwv);
     const int ncols = j.mode == 2 ? net.n_out : net.N[j.lsel];
     const unsigned n = (unsigned)((rows + per - 1) / per) * (unsigned)((ncols + 63) / 64);
     g = n > g ? n : g;
@@ -1674,6 +1737,15 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
   for (int l = 0; l < net.L; ++l) cj.j[cj.count++] = CurJob{0, l, t0, t1 - t0, t_base, buf, slot_stride};
   hipError_t e = launch_currents(net, cj, s);
   if (e != hipSuccess) return e;
+  const size_t n = (size_t)net.B * net.SN;
+  hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
+                     slot_stride, store_all, state_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
+                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
+  if (t1 <= t0) return hipErrorInvalidValue;
   const size_t n = (size_t)net.B * net.SN;
   hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
                      slot_stride, store_all, state_out);
@@ -1836,9 +1908,9 @@ bool bwd_stage_fusable(const NetDev &net, int dw_wide) {
   return true;
 }
 
-hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, hipStream_t s,
-                            const SpanHook *hook) {
-  if (!bwd_stage_fusable(net, batch.wide) || jobs.count < 1 || batch.count < 1) return hipErrorInvalidValue;
+hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, DuJob du,
+                            const float *g, hipStream_t s, const SpanHook *hook) {
+  if (!bwd_stage_fusable(net, batch.wide) || jobs.count < 1 || batch.count < 0) return hipErrorInvalidValue;
   for (int i = 0; i < jobs.count; ++i)
     if (jobs.j[i].t1 <= jobs.j[i].t0 || jobs.j[i].l < 0 || jobs.j[i].l >= net.L) return hipErrorInvalidValue;
   for (int i = 0; i < batch.count; ++i)
@@ -1850,10 +1922,11 @@ hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
   }
-  // the recurrence part holds 26 KB of static LDS; asking for 56 KB more puts the total above half of a
-  // compute unit's 160 KB, so every workgroup gets a compute unit of its own
-  size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
-  if (lds < 56 * 1024) lds = 56 * 1024;
+  const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
+  if (du.n != 0) {
+    if (du.t1 <= du.t0 || !du.dubuf) return hipErrorInvalidValue;
+    du.n = (net.B * net.n_out + 511) / 512;
+  }
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_stage<32, 8, 4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1861,7 +1934,61 @@ hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry
   }
   const int n_adj = net.B * jobs.count;
   if (hook) hook->begin(hook->ctx, 7);
-  hipLaunchKernelGGL((k_bwd_stage<32, 8, 4>), dim3(n_adj + total), dim3(512), lds, s, net, jobs, carry, batch, n_adj);
+  hipLaunchKernelGGL((k_bwd_stage<32, 8, 4>), dim3(n_adj + du.n + total), dim3(512), lds, s, net, jobs, carry, batch, du, g,
+                     n_adj);
+  if (hook) hook->end(hook->ctx);
+  return hipGetLastError();
+}
+
+// Fills kind / n_blocks / tiles_m of an inter-layer product by the same rule as launch_up_gemm (shapes and
+// tile-independent alignments only; the 64 x 64 LDS-tiled kernel stands in for both of its variants, which
+// add in the same order).
+static void plan_gemm(GemmJob *gj) {
+  const bool aligned16 = gj->K % 16 == 0 && gj->lda % 4 == 0 && ((uintptr_t)gj->A & 15) == 0 && ((uintptr_t)gj->W & 15) == 0;
+  if (aligned16 && (size_t)gj->N * gj->K <= 65536) {
+    gj->kind = 0;
+    gj->tiles_m = (gj->M + 15) / 16;
+    gj->n_blocks = (gj->tiles_m * ((gj->N + 15) / 16) + 3) / 4;
+  } else {
+    gj->kind = 1;
+    gj->tiles_m = (gj->M + 63) / 64;
+    gj->n_blocks = gj->tiles_m * ((gj->N + 63) / 64);
+  }
+}
+
+hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, const SpanHook *hook) {
+  if (ij.n_gemm < 0 || ij.n_gemm > SNN_MAXL + 1) return hipErrorInvalidValue;
+  int grid = 0;
+  for (int q = 0; q < ij.n_gemm; ++q) {
+    if (ij.g[q].M <= 0 || ij.g[q].N <= 0 || ij.g[q].K <= 0) return hipErrorInvalidValue;
+    plan_gemm(&ij.g[q]);
+    grid += ij.g[q].n_blocks;
+  }
+  PreJobs &pre = ij.pre;
+  pre.cur_gx = 0;
+  pre.ws = pre.lcap = 0;
+  size_t lds = 0;
+  if (pre.cur.count > 0) {
+    for (int i = 0; i < pre.cur.count; ++i)
+      if (pre.cur.j[i].mode != 0 || pre.cur.j[i].nsteps <= 0) return hipErrorInvalidValue;
+    unsigned gx;
+    currents_geometry(net, pre.cur, &gx, &pre.ws, &pre.lcap, 4);
+    pre.cur_gx = (int)gx;
+    lds = (size_t)4 * 16 * pre.ws * sizeof(uint64_t) + (size_t)4 * pre.lcap * sizeof(uint16_t);
+  }
+  if (pre.n_scan != 0) {
+    if (pre.t1 <= pre.t0) return hipErrorInvalidValue;
+    pre.n_scan = (int)(((size_t)net.B * net.SN + 255) / 256);
+  }
+  grid += pre.cur_gx * pre.cur.count + pre.n_scan;
+  if (grid == 0) return hipSuccess;
+  if (lds > 32 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_inter),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  if (hook) hook->begin(hook->ctx, 6);
+  hipLaunchKernelGGL(k_bwd_inter, dim3(grid), dim3(256), lds, s, net, ij);
   if (hook) hook->end(hook->ctx);
   return hipGetLastError();
 }

@@ -267,7 +267,8 @@ def test_graph_replay_matches_eager():
 def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
     """The adjoint pass runs its layers one chunk apart (layer l of chunk c together with layer l+1 of the
     chunk before it in time) when the budget has room for one chunk buffer per layer, and for layers of
-    193..256 neurons the weight gradients of a stage ride in the next stage's launch (one more buffer);
+    193..256 neurons the weight gradients of a stage ride in the next stage's launch (one more buffer) and so
+    does the recompute of the next two chunks (two more buffers);
     otherwise, or with SNN_BWD_PIPE=0 / SNN_BWD_FUSE=0, it falls back step by step to finishing a chunk layer
     by layer.  Gradients must not differ by a bit, for every strategy, with chunks longer and shorter than the
     adjoint tile, three layers, and mixed kernel flavours."""
@@ -304,6 +305,10 @@ def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
                         st3 = net.snn_bptt(strat, C, F, need + (L - 1) * chunk_len * 4 * w.B * sum(w.n_hidden))
                         assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
                         assert st3.ms_bwd_stage == 0 or strat == snn.SNN_STANDARD
+                        # room for the fused weight-gradient update but not for recomputing ahead
+                        st4 = net.snn_bptt(strat, C, F, need + L * chunk_len * 4 * w.B * sum(w.n_hidden))
+                        assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
+                        assert (st4.ms_bwd_stage > 0) == fusable
                         net.snn_bptt(strat, C, F, want_stats=False)  # and through graph replay
                         assert _identical(_gpu_grads(net, L), got[(mode, strat, C, F)][0]), (w.name, strat, C, F)
             finally:

@@ -86,7 +86,7 @@ def test_bytes_required_accounting():
     for strat, C, F in [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0), (snn.SNN_DOUBLE, 100, 10)]:
         slots, _ = snn.snn_state_slots(strat, 1000, C, F)
         chunk = {snn.SNN_STANDARD: 1000, snn.SNN_CHUNK: 32, snn.SNN_REMOTE: 32, snn.SNN_DOUBLE: 10}[strat]
-        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(min(chunk, 256) * 32 * (2 * 20 + 512) * 4, 64 * 32 * (8 * 20 + 2 * 512) * 4)
+        assert snn.snn_bytes_required(cfg, strat, 1000, C, F) == slots * Ms + spikes + max(min(chunk, 256) * 32 * (3 * 20 + 512) * 4, 64 * 32 * (8 * 20 + 2 * 512) * 4)
     # invalid intervals
     assert snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, 1000, 10, 20) == 0
     assert snn.snn_state_slots(snn.SNN_CHUNK, 10, 0, 11) == (0, 0)
