@@ -74,6 +74,9 @@ def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
     # fused forward stage launches (sequential parts + the currents the next stage consumes): the sequential
     # chain decides their length
     out["fwd_stage"] = out["fwd_seq"]
+    # launch between two backward stages: inter-layer products + recompute of later chunks; priced by the
+    # recompute traffic, its larger part
+    out["bwd_inter"] = out["recompute"]
     return out
 
 
@@ -288,20 +291,24 @@ def main():
     model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, n_bwd)
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
-          "fwd_stage": st.ms_fwd_stage}
+          "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
     launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
                 "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 2),
-                "fwd_stage": max(1, n_tiles + 2 * L - 2)}
+                "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 1)}
     if st.ms_bwd_stage > 0:
         # all but the first stage's recurrences and the last stage's weight gradients ran inside fused launches:
-        # what is left of the two separate kinds is one launch each, not worth a line
+        # what is left of the two separate kinds is one launch each, not worth a line.  The launch between two
+        # stages carries the inter-layer products and the recompute of the next two chunks (timed as one kind).
         ms["adjoint"] = ms["dw"] = 0.0
+        ms["bwd_inter"], ms["up_gemm"] = ms["up_gemm"], 0.0
+        if ms["recompute"] < 0.25 * ms["bwd_inter"]:  # only the first chunk's recompute ran on its own
+            ms["recompute"] = 0.0
     if st.ms_fwd_stage > 0:
         # likewise: what is left outside the fused launches is the first stage's currents, the last stage's
         # sequential parts and the readout scans
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
-                 "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_ws" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12),
              "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}

@@ -135,6 +135,7 @@ struct DwDesc {
   int post_stride, post_off;
   double *acc;              // [n_pre][n_post] fp64 accumulators
   int t0, t1, t_base;       // steps t1, ..., t0+1
+  int skip_empty;           // test for K-steps without a spike (pays for sparse presynaptic layers only)
   int tile0, tiles_n;       // filled by the launcher
 };
 struct DwBatch {

@@ -14,6 +14,7 @@
 //   * no floating-point atomics anywhere.
 #include "snn_internal.h"
 #include <stdlib.h>
+#include <type_traits>
 #include <string.h>
 
 #define WAVE 64
@@ -1188,16 +1189,22 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
 }
 
 // ------------------------------------------------------------------------------------------
-// B5, dense path: dW += S^T . P on the fp64 matrix cores, where S[(t,b)][j] are the presynaptic
-// spikes (0/1) and P[(t,b)][n] the postsynaptic adjoints dv_t (or du_t).  At the activity levels the
-// benchmark networks run at, adding rows event by event moves more bytes than this contraction
-// costs in flops.  v_mfma_f64_16x16x4: one K-step covers 4 consecutive batch elements of one time
-// step, K-steps run over (t descending, b ascending) and the fp64 accumulators persist in HBM
-// between launches, so the sequence of operations applied to an element does not depend on how the
-// time axis is cut into chunks: every storage strategy gets bit-identical gradients.  A K-step
-// whose 16x4 spike block is empty is skipped (it would add exact zeros).
+// B5, dense path: dW += S^T . P on the matrix cores, where S[(t,b)][j] are the presynaptic spikes (0/1)
+// and P[(t,b)][n] the postsynaptic adjoints dv_t (or du_t).  At the activity levels the benchmark
+// networks run at, adding rows event by event moves more bytes than this contraction costs in flops.
+// v_mfma_f32_16x16x4: one K-step covers 4 consecutive batch elements of one time step.  The products of
+// ONE time step (b ascending) are summed in an fp32 accumulator that starts from zero; at the end of the
+// time step it is added to the fp64 accumulator that persists in HBM between launches (a sum of at most
+// a few hundred exact terms in fp32, then tens of thousands of time steps in fp64).  Time steps run in
+// descending order and a chunk boundary is always a time-step boundary, so the sequence of operations
+// applied to an element does not depend on how the time axis is cut into chunks: every storage strategy
+// gets bit-identical gradients.  A K-step whose 16x4 spike block is empty is skipped (it would add exact
+// zeros).  Why not the fp64 matrix instruction: on this chip it runs at the rate of, and instead of, the
+// fp64 vector unit (the counters show no cycle in which a VALU instruction and an fp64 MFMA overlap), so
+// the ten VALU instructions that prepare each K-step cost as much again as the MFMA itself; the fp32
+// matrix core is twice as fast and runs beside the VALU.
 // Lane layouts (checked on gfx950): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
-// D[(lane/16) + 4r][lane%16] in register r of the lane.
+// D[4*(lane/16) + r][lane%16] in register r of the lane.
 // One launch covers every weight matrix of the network: blockIdx.x -> (matrix, 64 x 16*NT*CW tile).
 // ------------------------------------------------------------------------------------------
 typedef double dvec4 __attribute__((ext_vector_type(4)));
@@ -1231,11 +1238,17 @@ __device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vb
   const int li = lane & 15, lk = lane >> 4;
 
   dvec4 acc[NT];
+  v4f part[NT]; // fp32 sum of the current time step
+  const int kpt = Bp >> 2;
+  const bool galign = (kpt & 3) == 0; // a time step is a whole number of K-step groups
+  int kin = 0;
+#pragma unroll
+  for (int q = 0; q < NT; ++q) part[q] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int q = 0; q < NT; ++q)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * (cb0 + q) + li;
+      const int j = j0 + 16 * w + 4 * lk + r, n = n0 + 16 * (cb0 + q) + li;
       acc[q][r] = (j < d.n_pre && n < d.n_post) ? d.acc[(size_t)j * d.n_post + n] : 0.0;
     }
 
@@ -1312,36 +1325,84 @@ __device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vb
       // of the group after the last is clamped to the last one and discarded).
       constexpr int KU = 4;
       const int nrows = nts * Bp;
-      uint64_t word[2][KU];
+      uint32_t word[2][KU]; // the 32-bit half of the spike word that holds this wavefront's 16 presynaptic rows
       float pv[2][KU][NT];
-      auto fetch = [&](int r0, uint64_t (&wd)[KU], float (&p)[KU][NT]) {
+      const uint32_t *S32 = reinterpret_cast<const uint32_t *>(S) + (w >> 1);
+      const int sh = 16 * (w & 1) + li;
+      auto fetch = [&](int r0, uint32_t (&wd)[KU], float (&p)[KU][NT]) {
         const int rr = r0 < nrows ? r0 : nrows - 4 * KU < 0 ? 0 : ((nrows - 1) / (4 * KU)) * (4 * KU);
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
-          wd[u] = S[rr + 4 * u + lk];
+          wd[u] = S32[2 * (rr + 4 * u + lk)];
           const float *prow = P + (size_t)(rr + 4 * u + lk) * STRIDE + 16 * cb0 + li;
 #pragma unroll
           for (int q = 0; q < NT; ++q) p[u][q] = prow[16 * q];
         }
       };
-      auto mma = [&](const uint64_t (&wd)[KU], const float (&p)[KU][NT]) {
+      auto flush = [&]() {
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            acc[q][r] = acc[q][r] + (double)part[q][r];
+            part[q][r] = 0.0f;
+          }
+      };
+      // One group of KU K-steps.  SKIP (sparse presynaptic layers only): a K-step whose 16 x 4 spike block is
+      // empty is skipped (it would add exact zeros); for dense layers the test costs more than it saves, and
+      // the group is straight-line code.
+      auto group = [&](auto skip, const uint32_t (&wd)[KU], const float (&p)[KU][NT]) {
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
-          const bool bit = (wd[u] >> (16 * w + li)) & 1ull;
-          if (__ballot(bit) == 0ull) continue;
-          const double a = bit ? 1.0 : 0.0;
+          const uint32_t bit = (wd[u] >> sh) & 1u;
+          if (decltype(skip)::value && __ballot(bit != 0u) == 0ull) continue;
+          const float a = (float)bit;
 #pragma unroll
-          for (int q = 0; q < NT; ++q)
-            acc[q] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, (double)p[u][q], acc[q], 0, 0, 0);
+          for (int q = 0; q < NT; ++q) part[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, p[u][q], part[q], 0, 0, 0);
         }
       };
-      fetch(0, word[0], pv[0]);
-      for (int r0 = 0; r0 < nrows; r0 += 8 * KU) {
-        fetch(r0 + 4 * KU, word[1], pv[1]);
-        mma(word[0], pv[0]);
-        if (r0 + 4 * KU >= nrows) break;
-        fetch(r0 + 8 * KU, word[0], pv[0]);
-        mma(word[1], pv[1]);
+      // After the last K-step of a time step (Bp / 4 of them) the fp32 sum of the time step goes into the
+      // fp64 accumulator.  When a time step is a whole number of groups (gpt), the stage is a plain loop over
+      // groups; otherwise K-steps are counted one by one and those past the stage's last row left out.
+      auto run_aligned = [&](auto skip) {
+        const int ng = nrows / (4 * KU), gpt = kpt / KU;
+        int gin = 0;
+        fetch(0, word[0], pv[0]);
+        for (int g = 0; g < ng; g += 2) {
+          fetch((g + 1) * 4 * KU, word[1], pv[1]);
+          group(skip, word[0], pv[0]);
+          if (++gin == gpt) { gin = 0; flush(); }
+          if (g + 1 >= ng) break;
+          fetch((g + 2) * 4 * KU, word[0], pv[0]);
+          group(skip, word[1], pv[1]);
+          if (++gin == gpt) { gin = 0; flush(); }
+        }
+      };
+      auto mma_counted = [&](int rbase, const uint32_t (&wd)[KU], const float (&p)[KU][NT]) {
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          if (rbase + 4 * u >= nrows) break; // uniform
+          const uint32_t bit = (wd[u] >> sh) & 1u;
+          if (__ballot(bit != 0u) != 0ull) {
+            const float a = (float)bit;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) part[q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, p[u][q], part[q], 0, 0, 0);
+          }
+          if (++kin == kpt) { kin = 0; flush(); }
+        }
+      };
+      if (galign) {
+        if (d.skip_empty) run_aligned(std::true_type{});
+        else run_aligned(std::false_type{});
+      } else {
+        fetch(0, word[0], pv[0]);
+        for (int r0 = 0; r0 < nrows; r0 += 8 * KU) {
+          fetch(r0 + 4 * KU, word[1], pv[1]);
+          mma_counted(r0, word[0], pv[0]);
+          if (r0 + 4 * KU >= nrows) break;
+          fetch(r0 + 8 * KU, word[0], pv[0]);
+          mma_counted(r0 + 4 * KU, word[1], pv[1]);
+        }
       }
       if (sidx + 1 < nstages) stage_store(buf ^ 1, n_of(sidx + 1), reg[(pf + 1) % PF], wreg[(pf + 1) % PF]);
       __syncthreads();
@@ -1352,7 +1413,7 @@ __device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vb
   for (int q = 0; q < NT; ++q)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int j = j0 + 16 * w + lk + 4 * r, n = n0 + 16 * (cb0 + q) + li;
+      const int j = j0 + 16 * w + 4 * lk + r, n = n0 + 16 * (cb0 + q) + li;
       if (j < d.n_pre && n < d.n_post) d.acc[(size_t)j * d.n_post + n] = acc[q][r];
     }
 }
