@@ -52,6 +52,7 @@ struct snn_ctx {
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
   bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
   bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
+  bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -195,6 +196,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (const char *e = std::getenv("SNN_GRAPH")) c->graphs_enabled = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_BWD_PIPE")) c->bwd_pipeline = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_PRE_IN_STAGE")) c->pre_in_stage = std::strcmp(e, "0") != 0;
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -537,6 +539,7 @@ struct BwdPipe {
   bool first[SNN_MAXL + 1];
   bool dw_wide = false;
   bool fused = false; // the weight gradients of a stage ride along with the recurrences of the next one
+  bool pre_in_stage = true; // recompute work of later chunks: in the stage launch (else in the launch between stages)
   std::vector<BwdTile> inflight; // oldest (lowest layer) first
   std::vector<BwdTile> done;     // (tile, layer) pairs whose weight gradients are still to be added
   bool dw_every_stage = true;
@@ -593,7 +596,7 @@ struct BwdPipe {
         head_t0 = next->t0; head_t1 = next->t1;
         du_sel = (du_sel + 1) % 3;
       }
-      HIPCHK(c, launch_bwd_stage(n, jobs, c->carry, db, du, c->g, s, hk));
+      HIPCHK(c, launch_bwd_stage(n, jobs, c->carry, db, du, c->g, (have_pre && pre_in_stage) ? *pre : PreJobs{}, s, hk));
       done.clear();
       // launch 2: the products the next stage's recurrences need, and recompute work for later chunks
       InterJobs ij{};
@@ -607,7 +610,7 @@ struct BwdPipe {
         ij.g[ij.n_gemm++] = GemmJob{head_du, O, n.W_out, O, n.N[L - 1], up[L - 1], (next->t1 - next->t0) * B, 0, 0, 0};
         head_ready = true;
       }
-      if (have_pre) ij.pre = *pre;
+      if (have_pre && !pre_in_stage) ij.pre = *pre;
       HIPCHK(c, launch_bwd_inter(n, ij, s, hk));
     } else {
       if (have_pre) return fail(c, SNN_E_STATE, "internal: recompute work attached to an unfused stage");
@@ -836,6 +839,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   BwdPipe pipe{c, &hk, &tm, &st, s};
   pipe.init(std::min(p.chunk_len, SNN_BWD_TILE));
   pipe.dw_every_stage = pipelined;
+  pipe.pre_in_stage = c->pre_in_stage;
   pipe.fused = pipelined && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, pipe.dw_wide) &&
                (strategy == SNN_STANDARD || p.n_chunk_bufs >= L + 1);
   // Recompute ahead: with two more chunk buffers the currents of the chunk two stages ahead and the scan of

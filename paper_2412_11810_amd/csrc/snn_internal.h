@@ -150,8 +150,6 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
 bool bwd_stage_fusable(const NetDev &net, int dw_wide);
 // du_t of a tile, computed inside a stage launch (n != 0: present; the launcher turns it into a workgroup count)
 struct DuJob { int n, t0, t1, t_base, carry_init; float *dubuf; };
-hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, DuJob du,
-                            const float *g, hipStream_t s, const SpanHook *hook = nullptr);
 // Recompute work of later chunks that rides in the launch between two stages: part 1 (currents, mode-0 jobs of
 // all layers of one or two chunks) and/or part 2 (the scan of another chunk whose currents are already in its
 // buffer).
@@ -167,6 +165,10 @@ struct PreJobs {
 // C[m][:] = A[m][:] W^T, an inter-layer product of the adjoint pass (kind, n_blocks, tiles_m: filled by the launcher)
 struct GemmJob { const float *A; int lda; const float *W; int K, N; float *C; int M, kind, n_blocks, tiles_m; };
 struct InterJobs { GemmJob g[SNN_MAXL + 1]; int n_gemm; PreJobs pre; };
+// pre: recompute work to run on the compute units the contraction leaves free (or in the launch between two
+// stages, via launch_bwd_inter: whichever the caller picks)
+hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, DuJob du,
+                            const float *g, PreJobs pre, hipStream_t s, const SpanHook *hook = nullptr);
 hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, const SpanHook *hook = nullptr);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);

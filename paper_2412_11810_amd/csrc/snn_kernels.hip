@@ -1207,6 +1207,7 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
 // D[4*(lane/16) + r][lane%16] in register r of the lane.
 // One launch covers every weight matrix of the network: blockIdx.x -> (matrix, 64 x 16*NT*CW tile).
 // ------------------------------------------------------------------------------------------
+#define DW_STAGE_ELEMS 4096 // elements of P per stage of the contraction (rows x columns of a tile)
 typedef double dvec4 __attribute__((ext_vector_type(4)));
 
 template <int NT, int CW>
@@ -1230,8 +1231,8 @@ __device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vb
   // current one) have time to arrive.
   constexpr int TPR = COLS / 4;          // threads per row
   constexpr int RPP = 256 * CW / TPR;    // rows per pass
-  constexpr int NPASS = 4 / CW;
-  constexpr int ROWS = NPASS * RPP;      // rows per stage (= 4096 / COLS)
+  constexpr int NPASS = DW_STAGE_ELEMS / 1024 / CW;
+  constexpr int ROWS = NPASS * RPP;      // rows per stage (= DW_STAGE_ELEMS / COLS)
   const int TS = ROWS / Bp;              // time steps per stage (>= 1: the launcher checks Bp <= ROWS)
   float *Pt = (float *)smem;                                   // [2][ROWS][STRIDE]
   uint64_t *Sw = (uint64_t *)(Pt + (size_t)2 * ROWS * STRIDE); // [2][ROWS]
@@ -1429,7 +1430,8 @@ k_dw_mfma(DwBatch batch, int B) {
 // k_bwd_stage (512 threads), workgroup ranges in this order:
 //   [0, n_adj)        adjoint recurrences of the stage (job = block / B, batch element = block % B)
 //   [.., + du.n)      du_t of the NEXT tile (a scan over its steps; needs only the carried du)
-//   the rest          weight-gradient contraction of what the previous stage finished
+//   [.., + n_dw)      weight-gradient contraction of what the previous stage finished
+//   the rest          (optional) recompute work for later chunks, see k_bwd_inter
 // All of them are independent of each other, and the recurrences (a chain of dependent steps on a few dozen
 // compute units) leave most of the chip idle: the contraction fills it.  The register footprint of the
 // recurrence part keeps two workgroups from sharing a compute unit, so nothing competes with a recurrence
@@ -1437,7 +1439,7 @@ k_dw_mfma(DwBatch batch, int B) {
 template <int KH, int H, int R>
 __global__ void __launch_bounds__(512)
 k_bwd_stage(NetDev net, AdjJobs jobs, float *__restrict__ carry, DwBatch batch, DuJob du, const float *__restrict__ g,
-            int n_adj_blocks) {
+            PreJobs pre, int n_adj_blocks, int n_dw_blocks) {
   extern __shared__ __align__(16) unsigned char smem[];
   int v = (int)blockIdx.x; // every branch below is uniform per workgroup
   if (v < n_adj_blocks) {
@@ -1449,7 +1451,21 @@ k_bwd_stage(NetDev net, AdjJobs jobs, float *__restrict__ carry, DwBatch batch, 
     du_scan_body(g, carry, du.dubuf, net.B, net.n_out, net.SN, du.t0, du.t1, du.t_base, net.beta, du.carry_init, v);
     return;
   }
-  dw_mfma_body<1, 2>(batch, net.B, v - du.n, smem);
+  v -= du.n;
+  if (v < n_dw_blocks) {
+    dw_mfma_body<1, 2>(batch, net.B, v, smem);
+    return;
+  }
+  v -= n_dw_blocks;
+  // recompute work for later chunks, on the compute units the contraction has left
+  const int n_cur = pre.cur_gx * pre.cur.count;
+  if (v < n_cur) {
+    currents_mfma_body<8>(net, pre.cur.j[v / pre.cur_gx], pre.ws, pre.lcap, v % pre.cur_gx, smem);
+    return;
+  }
+  v -= n_cur;
+  if (v < pre.n_scan)
+    scan_body(net, pre.t0, pre.t1, pre.state_in, pre.buf, pre.t_base, pre.slot_stride, pre.store_all, pre.state_out, v);
 }
 
 // k_bwd_inter (256 threads) runs between two stage launches, workgroup ranges in this order:
@@ -1945,15 +1961,21 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s) {
   // wide tiles when the network's matrices already fill the chip with them; otherwise narrow ones and
   // two wavefronts per SIMD
   const bool wide = batch.wide && Bp <= 64;
-  const int cols = wide ? 64 : 32; // a stage holds 4096 / cols rows
+  const int cols = wide ? 64 : 32; // a stage holds DW_STAGE_ELEMS / cols rows
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
     batch.d[i].tiles_n = (batch.d[i].n_post + cols - 1) / cols;
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
   }
-  const int rows = 4096 / cols;
+  const int rows = DW_STAGE_ELEMS / cols;
   const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
+  {
+    const hipError_t e = hipFuncSetAttribute(wide ? reinterpret_cast<const void *>(k_dw_mfma<4, 1>)
+                                                  : reinterpret_cast<const void *>(k_dw_mfma<1, 2>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
   if (wide) hipLaunchKernelGGL((k_dw_mfma<4, 1>), dim3(total), dim3(256), lds, s, batch, B);
   else hipLaunchKernelGGL((k_dw_mfma<1, 2>), dim3(total), dim3(512), lds, s, batch, B);
   return hipGetLastError();
@@ -1969,24 +1991,50 @@ bool bwd_stage_fusable(const NetDev &net, int dw_wide) {
   return true;
 }
 
+// Geometry of the recompute jobs for a kernel with nwv wavefronts per workgroup; returns the LDS they need.
+static hipError_t plan_pre(const NetDev &net, PreJobs *pre, int nwv, size_t *lds) {
+  pre->cur_gx = 0;
+  pre->ws = pre->lcap = 0;
+  *lds = 0;
+  if (pre->cur.count > 0) {
+    for (int i = 0; i < pre->cur.count; ++i)
+      if (pre->cur.j[i].mode != 0 || pre->cur.j[i].nsteps <= 0) return hipErrorInvalidValue;
+    unsigned gx;
+    currents_geometry(net, pre->cur, &gx, &pre->ws, &pre->lcap, nwv);
+    pre->cur_gx = (int)gx;
+    *lds = (size_t)nwv * 16 * pre->ws * sizeof(uint64_t) + (size_t)nwv * pre->lcap * sizeof(uint16_t);
+  }
+  if (pre->n_scan != 0) {
+    if (pre->t1 <= pre->t0) return hipErrorInvalidValue;
+    pre->n_scan = (int)(((size_t)net.B * net.SN + 64 * nwv - 1) / (64 * nwv));
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry, DwBatch batch, DuJob du,
-                            const float *g, hipStream_t s, const SpanHook *hook) {
+                            const float *g, PreJobs pre, hipStream_t s, const SpanHook *hook) {
   if (!bwd_stage_fusable(net, batch.wide) || jobs.count < 1 || batch.count < 0) return hipErrorInvalidValue;
   for (int i = 0; i < jobs.count; ++i)
     if (jobs.j[i].t1 <= jobs.j[i].t0 || jobs.j[i].l < 0 || jobs.j[i].l >= net.L) return hipErrorInvalidValue;
   for (int i = 0; i < batch.count; ++i)
     if (batch.d[i].t1 <= batch.d[i].t0) return hipErrorInvalidValue;
-  const int cols = 32, rows = 4096 / cols;
+  const int cols = 32, rows = DW_STAGE_ELEMS / cols;
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
     batch.d[i].tiles_n = (batch.d[i].n_post + cols - 1) / cols;
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 63) / 64) * batch.d[i].tiles_n;
   }
-  const size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
+  size_t lds = (size_t)2 * rows * (cols + 16) * sizeof(float) + (size_t)2 * rows * 8;
   if (du.n != 0) {
     if (du.t1 <= du.t0 || !du.dubuf) return hipErrorInvalidValue;
     du.n = (net.B * net.n_out + 511) / 512;
+  }
+  {
+    size_t lp;
+    const hipError_t e = plan_pre(net, &pre, 8, &lp);
+    if (e != hipSuccess) return e;
+    lds = lp > lds ? lp : lds;
   }
   {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_stage<32, 8, 4>),
@@ -1995,8 +2043,9 @@ hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry
   }
   const int n_adj = net.B * jobs.count;
   if (hook) hook->begin(hook->ctx, 7);
-  hipLaunchKernelGGL((k_bwd_stage<32, 8, 4>), dim3(n_adj + du.n + total), dim3(512), lds, s, net, jobs, carry, batch, du, g,
-                     n_adj);
+  const int grid = n_adj + du.n + total + pre.cur_gx * pre.cur.count + pre.n_scan;
+  hipLaunchKernelGGL((k_bwd_stage<32, 8, 4>), dim3(grid), dim3(512), lds, s, net, jobs, carry, batch, du, g, pre, n_adj,
+                     total);
   if (hook) hook->end(hook->ctx);
   return hipGetLastError();
 }
@@ -2026,20 +2075,10 @@ hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, cons
     grid += ij.g[q].n_blocks;
   }
   PreJobs &pre = ij.pre;
-  pre.cur_gx = 0;
-  pre.ws = pre.lcap = 0;
   size_t lds = 0;
-  if (pre.cur.count > 0) {
-    for (int i = 0; i < pre.cur.count; ++i)
-      if (pre.cur.j[i].mode != 0 || pre.cur.j[i].nsteps <= 0) return hipErrorInvalidValue;
-    unsigned gx;
-    currents_geometry(net, pre.cur, &gx, &pre.ws, &pre.lcap, 4);
-    pre.cur_gx = (int)gx;
-    lds = (size_t)4 * 16 * pre.ws * sizeof(uint64_t) + (size_t)4 * pre.lcap * sizeof(uint16_t);
-  }
-  if (pre.n_scan != 0) {
-    if (pre.t1 <= pre.t0) return hipErrorInvalidValue;
-    pre.n_scan = (int)(((size_t)net.B * net.SN + 255) / 256);
+  {
+    const hipError_t e = plan_pre(net, &pre, 4, &lds);
+    if (e != hipSuccess) return e;
   }
   grid += pre.cur_gx * pre.cur.count + pre.n_scan;
   if (grid == 0) return hipSuccess;

@@ -278,14 +278,15 @@ def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
               [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 9), (snn.SNN_DOUBLE, 30, 4), (snn.SNN_REMOTE, 1, 0)]),
              (synth.Workload("pipe_50-100-72-300-7", 50, (100, 72, 300), 7, T=45, B=3, p_in=0.1, gain=0.5, seed=31),
               [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 12, 5), (snn.SNN_REMOTE, 1, 0)])]
-    modes = {"fused": {}, "pipelined": {"SNN_BWD_FUSE": "0"}, "plain": {"SNN_BWD_PIPE": "0"}}
+    modes = {"fused": {}, "fused_inter": {"SNN_PRE_IN_STAGE": "0"}, "pipelined": {"SNN_BWD_FUSE": "0"},
+             "plain": {"SNN_BWD_PIPE": "0"}}
     for w, strategies in cases:
         d = synth.generate(w)
         L = len(w.n_hidden)
         fusable = all(192 < n <= 256 for n in w.n_hidden)
         got = {}
         for mode, env in modes.items():
-            for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE"):
+            for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE", "SNN_PRE_IN_STAGE"):
                 monkeypatch.delenv(k, raising=False)
             for k, v in env.items():
                 monkeypatch.setenv(k, v)
@@ -314,14 +315,14 @@ def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
             finally:
                 net.snn_destroy()
         for strat, C, F in strategies:
-            a, b, c = (got[(m, strat, C, F)] for m in ("fused", "pipelined", "plain"))
-            assert _identical(a[0], b[0]) and _identical(a[0], c[0]), (w.name, strat, C, F)
+            a, b, c, a2 = (got[(m, strat, C, F)] for m in ("fused", "pipelined", "plain", "fused_inter"))
+            assert _identical(a[0], b[0]) and _identical(a[0], c[0]) and _identical(a[0], a2[0]), (w.name, strat, C, F)
             assert _identical(a[0], got[("fused",) + strategies[0]][0]), (w.name, strat, C, F)
             assert (a[2] > 0) == fusable and b[2] == 0 and c[2] == 0
             if strat != snn.SNN_STANDARD:
                 assert b[1] > c[1] == snn.snn_state_slots(strat, w.T, C, F)[0]
                 assert (a[1] > b[1]) == fusable
-    for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE"):
+    for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE", "SNN_PRE_IN_STAGE"):
         monkeypatch.delenv(k, raising=False)
 
 
