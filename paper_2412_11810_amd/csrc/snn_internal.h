@@ -71,6 +71,8 @@ struct FwdCallbacks {
   void *ctx;
   hipError_t (*layer_tile_done)(void *ctx, int layer, int t_end);
 };
+// leaky readout over one tile of readout currents (n != 0: present; the launcher turns it into a workgroup count)
+struct RoJob { int n; const float *iout; int nsteps, init; };
 struct SeqJob { int l, t0, t1, t_tile; const float *iin; };
 struct SeqJobs { SeqJob j[SNN_MAXL]; int count; };
 struct CurJob { int mode, lsel, t0, nsteps, t_base; float *out; size_t slot_stride; };

@@ -320,10 +320,9 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
 
 // A4: u_t = beta u_{t-1} + I_out,t ; usum += u_t over the steps of a tile (fp64 state: ubar feeds a
 // softmax, which turns an absolute error of ubar into a relative error of the loss gradient).
-__global__ void __launch_bounds__(256)
-k_readout_scan(const float *__restrict__ iout, double *__restrict__ readout, int B, int O, int nsteps, float beta,
-               int init) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void readout_scan_body(const float *__restrict__ iout, double *__restrict__ readout, int B,
+                                                  int O, int nsteps, float beta, int init, int vblock) {
+  const int i = vblock * blockDim.x + threadIdx.x;
   if (i >= B * O) return;
   const int b = i / O, o = i % O;
   double u = init ? 0.0 : readout[((size_t)b * 2 + 0) * O + o];
@@ -334,6 +333,12 @@ k_readout_scan(const float *__restrict__ iout, double *__restrict__ readout, int
   }
   readout[((size_t)b * 2 + 0) * O + o] = u;
   readout[((size_t)b * 2 + 1) * O + o] = us;
+}
+
+__global__ void __launch_bounds__(256)
+k_readout_scan(const float *__restrict__ iout, double *__restrict__ readout, int B, int O, int nsteps, float beta,
+               int init) {
+  readout_scan_body(iout, readout, B, O, nsteps, beta, init, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -553,19 +558,25 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
 // One stage of the pipelined forward pass in a single launch: the first n_seq_blocks workgroups run the
 // sequential part of every layer's current tile (job = block / B, batch element = block % B), the others
 // compute the synaptic currents that the NEXT stage's sequential parts will consume (virtual grid cur_gx x
-// jobs).  The two are independent; the launcher asks for enough LDS that every workgroup gets a compute unit
+// jobs) and run the leaky readout over the tile whose readout currents are ready.  The two are independent; the launcher asks for enough LDS that every workgroup gets a compute unit
 // of its own, so the current kernels fill the compute units the sequential part leaves idle without
 // competing with it for issue slots.
 __global__ void __launch_bounds__(256)
 k_fwd_stage(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, CurJobs cj, int ws, int lcap,
-            int n_seq_blocks, int cur_gx) {
+            int n_seq_blocks, int cur_gx, RoJob ro, double *__restrict__ readout) {
   extern __shared__ __align__(16) unsigned char smem[];
-  if ((int)blockIdx.x < n_seq_blocks) { // uniform per workgroup
-    layer_seq_rs_body<256>(net, sj.j[blockIdx.x / net.B], state, st, (int)blockIdx.x % net.B);
-  } else {
-    const int v = (int)blockIdx.x - n_seq_blocks;
-    currents_mfma_body<4>(net, cj.j[v / cur_gx], ws, lcap, v % cur_gx, smem);
+  int v = (int)blockIdx.x; // every branch below is uniform per workgroup
+  if (v < n_seq_blocks) {
+    layer_seq_rs_body<256>(net, sj.j[v / net.B], state, st, v % net.B);
+    return;
   }
+  v -= n_seq_blocks;
+  if (v < ro.n) { // leaky readout over the tile whose readout currents the previous stage computed
+    readout_scan_body(ro.iout, readout, net.B, net.n_out, ro.nsteps, net.beta, ro.init, v);
+    return;
+  }
+  v -= ro.n;
+  currents_mfma_body<4>(net, cj.j[v / cur_gx], ws, lcap, v % cur_gx, smem);
 }
 
 // B1, part 2: v_t = (alpha v_{t-1} - theta s_{t-1}) + I_t along a chunk, one thread per (b, neuron).
@@ -1681,7 +1692,7 @@ static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *
 }
 
 static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *state, const StoreSpec &st,
-                                   const CurJobs &cj, hipStream_t s) {
+                                   const CurJobs &cj, RoJob ro, double *readout, hipStream_t s) {
   for (int i = 0; i < cj.count; ++i)
     if (cj.j[i].nsteps <= 0) return hipErrorInvalidValue;
   unsigned gx;
@@ -1695,8 +1706,12 @@ static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (ea != hipSuccess) return ea;
   const int n_seq = net.B * sj.count;
-  hipLaunchKernelGGL(k_fwd_stage, dim3(n_seq + gx * cj.count), dim3(256), lds, s, net, sj, state, st, cj, ws, lcap, n_seq,
-                     (int)gx);
+  if (ro.n != 0) {
+    if (ro.nsteps <= 0 || !ro.iout) return hipErrorInvalidValue;
+    ro.n = (net.B * net.n_out + 255) / 256;
+  }
+  hipLaunchKernelGGL(k_fwd_stage, dim3(n_seq + ro.n + gx * cj.count), dim3(256), lds, s, net, sj, state, st, cj, ws, lcap,
+                     n_seq, (int)gx, ro, readout);
   return hipGetLastError();
 }
 
@@ -1727,6 +1742,7 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma();
   int ro_steps = 0, ro_tiles = 0;
   bool ro_first = true;
+  RoJob ro_pending{};
   for (int stage = 0; stage < n_tiles + 2 * L; ++stage) {
     // ---- parallel part: feed-forward currents for the next stage's sequential parts, readout currents ----
     CurJobs cj{};
@@ -1735,11 +1751,15 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
       if (k < 0 || k >= n_tiles) continue;
       cj.j[cj.count++] = CurJob{1, l, bounds[k], bounds[k + 1] - bounds[k], bounds[k], iin[l][k & 1], 0};
     }
-    // readout currents of the tile whose last-layer spikes are complete; they queue up in iout and
-    // the (cheap, sequential) leaky scan runs once per SNN_RO_TILES tiles
+    // readout currents of the tile whose last-layer spikes are complete.  Fused stages: the leaky scan over a
+    // tile rides in the launch after the one that computed its currents (two tile buffers, by parity).
+    // Otherwise the currents queue up in iout and the (cheap, sequential) scan runs once per SNN_RO_TILES tiles.
     const int ko = stage - 2 * L;
-    if (ko >= 0 && ko < n_tiles)
-      cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], iout + (size_t)ro_steps * B * O, 0};
+    const bool ro_now = ko >= 0 && ko < n_tiles;
+    if (ro_now) {
+      float *dst = fuse ? iout + (size_t)(ko & 1) * SNN_FWD_TILE * B * O : iout + (size_t)ro_steps * B * O;
+      cj.j[cj.count++] = CurJob{2, L, bounds[ko], bounds[ko + 1] - bounds[ko], bounds[ko], dst, 0};
+    }
     // ---- sequential part: every layer's current tile ----------------------------------------------
     SeqJobs rs{}, ga{};
     int nw = 64;
@@ -1751,11 +1771,36 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
       else ga.j[ga.count++] = job;
     }
     hipError_t e = hipSuccess;
-    if (fuse && rs.count && cj.count && !ga.count) {
-      hb(8);
-      e = launch_fwd_stage(net, rs, state, st, cj, s);
+    auto scan_now = [&](const RoJob &r) { // a launch of its own
+      hb(5);
+      hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, r.iout, readout, B, O, r.nsteps,
+                         net.beta, r.init);
       he();
-      if (e != hipSuccess) return e;
+    };
+    if (fuse) {
+      if (rs.count && cj.count && !ga.count) {
+        hb(8);
+        e = launch_fwd_stage(net, rs, state, st, cj, ro_pending, readout, s);
+        he();
+        if (e != hipSuccess) return e;
+        ro_pending = RoJob{};
+      } else {
+        hb(5);
+        e = launch_currents(net, cj, s);
+        he();
+        if (e != hipSuccess) return e;
+        if (rs.count) {
+          hb(4);
+          hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
+          he();
+        }
+        if (ro_pending.n) { scan_now(ro_pending); ro_pending = RoJob{}; }
+      }
+      if (ro_now) { // its currents are in flight: scan it with (or after) the next launch
+        ro_pending = RoJob{1, iout + (size_t)(ko & 1) * SNN_FWD_TILE * B * O, bounds[ko + 1] - bounds[ko],
+                           (ro_first && readout_init) ? 1 : 0};
+        ro_first = false;
+      }
     } else {
       hb(5);
       e = launch_currents(net, cj, s);
@@ -1782,7 +1827,7 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
       }
       he();
     }
-    if (ko >= 0 && ko < n_tiles) {
+    if (!fuse && ro_now) {
       ro_steps += bounds[ko + 1] - bounds[ko];
       if (++ro_tiles == SNN_RO_TILES || ko == n_tiles - 1) {
         hb(5);
@@ -1803,6 +1848,12 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
         e = cb->layer_tile_done(cb->ctx, l, bounds[k + 1]);
         if (e != hipSuccess) return e;
       }
+  }
+  if (ro_pending.n) { // the last tile's readout
+    hb(5);
+    hipLaunchKernelGGL(k_readout_scan, dim3((B * O + 255) / 256), dim3(256), 0, s, ro_pending.iout, readout, B, O,
+                       ro_pending.nsteps, net.beta, ro_pending.init);
+    he();
   }
   return hipGetLastError();
 }
