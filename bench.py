@@ -293,8 +293,8 @@ def main():
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
     launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
-                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 2),
-                "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 1)}
+                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 1),
+                "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
     if st.ms_bwd_stage > 0:
         # all but the first stage's recurrences and the last stage's weight gradients ran inside fused launches:
         # what is left of the two separate kinds is one launch each, not worth a line.  The launch between two
