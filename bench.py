@@ -74,9 +74,8 @@ def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
     # fused forward stage launches (sequential parts + the currents the next stage consumes): the sequential
     # chain decides their length
     out["fwd_stage"] = out["fwd_seq"]
-    # launch between two backward stages: inter-layer products + recompute of later chunks; priced by the
-    # recompute traffic, its larger part
-    out["bwd_inter"] = out["recompute"]
+    # launch between two backward stages: inter-layer products (priced) + the recompute scan of a later chunk
+    out["bwd_inter"] = out["up_gemm"]
     return out
 
 
@@ -430,7 +429,8 @@ def main():
         "config": {"workload": w.name, "T": w.T, "batch": w.B, "strategy": args.strategy, "coarse_interval": C,
                    "fine_interval": F, "hbm_budget_bytes": budget,
                    "hbm_activation_bytes": int(st.bytes_states + st.bytes_spikes + st.bytes_workspace),
-                   "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots, "state_slots_host": rslots,
+                   "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots,
+                   "state_slots_hbm_allocated": int(st.local_state_slots), "state_slots_host": rslots,
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
                    "host_link_bytes_per_step": int(st.d2h_bytes + st.h2d_bytes),
                    "other_strategies_neuron_timesteps_per_s": others},

@@ -122,8 +122,12 @@ snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *la
  *   DOUBLE needs 1 <= fine <= coarse <= T; HIER takes fine_interval = steps between checkpoints and
  *   coarse_interval = nb_local, the number of checkpoints per host transfer.  0 = default (coarse ceil(sqrt T), fine ceil(sqrt coarse),
  *   fine ceil(sqrt T) for CHUNK: the square-root rules of the paper's Hyperparameter Study).
- *   hbm_budget_bytes caps activation storage (states + spike bitmasks + workspace, i.e.
- *   snn_bytes_required); 0 = unlimited.  Over budget -> SNN_E_BUDGET before anything is allocated. */
+ *   hbm_budget_bytes caps activation storage (states + spike bitmasks + workspace); 0 = unlimited.
+ *   snn_bytes_required is the least the strategy can run in (one chunk buffer: the paper's state
+ *   count); below it -> SNN_E_BUDGET before anything is allocated.  With room to spare (or no budget)
+ *   the call takes up to n_layers + 2 more chunk buffers, which let the layers of the adjoint pass and
+ *   the recompute of the next chunks overlap; gradients are the same bit for bit either way, and
+ *   stats reports what was allocated. */
 snn_status snn_bptt(snn_ctx *ctx, snn_strategy strategy, int32_t coarse_interval, int32_t fine_interval,
                     size_t hbm_budget_bytes, snn_stats *stats_or_null);
 
@@ -144,8 +148,9 @@ snn_status snn_debug_states(snn_ctx *ctx, float *dst);
  * kernel, whose traffic is known (bytes read + bytes written). */
 snn_status snn_debug_copy(snn_ctx *ctx, const void *src, void *dst, size_t bytes);
 
-/* Activation bytes the strategy needs in HBM for sequence length T (no context, no GPU needed).
- * Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes + bytes_workspace. */
+/* Activation bytes the strategy needs at least in HBM for sequence length T (no context, no GPU
+ * needed).  Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes +
+ * bytes_workspace of a call whose budget is exactly this number. */
 size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t T, int32_t coarse_interval,
                           int32_t fine_interval);
 /* Number of M_s-sized state slots of that plan held in HBM (the paper's closed forms plus the
