@@ -410,6 +410,18 @@ def test_degenerate_sizes(T, B, strat, C, F):
     _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (strat, C, F)], nthreads=1)
 
 
+@pytest.mark.parametrize("B", [12, 100, 128, 130])
+def test_batch_sizes_of_the_weight_gradient_paths(B):
+    """The weight-gradient contraction sums the products of one time step in fp32 (B/4 K-steps: a whole number
+    of 4-K-step groups only when B is a multiple of 16) before the fp64 accumulation; more than 64 batch elements
+    take the narrow tiles, more than 128 the event-by-event kernel.  All against the oracle, with the stage
+    kernels (two layers of 193..256 neurons) and without (a narrower net)."""
+    for hidden in ((200, 256), (90, 70)):
+        w = synth.Workload(f"batch{B}_30-{hidden[0]}-{hidden[1]}-5", 30, hidden, 5, T=21, B=B, p_in=0.1, gain=0.5, seed=40 + B)
+        _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 10, 3)], nthreads=8,
+                     check_states=False)
+
+
 def _full_size_properties(idx, strategies, budget, prefix):
     """At a configuration's full size the oracle cannot run the whole step in test time.  Checked
     instead: (1) the forward pass is causal, so the first `prefix` steps of the full-length spike
