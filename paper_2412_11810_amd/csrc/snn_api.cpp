@@ -256,13 +256,18 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
       // exchange buffer + barrier counters in uncached device memory (coherent across the chip
       // without cache maintenance).  Such memory is never freed while the process lives: blocks are
       // kept in a per-process pool and handed out again.
-      const size_t bytes = (size_t)2 * B * nmax * 4 + 65 * sizeof(unsigned);
+      // one exchange buffer and one set of 64 counters per job of a launch (layers of equal width that are one
+      // tile apart share a launch), one error flag
+      const size_t n_bar = (size_t)64 * SNN_MAXL + 16; // counters + error flag, padded to a multiple of 64 bytes
+      const size_t xg_stride = ((size_t)2 * B * nmax + 15) & ~(size_t)15;
+      const size_t bytes = n_bar * sizeof(unsigned) + (size_t)SNN_MAXL * xg_stride * 4;
       void *blk = uncached_block(cfg->device, bytes);
       if (!blk) return fail(c, SNN_E_HIP, "uncached device allocation failed");
       c->ws.bar = (unsigned *)blk;
-      c->ws.xg = (float *)((char *)blk + 65 * sizeof(unsigned) + 60); // keep 64-byte alignment: 65*4+60 = 320
-      HIPCHK(c, hipMemsetAsync(c->ws.bar, 0, 65 * sizeof(unsigned), c->stream));
-      c->ws.err = c->ws.bar + 64;
+      c->ws.xg = (float *)((char *)blk + n_bar * sizeof(unsigned));
+      c->ws.xg_stride = (int)xg_stride;
+      HIPCHK(c, hipMemsetAsync(c->ws.bar, 0, n_bar * sizeof(unsigned), c->stream));
+      c->ws.err = c->ws.bar + 64 * SNN_MAXL;
       c->ws.max_groups = ws_max_resident_groups(cfg->device);
       c->ws.spin_limit = 4000000u; // ~1 s of polling: far beyond any real wait
       if (const char *e = std::getenv("SNN_WS_SPIN_LIMIT")) c->ws.spin_limit = (unsigned)std::strtoul(e, nullptr, 10);

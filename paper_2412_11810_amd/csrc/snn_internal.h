@@ -97,8 +97,9 @@ hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int 
 // Exchange buffer, barrier counters and error flag of the chip-wide weight-stationary recurrent
 // kernel (see k_adj_rec_ws); xg == NULL disables that kernel.
 struct WsArgs {
-  float *xg;           // [2][B][max N_l]
-  unsigned *bar;       // [64] counters, zeroed before every launch (bar[63] doubles as nothing else)
+  float *xg;           // SNN_MAXL x [2][B][max N_l], one per job of a launch
+  int xg_stride;       // floats between the exchange buffers of two jobs
+  unsigned *bar;       // SNN_MAXL x [64] counters, zeroed before every launch
   unsigned *err;       // raised if a barrier gave up waiting
   int max_groups;      // workgroups of that kernel that can be resident at once
   unsigned spin_limit; // barrier polls before giving up

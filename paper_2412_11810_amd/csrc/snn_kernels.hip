@@ -952,15 +952,23 @@ k_adj_rec_rs(NetDev net, AdjJobs jobs, float *__restrict__ carry) {
 // workgroup never arrives the kernel raises *err and every workgroup runs to completion.
 template <int NR>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) // one wave per SIMD: the weights must stay in registers
-k_adj_rec_ws(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, int t_base, const float *__restrict__ up,
-             int ldu, float *__restrict__ carry, int carry_init, float *xg, unsigned *bar, unsigned *err, int G_b,
-             unsigned spin_limit) {
+k_adj_rec_ws(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_b,
+             unsigned spin_limit, int blocks_per_job, int xg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_dead; // set by thread 0 when a barrier gave up
-  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out;
+  // Several jobs (layers of equal width that are one tile apart in the layer pipeline) share a launch: each
+  // has its own range of workgroups, exchange buffer and barrier counters; they never wait for each other.
+  const int jq = blockIdx.x / blocks_per_job, vb = blockIdx.x % blocks_per_job;
+  const AdjJob &jb = jobs.j[jq];
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  xg += (size_t)jq * xg_stride;
+  bar += jq * 64;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
   const int tid = threadIdx.x;
   if (tid == 0) s_dead = 0;
-  const int bg = blockIdx.x % G_b, js = blockIdx.x / G_b, n_slices = gridDim.x / G_b;
+  const int bg = vb % G_b, js = vb / G_b, n_slices = blocks_per_job / G_b;
   const int b0 = bg * 8, j0 = js * 32;
   const int NP = NR * 8;                       // padded reduction length (>= N)
   float *xs = (float *)smem;                   // [NP][8]  dv_{t+1}, batch-minor
@@ -1952,23 +1960,32 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       else hipLaunchKernelGGL((k_adj_rec_rs<32, 8, 4>), dim3(B, rs.count), dim3(nthr), 0, s, net, rs, carry);
     }
   }
+  bool taken[SNN_MAXL] = {};
   for (int i = 0; i < jobs.count; ++i) {
     const AdjJob &jb = jobs.j[i];
     const int l = jb.l, N = net.N[l];
-    if (N <= 256) continue;
+    if (N <= 256 || taken[i]) continue;
     if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
-      const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32;
+      const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
       const int NR = N <= 512 ? 64 : 128;
       const size_t lds = ((size_t)NR * 8 * 8 + 8 * 32 * 8) * sizeof(float);
-      hipError_t e = launch_fill_zero(ws.bar, 64 * sizeof(unsigned), s);
+      // layers of the same width go out together as long as all their workgroups can be resident at once
+      AdjJobs grp{};
+      for (int k = i; k < jobs.count; ++k)
+        if (!taken[k] && net.N[jobs.j[k].l] == N && (grp.count + 1) * bpj <= ws.max_groups) {
+          grp.j[grp.count++] = jobs.j[k];
+          taken[k] = true;
+        }
+      hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
       if (e != hipSuccess) return e;
       if (NR == 64)
-        hipLaunchKernelGGL((k_adj_rec_ws<64>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, jb.t0, jb.t1, jb.vbuf,
-                           jb.t_base, jb.up, N, carry, jb.carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
+        hipLaunchKernelGGL((k_adj_rec_ws<64>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
+                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
       else
-        hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(n_slices * G_b), dim3(256), lds, s, net, l, jb.t0, jb.t1, jb.vbuf,
-                           jb.t_base, jb.up, N, carry, jb.carry_init, ws.xg, ws.bar, ws.err, G_b, ws.spin_limit);
+        hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
+                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
     } else {
+      taken[i] = true;
       const int nt = 1024;
       const size_t lds = ((size_t)2 * N + nt) * sizeof(float);
       if (lds > 64 * 1024) {
