@@ -308,7 +308,7 @@ def main():
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
                  "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
-                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_ws" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
+                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12),
              "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
     kinds = {}

@@ -269,6 +269,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
       HIPCHK(c, hipMemsetAsync(c->ws.bar, 0, n_bar * sizeof(unsigned), c->stream));
       c->ws.err = c->ws.bar + 64 * SNN_MAXL;
       c->ws.max_groups = ws_max_resident_groups(cfg->device);
+      c->ws.max_groups_m = ws_max_resident_groups_mfma(cfg->device);
       c->ws.spin_limit = 4000000u; // ~1 s of polling: far beyond any real wait
       if (const char *e = std::getenv("SNN_WS_SPIN_LIMIT")) c->ws.spin_limit = (unsigned)std::strtoul(e, nullptr, 10);
     }

@@ -102,6 +102,7 @@ struct WsArgs {
   unsigned *bar;       // SNN_MAXL x [64] counters, zeroed before every launch
   unsigned *err;       // raised if a barrier gave up waiting
   int max_groups;      // workgroups of that kernel that can be resident at once
+  int max_groups_m;    // the same for its matrix-core version
   unsigned spin_limit; // barrier polls before giving up
 };
 // One recurrence of the adjoint pass: layer l over steps t1, ..., t0+1 of a tile whose states sit in vbuf.
@@ -122,6 +123,7 @@ hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_bas
 hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *carry, const WsArgs &ws, hipStream_t s,
                                const SpanHook *hook = nullptr);
 int ws_max_resident_groups(int device);
+int ws_max_resident_groups_mfma(int device);
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
 // element) and column offset post_off.

@@ -1094,6 +1094,164 @@ k_adj_rec_ws(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, uns
   if (fin) carry[(size_t)fb * (SN + O) + off + fj] = xs[(size_t)fj * 8 + fbb];
 }
 
+// The same chip-wide recurrence on the matrix cores.  Workgroup (js, bg) owns 32 postsynaptic rows x 16 batch
+// elements; wavefront q takes a quarter of the reduction range and, for each of the two 16-row blocks, keeps its
+// part of W_rec in registers as the A operands of NK K-steps (v_mfma_f32_16x16x4: A[i][k] in lane i + 16k).  The
+// B operand of a K-step is dv_{t+1} of 4 presynaptic neurons x 16 batch elements, read from LDS (batch-minor, so
+// the 64 lanes read 64 consecutive floats).  Per step a wavefront issues 2 NK MFMAs on two independent
+// accumulators and one LDS read per K-step, where the VALU version reads every dv value of 8 batch elements
+// once per thread and is bound by the LDS (about twice the time).  The four partial sums are combined in a
+// fixed order; exchange and barrier are those of k_adj_rec_ws.
+template <int NK> // K-steps per wavefront and row block: the padded width is 16 * NK
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) // the weights must stay in registers
+k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_b,
+              unsigned spin_limit, int blocks_per_job, int xg_stride) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_dead; // set by thread 0 when a barrier gave up
+  const int jq = blockIdx.x / blocks_per_job, vb = blockIdx.x % blocks_per_job;
+  const AdjJob &jb = jobs.j[jq];
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  xg += (size_t)jq * xg_stride;
+  bar += jq * 64;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, lk = lane >> 4;
+  if (tid == 0) s_dead = 0;
+  const int bg = vb % G_b, js = vb / G_b, n_slices = blocks_per_job / G_b;
+  const int b0 = bg * 16, j0 = js * 32;
+  constexpr int NP = 16 * NK;          // padded reduction length (>= N)
+  float *xs = (float *)smem;           // [NP][16]  dv_{t+1}, batch-minor
+  float *part = xs + (size_t)NP * 16;  // [4][32][16]
+
+  // A operands: a[rb][s] = W_rec[j0 + 16 rb + li][4 NK wv + 4 s + lk].  Every load unconditional, from a clamped
+  // address, zeroed with an integer mask afterwards (a select lets the compiler put each load under its condition).
+  float a[2][NK];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int j = j0 + 16 * rb + li, jc = j < N ? j : N - 1;
+#pragma unroll
+    for (int q = 0; q < NK; ++q) {
+      const int n = 4 * NK * wv + 4 * q + lk, nc = n < N ? n : N - 1;
+      a[rb][q] = net.W_recT[l][(size_t)nc * N + jc]; // = W_rec[j][n]
+    }
+#pragma unroll
+    for (int q = 0; q < NK; ++q)
+      a[rb][q] = __uint_as_float(__float_as_uint(a[rb][q]) & (0u - (uint32_t)(j < N && 4 * NK * wv + 4 * q + lk < N)));
+  }
+  // dv_{t1+1} of this batch group
+  {
+    float cv[NK];
+#pragma unroll
+    for (int r = 0; r < NK; ++r) {
+      const int i = tid + 256 * r, n = i >> 4, bb = i & 15;
+      cv[r] = carry[(size_t)(b0 + bb < B ? b0 + bb : B - 1) * (SN + O) + off + (n < N ? n : N - 1)];
+    }
+#pragma unroll
+    for (int r = 0; r < NK; ++r) {
+      const int i = tid + 256 * r, n = i >> 4, bb = i & 15;
+      xs[i] = __uint_as_float(__float_as_uint(cv[r]) & (0u - (uint32_t)(!carry_init && n < N && b0 + bb < B)));
+    }
+  }
+  __syncthreads();
+  // finalising role: 32 x 16 (row, batch element) pairs, two per thread
+  int fj[2], fbb[2], fb[2];
+  bool fin[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int pidx = tid + 256 * e;
+    fj[e] = j0 + (pidx >> 4);
+    fbb[e] = pidx & 15;
+    fb[e] = b0 + fbb[e];
+    fin[e] = fj[e] < N && fb[e] < B;
+  }
+  const size_t slot_stride = (size_t)B * SN;
+  unsigned step = 0;
+  bool dead = false;
+  for (int t = t1; t > t0; --t, ++step) {
+    const size_t slot = (size_t)(t - t_base - 1);
+    float vt[2] = {0.0f, 0.0f}, upv[2] = {0.0f, 0.0f};
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (fin[e]) {
+        vt[e] = vbuf[slot * slot_stride + (size_t)fb[e] * SN + off + fj[e]];
+        upv[e] = up[(slot * B + fb[e]) * ldu + fj[e]];
+      }
+    v4f acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *xb = xs + (size_t)(4 * NK * wv + lk) * 16 + li;
+#pragma unroll
+    for (int q = 0; q < NK; ++q) {
+      const float x = xb[64 * q];
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][q], x, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][q], x, acc1, 0, 0, 0);
+    }
+    // D[4 lk + r][li]: row 4 lk + r of the block, batch element li
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      part[((size_t)wv * 32 + 4 * lk + r) * 16 + li] = acc0[r];
+      part[((size_t)wv * 32 + 16 + 4 * lk + r) * 16 + li] = acc1[r];
+    }
+    __syncthreads();
+    const int par = step & 1;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (fin[e]) {
+        const int fr = fj[e] - j0;
+        float sacc = part[((size_t)0 * 32 + fr) * 16 + fbb[e]];
+#pragma unroll
+        for (int k = 1; k < 4; ++k) sacc = sacc + part[((size_t)k * 32 + fr) * 16 + fbb[e]];
+        const float dn = xs[(size_t)fj[e] * 16 + fbb[e]];
+        const float ds = (sacc + upv[e]) - net.theta * dn;
+        const float dvt = fmaf(ds, surrogate(net, vt[e]), net.alpha * dn);
+        vbuf[slot * slot_stride + (size_t)fb[e] * SN + off + fj[e]] = dvt;
+        xg[((size_t)par * B + fb[e]) * N + fj[e]] = dvt;
+      }
+    // ---- counting barrier over the workgroups of this batch group (see k_adj_rec_ws) ----------
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+    __syncthreads();
+    if (tid == 0 && !dead) {
+      __hip_atomic_fetch_add(&bar[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned target = (step + 1u) * (unsigned)n_slices;
+      unsigned spins = 0;
+      while (spin_limit == 0u || __hip_atomic_load(&bar[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_dead = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __syncthreads();
+    if (s_dead) dead = true; // keep going to the end of the chunk, never wait again
+    // ---- dv_t of the whole layer for this batch group -> LDS --------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    {
+      // thread -> batch element tid/16, columns (tid%16) + 16*i: all loads issued before the first use
+      const int bb = tid >> 4, nb = tid & 15;
+      const float *src = xg + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N;
+      float r[NK];
+#pragma unroll
+      for (int i = 0; i < NK; ++i) { // agent-scope loads: never served from this compute unit's L1
+        const int n = nb + 16 * i;
+        r[i] = __hip_atomic_load(&src[n < N ? n : N - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int i = 0; i < NK; ++i) {
+        const int n = nb + 16 * i;
+        xs[(size_t)n * 16 + bb] = __uint_as_float(__float_as_uint(r[i]) & (0u - (uint32_t)(n < N && b0 + bb < B)));
+      }
+    }
+    __syncthreads();
+  }
+  // carry out dv_{t0+1}: every workgroup writes its own rows
+#pragma unroll
+  for (int e = 0; e < 2; ++e)
+    if (fin[e]) carry[(size_t)fb[e] * (SN + O) + off + fj[e]] = xs[(size_t)fj[e] * 16 + fbb[e]];
+}
+
 // Recurrent part, any layer width: the transposed recurrent matrix is streamed from L2 every step
 // (coalesced over the output index), the reduction split over KG thread groups with a fixed
 // combination order.
@@ -1933,6 +2091,7 @@ hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_bas
   return e;
 }
 
+static bool ws_use_mfma();
 hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *carry, const WsArgs &ws, hipStream_t s,
                                const SpanHook *hook) {
   const int B = net.B;
@@ -1965,7 +2124,30 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
     const AdjJob &jb = jobs.j[i];
     const int l = jb.l, N = net.N[l];
     if (N <= 256 || taken[i]) continue;
-    if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
+    if (N <= 1024 && ws.xg && ws_use_mfma() && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
+      // matrix-core version: workgroup = 32 rows x 16 batch elements
+      const int G_b = (B + 15) / 16, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
+      const int NK = N <= 512 ? 32 : 64;
+      const size_t lds = ((size_t)16 * NK * 16 + 4 * 32 * 16) * sizeof(float);
+      AdjJobs grp{};
+      for (int k = i; k < jobs.count; ++k)
+        if (!taken[k] && net.N[jobs.j[k].l] == N && (grp.count + 1) * bpj <= ws.max_groups_m) {
+          grp.j[grp.count++] = jobs.j[k];
+          taken[k] = true;
+        }
+      hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(NK == 32 ? reinterpret_cast<const void *>(k_adj_rec_wsm<32>)
+                                       : reinterpret_cast<const void *>(k_adj_rec_wsm<64>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      if (NK == 32)
+        hipLaunchKernelGGL((k_adj_rec_wsm<32>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
+                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+      else
+        hipLaunchKernelGGL((k_adj_rec_wsm<64>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
+                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+    } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
       const int NR = N <= 512 ? 64 : 128;
       const size_t lds = ((size_t)NR * 8 * 8 + 8 * 32 * 8) * sizeof(float);
@@ -1999,6 +2181,23 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
   }
   if (hook) hook->end(hook->ctx);
   return hipGetLastError();
+}
+
+static bool ws_use_mfma() { // SNN_WS_KERNEL=valu selects the VALU version of the chip-wide recurrence
+  const char *e = getenv("SNN_WS_KERNEL");
+  return !(e && strcmp(e, "valu") == 0);
+}
+
+int ws_max_resident_groups_mfma(int device) {
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+  int per_cu = 0;
+  const size_t lds = ((size_t)16 * 64 * 16 + 4 * 32 * 16) * sizeof(float);
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<64>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)lds) != hipSuccess)
+    return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wsm<64>, 256, lds) != hipSuccess) return 0;
+  return per_cu * prop.multiProcessorCount;
 }
 
 int ws_max_resident_groups(int device) {

@@ -179,6 +179,16 @@ def test_surrogate_window():
     _full_parity(synth.config(2, T=24, B=3), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 5)], nthreads=3, window=0.4)
 
 
+def test_chip_wide_adjoint_valu_version(monkeypatch):
+    """Layers of 257..1024 neurons run the chip-wide adjoint recurrence on the matrix cores by default; the VALU
+    version of the same kernel (SNN_WS_KERNEL=valu) must meet the same bar against the oracle."""
+    monkeypatch.setenv("SNN_WS_KERNEL", "valu")
+    w = synth.Workload("wsvalu_24-512-300-6", 24, (512, 300), 6, T=18, B=5, p_in=0.1, gain=0.6, seed=23)
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3)], nthreads=5, check_states=False)
+    _full_parity(synth.config(2, T=12, B=3), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 5)], nthreads=3, check_states=False)
+    monkeypatch.delenv("SNN_WS_KERNEL")
+
+
 def test_config1_full_size():
     """Configuration 1 at its full size (T = 1000, batch 32), the launch configuration the benchmark times:
     Standard, Chunk(32), Remote(32) as the configuration lists, plus Double."""
