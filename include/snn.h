@@ -164,6 +164,17 @@ int32_t snn_state_slots(snn_strategy strategy, int32_t T, int32_t coarse_interva
 int64_t snn_schedule(snn_strategy strategy, int32_t T, int32_t coarse_interval, int32_t fine_interval,
                      int32_t *out_triples, int64_t cap);
 
+/* Intervals for a strategy under an HBM activation budget (no context, no GPU needed; paper Section
+ * "Hyperparameter Study": memory is smallest at the square-root intervals, time falls with longer chunks).
+ * Picks the longest chunk of at most 256 steps -- beyond that a longer chunk no longer saves time on this
+ * hardware -- whose plan fits hbm_budget_bytes (snn_bytes_required), never shorter than the square-root
+ * rule's; for DOUBLE then the longest coarse interval whose fine checkpoints still fit; for HIER nb_local by
+ * the square-root rule.  hbm_budget_bytes = 0: no limit.  Writes the intervals to *coarse_out / *fine_out
+ * (in the meaning snn_bptt gives them; 0 where the strategy ignores one).  SNN_E_BUDGET if even the
+ * memory-minimal plan does not fit, SNN_E_INVAL for invalid arguments. */
+snn_status snn_suggest_intervals(const snn_config *cfg, snn_strategy strategy, int32_t T, size_t hbm_budget_bytes,
+                                 int32_t *coarse_out, int32_t *fine_out);
+
 const char *snn_last_error(const snn_ctx *ctx); /* never NULL; "" if none */
 void snn_destroy(snn_ctx *ctx);
 

@@ -24,7 +24,8 @@ OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5:
 
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",
-           "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy"]
+           "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy",
+           "snn_suggest_intervals"]
 
 
 class snn_config(C.Structure):
@@ -88,6 +89,7 @@ def lib() -> C.CDLL:
         L.snn_debug_copy.argtypes = [vp, vp, vp, sz]
         L.snn_bytes_required.argtypes = [C.POINTER(snn_config), C.c_int, i32, i32, i32]
         L.snn_bytes_required.restype = sz
+        L.snn_suggest_intervals.argtypes = [C.POINTER(snn_config), C.c_int, i32, sz, C.POINTER(i32), C.POINTER(i32)]
         L.snn_state_slots.argtypes = [C.c_int, i32, i32, i32, C.POINTER(i32)]
         L.snn_state_slots.restype = i32
         L.snn_schedule.argtypes = [C.c_int, i32, i32, i32, vp, i64]
@@ -118,6 +120,14 @@ def make_config(n_in, n_hidden, n_out, T, batch, alpha=0.9, beta_out=0.9, theta=
 
 def snn_bytes_required(cfg: snn_config, strategy: int, T: int, coarse: int = 0, fine: int = 0) -> int:
     return int(lib().snn_bytes_required(C.byref(cfg), strategy, T, coarse, fine))
+
+
+def snn_suggest_intervals(cfg: snn_config, strategy: int, T: int, hbm_budget_bytes: int = 0):
+    c, f = C.c_int32(0), C.c_int32(0)
+    st = lib().snn_suggest_intervals(C.byref(cfg), strategy, T, hbm_budget_bytes, C.byref(c), C.byref(f))
+    if st != SNN_OK:
+        raise SnnError(st, "no plan of this strategy fits the budget" if st == SNN_E_BUDGET else "invalid arguments")
+    return int(c.value), int(f.value)
 
 
 def snn_state_slots(strategy: int, T: int, coarse: int = 0, fine: int = 0):

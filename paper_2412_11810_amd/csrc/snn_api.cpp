@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -177,6 +178,64 @@ size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t 
   fill_shape(*cfg, &n);
   const size_t Ms = (size_t)n.B * n.SN * sizeof(float);
   return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work_bytes(n, p.chunk_len);
+}
+
+snn_status snn_suggest_intervals(const snn_config *cfg, snn_strategy strategy, int32_t T, size_t budget,
+                                 int32_t *coarse_out, int32_t *fine_out) {
+  std::string why;
+  if (!valid_cfg(cfg, &why) || T < 1 || !coarse_out || !fine_out || (int)strategy < 0 || (int)strategy > SNN_HIER)
+    return SNN_E_INVAL;
+  auto fits = [&](int C, int F) {
+    const size_t need = snn_bytes_required(cfg, strategy, T, C, F);
+    return need != 0 && (budget == 0 || need <= budget);
+  };
+  auto isqrt_ceil = [](int x) {
+    int r = (int)std::ceil(std::sqrt((double)x));
+    while ((long long)r * r < x) ++r;
+    while (r > 1 && (long long)(r - 1) * (r - 1) >= x) --r;
+    return r < 1 ? 1 : r;
+  };
+  const int cap = std::min<int>(T, 256); // longer chunks no longer save time (chunk-size study)
+  int C = 0, F = 0;
+  switch (strategy) {
+    case SNN_STANDARD:
+      if (!fits(0, 0)) return SNN_E_BUDGET;
+      break;
+    case SNN_CHUNK:
+    case SNN_HIER: {
+      // state slots F + ceil(T/F) (+ ring): smallest at sqrt(T), growing with F beyond it
+      const int lo = std::min(isqrt_ceil(T), cap);
+      const int nb = strategy == SNN_HIER ? isqrt_ceil((T + lo - 1) / lo) : 0;
+      for (F = cap; F >= lo && !fits(strategy == SNN_HIER ? isqrt_ceil((T + F - 1) / F) : 0, F); --F) {}
+      if (F < lo) {
+        if (!fits(nb, lo)) return SNN_E_BUDGET;
+        F = lo;
+      }
+      C = strategy == SNN_HIER ? isqrt_ceil((T + F - 1) / F) : 0;
+      break;
+    }
+    case SNN_REMOTE:
+      for (C = cap; C >= 1 && !fits(C, 0); --C) {}
+      if (C < 1) return SNN_E_BUDGET;
+      break;
+    case SNN_DOUBLE: {
+      // slots F + ceil(C/F) + const: first the longest chunk F that fits with one fine checkpoint (C = F),
+      // then the longest coarse interval (a multiple of F) whose fine checkpoints still fit
+      for (F = cap; F >= 1 && !fits(F, F); --F) {}
+      if (F < 1) return SNN_E_BUDGET;
+      int lo_m = 1, hi_m = (T + F - 1) / F; // C = m * F, capped at T
+      auto Cm = [&](int m) { return (int)std::min<long long>((long long)m * F, T); };
+      while (lo_m < hi_m) {
+        const int mid = lo_m + (hi_m - lo_m + 1) / 2;
+        if (fits(Cm(mid), F)) lo_m = mid; else hi_m = mid - 1;
+      }
+      C = Cm(lo_m);
+      break;
+    }
+  }
+  *coarse_out = C;
+  *fine_out = F;
+  return SNN_OK;
 }
 
 snn_status snn_init(const snn_config *cfg, snn_ctx **out) {

@@ -228,6 +228,29 @@ def test_budget_and_argument_errors():
     net.snn_destroy()
 
 
+def test_suggested_intervals_train_within_the_budget():
+    """Intervals picked by snn_suggest_intervals for a budget: the step runs inside that budget and gives the
+    gradients of full storage bit for bit."""
+    w = synth.config(1, T=1000, B=8)
+    d = synth.generate(w)
+    L = len(w.n_hidden)
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        net.snn_bptt(snn.SNN_STANDARD)
+        ref = _gpu_grads(net, L)
+        full = snn.snn_bytes_required(net.cfg, snn.SNN_STANDARD, w.T)
+        for strat in (snn.SNN_CHUNK, snn.SNN_REMOTE, snn.SNN_DOUBLE, snn.SNN_HIER):
+            for frac in (0.35, 0.6):
+                budget = int(full * frac)
+                C, F = snn.snn_suggest_intervals(net.cfg, strat, w.T, budget)
+                st = net.snn_bptt(strat, C, F, budget)
+                assert st.bytes_states + st.bytes_spikes + st.bytes_workspace <= budget
+                assert _identical(_gpu_grads(net, L), ref), (strat, C, F)
+    finally:
+        net.snn_destroy()
+
+
 def test_shorter_sequence_in_same_context_and_device_inputs():
     """A context sized for T serves shorter sequences; inputs may already live in device memory."""
     torch = pytest.importorskip("torch")

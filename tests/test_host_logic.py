@@ -98,3 +98,35 @@ def test_double_local_memory_grows_like_fourth_root():
         Cc = int(round(T ** 0.5))
         Ff = int(round(Cc ** 0.5))
         assert snn.snn_state_slots(snn.SNN_DOUBLE, T, Cc, Ff)[0] - 9 == 2 * round(T ** 0.25)
+
+
+def test_suggested_intervals_fit_the_budget_and_grow_with_it():
+    """snn_suggest_intervals: the plan it returns fits the budget, a larger budget never shortens the chunk, no
+    budget gives the 256-step cap, and a budget below the memory-minimal plan is an error (paper Section
+    "Hyperparameter Study": memory is smallest at the square-root intervals)."""
+    cfg = snn.make_config(700, [256, 256], 20, 4096, 32)
+    T = 4096
+    for strat in (snn.SNN_CHUNK, snn.SNN_REMOTE, snn.SNN_DOUBLE, snn.SNN_HIER):
+        C0, F0 = snn.snn_suggest_intervals(cfg, strat, T, 0)
+        chunk0 = C0 if strat == snn.SNN_REMOTE else F0
+        assert chunk0 == 256
+        floor_plan = {snn.SNN_CHUNK: (0, 64), snn.SNN_REMOTE: (1, 0), snn.SNN_DOUBLE: (1, 1), snn.SNN_HIER: (8, 64)}[strat]
+        least = snn.snn_bytes_required(cfg, strat, T, *floor_plan)
+        with pytest.raises(snn.SnnError) as e:
+            snn.snn_suggest_intervals(cfg, strat, T, least - 1)
+        assert e.value.status == snn.SNN_E_BUDGET
+        prev = 0
+        for extra_mb in (0, 1, 2, 4, 8, 16, 64):
+            budget = least + extra_mb * (1 << 20)
+            C, F = snn.snn_suggest_intervals(cfg, strat, T, budget)
+            assert 0 < snn.snn_bytes_required(cfg, strat, T, C, F) <= budget
+            chunk = C if strat == snn.SNN_REMOTE else F
+            assert chunk >= prev
+            prev = chunk
+            if strat == snn.SNN_DOUBLE:
+                assert C % F == 0 or C == T
+                # one more fine checkpoint would not fit (or the segment already spans the sequence)
+                assert C == T or snn.snn_bytes_required(cfg, strat, T, min(C + F, T), F) > budget
+    assert snn.snn_suggest_intervals(cfg, snn.SNN_STANDARD, T, 0) == (0, 0)
+    with pytest.raises(snn.SnnError):
+        snn.snn_suggest_intervals(cfg, snn.SNN_STANDARD, T, 1 << 20)
