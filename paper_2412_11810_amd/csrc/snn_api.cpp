@@ -583,9 +583,6 @@ static snn_status check_ws_error(snn_ctx *c) {
   return SNN_OK;
 }
 
-// Queues one whole training step on the context's streams; no host synchronisation inside, no
-// allocation, no hipMemsetAsync (fill kernels instead), so that the same code can be recorded into
-// a HIP graph.  The copy stream is forked from and joined back into the compute stream with events.
 // Adjoint pass, layers one tile apart.  Layer l of a tile needs layer l+1 of the same tile (through the
 // inter-layer product) and layer l of the tile after it in time (through the carried dv): while the top layer
 // works on the newest tile, layer L-2 works on the one before, and so on.  The L recurrences of a stage are
@@ -740,6 +737,9 @@ struct BwdPipe {
   }
 };
 
+// Queues one whole training step on the context's streams; no host synchronisation inside, no
+// allocation, no hipMemsetAsync (fill kernels instead), so that the same code can be recorded into
+// a HIP graph.  The copy stream is forked from and joined back into the compute stream with events.
 static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &tm, hipEvent_t *ev_fwd_out) {
   NetDev &n = c->net;
   const int T = p.T, B = n.B, O = n.n_out, L = n.L, SN = n.SN;
