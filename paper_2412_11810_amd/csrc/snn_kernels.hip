@@ -2060,10 +2060,8 @@ static hipError_t launch_up_gemm(const float *A, int lda, const float *W, int K,
   if (aligned16 && (size_t)N * K <= 65536) {
     const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
     hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
-  } else if (((M + 63) / 64) * ((N + 63) / 64) >= 256)
+  } else // 64 x 64 tiles: measured faster than 32 x 32 blocks (one wavefront each) and than 128 x 64 at every shape in use
     hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
-  else // small products: one wavefront per 32 x 32 block, so that more compute units take part
-    hipLaunchKernelGGL((k_up_gemm<1, 1>), dim3((M + 31) / 32, (N + 31) / 32), dim3(64), 0, s, A, lda, W, K, N, C, N, M);
   return hipGetLastError();
 }
 
@@ -2318,8 +2316,7 @@ hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry
 }
 
 // Fills kind / n_blocks / tiles_m of an inter-layer product by the same rule as launch_up_gemm (shapes and
-// tile-independent alignments only; the 64 x 64 LDS-tiled kernel stands in for both of its variants, which
-// add in the same order).
+// tile-independent alignments only).
 static void plan_gemm(GemmJob *gj) {
   const bool aligned16 = gj->K % 16 == 0 && gj->lda % 4 == 0 && ((uintptr_t)gj->A & 15) == 0 && ((uintptr_t)gj->W & 15) == 0;
   if (aligned16 && (size_t)gj->N * gj->K <= 65536) {
