@@ -910,7 +910,9 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   // Recompute ahead: with two more chunk buffers the currents of the chunk two stages ahead and the scan of
   // the chunk one stage ahead ride in the stage launch (see k_bwd_stage).  pre_state[i] tells how far the
   // recompute of the REFWD2 op at index i has got (0 nothing, 1 currents in its buffer, 2 states in its buffer).
-  const bool prefetch = pipe.fused && strategy != SNN_STANDARD && p.n_chunk_bufs >= L + 3;
+  const int pre_place = bwd_pre_placement(n);
+  const bool prefetch = pipe.fused && strategy != SNN_STANDARD && p.n_chunk_bufs >= L + 3 && pre_place > 0;
+  if (pre_place < 2) pipe.pre_in_stage = false;
   std::vector<char> pre_state(ops.size(), 0);
   std::vector<int> refwd2_ordinal(ops.size(), -1);
   {

@@ -153,6 +153,7 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
 // (see k_bwd_stage).  Only for networks bwd_stage_fusable() accepts; the caller guarantees that the two
 // parts touch different tiles.
 bool bwd_stage_fusable(const NetDev &net, int dw_wide);
+int bwd_pre_placement(const NetDev &net);
 // du_t of a tile, computed inside a stage launch (n != 0: present; the launcher turns it into a workgroup count)
 struct DuJob { int n, t0, t1, t_base, carry_init; float *dubuf; };
 // Recompute work of later chunks that rides in the launch between two stages: part 1 (currents, mode-0 jobs of

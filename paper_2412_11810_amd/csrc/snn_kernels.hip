@@ -415,49 +415,52 @@ k_currents(NetDev net, CurJobs jobs) {
 // mode 2 (readout): like mode 1 with W_out and the last layer's spikes.
 // ------------------------------------------------------------------------------------------
 
-// Contraction over the presynaptic neurons list[0..n_pad) (ascending; n_pad a multiple of U*D, the
-// entries past the real ones point at an all-zero spike word, so they multiply a valid row by 0 and
-// add +0: no change).  Row segments are fetched with buffer loads (scalar row offset, per-lane column
-// offset: no vector address arithmetic), U at a time, D - 1 groups ahead of the MFMAs that consume
-// them.
+// Contraction over the presynaptic neurons ent[0..n_pad) (ascending; n_pad a multiple of U*D).  An entry is
+// (row index of the weight matrix) | (spikes of the 16 rows, bit r = row r) << 16; the entries past the real
+// ones carry an all-zero row mask, so they multiply a valid row by 0 and add +0: no change.  Everything per
+// presynaptic neuron happens in the vector unit, with nothing passed through scalar registers (a lane read
+// followed by scalar arithmetic costs a wavefront that is alone on its SIMD several issue slots): entries are
+// read from LDS four at a time (every lane the same address), the row offset is one multiply-add per lane,
+// the row segment (256 B, coalesced) comes through a buffer load with a per-lane offset, and the lane's spike
+// is one bit extract and one convert.  Loads stay D - 1 groups of U ahead of the MFMAs that consume them.
 template <int U, int D>
-static __device__ __forceinline__ void mfma_stream(const uint16_t *list, int n_pad, const uint32_t *myw32,
-                                                   __amdgpu_buffer_rsrc_t wres, uint32_t col4, int N, int P, int lane,
-                                                   v16f &acc) {
+static __device__ __forceinline__ void mfma_stream(const uint32_t *ent, int n_pad, __amdgpu_buffer_rsrc_t wres,
+                                                   uint32_t col4, int N, int lane, v16f &acc) {
+  static_assert(U % 4 == 0, "entries are fetched four at a time");
   if (n_pad <= 0) return;
   const int ng = n_pad / U;
-  float w[D][U];
-  uint32_t a[D][U]; // the 32-bit half word holding the row's bit for slot u; the bit is extracted at use
-  int sh[D][U];
-  auto issue = [&](int g, float (&wv)[U], uint32_t (&av)[U], int (&sv)[U]) {
-    int idx = g * U + (lane & (U - 1));
-    idx = idx < n_pad ? idx : n_pad - 1;
-    const int kv = list[idx];
+  const uint32_t bitpos = 16u + (uint32_t)(lane & 15), n4 = (uint32_t)N * 4u;
+  float w[D][U], a[D][U];
+  auto issue = [&](int g, float (&wv)[U], float (&av)[U]) {
+    const int gi = g < ng ? g : ng - 1; // groups past the end: loaded again, never consumed
+    const uint4 *e4 = reinterpret_cast<const uint4 *>(ent + (size_t)gi * U);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = __builtin_amdgcn_readlane(kv, u);
-      const int kr = k < P ? k : P - 1;
-      wv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, col4, kr * N * 4, 0));
-      av[u] = myw32[k >> 5];
-      sv[u] = k & 31;
+    for (int q = 0; q < U / 4; ++q) {
+      const uint4 e = e4[q];
+      const uint32_t ev[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t off = (ev[i] & 0xFFFFu) * n4 + col4;
+        wv[4 * q + i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, off, 0, 0));
+        av[4 * q + i] = (float)((ev[i] >> bitpos) & 1u);
+      }
     }
   };
 #pragma unroll
-  for (int s = 0; s < D - 1; ++s) issue(s, w[s], a[s], sh[s]);
+  for (int s = 0; s < D - 1; ++s) issue(s, w[s], a[s]);
   for (int g = 0; g < ng; g += D) {
 #pragma unroll
     for (int j = 0; j < D; ++j) {
       __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
-      issue(g + j + D - 1, w[(j + D - 1) % D], a[(j + D - 1) % D], sh[(j + D - 1) % D]);
+      issue(g + j + D - 1, w[(j + D - 1) % D], a[(j + D - 1) % D]);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        acc = __builtin_amdgcn_mfma_f32_16x16x1f32((float)((a[j][u] >> sh[j][u]) & 1u), w[j][u], acc, 2, 0, 0);
+      for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x1f32(a[j][u], w[j][u], acc, 2, 0, 0);
     }
   }
 }
 
 // ws: 64-bit words per row of the LDS copy of the spike words (odd, > the widest presynaptic layer
-// of the launch in words: one extra all-zero word); lcap: entries of a wave's list.
+// of the launch in words: one extra all-zero word); lcap: entries of a wave's list (a multiple of 32).
 template <int NWV> // wavefronts per workgroup (4 or 8)
 __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJob &ca, int ws, int lcap, int vblock,
                                                    unsigned char *smem) {
@@ -485,7 +488,11 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
     g = net.mask[pl] + ((size_t)(part == 0 ? t : t - 1) * B + b) * Wp;
   }
   uint64_t *words = (uint64_t *)smem + (size_t)wave * 16 * ws;              // [16][ws]
-  uint16_t *list = (uint16_t *)((uint64_t *)smem + (size_t)NWV * 16 * ws) + (size_t)wave * lcap;
+  // per wavefront: lcap 32-bit entries for the stream.  The list of indices as it is built (16 bits each) sits in
+  // the upper half of the same array: entry i overwrites list[2i - lcap] and its neighbour, both <= i, i.e.
+  // indices the wavefront has already turned into entries (it fills them in ascending order).
+  uint32_t *ent = (uint32_t *)((uint64_t *)smem + (size_t)NWV * 16 * ws) + (size_t)wave * lcap;
+  uint16_t *list = (uint16_t *)(ent + lcap / 2);
   // spike words of the 16 rows -> LDS (rows past the end are silent), plus one all-zero word per row
   for (int wi = lane >> 4; wi < Wp; wi += 4) words[(lane & 15) * ws + wi] = g ? g[wi] : 0ull;
   if (lane < 16) words[lane * ws + Wp] = 0ull;
@@ -515,14 +522,23 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
   const int n_pad = n > 0 ? (n + U * D - 1) / (U * D) * (U * D) : 0;
   if (n + lane < n_pad) list[n + lane] = (uint16_t)(Wp * 64 + (lane & 31));
   __syncthreads();
+  // stream entries: one lane per list entry gathers the entry's bit from the 16 rows (padding entries select
+  // the all-zero word) and clamps the row index into the matrix
+  for (int i = lane; i < n_pad; i += 64) {
+    const int k = list[i], wi = k >> 6, sh = k & 63;
+    uint32_t m = 0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) m |= (uint32_t)((words[r * ws + wi] >> sh) & 1ull) << r;
+    ent[i] = (uint32_t)(k < P ? k : P - 1) | (m << 16);
+  }
+  __syncthreads();
   const int col = cb * 64 + lane;
   v16f acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
   const __amdgpu_buffer_rsrc_t wres =
       __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((size_t)P * N * sizeof(float)), 0x00027000);
-  mfma_stream<U, D>(list, n_pad, (const uint32_t *)(words + (lane & 15) * ws), wres,
-                    (uint32_t)(col < N ? col : 0) * 4u, N, P, lane, acc);
+  mfma_stream<U, D>(ent, n_pad, wres, (uint32_t)(col < N ? col : 0) * 4u, N, lane, acc);
   if (ca.mode == 0) {
     if (part == 1) {
 #pragma unroll
@@ -549,10 +565,11 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
   }
 }
 
-__global__ void __launch_bounds__(256)
+template <int NWV> // 4 wavefronts per workgroup; 2 when the presynaptic layer is so wide that 4 would not fit the LDS
+__global__ void __launch_bounds__(64 * NWV)
 k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
   extern __shared__ __align__(16) unsigned char smem[];
-  currents_mfma_body<4>(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
+  currents_mfma_body<NWV>(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
 }
 
 // One stage of the pipelined forward pass in a single launch: the first n_seq_blocks workgroups run the
@@ -1800,6 +1817,10 @@ static bool currents_use_mfma() { // read at every launch: a test switches it be
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
 static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap, int nwv);
+static size_t currents_lds(int nwv, int ws, int lcap) {
+  return (size_t)nwv * 16 * ws * sizeof(uint64_t) + (size_t)nwv * lcap * sizeof(uint32_t);
+}
+#define SNN_LDS_PER_CU (160 * 1024)
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
   CurJobs mf{};
@@ -1809,13 +1830,19 @@ static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStr
   unsigned gx;
   int ws, lcap;
   currents_geometry(net, mf, &gx, &ws, &lcap, 4);
-  const size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
+  // 8 KB of static LDS (the combine buffer of recompute mode) beside the dynamic part
+  const int nwv = currents_lds(4, ws, lcap) + 8192 <= SNN_LDS_PER_CU ? 4 : 2;
+  if (nwv == 2) currents_geometry(net, mf, &gx, &ws, &lcap, 2);
+  const size_t lds = currents_lds(nwv, ws, lcap);
+  if (lds + 8192 > SNN_LDS_PER_CU) return hipErrorInvalidValue;
   if (lds > 48 * 1024) {
-    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_mfma),
+    const hipError_t ea = hipFuncSetAttribute(nwv == 4 ? reinterpret_cast<const void *>(k_currents_mfma<4>)
+                                                       : reinterpret_cast<const void *>(k_currents_mfma<2>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (ea != hipSuccess) return ea;
   }
-  hipLaunchKernelGGL(k_currents_mfma, dim3(gx, mf.count), dim3(256), lds, s, net, mf, ws, lcap);
+  if (nwv == 4) hipLaunchKernelGGL(k_currents_mfma<4>, dim3(gx, mf.count), dim3(256), lds, s, net, mf, ws, lcap);
+  else hipLaunchKernelGGL(k_currents_mfma<2>, dim3(gx, mf.count), dim3(128), lds, s, net, mf, ws, lcap);
   return hipGetLastError();
 }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
@@ -1857,6 +1884,14 @@ static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *
   *lcap = ((pmax + 31) & ~31) + 32;
 }
 
+// does the matrix-core current kernel of a fused forward stage fit the LDS beside the sequential part?
+static bool fwd_stage_fits(const NetDev &net) {
+  int pmax = net.n_in;
+  for (int l = 0; l < net.L; ++l) pmax = net.N[l] > pmax ? net.N[l] : pmax;
+  const int ws = ((pmax + 63) / 64 + 1) | 1, lcap = ((pmax + 31) & ~31) + 32;
+  return currents_lds(4, ws, lcap) + 17 * 1024 <= SNN_LDS_PER_CU;
+}
+
 static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *state, const StoreSpec &st,
                                    const CurJobs &cj, RoJob ro, double *readout, hipStream_t s) {
   for (int i = 0; i < cj.count; ++i)
@@ -1866,7 +1901,8 @@ static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *
   currents_geometry(net, cj, &gx, &ws, &lcap);
   // the sequential part holds ~8 KB of static LDS, the current part 8 KB; asking for 72 KB more puts the
   // total above half of a compute unit's 160 KB, so every workgroup gets a compute unit of its own
-  size_t lds = (size_t)4 * 16 * ws * sizeof(uint64_t) + (size_t)4 * lcap * sizeof(uint16_t);
+  size_t lds = currents_lds(4, ws, lcap);
+  if (lds + 17 * 1024 > SNN_LDS_PER_CU) return hipErrorInvalidValue; // the caller checks fwd_stage_fits first
   if (lds < 72 * 1024) lds = 72 * 1024;
   const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_fwd_stage),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1905,7 +1941,7 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   const LaunchCfg c = forward_cfg(net);
   int nmax = 0;
   for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
-  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma();
+  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma() && fwd_stage_fits(net);
   int ro_steps = 0, ro_tiles = 0;
   bool ro_first = true;
   RoJob ro_pending{};
@@ -2246,6 +2282,18 @@ hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Where the recompute work of later chunks can ride: 2 = in the stage launch (8 wavefronts per workgroup beside
+// 43 KB of static LDS), 1 = in the launch between stages (4 wavefronts, 25 KB static), 0 = nowhere (the spike
+// words and lists of so wide a presynaptic layer do not fit).
+int bwd_pre_placement(const NetDev &net) {
+  int pmax = net.n_in;
+  for (int l = 0; l < net.L; ++l) pmax = net.N[l] > pmax ? net.N[l] : pmax;
+  const int ws = ((pmax + 63) / 64 + 1) | 1, lcap = ((pmax + 31) & ~31) + 32;
+  if (currents_lds(8, ws, lcap) + 43 * 1024 <= SNN_LDS_PER_CU) return 2;
+  if (currents_lds(4, ws, lcap) + 25 * 1024 <= SNN_LDS_PER_CU) return 1;
+  return 0;
+}
+
 bool bwd_stage_fusable(const NetDev &net, int dw_wide) {
   // the fused stage kernel is built for 512-thread recurrences (layers of 193..256 neurons) and the narrow
   // contraction tiles
@@ -2267,7 +2315,7 @@ static hipError_t plan_pre(const NetDev &net, PreJobs *pre, int nwv, size_t *lds
     unsigned gx;
     currents_geometry(net, pre->cur, &gx, &pre->ws, &pre->lcap, nwv);
     pre->cur_gx = (int)gx;
-    *lds = (size_t)nwv * 16 * pre->ws * sizeof(uint64_t) + (size_t)nwv * pre->lcap * sizeof(uint16_t);
+    *lds = (size_t)nwv * 16 * pre->ws * sizeof(uint64_t) + (size_t)nwv * pre->lcap * sizeof(uint32_t);
   }
   if (pre->n_scan != 0) {
     if (pre->t1 <= pre->t0) return hipErrorInvalidValue;

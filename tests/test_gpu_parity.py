@@ -202,6 +202,15 @@ def test_chip_wide_adjoint_valu_version(monkeypatch):
     monkeypatch.delenv("SNN_WS_KERNEL")
 
 
+def test_wide_input_layer_with_stage_kernels():
+    """3000 input channels in front of two 256-wide layers: the spike words and lists of the matrix-core current
+    kernel still fit beside the sequential part of a forward stage, but no longer with eight wavefronts beside the
+    adjoint recurrences, so the recompute work of later chunks moves to the launch between the stages."""
+    w = synth.Workload("wide_in_3000-256-224-9", 3000, (256, 224), 9, T=70, B=4, p_in=0.03, gain=0.5, seed=27)
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 8), (snn.SNN_REMOTE, 16, 0), (snn.SNN_DOUBLE, 24, 5)],
+                 nthreads=4)
+
+
 def test_config1_full_size():
     """Configuration 1 at its full size (T = 1000, batch 32), the launch configuration the benchmark times:
     Standard, Chunk(32), Remote(32) as the configuration lists, plus Double."""
