@@ -36,8 +36,9 @@ STRATEGY_PARAMS = {
     1: {"standard": (0, 0), "chunk": (0, 32), "remote": (32, 0), "double": (100, 10), "hier": (4, 32)},
     2: {"standard": (0, 0), "chunk": (0, 100), "remote": (100, 0), "double": (100, 10), "hier": (4, 100)},
     3: {"standard": (0, 0), "chunk": (0, 316), "remote": (316, 0), "double": (316, 18), "hier": (4, 316)},
+    4: {"standard": (0, 0), "chunk": (0, 70), "remote": (70, 0), "double": (70, 10), "hier": (4, 70)},
 }
-BUDGET = {2: 8 * 10**9, 3: 4 * 10**9}
+BUDGET = {2: 8 * 10**9, 3: 4 * 10**9, 4: 32 * 10**9}
 SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3, "hier": 4}  # hier: (nb_local, chunk)
 
 
@@ -103,6 +104,7 @@ def main():
     ap.add_argument("--config", type=int, default=1)
     ap.add_argument("--strategy", default="remote", choices=list(SID))
     ap.add_argument("--T", type=int, default=0, help="override the sequence length")
+    ap.add_argument("--gain", type=float, default=0.0, help="override the weight gain (sets the hidden firing rate)")
     ap.add_argument("--coarse", type=int, default=-1)
     ap.add_argument("--fine", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -188,7 +190,7 @@ def main():
         print(json.dumps({"model_sweep": "700->N->N->20, batch 32", "T": T, "budget_bytes": budget_b, "rows": rows}))
         return
 
-    w = synth.config(args.config, **({"T": args.T} if args.T else {}))
+    w = synth.config(args.config, **({"T": args.T} if args.T else {}), **({"gain": args.gain} if args.gain else {}))
     d = synth.generate(w)
     x = torch.from_numpy(d["in_spikes"]).to(dev)
     y = torch.from_numpy(d["labels"]).to(dev)

@@ -311,14 +311,16 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   {
     int nmax = 0;
     for (int l = 0; l < L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
-    if (nmax > 256 && nmax <= 1024 && !std::getenv("SNN_NO_WS")) {
+    if (nmax > 256 && nmax <= 16384 && !std::getenv("SNN_NO_WS")) {
       // exchange buffer + barrier counters in uncached device memory (coherent across the chip
       // without cache maintenance).  Such memory is never freed while the process lives: blocks are
       // kept in a per-process pool and handed out again.
       // one exchange buffer and one set of 64 counters per job of a launch (layers of equal width that are one
       // tile apart share a launch), one error flag
       const size_t n_bar = (size_t)64 * SNN_MAXL + 16; // counters + error flag, padded to a multiple of 64 bytes
-      const size_t xg_stride = ((size_t)2 * B * nmax + 15) & ~(size_t)15;
+      // (the kernel for layers wider than 1024 pads the batch to whole blocks of 16: 1, 2 or 4 of them)
+      const size_t bp = nmax > 1024 && B <= 64 ? (size_t)((B + 15) / 16 == 3 ? 4 : (B + 15) / 16) * 16 : (size_t)B;
+      const size_t xg_stride = ((size_t)2 * bp * nmax + 15) & ~(size_t)15;
       const size_t bytes = n_bar * sizeof(unsigned) + (size_t)SNN_MAXL * xg_stride * 4;
       void *blk = uncached_block(cfg->device, bytes);
       if (!blk) return fail(c, SNN_E_HIP, "uncached device allocation failed");
@@ -331,6 +333,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
       c->ws.max_groups_m = ws_max_resident_groups_mfma(cfg->device);
       c->ws.spin_limit = 4000000u; // ~1 s of polling: far beyond any real wait
       if (const char *e = std::getenv("SNN_WS_SPIN_LIMIT")) c->ws.spin_limit = (unsigned)std::strtoul(e, nullptr, 10);
+      adjoint_prepare(n, c->ws);
     }
   }
   HIPCHK(c, hipMalloc(&c->counters, 8 * (SNN_MAXL + 1)));

@@ -124,6 +124,7 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
                                const SpanHook *hook = nullptr);
 int ws_max_resident_groups(int device);
 int ws_max_resident_groups_mfma(int device);
+void adjoint_prepare(const NetDev &net, const WsArgs &ws); // occupancy queries of the wide-layer kernel, at init
 // dW[j][:] += sum over t = t1..t0+1 (descending), b ascending, of pre-spike(t - lag, b, j) * post(t, b, :)
 // where post(t) sits at slot (t - t_base - 1) of postbuf with row stride post_stride (floats per batch
 // element) and column offset post_off.

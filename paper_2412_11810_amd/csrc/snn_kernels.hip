@@ -1269,6 +1269,190 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
     if (fin[e]) carry[(size_t)fb[e] * (SN + O) + off + fj[e]] = xs[(size_t)fj[e] * 16 + fbb[e]];
 }
 
+// The chip-wide recurrence for layers whose recurrent matrix does not fit the registers of the chip (N > 1024,
+// N a multiple of 64, batch <= 64).  Per step the whole batch shares ONE pass over W_rec: workgroup js owns
+// R = 16 RB postsynaptic rows and every batch element, its four wavefronts each take a quarter of the reduction
+// range.  A operand of a K-step group (v_mfma_f32_16x16x4, four K-steps per 16 presynaptic neurons): lane
+// (i, k) loads the 16 bytes W_rec[j0 + i][n .. n+4) with n = nb + 16 q + 4 k, so the four lanes of a row read 64
+// contiguous bytes and the stream over q walks each row front to back; component s of the load is the A value
+// of K-step s.  The B operand needs dv_{t+1}[n + s][b] in the same lane positions: the exchange buffer holds
+// dv as [batch block][n / 4][16 batch][4], one 16-byte load per lane and 1 KB contiguous per wavefront.  The
+// order of the sum (which neuron meets which K-step) is fixed by this layout and the same in every launch.
+// Loads of W_rec run D groups ahead of the MFMAs in a register ring that continues into the next step (the
+// matrix is the same), loads of dv start after the step's barrier.  Exchange, counting barrier and its bounded
+// spin are those of k_adj_rec_ws with one counter for the whole grid; dv is read with loads that bypass the
+// non-coherent cache levels (the exchange buffer is uncached device memory).
+template <int RB, int NBB>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+k_adj_rec_wide(NetDev net, AdjJob jb, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err,
+               unsigned spin_limit) {
+  constexpr int D = 8, R = 16 * RB, BP = 16 * NBB, ITEMS = (R / 4) * BP, NIT = (ITEMS + 255) / 256;
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_dead;
+  float *part = (float *)smem; // [4][R][BP]
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, lk = lane >> 4;
+  if (tid == 0) s_dead = 0;
+  const int j0 = blockIdx.x * R;
+  const unsigned n_wg = gridDim.x;
+  const int NQ = N / 64, NQp = (NQ + D - 1) / D * D; // K-step groups per wavefront and step; padded to the ring
+  const int nb = wv * (N / 4);
+  const size_t xpar = (size_t)BP * N; // floats per parity of the exchange buffer
+  const __amdgpu_buffer_rsrc_t xres =
+      __builtin_amdgcn_make_buffer_rsrc((void *)xg, 0, (int)(2 * xpar * sizeof(float)), 0x00027000);
+  const float4 *ap[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+    ap[rb] = reinterpret_cast<const float4 *>(net.W_rec[l] + (size_t)(j0 + 16 * rb + li) * N + nb) + lk;
+  // groups past the end of the range (ring padding) load the last group and are zeroed: they add 0 * dv
+  auto load_a = [&](int q, float4 (&dst)[RB]) {
+    const int qc = q < NQ ? q : NQ - 1;
+    const uint32_t m = 0u - (uint32_t)(q < NQ);
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float4 v = ap[rb][4 * qc];
+      dst[rb].x = __uint_as_float(__float_as_uint(v.x) & m);
+      dst[rb].y = __uint_as_float(__float_as_uint(v.y) & m);
+      dst[rb].z = __uint_as_float(__float_as_uint(v.z) & m);
+      dst[rb].w = __uint_as_float(__float_as_uint(v.w) & m);
+    }
+  };
+  auto load_x = [&](int par, int q, float4 (&dst)[NBB]) {
+    const int qc = q < NQ ? q : NQ - 1;
+#pragma unroll
+    for (int bk = 0; bk < NBB; ++bk) {
+      const uint32_t idx = (uint32_t)(((bk * (N / 4) + nb / 4 + 4 * qc + lk) * 16 + li) * 4);
+      const uint32_t byte = (uint32_t)(((size_t)par * xpar + idx) * sizeof(float));
+      dst[bk] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(xres, byte, 0, 17)); // sc0 sc1
+    }
+  };
+  bool dead = false;
+  unsigned arrivals = 0;
+  auto grid_barrier = [&]() {
+    // see k_adj_rec_ws: every wave waits for its own stores, then one arrival per workgroup
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+    __syncthreads();
+    arrivals += n_wg;
+    if (tid == 0 && !dead) {
+      __hip_atomic_fetch_add(&bar[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned spins = 0;
+      while (spin_limit == 0u || __hip_atomic_load(&bar[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < arrivals) {
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_dead = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __syncthreads();
+    if (s_dead) dead = true; // keep going to the end of the chunk, never wait again
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
+  // finalising role: item = 4 consecutive rows x one batch element
+  int fj[NIT], fbb[NIT];
+  bool fit[NIT], fin[NIT];
+  float dprev[NIT][4];
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int it = tid + 256 * i;
+    fit[i] = it < ITEMS;
+    fj[i] = j0 + 4 * ((it / BP) % (R / 4));
+    fbb[i] = it % BP;
+    fin[i] = fit[i] && fbb[i] < B;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      dprev[i][c] = (fin[i] && !carry_init) ? carry[(size_t)fbb[i] * (SN + O) + off + fj[i] + c] : 0.0f;
+  }
+  auto x_slot = [&](int par, int i) { // this item's four values in the exchange buffer
+    return xg + (size_t)par * xpar + ((size_t)((fbb[i] >> 4) * (N / 4) + fj[i] / 4) * 16 + (fbb[i] & 15)) * 4;
+  };
+  // dv_{t1+1} of the own rows into parity 1, which step 0 reads
+#pragma unroll
+  for (int i = 0; i < NIT; ++i)
+    if (fit[i]) *reinterpret_cast<float4 *>(x_slot(1, i)) = make_float4(dprev[i][0], dprev[i][1], dprev[i][2], dprev[i][3]);
+  float4 a[D][RB], x[D][NBB];
+#pragma unroll
+  for (int d = 0; d < D; ++d) load_a(d, a[d]);
+  grid_barrier();
+  const size_t slot_stride = (size_t)B * SN;
+  unsigned step = 0;
+  for (int t = t1; t > t0; --t, ++step) {
+    const int rd = (int)((step & 1u) ^ 1u);
+    const size_t slot = (size_t)(t - t_base - 1);
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_x(rd, d, x[d]);
+    float vt[NIT][4], upv[NIT][4];
+#pragma unroll
+    for (int i = 0; i < NIT; ++i)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        vt[i][c] = fin[i] ? vbuf[slot * slot_stride + (size_t)fbb[i] * SN + off + fj[i] + c] : 0.0f;
+        upv[i][c] = fin[i] ? up[(slot * B + fbb[i]) * ldu + fj[i] + c] : 0.0f;
+      }
+    v4f acc[RB][NBB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int bk = 0; bk < NBB; ++bk) acc[rb][bk] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int q0 = 0; q0 < NQp; q0 += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int bk = 0; bk < NBB; ++bk) {
+            acc[rb][bk] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[d][rb].x, x[d][bk].x, acc[rb][bk], 0, 0, 0);
+            acc[rb][bk] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[d][rb].y, x[d][bk].y, acc[rb][bk], 0, 0, 0);
+            acc[rb][bk] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[d][rb].z, x[d][bk].z, acc[rb][bk], 0, 0, 0);
+            acc[rb][bk] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[d][rb].w, x[d][bk].w, acc[rb][bk], 0, 0, 0);
+          }
+        const int qn = q0 + d + D;
+        load_x(rd, qn, x[d]);                        // past the end: a repeat of the last group, never used
+        load_a(qn >= NQp ? qn - NQp : qn, a[d]);     // past the end: the first groups of the next step
+      }
+    }
+    // D[4 lk + r][li] of block (rb, bk): row 16 rb + 4 lk + r, batch element 16 bk + li
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int bk = 0; bk < NBB; ++bk)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[((size_t)wv * R + 16 * rb + 4 * lk + r) * BP + 16 * bk + li] = acc[rb][bk][r];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NIT; ++i)
+      if (fit[i]) {
+        float dv[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int fr = fj[i] - j0 + c;
+          float sacc = part[((size_t)0 * R + fr) * BP + fbb[i]];
+#pragma unroll
+          for (int k = 1; k < 4; ++k) sacc = sacc + part[((size_t)k * R + fr) * BP + fbb[i]];
+          const float dn = dprev[i][c];
+          const float ds = (sacc + upv[i][c]) - net.theta * dn;
+          dv[c] = fin[i] ? fmaf(ds, surrogate(net, vt[i][c]), net.alpha * dn) : 0.0f;
+          if (fin[i]) vbuf[slot * slot_stride + (size_t)fbb[i] * SN + off + fj[i] + c] = dv[c];
+          dprev[i][c] = dv[c];
+        }
+        *reinterpret_cast<float4 *>(x_slot(rd ^ 1, i)) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+      }
+    if (t > t0 + 1) grid_barrier(); // nobody reads the exchange buffer after the last step
+  }
+  // carry out dv_{t0+1}: every workgroup writes its own rows
+#pragma unroll
+  for (int i = 0; i < NIT; ++i)
+    if (fin[i])
+#pragma unroll
+      for (int c = 0; c < 4; ++c) carry[(size_t)fbb[i] * (SN + O) + off + fj[i] + c] = dprev[i][c];
+}
+
 // Recurrent part, any layer width: the transposed recurrent matrix is streamed from L2 every step
 // (coalesced over the output index), the reduction split over KG thread groups with a fixed
 // combination order.
@@ -1834,7 +2018,7 @@ static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStr
   const int nwv = currents_lds(4, ws, lcap) + 8192 <= SNN_LDS_PER_CU ? 4 : 2;
   if (nwv == 2) currents_geometry(net, mf, &gx, &ws, &lcap, 2);
   const size_t lds = currents_lds(nwv, ws, lcap);
-  if (lds + 8192 > SNN_LDS_PER_CU) return hipErrorInvalidValue;
+  if (lds + 8192 > SNN_LDS_PER_CU) return launch_currents_gather(net, jobs, s); // same sums, event by event
   if (lds > 48 * 1024) {
     const hipError_t ea = hipFuncSetAttribute(nwv == 4 ? reinterpret_cast<const void *>(k_currents_mfma<4>)
                                                        : reinterpret_cast<const void *>(k_currents_mfma<2>),
@@ -2126,6 +2310,74 @@ hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_bas
 }
 
 static bool ws_use_mfma();
+
+// Chip-wide recurrence of a wide layer: geometry and launch.
+template <int RB, int NBB>
+static hipError_t launch_adj_wide_t(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, int device,
+                                    hipStream_t s, bool dry, int *resident) {
+  const int N = net.N[jb.l];
+  const size_t lds = (size_t)4 * (16 * RB) * (16 * NBB) * sizeof(float);
+  static int cached[16] = {}; // resident workgroups per device: the occupancy of the kernel does not change
+  if (device < 0 || device >= 16) return hipErrorInvalidValue;
+  if (!cached[device]) {
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, device);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wide<RB, NBB>, 256, lds);
+    if (e != hipSuccess) return e;
+    cached[device] = per_cu * prop.multiProcessorCount;
+  }
+  *resident = cached[device];
+  if (dry) return hipSuccess;
+  hipLaunchKernelGGL((k_adj_rec_wide<RB, NBB>), dim3(N / (16 * RB)), dim3(256), lds, s, net, jb, carry, ws.xg, ws.bar, ws.err,
+                     ws.spin_limit);
+  return hipGetLastError();
+}
+static hipError_t adj_wide_dispatch(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s,
+                                    bool dry, int *rows, int *resident) {
+  const int N = net.N[jb.l], nbb = (net.B + 15) / 16;
+  int device = 0;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return e;
+  const int rb = N >= 4096 ? 2 : 1; // 32 rows per workgroup once that still gives 128 workgroups
+  *rows = 16 * rb;
+  if (rb == 2) {
+    if (nbb == 1) return launch_adj_wide_t<2, 1>(net, jb, carry, ws, device, s, dry, resident);
+    if (nbb == 2) return launch_adj_wide_t<2, 2>(net, jb, carry, ws, device, s, dry, resident);
+    return launch_adj_wide_t<2, 4>(net, jb, carry, ws, device, s, dry, resident);
+  }
+  if (nbb == 1) return launch_adj_wide_t<1, 1>(net, jb, carry, ws, device, s, dry, resident);
+  if (nbb == 2) return launch_adj_wide_t<1, 2>(net, jb, carry, ws, device, s, dry, resident);
+  return launch_adj_wide_t<1, 4>(net, jb, carry, ws, device, s, dry, resident);
+}
+// SNN_WS_KERNEL=stream keeps wide layers on the one-workgroup-per-batch-element kernel
+static bool adj_wide_ok(const NetDev &net, int l, const WsArgs &ws) {
+  const int N = net.N[l], B = net.B;
+  const char *env = getenv("SNN_WS_KERNEL");
+  if (env && strcmp(env, "stream") == 0) return false;
+  if (!ws.xg || N % 64 != 0 || B > 64) return false;
+  const int bp = ((B + 15) / 16 == 3 ? 4 : (B + 15) / 16) * 16;
+  if ((size_t)2 * bp * N > (size_t)ws.xg_stride) return false;
+  AdjJob probe{};
+  probe.l = l;
+  int rows = 0, resident = 0;
+  if (adj_wide_dispatch(net, probe, nullptr, ws, nullptr, true, &rows, &resident) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return N / rows <= resident;
+}
+// Called once when a context is created: the occupancy queries run outside any stream capture.
+void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
+  for (int l = 0; l < net.L; ++l)
+    if (net.N[l] > 1024) (void)adj_wide_ok(net, l, ws);
+}
+static hipError_t launch_adj_wide(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s) {
+  int rows = 0, resident = 0;
+  return adj_wide_dispatch(net, jb, carry, ws, s, false, &rows, &resident);
+}
+
 hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *carry, const WsArgs &ws, hipStream_t s,
                                const SpanHook *hook) {
   const int B = net.B;
@@ -2200,6 +2452,12 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       else
         hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
                            ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+    } else if (adj_wide_ok(net, l, ws)) {
+      taken[i] = true;
+      hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * sizeof(unsigned), s);
+      if (e != hipSuccess) return e;
+      e = launch_adj_wide(net, jb, carry, ws, s);
+      if (e != hipSuccess) return e;
     } else {
       taken[i] = true;
       const int nt = 1024;

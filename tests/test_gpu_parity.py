@@ -202,6 +202,30 @@ def test_chip_wide_adjoint_valu_version(monkeypatch):
     monkeypatch.delenv("SNN_WS_KERNEL")
 
 
+@pytest.mark.parametrize("hidden,B,T", [((1088,), 5, 14), ((1152, 1088), 20, 10), ((1088,), 40, 8), ((4096,), 3, 9)])
+def test_streamed_chip_wide_adjoint(hidden, B, T, monkeypatch):
+    """Layers wider than 1024 neurons: the recurrence of the adjoint streams W_rec once per step for the whole
+    batch (matrix cores, workgroups of 16 or 32 rows, batch in 1, 2 or 4 blocks of 16, a reduction range that is
+    not a multiple of the prefetch ring).  Against the oracle, bit-identical between strategies, and within the
+    tolerance of the one-workgroup-per-batch-element kernel it replaces."""
+    w = synth.Workload("wide_" + "x".join(map(str, hidden)), 40, hidden, 7, T=T, B=B, p_in=0.1, seed=31 + B)
+    first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 4), (snn.SNN_DOUBLE, 8, 3)], nthreads=4)
+    monkeypatch.setenv("SNN_WS_KERNEL", "stream")
+    d = synth.generate(w)
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+        other = _gpu_grads(net, len(hidden))
+    finally:
+        net.snn_destroy()
+    monkeypatch.delenv("SNN_WS_KERNEL")
+    flat = lambda g: list(g[0]) + list(g[1]) + [g[2]]
+    for a, b in zip(flat(first), flat(other)):
+        scale = float(np.max(np.abs(b))) or 1.0
+        assert float(np.max(np.abs(a - b))) <= 1e-4 * scale
+
+
 def test_wide_input_layer_with_stage_kernels():
     """3000 input channels in front of two 256-wide layers: the spike words and lists of the matrix-core current
     kernel still fit beside the sequential part of a forward stage, but no longer with eight wavefronts beside the
@@ -406,12 +430,14 @@ def test_gather_and_matrix_core_currents_agree(monkeypatch):
     monkeypatch.delenv("SNN_CURRENTS")
 
 
-def test_barrier_timeout_is_reported_not_hung(monkeypatch):
-    """The chip-wide adjoint kernel of wide layers synchronises its workgroups with a counting barrier
+@pytest.mark.parametrize("width", [512, 1088])
+def test_barrier_timeout_is_reported_not_hung(monkeypatch, width):
+    """The chip-wide adjoint kernels of wide layers (weights in registers up to 1024 neurons, streamed
+    above) synchronise their workgroups with a counting barrier
     that polls a bounded number of times.  With the limit forced to zero from the host every workgroup
     gives up at its first barrier: all kernels still run to completion, and snn_bptt reports the
     failure instead of returning gradients.  A context created afterwards works normally."""
-    w = synth.Workload("wide_24-512-6", 24, (512,), 6, T=12, B=4, p_in=0.1, seed=11)
+    w = synth.Workload(f"wide_24-{width}-6", 24, (width,), 6, T=12, B=4, p_in=0.1, seed=11)
     d = synth.generate(w)
     monkeypatch.setenv("SNN_WS_SPIN_LIMIT", "0")
     net = snn.from_workload(w, d)
