@@ -572,6 +572,122 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
   currents_mfma_body<NWV>(net, jobs.j[blockIdx.y], ws, lcap, (int)blockIdx.x, smem);
 }
 
+// The same contraction for matrices far larger than the L2 (a presynaptic x postsynaptic product of tens of MB):
+// what bounds the list version there is the weight traffic, every block of 16 rows streaming its own selection
+// of weight rows from memory.  Here a workgroup owns 16 MB (t, b) rows x 256 postsynaptic neurons, wavefront w
+// the 64 columns 64 w .. 64 w + 63 of all 16 MB rows: it visits EVERY presynaptic neuron k in ascending order
+// (at a few percent activity the union over 64 rows is nearly full anyway), loads the 256-byte segment of weight
+// row k once (the four wavefronts of the workgroup read 1 KB contiguous per k) and issues one K = 1 MFMA per block of 16 rows with that
+// segment as the B operand, on MB independent accumulators (no dependent-issue stall).  The A operand of block
+// mb in lane r is bit k of the spike word of row 16 mb + r, taken from a register that is reloaded from LDS every
+// 64 k.  acc + 0 * w leaves acc as it is, so the result is bit-identical to the list version and to a gather.
+// mode 0 runs the feed-forward and the recurrent part one after the other in the same wavefront and adds the two
+// partial currents as I_in + I_rec.
+template <int MB>
+static __device__ __forceinline__ void dense_stream(const uint64_t *words, int ws, int lane, int P,
+                                                    __amdgpu_buffer_rsrc_t wres, uint32_t col4, int N, v16f (&acc)[MB]) {
+  constexpr int U = 8, D = 4;
+  const uint32_t n4 = (uint32_t)N * 4u;
+  const int Pw = (P + 63) >> 6;
+  float w[D][U];
+  auto issue = [&](int g, float (&wv)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = g * U + u, kc = k < P ? k : P - 1; // past the end: the last row again, multiplied by 0
+      wv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, col4, (uint32_t)kc * n4, 0));
+    }
+  };
+#pragma unroll
+  for (int g = 0; g < D - 1; ++g) issue(g, w[g]);
+  for (int kw = 0; kw < Pw; ++kw) {
+    uint64_t wr[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) wr[mb] = words[(size_t)(16 * mb + (lane & 15)) * ws + kw];
+#pragma unroll
+    for (int g8 = 0; g8 < 8; ++g8) {
+      __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
+      issue(kw * 8 + g8 + D - 1, w[(g8 + D - 1) % D]);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          const float a = (float)((uint32_t)(wr[mb] >> (8 * g8 + u)) & 1u);
+          acc[mb] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, w[g8 % D][u], acc[mb], 2, 0, 0);
+        }
+    }
+  }
+}
+
+template <int MB>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+k_currents_dense(NetDev net, CurJobs jobs, int ws) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t *words = (uint64_t *)smem; // [16 MB][ws]
+  constexpr int RW = 16 * MB;
+  const CurJob &ca = jobs.j[blockIdx.y];
+  const bool ro = ca.mode == 2;
+  const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
+  const int rows = ca.nsteps * B, ncg = (N + 255) >> 8, n_rg = (rows + RW - 1) / RW;
+  if ((int)blockIdx.x >= n_rg * ncg) return;
+  const int cg = (int)blockIdx.x % ncg, rg = (int)blockIdx.x / ncg;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int m0 = rg * RW, cb0 = cg * 256 + wave * 64, col = cb0 + lane;
+  const bool active = cb0 < N; // a wavefront past the last column only helps to load the spike words
+  v16f acc0[MB], acc1[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc0[mb][r] = acc1[mb][r] = 0.0f;
+  auto run_part = [&](int part, v16f (&acc)[MB]) {
+    const int pl = (part == 0 && !ro) ? l : l + 1;
+    const int Wp = net.Wd[pl];
+    const int P = ro ? net.N[l] : part == 0 ? (l == 0 ? net.n_in : net.N[l - 1]) : N;
+    const float *W = ro ? net.W_out : part == 0 ? net.W_in[l] : net.W_rec[l];
+    if (part) __syncthreads(); // everybody is done with the words of the first part
+    for (int idx = tid; idx < RW * Wp; idx += 256) {
+      const int r = idx / Wp, wi = idx - r * Wp, m = m0 + r;
+      uint64_t v = 0ull;
+      if (m < rows) {
+        const int t = ca.t0 + 1 + m / B, b = m % B;
+        v = net.mask[pl][((size_t)(part == 0 ? t : t - 1) * B + b) * Wp + wi];
+        const int rem = P - wi * 64;
+        if (rem < 64) v &= rem <= 0 ? 0ull : (1ull << rem) - 1ull;
+      }
+      words[(size_t)r * ws + wi] = v;
+    }
+    __syncthreads();
+    if (active) {
+      const __amdgpu_buffer_rsrc_t wres =
+          __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((size_t)P * N * sizeof(float)), 0x00027000);
+      dense_stream<MB>(words, ws, lane, P, wres, (uint32_t)(col < N ? col : 0) * 4u, N, acc);
+    }
+  };
+  run_part(0, acc0);
+  if (ca.mode == 0) run_part(1, acc1);
+  if (!active) return;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    if (ca.mode == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc0[mb][r] = acc0[mb][r] + acc1[mb][r];
+    }
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int mm = m0 + 16 * mb + 4 * (lane >> 4) + rr;
+      if (mm >= rows) continue;
+      const int t = ca.t0 + 1 + mm / B, b = mm % B;
+      float *dst = ca.mode == 0
+                       ? ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
+                       : ca.out + ((size_t)(t - ca.t_base - 1) * B + b) * N;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = cb0 + 16 * q + (lane & 15);
+        if (c < N) dst[c] = acc0[mb][4 * q + rr];
+      }
+    }
+  }
+}
+
 // One stage of the pipelined forward pass in a single launch: the first n_seq_blocks workgroups run the
 // sequential part of every layer's current tile (job = block / B, batch element = block % B), the others
 // compute the synaptic currents that the NEXT stage's sequential parts will consume (virtual grid cur_gx x
@@ -2005,11 +2121,64 @@ static size_t currents_lds(int nwv, int ws, int lcap) {
   return (size_t)nwv * 16 * ws * sizeof(uint64_t) + (size_t)nwv * lcap * sizeof(uint32_t);
 }
 #define SNN_LDS_PER_CU (160 * 1024)
+// Matrices of a job: presynaptic widths and the larger product with the postsynaptic width, in bytes.
+static void currents_job_shape(const NetDev &net, const CurJob &j, int *pmax, size_t *wbytes) {
+  const bool ro = j.mode == 2;
+  const int l = ro ? net.L - 1 : j.lsel, N = ro ? net.n_out : net.N[l];
+  int p = ro ? net.N[l] : (l == 0 ? net.n_in : net.N[l - 1]);
+  if (j.mode == 0 && N > p) p = N;
+  *pmax = p;
+  *wbytes = (size_t)p * N * sizeof(float);
+}
+// The dense version takes the jobs whose weights are far beyond the L2 (SNN_CURRENTS=dense: every job,
+// SNN_CURRENTS=mfma: none).
+#define SNN_DENSE_MB 4
+static bool currents_job_dense(const NetDev &net, const CurJob &j) {
+  int p;
+  size_t wb;
+  currents_job_shape(net, j, &p, &wb);
+  if (wb >= ((size_t)1 << 32)) return false;                                                   // one buffer descriptor
+  if ((size_t)16 * SNN_DENSE_MB * (((p + 63) >> 6) | 1) * 8 + 1024 > SNN_LDS_PER_CU) return false; // spike words of 64 rows
+  const char *e = getenv("SNN_CURRENTS");
+  if (e && strcmp(e, "dense") == 0) return true;
+  if (e && strcmp(e, "mfma") == 0) return false;
+  return wb >= ((size_t)32 << 20);
+}
+static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
+  unsigned gx = 0;
+  int ws = 1;
+  for (int i = 0; i < jobs.count; ++i) {
+    const CurJob &j = jobs.j[i];
+    int p;
+    size_t wb;
+    currents_job_shape(net, j, &p, &wb);
+    const int N = j.mode == 2 ? net.n_out : net.N[j.lsel], rows = j.nsteps * net.B;
+    const unsigned g = (unsigned)(((rows + 16 * SNN_DENSE_MB - 1) / (16 * SNN_DENSE_MB)) * ((N + 255) >> 8));
+    gx = g > gx ? g : gx;
+    const int w1 = ((p + 63) >> 6) | 1;
+    ws = w1 > ws ? w1 : ws;
+  }
+  const size_t lds = (size_t)16 * SNN_DENSE_MB * ws * sizeof(uint64_t);
+  if (lds > 48 * 1024) {
+    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (ea != hipSuccess) return ea;
+  }
+  hipLaunchKernelGGL(k_currents_dense<SNN_DENSE_MB>, dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
+  return hipGetLastError();
+}
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
-  CurJobs mf{};
+  CurJobs mf{}, dn{};
   for (int i = 0; i < jobs.count; ++i)
-    if (jobs.j[i].nsteps > 0) mf.j[mf.count++] = jobs.j[i];
+    if (jobs.j[i].nsteps > 0) {
+      if (currents_job_dense(net, jobs.j[i])) dn.j[dn.count++] = jobs.j[i];
+      else mf.j[mf.count++] = jobs.j[i];
+    }
+  if (dn.count) {
+    const hipError_t e = launch_currents_dense(net, dn, s);
+    if (e != hipSuccess) return e;
+  }
   if (!mf.count) return hipSuccess;
   unsigned gx;
   int ws, lcap;

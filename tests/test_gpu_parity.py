@@ -406,14 +406,18 @@ def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
 
 
 def test_gather_and_matrix_core_currents_agree(monkeypatch):
-    """The synaptic currents are computed either event by event (gather of the active rows) or by the K = 1
-    MFMA kernel, which visits the same rows in the same order.  Both must give the very same bits: spike
-    trains, membrane potentials and gradients, for a dense-activity and a sparse-activity network."""
-    for w in (synth.config(1, T=150, B=6), synth.Workload("sparse_90-200-130-7", 90, (200, 130), 7, T=150, B=5, p_in=0.03, gain=0.3, seed=21)):
+    """The synaptic currents are computed either event by event (gather of the active rows), by the K = 1
+    MFMA kernel that visits the rows active in a block of 16 (t, b) rows, or by its dense version that visits
+    every presynaptic neuron for 64 (t, b) rows at a time (meant for matrices far beyond the L2; forced here).
+    All add the same rows in the same order and must give the very same bits: spike trains, membrane
+    potentials and gradients, for a dense-activity and a sparse-activity network and for layers that run
+    outside the stage kernels (320 and 300 neurons: a ragged last block of columns, 70 inputs: a partial word)."""
+    for w in (synth.config(1, T=150, B=6), synth.Workload("sparse_90-200-130-7", 90, (200, 130), 7, T=150, B=5, p_in=0.03, gain=0.3, seed=21),
+              synth.Workload("mid_70-320-300-9", 70, (320, 300), 9, T=45, B=5, p_in=0.08, gain=0.6, seed=22)):
         d = synth.generate(w)
         L = len(w.n_hidden)
         got = {}
-        for mode in ("gather", "mfma"):
+        for mode in ("gather", "mfma", "dense"):
             monkeypatch.setenv("SNN_CURRENTS", mode)
             net = snn.from_workload(w, d)
             try:
@@ -423,10 +427,12 @@ def test_gather_and_matrix_core_currents_agree(monkeypatch):
                 got[mode] = (_gpu_grads(net, L), [net.snn_get_spikes(l, w.T) for l in range(L)], states)
             finally:
                 net.snn_destroy()
-        assert _identical(got["gather"][0], got["mfma"][0]), w.name
-        for a, b in zip(got["gather"][1], got["mfma"][1]):
-            assert np.array_equal(a, b), w.name
-        assert np.array_equal(got["gather"][2].view(np.uint32), got["mfma"][2].view(np.uint32)), w.name
+        for other in ("mfma", "dense"):
+            assert _identical(got["gather"][0], got[other][0]), (w.name, other)
+            for a, b in zip(got["gather"][1], got[other][1]):
+                assert np.array_equal(a, b), (w.name, other)
+            assert np.array_equal(got["gather"][2].view(np.uint32), got[other][2].view(np.uint32)), (w.name, other)
+        assert sum(int(x.sum()) for x in got["gather"][1]) > 0, w.name
     monkeypatch.delenv("SNN_CURRENTS")
 
 
