@@ -56,6 +56,12 @@ def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
     # forward, parallel part: rows of W_in (4*N_l bytes per event), the current tile written and read
     # once, readout rows (4*n_out per last-layer spike)
     out["fwd_currents"] = ("hbm", T * (sum(4.0 * N[l] * ev_in[l] + 8.0 * N[l] * B for l in range(L)) + 4.0 * w.n_out * ev_out))
+    # weight matrices far beyond the L2 (the library's rule: 32 MB and more) go through the dense matrix-core
+    # kernel, which visits every presynaptic neuron: priced as the contraction it is
+    dense = [4.0 * max(pre_n[l], N[l]) * N[l] >= (32 << 20) for l in range(L)]
+    dense_fwd = [4.0 * pre_n[l] * N[l] >= (32 << 20) for l in range(L)]
+    if any(dense_fwd):
+        out["fwd_currents"] = ("mfma32", T * B * sum(2.0 * N[l] * pre_n[l] for l in range(L) if dense_fwd[l]))
     # forward, sequential part: register-stationary layers do dense fma chains (2*N^2 flop per (b, t));
     # wider layers gather the rows of active neurons
     seq_flops = sum(2.0 * N[l] * N[l] * B * T for l in range(L) if N[l] <= 256)
@@ -63,12 +69,17 @@ def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
     out["fwd_seq"] = ("alu", seq_flops) if seq_flops >= seq_bytes else ("hbm", seq_bytes)
     # recompute: rows of W_in and W_rec per event + current written, read, state written (12*N_l per (b, t))
     out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * (ev_in[l] + ev_rec[l]) + 12.0 * N[l] * B for l in range(L)))
-    # adjoint: dense recurrent product, 2*N^2 flop per (b, t, layer)
+    if any(dense):
+        out["recompute"] = ("mfma32", refwd_steps * B * sum(2.0 * N[l] * (pre_n[l] + N[l]) for l in range(L) if dense[l]))
+    # adjoint: dense recurrent product, 2*N^2 flop per (b, t, layer); layers wider than 1024 stream W_rec from
+    # memory once per step for the whole batch (4*N^2 bytes per (t, layer)) and are bound by that
     out["adjoint"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)))
+    if max(N) > 1024:
+        out["adjoint"] = ("hbm", sum(4.0 * N[l] * N[l] * T for l in range(L) if N[l] > 1024))
     up = [w.n_out if l == L - 1 else N[l + 1] for l in range(L)]
     out["up_gemm"] = ("mfma32", sum(2.0 * N[l] * up[l] * B * T for l in range(L)))
-    # dW: dense fp64 contraction over (t, b): 2 * n_pre * n_post * B * T per matrix
-    out["dw"] = ("mfma", 2.0 * B * T * (sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out))
+    # dW: dense fp32 matrix-core contraction over (t, b): 2 * n_pre * n_post * B * T per matrix
+    out["dw"] = ("mfma32", 2.0 * B * T * (sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out))
     # fused stage launches (recurrences of one pipeline stage + weight gradients of the stage before): the
     # flops of both parts; the launch is as long as the longer of the two, the recurrence chain as a rule
     out["bwd_stage"] = ("alu", out["adjoint"][1] + out["dw"][1])
@@ -309,8 +320,9 @@ def main():
         # sequential parts and the readout scans
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
-                 "fwd_currents": "k_currents_mfma", "recompute": "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
-                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_stream")}
+                 "fwd_currents": "k_currents_dense" if model["fwd_currents"][0] == "mfma32" else "k_currents_mfma",
+                 "recompute": "k_currents_dense" if model["recompute"][0] == "mfma32" else "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
+                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12),
              "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
     kinds = {}

@@ -45,7 +45,7 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
-  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event; } };
+  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol; } };
   GraphKeyT graph_key{};
   hipGraphExec_t graph_exec = nullptr;
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
@@ -54,6 +54,7 @@ struct snn_ctx {
   bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
   bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
   bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
+  bool rate_driven = false;     // some weight matrix is far beyond the L2: the current kernel follows the firing rates
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -337,6 +338,10 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
     }
   }
   HIPCHK(c, hipMalloc(&c->counters, 8 * (SNN_MAXL + 1)));
+  for (int l = 0; l < L; ++l) {
+    const size_t pmax = (size_t)std::max(l == 0 ? n.n_in : n.N[l - 1], n.N[l]);
+    if (pmax * n.N[l] * sizeof(float) >= ((size_t)32 << 20)) c->rate_driven = true;
+  }
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return SNN_OK;
 }
@@ -574,6 +579,40 @@ struct Timer {
   SpanHook hook() { return SpanHook{this, &Timer::hook_begin, &Timer::hook_end}; }
 };
 } // namespace
+
+// Firing rates of the step that was just queued (spike counts of all stored bitmasks), and from them the current
+// kernel of the layers with very large weight matrices for the next step: the event-by-event gather pays per
+// presynaptic spike, the dense matrix-core version per presynaptic neuron; measured break-even about 4.5 %.
+static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out) {
+  const NetDev &n = c->net;
+  const int L = n.L, B = n.B;
+  hipStream_t s = c->stream;
+  HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
+  for (int l = 0; l <= L; ++l)
+    HIPCHK(c, launch_count_spikes(n.mask[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  unsigned long long cnt[SNN_MAXL + 1];
+  HIPCHK(c, hipMemcpy(cnt, c->counters, sizeof cnt, hipMemcpyDeviceToHost));
+  double r[SNN_MAXL + 1];
+  for (int l = 0; l <= L; ++l) r[l] = (double)cnt[l] / ((double)T * B * (l == 0 ? n.n_in : n.N[l - 1]));
+  if (rates_out)
+    for (int l = 0; l < L; ++l) rates_out[l] = (float)r[l + 1];
+  if (c->rate_driven) {
+    // one choice for the whole network (jobs of one launch then stay in one launch): presynaptic activity
+    // averaged over the weight rows of all layers
+    double ev_fw = 0, ev_re = 0, rows_fw = 0, rows_re = 0;
+    for (int l = 0; l < L; ++l) {
+      const double p_in = l == 0 ? n.n_in : n.N[l - 1], p_rec = n.N[l], w = n.N[l];
+      ev_fw += r[l] * p_in * w; rows_fw += p_in * w;
+      ev_re += (r[l] * p_in + r[l + 1] * p_rec) * w; rows_re += (p_in + p_rec) * w;
+    }
+    for (int l = 0; l < L; ++l) {
+      c->net.cur_pol[0][l] = ev_fw < 0.045 * rows_fw ? 1 : 2;
+      c->net.cur_pol[1][l] = ev_re < 0.045 * rows_re ? 1 : 2;
+    }
+  }
+  return SNN_OK;
+}
 
 static snn_status check_ws_error(snn_ctx *c) {
   if (!c->ws.err) return SNN_OK;
@@ -1117,7 +1156,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   Plan p;
   if (!snn_make_plan((int)strategy, T, C_in, F_in, &p)) return fail(c, SNN_E_INVAL, "invalid strategy/intervals");
   NetDev &n = c->net;
-  const int B = n.B, L = n.L;
+  const int L = n.L;
   const size_t Ms = c->Ms();
   // One chunk buffer per layer lets the adjoint pass run its layers one chunk apart (see BwdPipe).  The extra
   // (L - 1) * chunk_len state slots are taken only if the budget has room for them; the results are the same
@@ -1178,7 +1217,9 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // requested; the recording is redone whenever the plan or a buffer it refers to changes.
   const bool use_graph = c->graphs_enabled && !stats;
   if (use_graph) {
-    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven};
+    unsigned long long pol = 0;
+    for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
+    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
       Timer tm{c, false};
@@ -1195,6 +1236,10 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       c->graph_key = key;
     }
     HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
+    if (c->rate_driven) {
+      snn_status rr = update_current_policy(c, T, nullptr);
+      if (rr != SNN_OK) return rr;
+    }
     HIPCHK(c, hipStreamSynchronize(s));
     return check_ws_error(c);
   }
@@ -1205,16 +1250,12 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   snn_status rs = enqueue_step(c, p, st, tm, &ev_fwd);
   if (rs != SNN_OK) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamSynchronize(s); return rs; }
   hipEvent_t ev_end = tm.mark();
-  if (stats) {
-    HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
-    for (int l = 1; l <= L; ++l)
-      HIPCHK(c, launch_count_spikes(n.mask[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
+  if (stats || c->rate_driven) {
+    snn_status rr = update_current_policy(c, T, st.firing_rate);
+    if (rr != SNN_OK) return rr;
   }
   HIPCHK(c, hipStreamSynchronize(s));
   if (stats) {
-    unsigned long long cnt[SNN_MAXL + 1];
-    HIPCHK(c, hipMemcpy(cnt, c->counters, sizeof cnt, hipMemcpyDeviceToHost));
-    for (int l = 0; l < L; ++l) st.firing_rate[l] = (float)((double)cnt[l + 1] / ((double)T * B * n.N[l]));
     (void)hipEventElapsedTime(&st.ms_total, ev_start, ev_end);
     (void)hipEventElapsedTime(&st.ms_forward, ev_start, ev_fwd);
     (void)hipEventElapsedTime(&st.ms_backward_total, ev_fwd, ev_end);

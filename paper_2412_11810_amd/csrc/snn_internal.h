@@ -26,6 +26,10 @@ struct NetDev {
   uint64_t *mask[SNN_MAXL + 1];
   float alpha, beta, theta, k;
   float win;  // surrogate window (<= 0: none)
+  // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step
+  // (0: not known yet -> dense, 1: event-by-event gather, 2: dense matrix-core version); [0] forward currents
+  // (feed-forward part only), [1] recompute (both parts).  Every choice gives the same bits.
+  unsigned char cur_pol[2][SNN_MAXL];
 };
 
 // Where the forward / recompute kernel writes states it has to keep.

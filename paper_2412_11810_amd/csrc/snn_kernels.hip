@@ -2130,19 +2130,24 @@ static void currents_job_shape(const NetDev &net, const CurJob &j, int *pmax, si
   *pmax = p;
   *wbytes = (size_t)p * N * sizeof(float);
 }
-// The dense version takes the jobs whose weights are far beyond the L2 (SNN_CURRENTS=dense: every job,
-// SNN_CURRENTS=mfma: none).
+// Which kernel runs a job: 0 list version, 1 dense version, 2 event-by-event gather.  Weights that fit the L2
+// many times over: always the list version.  Weights far beyond it: what the context chose from the firing rates
+// of its last step (the gather below about 4.5 % presynaptic activity, the dense version above, and before any
+// rate is known).  SNN_CURRENTS=dense / mfma / gather forces one of them for every job.
 #define SNN_DENSE_MB 4
-static bool currents_job_dense(const NetDev &net, const CurJob &j) {
+static int currents_job_kernel(const NetDev &net, const CurJob &j) {
   int p;
   size_t wb;
   currents_job_shape(net, j, &p, &wb);
-  if (wb >= ((size_t)1 << 32)) return false;                                                   // one buffer descriptor
-  if ((size_t)16 * SNN_DENSE_MB * (((p + 63) >> 6) | 1) * 8 + 1024 > SNN_LDS_PER_CU) return false; // spike words of 64 rows
+  const bool dense_ok = wb < ((size_t)1 << 32) &&                                               // one buffer descriptor
+                        (size_t)16 * SNN_DENSE_MB * (((p + 63) >> 6) | 1) * 8 + 1024 <= SNN_LDS_PER_CU; // words of 64 rows
   const char *e = getenv("SNN_CURRENTS");
-  if (e && strcmp(e, "dense") == 0) return true;
-  if (e && strcmp(e, "mfma") == 0) return false;
-  return wb >= ((size_t)32 << 20);
+  if (e && strcmp(e, "dense") == 0) return dense_ok ? 1 : 0;
+  if (e && strcmp(e, "mfma") == 0) return 0;
+  if (wb < ((size_t)32 << 20) || j.mode == 2) return 0;
+  const int pol = net.cur_pol[j.mode == 0 ? 1 : 0][j.lsel];
+  if (pol == 1) return 2;
+  return dense_ok ? 1 : 0;
 }
 static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   unsigned gx = 0;
@@ -2169,14 +2174,19 @@ static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, 
 }
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
-  CurJobs mf{}, dn{};
+  CurJobs mf{}, dn{}, ga{};
   for (int i = 0; i < jobs.count; ++i)
     if (jobs.j[i].nsteps > 0) {
-      if (currents_job_dense(net, jobs.j[i])) dn.j[dn.count++] = jobs.j[i];
-      else mf.j[mf.count++] = jobs.j[i];
+      const int k = currents_job_kernel(net, jobs.j[i]);
+      CurJobs &dst = k == 1 ? dn : k == 2 ? ga : mf;
+      dst.j[dst.count++] = jobs.j[i];
     }
   if (dn.count) {
     const hipError_t e = launch_currents_dense(net, dn, s);
+    if (e != hipSuccess) return e;
+  }
+  if (ga.count) {
+    const hipError_t e = launch_currents_gather(net, ga, s);
     if (e != hipSuccess) return e;
   }
   if (!mf.count) return hipSuccess;
