@@ -465,11 +465,12 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
   if (rs != SNN_OK) return rs;
   HIPCHK(c, hipMemsetAsync(c->cur_state, 0, c->Ms(), c->stream));
   std::vector<int> bounds = tile_bounds(0, c->T_bound, c->T_bound);
-  HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, c->dubuf, c->stream));
+  HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, c->dubuf, c->stream, nullptr, nullptr, &c->ws));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
   return SNN_OK;
 }
 
+static snn_status check_ws_error(snn_ctx *c);
 snn_status snn_forward(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out) {
   snn_status s = snn_bind_inputs(c, in_spikes, labels, T);
   if (s != SNN_OK) return s;
@@ -479,7 +480,7 @@ snn_status snn_forward(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labe
   HIPCHK(c, hipMemcpyAsync(&loss, c->loss_dev, 4, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (loss_out) *loss_out = loss;
-  return SNN_OK;
+  return check_ws_error(c); // the sliced sequential kernels of wide layers wait for each other, with a bound
 }
 
 snn_status snn_debug_states(snn_ctx *c, float *dst) {
@@ -824,12 +825,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   if (strategy == SNN_STANDARD) {
     StoreSpec sp{chunk0, slot, 0, 1, 0, T, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T);
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, nullptr, &c->ws));
   } else if (strategy == SNN_CHUNK) {
     HIPCHK(c, launch_fill_zero(lckpt, Ms, s)); // x_0
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T);
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, nullptr, &c->ws));
   } else if (strategy == SNN_HIER) {
     // Checkpoint k = x_{kF} goes to slot k mod 2*nb_local of a ring of two batches.  When every layer
     // has passed the last checkpoint of a batch (and it is not the final batch), the batch travels to
@@ -877,12 +878,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     StoreSpec sp{lckpt, slot, 0, p.F, 1, T - 1, RB * NL};
     const FwdCallbacks cb{&hier, &Hier::done};
     const std::vector<int> bounds = tile_bounds(0, T, p.F);
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb, &c->ws));
   } else if (direct) {
     // x_0 lives in host slot 0 (zeroed on the host); the sequential kernels store x_{KC} into host slot K
     const StoreSpec sp{c->host_ckpt, slot, 0, p.C, 1, T - 1, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T); // no host-side work at the checkpoints: full tiles
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, nullptr, &c->ws));
     st.n_d2h += p.n_remote - 1;
     st.d2h_bytes += (int64_t)(p.n_remote - 1) * (int64_t)Ms;
   } else {
@@ -927,7 +928,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     const std::vector<int> bounds = tile_bounds(0, T, p.C);
     HIPCHK(c, snap.reserve(0)); // nothing to wait for yet; marks checkpoint 1 as reserved
     const StoreSpec sp{stage, slot, 0, p.C, 1, T - 1, p.n_stage_slots}; // x_{KC} -> staging slot K % n_stage
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb, &c->ws));
   }
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));

@@ -81,9 +81,10 @@ struct SeqJob { int l, t0, t1, t_tile; const float *iin; };
 struct SeqJobs { SeqJob j[SNN_MAXL]; int count; };
 struct CurJob { int mode, lsel, t0, nsteps, t_base; float *out; size_t slot_stride; };
 struct CurJobs { CurJob j[2 * SNN_MAXL + 1]; int count; };
+struct WsArgs;
 hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
                           double *readout /*[B][2][O]*/, int readout_init, float *work, hipStream_t s,
-                          const SpanHook *hook = nullptr, const FwdCallbacks *cb = nullptr);
+                          const SpanHook *hook = nullptr, const FwdCallbacks *cb = nullptr, const WsArgs *ws = nullptr);
 // Recompute pass over steps t0+1..t1 from state_in = x_{t0}, spikes read from the stored bitmasks:
 // currents of the whole range in parallel into buf (slot of x_t = t - t_base - 1), then a scan that
 // turns them into states in place (store_all) and/or writes x_{t1} to state_out.

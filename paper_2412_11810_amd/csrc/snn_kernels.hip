@@ -318,6 +318,110 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   }
 }
 
+// The same sequential part with the neurons of a layer spread over S workgroups per batch element (wide layers:
+// one workgroup per batch element leaves most of the chip idle and is bound by what one compute unit can load).
+// Workgroup (b, sl) owns the columns [sl N/S, (sl+1) N/S) -- whole 64-bit spike words -- and gathers its part of
+// the active rows of W_rec; sums per neuron are the same ascending sums.  After the threshold it writes its
+// spike words to the stored bitmask and to an exchange buffer (uncached device memory, double-buffered by the
+// parity of t), the S workgroups of the batch element meet at a counting barrier (bounded spin, error flag: see
+// k_adj_rec_ws), and each reads the whole layer's words back and expands them into its own copy of the index list.
+template <int NPT>
+__global__ void __launch_bounds__(512)
+k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw,
+                      unsigned *bar, unsigned *err, unsigned spin_limit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_dead;
+  const int jq = blockIdx.y;
+  const int l = jobs.j[jq].l, t0 = jobs.j[jq].t0, t1 = jobs.j[jq].t1, t_tile = jobs.j[jq].t_tile;
+  const float *__restrict__ iin = jobs.j[jq].iin;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
+  const int b = (int)blockIdx.x / S, sl = (int)blockIdx.x % S;
+  const int tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
+  const int Ns = N / S, c0 = sl * Ns, w0 = c0 >> 6; // own columns and their first word
+  uint64_t *words = (uint64_t *)smem;       // [Wd]  whole layer
+  int *cnt = (int *)(words + Wd);           // [1] (+3 pad)
+  uint16_t *list = (uint16_t *)(cnt + 4);   // [N]
+  uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
+  const size_t mstride = (size_t)B * Wd;
+  uint64_t *xb = xw + (size_t)(jq * B + b) * 2 * Wd; // [2][Wd]
+  unsigned *mybar = bar + jq * B + b;
+  if (tid == 0) { s_dead = 0; *cnt = 0; }
+  for (int i = tid; i < Wd; i += nt) words[i] = mbase[(size_t)t0 * mstride + i];
+  __syncthreads();
+  float v[NPT];
+  uint32_t sp = 0;
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    const int n = c0 + tid + k * nt;
+    v[k] = state[(size_t)b * SN + off + n];
+    if ((words[n >> 6] >> lane) & 1ull) sp |= 1u << k;
+  }
+  expand_all(words, Wd, list, cnt, tid, nt);
+  __syncthreads();
+  const size_t istride = (size_t)B * N;
+  unsigned step = 0;
+  bool dead = false;
+  for (int t = t0 + 1; t <= t1; ++t, ++step) {
+    int store_slot = -1;
+    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
+      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
+      if (st.slot_mod > 0) store_slot %= st.slot_mod;
+    }
+    const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N + c0;
+    float in_t[NPT];
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) in_t[k] = irow[tid + k * nt];
+    float unused[NPT], a_rec[NPT];
+    gather2<NPT>(net.W_rec[l] + c0, N, 0u, tid, nt, list, 0, list, *cnt, unused, a_rec);
+    uint64_t *xdst = xb + (size_t)(t & 1) * Wd;
+    uint32_t spn = 0;
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      const int nl = tid + k * nt, widx = w0 + (nl >> 6);
+      float a = net.alpha * v[k];
+      if ((sp >> k) & 1u) a = a - net.theta;
+      const float vn = a + (in_t[k] + a_rec[k]);
+      v[k] = vn;
+      const uint64_t word = __ballot(vn > net.theta);
+      if ((word >> lane) & 1ull) spn |= 1u << k;
+      if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + nl] = vn;
+      if (lane == 0) {
+        mbase[(size_t)t * mstride + widx] = word;
+        xdst[widx] = word;
+      }
+    }
+    sp = spn;
+    // ---- the S workgroups of this batch element meet ------------------------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the own words are in memory
+    __syncthreads();                    // (and every wave is done with the old list)
+    if (tid == 0 && !dead) {
+      __hip_atomic_fetch_add(mybar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const unsigned target = (step + 1u) * (unsigned)S;
+      unsigned spins = 0;
+      while (spin_limit == 0u || __hip_atomic_load(mybar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_dead = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __syncthreads();
+    if (s_dead) dead = true; // keep going to the end of the tile, never wait again
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    for (int i = tid; i < Wd; i += nt) words[i] = __hip_atomic_load(&xdst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) *cnt = 0;
+    __syncthreads();
+    expand_all(words, Wd, list, cnt, tid, nt);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) state[(size_t)b * SN + off + c0 + tid + k * nt] = v[k];
+}
+
 // A4: u_t = beta u_{t-1} + I_out,t ; usum += u_t over the steps of a tile (fp64 state: ubar feeds a
 // softmax, which turns an absolute error of ubar into a relative error of the loss gradient).
 __device__ __forceinline__ void readout_scan_body(const float *__restrict__ iout, double *__restrict__ readout, int B,
@@ -2287,9 +2391,61 @@ static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *
 // stage does is independent of everything else in it, so a stage is one launch (k_fwd_stage) when all
 // layers are register-stationary, and otherwise one launch per kernel flavour.  The current tiles are
 // double-buffered by tile parity.
+// Slices per batch element for the sequential part of wide layers (1: one workgroup per batch element).  All
+// workgroups of a launch must be resident at once (they wait for each other), every wide layer may have a job in
+// the same launch, a slice is a whole number of 512-thread rounds, and the counters and the exchange buffer of
+// the chip-wide kernels must hold one entry per (job, batch element).  SNN_SEQ_SLICES=1 turns slicing off.
+static size_t seq_gather_lds(const NetDev &net);
+template <int NPT>
+static int seq_sl_resident(int device, size_t lds) {
+  static int cached[16] = {};
+  if (device < 0 || device >= 16) return 0;
+  if (!cached[device]) {
+    hipDeviceProp_t prop;
+    int per_cu = 0;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_layer_seq_gather_sl<NPT>, 512, lds) != hipSuccess) return 0;
+    cached[device] = per_cu * prop.multiProcessorCount;
+  }
+  return cached[device];
+}
+static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, int *npt) {
+  if (!ws || !ws->xg || !ws->bar || ga.count < 1) return 1;
+  if (const char *e = getenv("SNN_SEQ_SLICES"))
+    if (strcmp(e, "1") == 0) return 1;
+  const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
+  if (N < 2048) return 1; // narrower: the weights sit in the L2 and a workgroup per batch element is faster (measured at 1024)
+  int n_wide = 0;
+  for (int l = 0; l < net.L; ++l) n_wide += net.N[l] > 256;
+  for (int i = 0; i < ga.count; ++i)
+    if (net.N[ga.j[i].l] != N) return 1;
+  if (net.B * n_wide > 64 * SNN_MAXL) return 1;
+  if ((size_t)n_wide * net.B * 2 * Wd * sizeof(uint64_t) > (size_t)ws->xg_stride * SNN_MAXL * sizeof(float)) return 1;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return 1;
+  const size_t lds = seq_gather_lds(net);
+  for (int S = 8; S >= 2; S /= 2) {
+    if (N % (512 * S) != 0) continue;
+    const int p = N / (512 * S);
+    int resident = 0;
+    switch (p) {
+      case 1: resident = seq_sl_resident<1>(device, lds); break;
+      case 2: resident = seq_sl_resident<2>(device, lds); break;
+      case 4: resident = seq_sl_resident<4>(device, lds); break;
+      case 8: resident = seq_sl_resident<8>(device, lds); break;
+      case 16: resident = seq_sl_resident<16>(device, lds); break;
+      default: continue;
+    }
+    if (S * net.B * n_wide > resident) continue;
+    *npt = p;
+    return S;
+  }
+  return 1;
+}
+
 hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
                           double *readout, int readout_init, float *work, hipStream_t s, const SpanHook *hook,
-                          const FwdCallbacks *cb) {
+                          const FwdCallbacks *cb, const WsArgs *ws) {
   if (n_tiles < 0) return hipErrorInvalidValue;
   for (int k = 0; k < n_tiles; ++k)
     if (bounds[k + 1] <= bounds[k] || bounds[k + 1] - bounds[k] > SNN_FWD_TILE) return hipErrorInvalidValue;
@@ -2377,7 +2533,25 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
         else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
         else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
       }
-      if (ga.count) {
+      int npt_sl = 0;
+      const int S = ga.count ? seq_slices(net, ga, ws, &npt_sl) : 1;
+      if (ga.count && S > 1) {
+        e = launch_fill_zero(ws->bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
+        if (e != hipSuccess) return e;
+        const size_t lds = seq_gather_lds(net);
+        const dim3 grid(B * S, ga.count), block(512);
+        uint64_t *xw = reinterpret_cast<uint64_t *>(ws->xg);
+#define SEQ_CASE(NPT_)                                                                                         \
+  case NPT_:                                                                                                    \
+    hipLaunchKernelGGL((k_layer_seq_gather_sl<NPT_>), grid, block, lds, s, net, ga, state, st, S, xw, ws->bar, \
+                       ws->err, ws->spin_limit);                                                                \
+    break;
+        switch (npt_sl) {
+          SEQ_CASE(1) SEQ_CASE(2) SEQ_CASE(4) SEQ_CASE(8) SEQ_CASE(16)
+          default: return hipErrorInvalidValue;
+        }
+#undef SEQ_CASE
+      } else if (ga.count) {
         const size_t lds = seq_gather_lds(net);
         const dim3 grid(B, ga.count), block(c.nt_neuron);
 #define SEQ_CASE(NPT_)                                                                               \
@@ -2551,6 +2725,14 @@ static bool adj_wide_ok(const NetDev &net, int l, const WsArgs &ws) {
 void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
   for (int l = 0; l < net.L; ++l)
     if (net.N[l] > 1024) (void)adj_wide_ok(net, l, ws);
+  for (int l = 0; l < net.L; ++l)
+    if (net.N[l] > 256) { // the sliced sequential part of the forward pass
+      SeqJobs probe{};
+      probe.j[0].l = l;
+      probe.count = 1;
+      int npt = 0;
+      (void)seq_slices(net, probe, &ws, &npt);
+    }
 }
 static hipError_t launch_adj_wide(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s) {
   int rows = 0, resident = 0;

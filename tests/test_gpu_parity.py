@@ -226,6 +226,36 @@ def test_streamed_chip_wide_adjoint(hidden, B, T, monkeypatch):
         assert float(np.max(np.abs(a - b))) <= 1e-4 * scale
 
 
+@pytest.mark.parametrize("hidden,B,T", [((2048, 2048), 3, 80), ((3072,), 3, 70), ((4096, 4096), 2, 20)])
+def test_sliced_sequential_forward_is_bitwise_neutral(hidden, B, T, monkeypatch):
+    """Layers of 2048 neurons and more whose width is a multiple of 1024: the sequential part of the forward pass spreads the neurons
+    of a batch element over several workgroups that exchange their spike words every step.  Spike trains, membrane
+    potentials and gradients must be the very bits of the one-workgroup-per-batch-element kernel, and match the
+    oracle."""
+    w = synth.Workload("sliced_" + "x".join(map(str, hidden)), 50, hidden, 6, T=T, B=B, p_in=0.1, gain=0.7, seed=41 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    got = {}
+    for slices in ("auto", "1"):
+        if slices == "1":
+            monkeypatch.setenv("SNN_SEQ_SLICES", "1")
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            states = net.snn_debug_states(w.T)
+            net.snn_bptt(snn.SNN_CHUNK, 0, 16)
+            got[slices] = (_gpu_grads(net, L), [net.snn_get_spikes(l, w.T) for l in range(L)], states)
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_SEQ_SLICES")
+    assert _identical(got["auto"][0], got["1"][0])
+    for a, b in zip(got["auto"][1], got["1"][1]):
+        assert np.array_equal(a, b)
+        assert a.sum() > 0
+    assert np.array_equal(got["auto"][2].view(np.uint32), got["1"][2].view(np.uint32))
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 16, 5)], nthreads=4)
+
+
 def test_wide_input_layer_with_stage_kernels():
     """3000 input channels in front of two 256-wide layers: the spike words and lists of the matrix-core current
     kernel still fit beside the sequential part of a forward stage, but no longer with eight wavefronts beside the
@@ -436,10 +466,11 @@ def test_gather_and_matrix_core_currents_agree(monkeypatch):
     monkeypatch.delenv("SNN_CURRENTS")
 
 
-@pytest.mark.parametrize("width", [512, 1088])
+@pytest.mark.parametrize("width", [512, 2048, 1088])
 def test_barrier_timeout_is_reported_not_hung(monkeypatch, width):
     """The chip-wide adjoint kernels of wide layers (weights in registers up to 1024 neurons, streamed
-    above) synchronise their workgroups with a counting barrier
+    above) and the sliced sequential part of their forward pass (widths from 2048 that are multiples of 1024)
+    synchronise their workgroups with a counting barrier
     that polls a bounded number of times.  With the limit forced to zero from the host every workgroup
     gives up at its first barrier: all kernels still run to completion, and snn_bptt reports the
     failure instead of returning gradients.  A context created afterwards works normally."""
