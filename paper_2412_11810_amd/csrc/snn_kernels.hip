@@ -690,7 +690,7 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
 template <int MB>
 static __device__ __forceinline__ void dense_stream(const uint64_t *words, int ws, int lane, int P,
                                                     __amdgpu_buffer_rsrc_t wres, uint32_t col4, int N, v16f (&acc)[MB]) {
-  constexpr int U = 8, D = 4;
+  constexpr int U = 4, D = 4, G = 64 / U; // G groups per 64-bit spike word
   const uint32_t n4 = (uint32_t)N * 4u;
   const int Pw = (P + 63) >> 6;
   float w[D][U];
@@ -708,14 +708,14 @@ static __device__ __forceinline__ void dense_stream(const uint64_t *words, int w
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) wr[mb] = words[(size_t)(16 * mb + (lane & 15)) * ws + kw];
 #pragma unroll
-    for (int g8 = 0; g8 < 8; ++g8) {
+    for (int g8 = 0; g8 < G; ++g8) {
       __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
-      issue(kw * 8 + g8 + D - 1, w[(g8 + D - 1) % D]);
+      issue(kw * G + g8 + D - 1, w[(g8 + D - 1) % D]);
 #pragma unroll
       for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-          const float a = (float)((uint32_t)(wr[mb] >> (8 * g8 + u)) & 1u);
+          const float a = (float)((uint32_t)(wr[mb] >> (U * g8 + u)) & 1u);
           acc[mb] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, w[g8 % D][u], acc[mb], 2, 0, 0);
         }
     }
@@ -723,7 +723,7 @@ static __device__ __forceinline__ void dense_stream(const uint64_t *words, int w
 }
 
 template <int MB>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_currents_dense(NetDev net, CurJobs jobs, int ws) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t *words = (uint64_t *)smem; // [16 MB][ws]
