@@ -319,7 +319,8 @@ def main():
         # likewise: what is left outside the fused launches is the first stage's currents, the last stage's
         # sequential parts and the readout scans
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
-    kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else "k_layer_seq_gather",
+    kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else
+                 ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather"),
                  "fwd_currents": "k_currents_dense" if model["fwd_currents"][0] == "mfma32" else "k_currents_mfma",
                  "recompute": "k_currents_dense" if model["recompute"][0] == "mfma32" else "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
