@@ -321,7 +321,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
       const size_t n_bar = (size_t)64 * SNN_MAXL + 16; // counters + error flag, padded to a multiple of 64 bytes
       // (the kernel for layers wider than 1024 pads the batch to whole blocks of 16: 1, 2 or 4 of them)
       const size_t bp = nmax > 1024 && B <= 64 ? (size_t)((B + 15) / 16 == 3 ? 4 : (B + 15) / 16) * 16 : (size_t)B;
-      const size_t xg_stride = ((size_t)2 * bp * nmax + 15) & ~(size_t)15;
+      const size_t xg_stride = ((size_t)4 * bp * nmax + 15) & ~(size_t)15; // [2][B][N] entries of 8 bytes (value + step tag)
       const size_t bytes = n_bar * sizeof(unsigned) + (size_t)SNN_MAXL * xg_stride * 4;
       void *blk = uncached_block(cfg->device, bytes);
       if (!blk) return fail(c, SNN_E_HIP, "uncached device allocation failed");

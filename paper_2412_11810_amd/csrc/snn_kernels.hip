@@ -1344,18 +1344,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_b,
               unsigned spin_limit, int blocks_per_job, int xg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_dead; // set by thread 0 when a barrier gave up
   const int jq = blockIdx.x / blocks_per_job, vb = blockIdx.x % blocks_per_job;
   const AdjJob &jb = jobs.j[jq];
   const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base, carry_init = jb.carry_init;
   float *__restrict__ vbuf = jb.vbuf;
   const float *__restrict__ up = jb.up;
-  xg += (size_t)jq * xg_stride;
-  bar += jq * 64;
+  // exchange entries: dv_t in the low half, the step count (from 1; the buffer is cleared before every launch)
+  // in the high half -- a reader polls the values it needs until they all carry the tag of the step
+  uint64_t *xq = reinterpret_cast<uint64_t *>(xg + (size_t)jq * xg_stride); // [2][B][N]
+  (void)bar;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, lk = lane >> 4;
-  if (tid == 0) s_dead = 0;
-  const int bg = vb % G_b, js = vb / G_b, n_slices = blocks_per_job / G_b;
+  const int bg = vb % G_b, js = vb / G_b;
   const int b0 = bg * 16, j0 = js * 32;
   constexpr int NP = 16 * NK;          // padded reduction length (>= N)
   float *xs = (float *)smem;           // [NP][16]  dv_{t+1}, batch-minor
@@ -1441,44 +1441,52 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
         const float ds = (sacc + upv[e]) - net.theta * dn;
         const float dvt = fmaf(ds, surrogate(net, vt[e]), net.alpha * dn);
         vbuf[slot * slot_stride + (size_t)fb[e] * SN + off + fj[e]] = dvt;
-        xg[((size_t)par * B + fb[e]) * N + fj[e]] = dvt;
+        __hip_atomic_store(&xq[((size_t)par * B + fb[e]) * N + fj[e]],
+                           ((uint64_t)(step + 1u) << 32) | (uint64_t)__float_as_uint(dvt), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
       }
-    // ---- counting barrier over the workgroups of this batch group (see k_adj_rec_ws) ----------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
-    __syncthreads();
-    if (tid == 0 && !dead) {
-      __hip_atomic_fetch_add(&bar[bg], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const unsigned target = (step + 1u) * (unsigned)n_slices;
-      unsigned spins = 0;
-      while (spin_limit == 0u || __hip_atomic_load(&bar[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-        if (++spins > spin_limit ||
-            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          s_dead = 1;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(1);
-      }
-    }
-    __syncthreads();
-    if (s_dead) dead = true; // keep going to the end of the chunk, never wait again
-    // ---- dv_t of the whole layer for this batch group -> LDS --------------------------------
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    __syncthreads(); // every thread has read its dv_{t+1} from LDS
+    // ---- dv_t of the whole layer for this batch group -> LDS ------------------------------------
+    // No barrier: the values themselves say when they have arrived.  One store and one load round trip per step
+    // instead of store, wait, atomic, poll, load.  The polling is bounded like the barrier of k_adj_rec_ws: a
+    // thread that gives up raises *err, and from then on nobody waits.
     {
       // thread -> batch element tid/16, columns (tid%16) + 16*i: all loads issued before the first use
       const int bb = tid >> 4, nb = tid & 15;
-      const float *src = xg + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N;
-      float r[NK];
-#pragma unroll
-      for (int i = 0; i < NK; ++i) { // agent-scope loads: never served from this compute unit's L1
-        const int n = nb + 16 * i;
-        r[i] = __hip_atomic_load(&src[n < N ? n : N - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint64_t *src = xq + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N;
+      const uint32_t want = step + 1u;
+      if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
+        __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        dead = true;
       }
+      constexpr int CH = NK < 32 ? NK : 32; // values polled at a time (registers)
 #pragma unroll
-      for (int i = 0; i < NK; ++i) {
-        const int n = nb + 16 * i;
-        xs[(size_t)n * 16 + bb] = __uint_as_float(__float_as_uint(r[i]) & (0u - (uint32_t)(n < N && b0 + bb < B)));
+      for (int c = 0; c < NK; c += CH) {
+        uint64_t r[CH];
+        unsigned spins = 0;
+        for (;;) {
+          uint32_t bad = 0;
+#pragma unroll
+          for (int i = 0; i < CH; ++i) { // agent-scope loads: never served from this compute unit's L1
+            const int n = nb + 16 * (c + i);
+            r[i] = __hip_atomic_load(&src[n < N ? n : N - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+#pragma unroll
+          for (int i = 0; i < CH; ++i) bad |= (uint32_t)(r[i] >> 32) ^ want;
+          if (bad == 0u || dead) break;
+          if (++spins > spin_limit / 8u ||
+              ((spins & 15u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+            __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            dead = true; // keep going to the end of the chunk, never wait again
+            break;
+          }
+          __builtin_amdgcn_s_sleep(1);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          const int n = nb + 16 * (c + i);
+          xs[(size_t)n * 16 + bb] = __uint_as_float((uint32_t)r[i] & (0u - (uint32_t)(n < N && b0 + bb < B)));
+        }
       }
     }
     __syncthreads();
@@ -2782,7 +2790,8 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
           grp.j[grp.count++] = jobs.j[k];
           taken[k] = true;
         }
-      hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
+      // tags of the exchange entries start from zero in every launch
+      hipError_t e = launch_fill_zero(ws.xg, (size_t)grp.count * ws.xg_stride * sizeof(float), s);
       if (e != hipSuccess) return e;
       e = hipFuncSetAttribute(NK == 32 ? reinterpret_cast<const void *>(k_adj_rec_wsm<32>)
                                        : reinterpret_cast<const void *>(k_adj_rec_wsm<64>),
