@@ -346,6 +346,34 @@ def main():
                 "note": "work = flops for alu/mfma kinds, bytes for hbm kinds; durations from HIP events on the compute stream",
                 "kinds": kinds}
 
+    # ---- measured peaks next to the published ones: a plain streaming copy (1 GiB read + 1 GiB written per
+    # launch, the library's copy kernel) and pinned-host copies of 64 MiB in both directions ---------------
+    def measured_peaks():
+        n = 1 << 30
+        a = torch.ones(n // 4, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        net.snn_debug_copy(a, b, n)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            net.snn_debug_copy(a, b, n)
+        hbm = 5 * 2 * n / (time.perf_counter() - t0) / 1e9
+        del a, b
+        m = 64 << 20
+        h = torch.empty(m, dtype=torch.uint8, pin_memory=True)
+        g = torch.empty(m, dtype=torch.uint8, device=dev)
+        out = {"hbm_copy_GBs": round(hbm, 1)}
+        for name, src, dst in (("h2d_pinned_GBs", h, g), ("d2h_pinned_GBs", g, h)):
+            dst.copy_(src, non_blocking=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                dst.copy_(src, non_blocking=True)
+            torch.cuda.synchronize()
+            out[name] = round(5 * m / (time.perf_counter() - t0) / 1e9, 1)
+        return out
+
+    roofline["measured_peaks"] = measured_peaks()
+
     # ---- "max trainable T" and the long-sequence comparison -----------------------------------------
     # Budget = what Standard BPTT needs for this workload's T.  Under that same budget: the largest T
     # each strategy can train (closed form from snn_bytes_required, intervals by the square-root rules
@@ -373,13 +401,23 @@ def main():
             return lo
         tmax = {"standard": t_max(snn.SNN_STANDARD, 0, 0), "chunk": t_max(snn.SNN_CHUNK, 0, 0),
                 "remote": t_max(snn.SNN_REMOTE, 0, 0), "double": t_max(snn.SNN_DOUBLE, 0, 0)}
+        # the dual the paper plots (Fig. 2, middle): HBM activation bytes against the sequence length, per
+        # strategy with the square-root intervals (closed form, no run)
+        def need_at(sid, T):
+            return snn.snn_bytes_required(snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T, w.B), sid, T, 0, 0)
+        Ts = [w.T * m for m in (1, 2, 4, 8, 16, 32)]
+        bytes_vs_T = {"T": Ts}
+        for name, sid in (("standard", snn.SNN_STANDARD), ("chunk", snn.SNN_CHUNK), ("remote", snn.SNN_REMOTE),
+                          ("double", snn.SNN_DOUBLE), ("hier", snn.SNN_HIER)):
+            bytes_vs_T[name] = [int(need_at(sid, T)) for T in Ts]
         T_long = 10 * w.T
         CL, FL = args.long_coarse, args.long_fine
         wl = synth.config(args.config, T=T_long)
         cfg_long = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T_long, w.B)
         need_long = snn.snn_bytes_required(cfg_long, snn.SNN_DOUBLE, T_long, CL, FL)
         long_seq = {"budget_bytes": ref_budget, "budget_is": f"Standard BPTT at T={w.T}", "t_max_under_budget": tmax,
-                    "double_T": T_long, "double_coarse": CL, "double_fine": FL, "double_bytes_required": need_long}
+                    "double_T": T_long, "double_coarse": CL, "double_fine": FL, "double_bytes_required": need_long,
+                    "hbm_activation_bytes_vs_T": bytes_vs_T}
         if 0 < need_long <= ref_budget:
             dl = synth.generate(wl)
             xl = torch.from_numpy(dl["in_spikes"]).to(dev)
