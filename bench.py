@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="chunk-size / remote-chunk-size study (use with --T 4096)")
     ap.add_argument("--pmc-copy", action="store_true")
+    ap.add_argument("--micro-currents", action="store_true",
+                    help="current kernels alone on teacher-forced hidden spike trains at 1 / 5 / 20 %% (use with --config, --T, --fine)")
     ap.add_argument("--model-sweep", action="store_true",
                     help="largest hidden width per strategy at fixed T and HBM budget (use with --T and --budget-mb)")
     ap.add_argument("--budget-mb", type=float, default=200.0)
@@ -216,6 +218,34 @@ def main():
         C, F = params[name]
         net.snn_bind_inputs(x, y, w.T)
         return net.snn_bptt(SID[name], C, F, budget, want_stats=stats)
+
+    if args.micro_currents:
+        # Kernel micro-benchmark at a controlled activity level: hidden spike trains drawn i.i.d. at an exact rate
+        # (decoupled from the dynamics) replace the stored ones, and the synaptic-current part of recompute runs
+        # over the whole sequence in chunks of --fine steps, with each of the three kernels.  "event_row_GBs" is the
+        # event-driven method's own traffic (one weight row of 4 N_l bytes per presynaptic spike) over the time.
+        net.snn_bind_inputs(x, y, w.T)
+        L = len(w.n_hidden)
+        chunk = args.fine if args.fine >= 1 else 10
+        in_rate = float(d["in_spikes"].mean())
+        pre_n = [w.n_in] + list(w.n_hidden[:-1])
+        rows = []
+        for rate in (0.01, 0.05, 0.2):
+            hid = [torch.from_numpy(h).to(dev) for h in synth.forced_spike_trains(w, [rate] * L)]
+            ev_bytes = w.T * w.B * sum(4.0 * w.n_hidden[l] * ((in_rate if l == 0 else rate) * pre_n[l] + rate * w.n_hidden[l])
+                                       for l in range(L))
+            dense_flops = w.T * w.B * sum(2.0 * w.n_hidden[l] * (pre_n[l] + w.n_hidden[l]) for l in range(L))
+            for mode in ("gather", "mfma", "dense"):
+                os.environ["SNN_CURRENTS"] = mode
+                ms = net.snn_debug_currents(hid, chunk, reps=2)
+                rows.append({"rate": rate, "kernel": {"gather": "k_currents", "mfma": "k_currents_mfma", "dense": "k_currents_dense"}[mode],
+                             "ms_per_pass": round(ms, 3), "event_row_GBs": round(ev_bytes / ms / 1e6, 1),
+                             "dense_TFLOPs": round(dense_flops / ms / 1e9, 2)})
+            del hid
+        os.environ.pop("SNN_CURRENTS", None)
+        print(json.dumps({"micro_currents": w.name, "T": w.T, "batch": w.B, "chunk": chunk, "input_rate": round(in_rate, 4), "rows": rows}))
+        net.snn_destroy()
+        return
 
     if args.sweep:
         # Hyper-parameter study (shape of the paper's Figs. 4-5): time per step and HBM state memory

@@ -148,6 +148,16 @@ snn_status snn_debug_states(snn_ctx *ctx, float *dst);
  * kernel, whose traffic is known (bytes read + bytes written). */
 snn_status snn_debug_copy(snn_ctx *ctx, const void *src, void *dst, size_t bytes);
 
+/* Measurement aid (the survey's kernel micro-benchmark at a controlled activity level): replaces the stored
+ * spike trains of the hidden layers by the ones given -- hidden[l]: [T][B][N_l] bytes 0/1, host or device, T the
+ * length bound by the last snn_forward / snn_bind_inputs call; a NULL entry leaves that layer's spikes as they are
+ * -- and runs the synaptic-current part of recompute (row A2 of the hot path: feed-forward and recurrent currents
+ * of every layer, no scan) over the whole sequence in chunks of `chunk` steps, `reps` times.  *ms_out: mean time
+ * of one pass over the sequence (HIP events on the library's stream).  The currents go to a scratch buffer of
+ * chunk states that the call allocates and frees; the context's spike trains stay replaced until the next
+ * snn_forward or snn_bptt.  SNN_E_STATE without bound inputs, SNN_E_INVAL for chunk or reps < 1. */
+snn_status snn_debug_currents(snn_ctx *ctx, const uint8_t *const *hidden, int32_t chunk, int32_t reps, float *ms_out);
+
 /* Activation bytes the strategy needs at least in HBM for sequence length T (no context, no GPU
  * needed).  Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes +
  * bytes_workspace of a call whose budget is exactly this number. */

@@ -25,7 +25,7 @@ OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5:
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",
            "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy",
-           "snn_suggest_intervals"]
+           "snn_suggest_intervals", "snn_debug_currents"]
 
 
 class snn_config(C.Structure):
@@ -87,6 +87,7 @@ def lib() -> C.CDLL:
         L.snn_get_readout.argtypes = [vp, vp, vp]
         L.snn_debug_states.argtypes = [vp, vp]
         L.snn_debug_copy.argtypes = [vp, vp, vp, sz]
+        L.snn_debug_currents.argtypes = [vp, C.POINTER(vp), i32, i32, C.POINTER(C.c_float)]
         L.snn_bytes_required.argtypes = [C.POINTER(snn_config), C.c_int, i32, i32, i32]
         L.snn_bytes_required.restype = sz
         L.snn_suggest_intervals.argtypes = [C.POINTER(snn_config), C.c_int, i32, sz, C.POINTER(i32), C.POINTER(i32)]
@@ -99,7 +100,7 @@ def lib() -> C.CDLL:
         L.snn_destroy.argtypes = [vp]
         L.snn_destroy.restype = None
         for name in ("snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
-                     "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy"):
+                     "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy", "snn_debug_currents"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -229,6 +230,25 @@ class Snn:
 
     def snn_debug_copy(self, src, dst, nbytes: int):
         self._check(lib().snn_debug_copy(self._h, _ptr(src), _ptr(dst), nbytes))
+
+    def snn_debug_currents(self, hidden, chunk: int, reps: int = 1) -> float:
+        """hidden: one array / tensor [T][B][N_l] of 0/1 bytes per hidden layer (None: keep the layer's spikes).
+        Returns the mean time in ms of one pass of the current kernels over the bound sequence."""
+        L = self.cfg.n_layers
+        arr = (C.c_void_p * L)()
+        keep = []
+        for l in range(L):
+            h = hidden[l] if l < len(hidden) else None
+            if h is None:
+                arr[l] = None
+                continue
+            if isinstance(h, np.ndarray):
+                h = np.ascontiguousarray(h, dtype=np.uint8)
+            keep.append(h)
+            arr[l] = _ptr(h)
+        ms = C.c_float(0.0)
+        self._check(lib().snn_debug_currents(self._h, arr, chunk, reps, C.byref(ms)))
+        return float(ms.value)
 
     def snn_destroy(self):
         if self._h:

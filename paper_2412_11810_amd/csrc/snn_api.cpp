@@ -534,6 +534,58 @@ snn_status snn_debug_copy(snn_ctx *c, const void *src, void *dst, size_t bytes) 
   return SNN_OK;
 }
 
+snn_status snn_debug_currents(snn_ctx *c, const uint8_t *const *hidden, int32_t chunk, int32_t reps, float *ms_out) {
+  if (!c || !hidden || !ms_out) return fail(c, SNN_E_INVAL, "null argument");
+  if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
+  if (chunk < 1 || reps < 1) return fail(c, SNN_E_INVAL, "chunk and reps must be positive");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  const NetDev &n = c->net;
+  const int T = c->T_bound, B = n.B;
+  hipStream_t s = c->stream;
+  if (c->own_stream) HIPCHK(c, hipStreamSynchronize(nullptr));
+  for (int l = 0; l < n.L; ++l) {
+    if (!hidden[l]) continue;
+    const size_t bytes = (size_t)T * B * n.N[l];
+    const uint8_t *src = hidden[l];
+    uint8_t *tmp = nullptr;
+    if (!is_device_ptr(src)) {
+      HIPCHK(c, hipMalloc(&tmp, bytes));
+      hipError_t e = hipMemcpyAsync(tmp, src, bytes, hipMemcpyHostToDevice, s);
+      if (e != hipSuccess) { (void)hipFree(tmp); return fail(c, SNN_E_HIP, hipGetErrorString(e)); }
+      src = tmp;
+    }
+    hipError_t e = launch_pack_inputs(src, n.mask[l + 1], T, B, n.N[l], n.Wd[l + 1], s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (tmp) (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  }
+  if (chunk > T) chunk = T;
+  float *buf = nullptr;
+  const size_t slot = (size_t)B * n.SN;
+  HIPCHK(c, hipMalloc(&buf, (size_t)chunk * slot * sizeof(float)));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  auto pass = [&]() {
+    for (int t0 = 0; t0 < T && e == hipSuccess; t0 += chunk)
+      e = launch_recompute_currents(n, t0, std::min(t0 + chunk, T), buf, t0, slot, s);
+  };
+  if (e == hipSuccess) pass(); // warm-up
+  if (e == hipSuccess) e = hipEventRecord(e0, s);
+  for (int r = 0; r < reps && e == hipSuccess; ++r) pass();
+  if (e == hipSuccess) e = hipEventRecord(e1, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipStreamSynchronize(s);
+  (void)hipFree(buf);
+  if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  *ms_out = ms / (float)reps;
+  return SNN_OK;
+}
+
 snn_status snn_grads(snn_ctx *c, int kind, int layer, float *dst, size_t n_elems) {
   if (!c || !dst) return fail(c, SNN_E_INVAL, "null argument");
   const NetDev &n = c->net;

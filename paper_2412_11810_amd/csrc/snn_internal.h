@@ -90,6 +90,9 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
 // turns them into states in place (store_all) and/or writes x_{t1} to state_out.
 hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                             size_t slot_stride, int store_all, float *state_out, hipStream_t s);
+// Part 1 of a recompute pass alone: the currents of steps t0+1..t1 of every layer into buf.
+hipError_t launch_recompute_currents(const NetDev &net, int t0, int t1, float *buf, int t_base, size_t slot_stride,
+                                     hipStream_t s);
 // Part 2 of a recompute pass alone: buf already holds the currents of steps t0+1..t1.
 hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                                  size_t slot_stride, int store_all, float *state_out, hipStream_t s);

@@ -2618,6 +2618,14 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
   return hipGetLastError();
 }
 
+hipError_t launch_recompute_currents(const NetDev &net, int t0, int t1, float *buf, int t_base, size_t slot_stride,
+                                     hipStream_t s) {
+  if (t1 <= t0) return hipErrorInvalidValue;
+  CurJobs cj{};
+  for (int l = 0; l < net.L; ++l) cj.j[cj.count++] = CurJob{0, l, t0, t1 - t0, t_base, buf, slot_stride};
+  return launch_currents(net, cj, s);
+}
+
 hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
                                  size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
   if (t1 <= t0) return hipErrorInvalidValue;

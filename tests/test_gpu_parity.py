@@ -256,6 +256,30 @@ def test_sliced_sequential_forward_is_bitwise_neutral(hidden, B, T, monkeypatch)
     _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 16, 5)], nthreads=4)
 
 
+def test_current_kernels_on_forced_spike_trains(monkeypatch):
+    """snn_debug_currents (the micro-benchmark entry): hidden spike trains at an exact rate replace the stored ones
+    and every current kernel runs over them; a training step afterwards is unaffected (the forward pass rewrites
+    the spike trains)."""
+    w = synth.Workload("forced_60-300-280-5", 60, (300, 280), 5, T=40, B=6, p_in=0.1, gain=0.6, seed=23)
+    d = synth.generate(w)
+    hid = synth.forced_spike_trains(w, [0.1, 0.1])
+    net = snn.from_workload(w, d)
+    try:
+        with pytest.raises(snn.SnnError):
+            net.snn_debug_currents(hid, 8)  # nothing bound yet
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        for mode in ("gather", "mfma", "dense"):
+            monkeypatch.setenv("SNN_CURRENTS", mode)
+            assert net.snn_debug_currents(hid, 8, reps=2) > 0.0
+        monkeypatch.delenv("SNN_CURRENTS")
+        assert net.snn_debug_currents([None, hid[1]], 100) > 0.0
+        with pytest.raises(snn.SnnError):
+            net.snn_debug_currents(hid, 0)
+    finally:
+        net.snn_destroy()
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 7)], nthreads=2)
+
+
 def test_wide_input_layer_with_stage_kernels():
     """3000 input channels in front of two 256-wide layers: the spike words and lists of the matrix-core current
     kernel still fit beside the sequential part of a forward stage, but no longer with eight wavefronts beside the
