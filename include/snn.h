@@ -148,7 +148,7 @@ snn_status snn_debug_states(snn_ctx *ctx, float *dst);
  * kernel, whose traffic is known (bytes read + bytes written). */
 snn_status snn_debug_copy(snn_ctx *ctx, const void *src, void *dst, size_t bytes);
 
-/* Measurement aid (the survey's kernel micro-benchmark at a controlled activity level): replaces the stored
+/* Measurement aid (kernel micro-benchmark at a controlled activity level): replaces the stored
  * spike trains of the hidden layers by the ones given -- hidden[l]: [T][B][N_l] bytes 0/1, host or device, T the
  * length bound by the last snn_forward / snn_bind_inputs call; a NULL entry leaves that layer's spikes as they are
  * -- and runs the synaptic-current part of recompute (row A2 of the hot path: feed-forward and recurrent currents
