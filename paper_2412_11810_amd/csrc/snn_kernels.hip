@@ -136,6 +136,67 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
   }
 }
 
+// The same expansion for the sequential kernels of wide layers: entry = byte offset of the weight row (index * n4),
+// so that a row load needs no address arithmetic beyond one add, and four entries past the end that point at row 0
+// (a wavefront reads entries four at a time).
+static __device__ __forceinline__ void expand_offsets(const uint64_t *words, int Wd, uint32_t *offs, int *cnt, int tid,
+                                                      int nt, uint32_t n4) {
+  for (int widx = tid >> 6; widx < Wd; widx += nt >> 6) {
+    const uint64_t word = words[widx];
+    int pre = 0;
+    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
+    if ((word >> lane_id()) & 1ull) offs[pre + __popcll(word & lanemask_lt())] = (uint32_t)(widx * WAVE + lane_id()) * n4;
+    if (widx == Wd - 1) {
+      const int total = pre + __popcll(word);
+      if (lane_id() == 0) *cnt = total;
+      if (lane_id() < 4) offs[total + lane_id()] = 0u;
+    }
+  }
+}
+
+// Sum of the weight rows offs[0..cnt) (ascending, from 0.0f) for the NPT columns of this thread (byte offsets
+// coff[k] inside a row).  Entries come from LDS four at a time (every lane the same address), the row segment
+// through a buffer load with a per-lane offset: per row one add, one load per owned neuron and one add per owned
+// neuron -- nothing passes through scalar registers.  U rows are in flight before their adds; only the last
+// group of four needs a select for the entries past the end.
+template <int NPT>
+static __device__ __forceinline__ void gather1(__amdgpu_buffer_rsrc_t wres, const uint32_t (&coff)[NPT],
+                                               const uint32_t *offs, int cnt_in, float (&acc)[NPT]) {
+  constexpr int U = NPT >= 16 ? 4 : (64 / NPT > 32 ? 32 : 64 / NPT); // multiple of 4
+  const int cnt = __builtin_amdgcn_readfirstlane(cnt_in);
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) acc[k] = 0.0f;
+  for (int q = 0; q < cnt; q += U) {
+    float w[U][NPT];
+#pragma unroll
+    for (int r0 = 0; r0 < U; r0 += 4) {
+      if (q + r0 >= cnt) continue; // uniform
+      const uint4 e = *reinterpret_cast<const uint4 *>(offs + q + r0);
+      const uint32_t ev[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < NPT; ++k)
+          w[r0 + i][k] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, ev[i] + coff[k], 0, 0));
+    }
+#pragma unroll
+    for (int r0 = 0; r0 < U; r0 += 4) {
+      if (q + r0 >= cnt) continue; // uniform
+      if (q + r0 + 4 <= cnt) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + w[r0 + i][k];
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + (q + r0 + i < cnt ? w[r0 + i][k] : 0.0f);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Forward pass.  The time axis is cut into tiles; inside a tile the layers run one after the other:
 //   1. k_currents (mode 1): feed-forward currents I_in^l of every step of the tile, in parallel -- they
@@ -252,9 +313,15 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x, lane = lane_id();
   uint64_t *words = (uint64_t *)smem;       // [Wd]
   int *cnt = (int *)(words + Wd);           // [1] (+3 pad)
-  uint16_t *list = (uint16_t *)(cnt + 4);   // [N]
+  uint32_t *offs = (uint32_t *)(cnt + 4);   // [N + 4] byte offsets of the active rows
   uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
   const size_t mstride = (size_t)B * Wd;
+  const uint32_t n4 = (uint32_t)N * 4u;
+  const __amdgpu_buffer_rsrc_t wres =
+      __builtin_amdgcn_make_buffer_rsrc((void *)net.W_rec[l], 0, (int)((size_t)N * N * sizeof(float)), 0x00027000);
+  uint32_t coff[NPT];
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) coff[k] = (uint32_t)(tid + k * nt < N ? tid + k * nt : 0) * 4u;
   float v[NPT];
   uint32_t sp = 0;
 #pragma unroll
@@ -269,7 +336,7 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   }
   if (tid == 0) *cnt = 0;
   __syncthreads();
-  expand_all(words, Wd, list, cnt, tid, nt);
+  expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
   __syncthreads();
   const size_t istride = (size_t)B * N;
   for (int t = t0 + 1; t <= t1; ++t) {
@@ -285,8 +352,8 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
       const int n = tid + k * nt;
       in_t[k] = n < N ? irow[n] : 0.0f;
     }
-    float unused[NPT], a_rec[NPT];
-    gather2<NPT>(net.W_rec[l], N, 0u, tid, nt, list, 0, list, *cnt, unused, a_rec);
+    float a_rec[NPT];
+    gather1<NPT>(wres, coff, offs, *cnt, a_rec);
     uint32_t spn = 0;
 #pragma unroll
     for (int k = 0; k < NPT; ++k) {
@@ -308,7 +375,7 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
     }
     sp = spn;
     __syncthreads(); // every wave is done with the old list
-    expand_all(words, Wd, list, cnt, tid, nt);
+    expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
     __syncthreads();
   }
 #pragma unroll
@@ -340,11 +407,18 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   const int Ns = N / S, c0 = sl * Ns, w0 = c0 >> 6; // own columns and their first word
   uint64_t *words = (uint64_t *)smem;       // [Wd]  whole layer
   int *cnt = (int *)(words + Wd);           // [1] (+3 pad)
-  uint16_t *list = (uint16_t *)(cnt + 4);   // [N]
+  uint32_t *offs = (uint32_t *)(cnt + 4);   // [N + 4] byte offsets of the active rows
   uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
   const size_t mstride = (size_t)B * Wd;
   uint64_t *xb = xw + (size_t)(jq * B + b) * 2 * Wd; // [2][Wd]
   unsigned *mybar = bar + jq * B + b;
+  const uint32_t n4 = (uint32_t)N * 4u;
+  // descriptor over the whole matrix, shifted to this slice's first column
+  const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)(net.W_rec[l] + c0), 0, (int)(((size_t)N * N - c0) * sizeof(float)), 0x00027000);
+  uint32_t coff[NPT];
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) coff[k] = (uint32_t)(tid + k * nt) * 4u;
   if (tid == 0) { s_dead = 0; *cnt = 0; }
   for (int i = tid; i < Wd; i += nt) words[i] = mbase[(size_t)t0 * mstride + i];
   __syncthreads();
@@ -356,7 +430,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
     v[k] = state[(size_t)b * SN + off + n];
     if ((words[n >> 6] >> lane) & 1ull) sp |= 1u << k;
   }
-  expand_all(words, Wd, list, cnt, tid, nt);
+  expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
   __syncthreads();
   const size_t istride = (size_t)B * N;
   unsigned step = 0;
@@ -371,8 +445,8 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
     float in_t[NPT];
 #pragma unroll
     for (int k = 0; k < NPT; ++k) in_t[k] = irow[tid + k * nt];
-    float unused[NPT], a_rec[NPT];
-    gather2<NPT>(net.W_rec[l] + c0, N, 0u, tid, nt, list, 0, list, *cnt, unused, a_rec);
+    float a_rec[NPT];
+    gather1<NPT>(wres, coff, offs, *cnt, a_rec);
     uint64_t *xdst = xb + (size_t)(t & 1) * Wd;
     uint32_t spn = 0;
 #pragma unroll
@@ -415,7 +489,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
     for (int i = tid; i < Wd; i += nt) words[i] = __hip_atomic_load(&xdst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (tid == 0) *cnt = 0;
     __syncthreads();
-    expand_all(words, Wd, list, cnt, tid, nt);
+    expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
     __syncthreads();
   }
 #pragma unroll
@@ -2180,7 +2254,7 @@ static size_t adjoint_lds(const NetDev &net, int nt) {
 static size_t seq_gather_lds(const NetDev &net) {
   size_t mx = 0;
   for (int l = 0; l < net.L; ++l) {
-    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)((net.N[l] + 7) & ~7) * 2;
+    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)(((net.N[l] + 7) & ~7) + 8) * 4; // words, count, row offsets
     mx = b > mx ? b : mx;
   }
   return mx;
