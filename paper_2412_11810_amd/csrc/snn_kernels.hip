@@ -385,19 +385,21 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   }
 }
 
-// The same sequential part with the neurons of a layer spread over S workgroups per batch element (wide layers:
-// one workgroup per batch element leaves most of the chip idle and is bound by what one compute unit can load).
-// Workgroup (b, sl) owns the columns [sl N/S, (sl+1) N/S) -- whole 64-bit spike words -- and gathers its part of
-// the active rows of W_rec; sums per neuron are the same ascending sums.  After the threshold it writes its
-// spike words to the stored bitmask and to an exchange buffer (uncached device memory, double-buffered by the
-// parity of t), the S workgroups of the batch element meet at a counting barrier (bounded spin, error flag: see
-// k_adj_rec_ws), and each reads the whole layer's words back and expands them into its own copy of the index list.
+// The same sequential part with the neurons of a layer spread over S workgroups per batch element (one workgroup
+// per batch element leaves most of the chip idle and is bound by what one compute unit can load: every active
+// weight row passes through its L1).  Workgroup (b, sl) owns the columns [sl N/S, (sl+1) N/S) -- whole 64-bit spike
+// words -- and gathers its part of the active rows of W_rec; sums per neuron are the same ascending sums.  After
+// the threshold it writes its spike words to the stored bitmask and, as two 8-byte entries per word (32 spike bits
+// in the low half, the step count of this launch in the high half), to an exchange buffer in uncached device
+// memory that is cleared before every launch and double-buffered by the parity of the step.  There is no barrier:
+// every workgroup polls the entries of the whole layer until all carry the tag of the step (bounded number of
+// polls; a thread that gives up raises *err and from then on nobody waits), then expands them into its own copy of
+// the list of active rows.
 template <int NPT>
 __global__ void __launch_bounds__(512)
 k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw,
-                      unsigned *bar, unsigned *err, unsigned spin_limit) {
+                      unsigned *err, unsigned spin_limit) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_dead;
   const int jq = blockIdx.y;
   const int l = jobs.j[jq].l, t0 = jobs.j[jq].t0, t1 = jobs.j[jq].t1, t_tile = jobs.j[jq].t_tile;
   const float *__restrict__ iin = jobs.j[jq].iin;
@@ -410,8 +412,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   uint32_t *offs = (uint32_t *)(cnt + 4);   // [N + 4] byte offsets of the active rows
   uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
   const size_t mstride = (size_t)B * Wd;
-  uint64_t *xb = xw + (size_t)(jq * B + b) * 2 * Wd; // [2][Wd]
-  unsigned *mybar = bar + jq * B + b;
+  uint64_t *xb = xw + (size_t)(jq * B + b) * 4 * Wd; // [2][2 Wd] tagged half-words
   const uint32_t n4 = (uint32_t)N * 4u;
   // descriptor over the whole matrix, shifted to this slice's first column
   const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
@@ -419,7 +420,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   uint32_t coff[NPT];
 #pragma unroll
   for (int k = 0; k < NPT; ++k) coff[k] = (uint32_t)(tid + k * nt) * 4u;
-  if (tid == 0) { s_dead = 0; *cnt = 0; }
+  if (tid == 0) *cnt = 0;
   for (int i = tid; i < Wd; i += nt) words[i] = mbase[(size_t)t0 * mstride + i];
   __syncthreads();
   float v[NPT];
@@ -433,6 +434,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
   __syncthreads();
   const size_t istride = (size_t)B * N;
+  uint32_t *words32 = reinterpret_cast<uint32_t *>(words);
   unsigned step = 0;
   bool dead = false;
   for (int t = t0 + 1; t <= t1; ++t, ++step) {
@@ -447,7 +449,8 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
     for (int k = 0; k < NPT; ++k) in_t[k] = irow[tid + k * nt];
     float a_rec[NPT];
     gather1<NPT>(wres, coff, offs, *cnt, a_rec);
-    uint64_t *xdst = xb + (size_t)(t & 1) * Wd;
+    uint64_t *xdst = xb + (size_t)(step & 1u) * 2 * Wd;
+    const uint64_t tag = (uint64_t)(step + 1u) << 32;
     uint32_t spn = 0;
 #pragma unroll
     for (int k = 0; k < NPT; ++k) {
@@ -459,36 +462,34 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
       const uint64_t word = __ballot(vn > net.theta);
       if ((word >> lane) & 1ull) spn |= 1u << k;
       if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + nl] = vn;
-      if (lane == 0) {
-        mbase[(size_t)t * mstride + widx] = word;
-        xdst[widx] = word;
-      }
+      if (lane == 0) mbase[(size_t)t * mstride + widx] = word;
+      if (lane < 2)
+        __hip_atomic_store(&xdst[2 * widx + lane], tag | (uint64_t)(uint32_t)(word >> (32 * lane)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
     }
     sp = spn;
-    // ---- the S workgroups of this batch element meet ------------------------------------------------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): the own words are in memory
-    __syncthreads();                    // (and every wave is done with the old list)
-    if (tid == 0 && !dead) {
-      __hip_atomic_fetch_add(mybar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const unsigned target = (step + 1u) * (unsigned)S;
+    // ---- the whole layer's spike words of this step, from all S workgroups of the batch element ------------
+    if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
+      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      dead = true;
+    }
+    for (int i = tid; i < 2 * Wd; i += nt) {
+      uint64_t e;
       unsigned spins = 0;
-      while (spin_limit == 0u || __hip_atomic_load(mybar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      for (;;) {
+        e = __hip_atomic_load(&xdst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(e >> 32) == step + 1u || dead) break;
         if (++spins > spin_limit ||
             ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
           __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          s_dead = 1;
+          dead = true; // keep going to the end of the tile, never wait again
           break;
         }
         __builtin_amdgcn_s_sleep(1);
       }
+      words32[i] = (uint32_t)e;
     }
-    __syncthreads();
-    if (s_dead) dead = true; // keep going to the end of the tile, never wait again
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    for (int i = tid; i < Wd; i += nt) words[i] = __hip_atomic_load(&xdst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid == 0) *cnt = 0;
-    __syncthreads();
+    __syncthreads(); // (every wave was done with the old list before the previous barrier)
     expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
     __syncthreads();
   }
@@ -2473,53 +2474,64 @@ static hipError_t launch_fwd_stage(const NetDev &net, const SeqJobs &sj, float *
 // stage does is independent of everything else in it, so a stage is one launch (k_fwd_stage) when all
 // layers are register-stationary, and otherwise one launch per kernel flavour.  The current tiles are
 // double-buffered by tile parity.
-// Slices per batch element for the sequential part of wide layers (1: one workgroup per batch element).  All
-// workgroups of a launch must be resident at once (they wait for each other), every wide layer may have a job in
-// the same launch, a slice is a whole number of 512-thread rounds, and the counters and the exchange buffer of
-// the chip-wide kernels must hold one entry per (job, batch element).  SNN_SEQ_SLICES=1 turns slicing off.
 static size_t seq_gather_lds(const NetDev &net);
 template <int NPT>
-static int seq_sl_resident(int device, size_t lds) {
-  static int cached[16] = {};
-  if (device < 0 || device >= 16) return 0;
-  if (!cached[device]) {
+static int seq_sl_resident(int device, size_t lds, int threads) {
+  static int cached[16][9] = {}; // per device and block size / 64
+  if (device < 0 || device >= 16 || threads < 64 || threads > 512) return 0;
+  int &c = cached[device][threads / 64];
+  if (!c) {
     hipDeviceProp_t prop;
     int per_cu = 0;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_layer_seq_gather_sl<NPT>, 512, lds) != hipSuccess) return 0;
-    cached[device] = per_cu * prop.multiProcessorCount;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_layer_seq_gather_sl<NPT>, threads, lds) != hipSuccess) return 0;
+    c = per_cu * prop.multiProcessorCount;
   }
-  return cached[device];
+  return c;
 }
-static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, int *npt) {
-  if (!ws || !ws->xg || !ws->bar || ga.count < 1) return 1;
-  if (const char *e = getenv("SNN_SEQ_SLICES"))
-    if (strcmp(e, "1") == 0) return 1;
+// Slices per batch element for the sequential part of layers wider than 256 neurons (1: one workgroup per batch
+// element).  All workgroups of a launch must be resident at once (they wait for each other), every wide layer may
+// have a job in the same launch, a slice is whole spike words and a whole number of rounds of its block, and the
+// exchange buffer of the chip-wide kernels must hold the entries of every (job, batch element).  Used from 2048
+// neurons (a single compute unit's L1 then bounds the step).  SNN_SEQ_SLICES=1 turns it off, =2, 4, 8 asks for
+// that many at any width.
+static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, int *npt, int *threads) {
+  if (!ws || !ws->xg || ga.count < 1) return 1;
+  int forced = 0;
+  if (const char *e = getenv("SNN_SEQ_SLICES")) forced = atoi(e);
+  if (forced == 1) return 1;
   const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
-  if (N < 2048) return 1; // narrower: the weights sit in the L2 and a workgroup per batch element is faster (measured at 1024)
   int n_wide = 0;
   for (int l = 0; l < net.L; ++l) n_wide += net.N[l] > 256;
   for (int i = 0; i < ga.count; ++i)
     if (net.N[ga.j[i].l] != N) return 1;
-  if (net.B * n_wide > 64 * SNN_MAXL) return 1;
-  if ((size_t)n_wide * net.B * 2 * Wd * sizeof(uint64_t) > (size_t)ws->xg_stride * SNN_MAXL * sizeof(float)) return 1;
+  // narrower layers: measured slower with slices at 512 and 1024 neurons (a wavefront walks every active row whatever
+  // the number of columns its workgroup owns, and that walk, not the compute unit's L1, is what takes the time)
+  if (!forced && N < 2048) return 1;
+  if ((size_t)n_wide * net.B * 4 * Wd * sizeof(uint64_t) > (size_t)ws->xg_stride * SNN_MAXL * sizeof(float)) return 1;
   int device = 0;
   if (hipGetDevice(&device) != hipSuccess) return 1;
   const size_t lds = seq_gather_lds(net);
   for (int S = 8; S >= 2; S /= 2) {
-    if (N % (512 * S) != 0) continue;
-    const int p = N / (512 * S);
+    if (forced && S != forced) continue;
+    if (N % (64 * S) != 0) continue;
+    const int Ns = N / S;
+    int p = 1;
+    while (Ns / p > 512) p *= 2;
+    if (p > 16 || Ns % (64 * p) != 0) continue;
+    const int th = Ns / p;
     int resident = 0;
     switch (p) {
-      case 1: resident = seq_sl_resident<1>(device, lds); break;
-      case 2: resident = seq_sl_resident<2>(device, lds); break;
-      case 4: resident = seq_sl_resident<4>(device, lds); break;
-      case 8: resident = seq_sl_resident<8>(device, lds); break;
-      case 16: resident = seq_sl_resident<16>(device, lds); break;
+      case 1: resident = seq_sl_resident<1>(device, lds, th); break;
+      case 2: resident = seq_sl_resident<2>(device, lds, th); break;
+      case 4: resident = seq_sl_resident<4>(device, lds, th); break;
+      case 8: resident = seq_sl_resident<8>(device, lds, th); break;
+      case 16: resident = seq_sl_resident<16>(device, lds, th); break;
       default: continue;
     }
     if (S * net.B * n_wide > resident) continue;
     *npt = p;
+    *threads = th;
     return S;
   }
   return 1;
@@ -2615,17 +2627,18 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
         else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
         else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
       }
-      int npt_sl = 0;
-      const int S = ga.count ? seq_slices(net, ga, ws, &npt_sl) : 1;
+      int npt_sl = 0, th_sl = 0;
+      const int S = ga.count ? seq_slices(net, ga, ws, &npt_sl, &th_sl) : 1;
       if (ga.count && S > 1) {
-        e = launch_fill_zero(ws->bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
+        // tags of the exchange entries start from zero in every launch
+        e = launch_fill_zero(ws->xg, (size_t)ga.count * B * 4 * net.Wd[ga.j[0].l + 1] * sizeof(uint64_t), s);
         if (e != hipSuccess) return e;
         const size_t lds = seq_gather_lds(net);
-        const dim3 grid(B * S, ga.count), block(512);
+        const dim3 grid(B * S, ga.count), block(th_sl);
         uint64_t *xw = reinterpret_cast<uint64_t *>(ws->xg);
 #define SEQ_CASE(NPT_)                                                                                         \
   case NPT_:                                                                                                    \
-    hipLaunchKernelGGL((k_layer_seq_gather_sl<NPT_>), grid, block, lds, s, net, ga, state, st, S, xw, ws->bar, \
+    hipLaunchKernelGGL((k_layer_seq_gather_sl<NPT_>), grid, block, lds, s, net, ga, state, st, S, xw,          \
                        ws->err, ws->spin_limit);                                                                \
     break;
         switch (npt_sl) {
@@ -2820,8 +2833,8 @@ void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
       SeqJobs probe{};
       probe.j[0].l = l;
       probe.count = 1;
-      int npt = 0;
-      (void)seq_slices(net, probe, &ws, &npt);
+      int npt = 0, th = 0;
+      (void)seq_slices(net, probe, &ws, &npt, &th);
     }
 }
 static hipError_t launch_adj_wide(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s) {

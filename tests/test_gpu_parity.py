@@ -226,9 +226,11 @@ def test_streamed_chip_wide_adjoint(hidden, B, T, monkeypatch):
         assert float(np.max(np.abs(a - b))) <= 1e-4 * scale
 
 
-@pytest.mark.parametrize("hidden,B,T", [((2048, 2048), 3, 80), ((3072,), 3, 70), ((4096, 4096), 2, 20)])
-def test_sliced_sequential_forward_is_bitwise_neutral(hidden, B, T, monkeypatch):
-    """Layers of 2048 neurons and more whose width is a multiple of 1024: the sequential part of the forward pass spreads the neurons
+@pytest.mark.parametrize("hidden,B,T,force", [((2048, 2048), 3, 80, "0"), ((3072,), 3, 70, "0"), ((4096, 4096), 2, 20, "0"),
+                                              ((512, 512), 5, 150, "8"), ((384,), 4, 100, "2")])
+def test_sliced_sequential_forward_is_bitwise_neutral(hidden, B, T, force, monkeypatch):
+    """Layers of 2048 neurons and more (narrower ones when SNN_SEQ_SLICES asks for it: 64-thread and 192-thread
+    workgroups): the sequential part of the forward pass spreads the neurons
     of a batch element over several workgroups that exchange their spike words every step.  Spike trains, membrane
     potentials and gradients must be the very bits of the one-workgroup-per-batch-element kernel, and match the
     oracle."""
@@ -237,8 +239,7 @@ def test_sliced_sequential_forward_is_bitwise_neutral(hidden, B, T, monkeypatch)
     L = len(hidden)
     got = {}
     for slices in ("auto", "1"):
-        if slices == "1":
-            monkeypatch.setenv("SNN_SEQ_SLICES", "1")
+        monkeypatch.setenv("SNN_SEQ_SLICES", "1" if slices == "1" else force)
         net = snn.from_workload(w, d)
         try:
             net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
