@@ -162,16 +162,44 @@ static __device__ __forceinline__ void expand_offsets(const uint64_t *words, int
 template <int NPT>
 static __device__ __forceinline__ void gather1(__amdgpu_buffer_rsrc_t wres, const uint32_t (&coff)[NPT],
                                                const uint32_t *offs, int cnt_in, float (&acc)[NPT]) {
-  constexpr int U = NPT >= 16 ? 4 : (64 / NPT > 32 ? 32 : 64 / NPT); // multiple of 4
+  // rows per chunk, a multiple of 4: 64 loads in flight (128 measured slower on the widest layers)
+  constexpr int U = NPT >= 16 ? 4 : (64 / NPT > 32 ? 32 : 64 / NPT);
+  constexpr int G = U / 4;
   const int cnt = __builtin_amdgcn_readfirstlane(cnt_in);
 #pragma unroll
   for (int k = 0; k < NPT; ++k) acc[k] = 0.0f;
-  for (int q = 0; q < cnt; q += U) {
+  const uint4 *offs4 = reinterpret_cast<const uint4 *>(offs);
+  int q = 0;
+  // whole chunks: straight-line code -- all entries of the chunk in one batch of LDS reads (one wait, not one per
+  // four rows), all loads issued, and the adds start when the first row arrives while the rest is still in flight
+  // (the number of loads after it is known at compile time).  (A second register set that keeps the next chunk's
+  // loads in flight during the adds was measured: no gain at one and two neurons per thread, a loss from four.)
+  for (; q + U <= cnt; q += U) {
+    uint4 e[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) e[g] = offs4[(q >> 2) + g];
+    float w[U][NPT];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const uint32_t ev[4] = {e[g].x, e[g].y, e[g].z, e[g].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < NPT; ++k)
+          w[4 * g + i][k] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, ev[i] + coff[k], 0, 0));
+    }
+#pragma unroll
+    for (int r = 0; r < U; ++r)
+#pragma unroll
+      for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + w[r][k];
+  }
+  // the last, partial chunk: groups of four behind uniform guards, a select for the entries past the end
+  if (q < cnt) {
     float w[U][NPT];
 #pragma unroll
     for (int r0 = 0; r0 < U; r0 += 4) {
       if (q + r0 >= cnt) continue; // uniform
-      const uint4 e = *reinterpret_cast<const uint4 *>(offs + q + r0);
+      const uint4 e = offs4[(q + r0) >> 2];
       const uint32_t ev[4] = {e.x, e.y, e.z, e.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -182,17 +210,10 @@ static __device__ __forceinline__ void gather1(__amdgpu_buffer_rsrc_t wres, cons
 #pragma unroll
     for (int r0 = 0; r0 < U; r0 += 4) {
       if (q + r0 >= cnt) continue; // uniform
-      if (q + r0 + 4 <= cnt) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + w[r0 + i][k];
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + (q + r0 + i < cnt ? w[r0 + i][k] : 0.0f);
-      }
+        for (int k = 0; k < NPT; ++k) acc[k] = acc[k] + (q + r0 + i < cnt ? w[r0 + i][k] : 0.0f);
     }
   }
 }
