@@ -229,6 +229,31 @@ static __device__ __forceinline__ void gather1(__amdgpu_buffer_rsrc_t wres, cons
 // definition, so spike trains match a plain sequential implementation bit for bit.
 // ------------------------------------------------------------------------------------------
 
+// Which steps of a tile store their state (StoreSpec), without a division per step: remainder and quotient of
+// (t - t_base) by the interval are carried from step to step.
+struct StoreCursor {
+  int rem, quo;
+  bool on;
+  __device__ __forceinline__ void init(const StoreSpec &st, int t_first) {
+    on = st.base != nullptr;
+    rem = quo = 0;
+    if (on) {
+      const int d = t_first - st.t_base;
+      quo = d / st.interval;
+      rem = d - quo * st.interval;
+    }
+  }
+  __device__ __forceinline__ int slot(const StoreSpec &st, int t) const { // -1: step t stores nothing
+    if (!on || rem != 0 || t > st.t_max) return -1;
+    int sl = quo - 1 + st.slot0;
+    if (st.slot_mod > 0) sl %= st.slot_mod;
+    return sl;
+  }
+  __device__ __forceinline__ void next(const StoreSpec &st) {
+    if (on && ++rem == st.interval) { rem = 0; ++quo; }
+  }
+};
+
 // Sequential part, layers of up to NW neurons: the recurrent matrix stays in registers (thread i keeps
 // column i, W_rec[0..NW)[i]).  The previous step's spike words are shared through LDS; each lane turns
 // bits into 0.0f/1.0f (lane L of register g: spike 16g + L%16), a DPP row broadcast feeds spike j to
@@ -275,6 +300,8 @@ __device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJo
   // from the staged ones, would wait for every outstanding load before each block of FMAs)
   __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
   if (own && t1 > t0) stage_issue(t0);
+  StoreCursor sc;
+  sc.init(st, t0 + 1);
   for (int tg = t0; tg < t1; tg += G) {
     if (own) {
 #pragma unroll
@@ -285,10 +312,12 @@ __device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJo
     for (int t = tg + 1; t <= thi; ++t) {
       const float in_t = own ? ring[t - tg - 1][i] : 0.0f;
       // lane L of sb[g] holds spike 16g + L%16 of the previous step as 0.0f / 1.0f
+      // (one bit-field extract from the 32-bit half that holds the 16 spikes, one convert)
       float sb[NW / 16];
+      const uint32_t *sw32 = reinterpret_cast<const uint32_t *>(sw[cur]);
 #pragma unroll
       for (int g = 0; g < NW / 16; ++g)
-        sb[g] = ((sw[cur][g >> 2] >> (16 * (g & 3) + (lane & 15))) & 1ull) ? 1.0f : 0.0f;
+        sb[g] = (float)__builtin_amdgcn_ubfe(sw32[g >> 1], (uint32_t)(16 * (g & 1) + (lane & 15)), 1u);
       float acc = 0.0f;
 #pragma unroll
       for (int g = 0; g < NW / 16; ++g) FMAC16_1(acc, sb[g], w, 16 * g);
@@ -301,11 +330,9 @@ __device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJo
         sw[cur ^ 1][wave] = word;
         if (wave < Wd) mrow[(size_t)t * mstride] = word;
       }
-      if (own && st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
-        int sl = (t - st.t_base) / st.interval - 1 + st.slot0;
-        if (st.slot_mod > 0) sl %= st.slot_mod;
-        st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
-      }
+      const int sl = sc.slot(st, t);
+      if (own && sl >= 0) st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
+      sc.next(st);
       __syncthreads();
       cur ^= 1;
     }
@@ -360,12 +387,11 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   expand_offsets(words, Wd, offs, cnt, tid, nt, n4);
   __syncthreads();
   const size_t istride = (size_t)B * N;
+  StoreCursor sc;
+  sc.init(st, t0 + 1);
   for (int t = t0 + 1; t <= t1; ++t) {
-    int store_slot = -1;
-    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
-      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
-      if (st.slot_mod > 0) store_slot %= st.slot_mod;
-    }
+    const int store_slot = sc.slot(st, t);
+    sc.next(st);
     const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N;
     float in_t[NPT];
 #pragma unroll
@@ -458,12 +484,11 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   uint32_t *words32 = reinterpret_cast<uint32_t *>(words);
   unsigned step = 0;
   bool dead = false;
+  StoreCursor sc;
+  sc.init(st, t0 + 1);
   for (int t = t0 + 1; t <= t1; ++t, ++step) {
-    int store_slot = -1;
-    if (st.base && t <= st.t_max && (t - st.t_base) % st.interval == 0) {
-      store_slot = (t - st.t_base) / st.interval - 1 + st.slot0;
-      if (st.slot_mod > 0) store_slot %= st.slot_mod;
-    }
+    const int store_slot = sc.slot(st, t);
+    sc.next(st);
     const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N + c0;
     float in_t[NPT];
 #pragma unroll
