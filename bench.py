@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--long-warmup", type=int, default=2)
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="chunk-size / remote-chunk-size study (use with --T 4096)")
+    ap.add_argument("--host-inputs", action="store_true",
+                    help="hand the input spikes over as host arrays every step (PCIe-inclusive rate; not the headline value)")
     ap.add_argument("--pmc-copy", action="store_true")
     ap.add_argument("--micro-currents", action="store_true",
                     help="current kernels alone on teacher-forced hidden spike trains at 1 / 5 / 20 %% (use with --config, --T, --fine)")
@@ -207,6 +209,8 @@ def main():
     d = synth.generate(w)
     x = torch.from_numpy(d["in_spikes"]).to(dev)
     y = torch.from_numpy(d["labels"]).to(dev)
+    if args.host_inputs:  # the library copies them to the device inside snn_bind_inputs, every step
+        x, y = d["in_spikes"], d["labels"]
     net = snn.from_workload(w, d)  # stream = None: the library runs on a stream of its own
     params = dict(STRATEGY_PARAMS[args.config])
     if args.coarse >= 0 or args.fine >= 0:
@@ -508,7 +512,7 @@ def main():
         "metric": "BPTT neuron-timesteps/sec (fwd+bwd) at fixed HBM budget", "value": round(nts / sec, 1),
         "unit": "neuron-timesteps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic" if not args.host_inputs else "synthetic, inputs handed over from host memory every step",
         "config": {"workload": w.name, "T": w.T, "batch": w.B, "strategy": args.strategy, "coarse_interval": C,
                    "fine_interval": F, "hbm_budget_bytes": budget,
                    "hbm_activation_bytes": int(st.bytes_states + st.bytes_spikes + st.bytes_workspace),
