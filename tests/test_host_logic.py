@@ -130,3 +130,29 @@ def test_suggested_intervals_fit_the_budget_and_grow_with_it():
     assert snn.snn_suggest_intervals(cfg, snn.SNN_STANDARD, T, 0) == (0, 0)
     with pytest.raises(snn.SnnError):
         snn.snn_suggest_intervals(cfg, snn.SNN_STANDARD, T, 1 << 20)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: asking for more exits with a message, before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+
+
+def test_synthetic_inputs_are_seeded_and_shaped():
+    """The shared input generator: same seed, same arrays; shapes and rates as the workload says; the forced spike
+    trains of the micro-benchmark hit their rate."""
+    import synth
+    w = synth.config(1, T=40, B=4)
+    a, b = synth.generate(w), synth.generate(w)
+    assert np.array_equal(a["in_spikes"], b["in_spikes"]) and np.array_equal(a["W_rec"][1], b["W_rec"][1])
+    assert a["in_spikes"].shape == (40, 4, 700) and a["in_spikes"].dtype == np.uint8
+    assert a["W_in"][0].shape == (700, 256) and a["W_out"].shape == (256, 20) and a["labels"].shape == (4,)
+    assert abs(float(a["in_spikes"].mean()) - w.p_in) < 0.005
+    m = synth.generate(synth.Workload("masked", 10, (64, 64), 3, T=5, B=2, p_in=0.1, rec_density=0.25, seed=5))
+    assert m["rec_mask"] is not None and abs(float(m["rec_mask"][0].mean()) - 0.25) < 0.05
+    assert np.all(m["W_rec"][0][m["rec_mask"][0] == 0] == 0.0)
+    h = synth.forced_spike_trains(synth.config(1, T=200, B=8), [0.05, 0.2])
+    assert h[0].shape == (200, 8, 256) and abs(float(h[0].mean()) - 0.05) < 0.005 and abs(float(h[1].mean()) - 0.2) < 0.01
