@@ -772,9 +772,22 @@ struct BwdPipe {
     } else {
       if (have_pre) return fail(c, SNN_E_STATE, "internal: recompute work attached to an unfused stage");
       HIPCHK(c, launch_adjoint_jobs(n, jobs, c->carry, c->ws, s, hk));
-      // what each finished layer feeds: the product for the layer below
+      // what each finished layer feeds: the product for the layer below.  The products of a stage are independent
+      // of each other: one launch for all of them (two 160-workgroup products of configuration 2 fill the chip
+      // together, not one after the other)
+      InterJobs ij{};
       for (const BwdTile &t : inflight)
-        if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
+        if (t.layer > 0) {
+          const int l = t.layer;
+          ij.g[ij.n_gemm++] = GemmJob{t.vbuf + (size_t)(t.t0 - t.base) * B * n.SN + n.off[l], n.SN, n.W_in[l], n.N[l],
+                                      n.N[l - 1], up[l - 1], (t.t1 - t.t0) * B, 0, 0, 0};
+        }
+      if (ij.n_gemm == 1) {
+        for (const BwdTile &t : inflight)
+          if (t.layer > 0) HIPCHK(c, launch_up_product(n, t.layer - 1, t.t0, t.t1, t.base, t.vbuf, up[t.layer - 1], s, hk));
+      } else if (ij.n_gemm > 1) {
+        HIPCHK(c, launch_bwd_inter(n, ij, s, hk));
+      }
     }
     for (const BwdTile &t : inflight) done.push_back(t);
     for (BwdTile &t : inflight) --t.layer;
