@@ -58,9 +58,9 @@ typedef enum { SNN_W_IN = 0, SNN_W_REC = 1, SNN_W_OUT = 2 } snn_tensor_kind;
 #define SNN_MAX_LAYERS 4
 
 typedef struct {
-  int32_t n_in;                     /* input channels                                  */
+  int32_t n_in;                     /* input channels (<= 4096)                        */
   int32_t n_layers;                 /* 1..SNN_MAX_LAYERS recurrent LIF layers          */
-  int32_t n_hidden[SNN_MAX_LAYERS]; /* neurons per layer (each <= 65535)               */
+  int32_t n_hidden[SNN_MAX_LAYERS]; /* neurons per layer (each <= 8192)                */
   int32_t n_out;                    /* leaky non-spiking readouts (<= 1024)            */
   int32_t T;                        /* maximum sequence length this context will see   */
   int32_t batch;
@@ -76,7 +76,10 @@ typedef struct {
                                        recorded into a HIP graph)                        */
 } snn_config;
 
-/* Filled by snn_bptt (all times in milliseconds, measured with HIP events on the
+/* Statistics of one training step: the quantities the paper's Results report (time per batch, peak local memory;
+ * Fig. 2) plus the terms of its closed forms -- state slots (eq. M_Base, M_Standard, M_Remote, M_Hier, M_Double),
+ * recompute steps (T_refwd in eq. T_Standard, T_Double) and host transfers (N_c, T_c in eq. T_Remote, T_Double).
+ * Filled by snn_bptt (all times in milliseconds, measured with HIP events on the
  * context's stream; bytes are what the call actually allocated/moved). */
 typedef struct {
   float ms_total, ms_forward, ms_backward_total; /* whole step; forward incl. loss; everything after */
@@ -101,22 +104,30 @@ typedef struct {
 } snn_stats;
 
 /* Create a context: validates the configuration, allocates weights, gradients and the
- * spike store for cfg->T steps on cfg->device.  No state storage is allocated here. */
+ * spike store for cfg->T steps on cfg->device (the paper's M_others, Section "Standard Checkpointing": weights and
+ * the sparse spike trains of the whole sequence, which no strategy recomputes).  No state storage is allocated
+ * here.  *out is set even on failure (so that snn_last_error can be read) and must be passed to snn_destroy.
+ * SNN_E_INVAL for a shape outside the limits noted in snn_config. */
 snn_status snn_init(const snn_config *cfg, snn_ctx **out);
 
-/* Copy one weight matrix into the context.  w: [pre][post] row-major fp32 (row = presynaptic
+/* Copy one weight matrix into the context (weights are part of M_others, Section "Standard Checkpointing").
+ * w: [pre][post] row-major fp32 (row = presynaptic
  * neuron), host or device.  kind SNN_W_IN/SNN_W_REC take layer 0..L-1, SNN_W_OUT ignores it.
  * mask_or_null (SNN_W_REC only): [N][N] bytes, 1 = synapse exists; masked weights must already
  * be zero in w; the gradient of a masked matrix is zero where the mask is zero. */
 snn_status snn_set_weights(snn_ctx *ctx, int kind, int layer, const float *w, const uint8_t *mask_or_null);
 
-/* Forward pass only (event-driven recurrence, readout, loss); binds the inputs that a following
+/* Forward pass only (the two operations of the paper's forward step, Section "Standard Checkpointing": the
+ * sparse matrix product that accumulates the weight rows of active presynaptic neurons, and spike generation into
+ * a sparse representation; then readout and loss); binds the inputs that a following
  * snn_bptt uses.  in_spikes: [T][B][n_in] bytes 0/1, host or device; T <= cfg.T.  labels: [B]
- * int32, host or device.  loss_out: one float, host.  Stores spikes (bitmasks) but no states. */
+ * int32, host or device, each in [0, n_out) (SNN_E_INVAL otherwise, checked on the host before anything is
+ * queued).  loss_out: one float, host.  Stores spikes (bitmasks) but no states. */
 snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out);
 
 /* One full training step (forward with the strategy's storage plan, loss, backward with
- * recomputation) on the inputs bound by the last snn_forward/snn_bind_inputs.  Gradients stay in
+ * recomputation: the execution orders of Fig. 1, one panel per strategy; Sections "Standard Checkpointing",
+ * "Remote Checkpointing", "Hierarchical Checkpointing", "Double Checkpointing") on the inputs bound by the last snn_forward/snn_bind_inputs.  Gradients stay in
  * the context (overwritten by each call) until snn_grads copies them out.
  *   STANDARD ignores both intervals; CHUNK uses fine_interval; REMOTE uses coarse_interval;
  *   DOUBLE needs 1 <= fine <= coarse <= T; HIER takes fine_interval = steps between checkpoints and
@@ -131,16 +142,28 @@ snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *la
 snn_status snn_bptt(snn_ctx *ctx, snn_strategy strategy, int32_t coarse_interval, int32_t fine_interval,
                     size_t hbm_budget_bytes, snn_stats *stats_or_null);
 
-/* Bind inputs without running anything (same arguments as snn_forward). */
+/* Bind inputs without running anything (same arguments and checks as snn_forward). */
 snn_status snn_bind_inputs(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T);
 
-/* Copy a gradient tensor out.  dst: [pre][post] fp32, host or device, n_elems must match. */
+/* Copy a gradient tensor out: the plain-BPTT gradient, which every strategy reproduces exactly (Section
+ * "Standard Checkpointing": checkpointing trades memory for recomputation, not accuracy).  dst: [pre][post] fp32,
+ * host or device, n_elems must match (SNN_E_INVAL otherwise). */
 snn_status snn_grads(snn_ctx *ctx, int kind, int layer, float *dst, size_t n_elems);
 
-/* Parity/debug accessors (valid after snn_forward or snn_bptt). */
+/* Parity/debug accessors (valid after snn_forward or snn_bptt; SNN_E_STATE before).  The spike trains are the
+ * sparse spike tensor that stays in local memory for the whole sequence (Section "Standard Checkpointing",
+ * Discussion). */
 snn_status snn_get_spikes(snn_ctx *ctx, int layer /*0..L-1*/, uint8_t *dst /*[T][B][N_l] bytes, host*/);
 snn_status snn_get_readout(snn_ctx *ctx, float *ubar /*[B][n_out], host*/, float *loss /*1 float, host*/);
-/* Runs a forward pass that stores every state and copies them out: dst [T][B][sum N_l] fp32, host. */
+/* Membrane potentials v^l_t of one layer at one step, t in 1..T: dst [B][N_l] fp32, host or device.  The state is
+ * rebuilt the way a recompute pass rebuilds it (Section "Standard Checkpointing": from a checkpoint -- here x_0 --
+ * through the stored spike trains, no spike generation), so it is available after a forward pass or a training
+ * step of any strategy and equals, bit for bit, what the forward pass held at step t.  Costs a recompute pass over
+ * steps 1..t and allocates (and frees) a buffer of min(t, 64) + 2 states.  SNN_E_STATE before a forward pass,
+ * SNN_E_INVAL for a layer or step out of range. */
+snn_status snn_get_state(snn_ctx *ctx, int layer, int32_t t, float *dst);
+/* Runs a forward pass that stores every state (the storage plan of plain BPTT, eq. M_Base) and copies the
+ * trajectory out: dst [T][B][sum N_l] fp32, host. */
 snn_status snn_debug_states(snn_ctx *ctx, float *dst);
 
 /* Measurement aid: one plain streaming copy kernel of `bytes` bytes (a multiple of 16), device to
@@ -159,7 +182,9 @@ snn_status snn_debug_copy(snn_ctx *ctx, const void *src, void *dst, size_t bytes
 snn_status snn_debug_currents(snn_ctx *ctx, const uint8_t *const *hidden, int32_t chunk, int32_t reps, float *ms_out);
 
 /* Activation bytes the strategy needs at least in HBM for sequence length T (no context, no GPU
- * needed).  Returns 0 for invalid arguments.  Equals stats.bytes_states + bytes_spikes +
+ * needed): M_s times the state count of eq. M_Base / M_Standard / M_Remote / M_Hier / M_Double plus the staging
+ * slots of the host tier, plus the spike bitmasks and the per-chunk workspace.  Returns 0 for invalid arguments
+ * and for shapes snn_init refuses.  Equals stats.bytes_states + bytes_spikes +
  * bytes_workspace of a call whose budget is exactly this number. */
 size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t T, int32_t coarse_interval,
                           int32_t fine_interval);
@@ -167,7 +192,7 @@ size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t 
  * staging slots of the host tier) and, in *remote_slots (may be NULL), on the host. */
 int32_t snn_state_slots(snn_strategy strategy, int32_t T, int32_t coarse_interval, int32_t fine_interval,
                         int32_t *remote_slots);
-/* Writes the schedule of the plan as int32 triples (op, a, b), at most cap triples, and returns
+/* The execution order of Fig. 1 for a plan.  Writes the schedule of the plan as int32 triples (op, a, b), at most cap triples, and returns
  * the number of triples the full schedule has.  Ops: 1 SAVE_LOCAL c, 2 SAVE_REMOTE c, 3 LOAD_REMOTE c,
  * 4 REFWD1 (a,b], 5 KEEP_FINE c, 6 REFWD2 (a,b], 7 BACKWARD a..b (descending), 8 SAVE_BATCH (first
  * checkpoint c, count), 9 LOAD_BATCH (first checkpoint c, count). */
@@ -187,6 +212,28 @@ snn_status snn_suggest_intervals(const snn_config *cfg, snn_strategy strategy, i
 
 const char *snn_last_error(const snn_ctx *ctx); /* never NULL; "" if none */
 void snn_destroy(snn_ctx *ctx);
+
+/*
+ * Test hooks.  The library chooses its kernels from the layer shapes, the batch size, the state size and the
+ * firing rates of the previous step; every choice gives the same bits.  The parity tests force each flavour
+ * through environment variables, read by the library at the points noted.  They are not part of the interface
+ * proper: a caller never needs them.
+ *   read by snn_init (fixed for the context's life):
+ *     SNN_HOST_TIER=dma|direct   Remote/Double checkpoints by hipMemcpyAsync / written and read by the kernels
+ *                                through the mapped pinned block (default: direct up to 1 MiB per state)
+ *     SNN_DW=event               event-by-event weight-gradient kernel instead of the matrix-core contraction
+ *     SNN_GRAPH=0                no HIP-graph replay of the training step
+ *     SNN_BWD_PIPE=0, SNN_BWD_FUSE=0, SNN_PRE_IN_STAGE=0
+ *                                adjoint pass layer by layer / weight gradients in launches of their own /
+ *                                recompute of later chunks between, not inside, the stage launches
+ *     SNN_NO_WS=1                no chip-wide kernels (no exchange buffer is allocated)
+ *     SNN_WS_SPIN_LIMIT=n        polls before a chip-wide kernel gives up waiting (0: at once; the error path)
+ *   read at the start of every call that launches kernels:
+ *     SNN_CURRENTS=gather|mfma|dense   kernel of the synaptic currents
+ *     SNN_WS_KERNEL=valu|stream        VALU version of the chip-wide adjoint recurrence / one workgroup per
+ *                                      batch element streaming the transposed matrix
+ *     SNN_SEQ_SLICES=1|2|4|8           workgroups per batch element in the sequential part of wide layers
+ */
 
 #ifdef __cplusplus
 }

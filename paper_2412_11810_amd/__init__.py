@@ -25,7 +25,7 @@ OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5:
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",
            "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy",
-           "snn_suggest_intervals", "snn_debug_currents"]
+           "snn_suggest_intervals", "snn_debug_currents", "snn_get_state"]
 
 
 class snn_config(C.Structure):
@@ -86,6 +86,7 @@ def lib() -> C.CDLL:
         L.snn_get_spikes.argtypes = [vp, C.c_int, vp]
         L.snn_get_readout.argtypes = [vp, vp, vp]
         L.snn_debug_states.argtypes = [vp, vp]
+        L.snn_get_state.argtypes = [vp, C.c_int, i32, vp]
         L.snn_debug_copy.argtypes = [vp, vp, vp, sz]
         L.snn_debug_currents.argtypes = [vp, C.POINTER(vp), i32, i32, C.POINTER(C.c_float)]
         L.snn_bytes_required.argtypes = [C.POINTER(snn_config), C.c_int, i32, i32, i32]
@@ -100,7 +101,8 @@ def lib() -> C.CDLL:
         L.snn_destroy.argtypes = [vp]
         L.snn_destroy.restype = None
         for name in ("snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
-                     "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy", "snn_debug_currents"):
+                     "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy", "snn_debug_currents",
+                     "snn_get_state"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -183,11 +185,20 @@ class Snn:
             mask = np.ascontiguousarray(mask, dtype=np.uint8)
         self._check(lib().snn_set_weights(self._h, kind, layer, _ptr(w), _ptr(mask)))
 
+    @staticmethod
+    def _check_inputs(in_spikes, labels):
+        """The C ABI takes raw pointers: the element types must already be right (uint8 spikes, int32 labels)."""
+        for name, a, want in (("in_spikes", in_spikes, "uint8"), ("labels", labels, "int32")):
+            if str(a.dtype).replace("torch.", "") != want:
+                raise TypeError(f"{name} must be {want}, got {a.dtype}")
+
     def snn_bind_inputs(self, in_spikes, labels, T: int):
+        self._check_inputs(in_spikes, labels)
         self._check(lib().snn_bind_inputs(self._h, _ptr(in_spikes), _ptr(labels), T))
 
     def snn_forward(self, in_spikes, labels, T: int) -> float:
         loss = C.c_float(0)
+        self._check_inputs(in_spikes, labels)
         self._check(lib().snn_forward(self._h, _ptr(in_spikes), _ptr(labels), T, C.byref(loss)))
         return float(loss.value)
 
@@ -221,6 +232,11 @@ class Snn:
         loss = C.c_float(0)
         self._check(lib().snn_get_readout(self._h, ubar.ctypes.data, C.addressof(loss)))
         return ubar, float(loss.value)
+
+    def snn_get_state(self, layer: int, t: int) -> np.ndarray:
+        out = np.empty((self.cfg.batch, self.cfg.n_hidden[layer]), dtype=np.float32)
+        self._check(lib().snn_get_state(self._h, layer, t, out.ctypes.data))
+        return out
 
     def snn_debug_states(self, T: int) -> np.ndarray:
         sn = sum(self.cfg.n_hidden[i] for i in range(self.cfg.n_layers))

@@ -32,6 +32,7 @@ struct snn_ctx {
   size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
   int32_t *labels = nullptr;
   int T_bound = 0;
+  int T_spikes = 0; // length of the sequence whose hidden spike trains are stored (0: none since the inputs were bound)
   double *readout = nullptr;
   WsArgs ws{};                // chip-wide recurrent kernel: exchange buffer, barrier counters, error flag
   float *cur_state = nullptr; // [B][SN] state carried through the forward pass
@@ -45,7 +46,7 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
-  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol; } };
+  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; unsigned sel; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol && sel == o.sel; } };
   GraphKeyT graph_key{};
   hipGraphExec_t graph_exec = nullptr;
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
@@ -126,6 +127,21 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
+// Test hooks that force a kernel flavour (documented in snn.h): read from the environment at the start of every
+// call that launches kernels, so that a test can switch them between two calls on one context.
+void read_kernel_hooks(snn_ctx *c) {
+  NetDev &n = c->net;
+  n.sel_currents = n.sel_adjoint = n.sel_slices = 0;
+  if (const char *e = std::getenv("SNN_CURRENTS"))
+    n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
+  if (const char *e = std::getenv("SNN_WS_KERNEL"))
+    n.sel_adjoint = !std::strcmp(e, "valu") ? 1 : !std::strcmp(e, "stream") ? 2 : 0;
+  if (const char *e = std::getenv("SNN_SEQ_SLICES")) {
+    const int v = std::atoi(e);
+    n.sel_slices = (v == 1 || v == 2 || v == 4 || v == 8) ? (unsigned char)v : 0;
+  }
+}
+
 // per-tile scratch of the adjoint pass: readout adjoints 3 x [tile][B][O] (three tiles alive) + one inter-layer product per layer
 // [tile][B][N_l] (the layers run one tile apart, so every layer's product is alive at once); the forward pass
 // uses the same scratch for the currents of one time tile
@@ -177,6 +193,8 @@ size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t 
   if (!snn_make_plan((int)strategy, T, C, F, &p)) return 0;
   NetDev n{};
   fill_shape(*cfg, &n);
+  char why_shape[160];
+  if (!snn_kernel_shape_ok(n, why_shape, sizeof why_shape)) return 0; // a shape snn_init refuses
   const size_t Ms = (size_t)n.B * n.SN * sizeof(float);
   return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work_bytes(n, p.chunk_len);
 }
@@ -257,6 +275,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (const char *e = std::getenv("SNN_BWD_PIPE")) c->bwd_pipeline = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_PRE_IN_STAGE")) c->pre_in_stage = std::strcmp(e, "0") != 0;
+  read_kernel_hooks(c);
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
   int ndev = 0;
@@ -386,6 +405,12 @@ snn_status snn_set_weights(snn_ctx *c, int kind, int layer, const float *w, cons
     return fail(c, SNN_E_INVAL, "bad tensor kind/layer");
   }
   if (mask && kind != SNN_W_REC) return fail(c, SNN_E_INVAL, "mask only for recurrent matrices");
+  // a recorded step holds the mask pointers of its gradient epilogue: record again after any change of weights
+  if (c->graph_exec) {
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    (void)hipGraphExecDestroy(c->graph_exec);
+    c->graph_exec = nullptr;
+  }
   const size_t ne = (size_t)rows * cols;
   HIPCHK(c, hipMemcpyAsync(dst, w, ne * 4, hipMemcpyDefault, c->stream));
   HIPCHK(c, launch_transpose(dst, dstT, rows, cols, c->stream));
@@ -411,6 +436,17 @@ snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *
   // does not synchronise with implicitly
   if (c->own_stream) HIPCHK(c, hipStreamSynchronize(nullptr));
   const NetDev &n = c->net;
+  {
+    // the loss kernel indexes the readout with the label: range-check the B labels on the host first
+    std::vector<int32_t> lab((size_t)n.B);
+    HIPCHK(c, hipMemcpy(lab.data(), labels, (size_t)n.B * 4, hipMemcpyDefault));
+    for (int b = 0; b < n.B; ++b)
+      if (lab[b] < 0 || lab[b] >= n.n_out) {
+        char msg[96];
+        snprintf(msg, sizeof msg, "label %d of batch element %d is outside [0, %d)", (int)lab[b], b, n.n_out);
+        return fail(c, SNN_E_INVAL, msg);
+      }
+  }
   const size_t bytes = (size_t)T * n.B * n.n_in;
   const uint8_t *src = in_spikes;
   uint8_t *tmp = nullptr;
@@ -425,8 +461,8 @@ snn_status snn_bind_inputs(snn_ctx *c, const uint8_t *in_spikes, const int32_t *
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (tmp) (void)hipFree(tmp);
   if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
-  // labels are validated on the host side of the binding; clamp nothing here
   c->T_bound = T;
+  c->T_spikes = 0;
   return SNN_OK;
 }
 
@@ -455,6 +491,7 @@ static snn_status ensure_work(snn_ctx *c, size_t bytes) {
 }
 
 static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
+  read_kernel_hooks(c);
   const NetDev &n = c->net;
   StoreSpec st{};
   if (traj_or_null) {
@@ -467,6 +504,7 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
   std::vector<int> bounds = tile_bounds(0, c->T_bound, c->T_bound);
   HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, c->dubuf, c->stream, nullptr, nullptr, &c->ws));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
+  c->T_spikes = c->T_bound;
   return SNN_OK;
 }
 
@@ -496,6 +534,32 @@ snn_status snn_debug_states(snn_ctx *c, float *dst) {
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   (void)hipFree(traj);
   if (s != SNN_OK) return s;
+  if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
+  return SNN_OK;
+}
+
+snn_status snn_get_state(snn_ctx *c, int layer, int32_t t, float *dst) {
+  if (!c || !dst || layer < 0 || layer >= c->net.L) return fail(c, SNN_E_INVAL, "bad argument");
+  if (c->T_spikes < 1) return fail(c, SNN_E_STATE, "no forward pass since the inputs were bound");
+  if (t < 1 || t > c->T_spikes) return fail(c, SNN_E_INVAL, "t outside 1..T");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  read_kernel_hooks(c);
+  const NetDev &n = c->net;
+  // what a recompute pass does: from x_0 = 0 through the stored spike trains, a chunk of currents at a time
+  const int chunk = std::min<int>(t, SNN_FWD_TILE);
+  const size_t slot = (size_t)n.B * n.SN;
+  float *buf = nullptr;
+  HIPCHK(c, hipMalloc(&buf, ((size_t)chunk + 2) * slot * sizeof(float)));
+  float *st[2] = {buf + (size_t)chunk * slot, buf + ((size_t)chunk + 1) * slot};
+  hipError_t e = launch_fill_zero(st[0], slot * sizeof(float), c->stream);
+  int cur = 0;
+  for (int a = 0; a < t && e == hipSuccess; a += chunk, cur ^= 1)
+    e = launch_recompute(n, a, std::min(a + chunk, (int)t), st[cur], buf, a, slot, 0, st[cur ^ 1], c->stream);
+  if (e == hipSuccess)
+    e = hipMemcpy2DAsync(dst, (size_t)n.N[layer] * 4, st[cur] + n.off[layer], (size_t)n.SN * 4, (size_t)n.N[layer] * 4,
+                         (size_t)n.B, hipMemcpyDefault, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  (void)hipFree(buf);
   if (e != hipSuccess) return fail(c, SNN_E_HIP, hipGetErrorString(e));
   return SNN_OK;
 }
@@ -539,6 +603,7 @@ snn_status snn_debug_currents(snn_ctx *c, const uint8_t *const *hidden, int32_t 
   if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
   if (chunk < 1 || reps < 1) return fail(c, SNN_E_INVAL, "chunk and reps must be positive");
   HIPCHK(c, hipSetDevice(c->cfg.device));
+  read_kernel_hooks(c);
   const NetDev &n = c->net;
   const int T = c->T_bound, B = n.B;
   hipStream_t s = c->stream;
@@ -1221,6 +1286,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   const int T = c->T_bound;
   Plan p;
   if (!snn_make_plan((int)strategy, T, C_in, F_in, &p)) return fail(c, SNN_E_INVAL, "invalid strategy/intervals");
+  read_kernel_hooks(c);
   NetDev &n = c->net;
   const int L = n.L;
   const size_t Ms = c->Ms();
@@ -1285,7 +1351,8 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   if (use_graph) {
     unsigned long long pol = 0;
     for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
-    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol};
+    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16;
+    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
       Timer tm{c, false};
@@ -1307,6 +1374,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       if (rr != SNN_OK) return rr;
     }
     HIPCHK(c, hipStreamSynchronize(s));
+    c->T_spikes = T;
     return check_ws_error(c);
   }
 
@@ -1341,6 +1409,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     }
     *stats = st;
   }
+  c->T_spikes = T;
   return check_ws_error(c);
 }
 

@@ -30,6 +30,11 @@ struct NetDev {
   // (0: not known yet -> dense, 1: event-by-event gather, 2: dense matrix-core version); [0] forward currents
   // (feed-forward part only), [1] recompute (both parts).  Every choice gives the same bits.
   unsigned char cur_pol[2][SNN_MAXL];
+  // Kernel selection forced from outside (test hooks; 0 = the library's own choice).  Every choice gives the same
+  // bits.  sel_currents: 1 event-by-event gather, 2 list version on the matrix cores, 3 dense version.
+  // sel_adjoint: 1 VALU version of the chip-wide recurrence, 2 one-workgroup-per-batch-element streaming kernel.
+  // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
+  unsigned char sel_currents, sel_adjoint, sel_slices;
 };
 
 // Where the forward / recompute kernel writes states it has to keep.

@@ -997,30 +997,37 @@ k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *bu
 __global__ void __launch_bounds__(256) k_loss(const double *__restrict__ readout, const int32_t *__restrict__ labels,
                                               int B, int O, int T, float *__restrict__ ubar, float *__restrict__ g,
                                               float *__restrict__ loss) {
-  extern __shared__ float lossb[]; // [B]
+  // The readout state is fp64, and so is everything here: with a confident (saturated) softmax the gradient
+  // softmax - onehot of the labelled class is a difference of nearly equal numbers.  It is formed as minus the
+  // sum of the other classes' probabilities, which has no cancellation, and rounded to fp32 once.
+  extern __shared__ double lossb[]; // [B]
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
     const double *us = readout + ((size_t)b * 2 + 1) * O;
     float *ub = ubar + (size_t)b * O;
-    float m = -INFINITY;
+    double m = -INFINITY;
     for (int o = 0; o < O; ++o) {
-      const float x = (float)(us[o] / (double)T);
-      ub[o] = x;
-      m = fmaxf(m, x);
+      const double x = us[o] / (double)T;
+      ub[o] = (float)x;
+      m = fmax(m, x);
     }
-    float z = 0.0f;
-    for (int o = 0; o < O; ++o) z = z + expf(ub[o] - m);
+    double z = 0.0;
+    for (int o = 0; o < O; ++o) z = z + exp(us[o] / (double)T - m);
     const int y = labels[b];
-    lossb[b] = (m + logf(z)) - ub[y];
+    lossb[b] = (m + log(z)) - us[y] / (double)T;
+    double others = 0.0;
+    for (int o = 0; o < O; ++o)
+      if (o != y) others = others + exp(us[o] / (double)T - m) / z;
+    const double scale = (double)B * (double)T;
     for (int o = 0; o < O; ++o) {
-      const float p = expf(ub[o] - m) / z;
-      g[(size_t)b * O + o] = (p - (o == y ? 1.0f : 0.0f)) / ((float)B * (float)T);
+      const double p = exp(us[o] / (double)T - m) / z;
+      g[(size_t)b * O + o] = (float)((o == y ? -others : p) / scale);
     }
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    float s = 0.0f;
+    double s = 0.0;
     for (int b = 0; b < B; ++b) s = s + lossb[b];
-    *loss = s / (float)B;
+    *loss = (float)(s / (double)B);
   }
 }
 
@@ -2343,11 +2350,9 @@ static void launch_currents_t(const NetDev &net, dim3 grid, int nt, size_t lds, 
   hipLaunchKernelGGL((k_currents<NPT>), grid, dim3(nt), lds, s, net, jobs);
 }
 // SNN_CURRENTS=gather selects the event-by-event gather kernel for every current (the default runs
-// the feed-forward and recurrent currents on the matrix cores and only the narrow readout as a gather).
-static bool currents_use_mfma() { // read at every launch: a test switches it between two contexts
-  const char *e = getenv("SNN_CURRENTS");
-  return !(e && strcmp(e, "gather") == 0);
-}
+// the feed-forward and recurrent currents on the matrix cores and only the narrow readout as a gather); the
+// context turns it into net.sel_currents.
+static bool currents_use_mfma(const NetDev &net) { return net.sel_currents != 1; }
 static hipError_t launch_currents_gather(const NetDev &net, const CurJobs &jobs, hipStream_t s);
 static void currents_geometry(const NetDev &net, const CurJobs &jobs, unsigned *gx, int *ws, int *lcap, int nwv);
 static size_t currents_lds(int nwv, int ws, int lcap) {
@@ -2374,9 +2379,8 @@ static int currents_job_kernel(const NetDev &net, const CurJob &j) {
   currents_job_shape(net, j, &p, &wb);
   const bool dense_ok = wb < ((size_t)1 << 32) &&                                               // one buffer descriptor
                         (size_t)16 * SNN_DENSE_MB * (((p + 63) >> 6) | 1) * 8 + 1024 <= SNN_LDS_PER_CU; // words of 64 rows
-  const char *e = getenv("SNN_CURRENTS");
-  if (e && strcmp(e, "dense") == 0) return dense_ok ? 1 : 0;
-  if (e && strcmp(e, "mfma") == 0) return 0;
+  if (net.sel_currents == 3) return dense_ok ? 1 : 0;
+  if (net.sel_currents == 2) return 0;
   if (wb < ((size_t)32 << 20) || j.mode == 2) return 0;
   const int pol = net.cur_pol[j.mode == 0 ? 1 : 0][j.lsel];
   if (pol == 1) return 2;
@@ -2406,7 +2410,7 @@ static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, 
   return hipGetLastError();
 }
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
-  if (!currents_use_mfma()) return launch_currents_gather(net, jobs, s);
+  if (!currents_use_mfma(net)) return launch_currents_gather(net, jobs, s);
   CurJobs mf{}, dn{}, ga{};
   for (int i = 0; i < jobs.count; ++i)
     if (jobs.j[i].nsteps > 0) {
@@ -2543,8 +2547,7 @@ static int seq_sl_resident(int device, size_t lds, int threads) {
 // that many at any width.
 static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, int *npt, int *threads) {
   if (!ws || !ws->xg || ga.count < 1) return 1;
-  int forced = 0;
-  if (const char *e = getenv("SNN_SEQ_SLICES")) forced = atoi(e);
+  const int forced = net.sel_slices;
   if (forced == 1) return 1;
   const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
   int n_wide = 0;
@@ -2600,7 +2603,7 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   const LaunchCfg c = forward_cfg(net);
   int nmax = 0;
   for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
-  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma() && fwd_stage_fits(net);
+  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma(net) && fwd_stage_fits(net);
   int ro_steps = 0, ro_tiles = 0;
   bool ro_first = true;
   RoJob ro_pending{};
@@ -2770,7 +2773,7 @@ hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float 
 
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar, float *g,
                        float *loss, hipStream_t s) {
-  hipLaunchKernelGGL(k_loss, dim3(1), dim3(256), (size_t)B * sizeof(float), s, readout, labels, B, O, T, ubar, g, loss);
+  hipLaunchKernelGGL(k_loss, dim3(1), dim3(256), (size_t)B * sizeof(double), s, readout, labels, B, O, T, ubar, g, loss);
   return hipGetLastError();
 }
 
@@ -2811,7 +2814,7 @@ hipError_t launch_up_product(const NetDev &net, int l, int t0, int t1, int t_bas
   return e;
 }
 
-static bool ws_use_mfma();
+static bool ws_use_mfma(const NetDev &net);
 
 // Chip-wide recurrence of a wide layer: geometry and launch.
 template <int RB, int NBB>
@@ -2856,8 +2859,7 @@ static hipError_t adj_wide_dispatch(const NetDev &net, const AdjJob &jb, float *
 // SNN_WS_KERNEL=stream keeps wide layers on the one-workgroup-per-batch-element kernel
 static bool adj_wide_ok(const NetDev &net, int l, const WsArgs &ws) {
   const int N = net.N[l], B = net.B;
-  const char *env = getenv("SNN_WS_KERNEL");
-  if (env && strcmp(env, "stream") == 0) return false;
+  if (net.sel_adjoint == 2) return false;
   if (!ws.xg || N % 64 != 0 || B > 64) return false;
   const int bp = ((B + 15) / 16 == 3 ? 4 : (B + 15) / 16) * 16;
   if ((size_t)2 * bp * N > (size_t)ws.xg_stride) return false;
@@ -2920,7 +2922,7 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
     const AdjJob &jb = jobs.j[i];
     const int l = jb.l, N = net.N[l];
     if (N <= 256 || taken[i]) continue;
-    if (N <= 1024 && ws.xg && ws_use_mfma() && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
+    if (N <= 1024 && ws.xg && ws_use_mfma(net) && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
       // matrix-core version: workgroup = 32 rows x 16 batch elements
       const int G_b = (B + 15) / 16, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
       const int NK = N <= 512 ? 32 : 64;
@@ -2986,10 +2988,7 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
   return hipGetLastError();
 }
 
-static bool ws_use_mfma() { // SNN_WS_KERNEL=valu selects the VALU version of the chip-wide recurrence
-  const char *e = getenv("SNN_WS_KERNEL");
-  return !(e && strcmp(e, "valu") == 0);
-}
+static bool ws_use_mfma(const NetDev &net) { return net.sel_adjoint != 1; } // 1: the VALU version of the chip-wide recurrence
 
 int ws_max_resident_groups_mfma(int device) {
   hipDeviceProp_t prop;

@@ -5,10 +5,9 @@ masks, Bernoulli input spike trains and labels.  It holds none of the method's
 arithmetic and is the only code shared by the CPU oracle's tests and the GPU
 library's tests/benchmark, so that both sides see identical arrays.
 
-The paper measures on spiking datasets it only cites (Results section: "a
-typical sequence length for applications and datasets"); these i.i.d. Bernoulli
-spike trains of the same shape (e.g. 700 input channels, 20 classes) stand in
-for them.
+The paper evaluates on spiking datasets that it only cites (Results section);
+these i.i.d. Bernoulli spike trains of the same shape (e.g. 700 input channels,
+20 classes) stand in for them.
 
 Draw order for one seed (numpy ``default_rng(seed)``): W_in^1, W_rec^1, ...,
 W_in^L, W_rec^L, W_out, recurrent masks (layer order), inputs, labels.

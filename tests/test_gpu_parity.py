@@ -75,21 +75,11 @@ def _identical(a, b):
     return all(np.array_equal(x, y) for x, y in zip(a[0] + a[1] + [a[2]], b[0] + b[1] + [b[2]]))
 
 
-def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0, skip_saturated=False):
+def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0, probe_states=()):
     d = synth.generate(w)
-    ref = _oracle(w, d, want_v=True, nthreads=nthreads, surr_window=window)
-    if skip_saturated:
-        # with a saturated softmax the loss gradient softmax(ubar) - onehot(y) is rounding noise of the fp32 readout,
-        # whatever the implementation: nothing to compare gradients against
-        z = ref.ubar - ref.ubar.max(axis=1, keepdims=True)
-        pr = np.exp(z) / np.exp(z).sum(axis=1, keepdims=True)
-        pr[np.arange(w.B), d["labels"]] -= 1.0
-        saturated = np.abs(pr).max() < 1e-3
-        if saturated:
-            print(f"[{w.name}] saturated softmax, max|dloss/dubar| = {np.abs(pr).max():.2e}: gradients only compared "
-                  "between strategies")
-    else:
-        saturated = False
+    # the fp32 oracle supplies the forward trajectory (its own gradients are not the reference: see
+    # test_gradient_reference_for_the_gpu_parity_bar among the oracle pins)
+    ref = _oracle(w, d, want_v=True, nthreads=nthreads, surr_window=window, backward=False)
     ref64 = _oracle_f64_on_f32_trajectory(w, d, ref, nthreads, window)
     net = snn.from_workload(w, d, surr_window=window)
     try:
@@ -110,8 +100,9 @@ def _full_parity(w, strategies, nthreads=8, check_states=True, window=0.0, skip_
             st = net.snn_bptt(strat, C, F)
             assert _check_spikes(net, w, ref, tag) == 0
             g = _gpu_grads(net, len(w.n_hidden))
-            if not saturated:
-                _check_grads(g, ref64, tag)
+            _check_grads(g, ref64, tag)
+            for (pl, pt) in probe_states:  # rebuilt from the stored spike trains, whatever the strategy stored
+                assert np.array_equal(net.snn_get_state(pl, pt), ref.v[pl][pt - 1]), f"{tag}: v of layer {pl} at t={pt}"
             if first is None:
                 first = g
             else:
@@ -291,10 +282,29 @@ def test_wide_input_layer_with_stage_kernels():
 
 
 def test_config1_full_size():
-    """Configuration 1 at its full size (T = 1000, batch 32), the launch configuration the benchmark times:
-    Standard, Chunk(32), Remote(32) as the configuration lists, plus Double."""
+    """Configuration 1 at its full size (T = 1000, batch 32): Standard, Chunk(32), Remote(32) as the configuration
+    lists, plus Double and Hier; single states through snn_get_state at a tile boundary, inside a tile and at T."""
     _full_parity(synth.config(1), [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 32), (snn.SNN_REMOTE, 32, 0),
-                                   (snn.SNN_DOUBLE, 100, 10), (snn.SNN_HIER, 4, 32)], nthreads=8, check_states=True)
+                                   (snn.SNN_DOUBLE, 100, 10), (snn.SNN_HIER, 4, 32)], nthreads=8, check_states=True,
+                 probe_states=[(0, 1), (1, 64), (0, 333), (1, 1000)])
+
+
+def test_config2_widths_full_batch():
+    """Configuration 2's widths at its full batch (64): the chip-wide adjoint recurrence with four batch groups and
+    two layers' jobs per launch, full 64-row blocks in the current kernels, the wide weight-gradient tiles -- the
+    launch shapes the benchmark times -- with gradients against the oracle."""
+    w = synth.config(2, T=40)
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 20, 10), (snn.SNN_CHUNK, 0, 10)], nthreads=16,
+                 check_states=True, probe_states=[(2, 40), (1, 17)])
+
+
+def test_config4_widths_full_batch():
+    """Configuration 4's widths at its full batch (32), masked recurrent matrices, with the library's own
+    rate-driven choice of current kernel (nothing forced; the first step runs before any rate is known, the
+    later ones after): gradients against the oracle."""
+    w = synth.config(4, T=8)
+    _full_parity(w, [(snn.SNN_DOUBLE, 4, 2), (snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 3)], nthreads=16,
+                 check_states=True, probe_states=[(3, 8), (0, 5)])
 
 
 def test_config3_width_reduced_length():
@@ -326,7 +336,59 @@ def test_budget_and_argument_errors():
     assert e.value.status == snn.SNN_E_INVAL
     with pytest.raises(snn.SnnError):
         net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T + 1)
+    # labels are range-checked on the host before any kernel indexes the readout with them
+    for bad in (w.n_out, -1):
+        lab = d["labels"].copy()
+        lab[1] = bad
+        with pytest.raises(snn.SnnError) as e:
+            net.snn_bind_inputs(d["in_spikes"], lab, w.T)
+        assert e.value.status == snn.SNN_E_INVAL and "label" in str(e.value)
+    with pytest.raises(TypeError):
+        net.snn_bind_inputs(d["in_spikes"], d["labels"].astype(np.int64), w.T)
+    net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+    with pytest.raises(snn.SnnError) as e:
+        net.snn_get_state(0, 1)  # no forward pass since the inputs were bound
+    assert e.value.status == snn.SNN_E_STATE
+    net.snn_bptt(snn.SNN_CHUNK, 0, 10)
+    for bad_t in (0, w.T + 1):
+        with pytest.raises(snn.SnnError) as e:
+            net.snn_get_state(0, bad_t)
+        assert e.value.status == snn.SNN_E_INVAL
     net.snn_destroy()
+
+
+def test_graph_replay_follows_a_change_of_the_recurrent_mask():
+    """A recorded training step holds the pointers it was recorded with, the recurrent mask among them.  Setting
+    weights (with a mask, then without) between replays must give what an eager step gives, bit for bit: masked
+    gradients are zero where the mask is, and a replay after the mask is dropped does not touch the freed mask."""
+    w = synth.Workload("maskswap_40-96-96-5", 40, (96, 96), 5, T=40, B=4, p_in=0.1, gain=0.8, rec_density=0.3, seed=13)
+    d = synth.generate(w)
+    L = len(w.n_hidden)
+    dense = [np.ascontiguousarray(d["W_rec"][l]) for l in range(L)]
+    net = snn.Snn(snn.make_config(w.n_in, list(w.n_hidden), w.n_out, w.T, w.B))
+    try:
+        for l in range(L):
+            net.snn_set_weights(snn.SNN_W_IN, l, d["W_in"][l])
+            net.snn_set_weights(snn.SNN_W_REC, l, dense[l])          # no mask yet
+        net.snn_set_weights(snn.SNN_W_OUT, 0, d["W_out"])
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        for phase in ("unmasked", "masked", "unmasked again"):
+            if phase == "masked":
+                for l in range(L):
+                    net.snn_set_weights(snn.SNN_W_REC, l, dense[l], d["rec_mask"][l])
+            elif phase == "unmasked again":
+                for l in range(L):
+                    net.snn_set_weights(snn.SNN_W_REC, l, dense[l])
+            net.snn_bptt(snn.SNN_DOUBLE, 12, 4, want_stats=True)      # eager
+            eager = _gpu_grads(net, L)
+            for rep in range(2):
+                net.snn_bptt(snn.SNN_DOUBLE, 12, 4, want_stats=False) # records, then replays
+                assert _identical(_gpu_grads(net, L), eager), (phase, rep)
+            for l in range(L):
+                outside = eager[1][l][d["rec_mask"][l] == 0]
+                assert (not outside.any()) == (phase == "masked"), phase
+    finally:
+        net.snn_destroy()
 
 
 def test_suggested_intervals_train_within_the_budget():
@@ -598,7 +660,8 @@ def test_seeded_random_shapes():
             else:
                 strategies.append((s, rng.randint(1, 5), rng.randint(1, T)))
         print(f"[random {it}] hidden={hidden} n_in={w.n_in} n_out={w.n_out} T={T} B={B} {strategies}", flush=True)
-        _full_parity(w, strategies, nthreads=min(8, B), check_states=(sum(hidden) * T * B < 4e6), skip_saturated=True)
+        _full_parity(w, strategies, nthreads=min(8, B), check_states=(sum(hidden) * T * B < 4e6),
+                     probe_states=[(L - 1, T), (0, max(1, T // 2))])
 
 
 def _full_size_properties(idx, strategies, budget, prefix):
