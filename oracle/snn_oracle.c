@@ -23,7 +23,7 @@
  *     loss  = (1/B) sum_b [ logsumexp(ubar_b) - ubar_b[y_b] ]
  *
  *   backward, surrogate derivative sigma'(x) = 1 / (1 + k|x|)^2  (k = surr_beta):
- *     g        = (softmax(ubar) - onehot(y)) / (B*T)
+ *     g        = (softmax(ubar) - onehot(y)) / (B*T)     (labelled class: - sum of the other classes' softmax)
  *     du_t     = beta * du_{t+1} + g
  *     dW_out[j,:]  += s^L_t[j] * du_t
  *     ds^l_t   = (l==L ? W_out du_t : W_in^{l+1} dv^{l+1}_t) + W_rec^l dv^l_{t+1} - theta * dv^l_{t+1}
@@ -414,9 +414,16 @@ static double bptt_one(const net_t *n, const spikes_t *sp, const int32_t *labels
     for (int o = 0; o < O; ++o) z = z + (REAL)exp((double)(ubar_out[o] - m));
     REAL lse = m + (REAL)log((double)z);
     loss_b = (double)(lse - ubar_out[labels[b]]);
+    /* softmax - onehot.  The softmax sums to one, so the labelled class's entry, softmax_y - 1, is minus the
+     * sum of the other classes' probabilities; it is formed that way because the difference of two numbers
+     * near one loses every digit once the softmax is confident (1 - softmax_y below the rounding step of
+     * REAL), while the sum of the small probabilities keeps them. */
+    REAL others = (REAL)0;
+    for (int o = 0; o < O; ++o)
+      if (o != labels[b]) others = others + (REAL)exp((double)(ubar_out[o] - m)) / z;
     for (int o = 0; o < O; ++o) {
       REAL p = (REAL)exp((double)(ubar_out[o] - m)) / z;
-      g[o] = (p - (o == labels[b] ? (REAL)1 : (REAL)0)) / ((REAL)B * (REAL)T);
+      g[o] = (o == labels[b] ? -others : p) / ((REAL)B * (REAL)T);
     }
   }
 

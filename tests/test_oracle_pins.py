@@ -481,3 +481,56 @@ def test_gradient_reference_for_the_gpu_parity_bar():
     assert spread32[-1] > 1e-4 and off_seq[-1] > 1e-4          # dW_out: measured 2.0e-4 and 1.9e-4
     assert max(spread64) < 1e-10                                # measured 3e-13
     assert max(off_par) < 5e-5                                  # measured 1.4e-5
+
+
+def test_loss_gradient_of_a_confident_softmax():
+    """d loss / d ubar = softmax - onehot, checked against 60-digit decimal arithmetic where the softmax is
+    saturated (the labelled class's probability is 1 - 1e-13 and less): the readout weights are scaled until the
+    time-averaged readouts are tens of units apart.  dW_out is linear in that gradient (dW_out[j] = sum over the
+    steps where neuron j fired of du_t, du_t = beta du_{t+1} + g), so it is rebuilt in decimal arithmetic from the
+    oracle's own spike train and compared.  Formed as a difference of numbers near one the labelled class's entry
+    would be off by 1e-3 here; as minus the sum of the other classes' probabilities it keeps full precision."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    net = _tiny(5, hidden=(6,), n_out=3, T=9, B=2)
+    beta = 0.75  # exact in binary and in decimal
+    checked = 0
+    W0 = net["W_out"].copy()
+    for scale in (40.0, 100.0):
+        net["W_out"] = np.round(W0 * scale * 64) / 64  # dyadic: the decimal copy is exact
+        first = oracle.bptt(net["n_in"], net["n_hidden"], net["n_out"], net["W_in"], net["W_rec"], net["W_out"],
+                            net["in_spikes"], net["labels"], dtype=np.float64, beta=beta, backward=False)
+        net["labels"] = first.ubar.argmax(axis=1).astype(np.int32)  # confident and right: softmax_y -> 1
+        r = oracle.bptt(net["n_in"], net["n_hidden"], net["n_out"], net["W_in"], net["W_rec"], net["W_out"],
+                        net["in_spikes"], net["labels"], dtype=np.float64, beta=beta)
+        T, B = net["in_spikes"].shape[:2]
+        N, O = net["W_out"].shape
+        Wd = [[Decimal(float(net["W_out"][j, o])) for o in range(O)] for j in range(N)]
+        exp_dW = [[Decimal(0)] * O for _ in range(N)]
+        for b in range(B):
+            u = [Decimal(0)] * O
+            usum = [Decimal(0)] * O
+            for t in range(T):
+                cur = [sum((Wd[j][o] for j in range(N) if r.spikes[0][t, b, j] != 0), Decimal(0)) for o in range(O)]
+                u = [Decimal(beta) * u[o] + cur[o] for o in range(O)]
+                usum = [usum[o] + u[o] for o in range(O)]
+            ubar = [x / T for x in usum]
+            m = max(ubar)
+            e = [(x - m).exp() for x in ubar]
+            z = sum(e)
+            y = int(net["labels"][b])
+            g = [(e[o] / z - (1 if o == y else 0)) / (B * T) for o in range(O)]
+            one_minus_py = 1 - e[y] / z
+            if Decimal(0) < one_minus_py < Decimal("1e-12"):
+                checked += 1
+            du = [Decimal(0)] * O
+            for t in reversed(range(T)):
+                du = [Decimal(beta) * du[o] + g[o] for o in range(O)]
+                for j in range(N):
+                    if r.spikes[0][t, b, j] != 0:
+                        exp_dW[j] = [exp_dW[j][o] + du[o] for o in range(O)]
+        exp = np.array([[float(x) for x in row] for row in exp_dW])
+        assert np.abs(exp).max() > 0
+        err = np.abs(r.dW_out - exp).max() / np.abs(exp).max()
+        assert err < 1e-11, (scale, err)
+    assert checked >= 1  # at least one batch element was saturated beyond fp64's rounding step of 1
