@@ -125,6 +125,18 @@ snn_status snn_set_weights(snn_ctx *ctx, int kind, int layer, const float *w, co
  * queued).  loss_out: one float, host.  Stores spikes (bitmasks) but no states. */
 snn_status snn_forward(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out);
 
+/* The forward pass of snn_forward for callers that cannot allocate device memory: code under HIP graph capture
+ * around it, tight serving loops, harnesses that forbid hipMalloc.  Same result as snn_forward bit for bit (spike
+ * trains, readout, loss; inputs bound for a following snn_bptt).  Differences: in_spikes and labels must be device
+ * pointers (a host buffer would need a staging allocation: SNN_E_INVAL); the per-tile currents of the forward pass,
+ * which snn_forward keeps in a workspace it allocates on demand, live in a static 16 MiB device array inside the
+ * library (one per GPU, held until the process ends).  A network whose workspace --
+ * 64 * batch * (8 * n_out + 2 * sum of n_hidden) * 4 bytes -- exceeds 16 MiB is refused with SNN_E_INVAL and a
+ * message that says so.  The call allocates and frees nothing, on the device or through the HIP runtime.  Every
+ * context on a GPU shares that GPU's array: calls that overlap in time on one GPU (two host threads, two contexts)
+ * race; calls one after the other do not interfere (nothing in the array is read before the same call wrote it). */
+snn_status snn_forward_noalloc(snn_ctx *ctx, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out);
+
 /* One full training step (forward with the strategy's storage plan, loss, backward with
  * recomputation: the execution orders of Fig. 1, one panel per strategy; Sections "Standard Checkpointing",
  * "Remote Checkpointing", "Hierarchical Checkpointing", "Double Checkpointing") on the inputs bound by the last snn_forward/snn_bind_inputs.  Gradients stay in

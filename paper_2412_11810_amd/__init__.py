@@ -25,7 +25,7 @@ OP_NAMES = {1: "SAVE_LOCAL", 2: "SAVE_REMOTE", 3: "LOAD_REMOTE", 4: "REFWD1", 5:
 EXPORTS = ["snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
            "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_bytes_required",
            "snn_state_slots", "snn_schedule", "snn_last_error", "snn_destroy", "snn_debug_copy",
-           "snn_suggest_intervals", "snn_debug_currents", "snn_get_state"]
+           "snn_suggest_intervals", "snn_debug_currents", "snn_get_state", "snn_forward_noalloc"]
 
 
 class snn_config(C.Structure):
@@ -80,6 +80,7 @@ def lib() -> C.CDLL:
         L.snn_init.argtypes = [C.POINTER(snn_config), C.POINTER(vp)]
         L.snn_set_weights.argtypes = [vp, C.c_int, C.c_int, vp, vp]
         L.snn_forward.argtypes = [vp, vp, vp, i32, C.POINTER(C.c_float)]
+        L.snn_forward_noalloc.argtypes = [vp, vp, vp, i32, C.POINTER(C.c_float)]
         L.snn_bptt.argtypes = [vp, C.c_int, i32, i32, sz, C.POINTER(snn_stats)]
         L.snn_bind_inputs.argtypes = [vp, vp, vp, i32]
         L.snn_grads.argtypes = [vp, C.c_int, C.c_int, vp, sz]
@@ -102,7 +103,7 @@ def lib() -> C.CDLL:
         L.snn_destroy.restype = None
         for name in ("snn_init", "snn_set_weights", "snn_forward", "snn_bptt", "snn_bind_inputs", "snn_grads",
                      "snn_get_spikes", "snn_get_readout", "snn_debug_states", "snn_debug_copy", "snn_debug_currents",
-                     "snn_get_state"):
+                     "snn_get_state", "snn_forward_noalloc"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -200,6 +201,12 @@ class Snn:
         loss = C.c_float(0)
         self._check_inputs(in_spikes, labels)
         self._check(lib().snn_forward(self._h, _ptr(in_spikes), _ptr(labels), T, C.byref(loss)))
+        return float(loss.value)
+
+    def snn_forward_noalloc(self, in_spikes, labels, T: int) -> float:
+        loss = C.c_float(0)
+        self._check_inputs(in_spikes, labels)
+        self._check(lib().snn_forward_noalloc(self._h, _ptr(in_spikes), _ptr(labels), T, C.byref(loss)))
         return float(loss.value)
 
     def snn_bptt(self, strategy: int, coarse: int = 0, fine: int = 0, hbm_budget_bytes: int = 0,

@@ -14,6 +14,15 @@
 
 #define SNN_BWD_TILE 256 // steps of the adjoint pass per launch group (bounds the per-chunk scratch)
 
+// Workspace of snn_forward_noalloc: the per-tile currents of the forward pass, which the allocating entry points
+// keep in a buffer they size and hipMalloc on demand.  One copy per GPU the library is loaded on, held until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: g_scratch_dev[device]
+// is the address kernels and copies get.
+#define SNN_NOALLOC_SCRATCH_BYTES ((size_t)16 << 20)
+static __device__ __align__(256) unsigned char scratch[SNN_NOALLOC_SCRATCH_BYTES];
+#define SNN_MAX_DEVICES 64
+static void *g_scratch_dev[SNN_MAX_DEVICES]; // per device ordinal, filled by snn_init with that device current
+
 struct snn_ctx {
   snn_config cfg{};
   NetDev net{};
@@ -31,6 +40,7 @@ struct snn_ctx {
   uint8_t *rec_mask[SNN_MAXL]{};
   size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
   int32_t *labels = nullptr;
+  unsigned char *host_small = nullptr; // pinned: 64 bytes (loss, error flag) + B labels, for calls that must not allocate
   int T_bound = 0;
   int T_spikes = 0; // length of the sequence whose hidden spike trains are stored (0: none since the inputs were bound)
   double *readout = nullptr;
@@ -290,8 +300,18 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
     c->own_stream = true;
   }
   HIPCHK(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+  if (cfg->device < SNN_MAX_DEVICES && !g_scratch_dev[cfg->device]) {
+    void *p = nullptr;
+    HIPCHK(c, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_dev[cfg->device] = p;
+  }
   NetDev &n = c->net;
   const int L = n.L, B = n.B, O = n.n_out;
+  if (hipHostMalloc(reinterpret_cast<void **>(&c->host_small), 64 + (size_t)B * 4, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    c->host_small = nullptr;
+    return fail(c, SNN_E_HOSTMEM, "pinned host allocation failed");
+  }
   for (int l = 0; l < L; ++l) {
     const size_t ni = (size_t)pre_of(n, l) * n.N[l], nr = (size_t)n.N[l] * n.N[l];
     HIPCHK(c, hipMalloc(&c->W_in[l], (ni + nr) * 4)); // [W_in ; W_rec] stacked row-wise
@@ -381,6 +401,7 @@ void snn_destroy(snn_ctx *c) {
   if (c->ws.bar) uncached_release(c->cfg.device, c->ws.bar); (void)hipFree(c->counters);
   (void)hipFree(c->arena); (void)hipFree(c->dubuf);
   if (c->host_ckpt) (void)hipHostFree(c->host_ckpt);
+  if (c->host_small) (void)hipHostFree(c->host_small);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
@@ -490,7 +511,7 @@ static snn_status ensure_work(snn_ctx *c, size_t bytes) {
   return SNN_OK;
 }
 
-static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
+static snn_status forward_only(snn_ctx *c, float *traj_or_null, float *work_or_null = nullptr) {
   read_kernel_hooks(c);
   const NetDev &n = c->net;
   StoreSpec st{};
@@ -498,11 +519,15 @@ static snn_status forward_only(snn_ctx *c, float *traj_or_null) {
     st.base = traj_or_null; st.slot_stride = (size_t)n.B * n.SN; st.t_base = 0; st.interval = 1; st.slot0 = 0;
     st.t_max = c->T_bound;
   }
-  snn_status rs = ensure_work(c, work_bytes(n, 1));
-  if (rs != SNN_OK) return rs;
-  HIPCHK(c, hipMemsetAsync(c->cur_state, 0, c->Ms(), c->stream));
+  float *work = work_or_null;
+  if (!work) { // the caller brought no workspace: the context's own, grown on demand
+    snn_status rs = ensure_work(c, work_bytes(n, 1));
+    if (rs != SNN_OK) return rs;
+    work = c->dubuf;
+  }
+  HIPCHK(c, launch_fill_zero(c->cur_state, c->Ms(), c->stream));
   std::vector<int> bounds = tile_bounds(0, c->T_bound, c->T_bound);
-  HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, c->dubuf, c->stream, nullptr, nullptr, &c->ws));
+  HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, st, c->readout, 1, work, c->stream, nullptr, nullptr, &c->ws));
   HIPCHK(c, launch_loss(c->readout, c->labels, n.B, n.n_out, c->T_bound, c->ubar, c->g, c->loss_dev, c->stream));
   c->T_spikes = c->T_bound;
   return SNN_OK;
@@ -519,6 +544,57 @@ snn_status snn_forward(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labe
   HIPCHK(c, hipStreamSynchronize(c->stream));
   if (loss_out) *loss_out = loss;
   return check_ws_error(c); // the sliced sequential kernels of wide layers wait for each other, with a bound
+}
+
+snn_status snn_forward_noalloc(snn_ctx *c, const uint8_t *in_spikes, const int32_t *labels, int32_t T, float *loss_out) {
+  if (!c || !in_spikes || !labels) return fail(c, SNN_E_INVAL, "null argument");
+  if (T < 1 || T > c->cfg.T) return fail(c, SNN_E_INVAL, "T out of range for this context");
+  const NetDev &n = c->net;
+  const int dev = c->cfg.device;
+  if (dev >= SNN_MAX_DEVICES || !g_scratch_dev[dev]) return fail(c, SNN_E_STATE, "no static workspace on this device");
+  const size_t need = work_bytes(n, 1);
+  if (need > SNN_NOALLOC_SCRATCH_BYTES) {
+    char msg[160];
+    snprintf(msg, sizeof msg, "snn_forward_noalloc: the forward workspace of this network is %zu B, the static one holds %zu B; "
+             "use snn_forward", need, (size_t)SNN_NOALLOC_SCRATCH_BYTES);
+    return fail(c, SNN_E_INVAL, msg);
+  }
+  HIPCHK(c, hipSetDevice(dev));
+  if (!is_device_ptr(in_spikes) || !is_device_ptr(labels))
+    return fail(c, SNN_E_INVAL, "snn_forward_noalloc takes device pointers (a host buffer would need a staging allocation)");
+  if (c->own_stream) HIPCHK(c, hipStreamSynchronize(nullptr));
+  hipStream_t s = c->stream;
+  // labels: to the context and, through the pinned block, to the host for the range check
+  int32_t *lab_host = reinterpret_cast<int32_t *>(c->host_small + 64);
+  HIPCHK(c, hipMemcpyAsync(lab_host, labels, (size_t)n.B * 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  for (int b = 0; b < n.B; ++b)
+    if (lab_host[b] < 0 || lab_host[b] >= n.n_out) {
+      char msg[96];
+      snprintf(msg, sizeof msg, "label %d of batch element %d is outside [0, %d)", (int)lab_host[b], b, n.n_out);
+      return fail(c, SNN_E_INVAL, msg);
+    }
+  HIPCHK(c, launch_pack_inputs(in_spikes, n.mask[0], T, n.B, n.n_in, n.Wd[0], s));
+  HIPCHK(c, hipMemcpyAsync(c->labels, labels, (size_t)n.B * 4, hipMemcpyDeviceToDevice, s));
+  c->T_bound = T;
+  c->T_spikes = 0;
+  // every current the sequential kernels read from the workspace is written earlier in the same call: nothing in
+  // it has to start at zero, and what the previous call left there is never read
+  const snn_status rs = forward_only(c, nullptr, static_cast<float *>(g_scratch_dev[dev]));
+  if (rs != SNN_OK) return rs;
+  float *loss_host = reinterpret_cast<float *>(c->host_small);
+  unsigned *err_host = reinterpret_cast<unsigned *>(c->host_small + 16);
+  *err_host = 0u;
+  HIPCHK(c, hipMemcpyAsync(loss_host, c->loss_dev, 4, hipMemcpyDeviceToHost, s));
+  if (c->ws.err) HIPCHK(c, hipMemcpyAsync(err_host, c->ws.err, 4, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  if (loss_out) *loss_out = *loss_host;
+  if (*err_host) {
+    HIPCHK(c, launch_fill_zero(c->ws.err, 4, s));
+    HIPCHK(c, hipStreamSynchronize(s));
+    return fail(c, SNN_E_HIP, "a workgroup barrier of a chip-wide kernel timed out; results are invalid");
+  }
+  return SNN_OK;
 }
 
 snn_status snn_debug_states(snn_ctx *c, float *dst) {
