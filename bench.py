@@ -6,7 +6,11 @@ input-spike packing, event-driven forward with the strategy's state storage, los
 from checkpoints, adjoint pass and weight-gradient accumulation (everything behind
 snn_bind_inputs + snn_bptt).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--strategy remote]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--strategy double]
+
+The default workload is configuration 4 (1024 -> 4 x 8192 -> 100, T = 5000, batch 32, recurrent matrices 90 % zero),
+the largest one of the benchmark configurations and the only one whose weights (1.9 GB) do not fit on the chip, run
+with Double Checkpointing under its 32 GB HBM activation budget.
 
 Other modes (used to produce the summaries under profiles/):
   --pmc-copy      run only the plain copy kernel (reference for scaling hardware byte counters)
@@ -26,7 +30,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
-MFMA_F64_PEAK_TF = 78.6   # MI355X published fp64 matrix peak
 MFMA_F32_PEAK_TF = 157.3  # MI355X published fp32 matrix peak
 ALU_F32_PEAK_TF = 157.3   # MI355X published fp32 vector peak (256 CUs x 4 SIMDs x 64 flop/clk x 2.4 GHz)
 
@@ -36,57 +39,50 @@ STRATEGY_PARAMS = {
     1: {"standard": (0, 0), "chunk": (0, 32), "remote": (32, 0), "double": (100, 10), "hier": (4, 32)},
     2: {"standard": (0, 0), "chunk": (0, 100), "remote": (100, 0), "double": (100, 10), "hier": (4, 100)},
     3: {"standard": (0, 0), "chunk": (0, 316), "remote": (316, 0), "double": (316, 18), "hier": (4, 316)},
-    4: {"standard": (0, 0), "chunk": (0, 70), "remote": (70, 0), "double": (70, 10), "hier": (4, 70)},
+    4: {"standard": (0, 0), "chunk": (0, 64), "remote": (64, 0), "double": (512, 64), "hier": (4, 64)},
 }
 BUDGET = {2: 8 * 10**9, 3: 4 * 10**9, 4: 32 * 10**9}
 SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3, "hier": 4}  # hier: (nb_local, chunk)
 
 
-def work_model(w, rates, in_rate, T, refwd_steps, n_bwd_launch):
-    """Algorithmic work of one training step per kernel kind (bytes for the bandwidth-bound kinds,
-    flops for the arithmetic ones), from the measured event counts."""
+def work_model(w, rates, in_rate, T, refwd_steps, rec_density):
+    """Own work of one training step per kernel kind: what the event-driven method must do, whatever a kernel
+    does internally -- bytes of the weight rows of ACTIVE presynaptic neurons (existing synapses only for a masked
+    recurrent matrix kept as compressed rows: 4-byte value + 2-byte index), one add per such weight, the dense
+    recurrent product of the adjoint pass (dense by necessity: the surrogate derivative has no compact support)
+    and the dense inter-layer products.  Event counts come from the measured firing rates."""
     B, L = w.B, len(w.n_hidden)
-    pre_n = [w.n_in] + list(w.n_hidden[:-1])
-    pre_r = [in_rate] + list(rates[:-1])
-    ev_in = [pre_r[l] * pre_n[l] * B for l in range(L)]       # feed-forward events per step
-    ev_rec = [rates[l] * w.n_hidden[l] * B for l in range(L)]  # recurrent events per step
-    ev_out = rates[-1] * w.n_hidden[-1] * B
     N = w.n_hidden
+    pre_n = [w.n_in] + list(N[:-1])
+    pre_r = [in_rate] + list(rates[:-1])
+    ev_in = [pre_r[l] * pre_n[l] * B for l in range(L)]       # feed-forward events per step (whole batch)
+    ev_rec = [rates[l] * N[l] * B for l in range(L)]          # recurrent events per step
+    ev_out = rates[-1] * N[-1] * B
+    masked = rec_density < 1.0
+    row_rec = [(6.0 * rec_density if masked else 4.0) * N[l] for l in range(L)]   # bytes of one recurrent row
+    ent_rec = [(rec_density if masked else 1.0) * N[l] for l in range(L)]         # weights in one recurrent row
     out = {}
-    # forward, parallel part: rows of W_in (4*N_l bytes per event), the current tile written and read
-    # once, readout rows (4*n_out per last-layer spike)
     out["fwd_currents"] = ("hbm", T * (sum(4.0 * N[l] * ev_in[l] + 8.0 * N[l] * B for l in range(L)) + 4.0 * w.n_out * ev_out))
-    # weight matrices far beyond the L2 (the library's rule: 32 MB and more) go through the dense matrix-core
-    # kernel, which visits every presynaptic neuron: priced as the contraction it is
-    dense = [4.0 * max(pre_n[l], N[l]) * N[l] >= (32 << 20) for l in range(L)]
-    dense_fwd = [4.0 * pre_n[l] * N[l] >= (32 << 20) for l in range(L)]
-    if any(dense_fwd):
-        out["fwd_currents"] = ("mfma32", T * B * sum(2.0 * N[l] * pre_n[l] for l in range(L) if dense_fwd[l]))
-    # forward, sequential part: register-stationary layers do dense fma chains (2*N^2 flop per (b, t));
-    # wider layers gather the rows of active neurons
-    seq_flops = sum(2.0 * N[l] * N[l] * B * T for l in range(L) if N[l] <= 256)
-    seq_bytes = T * sum(4.0 * N[l] * ev_rec[l] + (N[l] / 8.0 + 4.0 * N[l]) * B for l in range(L) if N[l] > 256)
-    out["fwd_seq"] = ("alu", seq_flops) if seq_flops >= seq_bytes else ("hbm", seq_bytes)
-    # recompute: rows of W_in and W_rec per event + current written, read, state written (12*N_l per (b, t))
-    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * (ev_in[l] + ev_rec[l]) + 12.0 * N[l] * B for l in range(L)))
-    if any(dense):
-        out["recompute"] = ("mfma32", refwd_steps * B * sum(2.0 * N[l] * (pre_n[l] + N[l]) for l in range(L) if dense[l]))
-    # adjoint: dense recurrent product, 2*N^2 flop per (b, t, layer); layers wider than 1024 stream W_rec from
-    # memory once per step for the whole batch (4*N^2 bytes per (t, layer)) and are bound by that
-    out["adjoint"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)))
+    seq_adds = T * sum(ent_rec[l] * ev_rec[l] for l in range(L) if N[l] <= 256)
+    seq_bytes = T * sum(row_rec[l] * ev_rec[l] + (N[l] / 8.0 + 4.0 * N[l]) * B for l in range(L) if N[l] > 256)
+    out["fwd_seq"] = ("alu", seq_adds) if max(N) <= 256 else ("hbm", seq_bytes)
+    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * ev_in[l] + row_rec[l] * ev_rec[l] + 12.0 * N[l] * B for l in range(L)))
+    # adjoint recurrence: layers wider than 1024 stream their recurrent matrix once per step for the whole batch
     if max(N) > 1024:
-        out["adjoint"] = ("hbm", sum(4.0 * N[l] * N[l] * T for l in range(L) if N[l] > 1024))
+        out["adjoint"] = ("hbm", T * sum((6.0 * rec_density if masked else 4.0) * N[l] * N[l] for l in range(L) if N[l] > 1024))
+    else:
+        out["adjoint"] = ("alu", sum(2.0 * ent_rec[l] * N[l] * B * T for l in range(L)))
     up = [w.n_out if l == L - 1 else N[l + 1] for l in range(L)]
     out["up_gemm"] = ("mfma32", sum(2.0 * N[l] * up[l] * B * T for l in range(L)))
-    # dW: dense fp32 matrix-core contraction over (t, b): 2 * n_pre * n_post * B * T per matrix
-    out["dw"] = ("mfma32", 2.0 * B * T * (sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out))
-    # fused stage launches (recurrences of one pipeline stage + weight gradients of the stage before): the
-    # flops of both parts; the launch is as long as the longer of the two, the recurrence chain as a rule
-    out["bwd_stage"] = ("alu", out["adjoint"][1] + out["dw"][1])
-    # fused forward stage launches (sequential parts + the currents the next stage consumes): the sequential
-    # chain decides their length
-    out["fwd_stage"] = out["fwd_seq"]
-    # launch between two backward stages: inter-layer products (priced) + the recompute scan of a later chunk
+    # weight gradients: read-modify-write of the gradient rows of active presynaptic neurons (fp32 in, fp32 out)
+    dw_bytes = T * (sum(8.0 * N[l] * ev_in[l] + 8.0 * ent_rec[l] * ev_rec[l] for l in range(L)) + 8.0 * w.n_out * ev_out)
+    dw_adds = T * (sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L)) + w.n_out * ev_out)
+    out["dw"] = ("hbm", dw_bytes)
+    # fused launches of the narrow-layer networks: the recurrences (dense) + the adds of the weight gradients and of
+    # the recompute currents that ride along; the forward stage: the adds of the active rows
+    rec_adds = refwd_steps * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L))
+    out["bwd_stage"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)) + dw_adds + rec_adds)
+    out["fwd_stage"] = ("alu", T * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L)))
     out["bwd_inter"] = out["up_gemm"]
     return out
 
@@ -112,19 +108,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1)
-    ap.add_argument("--strategy", default="remote", choices=list(SID))
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--strategy", default="double", choices=list(SID))
     ap.add_argument("--T", type=int, default=0, help="override the sequence length")
     ap.add_argument("--gain", type=float, default=0.0, help="override the weight gain (sets the hidden firing rate)")
     ap.add_argument("--coarse", type=int, default=-1)
     ap.add_argument("--fine", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-others", action="store_true", help="do not time the other strategies")
+    ap.add_argument("--others", default="auto", choices=["auto", "all", "none"],
+                    help="time the other strategies too (auto: all of them for configurations 0 and 1, none otherwise)")
     ap.add_argument("--no-long", action="store_true", help="skip the 10x-sequence-length comparison")
-    ap.add_argument("--long-coarse", type=int, default=1000)
-    ap.add_argument("--long-fine", type=int, default=100)
-    ap.add_argument("--long-reps", type=int, default=3)
-    ap.add_argument("--long-warmup", type=int, default=2)
+    ap.add_argument("--long-reps", type=int, default=1)
+    ap.add_argument("--budget", type=int, default=-1, help="HBM activation budget in bytes (default: the configuration's)")
     ap.add_argument("--single", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="chunk-size / remote-chunk-size study (use with --T 4096)")
     ap.add_argument("--host-inputs", action="store_true",
@@ -216,7 +211,10 @@ def main():
     if args.coarse >= 0 or args.fine >= 0:
         c0, f0 = params[args.strategy]
         params[args.strategy] = (args.coarse if args.coarse >= 0 else c0, args.fine if args.fine >= 0 else f0)
-    budget = BUDGET.get(args.config, 0)
+    budget = args.budget if args.budget >= 0 else BUDGET.get(args.config, 0)
+    if args.config in (0, 1) and args.budget < 0:
+        # configurations 0 and 1 name no budget: every strategy runs inside what plain BPTT needs for this T
+        budget = snn.snn_bytes_required(snn.make_config(w.n_in, list(w.n_hidden), w.n_out, w.T, w.B), snn.SNN_STANDARD, w.T)
 
     def step(name, stats=False):
         C, F = params[name]
@@ -306,7 +304,7 @@ def main():
     nts = w.neuron_timesteps()
     sec = time_strategy(args.strategy, args.steps, args.warmup)
     others = {}
-    if not args.no_others:
+    if args.others == "all" or (args.others == "auto" and args.config in (0, 1)):
         for name in params:
             if name != args.strategy:
                 try:
@@ -323,23 +321,20 @@ def main():
     C, F = params[args.strategy]
     slots, rslots = snn.snn_state_slots(SID[args.strategy], w.T, C, F)
     sched = snn.snn_schedule(SID[args.strategy], w.T, C, F)
-    n_bwd = max(1, sum(1 for o in sched if o[0] == "BACKWARD"))
-    if args.strategy == "hier":
-        rslots = 0  # forward tiles follow the checkpoint interval, not host segments
-    # Remote/Double with states of up to 1 MiB: the kernels access the pinned host block themselves, so the
-    # forward pass is not cut at the checkpoints (same rule as the library; SNN_HOST_TIER overrides it)
+    n_bwd = max(1, sum(-(-(o[1] - o[2] + 1) // 256) for o in sched if o[0] == "BACKWARD"))  # adjoint tiles of <= 256 steps
+    Ms = 4 * w.B * w.neurons
     tier = os.environ.get("SNN_HOST_TIER", "")
-    if args.strategy in ("remote", "double") and tier != "dma" and (tier == "direct" or 4 * w.B * w.neurons <= (1 << 20)):
-        rslots = 0
+    host_direct = args.strategy in ("remote", "double") and tier != "dma" and (tier == "direct" or Ms <= (1 << 20))
+    seg = C if (args.strategy in ("remote", "double") and not host_direct) else (F if args.strategy == "hier" else w.T)
+    n_tiles = sum(-(-(min(a + seg, w.T) - a) // 64) for a in range(0, w.T, seg))   # forward tiles of <= 64 steps
     n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
-    n_tiles = sum(-(-(min((k + 1) * C, w.T) - k * C) // 64) for k in range(rslots)) if rslots else -(-w.T // 64)
     L = len(w.n_hidden)
-    model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, n_bwd)
+    model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density)
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
     launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
-                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd, "bwd_stage": max(1, n_bwd + L - 1),
+                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
                 "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
     if st.ms_bwd_stage > 0:
         # all but the first stage's recurrences and the last stage's weight gradients ran inside fused launches:
@@ -350,38 +345,47 @@ def main():
         if ms["recompute"] < 0.25 * ms["bwd_inter"]:  # only the first chunk's recompute ran on its own
             ms["recompute"] = 0.0
     if st.ms_fwd_stage > 0:
-        # likewise: what is left outside the fused launches is the first stage's currents, the last stage's
-        # sequential parts and the readout scans
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
-    kernel_of = {"fwd_seq": "k_layer_seq_rs" if max(w.n_hidden) <= 256 else
-                 ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather"),
-                 "fwd_currents": "k_currents_dense" if model["fwd_currents"][0] == "mfma32" else "k_currents_mfma",
-                 "recompute": "k_currents_dense" if model["recompute"][0] == "mfma32" else "k_currents_mfma", "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage", "bwd_inter": "k_bwd_inter",
-                 "adjoint": "k_adj_rec_rs" if max(w.n_hidden) <= 256 else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
-    peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma": (MFMA_F64_PEAK_TF, "TFLOP/s", 1e12),
-             "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
+    wide = max(w.n_hidden) > 256
+    big = any(4.0 * max(pn, n) * n >= (32 << 20) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))
+    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden)
+    kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
+                            ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
+                 "fwd_currents": "k_currents_dense / k_currents (by firing rate)" if big else "k_currents_mfma",
+                 "recompute": ("k_currents_dense / k_currents (by firing rate)" if big else "k_currents_mfma") +
+                              (" + k_currents_csr" if w.rec_density < 1.0 and wide else "") + " + k_scan",
+                 "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "bwd_inter": "k_bwd_inter",
+                 "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
+    peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
     kinds = {}
     for k, (bound, work) in model.items():
         if ms[k] <= 0:
             continue
         peak, unit, scale = peaks[bound]
         ach = work / (ms[k] * 1e-3) / scale
-        kinds[k] = {"kernel": kernel_of[k], "bound": "mfma" if bound == "mfma32" else bound, "ms_per_step": round(ms[k], 3), "launches_per_step": launches[k],
-                    "avg_launch_ms": round(ms[k] / launches[k], 4), "achieved": round(ach, 3), "peak": round(peak, 1),
-                    "unit": unit, "frac": round(ach / peak, 5)}
+        kinds[k] = {"kernel": kernel_of[k], "bound": "mfma" if bound == "mfma32" else bound, "ms_per_step": round(ms[k], 3),
+                    "launches_per_step": launches[k], "avg_launch_ms": round(ms[k] / launches[k], 4),
+                    "achieved": round(ach, 3), "peak": round(peak, 1), "unit": unit, "frac": round(ach / peak, 5)}
     dom = max(kinds, key=lambda k: kinds[k]["ms_per_step"])
     dk = kinds[dom]
     work_per_launch = model[dom][1] / launches[dom]
+    first_kernel = dk["kernel"].split(" ")[0]
+    traffic = read_traffic(w.name, args.strategy, first_kernel)
     roofline = {"bound": dk["bound"], "kernel": dk["kernel"], "kind": dom, "achieved": dk["achieved"], "peak": dk["peak"],
-                "unit": dk["unit"], "frac": dk["frac"],
-                "traffic": read_traffic(w.name, args.strategy, dk["kernel"]),
+                "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic,
                 "launches_per_step": dk["launches_per_step"], "avg_launch_ms": dk["avg_launch_ms"],
                 "algorithmic_work_per_launch": int(work_per_launch),
-                "note": "work = flops for alu/mfma kinds, bytes for hbm kinds; durations from HIP events on the compute stream",
+                "note": "work = the event-driven method's own work per kind (bytes of the weight rows of active presynaptic "
+                        "neurons -- existing synapses only for masked matrices -- for hbm kinds; adds of those rows plus the "
+                        "dense recurrent product of the adjoint for alu kinds; dense inter-layer products for mfma kinds), "
+                        "never the dense-equivalent work of a kernel; durations from HIP events on the compute stream of an "
+                        "eager step; traffic = HBM bytes per launch of the kind's first kernel from the committed rocprofv3 "
+                        "--pmc summary of this workload (null if none)",
                 "kinds": kinds}
 
     # ---- measured peaks next to the published ones: a plain streaming copy (1 GiB read + 1 GiB written per
-    # launch, the library's copy kernel) and pinned-host copies of 64 MiB in both directions ---------------
+    # launch, the library's copy kernel) and pinned-host copies of one state (and of 64 MiB) in both directions ----
     def measured_peaks():
         n = 1 << 30
         a = torch.ones(n // 4, dtype=torch.float32, device=dev)
@@ -392,121 +396,141 @@ def main():
             net.snn_debug_copy(a, b, n)
         hbm = 5 * 2 * n / (time.perf_counter() - t0) / 1e9
         del a, b
-        m = 64 << 20
-        h = torch.empty(m, dtype=torch.uint8, pin_memory=True)
-        g = torch.empty(m, dtype=torch.uint8, device=dev)
         out = {"hbm_copy_GBs": round(hbm, 1)}
-        for name, src, dst in (("h2d_pinned_GBs", h, g), ("d2h_pinned_GBs", g, h)):
-            dst.copy_(src, non_blocking=True)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(5):
+        for tag, m in (("", 64 << 20), ("_one_state", max(4096, Ms))):
+            h = torch.empty(m, dtype=torch.uint8, pin_memory=True)
+            g = torch.empty(m, dtype=torch.uint8, device=dev)
+            for name, src, dst in (("h2d_pinned", h, g), ("d2h_pinned", g, h)):
                 dst.copy_(src, non_blocking=True)
-            torch.cuda.synchronize()
-            out[name] = round(5 * m / (time.perf_counter() - t0) / 1e9, 1)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(5):
+                    dst.copy_(src, non_blocking=True)
+                torch.cuda.synchronize()
+                out[name + tag + "_GBs"] = round(5 * m / (time.perf_counter() - t0) / 1e9, 1)
         return out
 
     roofline["measured_peaks"] = measured_peaks()
 
-    # ---- "max trainable T" and the long-sequence comparison -----------------------------------------
-    # Budget = what Standard BPTT needs for this workload's T.  Under that same budget: the largest T
-    # each strategy can train (closed form from snn_bytes_required, intervals by the square-root rules
-    # unless the configuration fixes them), and Double Checkpointing actually run at 10x the sequence
-    # length, with its time per time step next to Standard's.
+    # ---- host link: checkpoint traffic of the timed strategy.  With the DMA tier the copies run on a side stream
+    # beside the compute stream; the rate below is what the step needs from the link (bytes moved over the step's
+    # wall time), next to what one state-sized pinned copy achieves on this machine.
+    link_bytes = int(st.d2h_bytes + st.h2d_bytes)
+    host_link = {"tier": "none" if not link_bytes else ("direct (kernels write and read the mapped pinned block)" if host_direct else "dma (hipMemcpyAsync on the copy stream)"),
+                 "bytes_per_step": link_bytes, "transfers_per_step": int(st.n_d2h + st.n_h2d), "message_bytes": Ms,
+                 "sustained_GBs_over_the_step": round(link_bytes / sec / 1e9, 3),
+                 "pinned_copy_of_one_state_GBs": {"h2d": roofline["measured_peaks"]["h2d_pinned_one_state_GBs"],
+                                                  "d2h": roofline["measured_peaks"]["d2h_pinned_one_state_GBs"]},
+                 "link_time_if_serial_ms": round(link_bytes / max(1e-9, roofline["measured_peaks"]["d2h_pinned_one_state_GBs"]) / 1e6, 3)}
+
+    # ---- "max trainable T" and the 10x-sequence-length comparison ------------------------------------
+    # Budget = what Standard BPTT needs for a tenth of this workload's T.  Under that same budget: the largest T each
+    # strategy can train (closed form from snn_bytes_required, square-root intervals), and Double Checkpointing
+    # actually run at the full T -- ten times Standard's length -- with intervals chosen for that budget, its time
+    # per time step next to Standard's.
     long_seq = None
     if not args.no_long:
-        ref_budget = snn.snn_bytes_required(net.cfg, snn.SNN_STANDARD, w.T)
+        T_std = max(1, w.T // 10)
+        cfg_std = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T_std, w.B)
+        ref_budget = snn.snn_bytes_required(cfg_std, snn.SNN_STANDARD, T_std)
 
-        def fits(sid, T, Cc, Ff):
+        def fits(sid, T, Cc, Ff, bud):
             cfgT = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T, w.B)
             need = snn.snn_bytes_required(cfgT, sid, T, Cc, Ff)
-            return 0 < need <= ref_budget
+            return 0 < need <= bud
 
-        def t_max(sid, Cc, Ff):
-            lo, hi = 1, 1
-            while fits(sid, hi, min(Cc, hi), min(Ff, min(Cc, hi) if Cc else hi)) and hi < (1 << 26):
+        def t_max(sid, bud):
+            lo, hi = 0, 1
+            while fits(sid, hi, 0, 0, bud) and hi < (1 << 26):
                 lo, hi = hi, hi * 2
             while hi - lo > 1:
                 mid = (lo + hi) // 2
-                if fits(sid, mid, min(Cc, mid), min(Ff, min(Cc, mid) if Cc else mid)):
+                if fits(sid, mid, 0, 0, bud):
                     lo = mid
                 else:
                     hi = mid
             return lo
-        tmax = {"standard": t_max(snn.SNN_STANDARD, 0, 0), "chunk": t_max(snn.SNN_CHUNK, 0, 0),
-                "remote": t_max(snn.SNN_REMOTE, 0, 0), "double": t_max(snn.SNN_DOUBLE, 0, 0)}
-        # the dual the paper plots (Fig. 2, middle): HBM activation bytes against the sequence length, per
-        # strategy with the square-root intervals (closed form, no run)
+        names = (("standard", snn.SNN_STANDARD), ("chunk", snn.SNN_CHUNK), ("remote", snn.SNN_REMOTE), ("double", snn.SNN_DOUBLE))
+        tmax = {name: t_max(sid, ref_budget) for name, sid in names}
+        tmax_cfg = {name: t_max(sid, budget) for name, sid in names} if budget else None
+
         def need_at(sid, T):
             return snn.snn_bytes_required(snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T, w.B), sid, T, 0, 0)
         Ts = [w.T * m for m in (1, 2, 4, 8, 16, 32)]
         bytes_vs_T = {"T": Ts}
-        for name, sid in (("standard", snn.SNN_STANDARD), ("chunk", snn.SNN_CHUNK), ("remote", snn.SNN_REMOTE),
-                          ("double", snn.SNN_DOUBLE), ("hier", snn.SNN_HIER)):
+        for name, sid in names + (("hier", snn.SNN_HIER),):
             bytes_vs_T[name] = [int(need_at(sid, T)) for T in Ts]
-        T_long = 10 * w.T
-        CL, FL = args.long_coarse, args.long_fine
-        wl = synth.config(args.config, T=T_long)
-        cfg_long = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T_long, w.B)
-        need_long = snn.snn_bytes_required(cfg_long, snn.SNN_DOUBLE, T_long, CL, FL)
-        long_seq = {"budget_bytes": ref_budget, "budget_is": f"Standard BPTT at T={w.T}", "t_max_under_budget": tmax,
-                    "double_T": T_long, "double_coarse": CL, "double_fine": FL, "double_bytes_required": need_long,
-                    "hbm_activation_bytes_vs_T": bytes_vs_T}
-        if 0 < need_long <= ref_budget:
-            dl = synth.generate(wl)
-            xl = torch.from_numpy(dl["in_spikes"]).to(dev)
-            yl = torch.from_numpy(dl["labels"]).to(dev)
-            netl = snn.from_workload(wl, dl)
+        long_seq = {"budget_bytes": ref_budget, "budget_is": f"what Standard BPTT needs at T={T_std}", "t_max_under_budget": tmax,
+                    "t_max_under_the_configuration_budget": tmax_cfg, "hbm_activation_bytes_vs_T": bytes_vs_T}
+        try:
+            CL, FL = snn.snn_suggest_intervals(net.cfg, snn.SNN_DOUBLE, w.T, ref_budget)
+        except snn.SnnError:
+            CL = FL = 0
+        if CL:
+            need_long = snn.snn_bytes_required(net.cfg, snn.SNN_DOUBLE, w.T, CL, FL)
+            long_seq.update({"double_T": w.T, "double_coarse": CL, "double_fine": FL, "double_bytes_required": need_long})
 
             def step_long():
-                netl.snn_bind_inputs(xl, yl, T_long)
-                netl.snn_bptt(snn.SNN_DOUBLE, CL, FL, ref_budget, want_stats=False)
-            for _ in range(args.long_warmup):
-                step_long()
+                net.snn_bind_inputs(x, y, w.T)
+                return net.snn_bptt(snn.SNN_DOUBLE, CL, FL, ref_budget, want_stats=False)
+            step_long()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            nrep = args.long_reps
-            for _ in range(nrep):
+            for _ in range(args.long_reps):
                 step_long()
             torch.cuda.synchronize()
-            sec_long = (time.perf_counter() - t0) / nrep
+            sec_long = (time.perf_counter() - t0) / args.long_reps
+            xs_, n_std = x[:T_std].contiguous() if hasattr(x, "contiguous") else np.ascontiguousarray(x[:T_std]), 3
 
             def step_std():
-                net.snn_bind_inputs(x, y, w.T)
+                net.snn_bind_inputs(xs_, y, T_std)
                 net.snn_bptt(snn.SNN_STANDARD, 0, 0, ref_budget, want_stats=False)
             for _ in range(2):
                 step_std()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(max(3, args.steps // 4)):
+            for _ in range(n_std):
                 step_std()
             torch.cuda.synchronize()
-            sec_std = (time.perf_counter() - t0) / max(3, args.steps // 4)
+            sec_std = (time.perf_counter() - t0) / n_std
             long_seq.update({"double_ms_per_step": round(sec_long * 1e3, 3),
-                             "double_us_per_timestep": round(sec_long / T_long * 1e6, 4),
-                             "standard_T": w.T, "standard_ms_per_step": round(sec_std * 1e3, 3),
-                             "standard_us_per_timestep": round(sec_std / w.T * 1e6, 4),
-                             "time_per_timestep_ratio_double_over_standard": round((sec_long / T_long) / (sec_std / w.T), 4),
-                             "sequence_length_ratio": 10})
-            netl.snn_destroy()
-            del xl, yl
+                             "double_us_per_timestep": round(sec_long / w.T * 1e6, 4),
+                             "standard_T": T_std, "standard_ms_per_step": round(sec_std * 1e3, 3),
+                             "standard_us_per_timestep": round(sec_std / T_std * 1e6, 4),
+                             "time_per_timestep_ratio_double_over_standard": round((sec_long / w.T) / (sec_std / T_std), 4),
+                             "sequence_length_ratio": round(w.T / T_std, 2)})
 
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), w.B))
-        Tcpu = min(w.T, 1000 if w.neurons <= 1024 else 100)
-        xs = np.ascontiguousarray(d["in_spikes"][:Tcpu])
-        wall, reps = 0.0, 0
-        while reps < 6 and (reps < 1 or wall < 1.5):
-            t0 = time.perf_counter()
-            oracle.bptt(w.n_in, list(w.n_hidden), w.n_out, d["W_in"], d["W_rec"], d["W_out"], xs, d["labels"],
-                        alpha=w.alpha, beta=w.beta, theta=w.theta, surr_beta=w.surr_beta, dtype=np.float32, nthreads=cores)
-            wall += time.perf_counter() - t0
-            reps += 1
-        cpu = {"value": round(reps * w.B * Tcpu * w.neurons / wall, 1), "unit": "neuron-timesteps/s", "cores": cores,
-               "kind": "oracle",
-               "sample": f"oracle fp32 Standard BPTT (fwd+bwd), first {Tcpu} of {w.T} steps, full batch, {reps} repetitions, {wall:.2f} s wall"}
+        # the box's share of host cores: OMP_NUM_THREADS is set to it on the GPU machine (os.cpu_count() shows the
+        # whole machine); the oracle parallelises over batch elements
+        host_cores = os.cpu_count() or 1
+        cores = max(1, min(host_cores, int(os.environ.get("OMP_NUM_THREADS", "16")), w.B))
+
+        def time_oracle(Tc, nthreads, max_reps, min_wall):
+            xs = np.ascontiguousarray(d["in_spikes"][:Tc])
+            wall, reps, used = 0.0, 0, nthreads
+            while reps < max_reps and (reps < 1 or wall < min_wall):
+                t0 = time.perf_counter()
+                r = oracle.bptt(w.n_in, list(w.n_hidden), w.n_out, d["W_in"], d["W_rec"], d["W_out"], xs, d["labels"],
+                                alpha=w.alpha, beta=w.beta, theta=w.theta, surr_beta=w.surr_beta, rec_mask=d.get("rec_mask"),
+                                dtype=np.float32, nthreads=nthreads)
+                wall += time.perf_counter() - t0
+                reps += 1
+                used = r.stats.get("threads_used", nthreads) or nthreads
+            return reps * w.B * Tc * w.neurons / wall, wall, reps, used
+        # bounded samples: a prefix of the sequence sized from the network (about 10-30 s of CPU work in all)
+        per_step = w.B * sum(n * (pn + 2 * n) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))  # ~MACs per step
+        T_all = int(max(2, min(w.T, 4e10 / per_step)))
+        T_one = int(max(2, min(w.T, 4e9 / per_step)))
+        v_all, wall_all, reps_all, used = time_oracle(T_all, cores, 6, 1.5)
+        v_one, wall_one, reps_one, _ = time_oracle(T_one, 1, 3, 1.5)
+        cpu = {"value": round(v_all, 1), "unit": "neuron-timesteps/s", "cores": int(used), "kind": "oracle",
+               "one_thread_value": round(v_one, 1), "host_cpu_count": host_cores,
+               "sample": f"oracle fp32 Standard BPTT (fwd+bwd), full batch: first {T_all} of {w.T} steps with {used} threads "
+                         f"({reps_all} repetitions, {wall_all:.2f} s wall), first {T_one} steps with 1 thread "
+                         f"({reps_one} repetitions, {wall_one:.2f} s wall); time is linear in T"}
 
     out = {
         "metric": "BPTT neuron-timesteps/sec (fwd+bwd) at fixed HBM budget", "value": round(nts / sec, 1),
@@ -516,12 +540,13 @@ def main():
         "config": {"workload": w.name, "T": w.T, "batch": w.B, "strategy": args.strategy, "coarse_interval": C,
                    "fine_interval": F, "hbm_budget_bytes": budget,
                    "hbm_activation_bytes": int(st.bytes_states + st.bytes_spikes + st.bytes_workspace),
+                   "hbm_activation_bytes_min": int(snn.snn_bytes_required(net.cfg, SID[args.strategy], w.T, C, F)),
                    "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots,
                    "state_slots_hbm_allocated": int(st.local_state_slots), "state_slots_host": rslots,
+                   "recurrent_density": w.rec_density,
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
-                   "host_link_bytes_per_step": int(st.d2h_bytes + st.h2d_bytes),
                    "other_strategies_neuron_timesteps_per_s": others},
-        "roofline": roofline, "cpu_baseline": cpu, "long_sequence": long_seq,
+        "roofline": roofline, "cpu_baseline": cpu, "host_link": host_link, "long_sequence": long_seq,
     }
     print(json.dumps(out))
     net.snn_destroy()

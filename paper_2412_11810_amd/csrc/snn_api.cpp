@@ -38,6 +38,11 @@ struct snn_ctx {
   float *dW_in[SNN_MAXL]{}, *dW_rec[SNN_MAXL]{}, *dW_out = nullptr;
   double *acc_in[SNN_MAXL]{}, *acc_rec[SNN_MAXL]{}, *acc_out = nullptr; // fp64 gradient accumulators
   uint8_t *rec_mask[SNN_MAXL]{};
+  // compressed rows of the masked recurrent matrices (see NetDev::csr_sub); built by snn_set_weights
+  uint32_t *csr_sub[SNN_MAXL]{};
+  uint16_t *csr_col[SNN_MAXL]{};
+  float *csr_val[SNN_MAXL]{};
+  size_t csr_nnz[SNN_MAXL]{};
   size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
   int32_t *labels = nullptr;
   unsigned char *host_small = nullptr; // pinned: 64 bytes (loss, error flag) + B labels, for calls that must not allocate
@@ -141,7 +146,14 @@ int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 // call that launches kernels, so that a test can switch them between two calls on one context.
 void read_kernel_hooks(snn_ctx *c) {
   NetDev &n = c->net;
-  n.sel_currents = n.sel_adjoint = n.sel_slices = 0;
+  n.sel_currents = n.sel_adjoint = n.sel_slices = n.sel_csr = 0;
+  if (const char *e = std::getenv("SNN_CSR")) n.sel_csr = !std::strcmp(e, "0") ? 1 : !std::strcmp(e, "1") ? 2 : 0;
+  for (int l = 0; l < n.L; ++l) {
+    const bool on = c->csr_sub[l] && n.sel_csr != 1;
+    n.csr_sub[l] = on ? c->csr_sub[l] : nullptr;
+    n.csr_col[l] = on ? c->csr_col[l] : nullptr;
+    n.csr_val[l] = on ? c->csr_val[l] : nullptr;
+  }
   if (const char *e = std::getenv("SNN_CURRENTS"))
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
   if (const char *e = std::getenv("SNN_WS_KERNEL"))
@@ -174,6 +186,51 @@ size_t spike_bytes(const NetDev &n, int T) {
   size_t w = 0;
   for (int l = 0; l <= n.L; ++l) w += (size_t)(T + 1) * n.B * n.Wd[l];
   return w * 8;
+}
+
+void free_csr(snn_ctx *c, int l) {
+  (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]);
+  c->csr_sub[l] = nullptr; c->csr_col[l] = nullptr; c->csr_val[l] = nullptr; c->csr_nnz[l] = 0;
+}
+
+// Compressed rows of a masked recurrent matrix (layout: NetDev::csr_sub).  An entry exists where the mask says a
+// synapse exists, whatever its weight; its order inside a row is the ascending postsynaptic index.  Built on the
+// host (one pass over the matrix), uploaded once; the stream is idle when this is called.
+snn_status build_csr(snn_ctx *c, int l, const float *w, const uint8_t *mask) {
+  const int N = c->net.N[l], nsub = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW;
+  const size_t ne = (size_t)N * N;
+  std::vector<float> wh;
+  std::vector<uint8_t> mh;
+  if (is_device_ptr(w)) { wh.resize(ne); HIPCHK(c, hipMemcpy(wh.data(), w, ne * 4, hipMemcpyDeviceToHost)); w = wh.data(); }
+  if (is_device_ptr(mask)) { mh.resize(ne); HIPCHK(c, hipMemcpy(mh.data(), mask, ne, hipMemcpyDeviceToHost)); mask = mh.data(); }
+  size_t nnz = 0;
+  for (size_t i = 0; i < ne; ++i) nnz += mask[i] != 0;
+  if (nnz > 0xFFFFFFF0ull) return fail(c, SNN_E_INVAL, "recurrent matrix has too many synapses for 32-bit entry indices");
+  std::vector<uint32_t> sub((size_t)N * (nsub + 1));
+  std::vector<uint16_t> col(nnz + 1);
+  std::vector<float> val(nnz + 1);
+  size_t p = 0;
+  for (int j = 0; j < N; ++j) {
+    const uint8_t *mr = mask + (size_t)j * N;
+    const float *wr = w + (size_t)j * N;
+    uint32_t *sr = sub.data() + (size_t)j * (nsub + 1);
+    for (int r = 0; r < nsub; ++r) {
+      sr[r] = (uint32_t)p;
+      const int n1 = std::min(N, (r + 1) * SNN_CSR_SUBW);
+      for (int n = r * SNN_CSR_SUBW; n < n1; ++n)
+        if (mr[n]) { col[p] = (uint16_t)n; val[p] = wr[n]; ++p; }
+    }
+    sr[nsub] = (uint32_t)p;
+  }
+  free_csr(c, l);
+  HIPCHK(c, hipMalloc(&c->csr_sub[l], sub.size() * 4));
+  HIPCHK(c, hipMalloc(&c->csr_col[l], col.size() * 2));
+  HIPCHK(c, hipMalloc(&c->csr_val[l], val.size() * 4));
+  HIPCHK(c, hipMemcpy(c->csr_sub[l], sub.data(), sub.size() * 4, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->csr_col[l], col.data(), col.size() * 2, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(c->csr_val[l], val.data(), val.size() * 4, hipMemcpyHostToDevice));
+  c->csr_nnz[l] = nnz;
+  return SNN_OK;
 }
 
 } // namespace
@@ -392,6 +449,7 @@ void snn_destroy(snn_ctx *c) {
   for (int l = 0; l < SNN_MAXL; ++l) {
     (void)hipFree(c->W_in[l]); (void)hipFree(c->W_inT[l]); (void)hipFree(c->W_recT[l]);
     (void)hipFree(c->dW_in[l]); (void)hipFree(c->dW_rec[l]); (void)hipFree(c->rec_mask[l]);
+    (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]);
     (void)hipFree(c->acc_in[l]); (void)hipFree(c->acc_rec[l]);
   }
   for (int l = 0; l <= SNN_MAXL; ++l) (void)hipFree(c->net.mask[l]);
@@ -439,10 +497,14 @@ snn_status snn_set_weights(snn_ctx *c, int kind, int layer, const float *w, cons
     if (mask) {
       if (!c->rec_mask[layer]) HIPCHK(c, hipMalloc(&c->rec_mask[layer], ne));
       HIPCHK(c, hipMemcpyAsync(c->rec_mask[layer], mask, ne, hipMemcpyDefault, c->stream));
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      const snn_status rs = build_csr(c, layer, w, mask);
+      if (rs != SNN_OK) return rs;
     } else if (c->rec_mask[layer]) {
       HIPCHK(c, hipStreamSynchronize(c->stream));
       HIPCHK(c, hipFree(c->rec_mask[layer]));
       c->rec_mask[layer] = nullptr;
+      free_csr(c, layer);
     }
   }
   HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -1427,7 +1489,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   if (use_graph) {
     unsigned long long pol = 0;
     for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
-    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16;
+    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }

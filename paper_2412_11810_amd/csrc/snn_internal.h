@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #define SNN_MAXL 4
+#define SNN_CSR_SUBW 512 // postsynaptic neurons per sub-range of a compressed row (one wavefront's share)
 
 // Device-visible description of the network and of where its data lives in HBM.
 //
@@ -24,6 +25,15 @@ struct NetDev {
   const float *W_in[SNN_MAXL], *W_rec[SNN_MAXL], *W_out;
   const float *W_inT[SNN_MAXL], *W_recT[SNN_MAXL], *W_outT;
   uint64_t *mask[SNN_MAXL + 1];
+  // Compressed rows of a masked recurrent matrix (NULL: the layer has no mask, or its compressed form is switched
+  // off): the existing synapses of presynaptic neuron j, ascending in the postsynaptic index, are entries
+  // csr_sub[l][j * (nsub + 1) + 0] .. csr_sub[l][j * (nsub + 1) + nsub] of csr_col[l] (16-bit postsynaptic index)
+  // and csr_val[l]; csr_sub[l][j * (nsub + 1) + r] is the first entry whose postsynaptic index is at least
+  // r * SNN_CSR_SUBW, nsub = ceil(N_l / SNN_CSR_SUBW): a wavefront that owns the postsynaptic neurons
+  // [r * SNN_CSR_SUBW, (r + 1) * SNN_CSR_SUBW) finds its part of every row without searching.
+  const uint32_t *csr_sub[SNN_MAXL];
+  const uint16_t *csr_col[SNN_MAXL];
+  const float *csr_val[SNN_MAXL];
   float alpha, beta, theta, k;
   float win;  // surrogate window (<= 0: none)
   // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step
@@ -35,6 +45,8 @@ struct NetDev {
   // sel_adjoint: 1 VALU version of the chip-wide recurrence, 2 one-workgroup-per-batch-element streaming kernel.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
+  unsigned char sel_csr; // compressed rows of masked recurrent matrices: 1 never used (dense-stored walk everywhere),
+                         // 2 used wherever a kernel for them exists, 0 the library's choice
 };
 
 // Where the forward / recompute kernel writes states it has to keep.

@@ -543,6 +543,202 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
   for (int k = 0; k < NPT; ++k) state[(size_t)b * SN + off + c0 + tid + k * nt] = v[k];
 }
 
+// ------------------------------------------------------------------------------------------
+// A2 for masked recurrent matrices: the rows of active presynaptic neurons in compressed form (only the
+// synapses that exist).  A wavefront owns SNN_CSR_SUBW postsynaptic neurons and an accumulator for each in LDS.
+// It walks the active rows in ascending order; the lanes take the entries of the row that fall into its range
+// (their postsynaptic indices are distinct) and add them to the accumulators with LDS add instructions, which
+// execute in issue order, round to nearest even and follow the denormal mode like a vector add: every
+// accumulator receives the same addends in the same ascending order as in the dense-stored walk, which adds
+// +0.0f wherever no synapse exists -- the same bits.  Only the owning wavefront ever touches an accumulator.
+// ------------------------------------------------------------------------------------------
+template <int U>
+struct CsrGroup { // the entries of U consecutive rows that fall into the wavefront's sub-range, one entry per lane
+  uint32_t p[U], n[U], c[U];
+  float v[U];
+};
+template <int U>
+static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn,
+                                                 const uint16_t *__restrict__ col, const float *__restrict__ val, int lane) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) { // rows past the block carry no entries
+    const bool in = q + u < WAVE;
+    g.p[u] = __builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
+    g.n[u] = in ? __builtin_amdgcn_readlane(nn, (q + u) & (WAVE - 1)) : 0u;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    g.c[u] = 0u;
+    g.v[u] = 0.0f;
+    if ((uint32_t)lane < g.n[u]) {
+      g.c[u] = col[g.p[u] + lane];
+      g.v[u] = val[g.p[u] + lane];
+    }
+  }
+}
+template <int U>
+static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, uint32_t c_base, const uint16_t *__restrict__ col,
+                                                   const float *__restrict__ val, float *acc_w, int lane) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if ((uint32_t)lane < g.n[u])
+      (void)__hip_atomic_fetch_add(&acc_w[g.c[u] - c_base], g.v[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    for (uint32_t o = WAVE; o < g.n[u]; o += WAVE) // a row with more than 64 entries in this range: finish it first
+      if (o + lane < g.n[u])
+        (void)__hip_atomic_fetch_add(&acc_w[col[g.p[u] + o + lane] - c_base], val[g.p[u] + o + lane], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+}
+// The positions of 64 rows are fetched at once (one row per lane), one block of 64 rows ahead; the entries of two
+// groups of U rows are in flight while a third is added.
+static __device__ __forceinline__ void csr_gather_wave(const uint16_t *list, int cnt, const uint32_t *__restrict__ sub,
+                                                       int nsub1, int r, const uint16_t *__restrict__ col,
+                                                       const float *__restrict__ val, float *acc_w, int lane) {
+  constexpr int U = 16;
+  const uint32_t c_base = (uint32_t)r * SNN_CSR_SUBW;
+  auto meta = [&](int base, uint32_t &p0, uint32_t &nn) {
+    const int i = base + lane;
+    p0 = 0u;
+    nn = 0u;
+    if (i < cnt) {
+      const uint32_t *sp = sub + (size_t)list[i] * nsub1 + r;
+      p0 = sp[0];
+      nn = sp[1] - p0;
+    }
+  };
+  uint32_t p0, nn, p0n, nnn;
+  meta(0, p0, nn);
+  for (int base = 0; base < cnt; base += WAVE) {
+    meta(base + WAVE, p0n, nnn);
+    const int nr = cnt - base < WAVE ? cnt - base : WAVE;
+    CsrGroup<U> ga, gb;
+    csr_issue<U>(ga, 0, p0, nn, col, val, lane);
+    for (int q = 0; q < nr; q += 2 * U) {
+      __builtin_amdgcn_sched_barrier(0); // keep the loads of the next group ahead of the adds of this one
+      csr_issue<U>(gb, q + U, p0, nn, col, val, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      csr_consume<U>(ga, c_base, col, val, acc_w, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      csr_issue<U>(ga, q + 2 * U, p0, nn, col, val, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      csr_consume<U>(gb, c_base, col, val, acc_w, lane);
+    }
+    p0 = p0n;
+    nn = nnn;
+  }
+}
+
+// The sliced sequential part for a layer whose recurrent matrix has compressed rows (widths that are multiples
+// of 4 SNN_CSR_SUBW).  Workgroup (b, sl) owns 4 SNN_CSR_SUBW columns, wavefront w the sub-range 4 sl + w: it
+// walks the compressed rows of the neurons that fired in the previous step (csr_gather_wave, accumulators in LDS,
+// cleared by their owner at the start of the step) and moves 1/10 of the bytes of the dense-stored walk when
+// 90 % of the synapses do not exist.  Thread (w, lane) then owns the columns 64 k + lane of its wavefront's
+// sub-range for the LIF update, so a ballot is a whole spike word.  Exchange of the spike words between the
+// workgroups of a batch element, polling and time-out exactly as in k_layer_seq_gather_sl.
+__global__ void __launch_bounds__(256)
+k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw,
+                   unsigned *err, unsigned spin_limit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NPT = SNN_CSR_SUBW / WAVE, NS = 4 * SNN_CSR_SUBW;
+  const int jq = blockIdx.y;
+  const int l = jobs.j[jq].l, t0 = jobs.j[jq].t0, t1 = jobs.j[jq].t1, t_tile = jobs.j[jq].t_tile;
+  const float *__restrict__ iin = jobs.j[jq].iin;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
+  const int b = (int)blockIdx.x / S, sl = (int)blockIdx.x % S;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c0 = sl * NS + wave * SNN_CSR_SUBW, w0 = c0 >> 6; // own wavefront's first column and its spike word
+  const int nsub1 = N / SNN_CSR_SUBW + 1, r = sl * 4 + wave;
+  uint64_t *words = (uint64_t *)smem;                    // [Wd]  whole layer
+  int *cnt = (int *)(words + Wd);                        // [1] (+3 pad)
+  float *acc = (float *)(cnt + 4);                       // [4][SNN_CSR_SUBW]
+  uint16_t *list = (uint16_t *)(acc + NS);               // [N] indices of the active rows, ascending
+  float *acc_w = acc + wave * SNN_CSR_SUBW;
+  uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
+  const size_t mstride = (size_t)B * Wd;
+  uint64_t *xb = xw + (size_t)(jq * B + b) * 4 * Wd; // [2][2 Wd] tagged half-words
+  const uint32_t *__restrict__ sub = net.csr_sub[l];
+  const uint16_t *__restrict__ col = net.csr_col[l];
+  const float *__restrict__ val = net.csr_val[l];
+  if (tid == 0) *cnt = 0;
+  for (int i = tid; i < Wd; i += 256) words[i] = mbase[(size_t)t0 * mstride + i];
+  __syncthreads();
+  float v[NPT];
+  uint32_t sp = 0;
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) {
+    v[k] = state[(size_t)b * SN + off + c0 + 64 * k + lane];
+    if ((words[w0 + k] >> lane) & 1ull) sp |= 1u << k;
+  }
+  expand_all(words, Wd, list, cnt, tid, 256);
+  __syncthreads();
+  const size_t istride = (size_t)B * N;
+  uint32_t *words32 = reinterpret_cast<uint32_t *>(words);
+  unsigned step = 0;
+  bool dead = false;
+  StoreCursor sc;
+  sc.init(st, t0 + 1);
+  for (int t = t0 + 1; t <= t1; ++t, ++step) {
+    const int store_slot = sc.slot(st, t);
+    sc.next(st);
+    const float *irow = iin + (size_t)(t - 1 - t_tile) * istride + (size_t)b * N + c0;
+    float in_t[NPT];
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      in_t[k] = irow[64 * k + lane];
+      acc_w[64 * k + lane] = 0.0f;
+    }
+    csr_gather_wave(list, *cnt, sub, nsub1, r, col, val, acc_w, lane);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup"); // the adds of this wavefront have landed before it reads the sums
+    uint64_t *xdst = xb + (size_t)(step & 1u) * 2 * Wd;
+    const uint64_t tag = (uint64_t)(step + 1u) << 32;
+    uint32_t spn = 0;
+#pragma unroll
+    for (int k = 0; k < NPT; ++k) {
+      const int widx = w0 + k;
+      const float a_rec = acc_w[64 * k + lane];
+      float a = net.alpha * v[k];
+      if ((sp >> k) & 1u) a = a - net.theta;
+      const float vn = a + (in_t[k] + a_rec);
+      v[k] = vn;
+      const uint64_t word = __ballot(vn > net.theta);
+      if ((word >> lane) & 1ull) spn |= 1u << k;
+      if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + 64 * k + lane] = vn;
+      if (lane == 0) mbase[(size_t)t * mstride + widx] = word;
+      if (lane < 2)
+        __hip_atomic_store(&xdst[2 * widx + lane], tag | (uint64_t)(uint32_t)(word >> (32 * lane)), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    sp = spn;
+    // ---- the whole layer's spike words of this step, from all S workgroups of the batch element ------------
+    if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
+      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      dead = true;
+    }
+    __syncthreads(); // every wavefront is done with the list of the previous step (words32 aliases nothing it reads)
+    for (int i = tid; i < 2 * Wd; i += 256) {
+      uint64_t e;
+      unsigned spins = 0;
+      for (;;) {
+        e = __hip_atomic_load(&xdst[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(e >> 32) == step + 1u || dead) break;
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          dead = true; // keep going to the end of the tile, never wait again
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      words32[i] = (uint32_t)e;
+    }
+    __syncthreads();
+    expand_all(words, Wd, list, cnt, tid, 256);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < NPT; ++k) state[(size_t)b * SN + off + c0 + 64 * k + lane] = v[k];
+}
+
 // A4: u_t = beta u_{t-1} + I_out,t ; usum += u_t over the steps of a tile (fp64 state: ubar feeds a
 // softmax, which turns an absolute error of ubar into a relative error of the loss gradient).
 __device__ __forceinline__ void readout_scan_body(const float *__restrict__ iout, double *__restrict__ readout, int B,
@@ -586,6 +782,8 @@ k_currents(NetDev net, CurJobs jobs) {
   // mode 0: recompute, I_in + I_rec of layer ca.lsel into the state slot of x_t
   // mode 1: forward, feed-forward current I_in of layer ca.lsel into a [step][B][N] tile
   // mode 2: forward, readout current sum of W_out rows of the last layer's spikes, [step][B][O] tile
+  // mode 3: recompute of a layer whose recurrent matrix is kept as compressed rows: I_in alone into the state slot
+  //         of x_t (k_currents_csr then adds I_rec)
   const int l = ca.lsel;
   int N, P, Wi, Wr;
   const float *W;
@@ -613,8 +811,9 @@ k_currents(NetDev net, CurJobs jobs) {
   __syncthreads();
   float a_in[NPT], a_rec[NPT];
   gather2<NPT>(W, N, (uint32_t)P, tid, nt, l_in, cnt[0], l_rec, cnt[1], a_in, a_rec);
-  float *dst = ca.mode == 0 ? ca.out + (size_t)(t - t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
-                            : ca.out + ((size_t)(t - t_base - 1) * B + b) * N;
+  float *dst = (ca.mode == 0 || ca.mode == 3)
+                   ? ca.out + (size_t)(t - t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
+                   : ca.out + ((size_t)(t - t_base - 1) * B + b) * N;
 #pragma unroll
   for (int k = 0; k < NPT; ++k) {
     const int n = tid + k * nt;
@@ -779,7 +978,7 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
     const int mm = m0 + 4 * (lane >> 4) + rr;
     if (mm >= rows) continue;
     const int t = ca.t0 + 1 + mm / B, b = mm % B;
-    float *dst = ca.mode == 0
+    float *dst = (ca.mode == 0 || ca.mode == 3)
                      ? ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
                      : ca.out + ((size_t)(t - ca.t_base - 1) * B + b) * N;
 #pragma unroll
@@ -901,7 +1100,7 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
       const int mm = m0 + 16 * mb + 4 * (lane >> 4) + rr;
       if (mm >= rows) continue;
       const int t = ca.t0 + 1 + mm / B, b = mm % B;
-      float *dst = ca.mode == 0
+      float *dst = (ca.mode == 0 || ca.mode == 3)
                        ? ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l]
                        : ca.out + ((size_t)(t - ca.t_base - 1) * B + b) * N;
 #pragma unroll
@@ -910,6 +1109,40 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
         if (c < N) dst[c] = acc0[mb][4 * q + rr];
       }
     }
+  }
+}
+
+// Recompute, recurrent part of layers with compressed rows: workgroup = one (t, b) row of the chunk and a span of
+// 4 sub-ranges (one per wavefront).  The state slot of x_t holds I_in on entry (a mode-3 job wrote it) and
+// I_in + I_rec on return: two separate sums, added once, as everywhere.
+__global__ void __launch_bounds__(256) k_currents_csr(NetDev net, CurJobs jobs) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const CurJob &ca = jobs.j[blockIdx.y];
+  const int B = net.B, l = ca.lsel, N = net.N[l], Wd = net.Wd[l + 1];
+  const int nsub = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW, nspan = (nsub + 3) >> 2;
+  if ((int)blockIdx.x >= ca.nsteps * B * nspan) return;
+  const int span = (int)blockIdx.x % nspan, m = (int)blockIdx.x / nspan;
+  const int t = ca.t0 + 1 + m / B, b = m % B;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint64_t *words = (uint64_t *)smem;                 // [Wd]
+  int *cnt = (int *)(words + Wd);                     // [1] (+3 pad)
+  float *acc = (float *)(cnt + 4);                    // [4][SNN_CSR_SUBW]
+  uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_SUBW); // [N rounded up to 8]
+  const uint64_t *g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * Wd;
+  for (int i = tid; i < Wd; i += 256) words[i] = g_rec[i];
+  for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) acc[i] = 0.0f;
+  if (tid == 0) *cnt = 0;
+  __syncthreads();
+  expand_all(words, Wd, list, cnt, tid, 256);
+  __syncthreads();
+  const int r = span * 4 + wave;
+  if (r < nsub)
+    csr_gather_wave(list, *cnt, net.csr_sub[l], nsub + 1, r, net.csr_col[l], net.csr_val[l], acc + wave * SNN_CSR_SUBW, lane);
+  __syncthreads();
+  float *dst = ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l];
+  for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) {
+    const int n = span * 4 * SNN_CSR_SUBW + i;
+    if (n < N) dst[n] = dst[n] + acc[i];
   }
 }
 
@@ -2409,7 +2642,45 @@ static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, 
   hipLaunchKernelGGL(k_currents_dense<SNN_DENSE_MB>, dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
   return hipGetLastError();
 }
+static hipError_t launch_currents_csr(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
+  if (jobs.count <= 0) return hipSuccess;
+  unsigned gx = 0;
+  size_t lds = 0;
+  for (int i = 0; i < jobs.count; ++i) {
+    const int l = jobs.j[i].lsel, N = net.N[l], nsub = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW;
+    const unsigned g = (unsigned)((size_t)jobs.j[i].nsteps * net.B * ((nsub + 3) >> 2));
+    gx = g > gx ? g : gx;
+    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2;
+    lds = b > lds ? b : lds;
+  }
+  hipLaunchKernelGGL(k_currents_csr, dim3(gx, jobs.count), dim3(256), lds, s, net, jobs);
+  return hipGetLastError();
+}
+static hipError_t launch_currents_plain(const NetDev &net, const CurJobs &jobs, hipStream_t s);
+// Does the recurrent part of a recompute job walk compressed rows?  Like the event-by-event gather it pays per
+// presynaptic spike (with a tenth of the bytes per spike at 10 % density), the dense matrix-core version per
+// presynaptic neuron: it takes over where the context's firing-rate policy picks the gather, i.e. for matrices far
+// beyond the L2 at low activity.  net.sel_csr == 2 forces it wherever compressed rows exist.
+static bool currents_job_csr(const NetDev &net, const CurJob &j) {
+  const int l = j.lsel;
+  if (!net.csr_sub[l]) return false;
+  if (net.sel_csr == 2) return true;
+  return (size_t)net.N[l] * net.N[l] * sizeof(float) >= ((size_t)32 << 20) && net.cur_pol[1][l] == 1;
+}
+// Recompute jobs (mode 0) of layers whose recurrent matrix has compressed rows are split: the feed-forward part
+// goes through the usual kernels (mode 3), the recurrent part through k_currents_csr behind them.
 static hipError_t launch_currents(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
+  CurJobs plain = jobs, cs{};
+  for (int i = 0; i < plain.count; ++i)
+    if (plain.j[i].mode == 0 && plain.j[i].nsteps > 0 && currents_job_csr(net, plain.j[i])) {
+      cs.j[cs.count++] = plain.j[i];
+      plain.j[i].mode = 3;
+    }
+  const hipError_t e = launch_currents_plain(net, plain, s);
+  if (e != hipSuccess) return e;
+  return launch_currents_csr(net, cs, s);
+}
+static hipError_t launch_currents_plain(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
   if (!currents_use_mfma(net)) return launch_currents_gather(net, jobs, s);
   CurJobs mf{}, dn{}, ga{};
   for (int i = 0; i < jobs.count; ++i)
@@ -2586,6 +2857,45 @@ static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, in
   return 1;
 }
 
+// The compressed-row version of the sliced sequential part: every job's layer has compressed rows, the same width
+// (a multiple of 4 SNN_CSR_SUBW), all workgroups of the launch are resident at once and the exchange buffer holds
+// the entries of every (job, batch element).  Returns the slices per batch element, 0 if it cannot run.
+static size_t seq_csr_lds(int N, int Wd) {
+  return (size_t)Wd * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2;
+}
+static int seq_csr_resident(int device, size_t lds) {
+  static int cached[16] = {};
+  if (device < 0 || device >= 16) return 0;
+  if (!cached[device]) {
+    hipDeviceProp_t prop;
+    int per_cu = 0;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_layer_seq_csr_sl, 256, lds) != hipSuccess) return 0;
+    cached[device] = per_cu * prop.multiProcessorCount;
+  }
+  return cached[device];
+}
+static int seq_csr_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, bool need_rows = true) {
+  if (!ws || !ws->xg || ga.count < 1 || net.sel_slices == 1) return 0;
+  // Measured at configuration 4 (5 % activity, 10 % density): 440 us per step against 253 us for the dense-stored
+  // walk, which runs at the memory's read rate with 32 KB rows while this one keeps too few bytes in flight
+  // (4 wavefronts per 2048 columns, 100-200 B per load).  Until that is cured it runs only when asked for.
+  if (need_rows && net.sel_csr != 2) return 0;
+  const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
+  if (N % (4 * SNN_CSR_SUBW) != 0) return 0;
+  int n_wide = 0;
+  for (int l = 0; l < net.L; ++l) n_wide += net.N[l] > 256;
+  for (int i = 0; i < ga.count; ++i)
+    if (net.N[ga.j[i].l] != N || (need_rows && !net.csr_sub[ga.j[i].l])) return 0;
+  if ((size_t)n_wide * net.B * 4 * Wd * sizeof(uint64_t) > (size_t)ws->xg_stride * SNN_MAXL * sizeof(float)) return 0;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return 0;
+  // LDS of the widest layer the kernel can meet on this device (the occupancy is queried once, outside any capture)
+  const int S = N / (4 * SNN_CSR_SUBW);
+  if (S * net.B * n_wide > seq_csr_resident(device, seq_csr_lds(8192, 128))) return 0;
+  return S;
+}
+
 hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, float *state, const StoreSpec &st,
                           double *readout, int readout_init, float *work, hipStream_t s, const SpanHook *hook,
                           const FwdCallbacks *cb, const WsArgs *ws) {
@@ -2677,8 +2987,16 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
         else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
       }
       int npt_sl = 0, th_sl = 0;
-      const int S = ga.count ? seq_slices(net, ga, ws, &npt_sl, &th_sl) : 1;
-      if (ga.count && S > 1) {
+      const int S_csr = ga.count ? seq_csr_slices(net, ga, ws) : 0;
+      const int S = (ga.count && !S_csr) ? seq_slices(net, ga, ws, &npt_sl, &th_sl) : 1;
+      if (S_csr) {
+        // tags of the exchange entries start from zero in every launch
+        e = launch_fill_zero(ws->xg, (size_t)ga.count * B * 4 * net.Wd[ga.j[0].l + 1] * sizeof(uint64_t), s);
+        if (e != hipSuccess) return e;
+        const int Nc = net.N[ga.j[0].l];
+        hipLaunchKernelGGL(k_layer_seq_csr_sl, dim3(B * S_csr, ga.count), dim3(256), seq_csr_lds(Nc, net.Wd[ga.j[0].l + 1]), s,
+                           net, ga, state, st, S_csr, reinterpret_cast<uint64_t *>(ws->xg), ws->err, ws->spin_limit);
+      } else if (ga.count && S > 1) {
         // tags of the exchange entries start from zero in every launch
         e = launch_fill_zero(ws->xg, (size_t)ga.count * B * 4 * net.Wd[ga.j[0].l + 1] * sizeof(uint64_t), s);
         if (e != hipSuccess) return e;
@@ -2883,6 +3201,7 @@ void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
       probe.count = 1;
       int npt = 0, th = 0;
       (void)seq_slices(net, probe, &ws, &npt, &th);
+      (void)seq_csr_slices(net, probe, &ws, false);
     }
 }
 static hipError_t launch_adj_wide(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s) {

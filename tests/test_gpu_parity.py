@@ -713,3 +713,66 @@ def test_config4_widths_short():
     streamed adjoint kernel, masked gradients."""
     w = synth.config(4, T=6, B=2)
     _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 4, 2)], nthreads=2, check_states=True)
+
+
+@pytest.mark.parametrize("hidden,B,T,density,gain", [((1024,), 5, 30, 0.1, 1.0), ((600, 1100), 3, 24, 0.3, 0.8),
+                                                     ((2048,), 3, 20, 0.1, 1.0), ((4096, 4096), 2, 10, 0.1, 1.0), ((96, 96), 4, 40, 0.2, 0.8),
+                                                     ((1536,), 2, 16, 0.9, 0.5)])
+def test_compressed_rows_of_masked_matrices_are_bitwise_neutral(hidden, B, T, density, gain, monkeypatch):
+    """A masked recurrent matrix is also kept as compressed rows (only the synapses that exist), and the kernels
+    that gather its rows walk those (recompute; from 2048 neurons also the sequential part of the forward pass).
+    Adding +0.0f where no synapse exists changes nothing, so spike trains, membrane potentials -- the forward
+    pass's and the recomputed ones -- and gradients must be the very bits of the dense-stored walk (SNN_CSR=0), and
+    match the oracle.  Widths: one sub-range, several, a ragged last one, a row with more than 64 entries in a
+    sub-range (density 0.9), and a layer narrow enough for the register-stationary kernels (which ignore the
+    compressed form)."""
+    w = synth.Workload("csr_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=gain,
+                       rec_density=density, seed=51 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    got = {}
+    for csr in ("1", "0"):
+        monkeypatch.setenv("SNN_CSR", csr)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            states = net.snn_debug_states(w.T)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)
+            recomputed = [net.snn_get_state(l, t) for l in range(L) for t in (1, w.T // 2, w.T)]
+            got[csr] = (_gpu_grads(net, L), [net.snn_get_spikes(l, w.T) for l in range(L)], states, recomputed)
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_CSR")
+    assert _identical(got["1"][0], got["0"][0])
+    for a, b in zip(got["1"][1], got["0"][1]):
+        assert np.array_equal(a, b) and a.sum() > 0
+    assert np.array_equal(got["1"][2].view(np.uint32), got["0"][2].view(np.uint32))
+    for a, b in zip(got["1"][3], got["0"][3]):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3), (snn.SNN_CHUNK, 0, 5)], nthreads=4,
+                 probe_states=[(L - 1, w.T), (0, 2)])
+
+
+def test_compressed_rows_keep_denormal_sums():
+    """Weights so small that every synaptic sum is a denormal number: the compressed-row walk accumulates with LDS
+    add instructions, which must round and keep denormals exactly like the vector adds of the dense-stored walk
+    and like the oracle.  Nobody fires (potentials around 1e-38), so the check is on the membrane potentials."""
+    w = synth.Workload("csr_denormal_40-1024-6", 40, (1024,), 6, T=12, B=3, p_in=0.2, gain=1.0, rec_density=0.2, seed=77)
+    d = synth.generate(w)
+    d["W_in"] = [np.float32(3e-39) * np.sign(a) * (1 + np.arange(a.size, dtype=np.float32).reshape(a.shape) % 7) for a in d["W_in"]]
+    d["W_rec"] = [(np.float32(1e-39) * np.sign(a) * (1 + np.arange(a.size, dtype=np.float32).reshape(a.shape) % 5)).astype(np.float32)
+                  * d["rec_mask"][l] for l, a in enumerate(d["W_rec"])]
+    ref = _oracle(w, d, want_v=True, backward=False, forced_spikes=None)
+    assert 0 < np.abs(ref.v[0]).max() < 1e-35 and (np.abs(ref.v[0][ref.v[0] != 0]) < 1.1754944e-38).any()
+    # the recurrent walk needs spikes: force a spike train through the micro-benchmark entry, then rebuild states
+    hid = synth.forced_spike_trains(w, [0.1])
+    ref_forced = _oracle(w, d, want_v=True, backward=False, forced_spikes=[h.astype(np.float32) for h in hid])
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_forward(d["in_spikes"], d["labels"], w.T)
+        assert np.array_equal(net.snn_debug_states(w.T)[:, :, :1024].view(np.uint32), ref.v[0].view(np.uint32))
+        net.snn_debug_currents(hid, 4)  # replaces the stored hidden spike train
+        for t in (2, 7, 12):
+            assert np.array_equal(net.snn_get_state(0, t).view(np.uint32), ref_forced.v[0][t - 1].view(np.uint32)), t
+    finally:
+        net.snn_destroy()
