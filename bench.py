@@ -130,6 +130,8 @@ def main():
     ap.add_argument("--model-sweep", action="store_true",
                     help="largest hidden width per strategy at fixed T and HBM budget (use with --T and --budget-mb)")
     ap.add_argument("--budget-mb", type=float, default=200.0)
+    ap.add_argument("--surr-window", type=float, default=0.0,
+                    help="surrogate window w (not in the paper): derivative cut to 0 where |v - theta| >= w; <= 0: none")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -206,7 +208,7 @@ def main():
     y = torch.from_numpy(d["labels"]).to(dev)
     if args.host_inputs:  # the library copies them to the device inside snn_bind_inputs, every step
         x, y = d["in_spikes"], d["labels"]
-    net = snn.from_workload(w, d)  # stream = None: the library runs on a stream of its own
+    net = snn.from_workload(w, d, surr_window=args.surr_window)  # stream = None: the library runs on a stream of its own
     params = dict(STRATEGY_PARAMS[args.config])
     if args.coarse >= 0 or args.fine >= 0:
         c0, f0 = params[args.strategy]
@@ -543,7 +545,7 @@ def main():
                    "hbm_activation_bytes_min": int(snn.snn_bytes_required(net.cfg, SID[args.strategy], w.T, C, F)),
                    "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots,
                    "state_slots_hbm_allocated": int(st.local_state_slots), "state_slots_host": rslots,
-                   "recurrent_density": w.rec_density,
+                   "recurrent_density": w.rec_density, "surrogate_window": args.surr_window,
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
                    "other_strategies_neuron_timesteps_per_s": others},
         "roofline": roofline, "cpu_baseline": cpu, "host_link": host_link, "long_sequence": long_seq,

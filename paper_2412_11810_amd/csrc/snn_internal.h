@@ -25,6 +25,9 @@ struct NetDev {
   const float *W_in[SNN_MAXL], *W_rec[SNN_MAXL], *W_out;
   const float *W_inT[SNN_MAXL], *W_recT[SNN_MAXL], *W_outT;
   uint64_t *mask[SNN_MAXL + 1];
+  // > 0: mask[l] holds only a window of the sequence, as a ring of that many steps (row = step modulo the ring);
+  // the rest of the spike trains is in pinned host memory and travels per coarse segment.  0: all T + 1 rows.
+  int mring[SNN_MAXL + 1];
   // Compressed rows of a masked recurrent matrix (NULL: the layer has no mask, or its compressed form is switched
   // off): the existing synapses of presynaptic neuron j, ascending in the postsynaptic index, are entries
   // csr_sub[l][j * (nsub + 1) + 0] .. csr_sub[l][j * (nsub + 1) + nsub] of csr_col[l] (16-bit postsynaptic index)
@@ -42,7 +45,9 @@ struct NetDev {
   unsigned char cur_pol[2][SNN_MAXL];
   // Kernel selection forced from outside (test hooks; 0 = the library's own choice).  Every choice gives the same
   // bits.  sel_currents: 1 event-by-event gather, 2 list version on the matrix cores, 3 dense version.
-  // sel_adjoint: 1 VALU version of the chip-wide recurrence, 2 one-workgroup-per-batch-element streaming kernel.
+  // sel_adjoint: 1 VALU version of the chip-wide recurrence, 2 one-workgroup-per-batch-element streaming kernel,
+  // 3 event-driven rows (neurons inside the surrogate window only), 4 the same kernel evaluating every row, 5 the
+  // chip-wide kernels also under a surrogate window.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
   unsigned char sel_csr; // compressed rows of masked recurrent matrices: 1 never used (dense-stored walk everywhere),
@@ -155,7 +160,7 @@ void adjoint_prepare(const NetDev &net, const WsArgs &ws); // occupancy queries 
 // element) and column offset post_off.
 hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,
                      size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1,
-                     int t_base, double *dW, hipStream_t s);
+                     int t_base, double *dW, hipStream_t s, int pre_ring = 0);
 // One weight matrix of the dense dW contraction (see k_dw_mfma).
 struct DwDesc {
   const uint64_t *pre_mask; // spike words of the presynaptic layer, [T+1][B][pre_words]
@@ -168,6 +173,7 @@ struct DwDesc {
   int t0, t1, t_base;       // steps t1, ..., t0+1
   int skip_empty;           // test for K-steps without a spike (pays for sparse presynaptic layers only)
   int tile0, tiles_n;       // filled by the launcher
+  int pre_ring;             // > 0: pre_mask holds a ring of that many steps (row = step modulo the ring)
 };
 struct DwBatch {
   DwDesc d[2 * SNN_MAXL + 1];

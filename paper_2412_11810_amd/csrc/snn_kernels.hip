@@ -23,6 +23,12 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
 static __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+// Row of the stored spike words of layer index li that holds step t: the rows form a ring in time when only a
+// window of the sequence is kept in HBM (net.mring[li] rows; the rest lives in host memory), otherwise row t.
+static __device__ __forceinline__ size_t mrow_of(const NetDev &net, int li, int t) {
+  const int r = net.mring[li];
+  return (size_t)(r > 0 ? t % r : t);
+}
 
 // acc = fma(x[lane n of the own 16-lane row], w[n], acc) for n = 0..15, one VOP2 instruction each:
 // the DPP row broadcast (row_newbcast:n) feeds lane n of every row to all 16 lanes of that row, so a
@@ -278,7 +284,7 @@ __device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJo
   float v = own ? state[(size_t)b * SN + off + i] : 0.0f;
   uint64_t *mrow = net.mask[l + 1] + (size_t)b * Wd + wave;
   const size_t mstride = (size_t)B * Wd;
-  if (i < NWD) sw[0][i] = i < Wd ? net.mask[l + 1][(size_t)t0 * mstride + (size_t)b * Wd + i] : 0ull;
+  if (i < NWD) sw[0][i] = i < Wd ? net.mask[l + 1][mrow_of(net, l + 1, t0) * mstride + (size_t)b * Wd + i] : 0ull;
   __syncthreads();
   bool sprev = (sw[0][wave] >> lane) & 1ull;
   int cur = 0;
@@ -328,7 +334,7 @@ __device__ __forceinline__ void layer_seq_rs_body(const NetDev &net, const SeqJo
       const uint64_t word = __ballot(sprev);
       if (lane == 0) {
         sw[cur ^ 1][wave] = word;
-        if (wave < Wd) mrow[(size_t)t * mstride] = word;
+        if (wave < Wd) mrow[mrow_of(net, l + 1, t) * mstride] = word;
       }
       const int sl = sc.slot(st, t);
       if (own && sl >= 0) st.base[(size_t)sl * st.slot_stride + (size_t)b * SN + off + i] = v;
@@ -377,7 +383,7 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
     const int n = tid + k * nt, widx = n >> 6;
     v[k] = n < N ? state[(size_t)b * SN + off + n] : 0.0f;
     if (widx < Wd) {
-      const uint64_t word = mbase[(size_t)t0 * mstride + widx];
+      const uint64_t word = mbase[mrow_of(net, l + 1, t0) * mstride + widx];
       if (lane == 0) words[widx] = word;
       if ((word >> lane) & 1ull) sp |= 1u << k;
     }
@@ -416,7 +422,7 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
           st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + n] = vn;
         if (lane == 0) { // the words are only read by the list expansion, after the barrier
           words[widx] = word;
-          mbase[(size_t)t * mstride + widx] = word;
+          mbase[mrow_of(net, l + 1, t) * mstride + widx] = word;
         }
       }
     }
@@ -468,7 +474,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
 #pragma unroll
   for (int k = 0; k < NPT; ++k) coff[k] = (uint32_t)(tid + k * nt) * 4u;
   if (tid == 0) *cnt = 0;
-  for (int i = tid; i < Wd; i += nt) words[i] = mbase[(size_t)t0 * mstride + i];
+  for (int i = tid; i < Wd; i += nt) words[i] = mbase[mrow_of(net, l + 1, t0) * mstride + i];
   __syncthreads();
   float v[NPT];
   uint32_t sp = 0;
@@ -508,7 +514,7 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
       const uint64_t word = __ballot(vn > net.theta);
       if ((word >> lane) & 1ull) spn |= 1u << k;
       if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + nl] = vn;
-      if (lane == 0) mbase[(size_t)t * mstride + widx] = word;
+      if (lane == 0) mbase[mrow_of(net, l + 1, t) * mstride + widx] = word;
       if (lane < 2)
         __hip_atomic_store(&xdst[2 * widx + lane], tag | (uint64_t)(uint32_t)(word >> (32 * lane)), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
@@ -660,7 +666,7 @@ k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   const uint16_t *__restrict__ col = net.csr_col[l];
   const float *__restrict__ val = net.csr_val[l];
   if (tid == 0) *cnt = 0;
-  for (int i = tid; i < Wd; i += 256) words[i] = mbase[(size_t)t0 * mstride + i];
+  for (int i = tid; i < Wd; i += 256) words[i] = mbase[mrow_of(net, l + 1, t0) * mstride + i];
   __syncthreads();
   float v[NPT];
   uint32_t sp = 0;
@@ -703,7 +709,7 @@ k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
       const uint64_t word = __ballot(vn > net.theta);
       if ((word >> lane) & 1ull) spn |= 1u << k;
       if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + 64 * k + lane] = vn;
-      if (lane == 0) mbase[(size_t)t * mstride + widx] = word;
+      if (lane == 0) mbase[mrow_of(net, l + 1, t) * mstride + widx] = word;
       if (lane < 2)
         __hip_atomic_store(&xdst[2 * widx + lane], tag | (uint64_t)(uint32_t)(word >> (32 * lane)), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
@@ -790,12 +796,12 @@ k_currents(NetDev net, CurJobs jobs) {
   const uint64_t *g_in, *g_rec = nullptr;
   if (ca.mode == 2) {
     N = net.n_out; P = net.N[net.L - 1]; Wi = net.Wd[net.L]; Wr = 0; W = net.W_out;
-    g_in = net.mask[net.L] + ((size_t)t * B + b) * Wi;
+    g_in = net.mask[net.L] + (mrow_of(net, net.L, t) * B + b) * Wi;
   } else {
     N = net.N[l]; P = l == 0 ? net.n_in : net.N[l - 1]; Wi = net.Wd[l]; Wr = ca.mode == 0 ? net.Wd[l + 1] : 0;
     W = net.W_in[l];
-    g_in = net.mask[l] + ((size_t)t * B + b) * Wi;
-    g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * net.Wd[l + 1];
+    g_in = net.mask[l] + (mrow_of(net, l, t) * B + b) * Wi;
+    g_rec = net.mask[l + 1] + (mrow_of(net, l + 1, t - 1) * B + b) * net.Wd[l + 1];
   }
   uint64_t *w_in = (uint64_t *)smem;       // [Wi]
   uint64_t *w_rec = w_in + Wi;             // [Wr]
@@ -909,7 +915,7 @@ __device__ __forceinline__ void currents_mfma_body(const NetDev &net, const CurJ
   const uint64_t *g = nullptr;
   if (m < rows) {
     const int t = ca.t0 + 1 + m / B, b = m % B;
-    g = net.mask[pl] + ((size_t)(part == 0 ? t : t - 1) * B + b) * Wp;
+    g = net.mask[pl] + (mrow_of(net, pl, part == 0 ? t : t - 1) * B + b) * Wp;
   }
   uint64_t *words = (uint64_t *)smem + (size_t)wave * 16 * ws;              // [16][ws]
   // per wavefront: lcap 32-bit entries for the stream.  The list of indices as it is built (16 bits each) sits in
@@ -1073,7 +1079,7 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
       uint64_t v = 0ull;
       if (m < rows) {
         const int t = ca.t0 + 1 + m / B, b = m % B;
-        v = net.mask[pl][((size_t)(part == 0 ? t : t - 1) * B + b) * Wp + wi];
+        v = net.mask[pl][(mrow_of(net, pl, part == 0 ? t : t - 1) * B + b) * Wp + wi];
         const int rem = P - wi * 64;
         if (rem < 64) v &= rem <= 0 ? 0ull : (1ull << rem) - 1ull;
       }
@@ -1128,7 +1134,7 @@ __global__ void __launch_bounds__(256) k_currents_csr(NetDev net, CurJobs jobs) 
   int *cnt = (int *)(words + Wd);                     // [1] (+3 pad)
   float *acc = (float *)(cnt + 4);                    // [4][SNN_CSR_SUBW]
   uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_SUBW); // [N rounded up to 8]
-  const uint64_t *g_rec = net.mask[l + 1] + ((size_t)(t - 1) * B + b) * Wd;
+  const uint64_t *g_rec = net.mask[l + 1] + (mrow_of(net, l + 1, t - 1) * B + b) * Wd;
   for (int i = tid; i < Wd; i += 256) words[i] = g_rec[i];
   for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) acc[i] = 0.0f;
   if (tid == 0) *cnt = 0;
@@ -1197,7 +1203,7 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
 #pragma unroll
     for (int r = 0; r < U; ++r) {
       cur[r] = col[(size_t)(t + r - t_base - 1) * slot_stride];
-      wd[r] = mcol[(size_t)(t + r - 1) * mstride];
+      wd[r] = mcol[mrow_of(net, l + 1, t + r - 1) * mstride];
     }
 #pragma unroll
     for (int r = 0; r < U; ++r) {
@@ -1209,7 +1215,7 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
   }
   for (; t <= t1; ++t) {
     const float cur = col[(size_t)(t - t_base - 1) * slot_stride];
-    const uint64_t wd = mcol[(size_t)(t - 1) * mstride];
+    const uint64_t wd = mcol[mrow_of(net, l + 1, t - 1) * mstride];
     float a = net.alpha * v;
     if ((wd >> sh) & 1ull) a = a - net.theta;
     v = a + cur;
@@ -2110,6 +2116,176 @@ k_adj_rec_stream(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, in
   for (int i = tid; i < N; i += NT) cb[i] = x_next[i];
 }
 
+// B3/B4 under a surrogate window, event-driven (layers wider than 256 neurons; one workgroup per batch element).
+// With a window w > 0 the surrogate derivative is zero for every neuron whose potential is at least w away from
+// the threshold; for those dv_t = fma(ds, 0, alpha dv_{t+1}) = alpha dv_{t+1} whatever ds is, so the row of
+// W_rec . dv_{t+1} that would give ds is never evaluated.  Per step the workgroup (a) classifies its neurons from
+// the stored v_t, finishes the ones outside the window at once and compacts the others into an ascending list
+// (ballot, popcount prefix: the spike compaction of the forward pass applied to |v - theta| < w), (b) evaluates the
+// listed rows only, one wavefront per row: lane-strided products accumulated in index order, then a butterfly sum
+// over the lanes -- an order that depends on the row alone, so listing every row (list_all, the dense form of the
+// very same kernel) gives the same bits for the rows inside the window.  A masked recurrent matrix is read through
+// its compressed rows: only the synapses that exist.  dv_{t+1} of the batch element stays in LDS.
+__global__ void __launch_bounds__(1024)
+k_adj_rec_rows(NetDev net, AdjJobs jobs, float *__restrict__ carry, int list_all) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int wcnt[16];
+  const AdjJob &jb = jobs.j[blockIdx.y];
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  const int tid = threadIdx.x, NT = blockDim.x, b = blockIdx.x, lane = tid & 63, wave = tid >> 6, NW = NT >> 6;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, ldu = N;
+  float *xa = (float *)smem;                 // [N]
+  float *xb = xa + N;                        // [N]
+  uint16_t *list = (uint16_t *)(xb + N);     // [N]
+  float *cb = carry + (size_t)b * (SN + net.n_out) + off;
+  for (int i = tid; i < N; i += NT) { xa[i] = jb.carry_init ? 0.0f : cb[i]; xb[i] = 0.0f; }
+  __syncthreads();
+  float *x_next = xa, *x_cur = xb;
+  const float *__restrict__ Wl = net.W_rec[l];
+  const uint32_t *__restrict__ sub = net.csr_sub[l];
+  const uint16_t *__restrict__ col = net.csr_col[l];
+  const float *__restrict__ val = net.csr_val[l];
+  const int nsub1 = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW + 1;
+  const bool vec4 = (N & 3) == 0;
+  for (int t = t1; t > t0; --t) {
+    const size_t slot = (size_t)(t - t_base - 1);
+    float *vrow = vbuf + slot * ((size_t)B * SN) + (size_t)b * SN + off;
+    const float *urow = up + (slot * B + b) * ldu;
+    // (a) classify, finish the neurons outside the window, list the others in ascending order
+    int cnt = 0;
+    for (int j0 = 0; j0 < N; j0 += NT) {
+      const int j = j0 + tid;
+      bool inside = false;
+      if (j < N) {
+        const float vt = vrow[j];
+        inside = list_all || !(net.win > 0.0f) || fabsf(vt - net.theta) < net.win;
+        if (!inside) {
+          const float dvt = net.alpha * x_next[j];
+          x_cur[j] = dvt;
+          vrow[j] = dvt;
+        }
+      }
+      const uint64_t m = __ballot(inside);
+      if (lane == 0) wcnt[wave] = __popcll(m);
+      __syncthreads();
+      int before = 0, total = 0;
+      for (int q = 0; q < NW; ++q) {
+        const int c = wcnt[q];
+        before += q < wave ? c : 0;
+        total += c;
+      }
+      if (inside) list[cnt + before + __popcll(m & lanemask_lt())] = (uint16_t)j;
+      cnt += total;
+      __syncthreads();
+    }
+    // (b) the listed rows, one wavefront per row (rows wave, wave + NW, ... of the list)
+    auto finish = [&](int j, float a0, float a1) {
+      float sacc = a0 + a1;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) sacc = sacc + __shfl_xor(sacc, o, WAVE);
+      if (lane == 0) {
+        const float dn = x_next[j];
+        const float ds = (sacc + urow[j]) - net.theta * dn;
+        const float dvt = fmaf(ds, surrogate(net, vrow[j]), net.alpha * dn);
+        x_cur[j] = dvt;
+        vrow[j] = dvt;
+      }
+    };
+    if (sub) {
+      // compressed rows: the positions of this wavefront's next 64 rows are fetched at once (one row per lane); the
+      // entries of a row (up to CH x 64 per pass) are all in flight before the first product, and the next row's
+      // are requested before this row's products start
+      constexpr int CH = 16;
+      const int mine = cnt > wave ? (cnt - wave + NW - 1) / NW : 0; // rows of this wavefront
+      struct Row { float w[CH]; uint32_t c[CH]; };
+      auto fetch = [&](Row &r, uint32_t eb, uint32_t e1) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+          const uint32_t e = eb + (uint32_t)(WAVE * i + lane);
+          const bool ok = e < e1;
+          r.w[i] = ok ? val[e] : 0.0f;
+          r.c[i] = ok ? (uint32_t)col[e] : 0u;
+        }
+      };
+      auto mac = [&](const Row &r, float &a0, float &a1) {
+#pragma unroll
+        for (int i = 0; i < CH; i += 2) {
+          a0 = fmaf(r.w[i], x_next[r.c[i]], a0);
+          a1 = fmaf(r.w[i + 1], x_next[r.c[i + 1]], a1);
+        }
+      };
+      for (int rb = 0; rb < mine; rb += WAVE) {
+        uint32_t m0 = 0u, m1 = 0u;
+        int mj = 0;
+        if (rb + lane < mine) {
+          mj = list[wave + NW * (rb + lane)];
+          m0 = sub[(size_t)mj * nsub1];
+          m1 = sub[(size_t)mj * nsub1 + nsub1 - 1];
+        }
+        const int nr = mine - rb < WAVE ? mine - rb : WAVE;
+        Row ra, rbuf;
+        fetch(ra, __builtin_amdgcn_readlane(m0, 0), __builtin_amdgcn_readlane(m1, 0));
+        for (int q = 0; q < nr; ++q) {
+          const uint32_t e0 = __builtin_amdgcn_readlane(m0, q), e1 = __builtin_amdgcn_readlane(m1, q);
+          const int j = __builtin_amdgcn_readlane(mj, q);
+          const int qn = q + 1 < nr ? q + 1 : q; // past the end: the same row again, never used
+          __builtin_amdgcn_sched_barrier(0);
+          fetch(rbuf, __builtin_amdgcn_readlane(m0, qn), __builtin_amdgcn_readlane(m1, qn));
+          __builtin_amdgcn_sched_barrier(0);
+          float a0 = 0.0f, a1 = 0.0f;
+          mac(ra, a0, a1);
+          for (uint32_t eb = e0 + CH * WAVE; eb < e1; eb += CH * WAVE) { // rows longer than one pass
+            Row more;
+            fetch(more, eb, e1);
+            mac(more, a0, a1);
+          }
+          finish(j, a0, a1);
+          ra = rbuf;
+        }
+      }
+    } else {
+      for (int idx = wave; idx < cnt; idx += NW) {
+        const int j = list[idx];
+        float a0 = 0.0f, a1 = 0.0f;
+        if (vec4) {
+          const float4 *wr = reinterpret_cast<const float4 *>(Wl + (size_t)j * N);
+          const float4 *xr = reinterpret_cast<const float4 *>(x_next);
+          const int n4 = N >> 2;
+          for (int i0 = 0; i0 < n4; i0 += 8 * WAVE) { // 8 loads of 16 bytes in flight per lane
+            float4 wv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              const int i = i0 + u * WAVE + lane;
+              wv[u] = i < n4 ? wr[i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              const int i = i0 + u * WAVE + lane;
+              const float4 xv = xr[i < n4 ? i : 0];
+              float &a = (u & 1) ? a1 : a0;
+              a = fmaf(wv[u].x, xv.x, a); a = fmaf(wv[u].y, xv.y, a); a = fmaf(wv[u].z, xv.z, a); a = fmaf(wv[u].w, xv.w, a);
+            }
+          }
+        } else {
+          const float *wr = Wl + (size_t)j * N;
+          int n = lane;
+          for (; n + WAVE < N; n += 2 * WAVE) {
+            a0 = fmaf(wr[n], x_next[n], a0);
+            a1 = fmaf(wr[n + WAVE], x_next[n + WAVE], a1);
+          }
+          if (n < N) a0 = fmaf(wr[n], x_next[n], a0);
+        }
+        finish(j, a0, a1);
+      }
+    }
+    __syncthreads();
+    float *tmp = x_next; x_next = x_cur; x_cur = tmp;
+  }
+  for (int i = tid; i < N; i += NT) cb[i] = x_next[i];
+}
+
 // ------------------------------------------------------------------------------------------
 // B5: weight gradient over active spikes.  One workgroup per presynaptic row j (x column tile);
 // dW[j][:] += sum_{t = t1..t0+1 desc} sum_{b asc} [spike(t - lag, b, j)] * post(t, b, :)
@@ -2122,7 +2298,7 @@ k_adj_rec_stream(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, in
 __global__ void __launch_bounds__(256)
 k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float *__restrict__ postbuf,
      size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1, int t_base,
-     double *__restrict__ dW) {
+     double *__restrict__ dW, int pre_ring) {
   const int j = blockIdx.x;
   const int c0 = blockIdx.y * (256 * DW_NPT) + threadIdx.x;
   double acc[DW_NPT];
@@ -2134,8 +2310,8 @@ k_dw(const uint64_t *__restrict__ pre_mask, int pre_words, int lag, const float 
   const int wj = j >> 6;
   const uint64_t bit = 1ull << (j & 63);
   for (int t = t1; t > t0; --t) {
-    const int tp = t - lag; // row 0 of the mask (t = 0) is all zero
-    const uint64_t *mrow = pre_mask + (size_t)tp * B * pre_words + wj;
+    const int tp = t - lag; // step 0 of the mask is all zero
+    const uint64_t *mrow = pre_mask + (size_t)(pre_ring > 0 ? tp % pre_ring : tp) * B * pre_words + wj;
     const float *prow = postbuf + (size_t)(t - t_base - 1) * slot_stride + post_off;
     for (int b = 0; b < B; ++b) {
       if (mrow[(size_t)b * pre_words] & bit) {
@@ -2242,7 +2418,8 @@ __device__ __forceinline__ void dw_mfma_body(const DwBatch &batch, int B, int vb
     {
       const int ts = tid / Bp, b = tid - ts * Bp;
       const bool ok = tid < ROWS && ts < nts && b < B;
-      wreg = d.pre_mask[((size_t)(t_hi - (ok ? ts : 0) - d.lag) * B + (ok ? b : 0)) * d.pre_words + (j0 >> 6)];
+      const int tt = t_hi - (ok ? ts : 0) - d.lag; // its row of the stored spike words (a ring in time if d.pre_ring > 0)
+      wreg = d.pre_mask[((size_t)(d.pre_ring > 0 ? tt % d.pre_ring : tt) * B + (ok ? b : 0)) * d.pre_words + (j0 >> 6)];
     }
   };
   auto stage_store = [&](int buf, int nts, const float (&reg)[NPASS][4], uint64_t wreg) {
@@ -3241,6 +3418,24 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
     const AdjJob &jb = jobs.j[i];
     const int l = jb.l, N = net.N[l];
     if (N <= 256 || taken[i]) continue;
+    // Event-driven rows under a surrogate window: layers wider than 1024 (the streamed kernels pay for every row
+    // of the matrix every step), or wherever the hook asks (3: listed rows, 4: the same kernel listing every row)
+    if (net.sel_adjoint == 3 || net.sel_adjoint == 4 || (net.sel_adjoint == 0 && net.win > 0.0f && N > 1024)) {
+      AdjJobs grp{};
+      for (int k = i; k < jobs.count; ++k)
+        if (!taken[k] && net.N[jobs.j[k].l] == N) {
+          grp.j[grp.count++] = jobs.j[k];
+          taken[k] = true;
+        }
+      const size_t lds = (size_t)2 * N * sizeof(float) + (size_t)((N + 7) & ~7) * sizeof(uint16_t);
+      if (lds > 48 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_rows),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL(k_adj_rec_rows, dim3(B, grp.count), dim3(1024), lds, s, net, grp, carry, net.sel_adjoint == 4 ? 1 : 0);
+      continue;
+    }
     if (N <= 1024 && ws.xg && ws_use_mfma(net) && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
       // matrix-core version: workgroup = 32 rows x 16 batch elements
       const int G_b = (B + 15) / 16, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
@@ -3332,11 +3527,11 @@ int ws_max_resident_groups(int device) {
 
 hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag, const float *postbuf,
                      size_t slot_stride, int post_stride, int post_off, int n_post, int B, int t0, int t1,
-                     int t_base, double *dW, hipStream_t s) {
+                     int t_base, double *dW, hipStream_t s, int pre_ring) {
   if (t1 <= t0) return hipSuccess;
   const dim3 grid(n_pre, (n_post + 256 * DW_NPT - 1) / (256 * DW_NPT));
   hipLaunchKernelGGL(k_dw, grid, dim3(256), 0, s, pre_mask, pre_words, lag, postbuf, slot_stride, post_stride,
-                     post_off, n_post, B, t0, t1, t_base, dW);
+                     post_off, n_post, B, t0, t1, t_base, dW, pre_ring);
   return hipGetLastError();
 }
 

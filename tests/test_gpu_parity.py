@@ -776,3 +776,44 @@ def test_compressed_rows_keep_denormal_sums():
             assert np.array_equal(net.snn_get_state(0, t).view(np.uint32), ref_forced.v[0][t - 1].view(np.uint32)), t
     finally:
         net.snn_destroy()
+
+
+@pytest.mark.parametrize("hidden,B,T,density,window", [((1088,), 5, 14, 1.0, 0.4), ((2048, 1100), 3, 12, 0.15, 0.5),
+                                                      ((300, 1026), 4, 10, 1.0, 0.3)])
+def test_event_driven_adjoint_under_the_surrogate_window(hidden, B, T, density, window, monkeypatch):
+    """With a surrogate window only the neurons whose potential is inside it have a non-zero spike derivative; the
+    adjoint kernel for wide layers under a window lists those neurons from the stored potentials (ballot + popcount
+    prefix) and evaluates only their rows of W_rec . dv -- compressed rows for a masked matrix.  Checked: against
+    the oracle with the same window; bit-identical to the same kernel evaluating every row (SNN_WS_KERNEL=rows_all);
+    within the gradient tolerance of the chip-wide kernels with the same window (SNN_WS_KERNEL=chip); and the list
+    really is short (the fraction of neurons inside the window is printed)."""
+    w = synth.Workload("win_rows_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=0.7,
+                       rec_density=density, seed=61 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    got = {}
+    for mode in ("rows", "rows_all", "chip", None):
+        if mode is None:
+            monkeypatch.delenv("SNN_WS_KERNEL", raising=False)
+        else:
+            monkeypatch.setenv("SNN_WS_KERNEL", mode)
+        net = snn.from_workload(w, d, surr_window=window)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)
+            got[mode] = _gpu_grads(net, L)
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_WS_KERNEL", raising=False)
+    assert _identical(got["rows"], got["rows_all"])
+    flat = lambda g: list(g[0]) + list(g[1]) + [g[2]]
+    for a, b in zip(flat(got["rows"]), flat(got["chip"])):
+        scale = float(np.max(np.abs(b))) or 1.0
+        assert float(np.max(np.abs(a - b))) <= 1e-4 * scale
+    if max(hidden) > 1024 and min(hidden) > 1024:
+        assert _identical(got[None], got["rows"])  # the library's own choice for wide layers under a window
+    first, ref = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3), (snn.SNN_CHUNK, 0, 5)], nthreads=4,
+                              window=window)
+    inside = [float((np.abs(v - w.theta) < window).mean()) for v in ref.v]
+    print(f"[{w.name}] fraction of (t, b, neuron) inside the window of {window}: {[round(x, 4) for x in inside]}")
+    assert all(0.0 < x < 0.5 for x in inside)
