@@ -130,6 +130,8 @@ def main():
     ap.add_argument("--model-sweep", action="store_true",
                     help="largest hidden width per strategy at fixed T and HBM budget (use with --T and --budget-mb)")
     ap.add_argument("--budget-mb", type=float, default=200.0)
+    ap.add_argument("--spike-tier", type=int, default=0, choices=[0, 1],
+                    help="1: the hidden layers' spike bitmasks of finished coarse segments live in pinned host memory (Remote / Double)")
     ap.add_argument("--surr-window", type=float, default=0.0,
                     help="surrogate window w (not in the paper): derivative cut to 0 where |v - theta| >= w; <= 0: none")
     args = ap.parse_args()
@@ -208,11 +210,17 @@ def main():
     y = torch.from_numpy(d["labels"]).to(dev)
     if args.host_inputs:  # the library copies them to the device inside snn_bind_inputs, every step
         x, y = d["in_spikes"], d["labels"]
-    net = snn.from_workload(w, d, surr_window=args.surr_window)  # stream = None: the library runs on a stream of its own
+    net = snn.from_workload(w, d, surr_window=args.surr_window, spike_tier=args.spike_tier)  # stream = None: the library runs on a stream of its own
     params = dict(STRATEGY_PARAMS[args.config])
     if args.coarse >= 0 or args.fine >= 0:
         c0, f0 = params[args.strategy]
         params[args.strategy] = (args.coarse if args.coarse >= 0 else c0, args.fine if args.fine >= 0 else f0)
+    for name, (c_, f_) in list(params.items()):  # a shortened sequence (--T) shortens the intervals with it
+        if name == "hier":
+            params[name] = (c_, min(f_, w.T))
+        else:
+            c2 = min(c_, w.T) if c_ else 0
+            params[name] = (c2, min(f_, c2 if c2 else w.T) if f_ else 0)
     budget = args.budget if args.budget >= 0 else BUDGET.get(args.config, 0)
     if args.config in (0, 1) and args.budget < 0:
         # configurations 0 and 1 name no budget: every strategy runs inside what plain BPTT needs for this T
@@ -350,7 +358,7 @@ def main():
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     wide = max(w.n_hidden) > 256
     big = any(4.0 * max(pn, n) * n >= (32 << 20) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))
-    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden)
+    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and os.environ.get("SNN_CSR", "") == "1"
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
                  "fwd_currents": "k_currents_dense / k_currents (by firing rate)" if big else "k_currents_mfma",
@@ -545,7 +553,9 @@ def main():
                    "hbm_activation_bytes_min": int(snn.snn_bytes_required(net.cfg, SID[args.strategy], w.T, C, F)),
                    "hbm_state_bytes": int(st.bytes_states), "state_slots_hbm": slots,
                    "state_slots_hbm_allocated": int(st.local_state_slots), "state_slots_host": rslots,
-                   "recurrent_density": w.rec_density, "surrogate_window": args.surr_window,
+                   "recurrent_density": w.rec_density, "surrogate_window": args.surr_window, "spike_tier": args.spike_tier,
+                   "hbm_spike_bytes": int(st.bytes_spikes), "host_spike_bytes": int(st.bytes_host_spikes),
+                   "spike_link_bytes_per_step": int(st.spike_d2h_bytes + st.spike_h2d_bytes),
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
                    "other_strategies_neuron_timesteps_per_s": others},
         "roofline": roofline, "cpu_baseline": cpu, "host_link": host_link, "long_sequence": long_seq,

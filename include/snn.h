@@ -71,6 +71,15 @@ typedef struct {
   float surr_window;                /* w > 0: the surrogate derivative is 0 wherever
                                        |v-theta| >= w (compact support); <= 0: no window  */
   int32_t device;                   /* HIP device ordinal                              */
+  int32_t spike_tier;               /* 0: the spike bitmasks of the whole sequence stay in HBM (the paper's setting:
+                                       sparse spikes are part of the local, non-optimisable memory); 1: under REMOTE
+                                       and DOUBLE the hidden layers' bitmasks of finished coarse segments move to pinned
+                                       host memory on the copy stream and come back before the segment is recomputed;
+                                       HBM then holds a window of 2 * coarse_interval + 1600 steps of them whatever T
+                                       is (the extension the paper's Discussion leaves open: what bounds the sequence
+                                       length once the states are checkpointed is the spike store).  Results are the
+                                       same bit for bit.  Ignored by the other strategies and when the window would
+                                       not be shorter than the sequence. */
   void *stream;                     /* hipStream_t to queue work on; NULL = a stream the
                                        library creates (the legacy default stream cannot be
                                        recorded into a HIP graph)                        */
@@ -97,6 +106,8 @@ typedef struct {
   int64_t bytes_host;        /* pinned host memory holding remote checkpoints                  */
   int64_t d2h_bytes, h2d_bytes; /* checkpoint traffic over the host link                       */
   int32_t n_d2h, n_h2d;         /* number of checkpoint transfers (N_c = n_d2h + n_h2d)        */
+  int64_t spike_d2h_bytes, spike_h2d_bytes; /* spike bitmask traffic over the host link (spike_tier 1) */
+  int64_t bytes_host_spikes;    /* pinned host memory holding the hidden layers' spike bitmasks (spike_tier 1) */
   int64_t fwd_steps, refwd1_steps, refwd2_steps, bwd_steps; /* time steps per pass             */
   int32_t local_state_slots; /* states resident in HBM at the peak (M_s units)                 */
   int32_t remote_state_slots;

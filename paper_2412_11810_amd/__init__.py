@@ -32,7 +32,7 @@ class snn_config(C.Structure):
     _fields_ = [("n_in", C.c_int32), ("n_layers", C.c_int32), ("n_hidden", C.c_int32 * SNN_MAX_LAYERS),
                 ("n_out", C.c_int32), ("T", C.c_int32), ("batch", C.c_int32), ("alpha", C.c_float),
                 ("beta_out", C.c_float), ("theta", C.c_float), ("surr_beta", C.c_float),
-                ("surr_window", C.c_float), ("device", C.c_int32), ("stream", C.c_void_p)]
+                ("surr_window", C.c_float), ("device", C.c_int32), ("spike_tier", C.c_int32), ("stream", C.c_void_p)]
 
 
 class snn_stats(C.Structure):
@@ -42,7 +42,8 @@ class snn_stats(C.Structure):
                 ("ms_bwd_stage", C.c_float), ("ms_fwd_stage", C.c_float),
                 ("bytes_states", C.c_int64), ("bytes_spikes", C.c_int64), ("bytes_workspace", C.c_int64),
                 ("bytes_host", C.c_int64), ("d2h_bytes", C.c_int64), ("h2d_bytes", C.c_int64),
-                ("n_d2h", C.c_int32), ("n_h2d", C.c_int32), ("fwd_steps", C.c_int64),
+                ("n_d2h", C.c_int32), ("n_h2d", C.c_int32), ("spike_d2h_bytes", C.c_int64),
+                ("spike_h2d_bytes", C.c_int64), ("bytes_host_spikes", C.c_int64), ("fwd_steps", C.c_int64),
                 ("refwd1_steps", C.c_int64), ("refwd2_steps", C.c_int64), ("bwd_steps", C.c_int64),
                 ("local_state_slots", C.c_int32), ("remote_state_slots", C.c_int32),
                 ("firing_rate", C.c_float * SNN_MAX_LAYERS)]
@@ -110,7 +111,7 @@ def lib() -> C.CDLL:
 
 
 def make_config(n_in, n_hidden, n_out, T, batch, alpha=0.9, beta_out=0.9, theta=1.0, surr_beta=10.0,
-                device=0, stream=None, surr_window=0.0) -> snn_config:
+                device=0, stream=None, surr_window=0.0, spike_tier=0) -> snn_config:
     cfg = snn_config()
     cfg.n_in, cfg.n_layers, cfg.n_out, cfg.T, cfg.batch = n_in, len(n_hidden), n_out, T, batch
     for i, n in enumerate(n_hidden):
@@ -118,6 +119,7 @@ def make_config(n_in, n_hidden, n_out, T, batch, alpha=0.9, beta_out=0.9, theta=
     cfg.alpha, cfg.beta_out, cfg.theta, cfg.surr_beta = alpha, beta_out, theta, surr_beta
     cfg.surr_window = surr_window
     cfg.device = device
+    cfg.spike_tier = spike_tier
     cfg.stream = stream
     return cfg
 
@@ -286,10 +288,10 @@ class Snn:
 
 
 def from_workload(w, data: dict, T: int | None = None, device: int = 0, stream=None,
-                  surr_window: float = 0.0) -> Snn:
+                  surr_window: float = 0.0, spike_tier: int = 0) -> Snn:
     """Context for a synth.Workload with its weights loaded."""
     cfg = make_config(w.n_in, list(w.n_hidden), w.n_out, T or w.T, w.B, w.alpha, w.beta, w.theta,
-                      w.surr_beta, device, stream, surr_window)
+                      w.surr_beta, device, stream, surr_window, spike_tier)
     net = Snn(cfg)
     for l in range(len(w.n_hidden)):
         net.snn_set_weights(SNN_W_IN, l, data["W_in"][l])

@@ -44,6 +44,18 @@ struct snn_ctx {
   float *csr_val[SNN_MAXL]{};
   size_t csr_nnz[SNN_MAXL]{};
   size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
+  // Spike bitmasks on the host tier (cfg.spike_tier == 1, REMOTE / DOUBLE): the hidden layers' words of the whole
+  // sequence live in pinned host memory ([T+1][B][Wd] per layer index 1..L, row 0 zero); HBM holds a ring of
+  // ring_steps rows per layer.  mask_full[l] are the whole-sequence arrays in HBM (hidden layers: allocated on first
+  // use when spike_tier == 1); net.mask[l] points to whichever a launch should use.
+  uint64_t *mask_full[SNN_MAXL + 1]{};
+  uint64_t *mask_ring[SNN_MAXL + 1]{};
+  int ring_steps = 0;          // rows of the allocated rings
+  uint64_t *host_spk = nullptr;
+  size_t host_spk_bytes = 0;
+  size_t host_spk_off[SNN_MAXL + 2]{}; // word offset of layer index l inside host_spk (for the bound T_spk_rows)
+  int host_spk_rows = 0;       // rows per layer the host store is laid out for
+  bool spikes_on_host = false; // the hidden spike trains of the last step are in host_spk, not in mask_full
   int32_t *labels = nullptr;
   unsigned char *host_small = nullptr; // pinned: 64 bytes (loss, error flag) + B labels, for calls that must not allocate
   int T_bound = 0;
@@ -61,7 +73,7 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
-  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; unsigned sel; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol && sel == o.sel; } };
+  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; unsigned sel; void *ring, *host_spk, *mask1; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol && sel == o.sel && ring == o.ring && host_spk == o.host_spk && mask1 == o.mask1; } };
   GraphKeyT graph_key{};
   hipGraphExec_t graph_exec = nullptr;
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
@@ -123,6 +135,7 @@ bool valid_cfg(const snn_config *c, std::string *why) {
     if (c->n_hidden[l] < 1 || c->n_hidden[l] > 65535) { *why = "n_hidden must be 1..65535"; return false; }
   if (c->n_in > 65535) { *why = "n_in must be <= 65535"; return false; }
   if (!(c->surr_window == c->surr_window)) { *why = "surr_window must not be NaN"; return false; }
+  if (c->spike_tier != 0 && c->spike_tier != 1) { *why = "spike_tier must be 0 or 1"; return false; }
   return true;
 }
 
@@ -183,9 +196,18 @@ bool dw_wide_tiles(const NetDev &n) {
   return tiles4 >= 256;
 }
 
-size_t spike_bytes(const NetDev &n, int T) {
-  size_t w = 0;
-  for (int l = 0; l <= n.L; ++l) w += (size_t)(T + 1) * n.B * n.Wd[l];
+// rows of the hidden layers' spike ring for a plan (0: the whole sequence stays in HBM).  The ring must hold, in the
+// forward pass, the rows between the lowest layer's newest step and the oldest segment whose copy to the host is
+// not complete (a segment + the pipeline lag of the layers + a tile), in the backward pass the segment being
+// processed, the one being prefetched and the rows the lower layers of the pipelined adjoint pass still read.
+int spike_ring_steps(const snn_config &cfg, int strategy, int T, int C) {
+  if (cfg.spike_tier != 1 || (strategy != SNN_REMOTE && strategy != SNN_DOUBLE)) return 0;
+  const long long r = 2ll * C + 1600;
+  return r >= (long long)T + 1 ? 0 : (int)r;
+}
+size_t spike_bytes(const NetDev &n, int T, int ring = 0) {
+  size_t w = (size_t)(T + 1) * n.B * n.Wd[0];
+  for (int l = 1; l <= n.L; ++l) w += (size_t)(ring > 0 ? ring : T + 1) * n.B * n.Wd[l];
   return w * 8;
 }
 
@@ -264,7 +286,7 @@ size_t snn_bytes_required(const snn_config *cfg, snn_strategy strategy, int32_t 
   char why_shape[160];
   if (!snn_kernel_shape_ok(n, why_shape, sizeof why_shape)) return 0; // a shape snn_init refuses
   const size_t Ms = (size_t)n.B * n.SN * sizeof(float);
-  return (size_t)p.local_slots() * Ms + spike_bytes(n, T) + work_bytes(n, p.chunk_len);
+  return (size_t)p.local_slots() * Ms + spike_bytes(n, T, spike_ring_steps(*cfg, (int)strategy, T, p.C)) + work_bytes(n, p.chunk_len);
 }
 
 snn_status snn_suggest_intervals(const snn_config *cfg, snn_strategy strategy, int32_t T, size_t budget,
@@ -396,8 +418,10 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   n.W_out = c->W_out; n.W_outT = c->W_outT;
   for (int l = 0; l <= L; ++l) {
     c->mask_words[l] = (size_t)(cfg->T + 1) * B * n.Wd[l];
-    HIPCHK(c, hipMalloc(&n.mask[l], c->mask_words[l] * 8));
-    HIPCHK(c, hipMemsetAsync(n.mask[l], 0, c->mask_words[l] * 8, c->stream));
+    if (l > 0 && cfg->spike_tier == 1) continue; // hidden layers: allocated when a call needs the whole sequence in HBM
+    HIPCHK(c, hipMalloc(&c->mask_full[l], c->mask_words[l] * 8));
+    HIPCHK(c, hipMemsetAsync(c->mask_full[l], 0, c->mask_words[l] * 8, c->stream));
+    n.mask[l] = c->mask_full[l];
   }
   HIPCHK(c, hipMalloc(&c->labels, (size_t)B * 4));
   HIPCHK(c, hipMalloc(&c->readout, (size_t)B * 2 * O * 8));
@@ -453,7 +477,8 @@ void snn_destroy(snn_ctx *c) {
     (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]);
     (void)hipFree(c->acc_in[l]); (void)hipFree(c->acc_rec[l]);
   }
-  for (int l = 0; l <= SNN_MAXL; ++l) (void)hipFree(c->net.mask[l]);
+  for (int l = 0; l <= SNN_MAXL; ++l) { (void)hipFree(c->mask_full[l]); (void)hipFree(c->mask_ring[l]); }
+  if (c->host_spk) (void)hipHostFree(c->host_spk);
   (void)hipFree(c->W_out); (void)hipFree(c->W_outT); (void)hipFree(c->dW_out); (void)hipFree(c->acc_out);
   (void)hipFree(c->labels); (void)hipFree(c->readout); (void)hipFree(c->ubar); (void)hipFree(c->g);
   (void)hipFree(c->loss_dev); (void)hipFree(c->carry); (void)hipFree(c->cur_state);
@@ -574,8 +599,34 @@ static snn_status ensure_work(snn_ctx *c, size_t bytes) {
   return SNN_OK;
 }
 
+// The whole-sequence spike arrays in HBM, which the forward-only pass and the accessors work on.  A context with
+// spike_tier 1 allocates its hidden layers' arrays on first use; if the last training step left the hidden spike
+// trains in host memory they are brought back first.
+static snn_status ensure_full_masks(snn_ctx *c) {
+  NetDev &n = c->net;
+  for (int l = 1; l <= n.L; ++l)
+    if (!c->mask_full[l]) {
+      HIPCHK(c, hipMalloc(&c->mask_full[l], c->mask_words[l] * 8));
+      HIPCHK(c, hipMemsetAsync(c->mask_full[l], 0, c->mask_words[l] * 8, c->stream));
+    }
+  if (c->spikes_on_host) {
+    for (int l = 1; l <= n.L; ++l)
+      HIPCHK(c, hipMemcpyAsync(c->mask_full[l], c->host_spk + c->host_spk_off[l],
+                               (size_t)(c->T_spikes + 1) * n.B * n.Wd[l] * 8, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->spikes_on_host = false;
+  }
+  for (int l = 0; l <= n.L; ++l) { n.mask[l] = c->mask_full[l]; n.mring[l] = 0; }
+  return SNN_OK;
+}
+
 static snn_status forward_only(snn_ctx *c, float *traj_or_null, float *work_or_null = nullptr) {
   read_kernel_hooks(c);
+  c->spikes_on_host = false; // this pass rewrites the hidden spike trains, in HBM
+  {
+    const snn_status rm = ensure_full_masks(c);
+    if (rm != SNN_OK) return rm;
+  }
   const NetDev &n = c->net;
   StoreSpec st{};
   if (traj_or_null) {
@@ -623,6 +674,10 @@ snn_status snn_forward_noalloc(snn_ctx *c, const uint8_t *in_spikes, const int32
     return fail(c, SNN_E_INVAL, msg);
   }
   HIPCHK(c, hipSetDevice(dev));
+  for (int l = 1; l <= n.L; ++l)
+    if (!c->mask_full[l])
+      return fail(c, SNN_E_STATE, "snn_forward_noalloc: this spike_tier-1 context has not allocated its whole-sequence spike "
+                                  "arrays yet; call snn_forward once first");
   if (!is_device_ptr(in_spikes) || !is_device_ptr(labels))
     return fail(c, SNN_E_INVAL, "snn_forward_noalloc takes device pointers (a host buffer would need a staging allocation)");
   if (c->own_stream) HIPCHK(c, hipStreamSynchronize(nullptr));
@@ -683,6 +738,10 @@ snn_status snn_get_state(snn_ctx *c, int layer, int32_t t, float *dst) {
   if (t < 1 || t > c->T_spikes) return fail(c, SNN_E_INVAL, "t outside 1..T");
   HIPCHK(c, hipSetDevice(c->cfg.device));
   read_kernel_hooks(c);
+  {
+    const snn_status rm = ensure_full_masks(c);
+    if (rm != SNN_OK) return rm;
+  }
   const NetDev &n = c->net;
   // what a recompute pass does: from x_0 = 0 through the stored spike trains, a chunk of currents at a time
   const int chunk = std::min<int>(t, SNN_FWD_TILE);
@@ -707,6 +766,10 @@ snn_status snn_get_spikes(snn_ctx *c, int layer, uint8_t *dst) {
   if (!c || !dst || layer < 0 || layer >= c->net.L) return fail(c, SNN_E_INVAL, "bad argument");
   if (c->T_bound < 1) return fail(c, SNN_E_STATE, "no inputs bound");
   HIPCHK(c, hipSetDevice(c->cfg.device));
+  {
+    const snn_status rm = ensure_full_masks(c);
+    if (rm != SNN_OK) return rm;
+  }
   const NetDev &n = c->net;
   const size_t bytes = (size_t)c->T_bound * n.B * n.N[layer];
   uint8_t *tmp = nullptr;
@@ -743,6 +806,10 @@ snn_status snn_debug_currents(snn_ctx *c, const uint8_t *const *hidden, int32_t 
   if (chunk < 1 || reps < 1) return fail(c, SNN_E_INVAL, "chunk and reps must be positive");
   HIPCHK(c, hipSetDevice(c->cfg.device));
   read_kernel_hooks(c);
+  {
+    const snn_status rm = ensure_full_masks(c);
+    if (rm != SNN_OK) return rm;
+  }
   const NetDev &n = c->net;
   const int T = c->T_bound, B = n.B;
   hipStream_t s = c->stream;
@@ -840,13 +907,14 @@ struct Timer {
 // Firing rates of the step that was just queued (spike counts of all stored bitmasks), and from them the current
 // kernel of the layers with very large weight matrices for the next step: the event-by-event gather pays per
 // presynaptic spike, the dense matrix-core version per presynaptic neuron; measured break-even about 4.5 %.
-static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out) {
+static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out, bool hidden_counted) {
   const NetDev &n = c->net;
   const int L = n.L, B = n.B;
   hipStream_t s = c->stream;
-  HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
-  for (int l = 0; l <= L; ++l)
-    HIPCHK(c, launch_count_spikes(n.mask[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
+  // with the spike bitmasks on the host tier the step itself counted the hidden layers' spikes, segment by segment
+  if (!hidden_counted) HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
+  for (int l = 0; l <= (hidden_counted ? 0 : L); ++l)
+    HIPCHK(c, launch_count_spikes(c->mask_full[l] + (size_t)B * n.Wd[l], (size_t)T * B * n.Wd[l], c->counters + l, s));
   HIPCHK(c, hipStreamSynchronize(s));
   unsigned long long cnt[SNN_MAXL + 1];
   HIPCHK(c, hipMemcpy(cnt, c->counters, sizeof cnt, hipMemcpyDeviceToHost));
@@ -881,6 +949,101 @@ static snn_status check_ws_error(snn_ctx *c) {
   }
   return SNN_OK;
 }
+
+// Spike bitmasks on the host tier (spike_tier 1): the hidden layers' words of segment g -- steps (g C, (g+1) C] --
+// go to pinned host memory on the copy stream once nothing in the forward pass reads them any more, and the ring
+// rows they occupied are reused; in the backward pass a segment's rows come back before its recomputation, the
+// segment before it is prefetched meanwhile.  Row r of the sequence sits at ring row r % R.
+struct SpikeOff {
+  snn_ctx *c; int R, C, T; hipStream_t s, cs; Timer *tm; snn_stats *st;
+  const FwdCallbacks *inner = nullptr;
+  std::vector<hipEvent_t> ev_ready, ev_done; // per segment, reused modulo their number
+  int nseg = 0, issued = 0, waited = 0, top_prev_end = 0;
+  bool init() {
+    nseg = (T + C - 1) / C;
+    const int nev = R / C + 6;
+    for (int i = 0; i < nev; ++i) {
+      ev_ready.push_back(tm->get()); ev_done.push_back(tm->get());
+      if (!ev_ready.back() || !ev_done.back()) return false;
+    }
+    return true;
+  }
+  // rows r0..r1 (inclusive) of every hidden layer between the ring and the host store
+  hipError_t copy_rows(int r0, int r1, bool to_host, hipStream_t q) {
+    const NetDev &n = c->net;
+    for (int l = 1; l <= n.L; ++l) {
+      const size_t rw = (size_t)n.B * n.Wd[l]; // words per row
+      for (int a = r0; a <= r1;) {
+        const int pos = a % R, len = std::min(r1 - a + 1, R - pos);
+        uint64_t *dev = c->mask_ring[l] + (size_t)pos * rw, *host = c->host_spk + c->host_spk_off[l] + (size_t)a * rw;
+        const hipError_t e = to_host ? hipMemcpyAsync(host, dev, (size_t)len * rw * 8, hipMemcpyDeviceToHost, q)
+                                     : hipMemcpyAsync(dev, host, (size_t)len * rw * 8, hipMemcpyHostToDevice, q);
+        if (e != hipSuccess) return e;
+        (to_host ? st->spike_d2h_bytes : st->spike_h2d_bytes) += (int64_t)((size_t)len * rw * 8);
+        a += len;
+      }
+    }
+    return hipSuccess;
+  }
+  // spike counts of rows r0..r1 (firing rates), on the compute stream
+  hipError_t count_rows(int r0, int r1) {
+    const NetDev &n = c->net;
+    for (int l = 1; l <= n.L; ++l) {
+      const size_t rw = (size_t)n.B * n.Wd[l];
+      for (int a = r0; a <= r1;) {
+        const int pos = a % R, len = std::min(r1 - a + 1, R - pos);
+        const hipError_t e = launch_count_spikes(c->mask_ring[l] + (size_t)pos * rw, (size_t)len * rw, c->counters + l, s);
+        if (e != hipSuccess) return e;
+        a += len;
+      }
+    }
+    return hipSuccess;
+  }
+  hipError_t issue(int g) { // segment g leaves for the host
+    const int r0 = g * C + 1, r1 = std::min((g + 1) * C, T), k = g % (int)ev_ready.size();
+    hipError_t e = count_rows(r0, r1);
+    if (e == hipSuccess) e = hipEventRecord(ev_ready[k], s);
+    if (e == hipSuccess) e = hipStreamWaitEvent(cs, ev_ready[k], 0);
+    if (e == hipSuccess) e = copy_rows(r0, r1, true, cs);
+    if (e == hipSuccess) e = hipEventRecord(ev_done[k], cs);
+    return e;
+  }
+  hipError_t issue_upto(int row_limit) { // every segment that ends at or before row_limit
+    while (issued < nseg && std::min((issued + 1) * C, T) <= row_limit) {
+      const hipError_t e = issue(issued);
+      if (e != hipSuccess) return e;
+      ++issued;
+    }
+    return hipSuccess;
+  }
+  static hipError_t done(void *self, int layer, int t_end) {
+    SpikeOff &q = *static_cast<SpikeOff *>(self);
+    const NetDev &n = q.c->net;
+    hipError_t e = hipSuccess;
+    if (layer == 0) {
+      // the lowest layer is about to write rows up to t_end + 128 (its next two tiles): the rows R below them must
+      // have reached the host
+      const int old_row = std::min(t_end + 128, q.T) - q.R;
+      if (old_row >= 1) {
+        const int g = std::min((old_row - 1) / q.C, q.nseg - 1);
+        while (q.waited <= g) {
+          if (q.waited >= q.issued) return hipErrorAssert; // the ring is too short for the pipeline lag (never, by its size)
+          e = hipStreamWaitEvent(q.s, q.ev_done[q.waited % (int)q.ev_done.size()], 0);
+          if (e != hipSuccess) return e;
+          ++q.waited;
+        }
+      }
+    }
+    if (layer == n.L - 1) {
+      // everything that reads rows up to the START of the tile the top layer just finished has been queued
+      // (the readout currents of a tile are computed one stage after the top layer's sequential part)
+      e = q.issue_upto(q.top_prev_end);
+      if (e != hipSuccess) return e;
+      q.top_prev_end = t_end;
+    }
+    return q.inner ? q.inner->layer_tile_done(q.inner->ctx, layer, t_end) : hipSuccess;
+  }
+};
 
 // Adjoint pass, layers one tile apart.  Layer l of a tile needs layer l+1 of the same tile (through the
 // inter-layer product) and layer l of the tile after it in time (through the carried dv): while the top layer
@@ -1012,9 +1175,9 @@ struct BwdPipe {
     for (const BwdTile &t : done) {
       const int l = t.layer;
       if (l == L - 1)
-        db->d[db->count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0, 0};
-      db->d[db->count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, l == 0 ? 1 : 0, 0, 0};
-      db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0, 0};
+        db->d[db->count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0, 0, n.mring[L]};
+      db->d[db->count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, l == 0 ? 1 : 0, 0, 0, n.mring[l]};
+      db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0, 0, n.mring[l + 1]};
     }
   }
   snn_status emit_dw() {
@@ -1027,9 +1190,9 @@ struct BwdPipe {
       for (const BwdTile &t : done) {
         const int l = t.layer;
         if (l == L - 1)
-          HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, t.du, (size_t)B * O, O, 0, O, B, t.t0, t.t1, t.base, c->acc_out, s));
-        HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_in[l], s));
-        HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_rec[l], s));
+          HIPCHK(c, launch_dw(n.mask[L], n.Wd[L], n.N[L - 1], 0, t.du, (size_t)B * O, O, 0, O, B, t.t0, t.t1, t.base, c->acc_out, s, n.mring[L]));
+        HIPCHK(c, launch_dw(n.mask[l], n.Wd[l], pre_of(n, l), 0, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_in[l], s, n.mring[l]));
+        HIPCHK(c, launch_dw(n.mask[l + 1], n.Wd[l + 1], n.N[l], 1, t.vbuf, slot, SN, n.off[l], n.N[l], B, t.t0, t.t1, t.base, c->acc_rec[l], s, n.mring[l + 1]));
       }
     } else {
       DwBatch db{};
@@ -1088,6 +1251,37 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     HIPCHK(c, hipEventRecord(ev_fork, s));
     HIPCHK(c, hipStreamWaitEvent(cs, ev_fork, 0));
   }
+
+  // ---- spike bitmasks on the host tier: the launches of this step see the hidden layers' ring ----------------
+  const int R = spike_ring_steps(c->cfg, strategy, T, p.C);
+  struct MaskGuard { // net.mask / net.mring are per-launch arguments: point them at the ring for this step only
+    snn_ctx *c; bool on;
+    ~MaskGuard() {
+      if (!on) return;
+      for (int l = 1; l <= c->net.L; ++l) { c->net.mask[l] = c->mask_full[l]; c->net.mring[l] = 0; }
+    }
+  } mask_guard{c, R > 0};
+  SpikeOff so{c, R, p.C, T, s, cs, &tm, &st};
+  hipEvent_t ev_spk[2] = {nullptr, nullptr}, ev_spk_go[2] = {nullptr, nullptr};
+  bool spk_first_load = true;
+  if (R > 0) {
+    for (int l = 1; l <= L; ++l) { n.mask[l] = c->mask_ring[l]; n.mring[l] = R; }
+    if (!so.init()) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+    for (int i = 0; i < 2; ++i) {
+      ev_spk[i] = tm.get(); ev_spk_go[i] = tm.get();
+      if (!ev_spk[i] || !ev_spk_go[i]) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+    }
+    HIPCHK(c, launch_fill_zero(c->counters, 8 * (SNN_MAXL + 1), s));
+    // step 0 of every hidden layer (all silent) sits at ring row 0
+    for (int l = 1; l <= L; ++l) HIPCHK(c, launch_fill_zero(c->mask_ring[l], (size_t)B * n.Wd[l] * 8, s));
+    if (!remote) { // the copy stream joins this step also when the states take the direct tier
+      ev_fork = tm.get(); ev_join = tm.get();
+      if (!ev_fork || !ev_join) return fail(c, SNN_E_HIP, "hipEventCreate failed");
+      HIPCHK(c, hipEventRecord(ev_fork, s));
+      HIPCHK(c, hipStreamWaitEvent(cs, ev_fork, 0));
+    }
+  }
+  const FwdCallbacks cb_spk{&so, &SpikeOff::done};
 
   // ---- forward ------------------------------------------------------------------------------
   HIPCHK(c, launch_fill_zero(c->cur_state, Ms, s)); // x_0
@@ -1152,7 +1346,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     // x_0 lives in host slot 0 (zeroed on the host); the sequential kernels store x_{KC} into host slot K
     const StoreSpec sp{c->host_ckpt, slot, 0, p.C, 1, T - 1, 0};
     const std::vector<int> bounds = tile_bounds(0, T, T); // no host-side work at the checkpoints: full tiles
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, nullptr, &c->ws));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, R > 0 ? &cb_spk : nullptr, &c->ws));
     st.n_d2h += p.n_remote - 1;
     st.d2h_bytes += (int64_t)(p.n_remote - 1) * (int64_t)Ms;
   } else {
@@ -1194,11 +1388,14 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       if (!snap.ready.back() || !snap.freed.back()) return fail(c, SNN_E_HIP, "hipEventCreate failed");
     }
     const FwdCallbacks cb{&snap, &Snap::done};
+    so.inner = &cb;
     const std::vector<int> bounds = tile_bounds(0, T, p.C);
     HIPCHK(c, snap.reserve(0)); // nothing to wait for yet; marks checkpoint 1 as reserved
     const StoreSpec sp{stage, slot, 0, p.C, 1, T - 1, p.n_stage_slots}; // x_{KC} -> staging slot K % n_stage
-    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb, &c->ws));
+    HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, R > 0 ? &cb_spk : &cb, &c->ws));
+    so.inner = nullptr;
   }
+  if (R > 0) HIPCHK(c, so.issue_upto(T)); // everything of the forward pass is queued: the remaining segments leave
   st.fwd_steps = T;
   HIPCHK(c, launch_loss(c->readout, c->labels, B, O, T, c->ubar, c->g, c->loss_dev, s));
   if (ev_fwd_out) *ev_fwd_out = tm.mark();
@@ -1250,7 +1447,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       const SchedOp &o = ops[j];
       if (o.op == OP_REFWD1 || o.op == OP_LOAD_BATCH) break;
       if (o.op == OP_LOAD_REMOTE) {
-        if (!direct) break;
+        if (!direct || R > 0) break; // (with the spike bitmasks on the host tier the next segment's rows are not in yet)
         ss = o.a;
         sp = c->host_ckpt + (size_t)(o.a / p.C) * slot;
         continue;
@@ -1300,6 +1497,26 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     switch (op.op) {
       case OP_LOAD_REMOTE: {
         const int K = op.a / p.C;
+        if (R > 0) {
+          // this segment's spike rows [K C, end] are in the ring before anything of the segment is recomputed
+          // (row K C is the previous step of its first one); the rows of the segment before it follow while this
+          // one is worked on.  A load waits for everything queued so far: what it overwrites was read by work of
+          // segments at least 1600 steps later in the sequence, beyond the lag of the pipelined adjoint pass.
+          if (spk_first_load) {
+            HIPCHK(c, hipEventRecord(ev_spk_go[K & 1], s));
+            HIPCHK(c, hipStreamWaitEvent(cs, ev_spk_go[K & 1], 0));
+            HIPCHK(c, so.copy_rows(K * p.C, std::min((K + 1) * p.C, T), false, cs));
+            HIPCHK(c, hipEventRecord(ev_spk[K & 1], cs));
+            spk_first_load = false;
+          }
+          HIPCHK(c, hipStreamWaitEvent(s, ev_spk[K & 1], 0));
+          if (K > 0) {
+            HIPCHK(c, hipEventRecord(ev_spk_go[(K - 1) & 1], s));
+            HIPCHK(c, hipStreamWaitEvent(cs, ev_spk_go[(K - 1) & 1], 0));
+            HIPCHK(c, so.copy_rows((K - 1) * p.C, K * p.C - 1, false, cs));
+            HIPCHK(c, hipEventRecord(ev_spk[(K - 1) & 1], cs));
+          }
+        }
         if (direct) { // the recompute kernels read x_{KC} from the host slot themselves
           seg_start = op.a;
           seg_src = c->host_ckpt + (size_t)K * slot;
@@ -1412,7 +1629,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     HIPCHK(c, launch_finish_grad(c->acc_rec[l], c->rec_mask[l], c->dW_rec[l], (size_t)n.N[l] * n.N[l], s));
   }
   HIPCHK(c, launch_finish_grad(c->acc_out, nullptr, c->dW_out, (size_t)n.N[L - 1] * O, s));
-  if (remote) { // join the copy stream back
+  if (remote || R > 0) { // join the copy stream back
     HIPCHK(c, hipEventRecord(ev_join, cs));
     HIPCHK(c, hipStreamWaitEvent(s, ev_join, 0));
   }
@@ -1429,6 +1646,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   NetDev &n = c->net;
   const int L = n.L;
   const size_t Ms = c->Ms();
+  const int ring = spike_ring_steps(c->cfg, (int)strategy, T, p.C); // > 0: the hidden spike bitmasks live on the host tier
   // One chunk buffer per layer lets the adjoint pass run its layers one chunk apart (see BwdPipe).  The extra
   // (L - 1) * chunk_len state slots are taken only if the budget has room for them; the results are the same
   // bit for bit either way.
@@ -1440,12 +1658,12 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     for (int nb : cand) {
       Plan q = p;
       q.n_chunk_bufs = nb;
-      if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T) <= budget) { p = q; break; }
+      if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring) <= budget) { p = q; break; }
     }
   }
   const size_t need_states = (size_t)p.local_slots() * Ms;
   const size_t need_work = work_bytes(n, p.chunk_len);
-  const size_t need_spikes = spike_bytes(n, T);
+  const size_t need_spikes = spike_bytes(n, T, ring);
   if (budget && need_states + need_work + need_spikes > budget) {
     char buf[200];
     snprintf(buf, sizeof buf, "needs %zu B of HBM activation memory (%d state slots), budget is %zu B",
@@ -1478,10 +1696,44 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     c->host_bytes = need_host;
   }
   if (need_host) std::memset(c->host_ckpt, 0, Ms); // host slot 0 = x_0 (nothing is in flight here)
+  size_t need_host_spk = 0;
+  if (ring > 0) {
+    if (c->ring_steps != ring) {
+      HIPCHK(c, hipStreamSynchronize(s));
+      for (int l = 1; l <= L; ++l) {
+        if (c->mask_ring[l]) HIPCHK(c, hipFree(c->mask_ring[l]));
+        c->mask_ring[l] = nullptr;
+      }
+      c->ring_steps = 0;
+      for (int l = 1; l <= L; ++l) HIPCHK(c, hipMalloc(&c->mask_ring[l], (size_t)ring * n.B * n.Wd[l] * 8));
+      c->ring_steps = ring;
+    }
+    size_t words = 0;
+    for (int l = 1; l <= L; ++l) { c->host_spk_off[l] = words; words += (size_t)(T + 1) * n.B * n.Wd[l]; }
+    need_host_spk = words * 8;
+    if (c->host_spk_bytes < need_host_spk) {
+      HIPCHK(c, hipStreamSynchronize(s));
+      if (c->host_spk) HIPCHK(c, hipHostFree(c->host_spk));
+      c->host_spk = nullptr; c->host_spk_bytes = 0;
+      if (hipHostMalloc(reinterpret_cast<void **>(&c->host_spk), need_host_spk, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(c, SNN_E_HOSTMEM, "pinned host allocation for the spike bitmasks failed");
+      }
+      c->host_spk_bytes = need_host_spk;
+    }
+    c->host_spk_rows = T + 1;
+    for (int l = 1; l <= L; ++l) std::memset(c->host_spk + c->host_spk_off[l], 0, (size_t)n.B * n.Wd[l] * 8); // step 0: silent
+  } else {
+    // the whole sequence in HBM (a spike_tier-1 context allocates its hidden layers' arrays here on first use)
+    c->spikes_on_host = false; // the step rewrites the hidden spike trains
+    const snn_status rm = ensure_full_masks(c);
+    if (rm != SNN_OK) return rm;
+  }
 
   snn_stats st{};
   st.bytes_states = (int64_t)need_states; st.bytes_spikes = (int64_t)need_spikes; st.bytes_workspace = (int64_t)need_work;
   st.bytes_host = (int64_t)need_host; st.local_state_slots = p.local_slots(); st.remote_state_slots = p.n_remote;
+  st.bytes_host_spikes = (int64_t)need_host_spk;
 
   // A step whose launches are recorded once and replayed as a HIP graph: the per-launch host cost
   // (hundreds of small dependent kernels per step) disappears.  Used when no per-kernel timing is
@@ -1491,7 +1743,8 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     unsigned long long pol = 0;
     for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
     const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24;
-    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel};
+    snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,
+                           ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1]};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
       Timer tm{c, false};
@@ -1509,11 +1762,12 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     }
     HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
     if (c->rate_driven) {
-      snn_status rr = update_current_policy(c, T, nullptr);
+      snn_status rr = update_current_policy(c, T, nullptr, ring > 0);
       if (rr != SNN_OK) return rr;
     }
     HIPCHK(c, hipStreamSynchronize(s));
     c->T_spikes = T;
+    c->spikes_on_host = ring > 0;
     return check_ws_error(c);
   }
 
@@ -1524,7 +1778,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   if (rs != SNN_OK) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamSynchronize(s); return rs; }
   hipEvent_t ev_end = tm.mark();
   if (stats || c->rate_driven) {
-    snn_status rr = update_current_policy(c, T, st.firing_rate);
+    snn_status rr = update_current_policy(c, T, st.firing_rate, ring > 0);
     if (rr != SNN_OK) return rr;
   }
   HIPCHK(c, hipStreamSynchronize(s));
@@ -1549,6 +1803,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     *stats = st;
   }
   c->T_spikes = T;
+  c->spikes_on_host = ring > 0;
   return check_ws_error(c);
 }
 

@@ -817,3 +817,69 @@ def test_event_driven_adjoint_under_the_surrogate_window(hidden, B, T, density, 
     inside = [float((np.abs(v - w.theta) < window).mean()) for v in ref.v]
     print(f"[{w.name}] fraction of (t, b, neuron) inside the window of {window}: {[round(x, 4) for x in inside]}")
     assert all(0.0 < x < 0.5 for x in inside)
+
+
+@pytest.mark.parametrize("hidden,B,T,tier_env,strategies", [
+    ((256, 256), 4, 3000, "direct", [(2, 100, 0), (3, 200, 20)]),
+    ((200, 300), 3, 2600, "dma", [(3, 150, 30), (2, 64, 0)]),
+    ((1088,), 2, 2000, "dma", [(3, 60, 12)])])
+def test_spike_bitmasks_on_the_host_tier(hidden, B, T, tier_env, strategies, monkeypatch):
+    """spike_tier 1: under Remote and Double the hidden layers' spike bitmasks of finished coarse segments travel to
+    pinned host memory and come back before the segment is recomputed; HBM keeps a ring of 2 C + 1600 steps of them.
+    Gradients must be the very bits of the run that keeps every bitmask in HBM (eager and as a replayed graph, with
+    the states on either host tier), the HBM spike bytes must be the ring's, snn_bytes_required must drop by the
+    difference, the accessors must still return the whole spike train and every state, and all of it must match the
+    oracle."""
+    monkeypatch.setenv("SNN_HOST_TIER", tier_env)
+    w = synth.Workload("spk_host_" + "x".join(map(str, hidden)), 60, hidden, 6, T=T, B=B, p_in=0.05, gain=0.5, seed=71 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    ref_net = snn.from_workload(w, d)
+    net = snn.from_workload(w, d, spike_tier=1)
+    try:
+        ref_net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        for strat, C, F in strategies:
+            st0 = ref_net.snn_bptt(strat, C, F)
+            ref = _gpu_grads(ref_net, L)
+            st1 = net.snn_bptt(strat, C, F)
+            assert _identical(_gpu_grads(net, L), ref), (strat, C, F, "eager")
+            ring = 2 * C + 1600
+            words = sum(-(-n // 64) for n in hidden)
+            assert st0.bytes_spikes - st1.bytes_spikes == (w.T + 1 - ring) * w.B * words * 8
+            assert st1.bytes_host_spikes == (w.T + 1) * w.B * words * 8 and st0.bytes_host_spikes == 0
+            assert st1.spike_d2h_bytes == w.T * w.B * words * 8 and st1.spike_h2d_bytes >= st1.spike_d2h_bytes
+            assert np.allclose(list(st1.firing_rate)[:L], list(st0.firing_rate)[:L], atol=1e-7)
+            need0 = snn.snn_bytes_required(ref_net.cfg, strat, w.T, C, F)
+            need1 = snn.snn_bytes_required(net.cfg, strat, w.T, C, F)
+            assert need0 - need1 == (w.T + 1 - ring) * w.B * words * 8
+            st2 = net.snn_bptt(strat, C, F, need1)  # runs inside the smaller budget
+            assert _identical(_gpu_grads(net, L), ref), (strat, C, F, "tight budget")
+            assert st2.bytes_states + st2.bytes_spikes + st2.bytes_workspace == need1
+            for rep in range(2):
+                net.snn_bptt(strat, C, F, want_stats=False)
+                assert _identical(_gpu_grads(net, L), ref), (strat, C, F, "graph", rep)
+            for l in range(L):  # the whole spike train comes back from the host for the accessors
+                assert np.array_equal(net.snn_get_spikes(l, w.T), ref_net.snn_get_spikes(l, w.T))
+            assert np.array_equal(net.snn_get_state(L - 1, w.T), ref_net.snn_get_state(L - 1, w.T))
+        # strategies without a host tier ignore the setting
+        net.snn_bptt(snn.SNN_CHUNK, 0, 50)
+        ref_net.snn_bptt(snn.SNN_CHUNK, 0, 50)
+        assert _identical(_gpu_grads(net, L), _gpu_grads(ref_net, L))
+    finally:
+        net.snn_destroy()
+        ref_net.snn_destroy()
+    monkeypatch.delenv("SNN_HOST_TIER")
+    short = synth.Workload(w.name + "_oracle", 60, hidden, 6, T=T, B=B, p_in=0.05, gain=0.5, seed=71 + B)
+    strat, C, F = strategies[0]
+    dd = synth.generate(short)
+    ref32 = _oracle(short, dd, want_v=True, nthreads=4, backward=False)
+    ref64 = _oracle_f64_on_f32_trajectory(short, dd, ref32, 4)
+    net = snn.from_workload(short, dd, spike_tier=1)
+    try:
+        net.snn_bind_inputs(dd["in_spikes"], dd["labels"], short.T)
+        net.snn_bptt(strat, C, F)
+        assert _check_spikes(net, short, ref32, short.name) == 0
+        _check_grads(_gpu_grads(net, L), ref64, short.name)
+    finally:
+        net.snn_destroy()
