@@ -66,7 +66,10 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density):
     seq_adds = T * sum(ent_rec[l] * ev_rec[l] for l in range(L) if N[l] <= 256)
     seq_bytes = T * sum(row_rec[l] * ev_rec[l] + (N[l] / 8.0 + 4.0 * N[l]) * B for l in range(L) if N[l] > 256)
     out["fwd_seq"] = ("alu", seq_adds) if max(N) <= 256 else ("hbm", seq_bytes)
-    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * ev_in[l] + row_rec[l] * ev_rec[l] + 12.0 * N[l] * B for l in range(L)))
+    # recompute: part 1, the currents (weight rows of the events + the current written) and part 2, the scan (current
+    # read, state written, one spike bit read)
+    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * ev_in[l] + row_rec[l] * ev_rec[l] + 4.0 * N[l] * B for l in range(L)))
+    out["scan"] = ("hbm", refwd_steps * sum((8.0 + 1.0 / 8.0) * N[l] * B for l in range(L)))
     # adjoint recurrence: layers wider than 1024 stream their recurrent matrix once per step for the whole batch
     if max(N) > 1024:
         out["adjoint"] = ("hbm", T * sum((6.0 * rec_density if masked else 4.0) * N[l] * N[l] for l in range(L) if N[l] > 1024))
@@ -94,7 +97,7 @@ def read_traffic(workload, strategy, kernel):
         return None
     for line in open(path):
         p = line.split()
-        if len(p) >= 4 and p[0] == "kernel" and p[1] == kernel:
+        if len(p) >= 4 and p[0] == "kernel" and p[1] == kernel.replace(" ", ""):
             kv = dict(zip(p[2::2], p[3::2]))
             try:
                 return float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"])
@@ -340,11 +343,14 @@ def main():
     n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
     L = len(w.n_hidden)
     model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density)
-    ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute,
+    ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute, "scan": st.ms_scan,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
-    launches = {"fwd_seq": n_tiles * L, "fwd_currents": n_tiles * (L + 2), "recompute": max(1, 2 * n_rec),
-                "adjoint": n_bwd * L, "up_gemm": n_bwd * L, "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
+    # launches of each kind's main kernel per step (layers that share a width and a pipeline stage share a launch)
+    n_stage = n_tiles + 2 * (L - 1)
+    launches = {"fwd_seq": n_stage, "fwd_currents": n_stage, "recompute": max(1, n_rec), "scan": max(1, n_rec),
+                "adjoint": n_bwd * L if max(w.n_hidden) > 1024 else n_bwd + L - 1, "up_gemm": max(1, n_bwd + L - 2),
+                "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
                 "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
     if st.ms_bwd_stage > 0:
         # all but the first stage's recurrences and the last stage's weight gradients ran inside fused launches:
@@ -361,10 +367,11 @@ def main():
     csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and os.environ.get("SNN_CSR", "") == "1"
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
-                 "fwd_currents": "k_currents_dense / k_currents (by firing rate)" if big else "k_currents_mfma",
-                 "recompute": ("k_currents_dense / k_currents (by firing rate)" if big else "k_currents_mfma") +
-                              (" + k_currents_csr" if w.rec_density < 1.0 and wide else "") + " + k_scan",
-                 "up_gemm": "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 # (matrices of 32 MB and more: the dense matrix-core version from 4.5 % presynaptic activity, below it
+                 # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
+                 "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
+                 "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
+                 "scan": "k_scan", "up_gemm": "k_bwd_inter" if L > 2 else "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
@@ -380,8 +387,7 @@ def main():
     dom = max(kinds, key=lambda k: kinds[k]["ms_per_step"])
     dk = kinds[dom]
     work_per_launch = model[dom][1] / launches[dom]
-    first_kernel = dk["kernel"].split(" ")[0]
-    traffic = read_traffic(w.name, args.strategy, first_kernel)
+    traffic = read_traffic(w.name, args.strategy, dk["kernel"])
     roofline = {"bound": dk["bound"], "kernel": dk["kernel"], "kind": dom, "achieved": dk["achieved"], "peak": dk["peak"],
                 "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic,
                 "launches_per_step": dk["launches_per_step"], "avg_launch_ms": dk["avg_launch_ms"],
@@ -390,8 +396,9 @@ def main():
                         "neurons -- existing synapses only for masked matrices -- for hbm kinds; adds of those rows plus the "
                         "dense recurrent product of the adjoint for alu kinds; dense inter-layer products for mfma kinds), "
                         "never the dense-equivalent work of a kernel; durations from HIP events on the compute stream of an "
-                        "eager step; traffic = HBM bytes per launch of the kind's first kernel from the committed rocprofv3 "
-                        "--pmc summary of this workload (null if none)",
+                        "eager step; traffic = HBM bytes per launch of that kernel (FETCH_SIZE + WRITE_SIZE, scaled by the "
+                        "copy kernel) from the committed rocprofv3 --pmc summary of this workload at the same launch shape "
+                        "(profiles/pmc_traffic_<workload>_<strategy>.txt; null if none)",
                 "kinds": kinds}
 
     # ---- measured peaks next to the published ones: a plain streaming copy (1 GiB read + 1 GiB written per

@@ -100,6 +100,8 @@ typedef struct {
                                 weight-gradient contraction of the stage before (not in ms_adjoint / ms_dw) */
   float ms_fwd_stage;        /* launches that carry the sequential parts of one forward stage together with the
                                 currents of the next (not in ms_fwd_seq / ms_fwd_currents)                    */
+  float ms_scan;             /* recompute, part 2: the scans that turn a chunk's currents into states (ms_recompute
+                                holds part 1, the current kernels, alone)                                      */
   int64_t bytes_states;      /* HBM: trajectory / chunk buffer / checkpoints / staging slots */
   int64_t bytes_spikes;      /* HBM: spike bitmasks of all layers, all steps                  */
   int64_t bytes_workspace;   /* HBM: readout-adjoint tile and other per-chunk scratch          */

@@ -39,7 +39,7 @@ class snn_stats(C.Structure):
     _fields_ = [("ms_total", C.c_float), ("ms_forward", C.c_float), ("ms_backward_total", C.c_float),
                 ("ms_recompute", C.c_float), ("ms_adjoint", C.c_float), ("ms_dw", C.c_float),
                 ("ms_fwd_seq", C.c_float), ("ms_fwd_currents", C.c_float), ("ms_up_gemm", C.c_float),
-                ("ms_bwd_stage", C.c_float), ("ms_fwd_stage", C.c_float),
+                ("ms_bwd_stage", C.c_float), ("ms_fwd_stage", C.c_float), ("ms_scan", C.c_float),
                 ("bytes_states", C.c_int64), ("bytes_spikes", C.c_int64), ("bytes_workspace", C.c_int64),
                 ("bytes_host", C.c_int64), ("d2h_bytes", C.c_int64), ("h2d_bytes", C.c_int64),
                 ("n_d2h", C.c_int32), ("n_h2d", C.c_int32), ("spike_d2h_bytes", C.c_int64),

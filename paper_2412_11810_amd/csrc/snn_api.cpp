@@ -73,7 +73,7 @@ struct snn_ctx {
   float *host_ckpt = nullptr;
   size_t host_bytes = 0;
   std::vector<hipEvent_t> ev_pool;
-  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; unsigned sel; void *ring, *host_spk, *mask1; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol && sel == o.sel && ring == o.ring && host_spk == o.host_spk && mask1 == o.mask1; } };
+  struct GraphKeyT { int strategy, T, C, F, n_chunk_bufs; void *arena, *work, *host; bool dw_event; unsigned long long cur_pol; unsigned sel; void *ring, *host_spk, *mask1; int cache; bool operator==(const GraphKeyT &o) const { return strategy == o.strategy && T == o.T && C == o.C && F == o.F && n_chunk_bufs == o.n_chunk_bufs && arena == o.arena && work == o.work && host == o.host && dw_event == o.dw_event && cur_pol == o.cur_pol && sel == o.sel && ring == o.ring && host_spk == o.host_spk && mask1 == o.mask1 && cache == o.cache; } };
   GraphKeyT graph_key{};
   hipGraphExec_t graph_exec = nullptr;
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
@@ -83,6 +83,7 @@ struct snn_ctx {
   bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
   bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
   bool rate_driven = false;     // some weight matrix is far beyond the L2: the current kernel follows the firing rates
+  bool rf_cache = true;         // SNN_RF_CACHE=0: Double never keeps a segment's currents between its two recompute passes
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -365,6 +366,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (const char *e = std::getenv("SNN_BWD_PIPE")) c->bwd_pipeline = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_PRE_IN_STAGE")) c->pre_in_stage = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_RF_CACHE")) c->rf_cache = std::strcmp(e, "0") != 0;
   read_kernel_hooks(c);
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
@@ -1226,6 +1228,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   float *lckpt = chunk0 + (size_t)p.chunk_len * p.n_chunk_bufs * slot; // local checkpoints
   float *loadb = lckpt + (size_t)p.n_local_ckpt * slot;      // 2 slots receiving host checkpoints
   float *stage = loadb + (size_t)p.n_load_slots * slot;      // 2 slots staging D2H copies
+  float *ccache = p.n_cache_slots ? stage + (size_t)p.n_stage_slots * slot : nullptr; // currents of a coarse segment
+  int cache_a = -1, cache_b = -1; // ccache holds the currents of steps (cache_a, cache_b], slot t - cache_a - 1
 
   for (int l = 0; l < L; ++l) {
     HIPCHK(c, launch_fill_zero(c->acc_in[l], (size_t)pre_of(n, l) * n.N[l] * 8, s));
@@ -1551,12 +1555,25 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       case OP_REFWD1: {
         // rebuild the fine checkpoints x_{a+F}, x_{a+2F}, ..., x_b, one fine interval at a time: the
         // chunk buffer takes the currents of the interval, the scan keeps only its last state
-        tm.begin(1);
+        if (ccache) { // the currents of the whole segment in one launch, kept for Re-Forward_2
+          const int seg_end = std::min((op.a / p.C + 1) * p.C, T);
+          tm.begin(1);
+          HIPCHK(c, launch_recompute_currents(n, op.a, seg_end, ccache, op.a, slot, s));
+          tm.end();
+          cache_a = op.a; cache_b = seg_end;
+        }
         for (int a = op.a, m = 0; a < op.b; a += p.F, ++m) {
           const float *src = m == 0 ? seg_src : lckpt + (size_t)(m - 1) * slot;
-          HIPCHK(c, launch_recompute(n, a, a + p.F, src, chunk, a, slot, 0, lckpt + (size_t)m * slot, s));
+          if (!ccache) {
+            tm.begin(1);
+            HIPCHK(c, launch_recompute_currents(n, a, a + p.F, chunk, a, slot, s));
+            tm.end();
+          }
+          tm.begin(9);
+          if (ccache) HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, ccache, op.a, slot, 0, lckpt + (size_t)m * slot, s));
+          else HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, chunk, a, slot, 0, lckpt + (size_t)m * slot, s));
+          tm.end();
         }
-        tm.end();
         st.refwd1_steps += op.b - op.a;
         break;
       }
@@ -1568,9 +1585,14 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
         else src = lckpt + (size_t)((op.a - seg_start) / p.F - 1) * slot;
         chunk_base = op.a;
         if (pre_state[i] < 2) {
-          tm.begin(1);
-          if (pre_state[i] == 1) HIPCHK(c, launch_recompute_scan(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
-          else HIPCHK(c, launch_recompute(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s));
+          const bool cached = ccache && cache_a >= 0 && op.a >= cache_a && op.b <= cache_b; // Re-Forward_1 left them
+          if (pre_state[i] == 0 && !cached) {
+            tm.begin(1);
+            HIPCHK(c, launch_recompute_currents(n, op.a, op.b, chunk, op.a, slot, s));
+            tm.end();
+          }
+          tm.begin(9);
+          HIPCHK(c, launch_recompute_scan(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s, cached ? ccache : nullptr, cache_a));
           tm.end();
         }
         st.refwd2_steps += op.b - op.a;
@@ -1661,6 +1683,16 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring) <= budget) { p = q; break; }
     }
   }
+  // Double: with room for C more state slots, Re-Forward_1 computes the synaptic currents of its whole coarse
+  // segment once and keeps them; the scans of Re-Forward_2 read them instead of computing them again (the two
+  // recompute passes of the paper's Double Checkpointing then cost one pass of currents and two of scans).
+  // Same values, same order: bit-identical.  Not with the fused stage launches, which recompute ahead on their own.
+  if (strategy == SNN_DOUBLE && p.C > p.F && c->rf_cache &&
+      !(L > 1 && c->bwd_pipeline && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0))) {
+    Plan q = p;
+    q.n_cache_slots = p.C;
+    if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring) <= budget) p = q;
+  }
   const size_t need_states = (size_t)p.local_slots() * Ms;
   const size_t need_work = work_bytes(n, p.chunk_len);
   const size_t need_spikes = spike_bytes(n, T, ring);
@@ -1744,7 +1776,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
     const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,
-                           ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1]};
+                           ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1], p.n_cache_slots};
     if (!c->graph_exec || !(key == c->graph_key)) {
       if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
       Timer tm{c, false};
@@ -1797,6 +1829,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
         case 5: st.ms_fwd_currents += ms; break;
         case 7: st.ms_bwd_stage += ms; break;
         case 8: st.ms_fwd_stage += ms; break;
+        case 9: st.ms_scan += ms; break;
         default: st.ms_up_gemm += ms; break;
       }
     }

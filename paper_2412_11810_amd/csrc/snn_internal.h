@@ -116,8 +116,10 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
 hipError_t launch_recompute_currents(const NetDev &net, int t0, int t1, float *buf, int t_base, size_t slot_stride,
                                      hipStream_t s);
 // Part 2 of a recompute pass alone: buf already holds the currents of steps t0+1..t1.
+// cur_src != NULL: the currents of step t are read from slot (t - src_base - 1) of cur_src, buf only takes states.
 hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
-                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s);
+                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s,
+                                 const float *cur_src = nullptr, int src_base = 0);
 hipError_t launch_loss(const double *readout, const int32_t *labels, int B, int O, int T, float *ubar,
                        float *g, float *loss, hipStream_t s);
 // Adjoint pass over steps t1, t1-1, ..., t0+1 of a tile.  vbuf holds x_t at slot (t - t_base - 1) and is
@@ -230,7 +232,9 @@ struct Plan {
   int n_stage_slots;  // HBM slots staging device->host copies (layers are pipelined, see launch_forward)
                       // = SNN_FWD_LAG + 2, SNN_FWD_LAG = tiles the lowest layer can be ahead of the top one
   int n_remote;       // host slots
-  int local_slots() const { return chunk_len * n_chunk_bufs + n_local_ckpt + n_load_slots + n_stage_slots; }
+  int n_cache_slots;  // DOUBLE, when the budget has room: the synaptic currents of a whole coarse segment, computed once
+                      // by Re-Forward_1 and read again by the scans of Re-Forward_2 (C slots; 0: both passes compute them)
+  int local_slots() const { return chunk_len * n_chunk_bufs + n_local_ckpt + n_load_slots + n_stage_slots + n_cache_slots; }
 };
 // Resolves defaults (0 -> square-root rules) and validates.  Returns false on invalid arguments.
 bool snn_make_plan(int strategy, int T, int C, int F, Plan *out);

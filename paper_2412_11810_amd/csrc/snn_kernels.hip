@@ -1048,7 +1048,9 @@ static __device__ __forceinline__ void dense_stream(const uint64_t *words, int w
   }
 }
 
-template <int MB>
+// RC only names the instance: 1 for the launches of a recompute pass (modes 0 and 3), 0 for the forward pass's, so
+// that a kernel trace lists the two, whose shapes and durations differ, separately.
+template <int MB, int RC>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_currents_dense(NetDev net, CurJobs jobs, int ws) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1180,9 +1182,12 @@ k_fwd_stage(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, Cur
 // buf holds I_t at the slot of x_t on entry; with store_all the states replace the currents in
 // place, otherwise only the final state is written (state_out).  Same operations, in the same
 // order, as the forward pass, so the recomputed states are bit-identical to the original ones.
+// cur_src != NULL: the currents are read from there (slot of step t = t - src_base - 1) instead of from buf, which
+// then only receives the states.
 __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, const float *__restrict__ state_in,
                                           float *buf, int t_base, size_t slot_stride, int store_all,
-                                          float *__restrict__ state_out, int vblock) {
+                                          float *__restrict__ state_out, int vblock, const float *cur_src = nullptr,
+                                          int src_base = 0) {
   const size_t i = (size_t)vblock * blockDim.x + threadIdx.x;
   const int B = net.B, SN = net.SN;
   if (i >= (size_t)B * SN) return;
@@ -1195,6 +1200,7 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
   const int sh = n & 63;
   float v = state_in[i];
   float *col = buf + i;
+  const float *ccol = cur_src ? cur_src + i - (size_t)(src_base - t_base) * slot_stride : col; // indexed like col
   constexpr int U = 8;
   int t = t0 + 1;
   for (; t + U - 1 <= t1; t += U) {
@@ -1202,7 +1208,7 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
     uint64_t wd[U];
 #pragma unroll
     for (int r = 0; r < U; ++r) {
-      cur[r] = col[(size_t)(t + r - t_base - 1) * slot_stride];
+      cur[r] = ccol[(size_t)(t + r - t_base - 1) * slot_stride];
       wd[r] = mcol[mrow_of(net, l + 1, t + r - 1) * mstride];
     }
 #pragma unroll
@@ -1214,7 +1220,7 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
     }
   }
   for (; t <= t1; ++t) {
-    const float cur = col[(size_t)(t - t_base - 1) * slot_stride];
+    const float cur = ccol[(size_t)(t - t_base - 1) * slot_stride];
     const uint64_t wd = mcol[mrow_of(net, l + 1, t - 1) * mstride];
     float a = net.alpha * v;
     if ((wd >> sh) & 1ull) a = a - net.theta;
@@ -1226,8 +1232,8 @@ __device__ __forceinline__ void scan_body(const NetDev &net, int t0, int t1, con
 
 __global__ void __launch_bounds__(256)
 k_scan(NetDev net, int t0, int t1, const float *__restrict__ state_in, float *buf, int t_base, size_t slot_stride,
-       int store_all, float *__restrict__ state_out) {
-  scan_body(net, t0, t1, state_in, buf, t_base, slot_stride, store_all, state_out, (int)blockIdx.x);
+       int store_all, float *__restrict__ state_out, const float *cur_src, int src_base) {
+  scan_body(net, t0, t1, state_in, buf, t_base, slot_stride, store_all, state_out, (int)blockIdx.x, cur_src, src_base);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2811,12 +2817,15 @@ static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, 
     ws = w1 > ws ? w1 : ws;
   }
   const size_t lds = (size_t)16 * SNN_DENSE_MB * ws * sizeof(uint64_t);
+  const bool rc = jobs.j[0].mode == 0 || jobs.j[0].mode == 3;
   if (lds > 48 * 1024) {
-    const hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB>),
+    const hipError_t ea = hipFuncSetAttribute(rc ? reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB, 1>)
+                                                 : reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB, 0>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (ea != hipSuccess) return ea;
   }
-  hipLaunchKernelGGL(k_currents_dense<SNN_DENSE_MB>, dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
+  if (rc) hipLaunchKernelGGL((k_currents_dense<SNN_DENSE_MB, 1>), dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
+  else hipLaunchKernelGGL((k_currents_dense<SNN_DENSE_MB, 0>), dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
   return hipGetLastError();
 }
 static hipError_t launch_currents_csr(const NetDev &net, const CurJobs &jobs, hipStream_t s) {
@@ -3245,7 +3254,7 @@ hipError_t launch_recompute(const NetDev &net, int t0, int t1, const float *stat
   if (e != hipSuccess) return e;
   const size_t n = (size_t)net.B * net.SN;
   hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
-                     slot_stride, store_all, state_out);
+                     slot_stride, store_all, state_out, (const float *)nullptr, 0);
   return hipGetLastError();
 }
 
@@ -3258,11 +3267,12 @@ hipError_t launch_recompute_currents(const NetDev &net, int t0, int t1, float *b
 }
 
 hipError_t launch_recompute_scan(const NetDev &net, int t0, int t1, const float *state_in, float *buf, int t_base,
-                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s) {
+                                 size_t slot_stride, int store_all, float *state_out, hipStream_t s, const float *cur_src,
+                                 int src_base) {
   if (t1 <= t0) return hipErrorInvalidValue;
   const size_t n = (size_t)net.B * net.SN;
   hipLaunchKernelGGL(k_scan, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, net, t0, t1, state_in, buf, t_base,
-                     slot_stride, store_all, state_out);
+                     slot_stride, store_all, state_out, cur_src, src_base);
   return hipGetLastError();
 }
 

@@ -516,8 +516,11 @@ def test_layer_pipelined_adjoint_is_bitwise_neutral(monkeypatch):
             assert _identical(a[0], got[("fused",) + strategies[0]][0]), (w.name, strat, C, F)
             assert (a[2] > 0) == fusable and b[2] == 0 and c[2] == 0
             if strat != snn.SNN_STANDARD:
-                assert b[1] > c[1] == snn.snn_state_slots(strat, w.T, C, F)[0]
-                assert (a[1] > b[1]) == fusable
+                # (Double with room to spare also keeps the currents of a coarse segment between its two recompute
+                # passes, C more slots, except under the fused stage launches, which recompute ahead on their own)
+                cache = lambda mode: C if (strat == snn.SNN_DOUBLE and C > F and not (fusable and mode.startswith("fused"))) else 0
+                assert b[1] - cache("pipelined") > c[1] - cache("plain") == snn.snn_state_slots(strat, w.T, C, F)[0]
+                assert (a[1] - cache("fused") > b[1] - cache("pipelined")) == fusable
     for k in ("SNN_BWD_FUSE", "SNN_BWD_PIPE", "SNN_PRE_IN_STAGE"):
         monkeypatch.delenv(k, raising=False)
 
