@@ -28,6 +28,12 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
+_T0 = time.perf_counter()
+
+
+def progress(msg):
+    """Progress lines go to stderr (stdout carries the one JSON line): a step of the largest workload takes seconds."""
+    print(f"[bench {time.perf_counter() - _T0:7.1f} s] {msg}", file=sys.stderr, flush=True)
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 MFMA_F32_PEAK_TF = 157.3  # MI355X published fp32 matrix peak
@@ -45,7 +51,7 @@ BUDGET = {2: 8 * 10**9, 3: 4 * 10**9, 4: 32 * 10**9}
 SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3, "hier": 4}  # hier: (nb_local, chunk)
 
 
-def work_model(w, rates, in_rate, T, refwd_steps, rec_density):
+def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, dw_tile_chunks=0):
     """Own work of one training step per kernel kind: what the event-driven method must do, whatever a kernel
     does internally -- bytes of the weight rows of ACTIVE presynaptic neurons (existing synapses only for a masked
     recurrent matrix kept as compressed rows: 4-byte value + 2-byte index), one add per such weight, the dense
@@ -68,7 +74,10 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density):
     out["fwd_seq"] = ("alu", seq_adds) if max(N) <= 256 else ("hbm", seq_bytes)
     # recompute: part 1, the currents (weight rows of the events + the current written) and part 2, the scan (current
     # read, state written, one spike bit read)
-    out["recompute"] = ("hbm", refwd_steps * sum(4.0 * N[l] * ev_in[l] + row_rec[l] * ev_rec[l] + 4.0 * N[l] * B for l in range(L)))
+    # (cur_steps: the steps whose currents the recompute passes actually computed -- Double keeps a segment's currents
+    # between its two passes when the budget has room, so they are computed once)
+    cur_steps = refwd_steps if cur_steps is None else cur_steps
+    out["recompute"] = ("hbm", cur_steps * sum(4.0 * N[l] * ev_in[l] + row_rec[l] * ev_rec[l] + 4.0 * N[l] * B for l in range(L)))
     out["scan"] = ("hbm", refwd_steps * sum((8.0 + 1.0 / 8.0) * N[l] * B for l in range(L)))
     # adjoint recurrence: layers wider than 1024 stream their recurrent matrix once per step for the whole batch
     if max(N) > 1024:
@@ -81,9 +90,17 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density):
     dw_bytes = T * (sum(8.0 * N[l] * ev_in[l] + 8.0 * ent_rec[l] * ev_rec[l] for l in range(L)) + 8.0 * w.n_out * ev_out)
     dw_adds = T * (sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L)) + w.n_out * ev_out)
     out["dw"] = ("hbm", dw_bytes)
+    if dw_tile_chunks:
+        # the tiled event-driven kernel keeps the fp64 accumulators of a tile in registers for a whole launch (one
+        # adjoint tile of the backward pass): its own HBM work is the accumulators read and written once per launch,
+        # the adjoint rows of every matrix's postsynaptic layer read once and the spike words -- far below the
+        # read-modify-write per event of the scatter form priced above
+        entries = sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out
+        rows = T * B * (sum(4.0 * 2 * N[l] + (pre_n[l] + N[l]) / 8.0 for l in range(L)) + 4.0 * w.n_out + N[-1] / 8.0)
+        out["dw"] = ("hbm", dw_tile_chunks * 16.0 * entries + rows)
     # fused launches of the narrow-layer networks: the recurrences (dense) + the adds of the weight gradients and of
     # the recompute currents that ride along; the forward stage: the adds of the active rows
-    rec_adds = refwd_steps * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L))
+    rec_adds = cur_steps * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L))
     out["bwd_stage"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)) + dw_adds + rec_adds)
     out["fwd_stage"] = ("alu", T * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L)))
     out["bwd_inter"] = out["up_gemm"]
@@ -208,7 +225,9 @@ def main():
         return
 
     w = synth.config(args.config, **({"T": args.T} if args.T else {}), **({"gain": args.gain} if args.gain else {}))
+    progress(f"drawing the synthetic workload {w.name} (T={w.T}, batch {w.B})")
     d = synth.generate(w)
+    progress("workload drawn; loading weights")
     x = torch.from_numpy(d["in_spikes"]).to(dev)
     y = torch.from_numpy(d["labels"]).to(dev)
     if args.host_inputs:  # the library copies them to the device inside snn_bind_inputs, every step
@@ -305,12 +324,17 @@ def main():
         return
 
     def time_strategy(name, steps, warmup):
-        for _ in range(warmup):
+        for i in range(warmup):
             step(name)
+            progress(f"{name}: warm-up step {i + 1}/{warmup} done")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
+        last = t0
+        for i in range(steps):
             step(name)
+            if time.perf_counter() - last > 20.0:  # (each call returns after its step has completed)
+                progress(f"{name}: timed step {i + 1}/{steps} done")
+                last = time.perf_counter()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
@@ -327,8 +351,10 @@ def main():
 
     # instrumented (eager) steps of the timed strategy: per-kernel-kind durations from HIP events
     # recorded on the stream the kernels run on; the second one is used (the first pays one-time costs)
+    progress(f"timed: {sec * 1e3:.1f} ms per step; instrumented steps")
     step(args.strategy, stats=True)
     st = step(args.strategy, stats=True)
+    progress("instrumented steps done")
     rates = list(st.firing_rate)[: len(w.n_hidden)]
     in_rate = float(d["in_spikes"].mean())
     C, F = params[args.strategy]
@@ -342,13 +368,24 @@ def main():
     n_tiles = sum(-(-(min(a + seg, w.T) - a) // 64) for a in range(0, w.T, seg))   # forward tiles of <= 64 steps
     n_rec = sum(1 for o in sched if o[0] == "REFWD2") + sum(-(-(o[2] - o[1]) // max(F, 1)) for o in sched if o[0] == "REFWD1")
     L = len(w.n_hidden)
-    model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density)
+    big = any(4.0 * max(pn, n) * n >= (32 << 20) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))
+    dw_env = os.environ.get("SNN_DW", "")
+    dw_tile = w.B <= 64 and (dw_env == "tile" or (big and dw_env not in ("mfma", "event")))
+    model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density,
+                       cur_steps=st.refwd_current_steps or (st.refwd1_steps + st.refwd2_steps),
+                       dw_tile_chunks=n_bwd if dw_tile else 0)
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute, "scan": st.ms_scan,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
     # launches of each kind's main kernel per step (layers that share a width and a pipeline stage share a launch)
     n_stage = n_tiles + 2 * (L - 1)
-    launches = {"fwd_seq": n_stage, "fwd_currents": n_stage, "recompute": max(1, n_rec), "scan": max(1, n_rec),
+    n_cur = n_rec
+    if 0 < st.refwd_current_steps < st.refwd1_steps + st.refwd2_steps:
+        # Double kept the currents of a coarse segment: one current launch per segment with a Re-Forward_1 pass, plus
+        # one per chunk of the segments that have none
+        cached = {o[1] // C for o in sched if o[0] == "REFWD1"}
+        n_cur = len(cached) + sum(1 for o in sched if o[0] == "REFWD2" and o[1] // C not in cached)
+    launches = {"fwd_seq": n_stage, "fwd_currents": n_stage, "recompute": max(1, n_cur), "scan": max(1, n_rec),
                 "adjoint": n_bwd * L if max(w.n_hidden) > 1024 else n_bwd + L - 1, "up_gemm": max(1, n_bwd + L - 2),
                 "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
                 "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
@@ -363,7 +400,6 @@ def main():
     if st.ms_fwd_stage > 0:
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     wide = max(w.n_hidden) > 256
-    big = any(4.0 * max(pn, n) * n >= (32 << 20) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))
     csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and os.environ.get("SNN_CSR", "") == "1"
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
@@ -371,7 +407,7 @@ def main():
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
                  "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
                  "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
-                 "scan": "k_scan", "up_gemm": "k_bwd_inter" if L > 2 else "k_up_gemm", "dw": "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "scan": "k_scan", "up_gemm": "k_bwd_inter" if L > 2 else "k_up_gemm", "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
@@ -447,6 +483,7 @@ def main():
     # per time step next to Standard's.
     long_seq = None
     if not args.no_long:
+        progress("10x-sequence-length comparison")
         T_std = max(1, w.T // 10)
         cfg_std = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, T_std, w.B)
         ref_budget = snn.snn_bytes_required(cfg_std, snn.SNN_STANDARD, T_std)
@@ -519,6 +556,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
+        progress("CPU baseline (oracle)")
         import oracle
         # the box's share of host cores: OMP_NUM_THREADS is set to it on the GPU machine (os.cpu_count() shows the
         # whole machine); the oracle parallelises over batch elements
@@ -564,6 +602,9 @@ def main():
                    "hbm_spike_bytes": int(st.bytes_spikes), "host_spike_bytes": int(st.bytes_host_spikes),
                    "spike_link_bytes_per_step": int(st.spike_d2h_bytes + st.spike_h2d_bytes),
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
+                   "steps_per_pass": {"forward": int(st.fwd_steps), "re_forward_1": int(st.refwd1_steps),
+                                      "re_forward_2": int(st.refwd2_steps), "backward": int(st.bwd_steps),
+                                      "recompute_steps_whose_currents_were_computed": int(st.refwd_current_steps)},
                    "other_strategies_neuron_timesteps_per_s": others},
         "roofline": roofline, "cpu_baseline": cpu, "host_link": host_link, "long_sequence": long_seq,
     }

@@ -111,6 +111,8 @@ typedef struct {
   int64_t spike_d2h_bytes, spike_h2d_bytes; /* spike bitmask traffic over the host link (spike_tier 1) */
   int64_t bytes_host_spikes;    /* pinned host memory holding the hidden layers' spike bitmasks (spike_tier 1) */
   int64_t fwd_steps, refwd1_steps, refwd2_steps, bwd_steps; /* time steps per pass             */
+  int64_t refwd_current_steps; /* time steps whose synaptic currents the recompute passes computed: refwd1 + refwd2
+                                  unless Double kept a segment's currents between its two passes           */
   int32_t local_state_slots; /* states resident in HBM at the peak (M_s units)                 */
   int32_t remote_state_slots;
   float firing_rate[SNN_MAX_LAYERS]; /* measured mean rate of each hidden layer                */
@@ -246,7 +248,10 @@ void snn_destroy(snn_ctx *ctx);
  *   read by snn_init (fixed for the context's life):
  *     SNN_HOST_TIER=dma|direct   Remote/Double checkpoints by hipMemcpyAsync / written and read by the kernels
  *                                through the mapped pinned block (default: direct up to 1 MiB per state)
- *     SNN_DW=event               event-by-event weight-gradient kernel instead of the matrix-core contraction
+ *     SNN_DW=event|tile|mfma     weight gradients by the event-by-event kernel / the event-driven tiled kernel
+ *                                (batch <= 64) / the matrix-core contraction (default: tiled when some weight
+ *                                matrix has 32 MB or more, else the contraction)
+ *     SNN_RF_CACHE=0             Double: never keep a coarse segment's currents between its two recompute passes
  *     SNN_GRAPH=0                no HIP-graph replay of the training step
  *     SNN_BWD_PIPE=0, SNN_BWD_FUSE=0, SNN_PRE_IN_STAGE=0
  *                                adjoint pass layer by layer / weight gradients in launches of their own /

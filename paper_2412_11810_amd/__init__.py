@@ -45,6 +45,7 @@ class snn_stats(C.Structure):
                 ("n_d2h", C.c_int32), ("n_h2d", C.c_int32), ("spike_d2h_bytes", C.c_int64),
                 ("spike_h2d_bytes", C.c_int64), ("bytes_host_spikes", C.c_int64), ("fwd_steps", C.c_int64),
                 ("refwd1_steps", C.c_int64), ("refwd2_steps", C.c_int64), ("bwd_steps", C.c_int64),
+                ("refwd_current_steps", C.c_int64),
                 ("local_state_slots", C.c_int32), ("remote_state_slots", C.c_int32),
                 ("firing_rate", C.c_float * SNN_MAX_LAYERS)]
 

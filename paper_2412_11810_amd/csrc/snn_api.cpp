@@ -79,6 +79,7 @@ struct snn_ctx {
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
   bool own_stream = false;
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
+  bool dw_tile = false;         // the event-driven tiled kernel (networks with very large matrices, batch <= 64; SNN_DW=tile|mfma)
   bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
   bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
   bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
@@ -464,6 +465,15 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   for (int l = 0; l < L; ++l) {
     const size_t pmax = (size_t)std::max(l == 0 ? n.n_in : n.N[l - 1], n.N[l]);
     if (pmax * n.N[l] * sizeof(float) >= ((size_t)32 << 20)) c->rate_driven = true;
+  }
+  // The weight-gradient kernel is a fixed choice per context (the kernels differ in how they group the fp32 sum of
+  // a time step, and every training step of a context must give the same bits): the event-driven tiled kernel for
+  // networks with a weight matrix far beyond the L2 -- the class whose benchmark configuration runs at a few
+  // percent activity, where the dense contraction multiplies mostly zeros -- and batches of at most 64.
+  c->dw_tile = c->rate_driven && B <= 64;
+  if (const char *e = std::getenv("SNN_DW")) {
+    if (!std::strcmp(e, "tile")) c->dw_tile = B <= 64;
+    else if (!std::strcmp(e, "mfma") || !std::strcmp(e, "event")) c->dw_tile = false;
   }
   HIPCHK(c, hipStreamSynchronize(c->stream));
   return SNN_OK;
@@ -1199,7 +1209,8 @@ struct BwdPipe {
     } else {
       DwBatch db{};
       fill_dw_batch(&db);
-      HIPCHK(c, launch_dw_mfma(db, B, s));
+      if (c->dw_tile) HIPCHK(c, launch_dw_tile(db, B, s));
+      else HIPCHK(c, launch_dw_mfma(db, B, s));
     }
     tm->end();
     done.clear();
@@ -1418,7 +1429,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   pipe.init(std::min(p.chunk_len, SNN_BWD_TILE));
   pipe.dw_every_stage = pipelined;
   pipe.pre_in_stage = c->pre_in_stage;
-  pipe.fused = pipelined && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, pipe.dw_wide) &&
+  pipe.fused = pipelined && c->bwd_fuse && !c->dw_event_driven && !c->dw_tile && bwd_stage_fusable(n, pipe.dw_wide) &&
                (strategy == SNN_STANDARD || p.n_chunk_bufs >= L + 1);
   // Recompute ahead: with two more chunk buffers the currents of the chunk two stages ahead and the scan of
   // the chunk one stage ahead ride in the stage launch (see k_bwd_stage).  pre_state[i] tells how far the
@@ -1560,6 +1571,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
           tm.begin(1);
           HIPCHK(c, launch_recompute_currents(n, op.a, seg_end, ccache, op.a, slot, s));
           tm.end();
+          st.refwd_current_steps += seg_end - op.a;
           cache_a = op.a; cache_b = seg_end;
         }
         for (int a = op.a, m = 0; a < op.b; a += p.F, ++m) {
@@ -1568,6 +1580,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
             tm.begin(1);
             HIPCHK(c, launch_recompute_currents(n, a, a + p.F, chunk, a, slot, s));
             tm.end();
+            st.refwd_current_steps += p.F;
           }
           tm.begin(9);
           if (ccache) HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, ccache, op.a, slot, 0, lckpt + (size_t)m * slot, s));
@@ -1590,6 +1603,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
             tm.begin(1);
             HIPCHK(c, launch_recompute_currents(n, op.a, op.b, chunk, op.a, slot, s));
             tm.end();
+            st.refwd_current_steps += op.b - op.a;
           }
           tm.begin(9);
           HIPCHK(c, launch_recompute_scan(n, op.a, op.b, src, chunk, op.a, slot, 1, nullptr, s, cached ? ccache : nullptr, cache_a));
@@ -1675,7 +1689,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   if (L > 1 && c->bwd_pipeline && strategy != SNN_STANDARD) {
     // one more buffer when the weight gradients of a stage are fused into the next stage's launch, and two
     // more again when the recompute of the next two chunks rides in it as well
-    const bool fuse = c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0);
+    const bool fuse = c->bwd_fuse && !c->dw_event_driven && !c->dw_tile && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0);
     const int cand[3] = {fuse ? L + 3 : L, fuse ? L + 1 : L, L};
     for (int nb : cand) {
       Plan q = p;
@@ -1688,7 +1702,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   // recompute passes of the paper's Double Checkpointing then cost one pass of currents and two of scans).
   // Same values, same order: bit-identical.  Not with the fused stage launches, which recompute ahead on their own.
   if (strategy == SNN_DOUBLE && p.C > p.F && c->rf_cache &&
-      !(L > 1 && c->bwd_pipeline && c->bwd_fuse && !c->dw_event_driven && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0))) {
+      !(L > 1 && c->bwd_pipeline && c->bwd_fuse && !c->dw_event_driven && !c->dw_tile && bwd_stage_fusable(n, dw_wide_tiles(n) ? 1 : 0))) {
     Plan q = p;
     q.n_cache_slots = p.C;
     if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring) <= budget) p = q;

@@ -183,6 +183,8 @@ struct DwBatch {
   int wide;                 // tile shape, fixed per network (see snn_dw_wide_tiles)
 };
 hipError_t launch_dw_mfma(DwBatch batch, int B, hipStream_t s);
+// The same update event by event from LDS tiles (see k_dw_tile); batch sizes up to 64.
+hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s);
 // The recurrences of a stage and the weight-gradient contraction of the previous stage in one launch
 // (see k_bwd_stage).  Only for networks bwd_stage_fusable() accepts; the caller guarantees that the two
 // parts touch different tiles.

@@ -2576,6 +2576,117 @@ k_dw_mfma(DwBatch batch, int B) {
   dw_mfma_body<NT, CW>(batch, B, (int)blockIdx.x, smem);
 }
 
+// B5, event-driven and tiled (networks with very large matrices at a few percent activity, where the dense
+// contraction above spends nineteen of twenty matrix-core operations on zero spikes).  Workgroup = 128 presynaptic
+// rows x 256 postsynaptic columns of one matrix, 8 wavefronts: wavefront w owns rows 16w .. 16w+15, lane q the
+// columns 4q .. 4q+3, and keeps the 64 fp64 accumulators of its (row, column) pairs in registers for the whole
+// launch (loaded from and stored back to the accumulators in HBM, so the sequence of operations per element is
+// the one of the dense version: per time step, descending, an fp32 sum over the batch elements that spiked,
+// ascending, started from zero, then one fp64 add).  The time axis runs in tiles of floor(64 / B) steps: the tile's
+// adjoint rows P[(t, b)][256 columns] go to LDS (64 KB; the next tile's are in flight in registers meanwhile) and so
+// do the spike words of its rows for the workgroup's 128 presynaptic neurons; a ballot over the rows turns the
+// words into, per presynaptic neuron, the 64-bit set of rows in which it spiked (wavefront-uniform), and only
+// those rows are read from LDS and added: one 16-byte LDS read and four adds per (spike, four columns).
+__global__ void __launch_bounds__(512)
+k_dw_tile(DwBatch batch, int B) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int PJ = 128, PC = 256, RT = 64;
+  float *P = (float *)smem;                              // [RT][PC]
+  uint64_t *Wv = (uint64_t *)(P + RT * PC);              // [2][RT] spike words of the tile's rows
+  int di = 0;
+  while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
+  const DwDesc &d = batch.d[di];
+  const int tile = (int)blockIdx.x - d.tile0;
+  const int j0 = (tile / d.tiles_n) * PJ, n0 = (tile % d.tiles_n) * PC;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = d.t0, t1 = d.t1, t_base = d.t_base;
+  const int TS = RT / B;                                  // time steps per tile (B <= 64)
+  const int jw = j0 + 16 * wave;                          // first presynaptic row of this wavefront
+  const int wsel = (16 * wave) >> 6, bitbase = (16 * wave) & 63;
+  const int c0 = n0 + 4 * lane;
+  // accumulators: continued from HBM
+  double acc[16][4];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      acc[i][c] = (jw + i < d.n_pre && c0 + c < d.n_post) ? d.acc[(size_t)(jw + i) * d.n_post + c0 + c] : 0.0;
+  // staging of a tile: thread -> 8 x (row, 4 columns); 64 threads cover one row's 256 columns
+  const bool al = ((d.post_off + n0) & 3) == 0 && (d.post_stride & 3) == 0 && (d.slot_stride & 3) == 0 &&
+                  (((uintptr_t)d.post) & 15) == 0 && n0 + PC <= d.n_post;
+  float4 stg[8];
+  auto tile_load = [&](int t_hi, int nts) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int r = 8 * k + wave, ts = r / B, b = r - ts * B; // row r of the tile: step t_hi - ts, batch element b
+      const bool ok = ts < nts;
+      const float *prow = d.post + (size_t)(t_hi - (ok ? ts : 0) - t_base - 1) * d.slot_stride + d.post_off +
+                          (size_t)(ok ? b : 0) * d.post_stride;
+      float4 v;
+      if (al) {
+        v = *reinterpret_cast<const float4 *>(prow + c0);
+      } else {
+        v.x = c0 + 0 < d.n_post ? prow[c0 + 0] : 0.0f;
+        v.y = c0 + 1 < d.n_post ? prow[c0 + 1] : 0.0f;
+        v.z = c0 + 2 < d.n_post ? prow[c0 + 2] : 0.0f;
+        v.w = c0 + 3 < d.n_post ? prow[c0 + 3] : 0.0f;
+      }
+      stg[k] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+  };
+  auto tile_store = [&](int t_hi, int nts) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) *reinterpret_cast<float4 *>(P + (size_t)(8 * k + wave) * PC + 4 * lane) = stg[k];
+    if (tid < 2 * RT) { // spike words of the tile's rows for presynaptic neurons j0 .. j0+127
+      const int r = tid & (RT - 1), ws = tid >> 6, ts = r / B, b = r - ts * B;
+      uint64_t wv = 0ull;
+      if (ts < nts && (j0 >> 6) + ws < d.pre_words) {
+        const int tt = t_hi - ts - d.lag;
+        wv = d.pre_mask[((size_t)(d.pre_ring > 0 ? tt % d.pre_ring : tt) * B + b) * d.pre_words + (j0 >> 6) + ws];
+      }
+      Wv[ws * RT + r] = wv;
+    }
+  };
+  const uint64_t bmask = B >= 64 ? ~0ull : ((1ull << B) - 1ull);
+  int t_hi = t1;
+  tile_load(t_hi, t_hi - t0 < TS ? t_hi - t0 : TS);
+  while (t_hi > t0) {
+    const int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
+    __syncthreads(); // everybody is done with the previous tile
+    tile_store(t_hi, nts);
+    __syncthreads();
+    const int t_next = t_hi - nts;
+    if (t_next > t0) tile_load(t_next, t_next - t0 < TS ? t_next - t0 : TS); // in flight during the adds below
+    const uint64_t wv = Wv[wsel * RT + lane];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint64_t m = __ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
+      if (m == 0ull) continue;
+      for (int ts = 0; ts < nts; ++ts) {
+        uint64_t mt = (m >> (ts * B)) & bmask;
+        if (mt == 0ull) continue;
+        float4 part = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        while (mt) {
+          const int r = ts * B + (int)__builtin_ctzll(mt);
+          mt &= mt - 1ull;
+          const float4 pv = *reinterpret_cast<const float4 *>(P + (size_t)r * PC + 4 * lane);
+          part.x = part.x + pv.x; part.y = part.y + pv.y; part.z = part.z + pv.z; part.w = part.w + pv.w;
+        }
+        acc[i][0] = acc[i][0] + (double)part.x;
+        acc[i][1] = acc[i][1] + (double)part.y;
+        acc[i][2] = acc[i][2] + (double)part.z;
+        acc[i][3] = acc[i][3] + (double)part.w;
+      }
+    }
+    t_hi = t_next;
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (jw + i < d.n_pre && c0 + c < d.n_post) d.acc[(size_t)(jw + i) * d.n_post + c0 + c] = acc[i][c];
+}
+
 // One stage of the layer-pipelined backward pass takes two launches.
 // k_bwd_stage (512 threads), workgroup ranges in this order:
 //   [0, n_adj)        adjoint recurrences of the stage (job = block / B, batch element = block % B)
@@ -3542,6 +3653,24 @@ hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag
   const dim3 grid(n_pre, (n_post + 256 * DW_NPT - 1) / (256 * DW_NPT));
   hipLaunchKernelGGL(k_dw, grid, dim3(256), 0, s, pre_mask, pre_words, lag, postbuf, slot_stride, post_stride,
                      post_off, n_post, B, t0, t1, t_base, dW, pre_ring);
+  return hipGetLastError();
+}
+
+hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s) {
+  if (batch.count <= 0) return hipSuccess;
+  if (B > 64) return hipErrorInvalidValue; // a tile is at least one whole time step of at most 64 rows
+  int total = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    if (batch.d[i].t1 <= batch.d[i].t0) return hipErrorInvalidValue;
+    batch.d[i].tiles_n = (batch.d[i].n_post + 255) / 256;
+    batch.d[i].tile0 = total;
+    total += ((batch.d[i].n_pre + 127) / 128) * batch.d[i].tiles_n;
+  }
+  const size_t lds = (size_t)64 * 256 * sizeof(float) + (size_t)2 * 64 * sizeof(uint64_t);
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_dw_tile),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_dw_tile, dim3(total), dim3(512), lds, s, batch, B);
   return hipGetLastError();
 }
 

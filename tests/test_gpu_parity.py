@@ -886,3 +886,35 @@ def test_spike_bitmasks_on_the_host_tier(hidden, B, T, tier_env, strategies, mon
         _check_grads(_gpu_grads(net, L), ref64, short.name)
     finally:
         net.snn_destroy()
+
+
+@pytest.mark.parametrize("n_in,hidden,n_out,B,T", [(70, (100, 72, 130), 7, 3, 40), (50, (300, 1026), 5, 12, 21),
+                                                   (40, (256, 256), 20, 32, 70), (33, (520,), 9, 64, 9),
+                                                   (33, (130, 64), 3, 40, 17), (24, (64,), 2, 1, 30)])
+def test_event_driven_tiled_weight_gradients(n_in, hidden, n_out, B, T, monkeypatch):
+    """The tiled event-driven weight-gradient kernel (the default for networks with very large matrices, forced
+    here with SNN_DW=tile): row and column tiles that are ragged, column offsets that are not multiples of four,
+    batches that fill a 64-row tile exactly, partly, and with one element, several time steps per tile.  Against the
+    oracle, bit-identical between strategies, and within the tolerance of the matrix-core contraction."""
+    w = synth.Workload("dwtile_" + "x".join(map(str, hidden)), n_in, hidden, n_out, T=T, B=B, p_in=0.1, gain=0.5, seed=81 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    got = {}
+    for mode in ("tile", "mfma"):
+        monkeypatch.setenv("SNN_DW", mode)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            net.snn_bptt(snn.SNN_CHUNK, 0, 6)
+            got[mode] = _gpu_grads(net, L)
+        finally:
+            net.snn_destroy()
+    flat = lambda g: list(g[0]) + list(g[1]) + [g[2]]
+    for a, b in zip(flat(got["tile"]), flat(got["mfma"])):
+        scale = float(np.max(np.abs(b))) or 1.0
+        assert float(np.max(np.abs(a - b))) <= 1e-5 * scale
+    monkeypatch.setenv("SNN_DW", "tile")
+    first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 6), (snn.SNN_DOUBLE, 8, 3), (snn.SNN_REMOTE, 5, 0)],
+                            nthreads=4, check_states=False)
+    assert _identical(first, got["tile"])
+    monkeypatch.delenv("SNN_DW")
