@@ -377,6 +377,13 @@ def main():
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute, "scan": st.ms_scan,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
+    # adjoint recurrence of layers wider than 1024: event-driven rows under a surrogate window, chip-wide over the
+    # compressed rows for a masked matrix (all layers of a pipeline stage in one launch), else chip-wide over the
+    # dense-stored matrix (one launch per layer and tile)
+    ws_env = os.environ.get("SNN_WS_KERNEL", "")
+    adj_kernel = ("k_adj_rec_rows" if (args.surr_window > 0 and ws_env in ("", "rows", "rows_all")) or ws_env in ("rows", "rows_all") else
+                  "k_adj_rec_csrw" if (w.rec_density < 1.0 and w.B <= 64 and os.environ.get("SNN_CSR", "") != "0" and ws_env in ("", "csrw")) else
+                  "k_adj_rec_wide")
     # launches of each kind's main kernel per step (layers that share a width and a pipeline stage share a launch)
     n_stage = n_tiles + 2 * (L - 1)
     n_cur = n_rec
@@ -386,7 +393,8 @@ def main():
         cached = {o[1] // C for o in sched if o[0] == "REFWD1"}
         n_cur = len(cached) + sum(1 for o in sched if o[0] == "REFWD2" and o[1] // C not in cached)
     launches = {"fwd_seq": n_stage, "fwd_currents": n_stage, "recompute": max(1, n_cur), "scan": max(1, n_rec),
-                "adjoint": n_bwd * L if max(w.n_hidden) > 1024 else n_bwd + L - 1, "up_gemm": max(1, n_bwd + L - 2),
+                "adjoint": n_bwd * L if (max(w.n_hidden) > 1024 and adj_kernel == "k_adj_rec_wide") else n_bwd + L - 1,
+                "up_gemm": max(1, n_bwd + L - 2),
                 "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
                 "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
     if st.ms_bwd_stage > 0:
@@ -409,7 +417,7 @@ def main():
                  "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
                  "scan": "k_scan", "up_gemm": "k_bwd_inter" if L > 2 else "k_up_gemm", "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
-                 "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else "k_adj_rec_wide")}
+                 "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else adj_kernel)}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
     kinds = {}
     for k, (bound, work) in model.items():

@@ -40,14 +40,16 @@ struct NetDev {
   float alpha, beta, theta, k;
   float win;  // surrogate window (<= 0: none)
   // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step
-  // (0: not known yet -> dense, 1: event-by-event gather, 2: dense matrix-core version); [0] forward currents
+  // (0: not known yet -> dense, 1: event-by-event gather, 2: dense matrix-core version, 3 ([1] only): dense for the
+  // feed-forward part, gather over compressed rows for the recurrent part); [0] forward currents
   // (feed-forward part only), [1] recompute (both parts).  Every choice gives the same bits.
   unsigned char cur_pol[2][SNN_MAXL];
   // Kernel selection forced from outside (test hooks; 0 = the library's own choice).  Every choice gives the same
   // bits.  sel_currents: 1 event-by-event gather, 2 list version on the matrix cores, 3 dense version.
   // sel_adjoint: 1 VALU version of the chip-wide recurrence, 2 one-workgroup-per-batch-element streaming kernel,
   // 3 event-driven rows (neurons inside the surrogate window only), 4 the same kernel evaluating every row, 5 the
-  // chip-wide kernels also under a surrogate window.
+  // chip-wide kernels over the dense-stored matrix, also under a surrogate window, 6 the chip-wide kernel over
+  // compressed rows also under a surrogate window.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
   unsigned char sel_csr; // compressed rows of masked recurrent matrices: 1 never used (dense-stored walk everywhere),

@@ -22,6 +22,24 @@
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+// Sum of x over the 64 lanes, the same bits in every lane (all lanes must be active): neighbours within quads
+// (xor 1, xor 2), the two quads of a half row, the two halves of a row of 16 -- row-local DPP moves, no LDS -- then
+// the four row sums as (r0 + r1) + (r2 + r3).
+static __device__ __forceinline__ float wave_sum(float x) {
+  auto dpp = [](float v, auto ctrl) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value, 0xF, 0xF, true));
+  };
+  x = x + dpp(x, std::integral_constant<int, 0xB1>{});  // quad_perm [1, 0, 3, 2]
+  x = x + dpp(x, std::integral_constant<int, 0x4E>{});  // quad_perm [2, 3, 0, 1]
+  x = x + dpp(x, std::integral_constant<int, 0x141>{}); // row_half_mirror: the other quad of the half row
+  x = x + dpp(x, std::integral_constant<int, 0x140>{}); // row_mirror: the other half of the row
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
 static __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << lane_id()) - 1ull; }
 // Row of the stored spike words of layer index li that holds step t: the rows form a ring in time when only a
 // window of the sequence is kept in HBM (net.mring[li] rows; the rest lives in host memory), otherwise row t.
@@ -553,10 +571,10 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
 // A2 for masked recurrent matrices: the rows of active presynaptic neurons in compressed form (only the
 // synapses that exist).  A wavefront owns SNN_CSR_SUBW postsynaptic neurons and an accumulator for each in LDS.
 // It walks the active rows in ascending order; the lanes take the entries of the row that fall into its range
-// (their postsynaptic indices are distinct) and add them to the accumulators with LDS add instructions, which
-// execute in issue order, round to nearest even and follow the denormal mode like a vector add: every
-// accumulator receives the same addends in the same ascending order as in the dense-stored walk, which adds
-// +0.0f wherever no synapse exists -- the same bits.  Only the owning wavefront ever touches an accumulator.
+// (their postsynaptic indices are distinct) and add them to the accumulators (LDS read, vector add, LDS write; a
+// wavefront's LDS instructions execute in issue order): every accumulator receives the same addends in the same
+// ascending order as in the dense-stored walk, which adds +0.0f wherever no synapse exists -- the same bits.  Only
+// the owning wavefront ever touches an accumulator.
 // ------------------------------------------------------------------------------------------
 template <int U>
 struct CsrGroup { // the entries of U consecutive rows that fall into the wavefront's sub-range, one entry per lane
@@ -572,27 +590,36 @@ static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t
     g.p[u] = __builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
     g.n[u] = in ? __builtin_amdgcn_readlane(nn, (q + u) & (WAVE - 1)) : 0u;
   }
+  // every load unconditional, through a buffer descriptor whose range is the row's entries in this sub-range (lanes
+  // past the end read 0): straight-line code, so the loads of a whole group -- and of the next one -- stay in flight
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    g.c[u] = 0u;
-    g.v[u] = 0.0f;
-    if ((uint32_t)lane < g.n[u]) {
-      g.c[u] = col[g.p[u] + lane];
-      g.v[u] = val[g.p[u] + lane];
-    }
+    const __amdgpu_buffer_rsrc_t rc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(col + g.p[u]), 0, (int)(g.n[u] * sizeof(uint16_t)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rv =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(val + g.p[u]), 0, (int)(g.n[u] * sizeof(float)), 0x00027000);
+    g.c[u] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (uint32_t)lane * 2u, 0, 0);
+    g.v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)lane * 4u, 0, 0));
   }
 }
 template <int U>
 static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, uint32_t c_base, const uint16_t *__restrict__ col,
                                                    const float *__restrict__ val, float *acc_w, int lane) {
+  // Read, add, write back with ordinary LDS instructions: the entries of a row have distinct columns, only this
+  // wavefront touches acc_w, and its LDS instructions execute in program order, so the next row's read sees this
+  // row's write.  (LDS float atomics give the same bits but the counters show the wavefronts waiting two thirds of
+  // their cycles for them.)
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    if ((uint32_t)lane < g.n[u])
-      (void)__hip_atomic_fetch_add(&acc_w[g.c[u] - c_base], g.v[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if ((uint32_t)lane < g.n[u]) {
+      float *a = &acc_w[g.c[u] - c_base];
+      *a = *a + g.v[u];
+    }
     for (uint32_t o = WAVE; o < g.n[u]; o += WAVE) // a row with more than 64 entries in this range: finish it first
-      if (o + lane < g.n[u])
-        (void)__hip_atomic_fetch_add(&acc_w[col[g.p[u] + o + lane] - c_base], val[g.p[u] + o + lane], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (o + lane < g.n[u]) {
+        float *a = &acc_w[col[g.p[u] + o + lane] - c_base];
+        *a = *a + val[g.p[u] + o + lane];
+      }
   }
 }
 // The positions of 64 rows are fetched at once (one row per lane), one block of 64 rows ahead; the entries of two
@@ -2128,8 +2155,8 @@ k_adj_rec_stream(NetDev net, int l, int t0, int t1, float *__restrict__ vbuf, in
 // W_rec . dv_{t+1} that would give ds is never evaluated.  Per step the workgroup (a) classifies its neurons from
 // the stored v_t, finishes the ones outside the window at once and compacts the others into an ascending list
 // (ballot, popcount prefix: the spike compaction of the forward pass applied to |v - theta| < w), (b) evaluates the
-// listed rows only, one wavefront per row: lane-strided products accumulated in index order, then a butterfly sum
-// over the lanes -- an order that depends on the row alone, so listing every row (list_all, the dense form of the
+// listed rows only, one wavefront per row: lane-strided products accumulated in index order, then a fixed-order sum
+// over the lanes (wave_sum) -- an order that depends on the row alone, so listing every row (list_all, the dense form of the
 // very same kernel) gives the same bits for the rows inside the window.  A masked recurrent matrix is read through
 // its compressed rows: only the synapses that exist.  dv_{t+1} of the batch element stays in LDS.
 __global__ void __launch_bounds__(1024)
@@ -2188,9 +2215,7 @@ k_adj_rec_rows(NetDev net, AdjJobs jobs, float *__restrict__ carry, int list_all
     }
     // (b) the listed rows, one wavefront per row (rows wave, wave + NW, ... of the list)
     auto finish = [&](int j, float a0, float a1) {
-      float sacc = a0 + a1;
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) sacc = sacc + __shfl_xor(sacc, o, WAVE);
+      const float sacc = wave_sum(a0 + a1);
       if (lane == 0) {
         const float dn = x_next[j];
         const float ds = (sacc + urow[j]) - net.theta * dn;
@@ -2290,6 +2315,230 @@ k_adj_rec_rows(NetDev net, AdjJobs jobs, float *__restrict__ carry, int list_all
     float *tmp = x_next; x_next = x_cur; x_cur = tmp;
   }
   for (int i = tid; i < N; i += NT) cb[i] = x_next[i];
+}
+
+// B3/B4 for wide layers whose recurrent matrix is masked: the chip-wide recurrence over the compressed rows.
+// Streaming the dense-stored matrix costs 4 N^2 bytes per step whatever the mask; the compressed rows hold 6 bytes
+// per synapse that exists.  Workgroup (job, row block rb, batch group bg) owns R = ceil(N / n_rb) postsynaptic rows
+// and four batch elements: dv_{t+1} of those four, all N neurons, sits in LDS as float4 per neuron (16 N bytes), so
+// one 16-byte LDS read per synapse feeds four FMAs and a row of the matrix is fetched once for four batch elements.
+// The eight (or ceil(B / 4)) workgroups that share a row block are placed on the same die: they stream the same
+// rows at about the same time, so the die's L2 serves seven of the eight reads.  Rows are dealt to the sixteen
+// wavefronts in contiguous runs; a wavefront evaluates a row like k_adj_rec_rows does -- entries lane-strided, two
+// accumulators taking alternate groups of 64 entries, then wave_sum over the lanes: the same order, so the
+// same bits as that kernel listing every row -- with all entries of the next row requested before the products of
+// the current one (the first row of the next step before the step's barrier: the matrix does not change).  Lane r
+// then finishes row r for the four batch elements and writes dv_t as one float4 into the exchange buffer
+// [parity][batch group][N][4]; a counting barrier per (job, batch group) -- the batch groups never wait for each
+// other -- and every workgroup reloads its group's slice into LDS.  Bounded spin and error flag as in k_adj_rec_ws.
+__global__ void __launch_bounds__(1024)
+k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err,
+               unsigned spin_limit, int n_rb, int n_bg, int xg_stride, int lds_n) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_dead;
+  float4 *xs = reinterpret_cast<float4 *>(smem); // [N]: dv_{t+1} of the group's four batch elements
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float4 *sums = xs + lds_n + 64 * wave; // [16][64] behind the widest layer's slice: the row sums of a step, per wavefront
+  if (tid == 0) s_dead = 0;
+  // workgroups are dealt to the eight dies in turn: all batch groups of a (job, row block) onto one die
+  const int G = jobs.count * n_rb;
+  int g, bg;
+  if ((G & 7) == 0) {
+    const int die = (int)blockIdx.x & 7, k = (int)blockIdx.x >> 3;
+    g = die + 8 * (k / n_bg);
+    bg = k % n_bg;
+  } else {
+    g = (int)blockIdx.x / n_bg;
+    bg = (int)blockIdx.x % n_bg;
+  }
+  const int jq = g / n_rb, rb = g % n_rb;
+  const AdjJob &jb = jobs.j[jq];
+  const int l = jb.l, t0 = jb.t0, t1 = jb.t1, t_base = jb.t_base;
+  float *__restrict__ vbuf = jb.vbuf;
+  const float *__restrict__ up = jb.up;
+  const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
+  const uint32_t *__restrict__ sub = net.csr_sub[l];
+  const uint16_t *__restrict__ col = net.csr_col[l];
+  const float *__restrict__ val = net.csr_val[l];
+  const int nsub1 = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW + 1;
+  // rows: the workgroup's [rb R, rb R + R), the wavefront's nr <= 64 consecutive ones from jw0; lane r keeps the
+  // position of row jw0 + r
+  const int R = (N + n_rb - 1) / n_rb, nrw = (R + 15) / 16;
+  const int row_end = (rb + 1) * R < N ? (rb + 1) * R : N;
+  const int jw0 = rb * R + wave * nrw;
+  const int jw1 = jw0 + nrw < row_end ? jw0 + nrw : row_end;
+  const int nr = jw1 > jw0 ? jw1 - jw0 : 0;
+  const int j = jw0 + lane;
+  uint32_t m0 = 0u, m1 = 0u;
+  if (lane < nr) {
+    m0 = sub[(size_t)j * nsub1];
+    m1 = sub[(size_t)j * nsub1 + nsub1 - 1];
+  }
+  float *xq = xg + (size_t)jq * xg_stride; // [2][n_bg][N][4]
+  const __amdgpu_buffer_rsrc_t xres =
+      __builtin_amdgcn_make_buffer_rsrc((void *)xq, 0, (int)((size_t)2 * n_bg * N * 4 * sizeof(float)), 0x00027000);
+  unsigned *cnt = bar + 64 * jq + bg;
+  bool dead = false;
+  unsigned arrivals = 0;
+  auto group_barrier = [&]() {
+    // see k_adj_rec_ws: every wave waits for its own stores, then one arrival per workgroup
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+    __syncthreads();
+    arrivals += (unsigned)n_rb;
+    if (tid == 0 && !dead) {
+      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      unsigned spins = 0;
+      while (spin_limit == 0u || __hip_atomic_load(cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < arrivals) {
+        if (++spins > spin_limit ||
+            ((spins & 63u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          s_dead = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __syncthreads();
+    if (s_dead) dead = true; // keep going to the end of the chunk, never wait again
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  };
+  // dv_{t1+1} of the group's batch elements; nobody writes the carry before every workgroup has read it
+  for (int i = tid; i < N; i += 1024) {
+    float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (!jb.carry_init) {
+      const float *cp = carry + (size_t)(4 * bg) * (SN + O) + off + i;
+      if (4 * bg + 0 < B) v.x = cp[0];
+      if (4 * bg + 1 < B) v.y = cp[(size_t)1 * (SN + O)];
+      if (4 * bg + 2 < B) v.z = cp[(size_t)2 * (SN + O)];
+      if (4 * bg + 3 < B) v.w = cp[(size_t)3 * (SN + O)];
+    }
+    xs[i] = v;
+  }
+  group_barrier();
+  // Entries of a row through buffer loads whose range is the row: lane + 64 i past the end reads 0 (weight 0, column
+  // 0) with no address arithmetic or compare in the vector unit.
+  constexpr int CH = 14, CH2 = 2; // groups of 64 entries per pass (both even: group k always meets accumulator k & 1)
+  struct Row { float w[CH]; uint32_t c[CH]; };
+  auto fetch = [&](Row &r, uint32_t e0, uint32_t e1) {
+    const __amdgpu_buffer_rsrc_t rv =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(val + e0), 0, (int)((e1 - e0) * sizeof(float)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(col + e0), 0, (int)((e1 - e0) * sizeof(uint16_t)), 0x00027000);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      r.w[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(lane * 4), 256 * i, 0));
+      r.c[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (uint32_t)(lane * 2), 128 * i, 0);
+    }
+  };
+  // one row: its entries sit in `r` (requested a row ago); each pair of registers is reloaded with the next row's
+  // entries right after its products, so one row buffer serves both rows
+  Row r;
+  auto do_row = [&](int q) {
+    const uint32_t e0 = __builtin_amdgcn_readlane(m0, q), e1 = __builtin_amdgcn_readlane(m1, q);
+    const int qn = q + 1 < nr ? q + 1 : 0; // after the last row: the first row of the next step
+    const uint32_t n0 = __builtin_amdgcn_readlane(m0, qn), n1 = __builtin_amdgcn_readlane(m1, qn);
+    const __amdgpu_buffer_rsrc_t nv =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(val + n0), 0, (int)((n1 - n0) * sizeof(float)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t nc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(col + n0), 0, (int)((n1 - n0) * sizeof(uint16_t)), 0x00027000);
+    float a0[4] = {0.0f, 0.0f, 0.0f, 0.0f}, a1[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto fma2 = [&](float w0, const float4 &x0, float w1, const float4 &x1) {
+      a0[0] = fmaf(w0, x0.x, a0[0]); a0[1] = fmaf(w0, x0.y, a0[1]);
+      a0[2] = fmaf(w0, x0.z, a0[2]); a0[3] = fmaf(w0, x0.w, a0[3]);
+      a1[0] = fmaf(w1, x1.x, a1[0]); a1[1] = fmaf(w1, x1.y, a1[1]);
+      a1[2] = fmaf(w1, x1.z, a1[2]); a1[3] = fmaf(w1, x1.w, a1[3]);
+    };
+    auto mac2 = [&](float w0, uint32_t c0, float w1, uint32_t c1) { fma2(w0, xs[c0], w1, xs[c1]); };
+    // the LDS reads of a pair of groups are issued before the products of the pair before it
+    float4 xa = xs[r.c[0]], xb = xs[r.c[1]];
+#pragma unroll
+    for (int i = 0; i < CH; i += 2) {
+      float4 na = xa, nb = xb;
+      if (i + 2 < CH) {
+        na = xs[r.c[i + 2]];
+        nb = xs[r.c[i + 3]];
+      }
+      fma2(r.w[i], xa, r.w[i + 1], xb);
+#pragma unroll
+      for (int h = i; h < i + 2; ++h) { // the next row's entries into the registers just used
+        r.w[h] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nv, (uint32_t)(lane * 4), 256 * h, 0));
+        r.c[h] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(nc, (uint32_t)(lane * 2), 128 * h, 0);
+      }
+      xa = na;
+      xb = nb;
+    }
+    if (e1 - e0 > (uint32_t)(CH * WAVE)) { // rows longer than one pass
+      const __amdgpu_buffer_rsrc_t rv =
+          __builtin_amdgcn_make_buffer_rsrc((void *)(val + e0), 0, (int)((e1 - e0) * sizeof(float)), 0x00027000);
+      const __amdgpu_buffer_rsrc_t rc =
+          __builtin_amdgcn_make_buffer_rsrc((void *)(col + e0), 0, (int)((e1 - e0) * sizeof(uint16_t)), 0x00027000);
+      for (uint32_t eb = CH * WAVE; eb < e1 - e0; eb += CH2 * WAVE) {
+        const uint32_t o = eb + (uint32_t)lane;
+        const float w0 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, o * 4u, 0, 0));
+        const float w1 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, (o + WAVE) * 4u, 0, 0));
+        const uint32_t c0 = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, o * 2u, 0, 0);
+        const uint32_t c1 = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (o + WAVE) * 2u, 0, 0);
+        mac2(w0, c0, w1, c1);
+      }
+    }
+    const float4 sum4 = make_float4(wave_sum(a0[0] + a1[0]), wave_sum(a0[1] + a1[1]), wave_sum(a0[2] + a1[2]),
+                                    wave_sum(a0[3] + a1[3]));
+    if (lane == 0) sums[q] = sum4; // read back by lane q of this wavefront when the step's rows are done
+  };
+  if (nr > 0) fetch(r, __builtin_amdgcn_readlane(m0, 0), __builtin_amdgcn_readlane(m1, 0));
+  const size_t slot_stride = (size_t)B * SN;
+  unsigned step = 0;
+  for (int t = t1; t > t0; --t, ++step) {
+    const int wr = (int)(step & 1u);
+    const size_t slot = (size_t)(t - t_base - 1);
+    float vt[4] = {0.0f, 0.0f, 0.0f, 0.0f}, upv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (lane < nr) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (4 * bg + c < B) {
+          vt[c] = vbuf[slot * slot_stride + (size_t)(4 * bg + c) * SN + off + j];
+          upv[c] = up[(slot * B + 4 * bg + c) * ldu + j];
+        }
+    }
+    for (int q = 0; q < nr; ++q) do_row(q);
+    const bool last = t == t0 + 1;
+    if (lane < nr) {
+      const float4 dn4 = xs[j], my4 = sums[lane];
+      const float dn[4] = {dn4.x, dn4.y, dn4.z, dn4.w}, mys[4] = {my4.x, my4.y, my4.z, my4.w};
+      float dv[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bool ok = 4 * bg + c < B;
+        const float ds = (mys[c] + upv[c]) - net.theta * dn[c];
+        const float dvt = fmaf(ds, surrogate(net, vt[c]), net.alpha * dn[c]);
+        dv[c] = ok ? dvt : 0.0f;
+        if (ok) {
+          vbuf[slot * slot_stride + (size_t)(4 * bg + c) * SN + off + j] = dvt;
+          if (last) carry[(size_t)(4 * bg + c) * (SN + O) + off + j] = dvt; // dv_{t0+1}: every workgroup its own rows
+        }
+      }
+      if (!last)
+        *reinterpret_cast<float4 *>(xq + (((size_t)wr * n_bg + bg) * N + j) * 4) = make_float4(dv[0], dv[1], dv[2], dv[3]);
+    }
+    if (last) break; // nobody reads the exchange buffer after the last step
+    group_barrier();
+    const uint32_t xbase = (uint32_t)((((size_t)wr * n_bg + bg) * N) * 4 * sizeof(float));
+    for (int i0 = 0; i0 < N; i0 += 8 * 1024) {
+      float4 r[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * 1024 + tid, ic = i < N ? i : N - 1;
+        r[u] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(xres, xbase + (uint32_t)ic * 16u, 0, 17)); // sc0 sc1
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 + u * 1024 + tid;
+        if (i < N) xs[i] = r[u];
+      }
+    }
+    __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2578,8 +2827,8 @@ k_dw_mfma(DwBatch batch, int B) {
 
 // B5, event-driven and tiled (networks with very large matrices at a few percent activity, where the dense
 // contraction above spends nineteen of twenty matrix-core operations on zero spikes).  Workgroup = 128 presynaptic
-// rows x 256 postsynaptic columns of one matrix, 8 wavefronts: wavefront w owns rows 16w .. 16w+15, lane q the
-// columns 4q .. 4q+3, and keeps the 64 fp64 accumulators of its (row, column) pairs in registers for the whole
+// rows x 256 postsynaptic columns of one matrix, 16 wavefronts: wavefront w owns rows 8w .. 8w+7, lane q the
+// columns 4q .. 4q+3, and keeps the 32 fp64 accumulators of its (row, column) pairs in registers for the whole
 // launch (loaded from and stored back to the accumulators in HBM, so the sequence of operations per element is
 // the one of the dense version: per time step, descending, an fp32 sum over the batch elements that spiked,
 // ascending, started from zero, then one fp64 add).  The time axis runs in tiles of floor(64 / B) steps: the tile's
@@ -2587,10 +2836,13 @@ k_dw_mfma(DwBatch batch, int B) {
 // do the spike words of its rows for the workgroup's 128 presynaptic neurons; a ballot over the rows turns the
 // words into, per presynaptic neuron, the 64-bit set of rows in which it spiked (wavefront-uniform), and only
 // those rows are read from LDS and added: one 16-byte LDS read and four adds per (spike, four columns).
-__global__ void __launch_bounds__(512)
+// (Sixteen wavefronts of 8 rows rather than eight of 16: what bounds the kernel is the round trip LDS read -> add of
+// consecutive events, and four wavefronts per SIMD hide twice as much of it as two.)
+#define DWT_WAVES 16
+__global__ void __launch_bounds__(64 * DWT_WAVES)
 k_dw_tile(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int PJ = 128, PC = 256, RT = 64;
+  constexpr int PJ = 128, PC = 256, RT = 64, NWV = DWT_WAVES, RW = PJ / NWV, SK = RT / NWV; // rows per wavefront, staging loads per thread
   float *P = (float *)smem;                              // [RT][PC]
   uint64_t *Wv = (uint64_t *)(P + RT * PC);              // [2][RT] spike words of the tile's rows
   int di = 0;
@@ -2601,24 +2853,24 @@ k_dw_tile(DwBatch batch, int B) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = d.t0, t1 = d.t1, t_base = d.t_base;
   const int TS = RT / B;                                  // time steps per tile (B <= 64)
-  const int jw = j0 + 16 * wave;                          // first presynaptic row of this wavefront
-  const int wsel = (16 * wave) >> 6, bitbase = (16 * wave) & 63;
+  const int jw = j0 + RW * wave;                          // first presynaptic row of this wavefront
+  const int wsel = (RW * wave) >> 6, bitbase = (RW * wave) & 63;
   const int c0 = n0 + 4 * lane;
   // accumulators: continued from HBM
-  double acc[16][4];
+  double acc[RW][4];
 #pragma unroll
-  for (int i = 0; i < 16; ++i)
+  for (int i = 0; i < RW; ++i)
 #pragma unroll
     for (int c = 0; c < 4; ++c)
       acc[i][c] = (jw + i < d.n_pre && c0 + c < d.n_post) ? d.acc[(size_t)(jw + i) * d.n_post + c0 + c] : 0.0;
-  // staging of a tile: thread -> 8 x (row, 4 columns); 64 threads cover one row's 256 columns
+  // staging of a tile: thread -> SK x (row, 4 columns); 64 threads cover one row's 256 columns
   const bool al = ((d.post_off + n0) & 3) == 0 && (d.post_stride & 3) == 0 && (d.slot_stride & 3) == 0 &&
                   (((uintptr_t)d.post) & 15) == 0 && n0 + PC <= d.n_post;
-  float4 stg[8];
+  float4 stg[SK];
   auto tile_load = [&](int t_hi, int nts) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int r = 8 * k + wave, ts = r / B, b = r - ts * B; // row r of the tile: step t_hi - ts, batch element b
+    for (int k = 0; k < SK; ++k) {
+      const int r = NWV * k + wave, ts = r / B, b = r - ts * B; // row r of the tile: step t_hi - ts, batch element b
       const bool ok = ts < nts;
       const float *prow = d.post + (size_t)(t_hi - (ok ? ts : 0) - t_base - 1) * d.slot_stride + d.post_off +
                           (size_t)(ok ? b : 0) * d.post_stride;
@@ -2636,7 +2888,7 @@ k_dw_tile(DwBatch batch, int B) {
   };
   auto tile_store = [&](int t_hi, int nts) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) *reinterpret_cast<float4 *>(P + (size_t)(8 * k + wave) * PC + 4 * lane) = stg[k];
+    for (int k = 0; k < SK; ++k) *reinterpret_cast<float4 *>(P + (size_t)(NWV * k + wave) * PC + 4 * lane) = stg[k];
     if (tid < 2 * RT) { // spike words of the tile's rows for presynaptic neurons j0 .. j0+127
       const int r = tid & (RT - 1), ws = tid >> 6, ts = r / B, b = r - ts * B;
       uint64_t wv = 0ull;
@@ -2659,7 +2911,7 @@ k_dw_tile(DwBatch batch, int B) {
     if (t_next > t0) tile_load(t_next, t_next - t0 < TS ? t_next - t0 : TS); // in flight during the adds below
     const uint64_t wv = Wv[wsel * RT + lane];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RW; ++i) {
       const uint64_t m = __ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
       if (m == 0ull) continue;
       for (int ts = 0; ts < nts; ++ts) {
@@ -2681,7 +2933,7 @@ k_dw_tile(DwBatch batch, int B) {
     t_hi = t_next;
   }
 #pragma unroll
-  for (int i = 0; i < 16; ++i)
+  for (int i = 0; i < RW; ++i)
 #pragma unroll
     for (int c = 0; c < 4; ++c)
       if (jw + i < d.n_pre && c0 + c < d.n_post) d.acc[(size_t)(jw + i) * d.n_post + c0 + c] = acc[i][c];
@@ -2962,7 +3214,7 @@ static bool currents_job_csr(const NetDev &net, const CurJob &j) {
   const int l = j.lsel;
   if (!net.csr_sub[l]) return false;
   if (net.sel_csr == 2) return true;
-  return (size_t)net.N[l] * net.N[l] * sizeof(float) >= ((size_t)32 << 20) && net.cur_pol[1][l] == 1;
+  return (size_t)net.N[l] * net.N[l] * sizeof(float) >= ((size_t)32 << 20) && (net.cur_pol[1][l] == 1 || net.cur_pol[1][l] == 3);
 }
 // Recompute jobs (mode 0) of layers whose recurrent matrix has compressed rows are split: the feed-forward part
 // goes through the usual kernels (mode 3), the recurrent part through k_currents_csr behind them.
@@ -3472,6 +3724,38 @@ static hipError_t adj_wide_dispatch(const NetDev &net, const AdjJob &jb, float *
   if (nbb == 2) return launch_adj_wide_t<1, 2>(net, jb, carry, ws, device, s, dry, resident);
   return launch_adj_wide_t<1, 4>(net, jb, carry, ws, device, s, dry, resident);
 }
+// Chip-wide recurrence over compressed rows (k_adj_rec_csrw): workgroups that can be resident at once, and the row
+// blocks per job when `count` jobs share a launch (0: does not fit).
+static int adj_csrw_resident() {
+  static int cached[16] = {}; // per device: the occupancy of the kernel does not change
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= 16) return 0;
+  if (!cached[device]) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+    const size_t lds = ((size_t)8192 + 16 * 64) * 4 * sizeof(float); // the widest layer the library takes + the row sums
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_csrw), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+      return 0;
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_csrw, 1024, lds) != hipSuccess) return 0;
+    cached[device] = per_cu * prop.multiProcessorCount;
+    if (cached[device] <= 0) cached[device] = -1;
+  }
+  return cached[device] > 0 ? cached[device] : 0;
+}
+static int adj_csrw_row_blocks(const NetDev &net, int count, int n_max) {
+  const int n_bg = (net.B + 3) / 4;
+  const int n_rb = (adj_csrw_resident() / (n_bg * count)) & ~7; // a multiple of 8: whole row blocks per die
+  if (n_rb < 8 || (n_max + n_rb - 1) / n_rb > 1024) return 0;   // a wavefront keeps the positions of at most 64 rows
+  return n_rb;
+}
+static bool adj_csrw_ok(const NetDev &net, int l, const WsArgs &ws) {
+  const int N = net.N[l], B = net.B;
+  if ((net.sel_adjoint != 0 && net.sel_adjoint != 6) || !net.csr_sub[l] || N <= 1024 || N > 8192 || B > 64 || !ws.xg) return false;
+  if ((size_t)8 * ((B + 3) / 4) * N > (size_t)ws.xg_stride) return false;
+  return adj_csrw_row_blocks(net, 1, N) > 0;
+}
 // SNN_WS_KERNEL=stream keeps wide layers on the one-workgroup-per-batch-element kernel
 static bool adj_wide_ok(const NetDev &net, int l, const WsArgs &ws) {
   const int N = net.N[l], B = net.B;
@@ -3491,7 +3775,10 @@ static bool adj_wide_ok(const NetDev &net, int l, const WsArgs &ws) {
 // Called once when a context is created: the occupancy queries run outside any stream capture.
 void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
   for (int l = 0; l < net.L; ++l)
-    if (net.N[l] > 1024) (void)adj_wide_ok(net, l, ws);
+    if (net.N[l] > 1024) {
+      (void)adj_wide_ok(net, l, ws);
+      (void)adj_csrw_resident();
+    }
   for (int l = 0; l < net.L; ++l)
     if (net.N[l] > 256) { // the sliced sequential part of the forward pass
       SeqJobs probe{};
@@ -3600,6 +3887,25 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       else
         hipLaunchKernelGGL((k_adj_rec_ws<128>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
                            ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+    } else if (adj_csrw_ok(net, l, ws)) {
+      // masked wide layers: every such job of the stage in one launch, the chip divided among them
+      AdjJobs grp{};
+      int n_max = 0;
+      for (int k = i; k < jobs.count; ++k) {
+        const int lk = jobs.j[k].l;
+        if (taken[k] || !adj_csrw_ok(net, lk, ws)) continue;
+        const int nm = net.N[lk] > n_max ? net.N[lk] : n_max;
+        if (grp.count && !adj_csrw_row_blocks(net, grp.count + 1, nm)) continue;
+        grp.j[grp.count++] = jobs.j[k];
+        taken[k] = true;
+        n_max = nm;
+      }
+      const int n_bg = (B + 3) / 4, n_rb = adj_csrw_row_blocks(net, grp.count, n_max);
+      if (n_rb <= 0) return hipErrorInvalidValue;
+      hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * SNN_MAXL * sizeof(unsigned), s);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(k_adj_rec_csrw, dim3(grp.count * n_rb * n_bg), dim3(1024), ((size_t)n_max + 16 * 64) * 4 * sizeof(float),
+                         s, net, grp, carry, ws.xg, ws.bar, ws.err, ws.spin_limit, n_rb, n_bg, ws.xg_stride, n_max);
     } else if (adj_wide_ok(net, l, ws)) {
       taken[i] = true;
       hipError_t e = launch_fill_zero(ws.bar, (size_t)64 * sizeof(unsigned), s);
@@ -3670,7 +3976,7 @@ hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s) {
   const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_dw_tile),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_dw_tile, dim3(total), dim3(512), lds, s, batch, B);
+  hipLaunchKernelGGL(k_dw_tile, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
   return hipGetLastError();
 }
 

@@ -556,15 +556,15 @@ def test_gather_and_matrix_core_currents_agree(monkeypatch):
     monkeypatch.delenv("SNN_CURRENTS")
 
 
-@pytest.mark.parametrize("width", [512, 2048, 1088])
-def test_barrier_timeout_is_reported_not_hung(monkeypatch, width):
+@pytest.mark.parametrize("width,density", [(512, 1.0), (2048, 1.0), (1088, 1.0), (2048, 0.2)])
+def test_barrier_timeout_is_reported_not_hung(monkeypatch, width, density):
     """The chip-wide adjoint kernels of wide layers (weights in registers up to 1024 neurons, streamed
-    above) and the sliced sequential part of their forward pass (widths from 2048 that are multiples of 1024)
+    above, over compressed rows for a masked matrix) and the sliced sequential part of their forward pass (widths from 2048 that are multiples of 1024)
     synchronise their workgroups with a counting barrier
     that polls a bounded number of times.  With the limit forced to zero from the host every workgroup
     gives up at its first barrier: all kernels still run to completion, and snn_bptt reports the
     failure instead of returning gradients.  A context created afterwards works normally."""
-    w = synth.Workload(f"wide_24-{width}-6", 24, (width,), 6, T=12, B=4, p_in=0.1, seed=11)
+    w = synth.Workload(f"wide_24-{width}-6", 24, (width,), 6, T=12, B=4, p_in=0.1, rec_density=density, seed=11)
     d = synth.generate(w)
     monkeypatch.setenv("SNN_WS_SPIN_LIMIT", "0")
     net = snn.from_workload(w, d)
@@ -734,6 +734,9 @@ def test_compressed_rows_of_masked_matrices_are_bitwise_neutral(hidden, B, T, de
     d = synth.generate(w)
     L = len(hidden)
     got = {}
+    # (the adjoint recurrence of wide masked layers has a kernel of its own over the compressed rows, with its own
+    # order of summation: kept out of this bitwise comparison, it has a test of its own)
+    monkeypatch.setenv("SNN_WS_KERNEL", "chip")
     for csr in ("1", "0"):
         monkeypatch.setenv("SNN_CSR", csr)
         net = snn.from_workload(w, d)
@@ -746,6 +749,7 @@ def test_compressed_rows_of_masked_matrices_are_bitwise_neutral(hidden, B, T, de
         finally:
             net.snn_destroy()
     monkeypatch.delenv("SNN_CSR")
+    monkeypatch.delenv("SNN_WS_KERNEL")
     assert _identical(got["1"][0], got["0"][0])
     for a, b in zip(got["1"][1], got["0"][1]):
         assert np.array_equal(a, b) and a.sum() > 0
@@ -779,6 +783,55 @@ def test_compressed_rows_keep_denormal_sums():
             assert np.array_equal(net.snn_get_state(0, t).view(np.uint32), ref_forced.v[0][t - 1].view(np.uint32)), t
     finally:
         net.snn_destroy()
+
+
+@pytest.mark.parametrize("hidden,B,T,density,window", [
+    ((2048,), 5, 14, 0.1, 0.0),        # one job, a ragged batch group (5 = 4 + 1)
+    ((1536, 1100), 3, 12, 0.3, 0.0),   # two jobs of different widths in one launch, ragged row blocks
+    ((4096, 4096), 8, 10, 0.1, 0.0),   # two batch groups
+    ((2048,), 2, 9, 0.9, 0.0),         # rows of ~1840 entries: more than one pass of 14 x 64
+    ((2048, 256), 6, 12, 0.2, 0.0),    # a narrow layer beside it (weights in registers)
+    ((3072,), 4, 10, 0.15, 0.5)])      # under a surrogate window, forced (the library would list rows)
+def test_chip_wide_adjoint_over_compressed_rows(hidden, B, T, density, window, monkeypatch):
+    """Wide layers (more than 1024 neurons) with a masked recurrent matrix run the adjoint recurrence chip-wide over
+    the compressed rows: four batch elements per workgroup with their dv_{t+1} in LDS, rows dealt to wavefronts,
+    a barrier per batch group and step.  A row is summed in the order of the rows kernel (lane-strided, two
+    accumulators, butterfly), so the gradients must be the very bits of that kernel evaluating every row
+    (SNN_WS_KERNEL=rows_all); they must agree with the dense-stored chip-wide kernel (SNN_CSR=0) within the gradient
+    tolerance, and match the oracle under every strategy."""
+    w = synth.Workload("csrw_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=0.8,
+                       rec_density=density, seed=71 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    got = {}
+    for mode in ("csrw", "rows_all", "dense"):
+        monkeypatch.delenv("SNN_WS_KERNEL", raising=False)
+        monkeypatch.delenv("SNN_CSR", raising=False)
+        if mode == "rows_all":
+            monkeypatch.setenv("SNN_WS_KERNEL", "rows_all")
+        elif mode == "dense":
+            monkeypatch.setenv("SNN_CSR", "0")
+            monkeypatch.setenv("SNN_WS_KERNEL", "chip")
+        elif window > 0:
+            monkeypatch.setenv("SNN_WS_KERNEL", "csrw")
+        net = snn.from_workload(w, d, surr_window=window)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)
+            got[mode] = _gpu_grads(net, L)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)  # the replayed graph
+            assert _identical(_gpu_grads(net, L), got[mode]), mode
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_WS_KERNEL", raising=False)
+    monkeypatch.delenv("SNN_CSR", raising=False)
+    assert _identical(got["csrw"], got["rows_all"])
+    flat = lambda g: list(g[0]) + list(g[1]) + [g[2]]
+    for a, b in zip(flat(got["csrw"]), flat(got["dense"])):
+        scale = float(np.max(np.abs(b))) or 1.0
+        assert float(np.max(np.abs(a - b))) <= 1e-4 * scale
+    if window <= 0:
+        _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3), (snn.SNN_CHUNK, 0, 5)], nthreads=4)
 
 
 @pytest.mark.parametrize("hidden,B,T,density,window", [((1088,), 5, 14, 1.0, 0.4), ((2048, 1100), 3, 12, 0.15, 0.5),
