@@ -147,17 +147,32 @@ static __device__ __forceinline__ void gather2(const float *__restrict__ Wcat, i
   }
 }
 
-// Turns the bit words of one spike row into the ascending list of active indices: popcount prefix
-// over the words, then the rank of the own bit inside its word (A1, second half).
+// Turns the bit words of one spike row into the ascending list of active indices (A1, second half).  Every
+// wavefront takes a contiguous block of words: the number of spikes before the block is one lane-parallel
+// popcount sum, inside the block a running count; the rank of the own bit inside its word gives the position.
+// (A wavefront summing the popcounts of all earlier words for each of its words costs Wd^2 / 2 LDS reads per
+// step: at 128 words that was half of the time of a step of the sequential forward kernels.)
+template <typename Emit, typename Finish>
+static __device__ __forceinline__ void expand_words(const uint64_t *words, int Wd, int tid, int nt, Emit emit, Finish finish) {
+  const int lane = lane_id(), wave = tid >> 6, nw = nt >> 6;
+  const int per = (Wd + nw - 1) / nw;
+  const int wb = wave * per, we = wb + per < Wd ? wb + per : Wd;
+  if (wb >= Wd) return;
+  int pre = 0;
+  for (int q = lane; q < wb; q += WAVE) pre += __popcll(words[q]);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) pre += __shfl_xor(pre, o, WAVE);
+  for (int widx = wb; widx < we; ++widx) {
+    const uint64_t word = words[widx];
+    if ((word >> lane) & 1ull) emit(pre + __popcll(word & lanemask_lt()), widx * WAVE + lane);
+    pre += __popcll(word);
+  }
+  if (we == Wd) finish(pre); // the wavefront that holds the last word knows the total
+}
 static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd, uint16_t *list, int *cnt, int tid,
                                                   int nt) {
-  for (int widx = tid >> 6; widx < Wd; widx += nt >> 6) {
-    const uint64_t word = words[widx];
-    int pre = 0;
-    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
-    if ((word >> lane_id()) & 1ull) list[pre + __popcll(word & lanemask_lt())] = (uint16_t)(widx * WAVE + lane_id());
-    if (widx == Wd - 1 && lane_id() == 0) *cnt = pre + __popcll(word);
-  }
+  expand_words(words, Wd, tid, nt, [&](int pos, int idx) { list[pos] = (uint16_t)idx; },
+               [&](int total) { if (lane_id() == 0) *cnt = total; });
 }
 
 // The same expansion for the sequential kernels of wide layers: entry = byte offset of the weight row (index * n4),
@@ -165,17 +180,11 @@ static __device__ __forceinline__ void expand_all(const uint64_t *words, int Wd,
 // (a wavefront reads entries four at a time).
 static __device__ __forceinline__ void expand_offsets(const uint64_t *words, int Wd, uint32_t *offs, int *cnt, int tid,
                                                       int nt, uint32_t n4) {
-  for (int widx = tid >> 6; widx < Wd; widx += nt >> 6) {
-    const uint64_t word = words[widx];
-    int pre = 0;
-    for (int q = 0; q < widx; ++q) pre += __popcll(words[q]);
-    if ((word >> lane_id()) & 1ull) offs[pre + __popcll(word & lanemask_lt())] = (uint32_t)(widx * WAVE + lane_id()) * n4;
-    if (widx == Wd - 1) {
-      const int total = pre + __popcll(word);
-      if (lane_id() == 0) *cnt = total;
-      if (lane_id() < 4) offs[total + lane_id()] = 0u;
-    }
-  }
+  expand_words(words, Wd, tid, nt, [&](int pos, int idx) { offs[pos] = (uint32_t)idx * n4; },
+               [&](int total) {
+                 if (lane_id() == 0) *cnt = total;
+                 if (lane_id() < 4) offs[total + lane_id()] = 0u;
+               });
 }
 
 // Sum of the weight rows offs[0..cnt) (ascending, from 0.0f) for the NPT columns of this thread (byte offsets
