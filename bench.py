@@ -51,7 +51,7 @@ BUDGET = {2: 8 * 10**9, 3: 4 * 10**9, 4: 32 * 10**9}
 SID = {"standard": 0, "chunk": 1, "remote": 2, "double": 3, "hier": 4}  # hier: (nb_local, chunk)
 
 
-def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, dw_tile_chunks=0):
+def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, dw_tile_chunks=0, csr_recompute=False):
     """Own work of one training step per kernel kind: what the event-driven method must do, whatever a kernel
     does internally -- bytes of the weight rows of ACTIVE presynaptic neurons (existing synapses only for a masked
     recurrent matrix kept as compressed rows: 4-byte value + 2-byte index), one add per such weight, the dense
@@ -104,6 +104,12 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, d
     out["bwd_stage"] = ("alu", sum(2.0 * N[l] * N[l] * B * T for l in range(L)) + dw_adds + rec_adds)
     out["fwd_stage"] = ("alu", T * sum(N[l] * ev_in[l] + ent_rec[l] * ev_rec[l] for l in range(L)))
     out["bwd_inter"] = out["up_gemm"]
+    # what the dense matrix-core current kernel (matrices far beyond the L2) actually executes: one K = 1 matrix
+    # operation per presynaptic neuron whether it spiked or not -- its own bound, reported beside the own-work figure
+    # (which it can exceed: a weight row streamed once serves 64 (t, b) rows)
+    dense = {"fwd_currents": 2.0 * B * T * (sum(pre_n[l] * N[l] for l in range(L)) + N[-1] * w.n_out)}
+    dense["recompute"] = 2.0 * B * cur_steps * sum(pre_n[l] * N[l] + (0 if csr_recompute else N[l] * N[l]) for l in range(L))
+    out["_dense_flops"] = dense
     return out
 
 
@@ -373,7 +379,10 @@ def main():
     dw_tile = w.B <= 64 and (dw_env == "tile" or (big and dw_env not in ("mfma", "event")))
     model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density,
                        cur_steps=st.refwd_current_steps or (st.refwd1_steps + st.refwd2_steps),
-                       dw_tile_chunks=n_bwd if dw_tile else 0)
+                       dw_tile_chunks=n_bwd if dw_tile else 0,
+                       csr_recompute=big and w.rec_density < 1.0 and os.environ.get("SNN_CSR", "") != "0" and
+                       (os.environ.get("SNN_CSR", "") == "1" or max(rates) * w.rec_density < 0.01))
+    dense_flops = model.pop("_dense_flops")
     ms = {"fwd_seq": st.ms_fwd_seq, "fwd_currents": st.ms_fwd_currents, "recompute": st.ms_recompute, "scan": st.ms_scan,
           "adjoint": st.ms_adjoint, "up_gemm": st.ms_up_gemm, "dw": st.ms_dw, "bwd_stage": st.ms_bwd_stage,
           "fwd_stage": st.ms_fwd_stage, "bwd_inter": 0.0}
@@ -384,6 +393,8 @@ def main():
     adj_kernel = ("k_adj_rec_rows" if (args.surr_window > 0 and ws_env in ("", "rows", "rows_all")) or ws_env in ("rows", "rows_all") else
                   "k_adj_rec_csrw" if (w.rec_density < 1.0 and w.B <= 64 and os.environ.get("SNN_CSR", "") != "0" and ws_env in ("", "csrw")) else
                   "k_adj_rec_wide")
+    # inter-layer products of matrices from 2048 x 2048: one launch of the 128 x 128-tile kernel per product
+    gemm_big = L > 1 and min(w.n_hidden) >= 2048
     # launches of each kind's main kernel per step (layers that share a width and a pipeline stage share a launch)
     n_stage = n_tiles + 2 * (L - 1)
     n_cur = n_rec
@@ -394,7 +405,7 @@ def main():
         n_cur = len(cached) + sum(1 for o in sched if o[0] == "REFWD2" and o[1] // C not in cached)
     launches = {"fwd_seq": n_stage, "fwd_currents": n_stage, "recompute": max(1, n_cur), "scan": max(1, n_rec),
                 "adjoint": n_bwd * L if (max(w.n_hidden) > 1024 and adj_kernel == "k_adj_rec_wide") else n_bwd + L - 1,
-                "up_gemm": max(1, n_bwd + L - 2),
+                "up_gemm": n_bwd * (L - 1) if gemm_big else max(1, n_bwd + L - 2),
                 "dw": n_bwd + L - 1, "bwd_stage": max(1, n_bwd + L - 1),
                 "fwd_stage": max(1, n_tiles + 2 * L - 2), "bwd_inter": max(1, n_bwd + L - 2)}
     if st.ms_bwd_stage > 0:
@@ -408,14 +419,18 @@ def main():
     if st.ms_fwd_stage > 0:
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     wide = max(w.n_hidden) > 256
-    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and os.environ.get("SNN_CSR", "") == "1"
+    # compressed rows of masked recurrent matrices: forced by SNN_CSR=1, else the library's policy (matrices of 32 MB and
+    # more, firing rate x density below 0.01 in every layer)
+    csr_env = os.environ.get("SNN_CSR", "")
+    csr_pol = big and w.rec_density < 1.0 and max(rates) * w.rec_density < 0.01 and np.mean(rates) >= 0.045
+    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and (csr_env == "1" or (csr_env == "" and (csr_pol or (big and np.mean(rates) < 0.045))))
     kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
                  # (matrices of 32 MB and more: the dense matrix-core version from 4.5 % presynaptic activity, below it
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
                  "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
                  "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
-                 "scan": "k_scan", "up_gemm": "k_bwd_inter" if L > 2 else "k_up_gemm", "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "scan": "k_scan", "up_gemm": "k_up_gemm<2,2,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else adj_kernel)}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
@@ -428,6 +443,11 @@ def main():
         kinds[k] = {"kernel": kernel_of[k], "bound": "mfma" if bound == "mfma32" else bound, "ms_per_step": round(ms[k], 3),
                     "launches_per_step": launches[k], "avg_launch_ms": round(ms[k] / launches[k], 4),
                     "achieved": round(ach, 3), "peak": round(peak, 1), "unit": unit, "frac": round(ach / peak, 5)}
+        if kernel_of[k].startswith("k_currents_dense") and k in dense_flops:
+            tf = dense_flops[k] / (ms[k] * 1e-3) / 1e12
+            kinds[k]["kernel_executes"] = {"bound": "mfma", "what": "dense K=1 fp32 matrix operations, one per presynaptic neuron",
+                                           "achieved": round(tf, 2), "peak": MFMA_F32_PEAK_TF, "unit": "TFLOP/s",
+                                           "frac": round(tf / MFMA_F32_PEAK_TF, 4)}
     dom = max(kinds, key=lambda k: kinds[k]["ms_per_step"])
     dk = kinds[dom]
     work_per_launch = model[dom][1] / launches[dom]

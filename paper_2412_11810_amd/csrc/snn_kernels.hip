@@ -1351,18 +1351,25 @@ k_du_scan(const float *__restrict__ g, float *__restrict__ carry, float *__restr
 // element (k ascending in pairs) is fixed and independent of M, i.e. of how time is cut into chunks.
 //   lane layout (verified on the device): A[i][k] in lane i + 32k, B[k][j] in lane j + 32k,
 //   D[8*(r/4) + 4*(lane/32) + r%4][lane%32] in register r.
-template <int WM, int WN>
+template <int WM, int WN, int BM = 1, int BN = 1>
 __device__ __forceinline__ void up_gemm_body(const float *__restrict__ A, int lda, const float *__restrict__ W, int K,
                                              int N, float *__restrict__ C, int ldc, int M, int bx, int by) {
-  constexpr int NT = 64 * WM * WN, TM = 32 * WM, TN = 32 * WN, KT = 32;
+  // (BM x BN blocks of 32 x 32 per wavefront: every LDS value read feeds BN or BM matrix instructions, and a
+  // tile of 32 WM BM x 32 WN BN needs proportionally fewer operand bytes from the L2 per flop -- what bounds the
+  // 64 x 64 tiles once the matrices are far beyond it.  The operations per element of C are the same.)
+  constexpr int NT = 64 * WM * WN, TM = 32 * WM * BM, TN = 32 * WN * BN, KT = 32;
   constexpr int LA = TM * KT / NT, LW = TN * KT / NT;
   __shared__ float As[TM][KT + 1], Ws[TN][KT + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wn = wave / WM;
   const int m0 = bx * TM, j0 = by * TN;
-  v16f acc;
+  v16f acc[BM][BN];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  for (int p = 0; p < BM; ++p)
+#pragma unroll
+    for (int q = 0; q < BN; ++q)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[p][q][r] = 0.0f;
   float ra[LA], rw[LW];
   auto gload = [&](int k0) {
 #pragma unroll
@@ -1392,18 +1399,29 @@ __device__ __forceinline__ void up_gemm_body(const float *__restrict__ A, int ld
     if (k0 + KT < K) gload(k0 + KT);
 #pragma unroll
     for (int kk = 0; kk < KT; kk += 2) {
-      const float a = As[wm * 32 + (lane & 31)][kk + (lane >> 5)];
-      const float b = Ws[wn * 32 + (lane & 31)][kk + (lane >> 5)];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+      float a[BM], b[BN];
+#pragma unroll
+      for (int p = 0; p < BM; ++p) a[p] = As[(wm * BM + p) * 32 + (lane & 31)][kk + (lane >> 5)];
+#pragma unroll
+      for (int q = 0; q < BN; ++q) b[q] = Ws[(wn * BN + q) * 32 + (lane & 31)][kk + (lane >> 5)];
+#pragma unroll
+      for (int p = 0; p < BM; ++p)
+#pragma unroll
+        for (int q = 0; q < BN; ++q) acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[p], b[q], acc[p][q], 0, 0, 0);
     }
     __syncthreads();
   }
-  const int j = j0 + wn * 32 + (lane & 31);
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    if (m < M && j < N) C[(size_t)m * ldc + j] = acc[r];
-  }
+  for (int p = 0; p < BM; ++p)
+#pragma unroll
+    for (int q = 0; q < BN; ++q) {
+      const int j = j0 + (wn * BN + q) * 32 + (lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + (wm * BM + p) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < M && j < N) C[(size_t)m * ldc + j] = acc[p][q][r];
+      }
+    }
 }
 
 // The same product for small weight matrices (N * K <= 65536, K a multiple of 16, 16-byte aligned rows):
@@ -1417,12 +1435,14 @@ __device__ __forceinline__ void up_gemm_body(const float *__restrict__ A, int ld
 //   lane layout (verified on the device): A[i][k] in lane i + 16k, B[k][j] in lane j + 16k,
 //   D[4*(lane/16) + r][lane%16] in register r.
 typedef float v4f __attribute__((ext_vector_type(4)));
-template <int WM, int WN>
+template <int WM, int WN, int BM = 1, int BN = 1>
 __global__ void __launch_bounds__(64 * WM * WN)
 k_up_gemm(const float *__restrict__ A, int lda, const float *__restrict__ W, int K, int N, float *__restrict__ C,
           int ldc, int M) {
-  up_gemm_body<WM, WN>(A, lda, W, K, N, C, ldc, M, (int)blockIdx.x, (int)blockIdx.y);
+  up_gemm_body<WM, WN, BM, BN>(A, lda, W, K, N, C, ldc, M, (int)blockIdx.x, (int)blockIdx.y);
 }
+// Matrices from 2048 x 2048: 128 x 128 tiles (a rule on the layer's shape only, like the one for small matrices).
+static __host__ __device__ __forceinline__ bool up_gemm_big(int N, int K) { return N >= 2048 && K >= 2048; }
 
 __device__ __forceinline__ void up_gemm16_body(const float *__restrict__ A, int lda, const float *__restrict__ W, int K,
                                                int N, float *__restrict__ C, int ldc, int M, int vblock) {
@@ -3435,10 +3455,17 @@ static int seq_csr_resident(int device, size_t lds) {
 }
 static int seq_csr_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, bool need_rows = true) {
   if (!ws || !ws->xg || ga.count < 1 || net.sel_slices == 1) return 0;
-  // Measured at configuration 4 (5 % activity, 10 % density): 440 us per step against 253 us for the dense-stored
-  // walk, which runs at the memory's read rate with 32 KB rows while this one keeps too few bytes in flight
-  // (4 wavefronts per 2048 columns, 100-200 B per load).  Until that is cured it runs only when asked for.
-  if (need_rows && net.sel_csr != 2) return 0;
+  // The walk over compressed rows pays per presynaptic spike and per synapse that exists: it runs where the
+  // context's firing-rate policy has picked the gather over compressed rows for the recompute (rate x density
+  // below 0.01; configuration 4 at 5 % activity and 10 % density: 158 us per step against 220 us for the
+  // dense-stored walk), or wherever the hook asks.
+  if (need_rows && net.sel_csr != 2) {
+    if (net.sel_csr == 1) return 0;
+    for (int i = 0; i < ga.count; ++i) {
+      const int pol = net.cur_pol[1][ga.j[i].l];
+      if (pol != 1 && pol != 3) return 0;
+    }
+  }
   const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
   if (N % (4 * SNN_CSR_SUBW) != 0) return 0;
   int n_wide = 0;
@@ -3662,7 +3689,9 @@ static hipError_t launch_up_gemm(const float *A, int lda, const float *W, int K,
   if (aligned16 && (size_t)N * K <= 65536) {
     const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
     hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
-  } else // 64 x 64 tiles: measured faster than 32 x 32 blocks (one wavefront each) and than 128 x 64 at every shape in use
+  } else if (up_gemm_big(N, K)) {
+    hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3((M + 127) / 128, (N + 127) / 128), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+  } else // 64 x 64 tiles: measured faster than 32 x 32 blocks (one wavefront each) and than 128 x 64 up to 1024 x 1024
     hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
   return hipGetLastError();
 }
@@ -4107,6 +4136,10 @@ static void plan_gemm(GemmJob *gj) {
     gj->kind = 0;
     gj->tiles_m = (gj->M + 15) / 16;
     gj->n_blocks = (gj->tiles_m * ((gj->N + 15) / 16) + 3) / 4;
+  } else if (up_gemm_big(gj->N, gj->K)) {
+    gj->kind = 2;
+    gj->tiles_m = (gj->M + 127) / 128;
+    gj->n_blocks = gj->tiles_m * ((gj->N + 127) / 128);
   } else {
     gj->kind = 1;
     gj->tiles_m = (gj->M + 63) / 64;
@@ -4116,27 +4149,41 @@ static void plan_gemm(GemmJob *gj) {
 
 hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, const SpanHook *hook) {
   if (ij.n_gemm < 0 || ij.n_gemm > SNN_MAXL + 1) return hipErrorInvalidValue;
-  int grid = 0;
-  for (int q = 0; q < ij.n_gemm; ++q) {
+  int grid = 0, kept = 0;
+  for (int q = 0; q < ij.n_gemm; ++q)
     if (ij.g[q].M <= 0 || ij.g[q].N <= 0 || ij.g[q].K <= 0) return hipErrorInvalidValue;
-    plan_gemm(&ij.g[q]);
-    grid += ij.g[q].n_blocks;
-  }
   PreJobs &pre = ij.pre;
   size_t lds = 0;
   {
     const hipError_t e = plan_pre(net, &pre, 4, &lds);
     if (e != hipSuccess) return e;
   }
-  grid += pre.cur_gx * pre.cur.count + pre.n_scan;
-  if (grid == 0) return hipSuccess;
-  if (lds > 32 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_inter),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
   if (hook) hook->begin(hook->ctx, 6);
-  hipLaunchKernelGGL(k_bwd_inter, dim3(grid), dim3(256), lds, s, net, ij);
+  for (int q = 0; q < ij.n_gemm; ++q) {
+    plan_gemm(&ij.g[q]);
+    if (ij.g[q].kind == 2) {
+      // products of large matrices fill the chip by themselves and want the registers of the 128 x 128 tiles:
+      // launches of their own, the fused launch keeps the rest
+      const GemmJob &gj = ij.g[q];
+      hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3(gj.tiles_m, (gj.N + 127) / 128), dim3(256), 0, s, gj.A, gj.lda, gj.W,
+                         gj.K, gj.N, gj.C, gj.N, gj.M);
+      continue;
+    }
+    grid += ij.g[q].n_blocks;
+    ij.g[kept++] = ij.g[q];
+  }
+  ij.n_gemm = kept;
+  grid += pre.cur_gx * pre.cur.count + pre.n_scan;
+  if (grid > 0) {
+    hipError_t e = hipSuccess;
+    if (lds > 32 * 1024)
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_bwd_inter), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) hipLaunchKernelGGL(k_bwd_inter, dim3(grid), dim3(256), lds, s, net, ij);
+    if (e != hipSuccess) {
+      if (hook) hook->end(hook->ctx);
+      return e;
+    }
+  }
   if (hook) hook->end(hook->ctx);
   return hipGetLastError();
 }
