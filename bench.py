@@ -430,7 +430,7 @@ def main():
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
                  "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
                  "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
-                 "scan": "k_scan", "up_gemm": "k_up_gemm<2,2,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "scan": "k_scan", "up_gemm": "k_up_gemm<4,4,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else adj_kernel)}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}

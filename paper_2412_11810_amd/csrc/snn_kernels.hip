@@ -3690,7 +3690,10 @@ static hipError_t launch_up_gemm(const float *A, int lda, const float *W, int K,
     const int tiles = ((M + 15) / 16) * ((N + 15) / 16);
     hipLaunchKernelGGL(k_up_gemm16, dim3((tiles + 3) / 4), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
   } else if (up_gemm_big(N, K)) {
-    hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3((M + 127) / 128, (N + 127) / 128), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
+    if (N >= 4096 && M >= 2048)
+      hipLaunchKernelGGL((k_up_gemm<4, 4, 2, 2>), dim3((M + 255) / 256, (N + 255) / 256), dim3(1024), 0, s, A, lda, W, K, N, C, N, M);
+    else
+      hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3((M + 127) / 128, (N + 127) / 128), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
   } else // 64 x 64 tiles: measured faster than 32 x 32 blocks (one wavefront each) and than 128 x 64 up to 1024 x 1024
     hipLaunchKernelGGL((k_up_gemm<2, 2>), dim3((M + 63) / 64, (N + 63) / 64), dim3(256), 0, s, A, lda, W, K, N, C, N, M);
   return hipGetLastError();
@@ -4165,8 +4168,15 @@ hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, cons
       // products of large matrices fill the chip by themselves and want the registers of the 128 x 128 tiles:
       // launches of their own, the fused launch keeps the rest
       const GemmJob &gj = ij.g[q];
-      hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3(gj.tiles_m, (gj.N + 127) / 128), dim3(256), 0, s, gj.A, gj.lda, gj.W,
-                         gj.K, gj.N, gj.C, gj.N, gj.M);
+      // 256 x 256 tiles (16 wavefronts) where they still give a workgroup to every compute unit, else 128 x 128:
+      // 54 against 58 ms per step at configuration 4, T = 512 (256 x 128 with 8 wavefronts: 56; with 4: 62).  The
+      // operations per element of C are the same for every tile shape, so this choice may look at M.
+      if (gj.N >= 4096 && gj.M >= 2048)
+        hipLaunchKernelGGL((k_up_gemm<4, 4, 2, 2>), dim3((gj.M + 255) / 256, (gj.N + 255) / 256), dim3(1024), 0, s, gj.A, gj.lda,
+                           gj.W, gj.K, gj.N, gj.C, gj.N, gj.M);
+      else
+        hipLaunchKernelGGL((k_up_gemm<2, 2, 2, 2>), dim3(gj.tiles_m, (gj.N + 127) / 128), dim3(256), 0, s, gj.A, gj.lda, gj.W,
+                           gj.K, gj.N, gj.C, gj.N, gj.M);
       continue;
     }
     grid += ij.g[q].n_blocks;
