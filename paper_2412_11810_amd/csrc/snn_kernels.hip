@@ -1045,53 +1045,25 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
 // (at a few percent activity the union over 64 rows is nearly full anyway), loads the 256-byte segment of weight
 // row k once (the four wavefronts of the workgroup read 1 KB contiguous per k) and issues one K = 1 MFMA per block of 16 rows with that
 // segment as the B operand, on MB independent accumulators (no dependent-issue stall).  The A operand of block
-// mb in lane r is bit k of the spike word of row 16 mb + r, taken from a register that is reloaded from LDS every
-// 64 k.  acc + 0 * w leaves acc as it is, so the result is bit-identical to the list version and to a gather.
+// mb in lane r is bit k of the spike word of row 16 mb + r as 0.0f or 1.0f.  acc + 0 * w leaves acc as it is, so the
+// result is bit-identical to the list version and to a gather.
 // mode 0 runs the feed-forward and the recurrent part one after the other in the same wavefront and adds the two
 // partial currents as I_in + I_rec.
-template <int MB>
-static __device__ __forceinline__ void dense_stream(const uint64_t *words, int ws, int lane, int P,
-                                                    __amdgpu_buffer_rsrc_t wres, uint32_t col4, int N, v16f (&acc)[MB]) {
-  constexpr int U = 4, D = 4, G = 64 / U; // G groups per 64-bit spike word
-  const uint32_t n4 = (uint32_t)N * 4u;
-  const int Pw = (P + 63) >> 6;
-  float w[D][U];
-  auto issue = [&](int g, float (&wv)[U]) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = g * U + u, kc = k < P ? k : P - 1; // past the end: the last row again, multiplied by 0
-      wv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, col4, (uint32_t)kc * n4, 0));
-    }
-  };
-#pragma unroll
-  for (int g = 0; g < D - 1; ++g) issue(g, w[g]);
-  for (int kw = 0; kw < Pw; ++kw) {
-    uint64_t wr[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) wr[mb] = words[(size_t)(16 * mb + (lane & 15)) * ws + kw];
-#pragma unroll
-    for (int g8 = 0; g8 < G; ++g8) {
-      __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
-      issue(kw * G + g8 + D - 1, w[(g8 + D - 1) % D]);
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-          const float a = (float)((uint32_t)(wr[mb] >> (U * g8 + u)) & 1u);
-          acc[mb] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, w[g8 % D][u], acc[mb], 2, 0, 0);
-        }
-    }
-  }
-}
-
+// The A operands are prepared once per workgroup, not once per matrix operation: for every 64 presynaptic
+// neurons the 256 threads turn the spike bits of the 64 rows into 0.0f / 1.0f in LDS (thread (row, quarter): 16
+// bits of the row's word, which it reads straight from the stored bitmask one word ahead), and a wavefront reads
+// the operands of four consecutive k for a block of 16 rows with one 16-byte LDS read.  (Extracting and converting
+// the bit in front of every matrix operation cost 3.2 vector instructions per operation, and the counters showed
+// matrix and vector pipes busy 69 % + 27 % of the time: one after the other, not side by side.)
 // RC only names the instance: 1 for the launches of a recompute pass (modes 0 and 3), 0 for the forward pass's, so
 // that a kernel trace lists the two, whose shapes and durations differ, separately.
 template <int MB, int RC>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_currents_dense(NetDev net, CurJobs jobs, int ws) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint64_t *words = (uint64_t *)smem; // [16 MB][ws]
-  constexpr int RW = 16 * MB;
+  static_assert(MB == 4, "the staging step maps 256 threads onto 64 rows x 4 quarters of a word");
+  (void)ws;
+  constexpr int RW = 16 * MB, AP = 68; // rows per workgroup; floats per row of the operand buffer (64 + padding)
+  __shared__ __align__(16) float Af[2][RW][AP];
   const CurJob &ca = jobs.j[blockIdx.y];
   const bool ro = ca.mode == 2;
   const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
@@ -1100,7 +1072,9 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
   const int cg = (int)blockIdx.x % ncg, rg = (int)blockIdx.x / ncg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m0 = rg * RW, cb0 = cg * 256 + wave * 64, col = cb0 + lane;
-  const bool active = cb0 < N; // a wavefront past the last column only helps to load the spike words
+  const bool active = cb0 < N; // a wavefront past the last column only helps to prepare the operands
+  const int srow = tid >> 2, sq = tid & 3; // staging role: row of the tile, quarter of the word
+  const int sm = m0 + srow;
   v16f acc0[MB], acc1[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
@@ -1111,23 +1085,70 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
     const int Wp = net.Wd[pl];
     const int P = ro ? net.N[l] : part == 0 ? (l == 0 ? net.n_in : net.N[l - 1]) : N;
     const float *W = ro ? net.W_out : part == 0 ? net.W_in[l] : net.W_rec[l];
-    if (part) __syncthreads(); // everybody is done with the words of the first part
-    for (int idx = tid; idx < RW * Wp; idx += 256) {
-      const int r = idx / Wp, wi = idx - r * Wp, m = m0 + r;
-      uint64_t v = 0ull;
-      if (m < rows) {
-        const int t = ca.t0 + 1 + m / B, b = m % B;
-        v = net.mask[pl][(mrow_of(net, pl, part == 0 ? t : t - 1) * B + b) * Wp + wi];
-        const int rem = P - wi * 64;
-        if (rem < 64) v &= rem <= 0 ? 0ull : (1ull << rem) - 1ull;
-      }
-      words[(size_t)r * ws + wi] = v;
+    const int Pw = (P + 63) >> 6;
+    // the staging thread's row of spike words (a row past the end of the job: no spikes)
+    const uint64_t *wrow = nullptr;
+    if (sm < rows) {
+      const int t = ca.t0 + 1 + sm / B, b = sm % B;
+      wrow = net.mask[pl] + (mrow_of(net, pl, part == 0 ? t : t - 1) * B + b) * Wp;
     }
-    __syncthreads();
+    auto word_at = [&](int kw) -> uint64_t {
+      if (!wrow || kw >= Pw) return 0ull;
+      uint64_t v = wrow[kw];
+      const int rem = P - kw * 64;
+      if (rem < 64) v &= (1ull << rem) - 1ull;
+      return v;
+    };
+    auto stage = [&](int buf, uint64_t word) { // bits 16 sq .. 16 sq + 15 of the row's word -> floats
+      const uint32_t h = (uint32_t)(word >> (16 * sq)) & 0xFFFFu;
+      float4 *dst = reinterpret_cast<float4 *>(&Af[buf][srow][16 * sq]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        dst[q] = make_float4((float)((h >> (4 * q)) & 1u), (float)((h >> (4 * q + 1)) & 1u), (float)((h >> (4 * q + 2)) & 1u),
+                             (float)((h >> (4 * q + 3)) & 1u));
+    };
+    const __amdgpu_buffer_rsrc_t wres =
+        __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((size_t)P * N * sizeof(float)), 0x00027000);
+    const uint32_t col4 = (uint32_t)(col < N ? col : 0) * 4u, n4 = (uint32_t)N * 4u;
+    constexpr int U = 4, D = 4, G = 64 / U; // G groups of U presynaptic neurons per 64-bit spike word
+    float w[D][U];
+    auto issue = [&](int g, float (&wv)[U]) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = g * U + u, kc = k < P ? k : P - 1; // past the end: the last row again, multiplied by 0
+        wv[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(wres, col4, (uint32_t)kc * n4, 0));
+      }
+    };
+    if (part) __syncthreads(); // everybody is done with the operand buffers of the first part
+    uint64_t wnext = word_at(0);
+    stage(0, wnext);
+    wnext = word_at(1);
     if (active) {
-      const __amdgpu_buffer_rsrc_t wres =
-          __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((size_t)P * N * sizeof(float)), 0x00027000);
-      dense_stream<MB>(words, ws, lane, P, wres, (uint32_t)(col < N ? col : 0) * 4u, N, acc);
+#pragma unroll
+      for (int g = 0; g < D - 1; ++g) issue(g, w[g]);
+    }
+    for (int kw = 0; kw < Pw; ++kw) {
+      const int buf = kw & 1;
+      __syncthreads(); // operands of word kw are in place; everybody has left word kw - 1's
+      if (kw + 1 < Pw) stage(buf ^ 1, wnext);
+      wnext = word_at(kw + 2);
+      if (active) {
+#pragma unroll
+        for (int g8 = 0; g8 < G; ++g8) {
+          __builtin_amdgcn_sched_barrier(0); // keep the groups in program order: loads stay D - 1 groups ahead
+          issue(kw * G + g8 + D - 1, w[(g8 + D - 1) % D]);
+          float4 a4[MB];
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) a4[mb] = *reinterpret_cast<const float4 *>(&Af[buf][16 * mb + (lane & 15)][U * g8]);
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+              const float a = u == 0 ? a4[mb].x : u == 1 ? a4[mb].y : u == 2 ? a4[mb].z : a4[mb].w;
+              acc[mb] = __builtin_amdgcn_mfma_f32_16x16x1f32(a, w[g8 % D][u], acc[mb], 2, 0, 0);
+            }
+        }
+      }
     }
   };
   run_part(0, acc0);
@@ -3185,8 +3206,7 @@ static int currents_job_kernel(const NetDev &net, const CurJob &j) {
   int p;
   size_t wb;
   currents_job_shape(net, j, &p, &wb);
-  const bool dense_ok = wb < ((size_t)1 << 32) &&                                               // one buffer descriptor
-                        (size_t)16 * SNN_DENSE_MB * (((p + 63) >> 6) | 1) * 8 + 1024 <= SNN_LDS_PER_CU; // words of 64 rows
+  const bool dense_ok = wb < ((size_t)1 << 32); // one buffer descriptor
   if (net.sel_currents == 3) return dense_ok ? 1 : 0;
   if (net.sel_currents == 2) return 0;
   if (wb < ((size_t)32 << 20) || j.mode == 2) return 0;
@@ -3208,14 +3228,8 @@ static hipError_t launch_currents_dense(const NetDev &net, const CurJobs &jobs, 
     const int w1 = ((p + 63) >> 6) | 1;
     ws = w1 > ws ? w1 : ws;
   }
-  const size_t lds = (size_t)16 * SNN_DENSE_MB * ws * sizeof(uint64_t);
+  const size_t lds = 0; // the operand buffers are static
   const bool rc = jobs.j[0].mode == 0 || jobs.j[0].mode == 3;
-  if (lds > 48 * 1024) {
-    const hipError_t ea = hipFuncSetAttribute(rc ? reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB, 1>)
-                                                 : reinterpret_cast<const void *>(k_currents_dense<SNN_DENSE_MB, 0>),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (ea != hipSuccess) return ea;
-  }
   if (rc) hipLaunchKernelGGL((k_currents_dense<SNN_DENSE_MB, 1>), dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
   else hipLaunchKernelGGL((k_currents_dense<SNN_DENSE_MB, 0>), dim3(gx, jobs.count), dim3(256), lds, s, net, jobs, ws);
   return hipGetLastError();
