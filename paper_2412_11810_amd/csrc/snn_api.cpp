@@ -161,7 +161,8 @@ int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 // call that launches kernels, so that a test can switch them between two calls on one context.
 void read_kernel_hooks(snn_ctx *c) {
   NetDev &n = c->net;
-  n.sel_currents = n.sel_adjoint = n.sel_slices = n.sel_csr = 0;
+  n.sel_currents = n.sel_adjoint = n.sel_slices = n.sel_csr = n.sel_seq = 0;
+  if (const char *e = std::getenv("SNN_SEQ_KERNEL")) n.sel_seq = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "rs") ? 2 : 0;
   if (const char *e = std::getenv("SNN_CSR")) n.sel_csr = !std::strcmp(e, "0") ? 1 : !std::strcmp(e, "1") ? 2 : 0;
   for (int l = 0; l < n.L; ++l) {
     const bool on = c->csr_sub[l] && n.sel_csr != 1;
@@ -1796,8 +1797,8 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   const bool use_graph = c->graphs_enabled && !stats;
   if (use_graph) {
     unsigned long long pol = 0;
-    for (int l = 0; l < L; ++l) pol = pol * 16 + c->net.cur_pol[0][l] * 4 + c->net.cur_pol[1][l];
-    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24;
+    for (int l = 0; l < L; ++l) pol = pol * 32 + c->net.cur_pol[0][l] * 8 + c->net.cur_pol[1][l] * 2 + c->net.seq_pol[l];
+    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24 | (unsigned)n.sel_seq << 28;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,
                            ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1], p.n_cache_slots};
     if (!c->graph_exec || !(key == c->graph_key)) {

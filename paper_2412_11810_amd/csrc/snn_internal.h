@@ -52,6 +52,9 @@ struct NetDev {
   // compressed rows also under a surrogate window.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
+  // Sequential forward part of layers of up to 256 neurons: sel_seq 1 forces the event-driven gather, 2 the
+  // register-stationary chain, 0 follows seq_pol[l] (1: gather; set from the measured firing rates).
+  unsigned char sel_seq, seq_pol[SNN_MAXL];
   unsigned char sel_csr; // compressed rows of masked recurrent matrices: 1 never used (dense-stored walk everywhere),
                          // 2 used wherever a kernel for them exists, 0 the library's choice
 };

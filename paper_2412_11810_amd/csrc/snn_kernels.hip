@@ -3512,7 +3512,15 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
   const LaunchCfg c = forward_cfg(net);
   int nmax = 0;
   for (int l = 0; l < L; ++l) nmax = net.N[l] > nmax ? net.N[l] : nmax;
-  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma(net) && fwd_stage_fits(net);
+  // Layers of up to 256 neurons: the register-stationary chain (one FMA per presynaptic neuron, whatever the
+  // activity) or, where the context's policy has measured a low firing rate (or the hook asks), the event-driven
+  // gather over the rows of the neurons that fired.  Both give the same bits.
+  auto narrow_gather = [&](int l) {
+    return net.N[l] <= 256 && (net.sel_seq == 1 || (net.sel_seq == 0 && net.seq_pol[l] == 1));
+  };
+  bool any_narrow_gather = false;
+  for (int l = 0; l < L; ++l) any_narrow_gather = any_narrow_gather || narrow_gather(l);
+  const bool fuse = nmax > 128 && nmax <= 256 && currents_use_mfma(net) && fwd_stage_fits(net) && !any_narrow_gather;
   int ro_steps = 0, ro_tiles = 0;
   bool ro_first = true;
   RoJob ro_pending{};
@@ -3540,7 +3548,7 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
       const int k = stage - 2 * l - 1;
       if (k < 0 || k >= n_tiles) continue;
       const SeqJob job{l, bounds[k], bounds[k + 1], bounds[k], iin[l][k & 1]};
-      if (net.N[l] <= 256) { rs.j[rs.count++] = job; nw = net.N[l] > nw ? net.N[l] : nw; }
+      if (net.N[l] <= 256 && !narrow_gather(l)) { rs.j[rs.count++] = job; nw = net.N[l] > nw ? net.N[l] : nw; }
       else ga.j[ga.count++] = job;
     }
     hipError_t e = hipSuccess;
