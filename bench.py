@@ -433,7 +433,7 @@ def main():
     csr_env = os.environ.get("SNN_CSR", "")
     csr_pol = big and w.rec_density < 1.0 and max(rates) * w.rec_density < 0.01 and np.mean(rates) >= 0.045
     csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and (csr_env == "1" or (csr_env == "" and (csr_pol or (big and np.mean(rates) < 0.045))))
-    kernel_of = {"fwd_seq": "k_layer_seq_rs" if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
+    kernel_of = {"fwd_seq": ("k_layer_seq_gather" if os.environ.get("SNN_SEQ_KERNEL", "") == "gather" else "k_layer_seq_rs") if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
                  # (matrices of 32 MB and more: the dense matrix-core version from 4.5 % presynaptic activity, below it
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)

@@ -556,6 +556,34 @@ def test_gather_and_matrix_core_currents_agree(monkeypatch):
     monkeypatch.delenv("SNN_CURRENTS")
 
 
+def test_event_driven_step_of_narrow_layers_is_bitwise_neutral(monkeypatch):
+    """Layers of up to 256 neurons run the register-stationary chain (one FMA per presynaptic neuron whatever the
+    activity); SNN_SEQ_KERNEL=gather sends them through the event-driven gather of the wide layers instead.  Both
+    add the same weights in the same ascending order: spike trains, potentials and gradients must be identical,
+    at a low and at a high firing rate."""
+    for gain in (0.15, 1.0):
+        w = synth.config(1, T=120, B=6, gain=gain)
+        d = synth.generate(w)
+        L = len(w.n_hidden)
+        got = {}
+        for mode in ("rs", "gather"):
+            monkeypatch.setenv("SNN_SEQ_KERNEL", mode)
+            net = snn.from_workload(w, d)
+            try:
+                net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+                states = net.snn_debug_states(w.T)
+                net.snn_bptt(snn.SNN_DOUBLE, 30, 6)
+                got[mode] = (_gpu_grads(net, L), [net.snn_get_spikes(l, w.T) for l in range(L)], states)
+            finally:
+                net.snn_destroy()
+        monkeypatch.delenv("SNN_SEQ_KERNEL")
+        assert _identical(got["rs"][0], got["gather"][0]), gain
+        for a, b in zip(got["rs"][1], got["gather"][1]):
+            assert np.array_equal(a, b), gain
+        assert np.array_equal(got["rs"][2].view(np.uint32), got["gather"][2].view(np.uint32)), gain
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 7)], nthreads=2)
+
+
 @pytest.mark.parametrize("width,density", [(512, 1.0), (2048, 1.0), (1088, 1.0), (2048, 0.2)])
 def test_barrier_timeout_is_reported_not_hung(monkeypatch, width, density):
     """The chip-wide adjoint kernels of wide layers (weights in registers up to 1024 neurons, streamed
