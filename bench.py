@@ -452,6 +452,13 @@ def main():
         kinds[k] = {"kernel": kernel_of[k], "bound": "mfma" if bound == "mfma32" else bound, "ms_per_step": round(ms[k], 3),
                     "launches_per_step": launches[k], "avg_launch_ms": round(ms[k] / launches[k], 4),
                     "achieved": round(ach, 3), "peak": round(peak, 1), "unit": unit, "frac": round(ach / peak, 5)}
+        tr = read_traffic(w.name, args.strategy, kernel_of[k])
+        if tr is not None:
+            # HBM bytes per launch of this kernel from the committed counter summary (same launch shape; the recompute
+            # launch there covers a shorter coarse segment, see the file's header) next to the own-work bytes per launch
+            kinds[k]["traffic_bytes_per_launch"] = int(tr)
+            if bound == "hbm":
+                kinds[k]["own_bytes_per_launch"] = int(work / launches[k])
         what = None
         if kernel_of[k].startswith("k_currents_dense") and k in dense_flops:
             what, fl = "dense K=1 fp32 matrix operations, one per presynaptic neuron", dense_flops[k]
