@@ -95,7 +95,9 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, d
         # adjoint tile of the backward pass): its own HBM work is the accumulators read and written once per launch,
         # the adjoint rows of every matrix's postsynaptic layer read once and the spike words -- far below the
         # read-modify-write per event of the scatter form priced above
-        entries = sum(pre_n[l] * N[l] + N[l] * N[l] for l in range(L)) + N[-1] * w.n_out
+        # (a masked recurrent matrix keeps one accumulator per existing synapse when batch <= 32)
+        rec_frac = rec_density if (masked and B <= 32 and os.environ.get("SNN_DW_CSR", "") != "0" and os.environ.get("SNN_CSR", "") != "0") else 1.0
+        entries = sum(pre_n[l] * N[l] + rec_frac * N[l] * N[l] for l in range(L)) + N[-1] * w.n_out
         rows = T * B * (sum(4.0 * 2 * N[l] + (pre_n[l] + N[l]) / 8.0 for l in range(L)) + 4.0 * w.n_out + N[-1] / 8.0)
         out["dw"] = ("hbm", dw_tile_chunks * 16.0 * entries + rows)
     # fused launches of the narrow-layer networks: the recurrences (dense) + the adds of the weight gradients and of

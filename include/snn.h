@@ -252,6 +252,8 @@ void snn_destroy(snn_ctx *ctx);
  *                                (batch <= 64) / the matrix-core contraction (default: tiled when some weight
  *                                matrix has 32 MB or more, else the contraction)
  *     SNN_RF_CACHE=0             Double: never keep a coarse segment's currents between its two recompute passes
+ *     SNN_DW_CSR=0               tiled weight gradients of masked recurrent matrices over the dense tile, not per
+ *                                existing synapse
  *     SNN_GRAPH=0                no HIP-graph replay of the training step
  *     SNN_BWD_PIPE=0, SNN_BWD_FUSE=0, SNN_PRE_IN_STAGE=0
  *                                adjoint pass layer by layer / weight gradients in launches of their own /

@@ -43,6 +43,12 @@ struct snn_ctx {
   uint16_t *csr_col[SNN_MAXL]{};
   float *csr_val[SNN_MAXL]{};
   size_t csr_nnz[SNN_MAXL]{};
+  // fp64 gradient accumulators per existing synapse, in compressed-row order (k_dw_csr); csr_dw_ok: the entries
+  // beyond the 64 per row and sub-range that kernel keeps in registers fit its LDS (64 per 16 rows and sub-range)
+  double *acc_csr[SNN_MAXL]{};
+  bool csr_dw_ok[SNN_MAXL]{};
+
+  bool dw_csr = true;           // SNN_DW_CSR=0: masked recurrent matrices keep dense accumulators
   size_t mask_words[SNN_MAXL + 1]{}; // words in mask[l] ((T+1)*B*Wd)
   // Spike bitmasks on the host tier (cfg.spike_tier == 1, REMOTE / DOUBLE): the hidden layers' words of the whole
   // sequence live in pinned host memory ([T+1][B][Wd] per layer index 1..L, row 0 zero); HBM holds a ring of
@@ -157,6 +163,14 @@ void fill_shape(const snn_config &c, NetDev *n) {
 
 int pre_of(const NetDev &n, int l) { return l == 0 ? n.n_in : n.N[l - 1]; }
 
+// Does the recurrent matrix of layer l accumulate its gradient per existing synapse (k_dw_csr)?  Where the tiled
+// event-driven kernel runs, the compressed rows are in use (net.csr_sub follows the SNN_CSR hook), no row is too
+// long for it and a time step fits its tile.  Constant during a training step.
+bool dw_rec_csr(const snn_ctx *c, int l) {
+  return c->dw_tile && c->dw_csr && !c->dw_event_driven && c->net.csr_sub[l] && c->csr_dw_ok[l] && c->acc_csr[l] &&
+         c->net.B <= 32;
+}
+
 // Test hooks that force a kernel flavour (documented in snn.h): read from the environment at the start of every
 // call that launches kernels, so that a test can switch them between two calls on one context.
 void read_kernel_hooks(snn_ctx *c) {
@@ -215,8 +229,9 @@ size_t spike_bytes(const NetDev &n, int T, int ring = 0) {
 }
 
 void free_csr(snn_ctx *c, int l) {
-  (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]);
+  (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]); (void)hipFree(c->acc_csr[l]);
   c->csr_sub[l] = nullptr; c->csr_col[l] = nullptr; c->csr_val[l] = nullptr; c->csr_nnz[l] = 0;
+  c->acc_csr[l] = nullptr; c->csr_dw_ok[l] = false;
 }
 
 // Compressed rows of a masked recurrent matrix (layout: NetDev::csr_sub).  An entry exists where the mask says a
@@ -248,7 +263,22 @@ snn_status build_csr(snn_ctx *c, int l, const float *w, const uint8_t *mask) {
     }
     sr[nsub] = (uint32_t)p;
   }
+  // k_dw_csr: a wavefront owns 16 consecutive rows of a block of 256 and keeps 64 entries per row and sub-range in
+  // registers, up to 64 more per wavefront (and per row) in LDS
+  bool dw_ok = true;
+  for (int j0 = 0; j0 < N && dw_ok; j0 += 16)
+    for (int r = 0; r < nsub && dw_ok; ++r) {
+      uint32_t extra = 0;
+      for (int j = j0; j < std::min(N, j0 + 16); ++j) {
+        const uint32_t *sr = sub.data() + (size_t)j * (nsub + 1);
+        const uint32_t n = sr[r + 1] - sr[r];
+        if (n > 64) extra += n - 64;
+      }
+      if (extra > 64) dw_ok = false;
+    }
   free_csr(c, l);
+  HIPCHK(c, hipMalloc(&c->acc_csr[l], (nnz + 1) * sizeof(double)));
+  c->csr_dw_ok[l] = dw_ok;
   HIPCHK(c, hipMalloc(&c->csr_sub[l], sub.size() * 4));
   HIPCHK(c, hipMalloc(&c->csr_col[l], col.size() * 2));
   HIPCHK(c, hipMalloc(&c->csr_val[l], val.size() * 4));
@@ -369,6 +399,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_PRE_IN_STAGE")) c->pre_in_stage = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_RF_CACHE")) c->rf_cache = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_DW_CSR")) c->dw_csr = std::strcmp(e, "0") != 0;
   read_kernel_hooks(c);
   char buf[256];
   if (!snn_kernel_shape_ok(c->net, buf, sizeof buf)) return fail(c, SNN_E_INVAL, buf);
@@ -1197,9 +1228,12 @@ struct BwdPipe {
     for (const BwdTile &t : done) {
       const int l = t.layer;
       if (l == L - 1)
-        db->d[db->count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0, 0, n.mring[L]};
-      db->d[db->count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, l == 0 ? 1 : 0, 0, 0, n.mring[l]};
-      db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0, 0, n.mring[l + 1]};
+        db->d[db->count++] = DwDesc{n.mask[L], n.Wd[L], 0, n.N[L - 1], O, t.du, (size_t)B * O, O, 0, c->acc_out, t.t0, t.t1, t.base, 0, 0, 0, n.mring[L], nullptr, nullptr};
+      db->d[db->count++] = DwDesc{n.mask[l], n.Wd[l], 0, pre_of(n, l), n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_in[l], t.t0, t.t1, t.base, l == 0 ? 1 : 0, 0, 0, n.mring[l], nullptr, nullptr};
+      if (dw_rec_csr(c, l))
+        db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_csr[l], t.t0, t.t1, t.base, 0, 0, 0, n.mring[l + 1], n.csr_sub[l], n.csr_col[l]};
+      else
+        db->d[db->count++] = DwDesc{n.mask[l + 1], n.Wd[l + 1], 1, n.N[l], n.N[l], t.vbuf, slot, SN, n.off[l], c->acc_rec[l], t.t0, t.t1, t.base, 0, 0, 0, n.mring[l + 1], nullptr, nullptr};
     }
   }
   snn_status emit_dw() {
@@ -1254,7 +1288,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
 
   for (int l = 0; l < L; ++l) {
     HIPCHK(c, launch_fill_zero(c->acc_in[l], (size_t)pre_of(n, l) * n.N[l] * 8, s));
-    HIPCHK(c, launch_fill_zero(c->acc_rec[l], (size_t)n.N[l] * n.N[l] * 8, s));
+    if (dw_rec_csr(c, l)) HIPCHK(c, launch_fill_zero(c->acc_csr[l], c->csr_nnz[l] * 8, s));
+    else HIPCHK(c, launch_fill_zero(c->acc_rec[l], (size_t)n.N[l] * n.N[l] * 8, s));
   }
   HIPCHK(c, launch_fill_zero(c->acc_out, (size_t)n.N[L - 1] * O * 8, s));
 
@@ -1672,7 +1707,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
   }
   for (int l = 0; l < L; ++l) {
     HIPCHK(c, launch_finish_grad(c->acc_in[l], nullptr, c->dW_in[l], (size_t)pre_of(n, l) * n.N[l], s));
-    HIPCHK(c, launch_finish_grad(c->acc_rec[l], c->rec_mask[l], c->dW_rec[l], (size_t)n.N[l] * n.N[l], s));
+    if (dw_rec_csr(c, l)) HIPCHK(c, launch_finish_grad_csr(c->acc_csr[l], n.csr_sub[l], n.csr_col[l], n.N[l], c->dW_rec[l], s));
+    else HIPCHK(c, launch_finish_grad(c->acc_rec[l], c->rec_mask[l], c->dW_rec[l], (size_t)n.N[l] * n.N[l], s));
   }
   HIPCHK(c, launch_finish_grad(c->acc_out, nullptr, c->dW_out, (size_t)n.N[L - 1] * O, s));
   if (remote || R > 0) { // join the copy stream back

@@ -181,6 +181,10 @@ struct DwDesc {
   int skip_empty;           // test for K-steps without a spike (pays for sparse presynaptic layers only)
   int tile0, tiles_n;       // filled by the launcher
   int pre_ring;             // > 0: pre_mask holds a ring of that many steps (row = step modulo the ring)
+  // Masked recurrent matrix through its compressed rows (k_dw_csr): acc then holds one accumulator per existing
+  // synapse, in the order of the compressed entries (NetDev::csr_sub / csr_col); NULL: dense accumulators
+  const uint32_t *csr_sub;
+  const uint16_t *csr_col;
 };
 struct DwBatch {
   DwDesc d[2 * SNN_MAXL + 1];
@@ -219,6 +223,9 @@ hipError_t launch_bwd_stage(const NetDev &net, const AdjJobs &jobs, float *carry
 hipError_t launch_bwd_inter(const NetDev &net, InterJobs ij, hipStream_t s, const SpanHook *hook = nullptr);
 hipError_t launch_transpose(const float *src, float *dst, int rows, int cols, hipStream_t s);
 hipError_t launch_finish_grad(const double *acc, const uint8_t *mask_or_null, float *dW, size_t n, hipStream_t s);
+// The same for accumulators kept per existing synapse (compressed-row order): dW = 0 where no synapse exists.
+hipError_t launch_finish_grad_csr(const double *acc, const uint32_t *csr_sub, const uint16_t *csr_col, int N, float *dW,
+                                  hipStream_t s);
 hipError_t launch_unpack_spikes(const uint64_t *mask, int words, int N, int T, int B, uint8_t *dst,
                                 hipStream_t s);
 hipError_t launch_count_spikes(const uint64_t *mask, size_t n_words, unsigned long long *count, hipStream_t s);

@@ -2989,6 +2989,186 @@ k_dw_tile(DwBatch batch, int B) {
       if (jw + i < d.n_pre && c0 + c < d.n_post) d.acc[(size_t)(jw + i) * d.n_post + c0 + c] = acc[i][c];
 }
 
+// B5 for a masked recurrent matrix, over its compressed rows: the gradient of a synapse that does not exist is
+// zero by definition, so only the existing ones (a tenth at configuration 4) get an accumulator and an add.
+// Workgroup = 256 presynaptic rows x one sub-range of SNN_CSR_SUBW postsynaptic columns, 16 wavefronts of 16 rows.
+// For each of its rows a wavefront keeps the first 64 entries of the row's part of the sub-range one per lane: the
+// fp64 accumulator in a register for the whole launch and the column as an offset into a row of the adjoint tile
+// (the few entries beyond 64 -- 3 % of the rows have any at 10 % density -- keep theirs in LDS, up to 64 per wavefront;
+// the host checks that this is enough, else the matrix keeps dense accumulators).
+// The time axis runs in tiles of floor(32 / B) steps whose adjoint rows P[(t, b)][512 columns] go through LDS
+// (64 KB, the next tile's loads in flight meanwhile) with the spike words of the 256 presynaptic neurons; a ballot
+// gives the rows in which a neuron spiked, and each such row costs one LDS gather and one add per lane.
+// Per synapse the sequence of operations is the one of k_dw_tile and of the dense contraction: per time step,
+// descending, an fp32 sum over the batch elements that spiked, ascending, from zero, then one fp64 add.
+#define DWC_WAVES 16
+__global__ void __launch_bounds__(64 * DWC_WAVES)
+k_dw_csr(DwBatch batch, int B) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int PJ = 256, PC = SNN_CSR_SUBW, RT = 32, NWV = DWC_WAVES, RW = PJ / NWV, WPB = PJ / 64;
+  constexpr int SK = RT * (PC / 4) / (64 * NWV); // staging loads (float4) per thread
+  float *P = (float *)smem;                       // [RT][PC]
+  uint64_t *Wv = (uint64_t *)(P + RT * PC);       // [WPB][RT] spike words of the tile's rows
+  double *xacc_all = (double *)(Wv + WPB * RT);   // [NWV][64] accumulators of the entries beyond a row's 64th
+  uint32_t *xoff_all = (uint32_t *)(xacc_all + NWV * 64); // [NWV][64] their column offsets
+  int di = 0;
+  while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
+  const DwDesc &d = batch.d[di];
+  const int tile = (int)blockIdx.x - d.tile0;
+  const int nsub = d.tiles_n, r = tile % nsub, j0 = (tile / nsub) * PJ, n0 = r * PC;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  double *xacc = xacc_all + 64 * wave;
+  uint32_t *xoff = xoff_all + 64 * wave;
+  const int t0 = d.t0, t1 = d.t1, t_base = d.t_base;
+  const int TS = RT / B; // time steps per tile (B <= 32)
+  const int jw = j0 + RW * wave;
+  const int wsel = (RW * wave) >> 6, bitbase = (RW * wave) & 63;
+  // the wavefront's synapses: entry `lane` of every row's part of the sub-range
+  double acc[RW];
+  uint32_t offs[RW / 2]; // byte offsets of the entries' columns inside a row of the tile, two rows per register
+  auto entries = [&](int i, uint32_t &e0, uint32_t &n) { // first entry and number of entries of row jw + i here
+    e0 = 0u;
+    uint32_t e1 = 0u;
+    if (jw + i < d.n_pre) {
+      e0 = d.csr_sub[(size_t)(jw + i) * (nsub + 1) + r];
+      e1 = d.csr_sub[(size_t)(jw + i) * (nsub + 1) + r + 1];
+    }
+    e0 = __builtin_amdgcn_readfirstlane(e0);
+    n = __builtin_amdgcn_readfirstlane(e1) - e0;
+  };
+  // entries beyond the 64th of row i: their number (wavefront-uniform, a byte each); they sit one row after the
+  // other in xacc / xoff
+  uint32_t xpack[RW / 4] = {};
+  auto xn_of = [&](int i) { return (xpack[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
+  uint32_t xtot = 0u;
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    uint32_t e0, n;
+    entries(i, e0, n);
+    const bool has = (uint32_t)lane < n;
+    const uint32_t o = has ? ((uint32_t)d.csr_col[e0 + lane] - (uint32_t)n0) * 4u : 0u; // < 2048
+    if (i & 1) offs[i >> 1] |= o << 16;
+    else offs[i >> 1] = o;
+    acc[i] = has ? d.acc[e0 + lane] : 0.0;
+    const uint32_t xn = n > 64u ? n - 64u : 0u;
+    xpack[i >> 2] |= xn << (8 * (i & 3));
+    if ((uint32_t)lane < xn) { // (the host has checked: at most 64 per row and per wavefront)
+      xacc[xtot + lane] = d.acc[e0 + 64 + lane];
+      xoff[xtot + lane] = ((uint32_t)d.csr_col[e0 + 64 + lane] - (uint32_t)n0) * 4u;
+    }
+    xtot += xn;
+  }
+  // staging of a tile: 128 threads cover one row's 512 columns; thread -> SK x (row, 4 columns)
+  const int c4 = 4 * (tid & 127), srow = tid >> 7;
+  const bool al = ((d.post_off + n0) & 3) == 0 && (d.post_stride & 3) == 0 && (d.slot_stride & 3) == 0 &&
+                  (((uintptr_t)d.post) & 15) == 0 && n0 + PC <= d.n_post;
+  float4 stg[SK];
+  auto tile_load = [&](int t_hi, int nts) {
+#pragma unroll
+    for (int k = 0; k < SK; ++k) {
+      const int rr = 8 * k + srow, ts = rr / B, b = rr - ts * B; // row rr of the tile: step t_hi - ts, batch element b
+      const bool ok = ts < nts;
+      const float *prow = d.post + (size_t)(t_hi - (ok ? ts : 0) - t_base - 1) * d.slot_stride + d.post_off +
+                          (size_t)(ok ? b : 0) * d.post_stride + n0;
+      float4 v;
+      if (al) {
+        v = *reinterpret_cast<const float4 *>(prow + c4);
+      } else {
+        v.x = n0 + c4 + 0 < d.n_post ? prow[c4 + 0] : 0.0f;
+        v.y = n0 + c4 + 1 < d.n_post ? prow[c4 + 1] : 0.0f;
+        v.z = n0 + c4 + 2 < d.n_post ? prow[c4 + 2] : 0.0f;
+        v.w = n0 + c4 + 3 < d.n_post ? prow[c4 + 3] : 0.0f;
+      }
+      stg[k] = ok ? v : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+  };
+  auto tile_store = [&](int t_hi, int nts) {
+#pragma unroll
+    for (int k = 0; k < SK; ++k) *reinterpret_cast<float4 *>(P + (size_t)(8 * k + srow) * PC + c4) = stg[k];
+    if (tid < WPB * RT) { // spike words of the tile's rows for presynaptic neurons j0 .. j0 + 255
+      const int rr = tid & (RT - 1), ws = tid / RT, ts = rr / B, b = rr - ts * B;
+      uint64_t wv = 0ull;
+      if (ts < nts && (j0 >> 6) + ws < d.pre_words) {
+        const int tt = t_hi - ts - d.lag;
+        wv = d.pre_mask[((size_t)(d.pre_ring > 0 ? tt % d.pre_ring : tt) * B + b) * d.pre_words + (j0 >> 6) + ws];
+      }
+      Wv[ws * RT + rr] = wv;
+    }
+  };
+  const uint32_t bmask = B >= 32 ? ~0u : ((1u << B) - 1u);
+  int t_hi = t1;
+  tile_load(t_hi, t_hi - t0 < TS ? t_hi - t0 : TS);
+  while (t_hi > t0) {
+    const int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
+    __syncthreads(); // everybody is done with the previous tile
+    tile_store(t_hi, nts);
+    __syncthreads();
+    const int t_next = t_hi - nts;
+    if (t_next > t0) tile_load(t_next, t_next - t0 < TS ? t_next - t0 : TS); // in flight during the adds below
+    const uint64_t wv = lane < RT ? Wv[wsel * RT + lane] : 0ull;
+    uint32_t xbase = 0u;
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      const uint32_t xn = xn_of(i), xb = xbase;
+      xbase += xn;
+      const uint32_t m = (uint32_t)__ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
+      if (m == 0u) continue;
+      const uint32_t o = (i & 1) ? offs[i >> 1] >> 16 : offs[i >> 1] & 0xFFFFu;
+      for (int ts = 0; ts < nts; ++ts) {
+        uint32_t mt = (m >> (ts * B)) & bmask;
+        if (mt == 0u) continue;
+        float part = 0.0f;
+        const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + o;
+        while (mt) {
+          const int k = (int)__builtin_ctz(mt);
+          mt &= mt - 1u;
+          part = part + *reinterpret_cast<const float *>(Pts + (size_t)k * PC * sizeof(float));
+        }
+        acc[i] = acc[i] + (double)part;
+      }
+      if (xn) { // the row's entries beyond the 64th: the same walk, accumulators in LDS
+        const bool mine = (uint32_t)lane < xn;
+        const uint32_t ox = mine ? xoff[xb + lane] : 0u;
+        for (int ts = 0; ts < nts; ++ts) {
+          uint32_t mt = (m >> (ts * B)) & bmask;
+          if (mt == 0u) continue;
+          float part = 0.0f;
+          const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + ox;
+          while (mt) {
+            const int k = (int)__builtin_ctz(mt);
+            mt &= mt - 1u;
+            part = part + *reinterpret_cast<const float *>(Pts + (size_t)k * PC * sizeof(float));
+          }
+          if (mine) xacc[xb + lane] = xacc[xb + lane] + (double)part;
+        }
+      }
+    }
+    t_hi = t_next;
+  }
+  uint32_t xbase = 0u;
+#pragma unroll
+  for (int i = 0; i < RW; ++i) {
+    uint32_t e0, n;
+    entries(i, e0, n);
+    const uint32_t xn = xn_of(i);
+    if ((uint32_t)lane < n) d.acc[e0 + lane] = acc[i];
+    if ((uint32_t)lane < xn) d.acc[e0 + 64 + lane] = xacc[xbase + lane];
+    xbase += xn;
+  }
+}
+
+// Gradient of a masked matrix from the accumulators of its existing synapses: one workgroup per presynaptic row.
+__global__ void __launch_bounds__(256)
+k_finish_grad_csr(const double *__restrict__ acc, const uint32_t *__restrict__ sub, const uint16_t *__restrict__ col, int N,
+                  int nsub, float *__restrict__ dW) {
+  const int j = blockIdx.x;
+  float *row = dW + (size_t)j * N;
+  for (int n = threadIdx.x; n < N; n += 256) row[n] = 0.0f;
+  __syncthreads();
+  const uint32_t e0 = sub[(size_t)j * (nsub + 1)], e1 = sub[(size_t)j * (nsub + 1) + nsub];
+  for (uint32_t e = e0 + threadIdx.x; e < e1; e += 256) row[col[e]] = (float)acc[e];
+}
+
 // One stage of the layer-pipelined backward pass takes two launches.
 // k_bwd_stage (512 threads), workgroup ranges in this order:
 //   [0, n_adj)        adjoint recurrences of the stage (job = block / B, batch element = block % B)
@@ -4025,9 +4205,45 @@ hipError_t launch_dw(const uint64_t *pre_mask, int pre_words, int n_pre, int lag
   return hipGetLastError();
 }
 
+static hipError_t launch_dw_csr(DwBatch batch, int B, hipStream_t s) {
+  if (batch.count <= 0) return hipSuccess;
+  if (B > 32) return hipErrorInvalidValue; // a tile is at least one whole time step of at most 32 rows
+  int total = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    if (batch.d[i].t1 <= batch.d[i].t0 || !batch.d[i].csr_sub || batch.d[i].n_pre != batch.d[i].n_post) return hipErrorInvalidValue;
+    batch.d[i].tiles_n = (batch.d[i].n_post + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW; // = sub-ranges of a compressed row
+    batch.d[i].tile0 = total;
+    total += ((batch.d[i].n_pre + 255) / 256) * batch.d[i].tiles_n;
+  }
+  const size_t lds = (size_t)32 * SNN_CSR_SUBW * sizeof(float) + (size_t)4 * 32 * sizeof(uint64_t) + (size_t)DWC_WAVES * 64 * (sizeof(double) + sizeof(uint32_t));
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_dw_csr),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_dw_csr, dim3(total), dim3(64 * DWC_WAVES), lds, s, batch, B);
+  return hipGetLastError();
+}
+
+hipError_t launch_finish_grad_csr(const double *acc, const uint32_t *csr_sub, const uint16_t *csr_col, int N, float *dW,
+                                  hipStream_t s) {
+  hipLaunchKernelGGL(k_finish_grad_csr, dim3(N), dim3(256), 0, s, acc, csr_sub, csr_col, N,
+                     (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW, dW);
+  return hipGetLastError();
+}
+
 hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s) {
   if (batch.count <= 0) return hipSuccess;
   if (B > 64) return hipErrorInvalidValue; // a tile is at least one whole time step of at most 64 rows
+  { // matrices that go through their compressed rows: a launch of their own
+    DwBatch cs{}, dn{};
+    cs.wide = dn.wide = batch.wide;
+    for (int i = 0; i < batch.count; ++i) (batch.d[i].csr_sub ? cs.d[cs.count++] : dn.d[dn.count++]) = batch.d[i];
+    if (cs.count) {
+      const hipError_t e = launch_dw_csr(cs, B, s);
+      if (e != hipSuccess) return e;
+      batch = dn;
+      if (batch.count <= 0) return hipSuccess;
+    }
+  }
   int total = 0;
   for (int i = 0; i < batch.count; ++i) {
     if (batch.d[i].t1 <= batch.d[i].t0) return hipErrorInvalidValue;

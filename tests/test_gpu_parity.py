@@ -813,6 +813,49 @@ def test_compressed_rows_keep_denormal_sums():
         net.snn_destroy()
 
 
+@pytest.mark.parametrize("hidden,B,T,density", [
+    ((1024,), 5, 30, 0.12),       # about half of the (row, sub-range) pairs have more than 64 entries: the rest kernel
+    ((2048, 600), 3, 24, 0.1),    # a ragged last sub-range and a ragged block of presynaptic rows
+    ((1536,), 32, 10, 0.1),       # one whole time step per tile
+    ((1024, 1024), 7, 40, 0.05),  # tiles of four steps, the last one ragged
+    ((1024,), 33, 8, 0.1),        # batch above 32: dense accumulators (the choice must not change the result)
+    ((1024,), 4, 12, 0.6)])       # too dense for one entry per lane: dense accumulators
+def test_weight_gradients_over_compressed_rows(hidden, B, T, density, monkeypatch):
+    """With the tiled event-driven weight-gradient kernel, a masked recurrent matrix accumulates its gradient per
+    existing synapse, through its compressed rows (k_dw_csr + k_dw_csr_rest) instead of over the dense tile
+    (SNN_DW_CSR=0).  Per synapse the sequence of operations is the same, so the gradients must be identical bit for
+    bit (zero where no synapse exists), eagerly and as a replayed graph, and match the oracle under every
+    strategy."""
+    w = synth.Workload("dwcsr_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=0.8,
+                       rec_density=density, seed=91 + B)
+    d = synth.generate(w)
+    L = len(hidden)
+    monkeypatch.setenv("SNN_DW", "tile")
+    got = {}
+    for mode in ("csr", "dense"):
+        if mode == "dense":
+            monkeypatch.setenv("SNN_DW_CSR", "0")
+        else:
+            monkeypatch.delenv("SNN_DW_CSR", raising=False)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)
+            got[mode] = _gpu_grads(net, L)
+            net.snn_bptt(snn.SNN_DOUBLE, 8, 3)  # the replayed graph
+            assert _identical(_gpu_grads(net, L), got[mode]), mode
+            net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+            assert _identical(_gpu_grads(net, L), got[mode]), mode
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_DW_CSR", raising=False)
+    assert _identical(got["csr"], got["dense"])
+    for l in range(L):
+        assert np.all(got["csr"][1][l][d["rec_mask"][l] == 0] == 0.0) and np.abs(got["csr"][1][l]).max() > 0
+    _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 8, 3), (snn.SNN_CHUNK, 0, 5)], nthreads=4)
+    monkeypatch.delenv("SNN_DW")
+
+
 @pytest.mark.parametrize("hidden,B,T,density,window", [
     ((2048,), 5, 14, 0.1, 0.0),        # one job, a ragged batch group (5 = 4 + 1)
     ((1536, 1100), 3, 12, 0.3, 0.0),   # two jobs of different widths in one launch, ragged row blocks
