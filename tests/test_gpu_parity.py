@@ -1012,6 +1012,39 @@ def test_spike_bitmasks_on_the_host_tier(hidden, B, T, tier_env, strategies, mon
         net.snn_destroy()
 
 
+def test_spike_ring_with_the_compressed_row_kernels(monkeypatch):
+    """The kernels that walk compressed rows or stage their own operands address the stored spike words through the
+    ring when spike_tier = 1 keeps only 2 C + 1600 steps of them in HBM: forward and recompute gathers over compressed
+    rows, the chip-wide adjoint, the tiled and the per-synapse weight-gradient kernels (forced for this small matrix).
+    Gradients, spike trains and a recomputed state must be the very bits of the run that keeps every bitmask in HBM."""
+    monkeypatch.setenv("SNN_HOST_TIER", "dma")
+    monkeypatch.setenv("SNN_DW", "tile")
+    monkeypatch.setenv("SNN_CSR", "1")
+    w = synth.Workload("spk_ring_csr_2048", 60, (2048,), 6, T=1800, B=3, p_in=0.05, gain=0.6, rec_density=0.1, seed=97)
+    d = synth.generate(w)
+    ref_net = snn.from_workload(w, d)
+    net = snn.from_workload(w, d, spike_tier=1)
+    try:
+        ref_net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        for strat, C, F in [(snn.SNN_DOUBLE, 40, 10), (snn.SNN_REMOTE, 64, 0)]:
+            st0 = ref_net.snn_bptt(strat, C, F)
+            st1 = net.snn_bptt(strat, C, F)
+            assert st1.bytes_spikes < st0.bytes_spikes and st1.bytes_host_spikes > 0
+            assert _identical(_gpu_grads(net, 1), _gpu_grads(ref_net, 1)), (strat, "eager")
+            net.snn_bptt(strat, C, F, want_stats=False)
+            assert _identical(_gpu_grads(net, 1), _gpu_grads(ref_net, 1)), (strat, "graph")
+        g = _gpu_grads(net, 1)
+        assert np.abs(g[1][0]).max() > 0 and np.all(g[1][0][d["rec_mask"][0] == 0] == 0.0)
+        assert np.array_equal(net.snn_get_spikes(0, w.T), ref_net.snn_get_spikes(0, w.T))
+        assert np.array_equal(net.snn_get_state(0, 901).view(np.uint32), ref_net.snn_get_state(0, 901).view(np.uint32))
+    finally:
+        net.snn_destroy()
+        ref_net.snn_destroy()
+    for k in ("SNN_HOST_TIER", "SNN_DW", "SNN_CSR"):
+        monkeypatch.delenv(k)
+
+
 @pytest.mark.parametrize("n_in,hidden,n_out,B,T", [(70, (100, 72, 130), 7, 3, 40), (50, (300, 1026), 5, 12, 21),
                                                    (40, (256, 256), 20, 32, 70), (33, (520,), 9, 64, 9),
                                                    (33, (130, 64), 3, 40, 17), (24, (64,), 2, 1, 30)])
