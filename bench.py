@@ -285,14 +285,23 @@ def main():
             ev_bytes = w.T * w.B * sum(4.0 * w.n_hidden[l] * ((in_rate if l == 0 else rate) * pre_n[l] + rate * w.n_hidden[l])
                                        for l in range(L))
             dense_flops = w.T * w.B * sum(2.0 * w.n_hidden[l] * (pre_n[l] + w.n_hidden[l]) for l in range(L))
-            for mode in ("gather", "mfma", "dense"):
+            # own bytes when the recurrent rows are compressed (6 bytes per existing synapse)
+            ev_bytes_csr = w.T * w.B * sum(w.n_hidden[l] * (4.0 * (in_rate if l == 0 else rate) * pre_n[l] + 6.0 * w.rec_density * rate * w.n_hidden[l])
+                                           for l in range(L))
+            modes = [("gather", "0"), ("mfma", "0"), ("dense", "0")]
+            if w.rec_density < 1.0:  # masked recurrent matrices: the recurrent part over compressed rows
+                modes += [("gather", "1"), ("dense", "1")]
+            for mode, csr in modes:
                 os.environ["SNN_CURRENTS"] = mode
+                os.environ["SNN_CSR"] = csr
                 ms = net.snn_debug_currents(hid, chunk, reps=2)
-                rows.append({"rate": rate, "kernel": {"gather": "k_currents", "mfma": "k_currents_mfma", "dense": "k_currents_dense"}[mode],
-                             "ms_per_pass": round(ms, 3), "event_row_GBs": round(ev_bytes / ms / 1e6, 1),
+                name = {"gather": "k_currents", "mfma": "k_currents_mfma", "dense": "k_currents_dense"}[mode]
+                rows.append({"rate": rate, "kernel": name + (" (feed-forward) + k_currents_csr (recurrent)" if csr == "1" else ""),
+                             "ms_per_pass": round(ms, 3), "event_row_GBs": round((ev_bytes_csr if csr == "1" else ev_bytes) / ms / 1e6, 1),
                              "dense_TFLOPs": round(dense_flops / ms / 1e9, 2)})
             del hid
         os.environ.pop("SNN_CURRENTS", None)
+        os.environ.pop("SNN_CSR", None)
         print(json.dumps({"micro_currents": w.name, "T": w.T, "batch": w.B, "chunk": chunk, "input_rate": round(in_rate, 4), "rows": rows}))
         net.snn_destroy()
         return
