@@ -188,7 +188,7 @@ void read_kernel_hooks(snn_ctx *c) {
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
   if (const char *e = std::getenv("SNN_WS_KERNEL"))
     n.sel_adjoint = !std::strcmp(e, "valu") ? 1 : !std::strcmp(e, "stream") ? 2 : !std::strcmp(e, "rows") ? 3 :
-                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : 0;
+                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : !std::strcmp(e, "single") ? 7 : 0;
   if (const char *e = std::getenv("SNN_SEQ_SLICES")) {
     const int v = std::atoi(e);
     n.sel_slices = (v == 1 || v == 2 || v == 4 || v == 8) ? (unsigned char)v : 0;
@@ -478,7 +478,8 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
       // (the kernel for layers wider than 1024 pads the batch to whole blocks of 16: 1, 2 or 4 of them)
       const size_t bp = nmax > 1024 && B <= 64 ? (size_t)((B + 15) / 16 == 3 ? 4 : (B + 15) / 16) * 16 : (size_t)B;
       const size_t xg_stride = ((size_t)4 * bp * nmax + 15) & ~(size_t)15; // [2][B][N] entries of 8 bytes (value + step tag)
-      const size_t bytes = n_bar * sizeof(unsigned) + (size_t)SNN_MAXL * xg_stride * 4;
+      // (+ 16 KB: readers of the tagged exchange address a row padded to 1024 entries of 8 bytes)
+      const size_t bytes = n_bar * sizeof(unsigned) + (size_t)SNN_MAXL * xg_stride * 4 + 16384;
       void *blk = uncached_block(cfg->device, bytes);
       if (!blk) return fail(c, SNN_E_HIP, "uncached device allocation failed");
       c->ws.bar = (unsigned *)blk;

@@ -1789,9 +1789,13 @@ k_adj_rec_ws(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, uns
 // accumulators and one LDS read per K-step, where the VALU version reads every dv value of 8 batch elements
 // once per thread and is bound by the LDS (about twice the time).  The four partial sums are combined in a
 // fixed order; exchange and barrier are those of k_adj_rec_ws.
-template <int NK> // K-steps per wavefront and row block: the padded width is 16 * NK
+// With NG = 2 a workgroup serves two batch groups of 16 with the same registers of W_rec, half a step apart: while
+// the values one group has just stored travel through the exchange buffer, the matrix cores work on the other
+// group, and the two round trips of a step no longer add to its products.  Half as many workgroups per layer also
+// lets more layers of a pipeline stage share a launch.  The operations per element are those of NG = 1.
+template <int NK, int NG> // K-steps per wavefront and row block (the padded width is 16 * NK); batch groups per workgroup
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) // the weights must stay in registers
-k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_b,
+k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_w,
               unsigned spin_limit, int blocks_per_job, int xg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int jq = blockIdx.x / blocks_per_job, vb = blockIdx.x % blocks_per_job;
@@ -1805,11 +1809,11 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
   (void)bar;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, lk = lane >> 4;
-  const int bg = vb % G_b, js = vb / G_b;
-  const int b0 = bg * 16, j0 = js * 32;
-  constexpr int NP = 16 * NK;          // padded reduction length (>= N)
-  float *xs = (float *)smem;           // [NP][16]  dv_{t+1}, batch-minor
-  float *part = xs + (size_t)NP * 16;  // [4][32][16]
+  const int bg = vb % G_w, js = vb / G_w; // G_w workgroups of NG batch groups each per 32 rows
+  const int j0 = js * 32;
+  constexpr int NP = 16 * NK;                          // padded reduction length (>= N)
+  float *xs_all = (float *)smem;                       // [NG][NP][16]  dv_{t+1}, batch-minor
+  float *part_all = xs_all + (size_t)NG * NP * 16;     // [NG][4][32][16]
 
   // A operands: a[rb][s] = W_rec[j0 + 16 rb + li][4 NK wv + 4 s + lk].  Every load unconditional, from a clamped
   // address, zeroed with an integer mask afterwards (a select lets the compiler put each load under its condition).
@@ -1826,8 +1830,10 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
     for (int q = 0; q < NK; ++q)
       a[rb][q] = __uint_as_float(__float_as_uint(a[rb][q]) & (0u - (uint32_t)(j < N && 4 * NK * wv + 4 * q + lk < N)));
   }
-  // dv_{t1+1} of this batch group
-  {
+  // dv_{t1+1} of the batch groups
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const int b0 = (bg * NG + g) * 16;
     float cv[NK];
 #pragma unroll
     for (int r = 0; r < NK; ++r) {
@@ -1837,32 +1843,32 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
 #pragma unroll
     for (int r = 0; r < NK; ++r) {
       const int i = tid + 256 * r, n = i >> 4, bb = i & 15;
-      xs[i] = __uint_as_float(__float_as_uint(cv[r]) & (0u - (uint32_t)(!carry_init && n < N && b0 + bb < B)));
+      xs_all[(size_t)g * NP * 16 + i] =
+          __uint_as_float(__float_as_uint(cv[r]) & (0u - (uint32_t)(!carry_init && n < N && b0 + bb < B)));
     }
   }
   __syncthreads();
-  // finalising role: 32 x 16 (row, batch element) pairs, two per thread
-  int fj[2], fbb[2], fb[2];
-  bool fin[2];
+  // finalising role: 32 x 16 (row, batch element) pairs per group, two per thread
+  int fj[2], fbb[2];
 #pragma unroll
   for (int e = 0; e < 2; ++e) {
     const int pidx = tid + 256 * e;
     fj[e] = j0 + (pidx >> 4);
     fbb[e] = pidx & 15;
-    fb[e] = b0 + fbb[e];
-    fin[e] = fj[e] < N && fb[e] < B;
   }
   const size_t slot_stride = (size_t)B * SN;
-  unsigned step = 0;
   bool dead = false;
-  for (int t = t1; t > t0; --t, ++step) {
+  // one step of one batch group: products, the sum of the four partial results, the recurrence, the exchange stores
+  auto compute = [&](int g, unsigned step, int t) {
+    const int b0 = (bg * NG + g) * 16;
+    float *xs = xs_all + (size_t)g * NP * 16, *part = part_all + (size_t)g * 4 * 32 * 16;
     const size_t slot = (size_t)(t - t_base - 1);
     float vt[2] = {0.0f, 0.0f}, upv[2] = {0.0f, 0.0f};
 #pragma unroll
     for (int e = 0; e < 2; ++e)
-      if (fin[e]) {
-        vt[e] = vbuf[slot * slot_stride + (size_t)fb[e] * SN + off + fj[e]];
-        upv[e] = up[(slot * B + fb[e]) * ldu + fj[e]];
+      if (fj[e] < N && b0 + fbb[e] < B) {
+        vt[e] = vbuf[slot * slot_stride + (size_t)(b0 + fbb[e]) * SN + off + fj[e]];
+        upv[e] = up[(slot * B + b0 + fbb[e]) * ldu + fj[e]];
       }
     v4f acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
     const float *xb = xs + (size_t)(4 * NK * wv + lk) * 16 + li;
@@ -1882,69 +1888,91 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
     const int par = step & 1;
 #pragma unroll
     for (int e = 0; e < 2; ++e)
-      if (fin[e]) {
-        const int fr = fj[e] - j0;
+      if (fj[e] < N && b0 + fbb[e] < B) {
+        const int fr = fj[e] - j0, fb = b0 + fbb[e];
         float sacc = part[((size_t)0 * 32 + fr) * 16 + fbb[e]];
 #pragma unroll
         for (int k = 1; k < 4; ++k) sacc = sacc + part[((size_t)k * 32 + fr) * 16 + fbb[e]];
         const float dn = xs[(size_t)fj[e] * 16 + fbb[e]];
         const float ds = (sacc + upv[e]) - net.theta * dn;
         const float dvt = fmaf(ds, surrogate(net, vt[e]), net.alpha * dn);
-        vbuf[slot * slot_stride + (size_t)fb[e] * SN + off + fj[e]] = dvt;
-        __hip_atomic_store(&xq[((size_t)par * B + fb[e]) * N + fj[e]],
+        vbuf[slot * slot_stride + (size_t)fb * SN + off + fj[e]] = dvt;
+        __hip_atomic_store(&xq[((size_t)par * B + fb) * N + fj[e]],
                            ((uint64_t)(step + 1u) << 32) | (uint64_t)__float_as_uint(dvt), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
       }
-    __syncthreads(); // every thread has read its dv_{t+1} from LDS
-    // ---- dv_t of the whole layer for this batch group -> LDS ------------------------------------
-    // No barrier: the values themselves say when they have arrived.  One store and one load round trip per step
-    // instead of store, wait, atomic, poll, load.  The polling is bounded like the barrier of k_adj_rec_ws: a
-    // thread that gives up raises *err, and from then on nobody waits.
-    {
-      // thread -> batch element tid/16, columns (tid%16) + 16*i: all loads issued before the first use
-      const int bb = tid >> 4, nb = tid & 15;
-      const uint64_t *src = xq + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N;
-      const uint32_t want = step + 1u;
-      if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
-        __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        dead = true;
+  };
+  // dv_t of the whole layer for one batch group -> LDS.  No barrier: the values themselves say when they have
+  // arrived.  One store and one load round trip per step instead of store, wait, atomic, poll, load.  The polling
+  // is bounded like the barrier of k_adj_rec_ws: a thread that gives up raises *err, and from then on nobody waits.
+  auto poll = [&](int g, unsigned step) {
+    const int b0 = (bg * NG + g) * 16, par = step & 1;
+    float *xs = xs_all + (size_t)g * NP * 16;
+    // thread -> batch element tid/16, columns (tid%16) + 16*i: all loads of a round issued before the first use.
+    // One base address for all of them, the column in the constant offset: entries past the layer's width read
+    // whatever follows (the buffer has 16 KB of slack behind its last row) and are neither waited for nor used.
+    const int bb = tid >> 4, nb = tid & 15;
+    const uint64_t *src = xq + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N + nb;
+    const uint32_t want = step + 1u;
+    if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
+      __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      dead = true;
+    }
+    constexpr int CH = NK < 32 ? NK : 32; // values polled at a time: a round that comes too early is read again
+#pragma unroll
+    for (int c = 0; c < NK; c += CH) {
+      uint64_t r[CH];
+      unsigned spins = 0;
+      for (;;) {
+        uint32_t bad = 0;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) // agent-scope loads: never served from this compute unit's L1
+          r[i] = __hip_atomic_load(&src[16 * (c + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) bad |= ((uint32_t)(r[i] >> 32) ^ want) & (0u - (uint32_t)(nb + 16 * (c + i) < N));
+        if (bad == 0u || dead) break;
+        if (++spins > spin_limit / 8u ||
+            ((spins & 15u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+          __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          dead = true; // keep going to the end of the chunk, never wait again
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
       }
-      constexpr int CH = NK < 32 ? NK : 32; // values polled at a time (registers)
 #pragma unroll
-      for (int c = 0; c < NK; c += CH) {
-        uint64_t r[CH];
-        unsigned spins = 0;
-        for (;;) {
-          uint32_t bad = 0;
-#pragma unroll
-          for (int i = 0; i < CH; ++i) { // agent-scope loads: never served from this compute unit's L1
-            const int n = nb + 16 * (c + i);
-            r[i] = __hip_atomic_load(&src[n < N ? n : N - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          }
-#pragma unroll
-          for (int i = 0; i < CH; ++i) bad |= (uint32_t)(r[i] >> 32) ^ want;
-          if (bad == 0u || dead) break;
-          if (++spins > spin_limit / 8u ||
-              ((spins & 15u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-            __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            dead = true; // keep going to the end of the chunk, never wait again
-            break;
-          }
-          __builtin_amdgcn_s_sleep(1);
-        }
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-          const int n = nb + 16 * (c + i);
-          xs[(size_t)n * 16 + bb] = __uint_as_float((uint32_t)r[i] & (0u - (uint32_t)(n < N && b0 + bb < B)));
-        }
+      for (int i = 0; i < CH; ++i) {
+        const int n = nb + 16 * (c + i);
+        xs[(size_t)n * 16 + bb] = __uint_as_float((uint32_t)r[i] & (0u - (uint32_t)(n < N && b0 + bb < B)));
       }
     }
+  };
+  unsigned step = 0;
+  for (int t = t1; t > t0; --t, ++step) {
+    compute(0, step, t);
+    if (NG == 2) {
+      // the second group runs half a step behind: its values of the previous step have had the first group's
+      // products to arrive
+      if (step > 0u) poll(1, step - 1u);
+      __syncthreads();
+      compute(1, step, t);
+    }
+    __syncthreads(); // every thread has read its dv_{t+1} of the first group from LDS
+    poll(0, step);
+    __syncthreads();
+  }
+  if (NG == 2) {
+    poll(1, step - 1u);
     __syncthreads();
   }
   // carry out dv_{t0+1}: every workgroup writes its own rows
 #pragma unroll
-  for (int e = 0; e < 2; ++e)
-    if (fin[e]) carry[(size_t)fb[e] * (SN + O) + off + fj[e]] = xs[(size_t)fj[e] * 16 + fbb[e]];
+  for (int g = 0; g < NG; ++g) {
+    const int b0 = (bg * NG + g) * 16;
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+      if (fj[e] < N && b0 + fbb[e] < B)
+        carry[(size_t)(b0 + fbb[e]) * (SN + O) + off + fj[e]] = xs_all[(size_t)g * NP * 16 + (size_t)fj[e] * 16 + fbb[e]];
+  }
 }
 
 // The chip-wide recurrence for layers whose recurrent matrix does not fit the registers of the chip (N > 1024,
@@ -3995,7 +4023,7 @@ static int adj_csrw_row_blocks(const NetDev &net, int count, int n_max) {
 }
 static bool adj_csrw_ok(const NetDev &net, int l, const WsArgs &ws) {
   const int N = net.N[l], B = net.B;
-  if ((net.sel_adjoint != 0 && net.sel_adjoint != 6) || !net.csr_sub[l] || N <= 1024 || N > 8192 || B > 64 || !ws.xg) return false;
+  if ((net.sel_adjoint != 0 && net.sel_adjoint != 6 && net.sel_adjoint != 7) || !net.csr_sub[l] || N <= 1024 || N > 8192 || B > 64 || !ws.xg) return false;
   if ((size_t)8 * ((B + 3) / 4) * N > (size_t)ws.xg_stride) return false;
   return adj_csrw_row_blocks(net, 1, N) > 0;
 }
@@ -4088,10 +4116,12 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       continue;
     }
     if (N <= 1024 && ws.xg && ws_use_mfma(net) && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
-      // matrix-core version: workgroup = 32 rows x 16 batch elements
-      const int G_b = (B + 15) / 16, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
+      // matrix-core version: workgroup = 32 rows x 16 batch elements, or x 2 groups of 16 half a step apart when
+      // the batch has an even number of groups (net.sel_adjoint == 7 keeps one group per workgroup)
+      const int G_b = (B + 15) / 16, NG = (G_b % 2 == 0 && net.sel_adjoint != 7) ? 2 : 1;
+      const int G_w = G_b / NG, n_slices = (N + 31) / 32, bpj = n_slices * G_w;
       const int NK = N <= 512 ? 32 : 64;
-      const size_t lds = ((size_t)16 * NK * 16 + 4 * 32 * 16) * sizeof(float);
+      const size_t lds = (size_t)NG * ((size_t)16 * NK * 16 + 4 * 32 * 16) * sizeof(float);
       AdjJobs grp{};
       for (int k = i; k < jobs.count; ++k)
         if (!taken[k] && net.N[jobs.j[k].l] == N && (grp.count + 1) * bpj <= ws.max_groups_m) {
@@ -4101,16 +4131,25 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       // tags of the exchange entries start from zero in every launch
       hipError_t e = launch_fill_zero(ws.xg, (size_t)grp.count * ws.xg_stride * sizeof(float), s);
       if (e != hipSuccess) return e;
-      e = hipFuncSetAttribute(NK == 32 ? reinterpret_cast<const void *>(k_adj_rec_wsm<32>)
-                                       : reinterpret_cast<const void *>(k_adj_rec_wsm<64>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      const void *fn = NK == 32 ? (NG == 2 ? reinterpret_cast<const void *>(k_adj_rec_wsm<32, 2>)
+                                           : reinterpret_cast<const void *>(k_adj_rec_wsm<32, 1>))
+                                : (NG == 2 ? reinterpret_cast<const void *>(k_adj_rec_wsm<64, 2>)
+                                           : reinterpret_cast<const void *>(k_adj_rec_wsm<64, 1>));
+      e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
-      if (NK == 32)
-        hipLaunchKernelGGL((k_adj_rec_wsm<32>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
-                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+      const dim3 grid(bpj * grp.count), block(256);
+      if (NK == 32 && NG == 1)
+        hipLaunchKernelGGL((k_adj_rec_wsm<32, 1>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
+                           ws.spin_limit, bpj, ws.xg_stride);
+      else if (NK == 32)
+        hipLaunchKernelGGL((k_adj_rec_wsm<32, 2>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
+                           ws.spin_limit, bpj, ws.xg_stride);
+      else if (NG == 1)
+        hipLaunchKernelGGL((k_adj_rec_wsm<64, 1>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
+                           ws.spin_limit, bpj, ws.xg_stride);
       else
-        hipLaunchKernelGGL((k_adj_rec_wsm<64>), dim3(bpj * grp.count), dim3(256), lds, s, net, grp, carry, ws.xg, ws.bar,
-                           ws.err, G_b, ws.spin_limit, bpj, ws.xg_stride);
+        hipLaunchKernelGGL((k_adj_rec_wsm<64, 2>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
+                           ws.spin_limit, bpj, ws.xg_stride);
     } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
       const int NR = N <= 512 ? 64 : 128;
@@ -4178,11 +4217,12 @@ int ws_max_resident_groups_mfma(int device) {
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
   int per_cu = 0;
-  const size_t lds = ((size_t)16 * 64 * 16 + 4 * 32 * 16) * sizeof(float);
-  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<64>), hipFuncAttributeMaxDynamicSharedMemorySize,
+  // the version with two batch groups per workgroup has the larger LDS footprint and bounds both
+  const size_t lds = (size_t)2 * ((size_t)16 * 64 * 16 + 4 * 32 * 16) * sizeof(float);
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<64, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds) != hipSuccess)
     return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wsm<64>, 256, lds) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wsm<64, 2>, 256, lds) != hipSuccess) return 0;
   return per_cu * prop.multiProcessorCount;
 }
 
