@@ -395,7 +395,12 @@ def main():
     L = len(w.n_hidden)
     big = any(4.0 * max(pn, n) * n >= (32 << 20) for pn, n in zip([w.n_in] + list(w.n_hidden[:-1]), w.n_hidden))
     dw_env = os.environ.get("SNN_DW", "")
-    dw_tile = w.B <= 64 and (dw_env == "tile" or (big and dw_env not in ("mfma", "event")))
+    # (the library's rule: always for matrices of 32 MB and more; for other networks with layers wider than 256 below
+    # 8 % presynaptic activity averaged over the weight rows, from the second training step on)
+    pre_rates = [in_rate] + list(rates[:-1])
+    act = (sum((pre_rates[l] * (w.n_in if l == 0 else w.n_hidden[l - 1]) + rates[l] * w.n_hidden[l]) * w.n_hidden[l] for l in range(L)) /
+           sum(((w.n_in if l == 0 else w.n_hidden[l - 1]) + w.n_hidden[l]) * w.n_hidden[l] for l in range(L)))
+    dw_tile = w.B <= 64 and (dw_env == "tile" or (dw_env not in ("mfma", "event") and (big or (max(w.n_hidden) > 256 and act < 0.08))))
     model = work_model(w, rates, in_rate, w.T, st.refwd1_steps + st.refwd2_steps, w.rec_density,
                        cur_steps=st.refwd_current_steps or (st.refwd1_steps + st.refwd2_steps),
                        dw_tile_chunks=n_bwd if dw_tile else 0,
@@ -442,14 +447,14 @@ def main():
     # compressed rows of masked recurrent matrices: forced by SNN_CSR=1, else the library's policy (matrices of 32 MB and
     # more, firing rate x density below 0.01 in every layer)
     csr_env = os.environ.get("SNN_CSR", "")
-    csr_pol = big and w.rec_density < 1.0 and max(rates) * w.rec_density < 0.01 and np.mean(rates) >= 0.045
-    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and (csr_env == "1" or (csr_env == "" and (csr_pol or (big and np.mean(rates) < 0.045))))
+    csr_pol = big and w.rec_density < 1.0 and max(rates) * w.rec_density < 0.01 and np.mean(rates) >= 0.035
+    csr_fwd = w.rec_density < 1.0 and all(n % 2048 == 0 for n in w.n_hidden) and (csr_env == "1" or (csr_env == "" and (csr_pol or (big and np.mean(rates) < 0.035))))
     kernel_of = {"fwd_seq": ("k_layer_seq_gather" if os.environ.get("SNN_SEQ_KERNEL", "") == "gather" else "k_layer_seq_rs") if not wide else ("k_layer_seq_csr_sl" if csr_fwd else
                             ("k_layer_seq_gather_sl" if max(w.n_hidden) >= 2048 and max(w.n_hidden) % 1024 == 0 else "k_layer_seq_gather")),
-                 # (matrices of 32 MB and more: the dense matrix-core version from 4.5 % presynaptic activity, below it
+                 # (matrices of 32 MB and more: the dense matrix-core version from 3.5 % presynaptic activity, below it
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
-                 "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
-                 "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.045 else "k_currents") if big else "k_currents_mfma",
+                 "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.035 else "k_currents") if big else "k_currents_mfma",
+                 "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.035 else "k_currents") if big else "k_currents_mfma",
                  "scan": "k_scan", "up_gemm": "k_up_gemm<4,4,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else adj_kernel)}

@@ -85,7 +85,8 @@ struct snn_ctx {
   bool graphs_enabled = true;   // SNN_GRAPH=0 turns graph replay off
   bool own_stream = false;
   bool dw_event_driven = false; // SNN_DW=event selects the row-by-row kernel instead of the MFMA contraction
-  bool dw_tile = false;         // the event-driven tiled kernel (networks with very large matrices, batch <= 64; SNN_DW=tile|mfma)
+  bool dw_tile = false;         // the event-driven tiled kernel instead of the dense contraction (batch <= 64; SNN_DW=tile|mfma)
+  bool dw_rate_driven = false;  // ... chosen from the firing rates of the previous step (layers wider than 256, no SNN_DW)
   bool bwd_pipeline = true;     // SNN_BWD_PIPE=0: the adjoint pass finishes every layer of a chunk before the next chunk
   bool bwd_fuse = true;         // SNN_BWD_FUSE=0: weight gradients always in launches of their own
   bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
@@ -188,7 +189,7 @@ void read_kernel_hooks(snn_ctx *c) {
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
   if (const char *e = std::getenv("SNN_WS_KERNEL"))
     n.sel_adjoint = !std::strcmp(e, "valu") ? 1 : !std::strcmp(e, "stream") ? 2 : !std::strcmp(e, "rows") ? 3 :
-                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : !std::strcmp(e, "single") ? 7 : 0;
+                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : !std::strcmp(e, "single") ? 7 : !std::strcmp(e, "pair") ? 8 : 0;
   if (const char *e = std::getenv("SNN_SEQ_SLICES")) {
     const int v = std::atoi(e);
     n.sel_slices = (v == 1 || v == 2 || v == 4 || v == 8) ? (unsigned char)v : 0;
@@ -499,12 +500,20 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
     const size_t pmax = (size_t)std::max(l == 0 ? n.n_in : n.N[l - 1], n.N[l]);
     if (pmax * n.N[l] * sizeof(float) >= ((size_t)32 << 20)) c->rate_driven = true;
   }
-  // The weight-gradient kernel is a fixed choice per context (the kernels differ in how they group the fp32 sum of
-  // a time step, and every training step of a context must give the same bits): the event-driven tiled kernel for
-  // networks with a weight matrix far beyond the L2 -- the class whose benchmark configuration runs at a few
-  // percent activity, where the dense contraction multiplies mostly zeros -- and batches of at most 64.
+  // The weight-gradient kernel (both give the same bits: per time step an fp32 sum over the batch elements in
+  // ascending order, then one fp64 add): the event-driven tiled kernel pays per presynaptic spike, the dense
+  // contraction per presynaptic neuron.  Networks with a weight matrix far beyond the L2 always take the tiled kernel
+  // (with compressed rows for masked matrices it stays ahead of the dense contraction at 20 % activity as well);
+  // other networks with layers wider than 256 follow the firing rates of the previous step, like the current
+  // kernels, and start with the dense contraction.
   c->dw_tile = c->rate_driven && B <= 64;
+  {
+    int nmax = 0;
+    for (int l = 0; l < L; ++l) nmax = n.N[l] > nmax ? n.N[l] : nmax;
+    c->dw_rate_driven = nmax > 256 && B <= 64 && !c->rate_driven;
+  }
   if (const char *e = std::getenv("SNN_DW")) {
+    c->dw_rate_driven = false;
     if (!std::strcmp(e, "tile")) c->dw_tile = B <= 64;
     else if (!std::strcmp(e, "mfma") || !std::strcmp(e, "event")) c->dw_tile = false;
   }
@@ -951,7 +960,9 @@ struct Timer {
 
 // Firing rates of the step that was just queued (spike counts of all stored bitmasks), and from them the current
 // kernel of the layers with very large weight matrices for the next step: the event-by-event gather pays per
-// presynaptic spike, the dense matrix-core version per presynaptic neuron; measured break-even about 4.5 %.
+// presynaptic spike, the dense matrix-core version per presynaptic neuron; measured break-even about 3.5 %.
+// (weight gradients of 1024-wide layers, batch 64: tiled kernel 17 / 33 ms at 4.6 / 12 % activity, dense contraction 25.5)
+static constexpr double DW_TILE_MAX_ACTIVITY = 0.08;
 static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out, bool hidden_counted) {
   const NetDev &n = c->net;
   const int L = n.L, B = n.B;
@@ -967,18 +978,20 @@ static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out, boo
   for (int l = 0; l <= L; ++l) r[l] = (double)cnt[l] / ((double)T * B * (l == 0 ? n.n_in : n.N[l - 1]));
   if (rates_out)
     for (int l = 0; l < L; ++l) rates_out[l] = (float)r[l + 1];
+  // presynaptic activity averaged over the weight rows of all layers
+  double ev_fw = 0, ev_re = 0, rows_fw = 0, rows_re = 0;
+  for (int l = 0; l < L; ++l) {
+    const double p_in = l == 0 ? n.n_in : n.N[l - 1], p_rec = n.N[l], w = n.N[l];
+    ev_fw += r[l] * p_in * w; rows_fw += p_in * w;
+    ev_re += (r[l] * p_in + r[l + 1] * p_rec) * w; rows_re += (p_in + p_rec) * w;
+  }
+  // weight gradients: measured break-even of the tiled event-driven kernel and the dense contraction
+  if (c->dw_rate_driven) c->dw_tile = ev_re < DW_TILE_MAX_ACTIVITY * rows_re;
   if (c->rate_driven) {
-    // one choice for the whole network (jobs of one launch then stay in one launch): presynaptic activity
-    // averaged over the weight rows of all layers
-    double ev_fw = 0, ev_re = 0, rows_fw = 0, rows_re = 0;
+    // one choice for the whole network (jobs of one launch then stay in one launch)
     for (int l = 0; l < L; ++l) {
-      const double p_in = l == 0 ? n.n_in : n.N[l - 1], p_rec = n.N[l], w = n.N[l];
-      ev_fw += r[l] * p_in * w; rows_fw += p_in * w;
-      ev_re += (r[l] * p_in + r[l + 1] * p_rec) * w; rows_re += (p_in + p_rec) * w;
-    }
-    for (int l = 0; l < L; ++l) {
-      c->net.cur_pol[0][l] = ev_fw < 0.045 * rows_fw ? 1 : 2;
-      c->net.cur_pol[1][l] = ev_re < 0.045 * rows_re ? 1 : 2;
+      c->net.cur_pol[0][l] = ev_fw < 0.035 * rows_fw ? 1 : 2;
+      c->net.cur_pol[1][l] = ev_re < 0.035 * rows_re ? 1 : 2;
     }
     // A masked recurrent matrix kept as compressed rows: the gather over them pays per presynaptic spike and per
     // synapse that exists.  Measured at configuration 4's widths it takes 0.39 of the dense kernel's time for the
@@ -1835,6 +1848,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   if (use_graph) {
     unsigned long long pol = 0;
     for (int l = 0; l < L; ++l) pol = pol * 32 + c->net.cur_pol[0][l] * 8 + c->net.cur_pol[1][l] * 2 + c->net.seq_pol[l];
+    pol = pol * 2 + (c->dw_tile ? 1u : 0u);
     const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24 | (unsigned)n.sel_seq << 28;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,
                            ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1], p.n_cache_slots};
@@ -1854,7 +1868,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
       c->graph_key = key;
     }
     HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
-    if (c->rate_driven) {
+    if (c->rate_driven || c->dw_rate_driven) {
       snn_status rr = update_current_policy(c, T, nullptr, ring > 0);
       if (rr != SNN_OK) return rr;
     }
@@ -1870,7 +1884,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   snn_status rs = enqueue_step(c, p, st, tm, &ev_fwd);
   if (rs != SNN_OK) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamSynchronize(s); return rs; }
   hipEvent_t ev_end = tm.mark();
-  if (stats || c->rate_driven) {
+  if (stats || c->rate_driven || c->dw_rate_driven) {
     snn_status rr = update_current_policy(c, T, st.firing_rate, ring > 0);
     if (rr != SNN_OK) return rr;
   }

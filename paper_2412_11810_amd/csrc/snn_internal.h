@@ -50,7 +50,8 @@ struct NetDev {
   // 3 event-driven rows (neurons inside the surrogate window only), 4 the same kernel evaluating every row, 5 the
   // chip-wide kernels over the dense-stored matrix, also under a surrogate window, 6 the chip-wide kernel over
   // compressed rows also under a surrogate window, 7 the matrix-core version of the chip-wide recurrence with one
-  // batch group per workgroup (never two half a step apart).
+  // batch group per workgroup (never two half a step apart), 8 the same with two groups wherever the batch has an
+  // even number of groups.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
   // Sequential forward part of layers of up to 256 neurons: sel_seq 1 forces the event-driven gather, 2 the

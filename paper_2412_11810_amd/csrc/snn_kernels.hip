@@ -3407,7 +3407,7 @@ static void currents_job_shape(const NetDev &net, const CurJob &j, int *pmax, si
 }
 // Which kernel runs a job: 0 list version, 1 dense version, 2 event-by-event gather.  Weights that fit the L2
 // many times over: always the list version.  Weights far beyond it: what the context chose from the firing rates
-// of its last step (the gather below about 4.5 % presynaptic activity, the dense version above, and before any
+// of its last step (the gather below about 3.5 % presynaptic activity, the dense version above, and before any
 // rate is known).  SNN_CURRENTS=dense / mfma / gather forces one of them for every job.
 #define SNN_DENSE_MB 4
 static int currents_job_kernel(const NetDev &net, const CurJob &j) {
@@ -4023,7 +4023,7 @@ static int adj_csrw_row_blocks(const NetDev &net, int count, int n_max) {
 }
 static bool adj_csrw_ok(const NetDev &net, int l, const WsArgs &ws) {
   const int N = net.N[l], B = net.B;
-  if ((net.sel_adjoint != 0 && net.sel_adjoint != 6 && net.sel_adjoint != 7) || !net.csr_sub[l] || N <= 1024 || N > 8192 || B > 64 || !ws.xg) return false;
+  if ((net.sel_adjoint != 0 && net.sel_adjoint < 6) || !net.csr_sub[l] || N <= 1024 || N > 8192 || B > 64 || !ws.xg) return false;
   if ((size_t)8 * ((B + 3) / 4) * N > (size_t)ws.xg_stride) return false;
   return adj_csrw_row_blocks(net, 1, N) > 0;
 }
@@ -4116,9 +4116,20 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       continue;
     }
     if (N <= 1024 && ws.xg && ws_use_mfma(net) && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
-      // matrix-core version: workgroup = 32 rows x 16 batch elements, or x 2 groups of 16 half a step apart when
-      // the batch has an even number of groups (net.sel_adjoint == 7 keeps one group per workgroup)
-      const int G_b = (B + 15) / 16, NG = (G_b % 2 == 0 && net.sel_adjoint != 7) ? 2 : 1;
+      // matrix-core version: workgroup = 32 rows x 16 batch elements, or x 2 groups of 16 half a step apart.  Two
+      // groups per workgroup double the products a workgroup runs one after the other per step and halve the
+      // workgroups per layer: taken where that at least halves the launches the stage's layers of this width need
+      // (configuration 2: three layers in one launch instead of two launches) and the batch has an even number of
+      // groups (net.sel_adjoint == 7 keeps one group per workgroup, 8 takes two wherever the batch allows)
+      const int G_b = (B + 15) / 16;
+      int NG = (G_b % 2 == 0 && net.sel_adjoint == 8) ? 2 : 1;
+      if (G_b % 2 == 0 && net.sel_adjoint != 7 && net.sel_adjoint != 8) {
+        int cnt = 0;
+        for (int k = i; k < jobs.count; ++k)
+          if (!taken[k] && net.N[jobs.j[k].l] == N) ++cnt;
+        const int per1 = ((N + 31) / 32) * G_b, cap1 = ws.max_groups_m / per1, cap2 = ws.max_groups_m / (per1 / 2);
+        if (cap1 >= 1 && 2 * ((cnt + cap2 - 1) / cap2) <= (cnt + cap1 - 1) / cap1) NG = 2;
+      }
       const int G_w = G_b / NG, n_slices = (N + 31) / 32, bpj = n_slices * G_w;
       const int NK = N <= 512 ? 32 : 64;
       const size_t lds = (size_t)NG * ((size_t)16 * NK * 16 + 4 * 32 * 16) * sizeof(float);
