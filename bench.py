@@ -154,6 +154,8 @@ def main():
     ap.add_argument("--others", default="auto", choices=["auto", "all", "none"],
                     help="time the other strategies too (auto: all of them for configurations 0 and 1, none otherwise)")
     ap.add_argument("--no-long", action="store_true", help="skip the 10x-sequence-length comparison")
+    ap.add_argument("--no-tight", action="store_true",
+                    help="skip the same strategy under the smallest budget it can run in (snn_bytes_required)")
     ap.add_argument("--long-reps", type=int, default=1)
     ap.add_argument("--budget", type=int, default=-1, help="HBM activation budget in bytes (default: the configuration's)")
     ap.add_argument("--single", action="store_true")
@@ -373,6 +375,27 @@ def main():
                     others[name] = round(nts / time_strategy(name, max(2, args.steps // 4), 2), 1)
                 except snn.SnnError as e:
                     others[name] = str(e)
+
+    # the same strategy and intervals under the smallest budget they can run in: no currents cache (Double recomputes
+    # the currents twice), no buffers to pipeline the layers of the adjoint pass -- the other end of the trade
+    tight = None
+    if not args.no_tight and budget:
+        Ct, Ft = params[args.strategy]
+        need_min = int(snn.snn_bytes_required(net.cfg, SID[args.strategy], w.T, Ct, Ft))
+        if 0 < need_min < budget:
+            def step_tight():
+                net.snn_bind_inputs(x, y, w.T)
+                return net.snn_bptt(SID[args.strategy], Ct, Ft, need_min, want_stats=False)
+            step_tight()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(2):
+                step_tight()
+            torch.cuda.synchronize()
+            sec_t = (time.perf_counter() - t0) / 2
+            tight = {"hbm_budget_bytes": need_min, "ms_per_step": round(sec_t * 1e3, 3), "neuron_timesteps_per_s": round(nts / sec_t, 1)}
+            progress(f"under the smallest budget ({need_min} B): {sec_t * 1e3:.1f} ms per step")
+            step(args.strategy)  # back to the timed plan (its graph is recorded again) before the instrumented steps
 
     # instrumented (eager) steps of the timed strategy: per-kernel-kind durations from HIP events
     # recorded on the stream the kernels run on; the second one is used (the first pays one-time costs)
@@ -674,6 +697,8 @@ def main():
                    "hbm_spike_bytes": int(st.bytes_spikes), "host_spike_bytes": int(st.bytes_host_spikes),
                    "spike_link_bytes_per_step": int(st.spike_d2h_bytes + st.spike_h2d_bytes),
                    "firing_rate": [round(r, 4) for r in rates], "input_rate": round(in_rate, 4),
+                   "same_intervals_under_the_smallest_budget": tight,
+                   "forward_pass_kept_currents_of_steps": max(0, w.T - int(st.refwd_current_steps)) if args.strategy == "double" else 0,
                    "steps_per_pass": {"forward": int(st.fwd_steps), "re_forward_1": int(st.refwd1_steps),
                                       "re_forward_2": int(st.refwd2_steps), "backward": int(st.bwd_steps),
                                       "recompute_steps_whose_currents_were_computed": int(st.refwd_current_steps)},

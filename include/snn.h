@@ -112,7 +112,8 @@ typedef struct {
   int64_t bytes_host_spikes;    /* pinned host memory holding the hidden layers' spike bitmasks (spike_tier 1) */
   int64_t fwd_steps, refwd1_steps, refwd2_steps, bwd_steps; /* time steps per pass             */
   int64_t refwd_current_steps; /* time steps whose synaptic currents the recompute passes computed: refwd1 + refwd2
-                                  unless Double kept a segment's currents between its two passes           */
+                                  unless Double kept a segment's currents between its two passes (then once per
+                                  step) or the forward pass left them in that cache (then not at all)      */
   int32_t local_state_slots; /* states resident in HBM at the peak (M_s units)                 */
   int32_t remote_state_slots;
   float firing_rate[SNN_MAX_LAYERS]; /* measured mean rate of each hidden layer                */
@@ -164,8 +165,13 @@ snn_status snn_forward_noalloc(snn_ctx *ctx, const uint8_t *in_spikes, const int
  *   snn_bytes_required is the least the strategy can run in (one chunk buffer: the paper's state
  *   count); below it -> SNN_E_BUDGET before anything is allocated.  With room to spare (or no budget)
  *   the call takes up to n_layers + 2 more chunk buffers, which let the layers of the adjoint pass and
- *   the recompute of the next chunks overlap; gradients are the same bit for bit either way, and
- *   stats reports what was allocated. */
+ *   the recompute of the next chunks overlap; DOUBLE then takes coarse_interval more state slots to keep the
+ *   synaptic currents of a coarse segment between its two recompute passes (Section "Double Checkpointing":
+ *   T_Double's second recomputation then costs scans only) and, for networks whose layers all have more than 256
+ *   neurons, as many further slots as the budget leaves, in whole coarse segments from the end of the
+ *   sequence, in which the forward pass leaves the currents it computed, so that those segments' currents are
+ *   not recomputed at all (without a budget: the last segment only).  Gradients are the same bit for bit
+ *   either way, and stats reports what was allocated and how many steps' currents were recomputed. */
 snn_status snn_bptt(snn_ctx *ctx, snn_strategy strategy, int32_t coarse_interval, int32_t fine_interval,
                     size_t hbm_budget_bytes, snn_stats *stats_or_null);
 
@@ -252,6 +258,8 @@ void snn_destroy(snn_ctx *ctx);
  *                                (batch <= 64) / the matrix-core contraction (default: tiled when some weight
  *                                matrix has 32 MB or more, else the contraction)
  *     SNN_RF_CACHE=0             Double: never keep a coarse segment's currents between its two recompute passes
+ *     SNN_KEEP_CURRENTS=0        Double: the forward pass never leaves the currents of the last coarse segments in
+ *                                that cache (default: as many whole segments as the budget has room for)
  *     SNN_DW_CSR=0               tiled weight gradients of masked recurrent matrices over the dense tile, not per
  *                                existing synapse
  *     SNN_GRAPH=0                no HIP-graph replay of the training step

@@ -92,6 +92,7 @@ struct snn_ctx {
   bool pre_in_stage = true;     // SNN_PRE_IN_STAGE=0: recompute of later chunks in the launch between two stages
   bool rate_driven = false;     // some weight matrix is far beyond the L2: the current kernel follows the firing rates
   bool rf_cache = true;         // SNN_RF_CACHE=0: Double never keeps a segment's currents between its two recompute passes
+  bool keep_currents = true;    // SNN_KEEP_CURRENTS=0: the forward pass never leaves currents in that cache
   std::string err;
   size_t Ms() const { return (size_t)cfg.batch * net.SN * sizeof(float); }
 };
@@ -400,6 +401,7 @@ snn_status snn_init(const snn_config *cfg, snn_ctx **out) {
   if (const char *e = std::getenv("SNN_BWD_FUSE")) c->bwd_fuse = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_PRE_IN_STAGE")) c->pre_in_stage = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_RF_CACHE")) c->rf_cache = std::strcmp(e, "0") != 0;
+  if (const char *e = std::getenv("SNN_KEEP_CURRENTS")) c->keep_currents = std::strcmp(e, "0") != 0;
   if (const char *e = std::getenv("SNN_DW_CSR")) c->dw_csr = std::strcmp(e, "0") != 0;
   read_kernel_hooks(c);
   char buf[256];
@@ -1418,7 +1420,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, &cb, &c->ws));
   } else if (direct) {
     // x_0 lives in host slot 0 (zeroed on the host); the sequential kernels store x_{KC} into host slot K
-    const StoreSpec sp{c->host_ckpt, slot, 0, p.C, 1, T - 1, 0};
+    StoreSpec sp{c->host_ckpt, slot, 0, p.C, 1, T - 1, 0};
+    if (ccache && p.keep_from >= 0) { // the currents of the last coarse segment(s) stay for the backward pass
+      sp.cur = ccache;
+      sp.cur_from = p.keep_from;
+      cache_a = p.keep_from; cache_b = T;
+    }
     const std::vector<int> bounds = tile_bounds(0, T, T); // no host-side work at the checkpoints: full tiles
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, R > 0 ? &cb_spk : nullptr, &c->ws));
     st.n_d2h += p.n_remote - 1;
@@ -1465,7 +1472,12 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
     so.inner = &cb;
     const std::vector<int> bounds = tile_bounds(0, T, p.C);
     HIPCHK(c, snap.reserve(0)); // nothing to wait for yet; marks checkpoint 1 as reserved
-    const StoreSpec sp{stage, slot, 0, p.C, 1, T - 1, p.n_stage_slots}; // x_{KC} -> staging slot K % n_stage
+    StoreSpec sp{stage, slot, 0, p.C, 1, T - 1, p.n_stage_slots}; // x_{KC} -> staging slot K % n_stage
+    if (ccache && p.keep_from >= 0) { // the currents of the last coarse segment(s) stay for the backward pass
+      sp.cur = ccache;
+      sp.cur_from = p.keep_from;
+      cache_a = p.keep_from; cache_b = T;
+    }
     HIPCHK(c, launch_forward(n, bounds.data(), (int)bounds.size() - 1, c->cur_state, sp, c->readout, 1, c->dubuf, s, &hk, R > 0 ? &cb_spk : &cb, &c->ws));
     so.inner = nullptr;
   }
@@ -1625,7 +1637,8 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
       case OP_REFWD1: {
         // rebuild the fine checkpoints x_{a+F}, x_{a+2F}, ..., x_b, one fine interval at a time: the
         // chunk buffer takes the currents of the interval, the scan keeps only its last state
-        if (ccache) { // the currents of the whole segment in one launch, kept for Re-Forward_2
+        if (ccache && !(cache_a >= 0 && op.a >= cache_a && op.b <= cache_b)) { // (the forward pass left none for it)
+          // the currents of the whole segment in one launch, kept for Re-Forward_2
           const int seg_end = std::min((op.a / p.C + 1) * p.C, T);
           tm.begin(1);
           HIPCHK(c, launch_recompute_currents(n, op.a, seg_end, ccache, op.a, slot, s));
@@ -1642,7 +1655,7 @@ static snn_status enqueue_step(snn_ctx *c, const Plan &p, snn_stats &st, Timer &
             st.refwd_current_steps += p.F;
           }
           tm.begin(9);
-          if (ccache) HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, ccache, op.a, slot, 0, lckpt + (size_t)m * slot, s));
+          if (ccache) HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, ccache, cache_a, slot, 0, lckpt + (size_t)m * slot, s));
           else HIPCHK(c, launch_recompute_scan(n, a, a + p.F, src, chunk, a, slot, 0, lckpt + (size_t)m * slot, s));
           tm.end();
         }
@@ -1766,6 +1779,26 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     Plan q = p;
     q.n_cache_slots = p.C;
     if (!budget || (size_t)q.local_slots() * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring) <= budget) p = q;
+    // The forward pass computes the same currents (I_t = I_in,t + I_rec,t is a value of its own there too): with
+    // the cache in place it leaves those of the last coarse segment(s) in it -- as many whole segments, counted
+    // from the end of the sequence, as the budget has room for (without a budget: the last one, which the cache
+    // holds anyway) -- and Re-Forward_1 of those segments computes none.  With room for the whole sequence the
+    // backward pass recomputes states by scans only.  Layers above 256 neurons only: their sequential kernels
+    // write the currents out.
+    bool wide_only = true;
+    for (int l = 0; l < L; ++l) wide_only = wide_only && n.N[l] > 256;
+    if (p.n_cache_slots && c->keep_currents && wide_only) {
+      size_t room = (size_t)p.C;
+      if (budget) {
+        const size_t fixed = (size_t)(p.local_slots() - p.n_cache_slots) * Ms + work_bytes(n, p.chunk_len) + spike_bytes(n, T, ring);
+        room = std::min<size_t>((size_t)T, (budget - fixed) / Ms);
+      }
+      const int keep_from = (int)(((size_t)T - room + (size_t)p.C - 1) / (size_t)p.C) * p.C; // a coarse boundary
+      if (keep_from < T) {
+        p.keep_from = keep_from;
+        p.n_cache_slots = std::max(p.C, T - keep_from);
+      }
+    }
   }
   const size_t need_states = (size_t)p.local_slots() * Ms;
   const size_t need_work = work_bytes(n, p.chunk_len);

@@ -70,6 +70,11 @@ struct StoreSpec {
   int slot0;
   int t_max;          // ... and t <= t_max
   int slot_mod;       // if > 0 the slot index is taken modulo this (ring of checkpoint slots)
+  // Forward pass of wide layers only (the gather kernels of layers above 256 neurons): the synaptic current
+  // I_t = I_in,t + I_rec,t of every step t > cur_from also goes to cur[(t - cur_from - 1) * slot_stride + ...], laid
+  // out like a chunk of recomputed currents, so that the backward pass need not compute it again (NULL: nothing).
+  float *cur;
+  int cur_from;
 };
 
 // Optional timing hook: the launchers bracket groups of kernels of one kind (HIP events on the
@@ -250,6 +255,9 @@ struct Plan {
   int n_remote;       // host slots
   int n_cache_slots;  // DOUBLE, when the budget has room: the synaptic currents of a whole coarse segment, computed once
                       // by Re-Forward_1 and read again by the scans of Re-Forward_2 (C slots; 0: both passes compute them)
+                      // or more: the forward pass then leaves the currents of every step after keep_from there
+  int keep_from;      // DOUBLE: a multiple of C; the forward pass keeps the currents of steps (keep_from, T] in the
+                      // cache (slot t - keep_from - 1), Re-Forward_1 of those coarse segments computes none (-1: keeps none)
   int local_slots() const { return chunk_len * n_chunk_bufs + n_local_ckpt + n_load_slots + n_stage_slots + n_cache_slots; }
 };
 // Resolves defaults (0 -> square-root rules) and validates.  Returns false on invalid arguments.

@@ -441,8 +441,11 @@ k_layer_seq_gather(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
       if (widx < Wd) { // uniform per wave
         float a = net.alpha * v[k];
         if ((sp >> k) & 1u) a = a - net.theta;
-        const float vn = n < N ? a + (in_t[k] + a_rec[k]) : 0.0f;
+        const float it = in_t[k] + a_rec[k];
+        const float vn = n < N ? a + it : 0.0f;
         v[k] = vn;
+        if (st.cur && t > st.cur_from && n < N)
+          st.cur[(size_t)(t - st.cur_from - 1) * st.slot_stride + (size_t)b * SN + off + n] = it;
         const uint64_t word = __ballot(n < N && vn > net.theta);
         if ((word >> lane) & 1ull) spn |= 1u << k;
         if (store_slot >= 0 && n < N)
@@ -536,8 +539,10 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
       const int nl = tid + k * nt, widx = w0 + (nl >> 6);
       float a = net.alpha * v[k];
       if ((sp >> k) & 1u) a = a - net.theta;
-      const float vn = a + (in_t[k] + a_rec[k]);
+      const float it = in_t[k] + a_rec[k];
+      const float vn = a + it;
       v[k] = vn;
+      if (st.cur && t > st.cur_from) st.cur[(size_t)(t - st.cur_from - 1) * st.slot_stride + (size_t)b * SN + off + c0 + nl] = it;
       const uint64_t word = __ballot(vn > net.theta);
       if ((word >> lane) & 1ull) spn |= 1u << k;
       if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + nl] = vn;
@@ -740,8 +745,10 @@ k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
       const float a_rec = acc_w[64 * k + lane];
       float a = net.alpha * v[k];
       if ((sp >> k) & 1u) a = a - net.theta;
-      const float vn = a + (in_t[k] + a_rec);
+      const float it = in_t[k] + a_rec;
+      const float vn = a + it;
       v[k] = vn;
+      if (st.cur && t > st.cur_from) st.cur[(size_t)(t - st.cur_from - 1) * st.slot_stride + (size_t)b * SN + off + c0 + 64 * k + lane] = it;
       const uint64_t word = __ballot(vn > net.theta);
       if ((word >> lane) & 1ull) spn |= 1u << k;
       if (store_slot >= 0) st.base[(size_t)store_slot * st.slot_stride + (size_t)b * SN + off + c0 + 64 * k + lane] = vn;

@@ -22,6 +22,7 @@ static int isqrt_ceil(int x) {
 bool snn_make_plan(int strategy, int T, int C, int F, Plan *p) {
   if (T < 1 || C < 0 || F < 0) return false;
   Plan q{};
+  q.keep_from = -1;
   q.strategy = strategy;
   q.T = T;
   q.n_chunk_bufs = 1;

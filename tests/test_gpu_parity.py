@@ -193,6 +193,43 @@ def test_chip_wide_adjoint_valu_version(monkeypatch):
     monkeypatch.delenv("SNN_WS_KERNEL")
 
 
+@pytest.mark.parametrize("hidden,B,T,C,F,density", [((300, 520), 5, 43, 8, 3, 1.0), ((1024,), 20, 30, 10, 4, 1.0),
+                                                     ((2048, 2048), 3, 26, 8, 4, 0.1)])
+def test_forward_pass_keeps_currents_for_double(hidden, B, T, C, F, density, monkeypatch):
+    """Double with the currents cache: the forward pass of layers above 256 neurons leaves the synaptic currents of
+    the last coarse segments in the cache -- the last segment without a budget, as many whole segments as fit under a
+    budget, every step under a generous one -- and Re-Forward_1 of those segments computes none (counted in the
+    statistics).  Ragged last segment, three sequential kernels (one workgroup per batch element, sliced, sliced over
+    compressed rows).  Against the oracle, and bit-identical to the step that keeps nothing (SNN_KEEP_CURRENTS=0)."""
+    w = synth.Workload("keep_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=0.6,
+                       rec_density=density, seed=61 + B)
+    if density < 1.0:
+        monkeypatch.setenv("SNN_CSR", "1")
+    first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, C, F)], nthreads=8, check_states=False)
+    d = synth.generate(w)
+    cfg = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, w.T, w.B)
+    last = T - ((T - 1) // C) * C                      # steps of the (ragged) last coarse segment
+    tight = snn.snn_bytes_required(cfg, snn.SNN_DOUBLE, T, C, F)  # (one chunk buffer, no cache: both come first)
+    slot = 4 * B * sum(hidden)
+    seen = {}
+    for tag, keep, budget in (("none", "0", 0), ("last", "1", 0), ("one_more", "1", tight + (last + C + len(hidden) * F) * slot + slot // 2),
+                              ("all", "1", tight + 2 * T * slot)):
+        monkeypatch.setenv("SNN_KEEP_CURRENTS", keep)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            st = net.snn_bptt(snn.SNN_DOUBLE, C, F, budget)
+            assert _identical(first, _gpu_grads(net, len(hidden))), tag
+            seen[tag] = int(st.refwd_current_steps)
+            if budget:
+                assert st.bytes_states + st.bytes_spikes + st.bytes_workspace <= budget
+        finally:
+            net.snn_destroy()
+    monkeypatch.delenv("SNN_KEEP_CURRENTS")
+    assert seen["none"] == T and seen["last"] == T - last and seen["all"] == 0, seen
+    assert seen["one_more"] == T - last - C, seen
+
+
 def test_weight_gradient_kernel_follows_the_rates():
     """Networks with layers wider than 256 start with the dense contraction of the weight gradients and move to the
     tiled event-driven kernel when the previous step's presynaptic activity was below 8 % (configuration 2's widths
