@@ -464,7 +464,15 @@ def main():
         ms["bwd_inter"], ms["up_gemm"] = ms["up_gemm"], 0.0
         if ms["recompute"] < 0.25 * ms["bwd_inter"]:  # only the first chunk's recompute ran on its own
             ms["recompute"] = 0.0
+    fwd_fused_wide = False
     if st.ms_fwd_stage > 0:
+        if big:
+            # wide layers over compressed rows: the dense feed-forward currents for the next stage ride in the launch
+            # of a stage's sequential parts (k_fwd_stage_csr); the few current launches that stay on their own (first
+            # stage, readout) are counted with them
+            fwd_fused_wide = True
+            ms["fwd_stage"] += ms["fwd_seq"] + ms["fwd_currents"]
+            model["fwd_stage"] = ("hbm", model["fwd_seq"][1] + model["fwd_currents"][1])  # own work: both kinds' row bytes
         ms["fwd_seq"] = ms["fwd_currents"] = 0.0
     wide = max(w.n_hidden) > 256
     # compressed rows of masked recurrent matrices: forced by SNN_CSR=1, else the library's policy (matrices of 32 MB and
@@ -478,7 +486,7 @@ def main():
                  # the event-by-event gather k_currents, with k_currents_csr for masked recurrent matrices)
                  "fwd_currents": ("k_currents_dense<4,0>" if np.mean(rates) >= 0.035 else "k_currents") if big else "k_currents_mfma",
                  "recompute": ("k_currents_dense<4,1>" if np.mean(rates) >= 0.035 else "k_currents") if big else "k_currents_mfma",
-                 "scan": "k_scan", "up_gemm": "k_up_gemm<4,4,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage",
+                 "scan": "k_scan", "up_gemm": "k_up_gemm<4,4,2,2>" if gemm_big else ("k_bwd_inter" if L > 2 else "k_up_gemm"), "dw": "k_dw_tile" if dw_tile else "k_dw_mfma", "bwd_stage": "k_bwd_stage", "fwd_stage": "k_fwd_stage_csr" if fwd_fused_wide else "k_fwd_stage",
                  "bwd_inter": "k_bwd_inter",
                  "adjoint": "k_adj_rec_rs" if not wide else ("k_adj_rec_wsm" if max(w.n_hidden) <= 1024 else adj_kernel)}
     peaks = {"hbm": (HBM_PEAK_GBS, "GB/s", 1e9), "alu": (ALU_F32_PEAK_TF, "TFLOP/s", 1e12), "mfma32": (MFMA_F32_PEAK_TF, "TFLOP/s", 1e12)}
@@ -499,7 +507,10 @@ def main():
             if bound == "hbm":
                 kinds[k]["own_bytes_per_launch"] = int(work / launches[k])
         what = None
-        if kernel_of[k].startswith("k_currents_dense") and k in dense_flops:
+        if k == "fwd_stage" and fwd_fused_wide:
+            what, fl = ("dense K=1 fp32 matrix operations of the feed-forward currents, one per presynaptic neuron; the "
+                        "sequential chain over compressed rows runs beside them in the same launch"), dense_flops["fwd_currents"]
+        elif kernel_of[k].startswith("k_currents_dense") and k in dense_flops:
             what, fl = "dense K=1 fp32 matrix operations, one per presynaptic neuron", dense_flops[k]
         elif kernel_of[k] == "k_dw_mfma" and k == "dw":
             what, fl = "fp32 matrix operations over every (t, b) row, spikes as 0/1 operands", dense_flops[k]

@@ -281,6 +281,8 @@ void snn_destroy(snn_ctx *ctx);
  *     SNN_CSR=0|1                      compressed rows of masked recurrent matrices never / wherever a kernel
  *                                      for them exists (default: where the firing-rate policy picks a gather)
  *     SNN_SEQ_SLICES=1|2|4|8           workgroups per batch element in the sequential part of wide layers
+ *     SNN_FWD_FUSE=0                   wide layers over compressed rows: the dense currents for the next pipeline
+ *                                      stage never ride in the launch of a stage's sequential parts
  *     SNN_SEQ_KERNEL=gather|rs         sequential forward part of layers of up to 256 neurons: event-driven gather
  *                                      over the rows of the neurons that fired / the register-stationary chain
  *                                      (default: the chain; the gather was measured slower at every firing rate)

@@ -179,6 +179,8 @@ void read_kernel_hooks(snn_ctx *c) {
   NetDev &n = c->net;
   n.sel_currents = n.sel_adjoint = n.sel_slices = n.sel_csr = n.sel_seq = 0;
   if (const char *e = std::getenv("SNN_SEQ_KERNEL")) n.sel_seq = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "rs") ? 2 : 0;
+  n.no_fwd_fuse = 0;
+  if (const char *e = std::getenv("SNN_FWD_FUSE")) n.no_fwd_fuse = !std::strcmp(e, "0") ? 1 : 0;
   if (const char *e = std::getenv("SNN_CSR")) n.sel_csr = !std::strcmp(e, "0") ? 1 : !std::strcmp(e, "1") ? 2 : 0;
   for (int l = 0; l < n.L; ++l) {
     const bool on = c->csr_sub[l] && n.sel_csr != 1;
@@ -1882,7 +1884,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
     unsigned long long pol = 0;
     for (int l = 0; l < L; ++l) pol = pol * 32 + c->net.cur_pol[0][l] * 8 + c->net.cur_pol[1][l] * 2 + c->net.seq_pol[l];
     pol = pol * 2 + (c->dw_tile ? 1u : 0u);
-    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24 | (unsigned)n.sel_seq << 28;
+    const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24 | (unsigned)n.sel_seq << 28 | (unsigned)n.no_fwd_fuse << 30;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,
                            ring > 0 ? (void *)c->mask_ring[1] : nullptr, ring > 0 ? (void *)c->host_spk : nullptr, (void *)c->mask_full[1], p.n_cache_slots};
     if (!c->graph_exec || !(key == c->graph_key)) {

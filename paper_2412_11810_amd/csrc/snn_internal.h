@@ -54,6 +54,7 @@ struct NetDev {
   // even number of groups.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
+  unsigned char no_fwd_fuse; // 1: the dense currents of wide layers never ride in the launch of the sequential parts
   // Sequential forward part of layers of up to 256 neurons: sel_seq 1 forces the event-driven gather, 2 the
   // register-stationary chain, 0 follows seq_pol[l] (1: gather; set from the measured firing rates).
   unsigned char sel_seq, seq_pol[SNN_MAXL];

@@ -682,16 +682,14 @@ static __device__ __forceinline__ void csr_gather_wave(const uint16_t *list, int
 // 90 % of the synapses do not exist.  Thread (w, lane) then owns the columns 64 k + lane of its wavefront's
 // sub-range for the LIF update, so a ballot is a whole spike word.  Exchange of the spike words between the
 // workgroups of a batch element, polling and time-out exactly as in k_layer_seq_gather_sl.
-__global__ void __launch_bounds__(256)
-k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw,
-                   unsigned *err, unsigned spin_limit) {
-  extern __shared__ __align__(16) unsigned char smem[];
+static __device__ __forceinline__ void layer_seq_csr_sl_body(const NetDev &net, const SeqJobs &jobs, float *__restrict__ state,
+                                                             const StoreSpec &st, int S, uint64_t *xw, unsigned *err,
+                                                             unsigned spin_limit, unsigned char *smem, int bx, int jq) {
   constexpr int NPT = SNN_CSR_SUBW / WAVE, NS = 4 * SNN_CSR_SUBW;
-  const int jq = blockIdx.y;
   const int l = jobs.j[jq].l, t0 = jobs.j[jq].t0, t1 = jobs.j[jq].t1, t_tile = jobs.j[jq].t_tile;
   const float *__restrict__ iin = jobs.j[jq].iin;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, Wd = net.Wd[l + 1];
-  const int b = (int)blockIdx.x / S, sl = (int)blockIdx.x % S;
+  const int b = bx / S, sl = bx % S;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c0 = sl * NS + wave * SNN_CSR_SUBW, w0 = c0 >> 6; // own wavefront's first column and its spike word
   const int nsub1 = N / SNN_CSR_SUBW + 1, r = sl * 4 + wave;
@@ -786,6 +784,13 @@ k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpe
   }
 #pragma unroll
   for (int k = 0; k < NPT; ++k) state[(size_t)b * SN + off + c0 + 64 * k + lane] = v[k];
+}
+
+__global__ void __launch_bounds__(256)
+k_layer_seq_csr_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw,
+                   unsigned *err, unsigned spin_limit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  layer_seq_csr_sl_body(net, jobs, state, st, S, xw, err, spin_limit, smem, (int)blockIdx.x, (int)blockIdx.y);
 }
 
 // A4: u_t = beta u_{t-1} + I_out,t ; usum += u_t over the steps of a tile (fp64 state: ubar feeds a
@@ -1064,19 +1069,18 @@ k_currents_mfma(NetDev net, CurJobs jobs, int ws, int lcap) {
 // matrix and vector pipes busy 69 % + 27 % of the time: one after the other, not side by side.)
 // RC only names the instance: 1 for the launches of a recompute pass (modes 0 and 3), 0 for the forward pass's, so
 // that a kernel trace lists the two, whose shapes and durations differ, separately.
-template <int MB, int RC>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-k_currents_dense(NetDev net, CurJobs jobs, int ws) {
+#define SNN_DENSE_MB_ 4
+#define SNN_DENSE_AP 68 // floats per row of the operand buffer (64 + padding)
+template <int MB, int RC> // RC = 0: jobs of the forward pass (modes 1 and 2: one matrix per job)
+static __device__ __forceinline__ void currents_dense_body(const NetDev &net, const CurJob &ca, int bx,
+                                                           float (*Af)[16 * MB][SNN_DENSE_AP]) {
   static_assert(MB == 4, "the staging step maps 256 threads onto 64 rows x 4 quarters of a word");
-  (void)ws;
-  constexpr int RW = 16 * MB, AP = 68; // rows per workgroup; floats per row of the operand buffer (64 + padding)
-  __shared__ __align__(16) float Af[2][RW][AP];
-  const CurJob &ca = jobs.j[blockIdx.y];
+  constexpr int RW = 16 * MB; // rows per workgroup
   const bool ro = ca.mode == 2;
   const int B = net.B, l = ro ? net.L - 1 : ca.lsel, N = ro ? net.n_out : net.N[l];
   const int rows = ca.nsteps * B, ncg = (N + 255) >> 8, n_rg = (rows + RW - 1) / RW;
-  if ((int)blockIdx.x >= n_rg * ncg) return;
-  const int cg = (int)blockIdx.x % ncg, rg = (int)blockIdx.x / ncg;
+  if (bx >= n_rg * ncg) return;
+  const int cg = bx % ncg, rg = bx / ncg;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int m0 = rg * RW, cb0 = cg * 256 + wave * 64, col = cb0 + lane;
   const bool active = cb0 < N; // a wavefront past the last column only helps to prepare the operands
@@ -1159,11 +1163,11 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
     }
   };
   run_part(0, acc0);
-  if (ca.mode == 0) run_part(1, acc1);
+  if (RC && ca.mode == 0) run_part(1, acc1);
   if (!active) return;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
-    if (ca.mode == 0) {
+    if (RC && ca.mode == 0) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc0[mb][r] = acc0[mb][r] + acc1[mb][r];
     }
@@ -1181,6 +1185,36 @@ k_currents_dense(NetDev net, CurJobs jobs, int ws) {
         if (c < N) dst[c] = acc0[mb][4 * q + rr];
       }
     }
+  }
+}
+
+template <int MB, int RC>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_currents_dense(NetDev net, CurJobs jobs, int ws) {
+  (void)ws;
+  __shared__ __align__(16) float Af[2][16 * MB][SNN_DENSE_AP];
+  currents_dense_body<MB, RC>(net, jobs.j[blockIdx.y], (int)blockIdx.x, Af);
+}
+
+// One stage of the pipelined forward pass of wide layers with compressed recurrent rows in a single launch: the
+// first n_seq workgroups run the sequential parts of the stage's tiles (k_layer_seq_csr_sl: a chain of gathers
+// that leaves the matrix cores idle and most issue slots empty), the others the dense feed-forward currents that
+// the NEXT stage's sequential parts will consume (k_currents_dense; the two are independent).  Three wavefronts
+// per SIMD: two of sequential workgroups -- they come first in the grid, so all of them are resident before any
+// current workgroup, which their exchange of spike words needs -- and one of the current kernel, which keeps the
+// matrix cores as busy with one wavefront per SIMD as with two.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+k_fwd_stage_csr(NetDev net, SeqJobs sj, float *__restrict__ state, StoreSpec st, int S, uint64_t *xw, unsigned *err,
+                unsigned spin_limit, CurJobs cj, int n_seq_x, int cur_gx) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int n_seq = n_seq_x * sj.count;
+  if ((int)blockIdx.x < n_seq) {
+    __builtin_amdgcn_s_setprio(3); // the chain goes first wherever both have an instruction ready
+    layer_seq_csr_sl_body(net, sj, state, st, S, xw, err, spin_limit, smem, (int)blockIdx.x % n_seq_x, (int)blockIdx.x / n_seq_x);
+  } else {
+    const int i = (int)blockIdx.x - n_seq;
+    currents_dense_body<SNN_DENSE_MB_, 0>(net, cj.j[i / cur_gx], i % cur_gx,
+                                          reinterpret_cast<float (*)[16 * SNN_DENSE_MB_][SNN_DENSE_AP]>(smem));
   }
 }
 
@@ -3682,6 +3716,23 @@ static int seq_csr_resident(int device, size_t lds) {
   }
   return cached[device];
 }
+// The fused stage launch (k_fwd_stage_csr): workgroups per compute unit, queried once per device, outside any capture.
+#define SNN_FWD_STAGE_CSR_LDS ((size_t)2 * 16 * SNN_DENSE_MB_ * SNN_DENSE_AP * sizeof(float))
+static int fwd_stage_csr_per_cu(int device, int *n_cu) {
+  static int cached[16] = {}, cus[16] = {};
+  if (device < 0 || device >= 16) return 0;
+  if (!cached[device]) {
+    hipDeviceProp_t prop;
+    int per_cu = 0;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return 0;
+    const size_t a = seq_csr_lds(8192, 128), lds = a > SNN_FWD_STAGE_CSR_LDS ? a : SNN_FWD_STAGE_CSR_LDS;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_fwd_stage_csr, 256, lds) != hipSuccess) return 0;
+    cached[device] = per_cu > 0 ? per_cu : -1;
+    cus[device] = prop.multiProcessorCount;
+  }
+  *n_cu = cus[device];
+  return cached[device] > 0 ? cached[device] : 0;
+}
 static int seq_csr_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, bool need_rows = true) {
   if (!ws || !ws->xg || ga.count < 1 || net.sel_slices == 1) return 0;
   // The walk over compressed rows pays per presynaptic spike and per synapse that exists: it runs where the
@@ -3798,26 +3849,57 @@ hipError_t launch_forward(const NetDev &net, const int *bounds, int n_tiles, flo
         ro_first = false;
       }
     } else {
+      int npt_sl = 0, th_sl = 0;
+      const int S_csr = ga.count ? seq_csr_slices(net, ga, ws) : 0;
+      const int S = (ga.count && !S_csr) ? seq_slices(net, ga, ws, &npt_sl, &th_sl) : 1;
+      // Wide layers over compressed rows: the dense feed-forward currents for the next stage ride in the launch
+      // of this stage's sequential parts (k_fwd_stage_csr) when all sequential workgroups fit beside one current
+      // workgroup per compute unit; other current jobs (readout, matrices that fit the L2) go out on their own.
+      CurJobs cj_fused{};
+      if (S_csr && !net.no_fwd_fuse && currents_use_mfma(net)) {
+        int device = 0, n_cu = 0;
+        if (hipGetDevice(&device) != hipSuccess) return hipErrorInvalidDevice;
+        const int per_cu = fwd_stage_csr_per_cu(device, &n_cu);
+        if (per_cu >= 2 && B * S_csr * ga.count <= (per_cu - 1) * n_cu) {
+          CurJobs rest{};
+          for (int i = 0; i < cj.count; ++i) {
+            const bool dense = cj.j[i].nsteps > 0 && cj.j[i].mode == 1 && currents_job_kernel(net, cj.j[i]) == 1;
+            CurJobs &dst = dense ? cj_fused : rest;
+            dst.j[dst.count++] = cj.j[i];
+          }
+          if (cj_fused.count) cj = rest;
+        }
+      }
       hb(5);
       e = launch_currents(net, cj, s);
       he();
       if (e != hipSuccess) return e;
-      hb(4);
+      hb(cj_fused.count ? 8 : 4);
       if (rs.count) {
         if (nw <= 64) hipLaunchKernelGGL((k_layer_seq_rs<64>), dim3(B, rs.count), dim3(64), 0, s, net, rs, state, st);
         else if (nw <= 128) hipLaunchKernelGGL((k_layer_seq_rs<128>), dim3(B, rs.count), dim3(128), 0, s, net, rs, state, st);
         else hipLaunchKernelGGL((k_layer_seq_rs<256>), dim3(B, rs.count), dim3(256), 0, s, net, rs, state, st);
       }
-      int npt_sl = 0, th_sl = 0;
-      const int S_csr = ga.count ? seq_csr_slices(net, ga, ws) : 0;
-      const int S = (ga.count && !S_csr) ? seq_slices(net, ga, ws, &npt_sl, &th_sl) : 1;
       if (S_csr) {
         // tags of the exchange entries start from zero in every launch
         e = launch_fill_zero(ws->xg, (size_t)ga.count * B * 4 * net.Wd[ga.j[0].l + 1] * sizeof(uint64_t), s);
         if (e != hipSuccess) return e;
         const int Nc = net.N[ga.j[0].l];
-        hipLaunchKernelGGL(k_layer_seq_csr_sl, dim3(B * S_csr, ga.count), dim3(256), seq_csr_lds(Nc, net.Wd[ga.j[0].l + 1]), s,
-                           net, ga, state, st, S_csr, reinterpret_cast<uint64_t *>(ws->xg), ws->err, ws->spin_limit);
+        const size_t lds_seq = seq_csr_lds(Nc, net.Wd[ga.j[0].l + 1]);
+        if (cj_fused.count) {
+          unsigned gx = 0;
+          for (int i = 0; i < cj_fused.count; ++i) {
+            const CurJob &j = cj_fused.j[i];
+            const unsigned g = (unsigned)(((j.nsteps * B + 16 * SNN_DENSE_MB - 1) / (16 * SNN_DENSE_MB)) * ((net.N[j.lsel] + 255) >> 8));
+            gx = g > gx ? g : gx;
+          }
+          const size_t lds = lds_seq > SNN_FWD_STAGE_CSR_LDS ? lds_seq : SNN_FWD_STAGE_CSR_LDS;
+          hipLaunchKernelGGL(k_fwd_stage_csr, dim3(B * S_csr * ga.count + gx * cj_fused.count), dim3(256), lds, s, net, ga, state,
+                             st, S_csr, reinterpret_cast<uint64_t *>(ws->xg), ws->err, ws->spin_limit, cj_fused, B * S_csr, (int)gx);
+        } else {
+          hipLaunchKernelGGL(k_layer_seq_csr_sl, dim3(B * S_csr, ga.count), dim3(256), lds_seq, s,
+                             net, ga, state, st, S_csr, reinterpret_cast<uint64_t *>(ws->xg), ws->err, ws->spin_limit);
+        }
       } else if (ga.count && S > 1) {
         // tags of the exchange entries start from zero in every launch
         e = launch_fill_zero(ws->xg, (size_t)ga.count * B * 4 * net.Wd[ga.j[0].l + 1] * sizeof(uint64_t), s);
@@ -4065,6 +4147,8 @@ void adjoint_prepare(const NetDev &net, const WsArgs &ws) {
       int npt = 0, th = 0;
       (void)seq_slices(net, probe, &ws, &npt, &th);
       (void)seq_csr_slices(net, probe, &ws, false);
+      int device = 0, n_cu = 0;
+      if (hipGetDevice(&device) == hipSuccess) (void)fwd_stage_csr_per_cu(device, &n_cu);
     }
 }
 static hipError_t launch_adj_wide(const NetDev &net, const AdjJob &jb, float *carry, const WsArgs &ws, hipStream_t s) {

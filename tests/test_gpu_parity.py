@@ -230,6 +230,34 @@ def test_forward_pass_keeps_currents_for_double(hidden, B, T, C, F, density, mon
     assert seen["one_more"] == T - last - C, seen
 
 
+def test_forward_stage_of_wide_masked_layers_in_one_launch(monkeypatch):
+    """Wide layers over compressed rows with the dense current kernel: the feed-forward currents for the next pipeline
+    stage ride in the launch of a stage's sequential parts (k_fwd_stage_csr).  Two tiles (64 + 9 steps), two layers:
+    against the oracle (spikes, potentials, gradients), and bit-identical to the separate launches (SNN_FWD_FUSE=0)."""
+    w = synth.Workload("fwdstage_2048x2048", 40, (2048, 2048), 6, T=73, B=3, p_in=0.1, gain=0.6, rec_density=0.1, seed=77)
+    monkeypatch.setenv("SNN_CSR", "1")
+    monkeypatch.setenv("SNN_CURRENTS", "dense")
+    first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 16, 4)], nthreads=8)
+    monkeypatch.setenv("SNN_FWD_FUSE", "0")
+    d = synth.generate(w)
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+        net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+        assert _identical(first, _gpu_grads(net, 2))
+        spikes_sep = [net.snn_get_spikes(l, w.T) for l in range(2)]
+    finally:
+        net.snn_destroy()
+    monkeypatch.delenv("SNN_FWD_FUSE")
+    net = snn.from_workload(w, d)
+    try:
+        net.snn_forward(d["in_spikes"], d["labels"], w.T)
+        for l in range(2):
+            assert np.array_equal(net.snn_get_spikes(l, w.T), spikes_sep[l])
+    finally:
+        net.snn_destroy()
+
+
 def test_weight_gradient_kernel_follows_the_rates():
     """Networks with layers wider than 256 start with the dense contraction of the weight gradients and move to the
     tiled event-driven kernel when the previous step's presynaptic activity was below 8 % (configuration 2's widths
