@@ -205,6 +205,8 @@ def test_forward_pass_keeps_currents_for_double(hidden, B, T, C, F, density, mon
                        rec_density=density, seed=61 + B)
     if density < 1.0:
         monkeypatch.setenv("SNN_CSR", "1")
+    if len(hidden) == 1:  # checkpoints through the copy engine (states this small go out by direct stores otherwise)
+        monkeypatch.setenv("SNN_HOST_TIER", "dma")
     first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, C, F)], nthreads=8, check_states=False)
     d = synth.generate(w)
     cfg = snn.make_config(w.n_in, list(w.n_hidden), w.n_out, w.T, w.B)
