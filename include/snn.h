@@ -270,14 +270,15 @@ void snn_destroy(snn_ctx *ctx);
  *     SNN_WS_SPIN_LIMIT=n        polls before a chip-wide kernel gives up waiting (0: at once; the error path)
  *   read at the start of every call that launches kernels:
  *     SNN_CURRENTS=gather|mfma|dense   kernel of the synaptic currents
- *     SNN_WS_KERNEL=valu|stream|rows|rows_all|chip|csrw|single|pair
+ *     SNN_WS_KERNEL=valu|stream|rows|rows_all|chip|csrw|single|pair|rows64
  *                                      VALU version of the chip-wide adjoint recurrence / one workgroup per batch
  *                                      element streaming the transposed matrix / the event-driven rows kernel of
  *                                      the surrogate window at any width above 256 / the same kernel evaluating
  *                                      every row / the chip-wide kernels over the dense-stored matrix, also under a
  *                                      surrogate window / the chip-wide kernel over compressed rows also under one /
  *                                      the matrix-core version with one batch group per workgroup, never two /
- *                                      with two wherever the batch has an even number of groups of 16
+ *                                      with two wherever the batch has an even number of groups of 16 /
+ *                                      with workgroups of 64 rows (eight wavefronts) and one batch group
  *     SNN_CSR=0|1                      compressed rows of masked recurrent matrices never / wherever a kernel
  *                                      for them exists (default: where the firing-rate policy picks a gather)
  *     SNN_SEQ_SLICES=1|2|4|8           workgroups per batch element in the sequential part of wide layers

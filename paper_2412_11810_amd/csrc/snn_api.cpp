@@ -192,7 +192,7 @@ void read_kernel_hooks(snn_ctx *c) {
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
   if (const char *e = std::getenv("SNN_WS_KERNEL"))
     n.sel_adjoint = !std::strcmp(e, "valu") ? 1 : !std::strcmp(e, "stream") ? 2 : !std::strcmp(e, "rows") ? 3 :
-                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : !std::strcmp(e, "single") ? 7 : !std::strcmp(e, "pair") ? 8 : 0;
+                    !std::strcmp(e, "rows_all") ? 4 : !std::strcmp(e, "chip") ? 5 : !std::strcmp(e, "csrw") ? 6 : !std::strcmp(e, "single") ? 7 : !std::strcmp(e, "pair") ? 8 : !std::strcmp(e, "rows64") ? 9 : 0;
   if (const char *e = std::getenv("SNN_SEQ_SLICES")) {
     const int v = std::atoi(e);
     n.sel_slices = (v == 1 || v == 2 || v == 4 || v == 8) ? (unsigned char)v : 0;

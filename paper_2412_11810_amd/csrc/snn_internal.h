@@ -51,7 +51,7 @@ struct NetDev {
   // chip-wide kernels over the dense-stored matrix, also under a surrogate window, 6 the chip-wide kernel over
   // compressed rows also under a surrogate window, 7 the matrix-core version of the chip-wide recurrence with one
   // batch group per workgroup (never two half a step apart), 8 the same with two groups wherever the batch has an
-  // even number of groups.
+  // even number of groups, 9 the same with workgroups of 64 rows and one group.
   // sel_slices: workgroups per batch element in the sequential part of wide layers (1, 2, 4 or 8).
   unsigned char sel_currents, sel_adjoint, sel_slices;
   unsigned char no_fwd_fuse; // 1: the dense currents of wide layers never ride in the launch of the sequential parts

@@ -1834,8 +1834,11 @@ k_adj_rec_ws(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, uns
 // the values one group has just stored travel through the exchange buffer, the matrix cores work on the other
 // group, and the two round trips of a step no longer add to its products.  Half as many workgroups per layer also
 // lets more layers of a pipeline stage share a launch.  The operations per element are those of NG = 1.
-template <int NK, int NG> // K-steps per wavefront and row block (the padded width is 16 * NK); batch groups per workgroup
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) // the weights must stay in registers
+// With RH = 2 a workgroup has eight wavefronts and owns 64 rows (wavefront w: rows 32 (w / 4) .., quarter w % 4 of
+// the reduction range; two wavefronts per SIMD, 256 registers each): half as many workgroups read a batch group's
+// dv_t from the exchange buffer, which is what a step costs.
+template <int NK, int NG, int RH> // K-steps per wavefront and row block (padded width 16 NK); batch groups and 32-row halves per workgroup
+__global__ void __launch_bounds__(256 * RH) __attribute__((amdgpu_waves_per_eu(RH, RH))) // the weights must stay in registers
 k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, unsigned *bar, unsigned *err, int G_w,
               unsigned spin_limit, int blocks_per_job, int xg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1849,19 +1852,20 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
   uint64_t *xq = reinterpret_cast<uint64_t *>(xg + (size_t)jq * xg_stride); // [2][B][N]
   (void)bar;
   const int N = net.N[l], off = net.off[l], B = net.B, SN = net.SN, O = net.n_out, ldu = N;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, li = lane & 15, lk = lane >> 4;
-  const int bg = vb % G_w, js = vb / G_w; // G_w workgroups of NG batch groups each per 32 rows
-  const int j0 = js * 32;
+  constexpr int NT = 256 * RH;
+  const int tid = threadIdx.x, lane = tid & 63, wv = (tid >> 6) & 3, rh = tid >> 8, li = lane & 15, lk = lane >> 4;
+  const int bg = vb % G_w, js = vb / G_w; // G_w workgroups of NG batch groups each per 32 RH rows
+  const int j0 = js * 32 * RH, jw = j0 + 32 * rh; // first row of the workgroup, of the wavefront
   constexpr int NP = 16 * NK;                          // padded reduction length (>= N)
   float *xs_all = (float *)smem;                       // [NG][NP][16]  dv_{t+1}, batch-minor
-  float *part_all = xs_all + (size_t)NG * NP * 16;     // [NG][4][32][16]
+  float *part_all = xs_all + (size_t)NG * NP * 16;     // [NG][RH][4][32][16]
 
   // A operands: a[rb][s] = W_rec[j0 + 16 rb + li][4 NK wv + 4 s + lk].  Every load unconditional, from a clamped
   // address, zeroed with an integer mask afterwards (a select lets the compiler put each load under its condition).
   float a[2][NK];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int j = j0 + 16 * rb + li, jc = j < N ? j : N - 1;
+    const int j = jw + 16 * rb + li, jc = j < N ? j : N - 1;
 #pragma unroll
     for (int q = 0; q < NK; ++q) {
       const int n = 4 * NK * wv + 4 * q + lk, nc = n < N ? n : N - 1;
@@ -1875,25 +1879,25 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
 #pragma unroll
   for (int g = 0; g < NG; ++g) {
     const int b0 = (bg * NG + g) * 16;
-    float cv[NK];
+    float cv[NK / RH];
 #pragma unroll
-    for (int r = 0; r < NK; ++r) {
-      const int i = tid + 256 * r, n = i >> 4, bb = i & 15;
+    for (int r = 0; r < NK / RH; ++r) {
+      const int i = tid + NT * r, n = i >> 4, bb = i & 15;
       cv[r] = carry[(size_t)(b0 + bb < B ? b0 + bb : B - 1) * (SN + O) + off + (n < N ? n : N - 1)];
     }
 #pragma unroll
-    for (int r = 0; r < NK; ++r) {
-      const int i = tid + 256 * r, n = i >> 4, bb = i & 15;
+    for (int r = 0; r < NK / RH; ++r) {
+      const int i = tid + NT * r, n = i >> 4, bb = i & 15;
       xs_all[(size_t)g * NP * 16 + i] =
           __uint_as_float(__float_as_uint(cv[r]) & (0u - (uint32_t)(!carry_init && n < N && b0 + bb < B)));
     }
   }
   __syncthreads();
-  // finalising role: 32 x 16 (row, batch element) pairs per group, two per thread
+  // finalising role: 32 RH x 16 (row, batch element) pairs per group, two per thread
   int fj[2], fbb[2];
 #pragma unroll
   for (int e = 0; e < 2; ++e) {
-    const int pidx = tid + 256 * e;
+    const int pidx = tid + NT * e;
     fj[e] = j0 + (pidx >> 4);
     fbb[e] = pidx & 15;
   }
@@ -1902,7 +1906,7 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
   // one step of one batch group: products, the sum of the four partial results, the recurrence, the exchange stores
   auto compute = [&](int g, unsigned step, int t) {
     const int b0 = (bg * NG + g) * 16;
-    float *xs = xs_all + (size_t)g * NP * 16, *part = part_all + (size_t)g * 4 * 32 * 16;
+    float *xs = xs_all + (size_t)g * NP * 16, *part = part_all + (size_t)g * RH * 4 * 32 * 16;
     const size_t slot = (size_t)(t - t_base - 1);
     float vt[2] = {0.0f, 0.0f}, upv[2] = {0.0f, 0.0f};
 #pragma unroll
@@ -1922,18 +1926,18 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
     // D[4 lk + r][li]: row 4 lk + r of the block, batch element li
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      part[((size_t)wv * 32 + 4 * lk + r) * 16 + li] = acc0[r];
-      part[((size_t)wv * 32 + 16 + 4 * lk + r) * 16 + li] = acc1[r];
+      part[((size_t)(4 * rh + wv) * 32 + 4 * lk + r) * 16 + li] = acc0[r];
+      part[((size_t)(4 * rh + wv) * 32 + 16 + 4 * lk + r) * 16 + li] = acc1[r];
     }
     __syncthreads();
     const int par = step & 1;
 #pragma unroll
     for (int e = 0; e < 2; ++e)
       if (fj[e] < N && b0 + fbb[e] < B) {
-        const int fr = fj[e] - j0, fb = b0 + fbb[e];
-        float sacc = part[((size_t)0 * 32 + fr) * 16 + fbb[e]];
+        const int fr = (fj[e] - j0) & 31, fh = (fj[e] - j0) >> 5, fb = b0 + fbb[e];
+        float sacc = part[((size_t)(4 * fh) * 32 + fr) * 16 + fbb[e]];
 #pragma unroll
-        for (int k = 1; k < 4; ++k) sacc = sacc + part[((size_t)k * 32 + fr) * 16 + fbb[e]];
+        for (int k = 1; k < 4; ++k) sacc = sacc + part[((size_t)(4 * fh + k) * 32 + fr) * 16 + fbb[e]];
         const float dn = xs[(size_t)fj[e] * 16 + fbb[e]];
         const float ds = (sacc + upv[e]) - net.theta * dn;
         const float dvt = fmaf(ds, surrogate(net, vt[e]), net.alpha * dn);
@@ -1949,28 +1953,30 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
   auto poll = [&](int g, unsigned step) {
     const int b0 = (bg * NG + g) * 16, par = step & 1;
     float *xs = xs_all + (size_t)g * NP * 16;
-    // thread -> batch element tid/16, columns (tid%16) + 16*i: all loads of a round issued before the first use.
-    // One base address for all of them, the column in the constant offset: entries past the layer's width read
-    // whatever follows (the buffer has 16 KB of slack behind its last row) and are neither waited for nor used.
-    const int bb = tid >> 4, nb = tid & 15;
+    // thread -> batch element tid / (16 RH), columns tid % (16 RH) + 16 RH i: all loads of a round issued before
+    // the first use.  One base address for all of them, the column in the constant offset: entries past the layer's
+    // width read whatever follows (the buffer has 16 KB of slack behind its last row) and are neither waited for
+    // nor used.
+    constexpr int NB = 16 * RH, NE = NK / RH; // lanes along the row, entries per thread
+    const int bb = tid / NB, nb = tid % NB;
     const uint64_t *src = xq + ((size_t)par * B + (b0 + bb < B ? b0 + bb : B - 1)) * N + nb;
     const uint32_t want = step + 1u;
     if (spin_limit == 0u && !dead) { // only ever set by a test of this path: give up at once, arrived or not
       __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       dead = true;
     }
-    constexpr int CH = NK < 32 ? NK : 32; // values polled at a time: a round that comes too early is read again
+    constexpr int CH = RH == 2 ? NE / 2 : (NE < 32 ? NE : 32); // values polled at a time: a round that comes too early is read again
 #pragma unroll
-    for (int c = 0; c < NK; c += CH) {
+    for (int c = 0; c < NE; c += CH) {
       uint64_t r[CH];
       unsigned spins = 0;
       for (;;) {
         uint32_t bad = 0;
 #pragma unroll
         for (int i = 0; i < CH; ++i) // agent-scope loads: never served from this compute unit's L1
-          r[i] = __hip_atomic_load(&src[16 * (c + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          r[i] = __hip_atomic_load(&src[NB * (c + i)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int i = 0; i < CH; ++i) bad |= ((uint32_t)(r[i] >> 32) ^ want) & (0u - (uint32_t)(nb + 16 * (c + i) < N));
+        for (int i = 0; i < CH; ++i) bad |= ((uint32_t)(r[i] >> 32) ^ want) & (0u - (uint32_t)(nb + NB * (c + i) < N));
         if (bad == 0u || dead) break;
         if (++spins > spin_limit / 8u ||
             ((spins & 15u) == 0u && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
@@ -1982,7 +1988,7 @@ k_adj_rec_wsm(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, un
       }
 #pragma unroll
       for (int i = 0; i < CH; ++i) {
-        const int n = nb + 16 * (c + i);
+        const int n = nb + NB * (c + i);
         xs[(size_t)n * 16 + bb] = __uint_as_float((uint32_t)r[i] & (0u - (uint32_t)(n < N && b0 + bb < B)));
       }
     }
@@ -4207,23 +4213,26 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       continue;
     }
     if (N <= 1024 && ws.xg && ws_use_mfma(net) && (B + 15) / 16 <= 64 && ((N + 31) / 32) * ((B + 15) / 16) <= ws.max_groups_m) {
-      // matrix-core version: workgroup = 32 rows x 16 batch elements, or x 2 groups of 16 half a step apart.  Two
+      // matrix-core version: workgroup = 32 rows x 16 batch elements, or x 2 groups of 16 half a step apart (two
       // groups per workgroup double the products a workgroup runs one after the other per step and halve the
-      // workgroups per layer: taken where that at least halves the launches the stage's layers of this width need
-      // (configuration 2: three layers in one launch instead of two launches) and the batch has an even number of
-      // groups (net.sel_adjoint == 7 keeps one group per workgroup, 8 takes two wherever the batch allows)
+      // workgroups per layer; only where net.sel_adjoint == 8 asks and the batch has an even number of groups;
+      // 7 keeps 32 rows and one group per workgroup).
       const int G_b = (B + 15) / 16;
-      int NG = (G_b % 2 == 0 && net.sel_adjoint == 8) ? 2 : 1;
-      if (G_b % 2 == 0 && net.sel_adjoint != 7 && net.sel_adjoint != 8) {
-        int cnt = 0;
-        for (int k = i; k < jobs.count; ++k)
-          if (!taken[k] && net.N[jobs.j[k].l] == N) ++cnt;
-        const int per1 = ((N + 31) / 32) * G_b, cap1 = ws.max_groups_m / per1, cap2 = ws.max_groups_m / (per1 / 2);
-        if (cap1 >= 1 && 2 * ((cnt + cap2 - 1) / cap2) <= (cnt + cap1 - 1) / cap1) NG = 2;
-      }
-      const int G_w = G_b / NG, n_slices = (N + 31) / 32, bpj = n_slices * G_w;
+      // Workgroups of eight wavefronts and 64 rows (RH = 2) halve the workgroups per layer as well, and with them
+      // the reads of the exchange buffer, at one batch group per workgroup: measured faster than two groups where
+      // the stage's layers do not fit one launch otherwise (configuration 2: 147 against 171 ms per step), slower
+      // where they do (configuration 3: 36 against 28 ms: few workgroups, each with twice the products per step).
+      // net.sel_adjoint == 9 forces them.
+      int cnt = 0;
+      for (int k = i; k < jobs.count; ++k)
+        if (!taken[k] && net.N[jobs.j[k].l] == N) ++cnt;
+      const int per1 = ((N + 31) / 32) * G_b, cap1 = ws.max_groups_m / per1;
+      const bool plain = net.sel_adjoint == 7 || net.sel_adjoint == 8;
+      const int RH = (net.sel_adjoint == 9 || (!plain && cap1 >= 1 && cnt > cap1)) ? 2 : 1;
+      const int NG = (G_b % 2 == 0 && net.sel_adjoint == 8) ? 2 : 1;
+      const int G_w = G_b / NG, n_slices = (N + 32 * RH - 1) / (32 * RH), bpj = n_slices * G_w;
       const int NK = N <= 512 ? 32 : 64;
-      const size_t lds = (size_t)NG * ((size_t)16 * NK * 16 + 4 * 32 * 16) * sizeof(float);
+      const size_t lds = (size_t)NG * ((size_t)16 * NK * 16 + RH * 4 * 32 * 16) * sizeof(float);
       AdjJobs grp{};
       for (int k = i; k < jobs.count; ++k)
         if (!taken[k] && net.N[jobs.j[k].l] == N && (grp.count + 1) * bpj <= ws.max_groups_m) {
@@ -4233,25 +4242,23 @@ hipError_t launch_adjoint_jobs(const NetDev &net, const AdjJobs &jobs, float *ca
       // tags of the exchange entries start from zero in every launch
       hipError_t e = launch_fill_zero(ws.xg, (size_t)grp.count * ws.xg_stride * sizeof(float), s);
       if (e != hipSuccess) return e;
-      const void *fn = NK == 32 ? (NG == 2 ? reinterpret_cast<const void *>(k_adj_rec_wsm<32, 2>)
-                                           : reinterpret_cast<const void *>(k_adj_rec_wsm<32, 1>))
-                                : (NG == 2 ? reinterpret_cast<const void *>(k_adj_rec_wsm<64, 2>)
-                                           : reinterpret_cast<const void *>(k_adj_rec_wsm<64, 1>));
-      e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      const dim3 grid(bpj * grp.count), block(256);
-      if (NK == 32 && NG == 1)
-        hipLaunchKernelGGL((k_adj_rec_wsm<32, 1>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
-                           ws.spin_limit, bpj, ws.xg_stride);
-      else if (NK == 32)
-        hipLaunchKernelGGL((k_adj_rec_wsm<32, 2>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
-                           ws.spin_limit, bpj, ws.xg_stride);
-      else if (NG == 1)
-        hipLaunchKernelGGL((k_adj_rec_wsm<64, 1>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
-                           ws.spin_limit, bpj, ws.xg_stride);
-      else
-        hipLaunchKernelGGL((k_adj_rec_wsm<64, 2>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err, G_w,
-                           ws.spin_limit, bpj, ws.xg_stride);
+      const dim3 grid(bpj * grp.count), block(256 * RH);
+#define WSM_CASE(NK_, NG_, RH_)                                                                                         \
+  {                                                                                                                     \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<NK_, NG_, RH_>),                               \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                                      \
+    if (e != hipSuccess) return e;                                                                                      \
+    hipLaunchKernelGGL((k_adj_rec_wsm<NK_, NG_, RH_>), grid, block, lds, s, net, grp, carry, ws.xg, ws.bar, ws.err,     \
+                       G_w, ws.spin_limit, bpj, ws.xg_stride);                                                          \
+  }
+      if (RH == 2) {
+        if (NK == 32) WSM_CASE(32, 1, 2) else WSM_CASE(64, 1, 2)
+      } else if (NK == 32) {
+        if (NG == 1) WSM_CASE(32, 1, 1) else WSM_CASE(32, 2, 1)
+      } else {
+        if (NG == 1) WSM_CASE(64, 1, 1) else WSM_CASE(64, 2, 1)
+      }
+#undef WSM_CASE
     } else if (N <= 1024 && ws.xg && (B + 7) / 8 <= 64 && ((N + 31) / 32) * ((B + 7) / 8) <= ws.max_groups) {
       const int G_b = (B + 7) / 8, n_slices = (N + 31) / 32, bpj = n_slices * G_b;
       const int NR = N <= 512 ? 64 : 128;
@@ -4321,10 +4328,10 @@ int ws_max_resident_groups_mfma(int device) {
   int per_cu = 0;
   // the version with two batch groups per workgroup has the larger LDS footprint and bounds both
   const size_t lds = (size_t)2 * ((size_t)16 * 64 * 16 + 4 * 32 * 16) * sizeof(float);
-  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<64, 2>), hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute(reinterpret_cast<const void *>(k_adj_rec_wsm<64, 2, 1>), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds) != hipSuccess)
     return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wsm<64, 2>, 256, lds) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_adj_rec_wsm<64, 2, 1>, 256, lds) != hipSuccess) return 0;
   return per_cu * prop.multiProcessorCount;
 }
 

@@ -278,25 +278,27 @@ def test_weight_gradient_kernel_follows_the_rates():
 def test_chip_wide_adjoint_two_batch_groups_per_workgroup(hidden, B, T, monkeypatch):
     """Layers of 257..1024 neurons with an even number of 16-element batch groups: a workgroup of the chip-wide
     adjoint recurrence can serve two groups half a step apart with the same registers of W_rec (the library does so
-    where that halves the launches; SNN_WS_KERNEL=pair: wherever the batch allows).  A ragged second group, widths
-    below the padded reduction length, three layers in one launch: against the oracle, and bit-identical to the same
-    kernel with one group per workgroup (SNN_WS_KERNEL=single)."""
+    only when asked, SNN_WS_KERNEL=pair), or own 64 rows with eight wavefronts (where the stage's layers would not
+    fit one launch otherwise, or SNN_WS_KERNEL=rows64).  A ragged second group, widths below the padded reduction
+    length, a ragged last row block, three layers in one launch: against the oracle, and bit-identical to the kernel
+    with 32 rows and one group per workgroup (SNN_WS_KERNEL=single)."""
     w = synth.Workload("ws2_" + "x".join(map(str, hidden)), 40, hidden, 6, T=T, B=B, p_in=0.1, gain=0.6, seed=41 + B)
     monkeypatch.setenv("SNN_WS_KERNEL", "pair")
     first, _ = _full_parity(w, [(snn.SNN_STANDARD, 0, 0), (snn.SNN_DOUBLE, 6, 3)], nthreads=8, check_states=False)
-    monkeypatch.setenv("SNN_WS_KERNEL", "single")
     d = synth.generate(w)
-    net = snn.from_workload(w, d)
-    try:
-        net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
-        net.snn_bptt(snn.SNN_STANDARD, 0, 0)
-        other = _gpu_grads(net, len(hidden))
-    finally:
-        net.snn_destroy()
-    monkeypatch.delenv("SNN_WS_KERNEL")
     flat = lambda g: list(g[0]) + list(g[1]) + [g[2]]
-    for a, b in zip(flat(first), flat(other)):
-        assert np.array_equal(a, b)
+    for mode in ("single", "rows64"):  # one group and 32 rows per workgroup; 64 rows (eight wavefronts)
+        monkeypatch.setenv("SNN_WS_KERNEL", mode)
+        net = snn.from_workload(w, d)
+        try:
+            net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
+            net.snn_bptt(snn.SNN_STANDARD, 0, 0)
+            other = _gpu_grads(net, len(hidden))
+        finally:
+            net.snn_destroy()
+        for a, b in zip(flat(first), flat(other)):
+            assert np.array_equal(a, b), mode
+    monkeypatch.delenv("SNN_WS_KERNEL")
 
 
 @pytest.mark.parametrize("hidden,B,T", [((1088,), 5, 14), ((1152, 1088), 20, 10), ((1088,), 40, 8), ((4096,), 3, 9)])
