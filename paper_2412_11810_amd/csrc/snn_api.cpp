@@ -187,6 +187,7 @@ void read_kernel_hooks(snn_ctx *c) {
     n.csr_sub[l] = on ? c->csr_sub[l] : nullptr;
     n.csr_col[l] = on ? c->csr_col[l] : nullptr;
     n.csr_val[l] = on ? c->csr_val[l] : nullptr;
+    n.csr_nnz[l] = on ? (uint32_t)c->csr_nnz[l] : 0u;
   }
   if (const char *e = std::getenv("SNN_CURRENTS"))
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;

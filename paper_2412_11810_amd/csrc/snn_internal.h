@@ -37,6 +37,7 @@ struct NetDev {
   const uint32_t *csr_sub[SNN_MAXL];
   const uint16_t *csr_col[SNN_MAXL];
   const float *csr_val[SNN_MAXL];
+  uint32_t csr_nnz[SNN_MAXL]; // synapses that exist (csr_col and csr_val hold one entry more)
   float alpha, beta, theta, k;
   float win;  // surrogate window (<= 0: none)
   // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step

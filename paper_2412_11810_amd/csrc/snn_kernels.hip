@@ -592,57 +592,72 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
 // ------------------------------------------------------------------------------------------
 template <int U>
 struct CsrGroup { // the entries of U consecutive rows that fall into the wavefront's sub-range, one entry per lane
-  uint32_t p[U], n[U], c[U];
+  uint32_t n[U], c[U];
   float v[U];
 };
-template <int U>
-static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn,
-                                                 const uint16_t *__restrict__ col, const float *__restrict__ val, int lane) {
-#pragma unroll
-  for (int u = 0; u < U; ++u) { // rows past the block carry no entries
-    const bool in = q + u < WAVE;
-    g.p[u] = __builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
-    g.n[u] = in ? __builtin_amdgcn_readlane(nn, (q + u) & (WAVE - 1)) : 0u;
-  }
-  // every load unconditional, through a buffer descriptor whose range is the row's entries in this sub-range (lanes
-  // past the end read 0): straight-line code, so the loads of a whole group -- and of the next one -- stay in flight
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const __amdgpu_buffer_rsrc_t rc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(col + g.p[u]), 0, (int)(g.n[u] * sizeof(uint16_t)), 0x00027000);
-    const __amdgpu_buffer_rsrc_t rv =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(val + g.p[u]), 0, (int)(g.n[u] * sizeof(float)), 0x00027000);
-    g.c[u] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (uint32_t)lane * 2u, 0, 0);
-    g.v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)lane * 4u, 0, 0));
-  }
+// The two arrays of a layer's compressed rows as buffer descriptors over the whole arrays (nnz + 1 entries each): one
+// pair per wavefront and call, so a row costs no scalar descriptor arithmetic (the compute unit's one scalar unit is
+// what eight gathering wavefronts would otherwise queue for); a lane past the end of the arrays reads 0.
+struct CsrRes { __amdgpu_buffer_rsrc_t c, v; };
+static __device__ __forceinline__ CsrRes csr_res(const uint16_t *col, const float *val, uint32_t nnz) {
+  CsrRes r;
+  r.c = __builtin_amdgcn_make_buffer_rsrc((void *)col, 0, (int)((nnz + 1u) * sizeof(uint16_t)), 0x00027000);
+  r.v = __builtin_amdgcn_make_buffer_rsrc((void *)val, 0, (int)((nnz + 1u) * sizeof(float)), 0x00027000);
+  return r;
 }
 template <int U>
-static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, uint32_t c_base, const uint16_t *__restrict__ col,
-                                                   const float *__restrict__ val, float *acc_w, int lane) {
-  // Read, add, write back with ordinary LDS instructions: the entries of a row have distinct columns, only this
-  // wavefront touches acc_w, and its LDS instructions execute in program order, so the next row's read sees this
-  // row's write.  (LDS float atomics give the same bits but the counters show the wavefronts waiting two thirds of
-  // their cycles for them.)
+static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn, const CsrRes &res,
+                                                 uint32_t lane2, uint32_t lane4) {
+  // every load unconditional: lane k takes entry k of the row's part of this sub-range; lanes past the part's end
+  // fetch the entries that follow in memory (discarded by csr_consume).  Straight-line code, so the loads of a whole
+  // group -- and of the next one -- stay in flight.  q is a constant after unrolling: the positions come out of
+  // p0 / nn with constant lane numbers.
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    if ((uint32_t)lane < g.n[u]) {
-      float *a = &acc_w[g.c[u] - c_base];
-      *a = *a + g.v[u];
+    const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
+    g.n[u] = (uint32_t)__builtin_amdgcn_readlane(nn, (q + u) & (WAVE - 1));
+    g.c[u] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(res.c, (p << 1) + lane2, 0, 0);
+    g.v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(res.v, (p << 2) + lane4, 0, 0));
+  }
+}
+typedef __attribute__((address_space(3))) float lds_float;
+// OVER: some row of the block has more than 64 entries in this sub-range (decided once per block of 64 rows).
+// accb: LDS byte address of the accumulator of column 0 (the wavefront's first accumulator minus 4 c_base);
+// spareb: LDS byte address of this lane's spare word.
+template <int U, bool OVER>
+static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, int q, uint32_t p0, uint32_t accb, uint32_t spareb,
+                                                   const uint16_t *__restrict__ col, const float *__restrict__ val, int lane) {
+  // Read, add, write back with ordinary LDS instructions: the entries of a row have distinct columns, only this
+  // wavefront touches its accumulators, and its LDS instructions execute in program order, so the next row's read
+  // sees this row's write.  (LDS float atomics give the same bits but the counters show the wavefronts waiting two
+  // thirds of their cycles for them.)  A lane without an entry adds zero to a spare word of its own instead of
+  // being masked out: no change of the execution mask, hence no scalar instruction, per row.
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const bool on = (uint32_t)lane < g.n[u];
+    lds_float *a = (lds_float *)(uintptr_t)(on ? (g.c[u] << 2) + accb : spareb);
+    *a = *a + (on ? g.v[u] : 0.0f);
+    if (OVER) {
+      const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
+      for (uint32_t o = WAVE; o < g.n[u]; o += WAVE) // a row with more than 64 entries in this range: finish it first
+        if (o + lane < g.n[u]) {
+          lds_float *x = (lds_float *)(uintptr_t)(((uint32_t)col[p + o + lane] << 2) + accb);
+          *x = *x + val[p + o + lane];
+        }
     }
-    for (uint32_t o = WAVE; o < g.n[u]; o += WAVE) // a row with more than 64 entries in this range: finish it first
-      if (o + lane < g.n[u]) {
-        float *a = &acc_w[col[g.p[u] + o + lane] - c_base];
-        *a = *a + val[g.p[u] + o + lane];
-      }
   }
 }
 // The positions of 64 rows are fetched at once (one row per lane), one block of 64 rows ahead; the entries of two
-// groups of U rows are in flight while a third is added.
+// groups of U rows are in flight while a third is added.  spare: 64 floats of LDS of this wavefront's own.
 static __device__ __forceinline__ void csr_gather_wave(const uint16_t *list, int cnt, const uint32_t *__restrict__ sub,
                                                        int nsub1, int r, const uint16_t *__restrict__ col,
-                                                       const float *__restrict__ val, float *acc_w, int lane) {
+                                                       const float *__restrict__ val, uint32_t nnz, float *acc_w,
+                                                       float *spare, int lane) {
   constexpr int U = 16;
-  const uint32_t c_base = (uint32_t)r * SNN_CSR_SUBW;
+  const CsrRes res = csr_res(col, val, nnz);
+  const uint32_t accb = (uint32_t)(uintptr_t)(lds_float *)acc_w - (uint32_t)r * SNN_CSR_SUBW * 4u;
+  const uint32_t spareb = (uint32_t)(uintptr_t)(lds_float *)(spare + lane);
+  const uint32_t lane2 = (uint32_t)lane * 2u, lane4 = (uint32_t)lane * 4u;
   auto meta = [&](int base, uint32_t &p0, uint32_t &nn) {
     const int i = base + lane;
     p0 = 0u;
@@ -653,23 +668,30 @@ static __device__ __forceinline__ void csr_gather_wave(const uint16_t *list, int
       nn = sp[1] - p0;
     }
   };
+  auto block = [&](auto over, int nr, uint32_t p0, uint32_t nn) {
+    constexpr bool OVER = decltype(over)::value;
+    CsrGroup<U> ga, gb;
+    csr_issue<U>(ga, 0, p0, nn, res, lane2, lane4);
+#pragma unroll
+    for (int q = 0; q < WAVE; q += 2 * U) {
+      if (q >= nr) break;
+      __builtin_amdgcn_sched_barrier(0); // keep the loads of the next group ahead of the adds of this one
+      csr_issue<U>(gb, q + U, p0, nn, res, lane2, lane4);
+      __builtin_amdgcn_sched_barrier(0);
+      csr_consume<U, OVER>(ga, q, p0, accb, spareb, col, val, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (q + 2 * U < WAVE) csr_issue<U>(ga, q + 2 * U, p0, nn, res, lane2, lane4); // (rows past nr carry no entries)
+      __builtin_amdgcn_sched_barrier(0);
+      csr_consume<U, OVER>(gb, q + U, p0, accb, spareb, col, val, lane);
+    }
+  };
   uint32_t p0, nn, p0n, nnn;
   meta(0, p0, nn);
   for (int base = 0; base < cnt; base += WAVE) {
     meta(base + WAVE, p0n, nnn);
     const int nr = cnt - base < WAVE ? cnt - base : WAVE;
-    CsrGroup<U> ga, gb;
-    csr_issue<U>(ga, 0, p0, nn, col, val, lane);
-    for (int q = 0; q < nr; q += 2 * U) {
-      __builtin_amdgcn_sched_barrier(0); // keep the loads of the next group ahead of the adds of this one
-      csr_issue<U>(gb, q + U, p0, nn, col, val, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      csr_consume<U>(ga, c_base, col, val, acc_w, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      csr_issue<U>(ga, q + 2 * U, p0, nn, col, val, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      csr_consume<U>(gb, c_base, col, val, acc_w, lane);
-    }
+    if (__ballot(nn > (uint32_t)WAVE) != 0ull) block(std::true_type{}, nr, p0, nn);
+    else block(std::false_type{}, nr, p0, nn);
     p0 = p0n;
     nn = nnn;
   }
@@ -696,7 +718,8 @@ static __device__ __forceinline__ void layer_seq_csr_sl_body(const NetDev &net, 
   uint64_t *words = (uint64_t *)smem;                    // [Wd]  whole layer
   int *cnt = (int *)(words + Wd);                        // [1] (+3 pad)
   float *acc = (float *)(cnt + 4);                       // [4][SNN_CSR_SUBW]
-  uint16_t *list = (uint16_t *)(acc + NS);               // [N] indices of the active rows, ascending
+  uint16_t *list = (uint16_t *)(acc + NS);               // [N rounded up to 8] indices of the active rows, ascending
+  float *spare = (float *)(list + ((N + 7) & ~7)) + 64 * wave; // [4][64] where lanes without an entry add
   float *acc_w = acc + wave * SNN_CSR_SUBW;
   uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
   const size_t mstride = (size_t)B * Wd;
@@ -732,7 +755,7 @@ static __device__ __forceinline__ void layer_seq_csr_sl_body(const NetDev &net, 
       in_t[k] = irow[64 * k + lane];
       acc_w[64 * k + lane] = 0.0f;
     }
-    csr_gather_wave(list, *cnt, sub, nsub1, r, col, val, acc_w, lane);
+    csr_gather_wave(list, *cnt, sub, nsub1, r, col, val, net.csr_nnz[l], acc_w, spare, lane);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup"); // the adds of this wavefront have landed before it reads the sums
     uint64_t *xdst = xb + (size_t)(step & 1u) * 2 * Wd;
     const uint64_t tag = (uint64_t)(step + 1u) << 32;
@@ -1234,6 +1257,7 @@ __global__ void __launch_bounds__(256) k_currents_csr(NetDev net, CurJobs jobs) 
   int *cnt = (int *)(words + Wd);                     // [1] (+3 pad)
   float *acc = (float *)(cnt + 4);                    // [4][SNN_CSR_SUBW]
   uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_SUBW); // [N rounded up to 8]
+  float *spare = (float *)(list + ((N + 7) & ~7)) + 64 * wave; // [4][64] where lanes without an entry add
   const uint64_t *g_rec = net.mask[l + 1] + (mrow_of(net, l + 1, t - 1) * B + b) * Wd;
   for (int i = tid; i < Wd; i += 256) words[i] = g_rec[i];
   for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) acc[i] = 0.0f;
@@ -1243,7 +1267,8 @@ __global__ void __launch_bounds__(256) k_currents_csr(NetDev net, CurJobs jobs) 
   __syncthreads();
   const int r = span * 4 + wave;
   if (r < nsub)
-    csr_gather_wave(list, *cnt, net.csr_sub[l], nsub + 1, r, net.csr_col[l], net.csr_val[l], acc + wave * SNN_CSR_SUBW, lane);
+    csr_gather_wave(list, *cnt, net.csr_sub[l], nsub + 1, r, net.csr_col[l], net.csr_val[l], net.csr_nnz[l],
+                    acc + wave * SNN_CSR_SUBW, spare, lane);
   __syncthreads();
   float *dst = ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l];
   for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) {
@@ -3497,7 +3522,7 @@ static hipError_t launch_currents_csr(const NetDev &net, const CurJobs &jobs, hi
     const int l = jobs.j[i].lsel, N = net.N[l], nsub = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW;
     const unsigned g = (unsigned)((size_t)jobs.j[i].nsteps * net.B * ((nsub + 3) >> 2));
     gx = g > gx ? g : gx;
-    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2;
+    const size_t b = (size_t)net.Wd[l + 1] * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2 + (size_t)4 * 64 * 4;
     lds = b > lds ? b : lds;
   }
   hipLaunchKernelGGL(k_currents_csr, dim3(gx, jobs.count), dim3(256), lds, s, net, jobs);
@@ -3708,7 +3733,7 @@ static int seq_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, in
 // (a multiple of 4 SNN_CSR_SUBW), all workgroups of the launch are resident at once and the exchange buffer holds
 // the entries of every (job, batch element).  Returns the slices per batch element, 0 if it cannot run.
 static size_t seq_csr_lds(int N, int Wd) {
-  return (size_t)Wd * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2;
+  return (size_t)Wd * 8 + 16 + (size_t)4 * SNN_CSR_SUBW * 4 + (size_t)((N + 7) & ~7) * 2 + (size_t)4 * 64 * 4;
 }
 static int seq_csr_resident(int device, size_t lds) {
   static int cached[16] = {};

@@ -817,9 +817,11 @@ def _full_size_properties(idx, strategies, budget, prefix):
     try:
         net.snn_bind_inputs(d["in_spikes"], d["labels"], w.T)
         first = None
-        for strat, C, F in strategies:
-            st = net.snn_bptt(strat, C, F, budget)
-            assert st.bytes_states + st.bytes_spikes + st.bytes_workspace <= budget
+        for strat, C, F, *own in strategies:
+            # a fourth entry: this strategy's own budget ("min" = the smallest one its intervals can run in)
+            bud = budget if not own else (snn.snn_bytes_required(net.cfg, strat, w.T, C, F) if own[0] == "min" else own[0])
+            st = net.snn_bptt(strat, C, F, bud)
+            assert st.bytes_states + st.bytes_spikes + st.bytes_workspace <= bud
             g = _gpu_grads(net, len(w.n_hidden))
             assert all(np.isfinite(x).all() for x in g[0] + g[1] + [g[2]])
             if first is None:
@@ -844,6 +846,15 @@ def test_config2_full_size_properties():
 def test_config3_full_size_properties():
     """Configuration 3 (128 -> 2x512 -> 10, T = 100 000, batch 16) under its 4 GB budget: Double(316, 18)."""
     _full_size_properties(3, [(snn.SNN_DOUBLE, 316, 18), (snn.SNN_CHUNK, 0, 316)], 4 * 10**9, 1500)
+
+
+def test_config4_full_size_properties():
+    """Configuration 4 (1024 -> 4x8192 -> 100, T = 5000, batch 32, recurrent matrices 90 % zero) as the benchmark
+    times it: Double(512, 64) under the 32 GB budget (the forward pass's currents kept, stage launches over compressed
+    rows), the same intervals under the smallest budget they run in (currents recomputed, no pipelining buffers), and
+    Remote(512) under the 32 GB."""
+    _full_size_properties(4, [(snn.SNN_DOUBLE, 512, 64), (snn.SNN_DOUBLE, 512, 64, "min"), (snn.SNN_REMOTE, 512, 0)],
+                          32 * 10**9, 5)
 
 
 def test_config4_widths_short():
