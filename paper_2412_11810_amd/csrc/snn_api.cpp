@@ -42,6 +42,7 @@ struct snn_ctx {
   uint32_t *csr_sub[SNN_MAXL]{};
   uint16_t *csr_col[SNN_MAXL]{};
   float *csr_val[SNN_MAXL]{};
+  uint64_t *csr_pk[SNN_MAXL]{};
   size_t csr_nnz[SNN_MAXL]{};
   // fp64 gradient accumulators per existing synapse, in compressed-row order (k_dw_csr); csr_dw_ok: the entries
   // beyond the 64 per row and sub-range that kernel keeps in registers fit its LDS (64 per 16 rows and sub-range)
@@ -188,6 +189,7 @@ void read_kernel_hooks(snn_ctx *c) {
     n.csr_col[l] = on ? c->csr_col[l] : nullptr;
     n.csr_val[l] = on ? c->csr_val[l] : nullptr;
     n.csr_nnz[l] = on ? (uint32_t)c->csr_nnz[l] : 0u;
+    n.csr_pk[l] = on ? c->csr_pk[l] : nullptr;
   }
   if (const char *e = std::getenv("SNN_CURRENTS"))
     n.sel_currents = !std::strcmp(e, "gather") ? 1 : !std::strcmp(e, "mfma") ? 2 : !std::strcmp(e, "dense") ? 3 : 0;
@@ -235,7 +237,8 @@ size_t spike_bytes(const NetDev &n, int T, int ring = 0) {
 
 void free_csr(snn_ctx *c, int l) {
   (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]); (void)hipFree(c->acc_csr[l]);
-  c->csr_sub[l] = nullptr; c->csr_col[l] = nullptr; c->csr_val[l] = nullptr; c->csr_nnz[l] = 0;
+  (void)hipFree(c->csr_pk[l]);
+  c->csr_sub[l] = nullptr; c->csr_col[l] = nullptr; c->csr_val[l] = nullptr; c->csr_pk[l] = nullptr; c->csr_nnz[l] = 0;
   c->acc_csr[l] = nullptr; c->csr_dw_ok[l] = false;
 }
 
@@ -251,7 +254,7 @@ snn_status build_csr(snn_ctx *c, int l, const float *w, const uint8_t *mask) {
   if (is_device_ptr(mask)) { mh.resize(ne); HIPCHK(c, hipMemcpy(mh.data(), mask, ne, hipMemcpyDeviceToHost)); mask = mh.data(); }
   size_t nnz = 0;
   for (size_t i = 0; i < ne; ++i) nnz += mask[i] != 0;
-  if (nnz > 0xFFFFFFF0ull) return fail(c, SNN_E_INVAL, "recurrent matrix has too many synapses for 32-bit entry indices");
+  if (nnz > 0x1FF00000ull) return fail(c, SNN_E_INVAL, "recurrent matrix has too many synapses for 32-bit byte offsets of its entries");
   std::vector<uint32_t> sub((size_t)N * (nsub + 1));
   std::vector<uint16_t> col(nnz + 1);
   std::vector<float> val(nnz + 1);
@@ -290,6 +293,19 @@ snn_status build_csr(snn_ctx *c, int l, const float *w, const uint8_t *mask) {
   HIPCHK(c, hipMemcpy(c->csr_sub[l], sub.data(), sub.size() * 4, hipMemcpyHostToDevice));
   HIPCHK(c, hipMemcpy(c->csr_col[l], col.data(), col.size() * 2, hipMemcpyHostToDevice));
   HIPCHK(c, hipMemcpy(c->csr_val[l], val.data(), val.size() * 4, hipMemcpyHostToDevice));
+  {
+    // packed copy for the gather (layout: NetDev::csr_pk)
+    std::vector<uint64_t> pk(nnz + (size_t)nsub * 64);
+    for (size_t e = 0; e < nnz; ++e) {
+      uint32_t bits;
+      memcpy(&bits, &val[e], 4);
+      pk[e] = (uint64_t)bits | ((uint64_t)col[e] << 32);
+    }
+    for (int r = 0; r < nsub; ++r)
+      for (int k = 0; k < 64; ++k) pk[nnz + (size_t)r * 64 + k] = (uint64_t)((r + 1) * SNN_CSR_SUBW + k) << 32;
+    HIPCHK(c, hipMalloc(&c->csr_pk[l], pk.size() * 8));
+    HIPCHK(c, hipMemcpy(c->csr_pk[l], pk.data(), pk.size() * 8, hipMemcpyHostToDevice));
+  }
   c->csr_nnz[l] = nnz;
   return SNN_OK;
 }
@@ -534,6 +550,7 @@ void snn_destroy(snn_ctx *c) {
     (void)hipFree(c->W_in[l]); (void)hipFree(c->W_inT[l]); (void)hipFree(c->W_recT[l]);
     (void)hipFree(c->dW_in[l]); (void)hipFree(c->dW_rec[l]); (void)hipFree(c->rec_mask[l]);
     (void)hipFree(c->csr_sub[l]); (void)hipFree(c->csr_col[l]); (void)hipFree(c->csr_val[l]);
+    (void)hipFree(c->csr_pk[l]);
     (void)hipFree(c->acc_in[l]); (void)hipFree(c->acc_rec[l]);
   }
   for (int l = 0; l <= SNN_MAXL; ++l) { (void)hipFree(c->mask_full[l]); (void)hipFree(c->mask_ring[l]); }

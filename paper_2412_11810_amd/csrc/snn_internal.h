@@ -38,6 +38,12 @@ struct NetDev {
   const uint16_t *csr_col[SNN_MAXL];
   const float *csr_val[SNN_MAXL];
   uint32_t csr_nnz[SNN_MAXL]; // synapses that exist (csr_col and csr_val hold one entry more)
+  // The same entries once more, packed for the gather of the forward and recompute passes: entry e as one 64-bit
+  // word, weight bits in the low half, postsynaptic index in the high half (one load per row and lane).  Behind
+  // the nnz entries sit nsub * 64 zero-weight entries, number r * 64 + k with postsynaptic index
+  // (r + 1) * SNN_CSR_SUBW + k: where a lane has no entry of a row it loads this one, and the add goes to word k of
+  // the 64 spare words that follow the SNN_CSR_SUBW accumulators of sub-range r in LDS.
+  const uint64_t *csr_pk[SNN_MAXL];
   float alpha, beta, theta, k;
   float win;  // surrogate window (<= 0: none)
   // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step

@@ -590,110 +590,118 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
 // ascending order as in the dense-stored walk, which adds +0.0f wherever no synapse exists -- the same bits.  Only
 // the owning wavefront ever touches an accumulator.
 // ------------------------------------------------------------------------------------------
+#define SNN_CSR_ACCW (SNN_CSR_SUBW + 64) // floats of LDS per wavefront: its accumulators and 64 spare words behind them
 template <int U>
 struct CsrGroup { // the entries of U consecutive rows that fall into the wavefront's sub-range, one entry per lane
-  uint32_t n[U], c[U];
+  uint32_t c[U];
   float v[U];
 };
-// The two arrays of a layer's compressed rows as buffer descriptors over the whole arrays (nnz + 1 entries each): one
-// pair per wavefront and call, so a row costs no scalar descriptor arithmetic (the compute unit's one scalar unit is
-// what eight gathering wavefronts would otherwise queue for); a lane past the end of the arrays reads 0.
-struct CsrRes { __amdgpu_buffer_rsrc_t c, v; };
-static __device__ __forceinline__ CsrRes csr_res(const uint16_t *col, const float *val, uint32_t nnz) {
-  CsrRes r;
-  r.c = __builtin_amdgcn_make_buffer_rsrc((void *)col, 0, (int)((nnz + 1u) * sizeof(uint16_t)), 0x00027000);
-  r.v = __builtin_amdgcn_make_buffer_rsrc((void *)val, 0, (int)((nnz + 1u) * sizeof(float)), 0x00027000);
-  return r;
-}
+typedef __attribute__((address_space(3))) float lds_float;
+typedef unsigned int csr_u32x2 __attribute__((ext_vector_type(2)));
+// Requests the entries of rows q .. q + U - 1 of a block (positions and counts one row per lane in p0 / nn; q is a
+// constant after unrolling).  One 8-byte load per row from the packed copy (NetDev::csr_pk) through one descriptor
+// over the whole array: no scalar descriptor arithmetic per row (the compute unit's one scalar unit is what eight
+// gathering wavefronts would otherwise queue for).  A lane past the end of the row's part loads its zero-weight
+// entry instead (byte offset `zero`), so the consumer needs neither the count nor a change of the execution mask.
+// Straight-line code: the loads of three groups stay in flight.
 template <int U>
-static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn, const CsrRes &res,
-                                                 uint32_t lane2, uint32_t lane4) {
-  // every load unconditional: lane k takes entry k of the row's part of this sub-range; lanes past the part's end
-  // fetch the entries that follow in memory (discarded by csr_consume).  Straight-line code, so the loads of a whole
-  // group -- and of the next one -- stay in flight.  q is a constant after unrolling: the positions come out of
-  // p0 / nn with constant lane numbers.
+static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn,
+                                                 __amdgpu_buffer_rsrc_t res, uint32_t lane, uint32_t lane8, uint32_t zero) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
-    g.n[u] = (uint32_t)__builtin_amdgcn_readlane(nn, (q + u) & (WAVE - 1));
-    g.c[u] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(res.c, (p << 1) + lane2, 0, 0);
-    g.v[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(res.v, (p << 2) + lane4, 0, 0));
+    const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, q + u), n = (uint32_t)__builtin_amdgcn_readlane(nn, q + u);
+    const csr_u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(res, lane < n ? (p << 3) + lane8 : zero, 0, 0);
+    g.v[u] = __builtin_bit_cast(float, e.x);
+    g.c[u] = e.y;
   }
 }
-typedef __attribute__((address_space(3))) float lds_float;
-// OVER: some row of the block has more than 64 entries in this sub-range (decided once per block of 64 rows).
-// accb: LDS byte address of the accumulator of column 0 (the wavefront's first accumulator minus 4 c_base);
-// spareb: LDS byte address of this lane's spare word.
+// Read, add, write back with ordinary LDS instructions: the entries of a row have distinct columns, only this
+// wavefront touches its accumulators, and its LDS instructions execute in program order, so the next row's read sees
+// this row's write.  (LDS float atomics give the same bits but the counters show the wavefronts waiting two thirds of
+// their cycles for them.)  accb: LDS byte address of the accumulator of postsynaptic index 0 (the wavefront's
+// first accumulator minus 4 c_base).  OVER: some row of the block has more than 64 entries in this sub-range
+// (decided once per block).
 template <int U, bool OVER>
-static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, int q, uint32_t p0, uint32_t accb, uint32_t spareb,
-                                                   const uint16_t *__restrict__ col, const float *__restrict__ val, int lane) {
-  // Read, add, write back with ordinary LDS instructions: the entries of a row have distinct columns, only this
-  // wavefront touches its accumulators, and its LDS instructions execute in program order, so the next row's read
-  // sees this row's write.  (LDS float atomics give the same bits but the counters show the wavefronts waiting two
-  // thirds of their cycles for them.)  A lane without an entry adds zero to a spare word of its own instead of
-  // being masked out: no change of the execution mask, hence no scalar instruction, per row.
+static __device__ __forceinline__ void csr_consume(const CsrGroup<U> &g, int q, uint32_t p0, uint32_t nn, uint32_t accb,
+                                                   const uint64_t *__restrict__ pk, int lane) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const bool on = (uint32_t)lane < g.n[u];
-    lds_float *a = (lds_float *)(uintptr_t)(on ? (g.c[u] << 2) + accb : spareb);
-    *a = *a + (on ? g.v[u] : 0.0f);
+    lds_float *a = (lds_float *)(uintptr_t)((g.c[u] << 2) + accb);
+    *a = *a + g.v[u];
     if (OVER) {
-      const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, (q + u) & (WAVE - 1));
-      for (uint32_t o = WAVE; o < g.n[u]; o += WAVE) // a row with more than 64 entries in this range: finish it first
-        if (o + lane < g.n[u]) {
-          lds_float *x = (lds_float *)(uintptr_t)(((uint32_t)col[p + o + lane] << 2) + accb);
-          *x = *x + val[p + o + lane];
+      const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, q + u), n = (uint32_t)__builtin_amdgcn_readlane(nn, q + u);
+      for (uint32_t o = WAVE; o < n; o += WAVE) // a row with more than 64 entries in this range: finish it first
+        if (o + lane < n) {
+          const uint64_t e = pk[p + o + lane];
+          lds_float *x = (lds_float *)(uintptr_t)(((uint32_t)(e >> 32) << 2) + accb);
+          *x = *x + __builtin_bit_cast(float, (uint32_t)e);
         }
     }
   }
 }
-// The positions of 64 rows are fetched at once (one row per lane), one block of 64 rows ahead; the entries of two
-// groups of U rows are in flight while a third is added.  spare: 64 floats of LDS of this wavefront's own.
+// The walk of one wavefront over the active rows (list, ascending) for sub-range r.  Rows go in blocks of 48: the
+// positions of a block's rows are fetched at once (one row per lane) two blocks ahead of their use, and the entries
+// of three groups of 16 rows are in flight while a fourth is added -- a continuous pipeline over the whole list, so
+// the wavefront waits for memory once per step and not once per block.  acc_w: SNN_CSR_ACCW floats of LDS.
 static __device__ __forceinline__ void csr_gather_wave(const uint16_t *list, int cnt, const uint32_t *__restrict__ sub,
-                                                       int nsub1, int r, const uint16_t *__restrict__ col,
-                                                       const float *__restrict__ val, uint32_t nnz, float *acc_w,
-                                                       float *spare, int lane) {
-  constexpr int U = 16;
-  const CsrRes res = csr_res(col, val, nnz);
+                                                       int nsub1, int r, const uint64_t *__restrict__ pk, uint32_t nnz,
+                                                       float *acc_w, int lane) {
+  constexpr int U = 16, BL = 3 * U;
+  const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(
+      (void *)pk, 0, (int)((nnz + (uint32_t)(nsub1 - 1) * 64u) * sizeof(uint64_t)), 0x00027000);
   const uint32_t accb = (uint32_t)(uintptr_t)(lds_float *)acc_w - (uint32_t)r * SNN_CSR_SUBW * 4u;
-  const uint32_t spareb = (uint32_t)(uintptr_t)(lds_float *)(spare + lane);
-  const uint32_t lane2 = (uint32_t)lane * 2u, lane4 = (uint32_t)lane * 4u;
+  const uint32_t lane8 = (uint32_t)lane * 8u, zero = (nnz + (uint32_t)r * 64u + (uint32_t)lane) * 8u;
   auto meta = [&](int base, uint32_t &p0, uint32_t &nn) {
     const int i = base + lane;
     p0 = 0u;
     nn = 0u;
-    if (i < cnt) {
+    if (lane < BL && i < cnt) {
       const uint32_t *sp = sub + (size_t)list[i] * nsub1 + r;
       p0 = sp[0];
       nn = sp[1] - p0;
     }
   };
-  auto block = [&](auto over, int nr, uint32_t p0, uint32_t nn) {
-    constexpr bool OVER = decltype(over)::value;
-    CsrGroup<U> ga, gb;
-    csr_issue<U>(ga, 0, p0, nn, res, lane2, lane4);
-#pragma unroll
-    for (int q = 0; q < WAVE; q += 2 * U) {
-      if (q >= nr) break;
-      __builtin_amdgcn_sched_barrier(0); // keep the loads of the next group ahead of the adds of this one
-      csr_issue<U>(gb, q + U, p0, nn, res, lane2, lane4);
-      __builtin_amdgcn_sched_barrier(0);
-      csr_consume<U, OVER>(ga, q, p0, accb, spareb, col, val, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      if (q + 2 * U < WAVE) csr_issue<U>(ga, q + 2 * U, p0, nn, res, lane2, lane4); // (rows past nr carry no entries)
-      __builtin_amdgcn_sched_barrier(0);
-      csr_consume<U, OVER>(gb, q + U, p0, accb, spareb, col, val, lane);
-    }
-  };
-  uint32_t p0, nn, p0n, nnn;
+  if (cnt <= 0) return;
+  uint32_t p0, nn, p1, n1;
+  CsrGroup<U> ga, gb, gc;
   meta(0, p0, nn);
-  for (int base = 0; base < cnt; base += WAVE) {
-    meta(base + WAVE, p0n, nnn);
-    const int nr = cnt - base < WAVE ? cnt - base : WAVE;
-    if (__ballot(nn > (uint32_t)WAVE) != 0ull) block(std::true_type{}, nr, p0, nn);
-    else block(std::false_type{}, nr, p0, nn);
-    p0 = p0n;
-    nn = nnn;
+  meta(BL, p1, n1);
+  __builtin_amdgcn_sched_barrier(0); // (group by group: the byte offsets of one group at a time in registers)
+  csr_issue<U>(ga, 0, p0, nn, res, lane, lane8, zero);
+  __builtin_amdgcn_sched_barrier(0);
+  csr_issue<U>(gb, U, p0, nn, res, lane, lane8, zero);
+  __builtin_amdgcn_sched_barrier(0);
+  csr_issue<U>(gc, 2 * U, p0, nn, res, lane, lane8, zero);
+  __builtin_amdgcn_sched_barrier(0);
+  for (int base = 0; base < cnt; base += BL) {
+    const int nr = cnt - base; // rows of this block (>= 1); those past the list's end carry zero entries only
+    const bool over = __ballot(nn > (uint32_t)WAVE) != 0ull;
+    uint32_t p2, n2;
+    meta(base + 2 * BL, p2, n2);
+    // The next block's groups are requested as this one's are added -- unconditionally (past the list's end every
+    // lane loads its zero entry), so the three register sets have one definition per iteration.
+    __builtin_amdgcn_sched_barrier(0); // keep the order: loads of later groups ahead of the adds of earlier ones
+    if (over) csr_consume<U, true>(ga, 0, p0, nn, accb, pk, lane);
+    else csr_consume<U, false>(ga, 0, p0, nn, accb, pk, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    csr_issue<U>(ga, 0, p1, n1, res, lane, lane8, zero);
+    __builtin_amdgcn_sched_barrier(0);
+    if (nr > U) {
+      if (over) csr_consume<U, true>(gb, U, p0, nn, accb, pk, lane);
+      else csr_consume<U, false>(gb, U, p0, nn, accb, pk, lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    csr_issue<U>(gb, U, p1, n1, res, lane, lane8, zero);
+    __builtin_amdgcn_sched_barrier(0);
+    if (nr > 2 * U) {
+      if (over) csr_consume<U, true>(gc, 2 * U, p0, nn, accb, pk, lane);
+      else csr_consume<U, false>(gc, 2 * U, p0, nn, accb, pk, lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    csr_issue<U>(gc, 2 * U, p1, n1, res, lane, lane8, zero);
+    __builtin_amdgcn_sched_barrier(0);
+    p0 = p1; nn = n1;
+    p1 = p2; n1 = n2;
   }
 }
 
@@ -717,16 +725,13 @@ static __device__ __forceinline__ void layer_seq_csr_sl_body(const NetDev &net, 
   const int nsub1 = N / SNN_CSR_SUBW + 1, r = sl * 4 + wave;
   uint64_t *words = (uint64_t *)smem;                    // [Wd]  whole layer
   int *cnt = (int *)(words + Wd);                        // [1] (+3 pad)
-  float *acc = (float *)(cnt + 4);                       // [4][SNN_CSR_SUBW]
-  uint16_t *list = (uint16_t *)(acc + NS);               // [N rounded up to 8] indices of the active rows, ascending
-  float *spare = (float *)(list + ((N + 7) & ~7)) + 64 * wave; // [4][64] where lanes without an entry add
-  float *acc_w = acc + wave * SNN_CSR_SUBW;
+  float *acc = (float *)(cnt + 4);                       // [4][SNN_CSR_ACCW]
+  uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_ACCW); // [N rounded up to 8] indices of the active rows, ascending
+  float *acc_w = acc + wave * SNN_CSR_ACCW;
   uint64_t *mbase = net.mask[l + 1] + (size_t)b * Wd;
   const size_t mstride = (size_t)B * Wd;
   uint64_t *xb = xw + (size_t)(jq * B + b) * 4 * Wd; // [2][2 Wd] tagged half-words
   const uint32_t *__restrict__ sub = net.csr_sub[l];
-  const uint16_t *__restrict__ col = net.csr_col[l];
-  const float *__restrict__ val = net.csr_val[l];
   if (tid == 0) *cnt = 0;
   for (int i = tid; i < Wd; i += 256) words[i] = mbase[mrow_of(net, l + 1, t0) * mstride + i];
   __syncthreads();
@@ -755,7 +760,7 @@ static __device__ __forceinline__ void layer_seq_csr_sl_body(const NetDev &net, 
       in_t[k] = irow[64 * k + lane];
       acc_w[64 * k + lane] = 0.0f;
     }
-    csr_gather_wave(list, *cnt, sub, nsub1, r, col, val, net.csr_nnz[l], acc_w, spare, lane);
+    csr_gather_wave(list, *cnt, sub, nsub1, r, net.csr_pk[l], net.csr_nnz[l], acc_w, lane);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup"); // the adds of this wavefront have landed before it reads the sums
     uint64_t *xdst = xb + (size_t)(step & 1u) * 2 * Wd;
     const uint64_t tag = (uint64_t)(step + 1u) << 32;
@@ -1255,25 +1260,23 @@ __global__ void __launch_bounds__(256) k_currents_csr(NetDev net, CurJobs jobs) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint64_t *words = (uint64_t *)smem;                 // [Wd]
   int *cnt = (int *)(words + Wd);                     // [1] (+3 pad)
-  float *acc = (float *)(cnt + 4);                    // [4][SNN_CSR_SUBW]
-  uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_SUBW); // [N rounded up to 8]
-  float *spare = (float *)(list + ((N + 7) & ~7)) + 64 * wave; // [4][64] where lanes without an entry add
+  float *acc = (float *)(cnt + 4);                    // [4][SNN_CSR_ACCW]
+  uint16_t *list = (uint16_t *)(acc + 4 * SNN_CSR_ACCW); // [N rounded up to 8]
   const uint64_t *g_rec = net.mask[l + 1] + (mrow_of(net, l + 1, t - 1) * B + b) * Wd;
   for (int i = tid; i < Wd; i += 256) words[i] = g_rec[i];
-  for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) acc[i] = 0.0f;
+  for (int i = tid; i < 4 * SNN_CSR_ACCW; i += 256) acc[i] = 0.0f;
   if (tid == 0) *cnt = 0;
   __syncthreads();
   expand_all(words, Wd, list, cnt, tid, 256);
   __syncthreads();
   const int r = span * 4 + wave;
   if (r < nsub)
-    csr_gather_wave(list, *cnt, net.csr_sub[l], nsub + 1, r, net.csr_col[l], net.csr_val[l], net.csr_nnz[l],
-                    acc + wave * SNN_CSR_SUBW, spare, lane);
+    csr_gather_wave(list, *cnt, net.csr_sub[l], nsub + 1, r, net.csr_pk[l], net.csr_nnz[l], acc + wave * SNN_CSR_ACCW, lane);
   __syncthreads();
   float *dst = ca.out + (size_t)(t - ca.t_base - 1) * ca.slot_stride + (size_t)b * net.SN + net.off[l];
   for (int i = tid; i < 4 * SNN_CSR_SUBW; i += 256) {
     const int n = span * 4 * SNN_CSR_SUBW + i;
-    if (n < N) dst[n] = dst[n] + acc[i];
+    if (n < N) dst[n] = dst[n] + acc[(i / SNN_CSR_SUBW) * SNN_CSR_ACCW + i % SNN_CSR_SUBW];
   }
 }
 
