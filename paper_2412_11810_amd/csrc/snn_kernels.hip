@@ -3072,8 +3072,8 @@ k_dw_tile(DwBatch batch, int B) {
         if (mt == 0ull) continue;
         float4 part = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         while (mt) {
-          const int r = ts * B + (int)__builtin_ctzll(mt);
-          mt &= mt - 1ull;
+          const int kb = (int)__builtin_ctzll(mt), r = ts * B + kb;
+          asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(kb)); // mt &= ~(1 << kb) as one scalar instruction
           const float4 pv = *reinterpret_cast<const float4 *>(P + (size_t)r * PC + 4 * lane);
           part.x = part.x + pv.x; part.y = part.y + pv.y; part.z = part.z + pv.z; part.w = part.w + pv.w;
         }
@@ -3224,7 +3224,7 @@ k_dw_csr(DwBatch batch, int B) {
         const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + o;
         while (mt) {
           const int k = (int)__builtin_ctz(mt);
-          mt &= mt - 1u;
+          asm("s_bitset0_b32 %0, %1" : "+s"(mt) : "s"(k)); // mt &= ~(1 << k) as one scalar instruction
           part = part + *reinterpret_cast<const float *>(Pts + (size_t)k * PC * sizeof(float));
         }
         acc[i] = acc[i] + (double)part;
@@ -3239,7 +3239,7 @@ k_dw_csr(DwBatch batch, int B) {
           const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + ox;
           while (mt) {
             const int k = (int)__builtin_ctz(mt);
-            mt &= mt - 1u;
+            asm("s_bitset0_b32 %0, %1" : "+s"(mt) : "s"(k));
             part = part + *reinterpret_cast<const float *>(Pts + (size_t)k * PC * sizeof(float));
           }
           if (mine) xacc[xb + lane] = xacc[xb + lane] + (double)part;
