@@ -590,6 +590,9 @@ k_layer_seq_gather_sl(NetDev net, SeqJobs jobs, float *__restrict__ state, Store
 // ascending order as in the dense-stored walk, which adds +0.0f wherever no synapse exists -- the same bits.  Only
 // the owning wavefront ever touches an accumulator.
 // ------------------------------------------------------------------------------------------
+#ifndef SNN_CSR_AUX
+#define SNN_CSR_AUX 0 // cached like any load: the rows of a step are shared between batch elements (non-temporal: 48 -> 63 ms at configuration 4, T = 512)
+#endif
 #define SNN_CSR_ACCW (SNN_CSR_SUBW + 64) // floats of LDS per wavefront: its accumulators and 64 spare words behind them
 template <int U>
 struct CsrGroup { // the entries of U consecutive rows that fall into the wavefront's sub-range, one entry per lane
@@ -610,7 +613,7 @@ static __device__ __forceinline__ void csr_issue(CsrGroup<U> &g, int q, uint32_t
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const uint32_t p = (uint32_t)__builtin_amdgcn_readlane(p0, q + u), n = (uint32_t)__builtin_amdgcn_readlane(nn, q + u);
-    const csr_u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(res, lane < n ? (p << 3) + lane8 : zero, 0, 0);
+    const csr_u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(res, lane < n ? (p << 3) + lane8 : zero, 0, SNN_CSR_AUX);
     g.v[u] = __builtin_bit_cast(float, e.x);
     g.c[u] = e.y;
   }
