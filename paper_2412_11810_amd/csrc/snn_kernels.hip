@@ -3073,10 +3073,14 @@ k_dw_tile(DwBatch batch, int B) {
       for (int ts = 0; ts < nts; ++ts) {
         uint64_t mt = (m >> (ts * B)) & bmask;
         if (mt == 0ull) continue;
-        float4 part = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        // the first row starts the sum (0.0f + x and x differ only for x = -0.0f, and a sum that is -0.0f or +0.0f
+        // leaves the fp64 accumulator, which never is -0.0, the same)
+        const int k0 = (int)__builtin_ctzll(mt);
+        asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(k0)); // mt &= ~(1 << k0) as one scalar instruction
+        float4 part = *reinterpret_cast<const float4 *>(P + (size_t)(ts * B + k0) * PC + 4 * lane);
         while (mt) {
           const int kb = (int)__builtin_ctzll(mt), r = ts * B + kb;
-          asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(kb)); // mt &= ~(1 << kb) as one scalar instruction
+          asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(kb));
           const float4 pv = *reinterpret_cast<const float4 *>(P + (size_t)r * PC + 4 * lane);
           part.x = part.x + pv.x; part.y = part.y + pv.y; part.z = part.z + pv.z; part.w = part.w + pv.w;
         }
@@ -3223,8 +3227,10 @@ k_dw_csr(DwBatch batch, int B) {
       for (int ts = 0; ts < nts; ++ts) {
         uint32_t mt = (m >> (ts * B)) & bmask;
         if (mt == 0u) continue;
-        float part = 0.0f;
         const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + o;
+        const int k0 = (int)__builtin_ctz(mt); // the first row starts the sum (see k_dw_tile)
+        asm("s_bitset0_b32 %0, %1" : "+s"(mt) : "s"(k0));
+        float part = *reinterpret_cast<const float *>(Pts + (size_t)k0 * PC * sizeof(float));
         while (mt) {
           const int k = (int)__builtin_ctz(mt);
           asm("s_bitset0_b32 %0, %1" : "+s"(mt) : "s"(k)); // mt &= ~(1 << k) as one scalar instruction
