@@ -2516,6 +2516,7 @@ k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, u
   const uint32_t *__restrict__ sub = net.csr_sub[l];
   const uint16_t *__restrict__ col = net.csr_col[l];
   const float *__restrict__ val = net.csr_val[l];
+  const uint64_t *__restrict__ pk = net.csr_pk[l];
   const int nsub1 = (N + SNN_CSR_SUBW - 1) / SNN_CSR_SUBW + 1;
   // rows: the workgroup's [rb R, rb R + R), the wavefront's nr <= 64 consecutive ones from jw0; lane r keeps the
   // position of row jw0 + r
@@ -2576,15 +2577,15 @@ k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, u
   // 0) with no address arithmetic or compare in the vector unit.
   constexpr int CH = 14, CH2 = 2; // groups of 64 entries per pass (both even: group k always meets accumulator k & 1)
   struct Row { float w[CH]; uint32_t c[CH]; };
+  // (weight and index of an entry come as one 8-byte load from the packed copy of the rows, NetDev::csr_pk)
   auto fetch = [&](Row &r, uint32_t e0, uint32_t e1) {
-    const __amdgpu_buffer_rsrc_t rv =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(val + e0), 0, (int)((e1 - e0) * sizeof(float)), 0x00027000);
-    const __amdgpu_buffer_rsrc_t rc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(col + e0), 0, (int)((e1 - e0) * sizeof(uint16_t)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rp =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(pk + e0), 0, (int)((e1 - e0) * sizeof(uint64_t)), 0x00027000);
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
-      r.w[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, (uint32_t)(lane * 4), 256 * i, 0));
-      r.c[i] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rc, (uint32_t)(lane * 2), 128 * i, 0);
+      const csr_u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(rp, (uint32_t)(lane * 8), 512 * i, 0);
+      r.w[i] = __builtin_bit_cast(float, e.x);
+      r.c[i] = e.y;
     }
   };
   // one row: its entries sit in `r` (requested a row ago); each pair of registers is reloaded with the next row's
@@ -2594,10 +2595,8 @@ k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, u
     const uint32_t e0 = __builtin_amdgcn_readlane(m0, q), e1 = __builtin_amdgcn_readlane(m1, q);
     const int qn = q + 1 < nr ? q + 1 : 0; // after the last row: the first row of the next step
     const uint32_t n0 = __builtin_amdgcn_readlane(m0, qn), n1 = __builtin_amdgcn_readlane(m1, qn);
-    const __amdgpu_buffer_rsrc_t nv =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(val + n0), 0, (int)((n1 - n0) * sizeof(float)), 0x00027000);
-    const __amdgpu_buffer_rsrc_t nc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)(col + n0), 0, (int)((n1 - n0) * sizeof(uint16_t)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t np =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(pk + n0), 0, (int)((n1 - n0) * sizeof(uint64_t)), 0x00027000);
     float a0[4] = {0.0f, 0.0f, 0.0f, 0.0f}, a1[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     auto fma2 = [&](float w0, const float4 &x0, float w1, const float4 &x1) {
       a0[0] = fmaf(w0, x0.x, a0[0]); a0[1] = fmaf(w0, x0.y, a0[1]);
@@ -2618,8 +2617,9 @@ k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, u
       fma2(r.w[i], xa, r.w[i + 1], xb);
 #pragma unroll
       for (int h = i; h < i + 2; ++h) { // the next row's entries into the registers just used
-        r.w[h] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(nv, (uint32_t)(lane * 4), 256 * h, 0));
-        r.c[h] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(nc, (uint32_t)(lane * 2), 128 * h, 0);
+        const csr_u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(np, (uint32_t)(lane * 8), 512 * h, 0);
+        r.w[h] = __builtin_bit_cast(float, e.x);
+        r.c[h] = e.y;
       }
       xa = na;
       xb = nb;
