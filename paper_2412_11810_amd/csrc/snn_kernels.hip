@@ -3000,8 +3000,12 @@ __global__ void __launch_bounds__(64 * DWT_WAVES)
 k_dw_tile(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int PJ = 128, PC = 256, RT = 64, NWV = DWT_WAVES, RW = PJ / NWV, SK = RT / NWV; // rows per wavefront, staging loads per thread
-  float *P = (float *)smem;                              // [RT][PC]
-  uint64_t *Wv = (uint64_t *)(P + RT * PC);              // [2][RT] spike words of the tile's rows
+  // two tile buffers in turn: a tile is written while slower wavefronts still read the one before it, so a tile
+  // costs one barrier, not two
+  float *const Pb = (float *)smem;                       // [2][RT][PC]
+  uint64_t *const Wb = (uint64_t *)(Pb + 2 * RT * PC);   // [2][2][RT] spike words of the tile's rows
+  float *P = Pb;
+  uint64_t *Wv = Wb;
   int di = 0;
   while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
   const DwDesc &d = batch.d[di];
@@ -3059,9 +3063,11 @@ k_dw_tile(DwBatch batch, int B) {
   const uint64_t bmask = B >= 64 ? ~0ull : ((1ull << B) - 1ull);
   int t_hi = t1;
   tile_load(t_hi, t_hi - t0 < TS ? t_hi - t0 : TS);
-  while (t_hi > t0) {
+  for (int it = 0; t_hi > t0; ++it) {
     const int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
-    __syncthreads(); // everybody is done with the previous tile
+    // the buffer read two tiles ago: every wavefront has left it, or it would not have passed the barrier of the tile between
+    P = Pb + (it & 1) * RT * PC;
+    Wv = Wb + (it & 1) * 2 * RT;
     tile_store(t_hi, nts);
     __syncthreads();
     const int t_next = t_hi - nts;
@@ -3143,9 +3149,11 @@ k_dw_csr(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int PJ = 256, PC = SNN_CSR_SUBW, RT = 32, NWV = DWC_WAVES, RW = PJ / NWV, WPB = PJ / 64;
   constexpr int SK = RT * (PC / 4) / (64 * NWV); // staging loads (float4) per thread
-  float *P = (float *)smem;                       // [RT][PC]
-  uint64_t *Wv = (uint64_t *)(P + RT * PC);       // [WPB][RT] spike words of the tile's rows
-  double *xacc_all = (double *)(Wv + WPB * RT);   // [NWV][64] accumulators of the entries beyond a row's 64th
+  float *const Pb = (float *)smem;                       // [2][RT][PC]: two tile buffers in turn, one barrier per tile (see k_dw_tile)
+  uint64_t *const Wb = (uint64_t *)(Pb + 2 * RT * PC);   // [2][WPB][RT] spike words of the tile's rows
+  float *P = Pb;
+  uint64_t *Wv = Wb;
+  double *xacc_all = (double *)(Wb + 2 * WPB * RT);      // [NWV][64] accumulators of the entries beyond a row's 64th
   uint32_t *xoff_all = (uint32_t *)(xacc_all + NWV * 64); // [NWV][64] their column offsets
   int di = 0;
   while (di + 1 < batch.count && (int)blockIdx.x >= batch.d[di + 1].tile0) ++di;
@@ -3234,9 +3242,10 @@ k_dw_csr(DwBatch batch, int B) {
   const uint32_t bmask = B >= 32 ? ~0u : ((1u << B) - 1u);
   int t_hi = t1;
   tile_load(t_hi, t_hi - t0 < TS ? t_hi - t0 : TS);
-  while (t_hi > t0) {
+  for (int it = 0; t_hi > t0; ++it) {
     const int nts = t_hi - t0 < TS ? t_hi - t0 : TS;
-    __syncthreads(); // everybody is done with the previous tile
+    P = Pb + (it & 1) * RT * PC;
+    Wv = Wb + (it & 1) * WPB * RT;
     tile_store(t_hi, nts);
     __syncthreads();
     const int t_next = t_hi - nts;
@@ -4427,7 +4436,7 @@ static hipError_t launch_dw_csr(DwBatch batch, int B, hipStream_t s) {
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 255) / 256) * batch.d[i].tiles_n;
   }
-  const size_t lds = (size_t)32 * SNN_CSR_SUBW * sizeof(float) + (size_t)4 * 32 * sizeof(uint64_t) + (size_t)DWC_WAVES * 64 * (sizeof(double) + sizeof(uint32_t));
+  const size_t lds = (size_t)2 * 32 * SNN_CSR_SUBW * sizeof(float) + (size_t)2 * 4 * 32 * sizeof(uint64_t) + (size_t)DWC_WAVES * 64 * (sizeof(double) + sizeof(uint32_t));
   const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_dw_csr),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
@@ -4463,7 +4472,7 @@ hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s) {
     batch.d[i].tile0 = total;
     total += ((batch.d[i].n_pre + 127) / 128) * batch.d[i].tiles_n;
   }
-  const size_t lds = (size_t)64 * 256 * sizeof(float) + (size_t)2 * 64 * sizeof(uint64_t);
+  const size_t lds = (size_t)2 * 64 * 256 * sizeof(float) + (size_t)2 * 2 * 64 * sizeof(uint64_t);
   const hipError_t e = hipFuncSetAttribute(B == 32 ? reinterpret_cast<const void *>(k_dw_tile<true>)
                                                    : reinterpret_cast<const void *>(k_dw_tile<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
