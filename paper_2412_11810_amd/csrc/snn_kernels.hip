@@ -2988,7 +2988,7 @@ k_dw_mfma(DwBatch batch, int B) {
 // launch (loaded from and stored back to the accumulators in HBM, so the sequence of operations per element is
 // the one of the dense version: per time step, descending, an fp32 sum over the batch elements that spiked,
 // ascending, started from zero, then one fp64 add).  The time axis runs in tiles of floor(64 / B) steps: the tile's
-// adjoint rows P[(t, b)][256 columns] go to LDS (64 KB; the next tile's are in flight in registers meanwhile) and so
+// adjoint rows P[(t, b)][256 columns] go to LDS (64 KB, two such buffers in turn; the next tile's are in flight in registers meanwhile) and so
 // do the spike words of its rows for the workgroup's 128 presynaptic neurons; a ballot over the rows turns the
 // words into, per presynaptic neuron, the 64-bit set of rows in which it spiked (wavefront-uniform), and only
 // those rows are read from LDS and added: one 16-byte LDS read and four adds per (spike, four columns).
@@ -3139,7 +3139,7 @@ k_dw_tile(DwBatch batch, int B) {
 // (the few entries beyond 64 -- 3 % of the rows have any at 10 % density -- keep theirs in LDS, up to 64 per wavefront;
 // the host checks that this is enough, else the matrix keeps dense accumulators).
 // The time axis runs in tiles of floor(32 / B) steps whose adjoint rows P[(t, b)][512 columns] go through LDS
-// (64 KB, the next tile's loads in flight meanwhile) with the spike words of the 256 presynaptic neurons; a ballot
+// (64 KB, two such buffers in turn, the next tile's loads in flight meanwhile) with the spike words of the 256 presynaptic neurons; a ballot
 // gives the rows in which a neuron spiked, and each such row costs one LDS gather and one add per lane.
 // Per synapse the sequence of operations is the one of k_dw_tile and of the dense contraction: per time step,
 // descending, an fp32 sum over the batch elements that spiked, ascending, from zero, then one fp64 add.
