@@ -25,6 +25,23 @@ static __device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1
 // Sum of x over the 64 lanes, the same bits in every lane (all lanes must be active): neighbours within quads
 // (xor 1, xor 2), the two quads of a half row, the two halves of a row of 16 -- row-local DPP moves, no LDS -- then
 // the four row sums as (r0 + r1) + (r2 + r3).
+// The same sum with the same bits, valid in lane 63 only: the four row sums meet through two row broadcasts
+// ((r1 + r0) in row 1 and (r3 + r2) in row 3, then (r3 + r2) + (r1 + r0) in row 3; additions commute bit for bit)
+// instead of four lane reads and three adds.
+static __device__ __forceinline__ float wave_sum_lane63(float x) {
+  auto dpp = [](float v, auto ctrl, auto rows) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                 decltype(rows)::value, 0xF, false));
+  };
+  using all = std::integral_constant<int, 0xF>;
+  x = x + dpp(x, std::integral_constant<int, 0xB1>{}, all{});  // quad_perm [1, 0, 3, 2]
+  x = x + dpp(x, std::integral_constant<int, 0x4E>{}, all{});  // quad_perm [2, 3, 0, 1]
+  x = x + dpp(x, std::integral_constant<int, 0x141>{}, all{}); // row_half_mirror
+  x = x + dpp(x, std::integral_constant<int, 0x140>{}, all{}); // row_mirror: every lane of a row holds the row's sum
+  x = x + dpp(x, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xA>{}); // row_bcast 15 into rows 1, 3
+  x = x + dpp(x, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xC>{}); // row_bcast 31 into rows 2, 3
+  return x;
+}
 static __device__ __forceinline__ float wave_sum(float x) {
   auto dpp = [](float v, auto ctrl) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value, 0xF, 0xF, true));
@@ -2638,9 +2655,9 @@ k_adj_rec_csrw(NetDev net, AdjJobs jobs, float *__restrict__ carry, float *xg, u
         mac2(w0, c0, w1, c1);
       }
     }
-    const float4 sum4 = make_float4(wave_sum(a0[0] + a1[0]), wave_sum(a0[1] + a1[1]), wave_sum(a0[2] + a1[2]),
-                                    wave_sum(a0[3] + a1[3]));
-    if (lane == 0) sums[q] = sum4; // read back by lane q of this wavefront when the step's rows are done
+    const float4 sum4 = make_float4(wave_sum_lane63(a0[0] + a1[0]), wave_sum_lane63(a0[1] + a1[1]),
+                                    wave_sum_lane63(a0[2] + a1[2]), wave_sum_lane63(a0[3] + a1[3]));
+    if (lane == 63) sums[q] = sum4; // read back by lane q of this wavefront when the step's rows are done
   };
   if (nr > 0) fetch(r, __builtin_amdgcn_readlane(m0, 0), __builtin_amdgcn_readlane(m1, 0));
   const size_t slot_stride = (size_t)B * SN;
