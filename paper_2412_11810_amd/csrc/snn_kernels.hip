@@ -3012,7 +3012,8 @@ k_dw_mfma(DwBatch batch, int B) {
 // (Sixteen wavefronts of 8 rows rather than eight of 16: what bounds the kernel is the round trip LDS read -> add of
 // consecutive events, and four wavefronts per SIMD hide twice as much of it as two.)
 #define DWT_WAVES 16
-template <bool B32> // B32: the batch is 32 (a tile is two whole time steps: the halves of a 64-bit set of rows)
+template <int BS> // BS = 32 / 64: the batch is 32 (a tile is two whole time steps: the halves of a 64-bit set of rows) or 64
+                   // (one time step: the whole set); 0: any batch up to 64
 __global__ void __launch_bounds__(64 * DWT_WAVES)
 k_dw_tile(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -3090,7 +3091,26 @@ k_dw_tile(DwBatch batch, int B) {
     const int t_next = t_hi - nts;
     if (t_next > t0) tile_load(t_next, t_next - t0 < TS ? t_next - t0 : TS); // in flight during the adds below
     const uint64_t wv = Wv[wsel * RT + lane];
-    if constexpr (B32) { // two time steps of 32 rows: the halves of the row set, no shifts, masks or loop counter (rows past nts hold no spikes)
+    if constexpr (BS == 64) { // one time step of 64 rows: the row set as it is
+#pragma unroll
+      for (int i = 0; i < RW; ++i) {
+        uint64_t mt = __ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
+        if (mt == 0ull) continue;
+        const int k0 = (int)__builtin_ctzll(mt); // the first row starts the sum (see below)
+        asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(k0));
+        float4 part = *reinterpret_cast<const float4 *>(P + (size_t)k0 * PC + 4 * lane);
+        while (mt) {
+          const int kb = (int)__builtin_ctzll(mt);
+          asm("s_bitset0_b64 %0, %1" : "+s"(mt) : "s"(kb));
+          const float4 pv = *reinterpret_cast<const float4 *>(P + (size_t)kb * PC + 4 * lane);
+          part.x = part.x + pv.x; part.y = part.y + pv.y; part.z = part.z + pv.z; part.w = part.w + pv.w;
+        }
+        acc[i][0] = acc[i][0] + (double)part.x;
+        acc[i][1] = acc[i][1] + (double)part.y;
+        acc[i][2] = acc[i][2] + (double)part.z;
+        acc[i][3] = acc[i][3] + (double)part.w;
+      }
+    } else if constexpr (BS == 32) { // two time steps of 32 rows: the halves of the row set, no shifts, masks or loop counter (rows past nts hold no spikes)
 #pragma unroll
       for (int i = 0; i < RW; ++i) {
         const uint64_t m = __ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
@@ -4490,12 +4510,13 @@ hipError_t launch_dw_tile(DwBatch batch, int B, hipStream_t s) {
     total += ((batch.d[i].n_pre + 127) / 128) * batch.d[i].tiles_n;
   }
   const size_t lds = (size_t)2 * 64 * 256 * sizeof(float) + (size_t)2 * 2 * 64 * sizeof(uint64_t);
-  const hipError_t e = hipFuncSetAttribute(B == 32 ? reinterpret_cast<const void *>(k_dw_tile<true>)
-                                                   : reinterpret_cast<const void *>(k_dw_tile<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  const void *fn = B == 32 ? reinterpret_cast<const void *>(k_dw_tile<32>)
+                   : B == 64 ? reinterpret_cast<const void *>(k_dw_tile<64>) : reinterpret_cast<const void *>(k_dw_tile<0>);
+  const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  if (B == 32) hipLaunchKernelGGL(k_dw_tile<true>, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
-  else hipLaunchKernelGGL(k_dw_tile<false>, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
+  if (B == 32) hipLaunchKernelGGL(k_dw_tile<32>, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
+  else if (B == 64) hipLaunchKernelGGL(k_dw_tile<64>, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
+  else hipLaunchKernelGGL(k_dw_tile<0>, dim3(total), dim3(64 * DWT_WAVES), lds, s, batch, B);
   return hipGetLastError();
 }
 
