@@ -65,7 +65,9 @@ def work_model(w, rates, in_rate, T, refwd_steps, rec_density, cur_steps=None, d
     ev_rec = [rates[l] * N[l] * B for l in range(L)]          # recurrent events per step
     ev_out = rates[-1] * N[-1] * B
     masked = rec_density < 1.0
-    row_rec = [(6.0 * rec_density if masked else 4.0) * N[l] for l in range(L)]   # bytes of one recurrent row
+    # bytes of one recurrent row: the method's own figure for a masked matrix is a weight and a 16-bit index per existing
+    # synapse (6 bytes); the gather and adjoint kernels read a packed 8-byte entry, which the counters show, not this model
+    row_rec = [(6.0 * rec_density if masked else 4.0) * N[l] for l in range(L)]
     ent_rec = [(rec_density if masked else 1.0) * N[l] for l in range(L)]         # weights in one recurrent row
     out = {}
     out["fwd_currents"] = ("hbm", T * (sum(4.0 * N[l] * ev_in[l] + 8.0 * N[l] * B for l in range(L)) + 4.0 * w.n_out * ev_out))
