@@ -3181,6 +3181,7 @@ k_dw_tile(DwBatch batch, int B) {
 // Per synapse the sequence of operations is the one of k_dw_tile and of the dense contraction: per time step,
 // descending, an fp32 sum over the batch elements that spiked, ascending, from zero, then one fp64 add.
 #define DWC_WAVES 16
+template <bool B32> // B32: the batch is 32 -- a tile is exactly one time step, the set of rows needs no shift or mask
 __global__ void __launch_bounds__(64 * DWC_WAVES)
 k_dw_csr(DwBatch batch, int B) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -3296,8 +3297,8 @@ k_dw_csr(DwBatch batch, int B) {
       const uint32_t m = (uint32_t)__ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
       if (m == 0u) continue;
       const uint32_t o = (i & 1) ? offs[i >> 1] >> 16 : offs[i >> 1] & 0xFFFFu;
-      for (int ts = 0; ts < nts; ++ts) {
-        uint32_t mt = (m >> (ts * B)) & bmask;
+      for (int ts = 0; ts < (B32 ? 1 : nts); ++ts) {
+        uint32_t mt = B32 ? m : (m >> (ts * B)) & bmask;
         if (mt == 0u) continue;
         const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + o;
         const int k0 = (int)__builtin_ctz(mt); // the first row starts the sum (see k_dw_tile)
@@ -3313,8 +3314,8 @@ k_dw_csr(DwBatch batch, int B) {
       if (xn) { // the row's entries beyond the 64th: the same walk, accumulators in LDS
         const bool mine = (uint32_t)lane < xn;
         const uint32_t ox = mine ? xoff[xb + lane] : 0u;
-        for (int ts = 0; ts < nts; ++ts) {
-          uint32_t mt = (m >> (ts * B)) & bmask;
+        for (int ts = 0; ts < (B32 ? 1 : nts); ++ts) {
+          uint32_t mt = B32 ? m : (m >> (ts * B)) & bmask;
           if (mt == 0u) continue;
           float part = 0.0f;
           const unsigned char *Pts = reinterpret_cast<const unsigned char *>(P) + (size_t)ts * B * PC * sizeof(float) + ox;
@@ -4474,10 +4475,12 @@ static hipError_t launch_dw_csr(DwBatch batch, int B, hipStream_t s) {
     total += ((batch.d[i].n_pre + 255) / 256) * batch.d[i].tiles_n;
   }
   const size_t lds = (size_t)2 * 32 * SNN_CSR_SUBW * sizeof(float) + (size_t)2 * 4 * 32 * sizeof(uint64_t) + (size_t)DWC_WAVES * 64 * (sizeof(double) + sizeof(uint32_t));
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_dw_csr),
+  const hipError_t e = hipFuncSetAttribute(B == 32 ? reinterpret_cast<const void *>(k_dw_csr<true>)
+                                                   : reinterpret_cast<const void *>(k_dw_csr<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_dw_csr, dim3(total), dim3(64 * DWC_WAVES), lds, s, batch, B);
+  if (B == 32) hipLaunchKernelGGL(k_dw_csr<true>, dim3(total), dim3(64 * DWC_WAVES), lds, s, batch, B);
+  else hipLaunchKernelGGL(k_dw_csr<false>, dim3(total), dim3(64 * DWC_WAVES), lds, s, batch, B);
   return hipGetLastError();
 }
 
