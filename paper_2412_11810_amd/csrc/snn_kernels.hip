@@ -3222,7 +3222,7 @@ k_dw_csr(DwBatch batch, int B) {
   // other in xacc / xoff
   uint32_t xpack[RW / 4] = {};
   auto xn_of = [&](int i) { return (xpack[i >> 2] >> (8 * (i & 3))) & 0xFFu; };
-  uint32_t xtot = 0u;
+  uint32_t xtot = 0u, xmask = 0u; // xmask: bit i = row i has such entries (3 % of the rows at 10 % density)
 #pragma unroll
   for (int i = 0; i < RW; ++i) {
     uint32_t e0, n;
@@ -3234,6 +3234,7 @@ k_dw_csr(DwBatch batch, int B) {
     acc[i] = has ? d.acc[e0 + lane] : 0.0;
     const uint32_t xn = n > 64u ? n - 64u : 0u;
     xpack[i >> 2] |= xn << (8 * (i & 3));
+    if (xn) xmask |= 1u << i;
     if ((uint32_t)lane < xn) { // (the host has checked: at most 64 per row and per wavefront)
       xacc[xtot + lane] = d.acc[e0 + 64 + lane];
       xoff[xtot + lane] = ((uint32_t)d.csr_col[e0 + 64 + lane] - (uint32_t)n0) * 4u;
@@ -3289,11 +3290,8 @@ k_dw_csr(DwBatch batch, int B) {
     const int t_next = t_hi - nts;
     if (t_next > t0) tile_load(t_next, t_next - t0 < TS ? t_next - t0 : TS); // in flight during the adds below
     const uint64_t wv = lane < RT ? Wv[wsel * RT + lane] : 0ull;
-    uint32_t xbase = 0u;
 #pragma unroll
     for (int i = 0; i < RW; ++i) {
-      const uint32_t xn = xn_of(i), xb = xbase;
-      xbase += xn;
       const uint32_t m = (uint32_t)__ballot((wv >> (bitbase + i)) & 1ull); // rows of the tile in which neuron jw + i spiked
       if (m == 0u) continue;
       const uint32_t o = (i & 1) ? offs[i >> 1] >> 16 : offs[i >> 1] & 0xFFFFu;
@@ -3311,7 +3309,11 @@ k_dw_csr(DwBatch batch, int B) {
         }
         acc[i] = acc[i] + (double)part;
       }
-      if (xn) { // the row's entries beyond the 64th: the same walk, accumulators in LDS
+      if ((xmask >> i) & 1u) { // the row's entries beyond the 64th: the same walk, accumulators in LDS
+        const uint32_t xn = xn_of(i);
+        uint32_t xb = 0u; // they sit behind those of the rows before it
+#pragma unroll
+        for (int k = 0; k < i; ++k) xb += xn_of(k);
         const bool mine = (uint32_t)lane < xn;
         const uint32_t ox = mine ? xoff[xb + lane] : 0u;
         for (int ts = 0; ts < (B32 ? 1 : nts); ++ts) {
