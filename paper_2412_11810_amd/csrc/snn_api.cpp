@@ -1016,13 +1016,18 @@ static snn_status update_current_policy(snn_ctx *c, int T, float *rates_out, boo
       c->net.cur_pol[1][l] = ev_re < 0.035 * rows_re ? 1 : 2;
     }
     // A masked recurrent matrix kept as compressed rows: the gather over them pays per presynaptic spike and per
-    // synapse that exists.  Measured at configuration 4's widths it takes 0.39 of the dense kernel's time for the
-    // recurrent part at (firing rate x density) = 0.005: below 0.01 the recurrent part of the recompute goes through
-    // the compressed rows (3) while the feed-forward part stays dense.
+    // synapse that exists.  Measured at configuration 4's widths (10 % density) the recurrent part of the recompute
+    // over compressed rows takes 0.39 of the dense kernel's time at 5 % activity and still wins at 20 % (23.2 against
+    // 26.2 ms per 100 steps, feed-forward part dense in both): below (firing rate x density) = 0.025 it goes through
+    // the compressed rows (3) while the feed-forward part stays dense.  Above that the recompute is all dense, but the
+    // sequential forward part -- event-driven either way -- keeps walking the compressed rows (4) as long as a row's
+    // part of a sub-range fits one entry per lane on average (density <= 1/8): at 15-45 % activity it takes 109-134 ms
+    // where the walk over the dense-stored rows takes 124-150 (T = 200).
     for (int l = 0; l < L; ++l)
       if (c->csr_sub[l] && c->net.cur_pol[1][l] == 2) {
         const double dens = (double)c->csr_nnz[l] / ((double)n.N[l] * n.N[l]);
-        if (r[l + 1] * dens < 0.01) c->net.cur_pol[1][l] = 3;
+        if (r[l + 1] * dens < 0.025) c->net.cur_pol[1][l] = 3;
+        else if (dens <= 0.125) c->net.cur_pol[1][l] = 4;
       }
   }
   return SNN_OK;
@@ -1900,7 +1905,7 @@ snn_status snn_bptt(snn_ctx *c, snn_strategy strategy, int32_t C_in, int32_t F_i
   const bool use_graph = c->graphs_enabled && !stats;
   if (use_graph) {
     unsigned long long pol = 0;
-    for (int l = 0; l < L; ++l) pol = pol * 32 + c->net.cur_pol[0][l] * 8 + c->net.cur_pol[1][l] * 2 + c->net.seq_pol[l];
+    for (int l = 0; l < L; ++l) pol = pol * 64 + c->net.cur_pol[0][l] * 16 + c->net.cur_pol[1][l] * 2 + c->net.seq_pol[l];
     pol = pol * 2 + (c->dw_tile ? 1u : 0u);
     const unsigned sel = (unsigned)n.sel_currents | (unsigned)n.sel_adjoint << 8 | (unsigned)n.sel_slices << 16 | (unsigned)n.sel_csr << 24 | (unsigned)n.sel_seq << 28 | (unsigned)n.no_fwd_fuse << 30;
     snn_ctx::GraphKeyT key{(int)strategy, T, p.C, p.F, p.n_chunk_bufs, c->arena, c->dubuf, c->host_ckpt, c->dw_event_driven, pol, sel,

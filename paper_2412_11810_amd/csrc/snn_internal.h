@@ -48,7 +48,8 @@ struct NetDev {
   float win;  // surrogate window (<= 0: none)
   // Current kernel for the layers whose weights are far beyond the L2, from the firing rates of the last step
   // (0: not known yet -> dense, 1: event-by-event gather, 2: dense matrix-core version, 3 ([1] only): dense for the
-  // feed-forward part, gather over compressed rows for the recurrent part); [0] forward currents
+  // feed-forward part, gather over compressed rows for the recurrent part, 4 ([1] only): dense for both, but the
+  // sequential forward part walks the compressed rows); [0] forward currents
   // (feed-forward part only), [1] recompute (both parts).  Every choice gives the same bits.
   unsigned char cur_pol[2][SNN_MAXL];
   // Kernel selection forced from outside (test hooks; 0 = the library's own choice).  Every choice gives the same

@@ -3854,14 +3854,13 @@ static int fwd_stage_csr_per_cu(int device, int *n_cu) {
 static int seq_csr_slices(const NetDev &net, const SeqJobs &ga, const WsArgs *ws, bool need_rows = true) {
   if (!ws || !ws->xg || ga.count < 1 || net.sel_slices == 1) return 0;
   // The walk over compressed rows pays per presynaptic spike and per synapse that exists: it runs where the
-  // context's firing-rate policy has picked the gather over compressed rows for the recompute (rate x density
-  // below 0.01; configuration 4 at 5 % activity and 10 % density: 158 us per step against 220 us for the
-  // dense-stored walk), or wherever the hook asks.
+  // context's firing-rate policy has picked the gather over compressed rows for the recompute or, at higher
+  // activity, for this walk alone (cur_pol 1, 3, 4), or wherever the hook asks.
   if (need_rows && net.sel_csr != 2) {
     if (net.sel_csr == 1) return 0;
     for (int i = 0; i < ga.count; ++i) {
       const int pol = net.cur_pol[1][ga.j[i].l];
-      if (pol != 1 && pol != 3) return 0;
+      if (pol != 1 && pol != 3 && pol != 4) return 0;
     }
   }
   const int N = net.N[ga.j[0].l], Wd = net.Wd[ga.j[0].l + 1];
