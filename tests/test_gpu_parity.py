@@ -415,6 +415,15 @@ def test_config4_widths_full_batch():
                  check_states=True, probe_states=[(3, 8), (0, 5)])
 
 
+def test_config4_widths_full_batch_high_activity():
+    """The same network driven to 15-40 % hidden activity (weight gain 0.45), nothing forced: from the second training
+    step on the rate-driven choice computes the recompute currents of the masked layers dense but still walks their
+    compressed rows in the sequential forward part; gradients against the oracle, strategies bit-identical."""
+    w = synth.config(4, T=8, gain=0.45)
+    _full_parity(w, [(snn.SNN_DOUBLE, 4, 2), (snn.SNN_STANDARD, 0, 0), (snn.SNN_CHUNK, 0, 3)], nthreads=16,
+                 check_states=True, probe_states=[(3, 8), (1, 3)])
+
+
 def test_config3_width_reduced_length():
     w = synth.config(3, T=700, B=4)
     _full_parity(w, [(snn.SNN_CHUNK, 0, 27), (snn.SNN_DOUBLE, 316, 18)], nthreads=4, check_states=False)
